@@ -1,0 +1,561 @@
+"""Pins for the fp64 oracle: what the paper and the mathematics fix.
+
+None of these call the HIP library.  Each test names the passage it pins.
+"""
+
+import itertools
+import json
+import math
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+import scipy.special
+
+from oracle import mpv_oracle as orc
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+METHODS = [orc.SPECINFER, orc.TRAVERSAL]
+
+
+# --------------------------------------------------------------------------
+# tree builders used only by these tests
+# --------------------------------------------------------------------------
+
+def delayed_parent(K, L1, L2):
+    """Parent array of a (K, L1, L2) delayed tree (Sec. 5, Def. 5.2); L1 = 0 is
+    root expansion (Sec. 3.2).  Trunk first, then chain by chain."""
+    parent = [-1]
+    last = 0
+    for _ in range(L1):
+        parent.append(last)
+        last = len(parent) - 1
+    for _ in range(K):
+        prev = last
+        for _ in range(L2):
+            parent.append(prev)
+            prev = len(parent) - 1
+    return parent
+
+
+def random_dist(rng, V, sparsity=0.0):
+    x = rng.gamma(0.7, size=V) + 1e-3
+    if sparsity > 0:
+        mask = rng.random(V) < sparsity
+        if mask.all():
+            mask[rng.integers(V)] = False
+        x = np.where(mask, 0.0, x)
+    return x / x.sum()
+
+
+class ContextModel:
+    """Context-consistent next-token distributions p(.|prefix), q(.|prefix)."""
+
+    def __init__(self, rng, V, max_len, zero_frac=0.0):
+        self.V = V
+        self.p = {}
+        self.q = {}
+        for ln in range(max_len + 1):
+            for pre in itertools.product(range(V), repeat=ln):
+                self.p[pre] = random_dist(rng, V, zero_frac)
+                # the draft must be able to propose everything it is asked about
+                self.q[pre] = random_dist(rng, V, 0.0)
+
+    def seq_prob_p(self, seq):
+        pr = 1.0
+        for i, t in enumerate(seq):
+            pr *= self.p[tuple(seq[:i])][t]
+        return pr
+
+
+def node_contexts(parent, tokens):
+    ctx = [()]
+    for n in range(1, len(parent)):
+        ctx.append(ctx[parent[n]] + (int(tokens[n]),))
+    return ctx
+
+
+def output_distribution(method, parent, model):
+    """Exact distribution of the emitted sequence (accepted tokens + bonus),
+    over the randomness of drafting (tokens ~ q along every edge, i.i.d. across
+    siblings) and of verification."""
+    N = len(parent)
+    V = model.V
+    out = {}
+    for toks in itertools.product(range(V), repeat=N - 1):
+        tokens = (0,) + toks
+        ctx = node_contexts(parent, tokens)
+        tree_prob = 1.0
+        for n in range(1, N):
+            tree_prob *= model.q[ctx[parent[n]]][tokens[n]]
+        if tree_prob == 0.0:
+            continue
+        outcomes = orc.enumerate_outcomes(
+            method, parent, tokens, lambda n: model.p[ctx[n]], lambda n: model.q[ctx[n]])
+        assert abs(sum(pr for pr, _, _ in outcomes) - 1.0) < 1e-12
+        for pr, stop, P in outcomes:
+            assert np.all(P >= 0) and abs(P.sum() - 1.0) < 1e-12
+            for y in range(V):
+                if P[y] > 0:
+                    seq = ctx[stop] + (y,)
+                    out[seq] = out.get(seq, 0.0) + tree_prob * pr * P[y]
+    return out
+
+
+def losslessness_error(out, model, full_len):
+    """max over full-length sequences w of | P(output extended by p equals w) - prod p(w_i|w_<i) |."""
+    V = model.V
+    worst = 0.0
+    for w in itertools.product(range(V), repeat=full_len):
+        got = 0.0
+        for ln in range(1, full_len + 1):
+            m = out.get(tuple(w[:ln]), 0.0)
+            if m:
+                ext = 1.0
+                for i in range(ln, full_len):
+                    ext *= model.p[tuple(w[:i])][w[i]]
+                got += m * ext
+        worst = max(worst, abs(got - model.seq_prob_p(w)))
+    return worst
+
+
+# --------------------------------------------------------------------------
+# T1  losslessness (Sec. 3.2 Def. 3.2; Sec. 5 "preserving the target distribution")
+# --------------------------------------------------------------------------
+
+LOSSLESS_SHAPES = [
+    # (V, K, L1, L2)
+    (4, 1, 0, 2), (4, 2, 0, 1), (4, 2, 0, 2), (3, 3, 0, 2), (5, 2, 0, 2),
+    (4, 2, 1, 1), (4, 2, 1, 2), (3, 2, 2, 1), (3, 3, 1, 1), (6, 2, 0, 2),
+]
+
+
+@pytest.mark.parametrize("method", METHODS)
+@pytest.mark.parametrize("V,K,L1,L2", LOSSLESS_SHAPES)
+def test_T1_output_follows_target_distribution(method, V, K, L1, L2):
+    rng = np.random.default_rng(1000 * V + 100 * K + 10 * L1 + L2)
+    depth = L1 + L2
+    model = ContextModel(rng, V, depth, zero_frac=0.25)
+    parent = delayed_parent(K, L1, L2)
+    out = output_distribution(method, parent, model)
+    assert abs(sum(out.values()) - 1.0) < 1e-12
+    assert losslessness_error(out, model, depth + 1) < 1e-13
+
+
+def test_T1_irregular_tree_is_lossless_too():
+    # a tree that is neither root- nor delayed-expanded: the rules are stated
+    # for any ordered tree whose sibling tokens are i.i.d. draws from q
+    parent = [-1, 0, 0, 1, 1, 2]
+    rng = np.random.default_rng(77)
+    model = ContextModel(rng, 3, 2, zero_frac=0.2)
+    for method in METHODS:
+        out = output_distribution(method, parent, model)
+        assert losslessness_error(out, model, 3) < 1e-13
+
+
+# --------------------------------------------------------------------------
+# T2  SpecInfer on a single path is naive speculative sampling (Sec. 3.1, App. B.4)
+# --------------------------------------------------------------------------
+
+def naive_speculative_sampling(p_rows, q_rows, tokens, u):
+    """Sec. 3.1: accept node i independently with min(1, p/q); keep the deepest
+    node whose ancestors are all accepted; correction from norm (p-q)_+ of that
+    node, or p itself at the end of the block."""
+    L = len(tokens) - 1
+    acc = [u[i] < min(1.0, p_rows[i - 1][tokens[i]] / q_rows[i - 1][tokens[i]])
+           for i in range(1, L + 1)]
+    tau = 0
+    while tau < L and acc[tau]:
+        tau += 1
+    if tau < L:
+        r = np.maximum(p_rows[tau] - q_rows[tau], 0.0)
+        return tau, r / r.sum()
+    return tau, p_rows[L]
+
+
+@pytest.mark.parametrize("seed", range(20))
+def test_T2_specinfer_k1_is_naive(seed):
+    rng = np.random.default_rng(seed)
+    V, L = 9, 4
+    parent = delayed_parent(1, 0, L)
+    zt = rng.normal(size=(L + 1, V)) * 1.5
+    zd = zt + rng.normal(size=(L + 1, V))
+    T = 0.8
+    p_rows = [orc.softmax_T(z, T) for z in zt]
+    q_rows = [orc.softmax_T(z, T) for z in zd]
+    tokens = [0] + [int(rng.choice(V, p=q_rows[i])) for i in range(L)]
+    u = rng.random(L + 1)
+    res = orc.verify_tree(orc.SPECINFER, parent, tokens, zt, zd, T, u)
+    tau, resid = naive_speculative_sampling(p_rows, q_rows, tokens, u)
+    assert res["accept_len"] == tau
+    np.testing.assert_allclose(res["residual"], resid, atol=1e-14)
+
+
+# --------------------------------------------------------------------------
+# T3  Traversal on a single path is block verification (Sec. 3.1, Sec. 3.2)
+# --------------------------------------------------------------------------
+
+@pytest.mark.parametrize("seed", range(10))
+def test_T3_traversal_k1_has_block_verification_weights(seed):
+    rng = np.random.default_rng(100 + seed)
+    V, L = 7, 5
+    parent = delayed_parent(1, 0, L)
+    zt = rng.normal(size=(L + 1, V)) * 2
+    zd = zt + rng.normal(size=(L + 1, V)) * 1.2
+    p_rows = [orc.softmax_T(z, 1.0) for z in zt]
+    q_rows = [orc.softmax_T(z, 1.0) for z in zd]
+    tokens = [0] + [int(rng.choice(V, p=q_rows[i])) for i in range(L)]
+    probs, dists = orc.all_test_probs(orc.TRAVERSAL, parent, tokens, zt, zd, 1.0)
+    # Sec. 3.1: w(a_1:i) = min(1, w(a_1:i-1) p/q)
+    w = [1.0]
+    for i in range(1, L + 1):
+        w.append(min(1.0, w[i - 1] * p_rows[i - 1][tokens[i]] / q_rows[i - 1][tokens[i]]))
+    # the leaf is tested with its weight
+    assert probs[L] == pytest.approx(w[L], abs=1e-15)
+    # an inner node, reached only after everything below was rejected, is kept
+    # with the w-weighted residual mass S/(S+1-w); correction from norm (w p - q)_+
+    for i in range(1, L):
+        r = np.maximum(w[i] * p_rows[i] - q_rows[i], 0.0)
+        S = r.sum()
+        if S == 0.0:        # w p <= q everywhere: the node cannot be kept
+            assert w[i] < 1.0 and probs[i] == 0.0
+            continue
+        assert probs[i] == pytest.approx(S / (S + 1 - w[i]), abs=1e-14)
+        np.testing.assert_allclose(dists[i], r / S, atol=1e-14)
+    np.testing.assert_allclose(dists[L], p_rows[L], atol=1e-15)
+
+
+def test_T3b_block_verification_not_worse_than_naive():
+    # Sec. 3.1: block verification provably improves on naive speculative
+    # sampling; at L = 1 the two coincide.
+    rng = np.random.default_rng(5)
+    V = 4
+    for L in (1, 2, 3):
+        model = ContextModel(rng, V, L)
+        parent = delayed_parent(1, 0, L)
+        eff = {}
+        for method in METHODS:
+            out = output_distribution(method, parent, model)
+            eff[method] = sum(len(s) * m for s, m in out.items())
+        if L == 1:
+            assert eff[orc.TRAVERSAL] == pytest.approx(eff[orc.SPECINFER], abs=1e-13)
+        else:
+            assert eff[orc.TRAVERSAL] >= eff[orc.SPECINFER] - 1e-13
+
+
+def test_depth1_traversal_equals_specinfer():
+    # With K i.i.d. children of the root and nothing below, both rules test the
+    # children in the same order with the same probabilities.
+    rng = np.random.default_rng(11)
+    V, K = 6, 3
+    parent = delayed_parent(K, 0, 1)
+    zt = rng.normal(size=(K + 1, V)) * 2
+    zd = zt + rng.normal(size=(K + 1, V))
+    q0 = orc.softmax_T(zd[0], 1.0)
+    tokens = [0] + [int(rng.choice(V, p=q0)) for _ in range(K)]
+    ps, ds = orc.all_test_probs(orc.SPECINFER, parent, tokens, zt, zd, 1.0)
+    pt, dt = orc.all_test_probs(orc.TRAVERSAL, parent, tokens, zt, zd, 1.0)
+    np.testing.assert_allclose(ps, pt, atol=1e-14)
+    np.testing.assert_allclose(ds[0], dt[0], atol=1e-14)
+
+
+# --------------------------------------------------------------------------
+# T4  SpecInfer acceptance rate (Sec. 5 Def. 5.1; App. C, "SpecInfer Acceptance")
+# --------------------------------------------------------------------------
+
+def specinfer_acceptance_formula(p, q, k):
+    p = p.copy()
+    p_rej = 1.0
+    m = np.ones_like(p)
+    for _ in range(k):
+        r = np.minimum(p, q).sum()
+        p_rej *= (1.0 - r)
+        if 1.0 - r > 0:
+            m = m * (1.0 - np.maximum(q - p, 0.0) / (1.0 - r))
+        res = np.maximum(p - q, 0.0)
+        if res.sum() > 0:
+            p = res / res.sum()
+    return (1.0 - p_rej) + p_rej * float(np.sum(p * (1.0 - m)))
+
+
+def solver_output_distribution(p, q, xs):
+    """Distribution of the token the oracle's SpecInfer solver outputs for the
+    child tokens xs (a root with len(xs) leaf children)."""
+    k = len(xs)
+    parent = delayed_parent(k, 0, 1)
+    tokens = [0] + list(xs)
+    outcomes = orc.enumerate_outcomes(orc.SPECINFER, parent, tokens, lambda n: p, lambda n: q)
+    dist = np.zeros(len(p))
+    for pr, stop, P in outcomes:
+        if stop == 0:
+            dist += pr * P
+        else:
+            dist[tokens[stop]] += pr
+    return dist
+
+
+@pytest.mark.parametrize("V,k", [(4, 1), (4, 2), (5, 3), (3, 4)])
+def test_T4_specinfer_acceptance_rate(V, k):
+    rng = np.random.default_rng(40 + V + k)
+    p = random_dist(rng, V, 0.2)
+    q = random_dist(rng, V)
+    alpha = 0.0
+    marginal = np.zeros(V)
+    for xs in itertools.product(range(V), repeat=k):
+        w = float(np.prod([q[x] for x in xs]))
+        d = solver_output_distribution(p, q, xs)
+        alpha += w * sum(d[t] for t in set(xs))
+        marginal += w * d
+    assert alpha == pytest.approx(specinfer_acceptance_formula(p, q, k), abs=1e-13)
+    # Def. 3.2: the solver's output follows p
+    np.testing.assert_allclose(marginal, p, atol=1e-13)
+
+
+def test_T6_k1_acceptance_is_overlap_mass():
+    # App. C "Naive Acceptance" at k = 1: sum min(p,q) = 1 - ||p-q||_1 / 2 (Sec. 5)
+    rng = np.random.default_rng(3)
+    p, q = random_dist(rng, 8), random_dist(rng, 8)
+    acc = sum(q[x] * solver_output_distribution(p, q, [x])[x] for x in range(8))
+    assert acc == pytest.approx(np.minimum(p, q).sum(), abs=1e-14)
+    assert acc == pytest.approx(1 - 0.5 * np.abs(p - q).sum(), abs=1e-14)
+
+
+# --------------------------------------------------------------------------
+# T5  SpecInfer branching probabilities (Sec. 5 Def. 5.3; App. D "SpecInfer Branching")
+# --------------------------------------------------------------------------
+
+def specinfer_branching_formula(p, q, xs):
+    """App. D: level i of the recursion has k-i tokens left and works with the
+    i-times-updated residual p_i; its acceptance vector is min(1, p_i/q)."""
+    k = len(xs)
+    ps = [p.copy()]
+    for _ in range(k):
+        r = np.maximum(ps[-1] - q, 0.0)
+        ps.append(r / r.sum() if r.sum() > 0 else ps[-1])
+    acc = [np.minimum(1.0, np.divide(pi, q, out=np.ones_like(pi), where=q > 0)) for pi in ps]
+
+    def B(i, S, x):
+        if i == k:
+            return ps[k][x]
+        tot = 0.0
+        for j, t in enumerate(S):
+            rest = S[:j] + S[j + 1:]
+            tot += acc[i][t] * (1.0 if t == x else 0.0) + (1 - acc[i][t]) * B(i + 1, rest, x)
+        return tot / len(S)
+
+    return {x: B(0, tuple(xs), x) for x in set(xs)}
+
+
+@pytest.mark.parametrize("xs", [(0,), (0, 1), (2, 2), (0, 1, 2), (1, 3, 1), (0, 1, 2, 3)])
+def test_T5_specinfer_branching_probabilities(xs):
+    rng = np.random.default_rng(50 + len(xs))
+    V = 5
+    p, q = random_dist(rng, V), random_dist(rng, V)
+    want = specinfer_branching_formula(p, q, xs)
+    # Alg. 4 picks the next child uniformly at random; the oracle takes them in
+    # index order, so averaging over all orders must give the same law.
+    perms = list(itertools.permutations(xs))
+    got = np.zeros(V)
+    for perm in perms:
+        got += solver_output_distribution(p, q, perm) / len(perms)
+    for x, b in want.items():
+        assert got[x] == pytest.approx(b, abs=1e-13)
+
+
+def test_T7_block_efficiency_is_sum_of_reach_probabilities():
+    # Sec. 5 Eq. (1)-(3): E[tau+1 | tree] = sum over nodes of prod_j B(...).
+    rng = np.random.default_rng(8)
+    V = 5
+    parent = delayed_parent(2, 0, 2)          # nodes: 0; 1-2; 3-4
+    p_rows = [random_dist(rng, V) for _ in range(5)]
+    q_rows = [random_dist(rng, V) for _ in range(5)]
+    tokens = [0, 1, 3, 2, 0]                  # distinct tokens under the root
+    # oracle side: average over the two orders of the root's children
+    eff = 0.0
+    for order in ([0, 1, 2, 3, 4], [0, 3, 4, 1, 2]):
+        toks = [tokens[i] for i in order]
+        pr = [p_rows[i] for i in order]
+        qr = [q_rows[i] for i in order]
+        outs = orc.enumerate_outcomes(orc.SPECINFER, parent, toks, lambda n: pr[n], lambda n: qr[n])
+        depth = orc.node_depths(parent)
+        eff += 0.5 * sum(w * (depth[s] + 1) for w, s, _ in outs)
+    # formula side
+    Broot = specinfer_branching_formula(p_rows[0], q_rows[0], (tokens[1], tokens[3]))
+    b2 = min(1.0, p_rows[1][tokens[2]] / q_rows[1][tokens[2]])
+    b4 = min(1.0, p_rows[3][tokens[4]] / q_rows[3][tokens[4]])
+    want = 1.0 + Broot[tokens[1]] * (1 + b2) + Broot[tokens[3]] * (1 + b4)
+    assert eff == pytest.approx(want, abs=1e-13)
+
+
+# --------------------------------------------------------------------------
+# hand-derived worked example
+# --------------------------------------------------------------------------
+
+@pytest.mark.parametrize("name,method", [("specinfer", orc.SPECINFER), ("traversal", orc.TRAVERSAL)])
+def test_worked_example(name, method):
+    with open(os.path.join(GOLDEN, "worked_example_v3.json")) as f:
+        g = json.load(f)
+    parent, tokens = g["parent"], g["tokens"]
+    p = [np.array(r) if r is not None else None for r in g["p"]]
+    q = [np.array(r) if r is not None else None for r in g["q"]]
+    outs = orc.enumerate_outcomes(method, parent, tokens, lambda n: p[n], lambda n: q[n])
+    stop_prob = {}
+    for w, s, P in outs:
+        stop_prob[s] = stop_prob.get(s, 0.0) + w
+        np.testing.assert_allclose(P, g[name]["stop_dist"][str(s)], atol=1e-14)
+    for s, frac in g[name]["stop_prob"].items():
+        assert stop_prob.get(int(s), 0.0) == pytest.approx(float(Fraction(frac)), abs=1e-15)
+    depth = orc.node_depths(parent)
+    eff = sum(w * (depth[s] + 1) for w, s, _ in outs)
+    assert eff == pytest.approx(float(Fraction(g[name]["block_efficiency"])), abs=1e-14)
+    # per-node test probabilities through the logits interface
+    zt = np.log(np.array([r if r is not None else [1, 1, 1] for r in g["p"]], dtype=float))
+    zd = np.log(np.array([r if r is not None else [1, 1, 1] for r in g["q"]], dtype=float))
+    probs, _ = orc.all_test_probs(method, parent, tokens, zt, zd, 1.0)
+    for n, frac in g[name]["test_prob"].items():
+        assert probs[int(n)] == pytest.approx(float(Fraction(frac)), abs=1e-13)
+
+
+def test_traversal_block_efficiency_not_below_specinfer():
+    # Sec. 4.2: Traversal has the best block efficiency of all methods compared
+    # (an empirical claim; checked here on exact small cases as a sanity pin).
+    rng = np.random.default_rng(21)
+    for (K, L1, L2) in [(2, 0, 2), (2, 1, 1), (3, 0, 2)]:
+        model = ContextModel(rng, 3, L1 + L2)
+        parent = delayed_parent(K, L1, L2)
+        eff = {}
+        for method in METHODS:
+            out = output_distribution(method, parent, model)
+            eff[method] = sum(len(s) * m for s, m in out.items())
+        assert eff[orc.TRAVERSAL] >= eff[orc.SPECINFER] - 1e-12
+
+
+# --------------------------------------------------------------------------
+# T9  invariants and library / brute-force pins of the helpers
+# --------------------------------------------------------------------------
+
+def test_softmax_matches_library_routine():
+    rng = np.random.default_rng(0)
+    z = rng.normal(size=1000) * 5
+    for T in (0.2, 0.6, 1.0, 1.2):
+        np.testing.assert_allclose(orc.softmax_T(z, T), scipy.special.softmax(z / T), rtol=1e-13)
+    assert orc.softmax_T(np.array([1e4, 1e4 - 1.0]), 1.0)[0] == pytest.approx(1 / (1 + math.exp(-1)))
+
+
+def test_sample_index_against_linear_scan():
+    rng = np.random.default_rng(1)
+    for _ in range(200):
+        V = int(rng.integers(1, 12))
+        r = rng.random(V) * (rng.random(V) < 0.6)
+        if r.sum() == 0:
+            r[rng.integers(V)] = 1.0
+        u = rng.random()
+        acc, want = 0.0, None
+        for t in range(V):
+            acc += r[t]
+            if acc > u * np.cumsum(r)[-1]:
+                want = t
+                break
+        t, gap = orc.sample_index(r, u)
+        assert t == want and r[t] > 0 and gap >= 0
+    # u = 0 lands on the first token with mass; a zero-mass token is never drawn
+    assert orc.sample_index([0.0, 0.0, 0.5, 0.5], 0.0)[0] == 2
+    assert orc.sample_index([0.5, 0.0, 0.5], 0.5)[0] == 2
+
+
+def test_sample_index_frequencies():
+    r = np.array([0.1, 0.0, 0.6, 0.3])
+    us = (np.arange(100000) + 0.5) / 100000
+    counts = np.bincount([orc.sample_index(r, u)[0] for u in us[::50]], minlength=4)
+    np.testing.assert_allclose(counts / counts.sum(), r, atol=2e-3)
+
+
+@pytest.mark.parametrize("method", METHODS)
+def test_T9_invariants_on_random_trees(method):
+    rng = np.random.default_rng(9)
+    V = 50
+    for trial in range(30):
+        K, L1, L2 = int(rng.integers(1, 4)), int(rng.integers(0, 3)), int(rng.integers(1, 4))
+        parent = delayed_parent(K, L1, L2)
+        N = len(parent)
+        zt = rng.normal(size=(N, V)) * 3
+        zd = zt + rng.normal(size=(N, V)) * rng.choice([0.0, 0.5, 2.0])
+        T = float(rng.choice([0.2, 0.6, 1.0, 1.2]))
+        tokens = [0] * N
+        for n in range(1, N):
+            tokens[n] = int(rng.choice(V, p=orc.softmax_T(zd[parent[n]], T)))
+        u = rng.random(N)
+        res = orc.verify_tree(method, parent, tokens, zt, zd, T, u)
+        assert np.all(res["residual"] >= 0) and abs(res["residual"].sum() - 1) < 1e-12
+        assert res["residual"][res["bonus_token"]] > 0
+        assert res["path_nodes"] == orc.path_to(parent, res["stop_node"])
+        for (_, a, _, _) in res["decisions"]:
+            assert 0.0 <= a <= 1.0
+        probs, dists = orc.all_test_probs(method, parent, tokens, zt, zd, T)
+        assert np.all((probs >= 0) & (probs <= 1))
+        # the sample-mode walk uses exactly those probabilities
+        for (c, a, _, _) in res["decisions"]:
+            assert a == pytest.approx(probs[c], abs=1e-15)
+        np.testing.assert_allclose(res["residual"], dists[res["stop_node"]], atol=1e-15)
+
+
+def test_identical_models_accept_everything():
+    # p = q: every ratio is 1, the deepest first leaf is accepted by both rules
+    rng = np.random.default_rng(2)
+    parent = delayed_parent(3, 1, 2)
+    N, V = len(parent), 20
+    z = rng.normal(size=(N, V))
+    tokens = [0] + [int(rng.integers(V)) for _ in range(N - 1)]
+    u = rng.random(N)
+    for method in METHODS:
+        res = orc.verify_tree(method, parent, tokens, z, z, 1.0, u)
+        assert res["path_nodes"] == [1, 2, 3]
+        np.testing.assert_allclose(res["residual"], orc.softmax_T(z[3], 1.0), atol=1e-15)
+
+
+def test_zero_target_mass_token_is_never_accepted():
+    V = 4
+    parent = [-1, 0]
+    zt = np.array([[0.0, -np.inf, 0.0, 0.0], [0.0] * V])
+    zd = np.zeros((2, V))
+    for method in METHODS:
+        res = orc.verify_tree(method, parent, [0, 1], zt, zd, 1.0, np.array([0.3, 0.0]))
+        assert res["accept_len"] == 0 and res["bonus_token"] != 1
+
+
+@pytest.mark.parametrize("method", METHODS)
+def test_residual_is_a_shifted_difference_of_p_and_q(method):
+    """Every distribution either rule ever draws from has the form
+    (p - c q)_+ / W(c) for one scalar c (follows from (x_+/W - q)_+ = (x - W q)_+/W).
+    The GPU path relies on this; here the explicit-vector oracle confirms it."""
+    rng = np.random.default_rng(31)
+    parent = delayed_parent(4, 1, 2)
+    N, V = len(parent), 40
+    zt = rng.normal(size=(N, V)) * 2
+    zd = zt + rng.normal(size=(N, V))
+    tokens = [0] * N
+    for n in range(1, N):
+        tokens[n] = int(rng.choice(V, p=orc.softmax_T(zd[parent[n]], 1.0)))
+    _, dists = orc.all_test_probs(method, parent, tokens, zt, zd, 1.0)
+    for n in range(N):
+        p, q, d = orc.softmax_T(zt[n], 1.0), orc.softmax_T(zd[n], 1.0), dists[n]
+        sup = d > 0
+        # on the support d = (p - c q)/W: recover c and W by least squares
+        A = np.stack([p[sup], -q[sup]], axis=1)
+        (invW, c_over_W), *_ = np.linalg.lstsq(A, d[sup], rcond=None)
+        c = c_over_W / invW
+        model = np.maximum(p - c * q, 0.0)
+        np.testing.assert_allclose(model / model.sum(), d, atol=1e-10)
+
+
+def test_uniform_generator_is_reproducible_and_in_range():
+    a = orc.uniforms_from_seed(12345, 1000)
+    b = orc.uniforms_from_seed(12345, 1000)
+    c = orc.uniforms_from_seed(12346, 1000)
+    assert a.dtype == np.float32 and np.array_equal(a, b) and not np.array_equal(a, c)
+    assert a.min() >= 0.0 and a.max() < 1.0
+    assert abs(a.mean() - 0.5) < 0.03
+    # SplitMix64 reference value: first output of the generator seeded with 0
+    # is 0xE220A8397B1DCDAF (Steele, Lea, Flood 2014; widely tabulated).
+    assert orc.uniforms_from_seed(0, 1)[0] == np.float32((0xE220A8397B1DCDAF >> 40) / 2 ** 24)
