@@ -1,0 +1,155 @@
+/*
+ * mpv.h -- batched lossless multi-path verification of draft token trees on one
+ * AMD MI355X (gfx950).  C ABI; no C++ or PyTorch types cross this boundary.
+ *
+ * The operation (paper Sec. 2, step 3 "Verification"): for each of B draft trees
+ * that share one shape, given the target and draft logits of every node, accept
+ * one node of the tree and draw one correction ("bonus") token so that the
+ * emitted tokens follow the target model's distribution.
+ *
+ * Tree (Sec. 3, Def. 3.1; Sec. 3.2 root expansion; Sec. 5, Def. 5.2 delayed
+ * expansion): node 0 is the root (the current context; it has logits but no
+ * token).  parent[n] < n is the parent of node n >= 1.  The ordered child list
+ * of a node is its children in ascending node index.  Sibling tokens are assumed
+ * to be i.i.d. draws from the draft distribution of their parent; equal tokens
+ * under one parent are separate nodes with separate rows.
+ *
+ * Node distributions (Sec. 3; Sec. 4.1 temperatures): p = softmax(z_target / T),
+ * q = softmax(z_draft / T) over the full vocabulary, the same T for both.
+ *
+ * Methods:
+ *   MPV_METHOD_SPECINFER  top-down walk of Sec. 3.2 with the SpecInfer solver of
+ *                         App. B, Alg. 4 (children tried in list order; a child x
+ *                         is accepted with min(1, p(x)/q(x)), otherwise
+ *                         p <- normalise((p - q)_+)); when no child is accepted the
+ *                         bonus token is drawn from the current p.
+ *   MPV_METHOD_TRAVERSAL  bottom-up Traversal Verification (Sec. 3.2), with the
+ *                         block-verification weights of Sec. 3.1:
+ *                         w(child) = min(1, w(node) * P(x)/q(x)); leaves are tested
+ *                         first in depth-first order; when a whole child subtree
+ *                         is rejected the node's weight a and distribution P become
+ *                         S/(S+1-a) and (a*P - q)_+/S with S = sum (a*P - q)_+.
+ *                         The root is always accepted when reached.
+ *
+ * Randomness: the caller supplies one uniform in [0,1) per node and tree.
+ * uniforms[b,n] (n >= 1) is used only by the test of node n ("accept iff u < a");
+ * uniforms[b,0] draws the bonus token by inverse CDF in vocabulary order
+ * (smallest t whose cumulative residual mass exceeds u times the total).
+ *
+ * All calls are thread-compatible, not thread-safe per stream.  No call
+ * allocates or frees device memory or synchronises the device.
+ */
+#ifndef MPV_H
+#define MPV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define MPV_ABI_VERSION 1
+
+/* limits (larger requests return MPV_ERR_UNSUPPORTED) */
+#define MPV_MAX_NODES    64   /* nodes per tree, root included            */
+#define MPV_MAX_CHILDREN 16   /* children of one node                      */
+#define MPV_MAX_VOCAB    (1 << 21)
+
+#define MPV_METHOD_SPECINFER 0
+#define MPV_METHOD_TRAVERSAL 1
+
+#define MPV_DTYPE_F32  0      /* IEEE binary32 logits                      */
+#define MPV_DTYPE_BF16 1      /* bfloat16 logits (upper half of binary32)  */
+
+/* error codes: 0 = success, negative = failure (nothing was launched unless the
+ * code is MPV_ERR_HIP, in which case some kernels may already be enqueued) */
+#define MPV_OK                   0
+#define MPV_ERR_NULL            -1   /* a required pointer is NULL                   */
+#define MPV_ERR_BAD_SHAPE       -2   /* B < 0, N < 1, V < 1, max_depth < tree depth   */
+#define MPV_ERR_BAD_TREE        -3   /* parent[0] != -1 or parent[n] not in [0, n)    */
+#define MPV_ERR_BAD_TEMPERATURE -4   /* T is not a finite number > 0                  */
+#define MPV_ERR_BAD_METHOD      -5
+#define MPV_ERR_BAD_DTYPE       -6
+#define MPV_ERR_WORKSPACE       -7   /* workspace NULL, misaligned or too small       */
+#define MPV_ERR_UNSUPPORTED     -8   /* beyond MPV_MAX_*                              */
+#define MPV_ERR_HIP             -9   /* a HIP call failed; see mpv_last_hip_error()   */
+#define MPV_ERR_ALIGNMENT      -10   /* a logit base pointer is not element-aligned   */
+
+/* Problem description.  Host memory, read during the call only. */
+typedef struct mpv_problem {
+    int32_t B;              /* trees in the batch (0 is allowed: nothing to do)      */
+    int32_t N;              /* nodes per tree, root included                         */
+    int32_t V;              /* vocabulary size                                       */
+    int32_t method;         /* MPV_METHOD_*                                          */
+    int32_t logit_dtype;    /* MPV_DTYPE_*                                           */
+    float   temperature;    /* T > 0, applied to target and draft rows alike         */
+    int32_t max_depth;      /* row width of path_nodes / path_tokens, >= tree depth  */
+    const int32_t* parent;  /* HOST pointer, length N, shared by all trees           */
+} mpv_problem;
+
+/* Device buffers, all caller-owned, borrowed until the enqueued work has run.
+ * Row-major, innermost index contiguous. */
+typedef struct mpv_buffers {
+    /* inputs */
+    const void*    target_logits;  /* [B,N,V] of logit_dtype; every row may be read           */
+    const void*    draft_logits;   /* [B,N,V] of logit_dtype; rows of leaves are never read   */
+    const int32_t* tokens;         /* [B,N]; tokens[b,0] ignored; others in [0,V)             */
+    const float*   uniforms;       /* [B,N] in [0,1)                                          */
+    /* outputs */
+    int32_t*  accept_len;          /* [B]   depth tau of the accepted node                    */
+    int32_t*  path_nodes;          /* [B,max_depth] node indices root-to-accepted, -1 padded  */
+    int32_t*  path_tokens;         /* [B,max_depth] their tokens, -1 padded                   */
+    int32_t*  bonus_token;         /* [B]   the correction token                              */
+    uint32_t* counters;            /* [4]   see MPV_COUNTER_*; zeroed by the call             */
+    /* optional debug outputs (NULL = not wanted) */
+    float* stats;                  /* [B,N,4] m_t, logZ_t, m_d, logZ_d: row maximum and
+                                      ln sum exp((z-m)/T); draft entries of leaves are NaN    */
+    float* edge_probs;             /* [B,N,2] p(x_n), q(x_n) under the parent's softmax; n=0: 1,1 */
+    float* accept_prob;            /* [B,N] probability node n is tested with when reached; n=0: 1 */
+    float* final_residual;         /* [B,V] normalised distribution the bonus token is drawn from */
+} mpv_buffers;
+
+#define MPV_COUNTER_NEAR_TIE_ACCEPT 0  /* tests on the accepted walk with |a - u| < 1e-6     */
+#define MPV_COUNTER_NEAR_TIE_BONUS  1  /* bonus draws within 1e-6 (relative) of a CDF step   */
+#define MPV_COUNTER_ZERO_MASS       2  /* residual updates that found zero mass              */
+#define MPV_COUNTER_BAD_TOKEN       3  /* tokens outside [0,V) (treated as never accepted)   */
+
+/* ABI version of the loaded library (MPV_ABI_VERSION it was built with). */
+int mpv_version(void);
+
+/* Static, never-freed description of an error code. */
+const char* mpv_strerror(int code);
+
+/* The hipError_t (as int) of the most recent failing HIP call made by this
+ * library on the calling thread, 0 if none. */
+int mpv_last_hip_error(void);
+
+/* Bytes of device scratch mpv_verify needs for this problem (depends on B, N and
+ * the tree only).  Writes *out; returns MPV_OK or an error for an invalid problem. */
+int mpv_workspace_bytes(const mpv_problem* problem, size_t* out);
+
+/* Enqueue the whole verification of the batch on `hip_stream` (a hipStream_t
+ * passed as void*; NULL = the default stream) and return without waiting.
+ * `workspace` is DEVICE memory, 256-byte aligned, of at least
+ * mpv_workspace_bytes() bytes, owned by the caller; its contents on entry are
+ * ignored and on exit unspecified.  Two calls that share a workspace or output
+ * buffers must be ordered by the caller (same stream, or events). */
+int mpv_verify(const mpv_problem* problem, const mpv_buffers* buffers,
+               void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Softmax statistics of `rows` contiguous logit rows of length V (the first step
+ * of the path, exposed on its own): out[r] = { max_v z, ln sum_v exp((z - max)/T) }
+ * as float32 pairs.  `logits` and `out` are DEVICE pointers. */
+int mpv_row_stats(const void* logits, int32_t logit_dtype, int64_t rows, int32_t V,
+                  float temperature, float* out, void* hip_stream);
+
+/* Fill d_u[0..count) (DEVICE) with counter-based uniforms in [0,1): element i is
+ * the top 24 bits of the SplitMix64 finaliser applied to
+ * seed + (i+1) * 0x9E3779B97F4A7C15, times 2^-24. */
+int mpv_fill_uniforms(uint64_t seed, int64_t count, float* d_u, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MPV_H */

@@ -1,0 +1,13 @@
+"""MI355X-native batched multi-path verification of draft token trees.
+
+The product is the C-ABI library built from csrc/ (see include/mpv.h); this
+package is only the ctypes binding and the tree-shape helpers around it.
+"""
+
+from .binding import (  # noqa: F401
+    MPV_DTYPE_BF16, MPV_DTYPE_F32, MPV_METHOD_SPECINFER, MPV_METHOD_TRAVERSAL,
+    MpvError, VerifyResult, lib_path, load_library,
+    mpv_fill_uniforms, mpv_last_hip_error, mpv_row_stats, mpv_strerror,
+    mpv_verify, mpv_version, mpv_workspace_bytes,
+)
+from .trees import delayed_tree, root_tree, tree_depth  # noqa: F401

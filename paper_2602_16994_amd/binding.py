@@ -1,0 +1,231 @@
+"""ctypes binding of libmpv.so: argument marshalling only.
+
+Function names and argument order follow include/mpv.h.  torch is used for
+device memory (tensor.data_ptr()) and for the current HIP stream; every step of
+the computation runs in the library's kernels.  There is no CPU fallback: if the
+library is missing, loading raises.
+"""
+
+import ctypes
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+MPV_METHOD_SPECINFER = 0
+MPV_METHOD_TRAVERSAL = 1
+MPV_DTYPE_F32 = 0
+MPV_DTYPE_BF16 = 1
+
+_PKG_DIR = os.path.dirname(os.path.abspath(__file__))
+
+
+def lib_path():
+    return os.path.join(_PKG_DIR, "libmpv.so")
+
+
+class MpvError(RuntimeError):
+    def __init__(self, code, where):
+        self.code = code
+        super().__init__(f"{where}: {mpv_strerror(code)} (code {code})")
+
+
+class _Problem(ctypes.Structure):
+    _fields_ = [
+        ("B", ctypes.c_int32), ("N", ctypes.c_int32), ("V", ctypes.c_int32),
+        ("method", ctypes.c_int32), ("logit_dtype", ctypes.c_int32),
+        ("temperature", ctypes.c_float), ("max_depth", ctypes.c_int32),
+        ("parent", ctypes.POINTER(ctypes.c_int32)),
+    ]
+
+
+class _Buffers(ctypes.Structure):
+    _fields_ = [(name, ctypes.c_void_p) for name in (
+        "target_logits", "draft_logits", "tokens", "uniforms",
+        "accept_len", "path_nodes", "path_tokens", "bonus_token", "counters",
+        "stats", "edge_probs", "accept_prob", "final_residual")]
+
+
+_lib = None
+
+
+def load_library(path=None):
+    """Load libmpv.so (built by paper_2602_16994_amd.build) and declare prototypes."""
+    global _lib
+    if _lib is not None and path is None:
+        return _lib
+    path = path or lib_path()
+    if not os.path.exists(path):
+        raise FileNotFoundError(
+            f"{path} not found: build it with `python -m paper_2602_16994_amd.build` "
+            "(there is no fallback implementation)")
+    lib = ctypes.CDLL(path)
+    lib.mpv_version.restype = ctypes.c_int
+    lib.mpv_version.argtypes = []
+    lib.mpv_strerror.restype = ctypes.c_char_p
+    lib.mpv_strerror.argtypes = [ctypes.c_int]
+    lib.mpv_last_hip_error.restype = ctypes.c_int
+    lib.mpv_last_hip_error.argtypes = []
+    lib.mpv_workspace_bytes.restype = ctypes.c_int
+    lib.mpv_workspace_bytes.argtypes = [ctypes.POINTER(_Problem), ctypes.POINTER(ctypes.c_size_t)]
+    lib.mpv_verify.restype = ctypes.c_int
+    lib.mpv_verify.argtypes = [ctypes.POINTER(_Problem), ctypes.POINTER(_Buffers),
+                               ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+    lib.mpv_row_stats.restype = ctypes.c_int
+    lib.mpv_row_stats.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_int32,
+                                  ctypes.c_float, ctypes.c_void_p, ctypes.c_void_p]
+    lib.mpv_fill_uniforms.restype = ctypes.c_int
+    lib.mpv_fill_uniforms.argtypes = [ctypes.c_uint64, ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p]
+    _lib = lib
+    return lib
+
+
+def mpv_version():
+    return load_library().mpv_version()
+
+
+def mpv_strerror(code):
+    return load_library().mpv_strerror(int(code)).decode()
+
+
+def mpv_last_hip_error():
+    return load_library().mpv_last_hip_error()
+
+
+def _make_problem(B, N, V, method, logit_dtype, temperature, max_depth, parent):
+    arr = (ctypes.c_int32 * len(parent))(*[int(x) for x in parent]) if parent is not None else None
+    prob = _Problem(int(B), int(N), int(V), int(method), int(logit_dtype), float(temperature),
+                    int(max_depth), arr)
+    prob._keepalive = arr
+    return prob
+
+
+def mpv_workspace_bytes(B, N, V, method, logit_dtype, temperature, max_depth, parent):
+    prob = _make_problem(B, N, V, method, logit_dtype, temperature, max_depth, parent)
+    out = ctypes.c_size_t(0)
+    rc = load_library().mpv_workspace_bytes(ctypes.byref(prob), ctypes.byref(out))
+    if rc != 0:
+        raise MpvError(rc, "mpv_workspace_bytes")
+    return out.value
+
+
+def _stream_ptr(stream):
+    import torch
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _dtype_id(t):
+    import torch
+    if t.dtype == torch.float32:
+        return MPV_DTYPE_F32
+    if t.dtype == torch.bfloat16:
+        return MPV_DTYPE_BF16
+    raise TypeError(f"logits must be float32 or bfloat16, got {t.dtype}")
+
+
+@dataclass
+class VerifyResult:
+    accept_len: "object"
+    path_nodes: "object"
+    path_tokens: "object"
+    bonus_token: "object"
+    counters: "object"
+    stats: Optional["object"] = None
+    edge_probs: Optional["object"] = None
+    accept_prob: Optional["object"] = None
+    final_residual: Optional["object"] = None
+    workspace: Optional["object"] = None
+
+
+def mpv_verify(parent, tokens, target_logits, draft_logits, temperature, uniforms, method,
+               max_depth=None, debug=False, out=None, workspace=None, stream=None):
+    """Enqueue one batched verification on the current (or given) torch stream.
+
+    parent: list of N ints (host).  tokens int32 [B,N], target_logits / draft_logits
+    [B,N,V] float32 or bfloat16, uniforms float32 [B,N]: CUDA tensors, contiguous.
+    Returns a VerifyResult of CUDA tensors (asynchronous; synchronise before reading
+    on the host).  `out` may be a previous VerifyResult whose buffers are reused.
+    """
+    import torch
+    from .trees import tree_depth
+    B, N, V = target_logits.shape
+    for t, name in ((tokens, "tokens"), (target_logits, "target_logits"),
+                    (draft_logits, "draft_logits"), (uniforms, "uniforms")):
+        if not t.is_cuda or not t.is_contiguous():
+            raise ValueError(f"{name} must be a contiguous CUDA tensor")
+    if tokens.dtype != torch.int32 or uniforms.dtype != torch.float32:
+        raise TypeError("tokens must be int32 and uniforms float32")
+    if draft_logits.shape != target_logits.shape or draft_logits.dtype != target_logits.dtype:
+        raise ValueError("target and draft logits must have the same shape and dtype")
+    if tuple(tokens.shape) != (B, N) or tuple(uniforms.shape) != (B, N):
+        raise ValueError("tokens and uniforms must be [B,N]")
+    if max_depth is None:
+        max_depth = max(1, tree_depth(list(parent)) if len(parent) == N and N > 0 else 1)
+    dev = target_logits.device
+    prob = _make_problem(B, N, V, method, _dtype_id(target_logits), temperature, max_depth, parent)
+    if out is None:
+        i32 = dict(dtype=torch.int32, device=dev)
+        out = VerifyResult(
+            accept_len=torch.empty(B, **i32),
+            path_nodes=torch.empty(B, max_depth, **i32),
+            path_tokens=torch.empty(B, max_depth, **i32),
+            bonus_token=torch.empty(B, **i32),
+            counters=torch.empty(4, dtype=torch.int32, device=dev),
+        )
+        if debug:
+            f32 = dict(dtype=torch.float32, device=dev)
+            out.stats = torch.empty(B, N, 4, **f32)
+            out.edge_probs = torch.empty(B, N, 2, **f32)
+            out.accept_prob = torch.empty(B, N, **f32)
+            out.final_residual = torch.empty(B, V, **f32)
+    lib = load_library()
+    need = ctypes.c_size_t(0)
+    rc = lib.mpv_workspace_bytes(ctypes.byref(prob), ctypes.byref(need))
+    if rc != 0:
+        raise MpvError(rc, "mpv_workspace_bytes")
+    if workspace is None:
+        workspace = out.workspace
+    if workspace is None or workspace.numel() < need.value:
+        workspace = torch.empty(max(need.value, 256), dtype=torch.uint8, device=dev)
+    out.workspace = workspace
+
+    def ptr(t):
+        return ctypes.c_void_p(t.data_ptr()) if t is not None else ctypes.c_void_p(0)
+
+    bufs = _Buffers(ptr(target_logits), ptr(draft_logits), ptr(tokens), ptr(uniforms),
+                    ptr(out.accept_len), ptr(out.path_nodes), ptr(out.path_tokens),
+                    ptr(out.bonus_token), ptr(out.counters),
+                    ptr(out.stats), ptr(out.edge_probs), ptr(out.accept_prob), ptr(out.final_residual))
+    rc = lib.mpv_verify(ctypes.byref(prob), ctypes.byref(bufs), ptr(workspace),
+                        ctypes.c_size_t(workspace.numel()), _stream_ptr(stream))
+    if rc != 0:
+        raise MpvError(rc, "mpv_verify")
+    return out
+
+
+def mpv_row_stats(logits, temperature, out=None, stream=None):
+    """(max, ln sum exp((z-max)/T)) of every row of a [rows, V] CUDA tensor."""
+    import torch
+    if not logits.is_cuda or not logits.is_contiguous() or logits.dim() != 2:
+        raise ValueError("logits must be a contiguous 2-D CUDA tensor")
+    rows, V = logits.shape
+    if out is None:
+        out = torch.empty(rows, 2, dtype=torch.float32, device=logits.device)
+    rc = load_library().mpv_row_stats(ctypes.c_void_p(logits.data_ptr()), _dtype_id(logits), rows, V,
+                                      float(temperature), ctypes.c_void_p(out.data_ptr()), _stream_ptr(stream))
+    if rc != 0:
+        raise MpvError(rc, "mpv_row_stats")
+    return out
+
+
+def mpv_fill_uniforms(seed, count, out=None, device="cuda", stream=None):
+    """count counter-based uniforms in [0,1) from `seed` (see include/mpv.h)."""
+    import torch
+    if out is None:
+        out = torch.empty(count, dtype=torch.float32, device=device)
+    rc = load_library().mpv_fill_uniforms(ctypes.c_uint64(seed & (2 ** 64 - 1)), int(count),
+                                          ctypes.c_void_p(out.data_ptr()), _stream_ptr(stream))
+    if rc != 0:
+        raise MpvError(rc, "mpv_fill_uniforms")
+    return out

@@ -1,0 +1,752 @@
+// mpv.hip -- kernels and C ABI of the tree-verification library (gfx950 only).
+//
+// Path of one mpv_verify call (all on the caller's stream):
+//   init_kernel            zero counters, root weight = 1
+//   node_task_kernel       one workgroup per (tree, internal node):
+//                            softmax statistics of the node's target and draft rows,
+//                            then, for each child in list order, the probability
+//                            the child is tested with and the residual mass after
+//                            its rejection (a V-wide reduction per child)
+//                          SpecInfer: one launch over all internal nodes
+//                          Traversal: one launch per tree depth (a node's initial
+//                            weight comes from its parent's task)
+//   walk_kernel            one lane per tree: the uniform-dependent walk
+//   sample_kernel          one workgroup per tree: inverse-CDF bonus draw from the
+//                          residual of the stopping node
+//
+// Why this is the same computation as the step-by-step rules: every distribution
+// either rule draws from is (p - c q)_+ / W(c) for one scalar c per node state
+// (since (x_+/W - q)_+ = (x - W q)_+ / W), and each node is tested after exactly
+// one possible history, so its test probability does not depend on the uniforms.
+
+#include <hip/hip_runtime.h>
+#include <math.h>
+#include <stdint.h>
+#include <string.h>
+
+#include "mpv.h"
+#include "mpv_device.h"
+
+namespace mpv {
+
+// ------------------------------------------------------------------ host/device tree tables
+
+struct TreeDesc {
+    int32_t N;
+    int8_t parent[MPV_MAX_NODES];
+    uint8_t nchild[MPV_MAX_NODES];
+    uint8_t child_off[MPV_MAX_NODES];    // start of the node's children in child_list
+    uint8_t child_list[MPV_MAX_NODES];   // children of node 0, of node 1, ... ascending
+    uint8_t depth[MPV_MAX_NODES];
+};
+
+struct NodeList {
+    int32_t count;
+    uint8_t nodes[MPV_MAX_NODES];
+};
+
+// Per-(tree,node) scalars kept in the workspace, all double, each [B*N].
+struct Workspace {
+    double* At;      // log2-partition of the target row (internal nodes)
+    double* Ad;      // same for the draft row
+    double* cfin;    // c of the node's final state (all children rejected)
+    double* Wfin;    // W(c) of that state
+    double* a0;      // Traversal: weight the node starts with
+    double* atest;   // probability the node is tested with
+    float* mt;       // row maxima (for the debug statistics)
+    float* md;
+    int32_t* stop;   // [B] stopping node
+};
+
+struct Args {
+    const void* zt;
+    const void* zd;
+    const int32_t* tokens;
+    const float* uniforms;
+    int32_t* accept_len;
+    int32_t* path_nodes;
+    int32_t* path_tokens;
+    int32_t* bonus;
+    uint32_t* counters;
+    float* dbg_stats;
+    float* dbg_edge;
+    float* dbg_accept;
+    float* dbg_resid;
+    int32_t B, N, V, max_depth;
+    float k32;       // float(log2(e)/T)
+    float invT;
+};
+
+constexpr int kTaskBlock = 512;
+constexpr int kTaskUnroll = 4;
+constexpr int kSampleBlock = 512;
+constexpr int kTile = 512;               // elements per wave tile in the sampler
+constexpr int kMaxTiles = MPV_MAX_VOCAB / kTile;
+
+// ------------------------------------------------------------------ init
+
+__global__ void init_kernel(Workspace ws, Args a) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < 4) a.counters[i] = 0u;
+    if (i < a.B) {
+        ws.a0[static_cast<size_t>(i) * a.N] = 1.0;
+        ws.atest[static_cast<size_t>(i) * a.N] = 1.0;
+        if (a.dbg_edge) {
+            a.dbg_edge[static_cast<size_t>(i) * a.N * 2] = 1.f;
+            a.dbg_edge[static_cast<size_t>(i) * a.N * 2 + 1] = 1.f;
+        }
+    }
+}
+
+// ------------------------------------------------------------------ node task
+
+template <class E, int METHOD>
+__global__ __launch_bounds__(kTaskBlock) void node_task_kernel(TreeDesc tree, NodeList list,
+                                                              Workspace ws, Args a) {
+    using T = typename E::T;
+    __shared__ double scratch[2 * (kTaskBlock / kWave)];
+
+    const int b = blockIdx.x / list.count;
+    const int n = list.nodes[blockIdx.x % list.count];
+    const size_t bn = static_cast<size_t>(b) * a.N + n;
+    const T* zt = static_cast<const T*>(a.zt) + bn * a.V;
+    const T* zd = static_cast<const T*>(a.zd) + bn * a.V;
+    const int V = a.V;
+    const float k32 = a.k32;
+
+    // ---- softmax statistics of both rows (one read of the pair)
+    RowStat rt, rd;
+    {
+        PairStatsF<E, kTaskBlock, kTaskUnroll> f;
+        f.t.init(); f.d.init(); f.k32 = k32;
+        sweep_pair<E, kTaskBlock, kTaskUnroll>(zt, zd, V, f);
+        finish_stats2<kTaskBlock>(f.t, f.d, rt, rd, scratch);
+    }
+
+    // ---- per-child scalars and one residual-mass reduction per child
+    double wa = (METHOD == MPV_METHOD_TRAVERSAL) ? ws.a0[bn] : 1.0;   // node weight a
+    double c = 0.0, W = 1.0;
+    const int k = tree.nchild[n];
+    const double kd = static_cast<double>(k32);
+    for (int j = 0; j < k; ++j) {
+        const int cn = tree.child_list[tree.child_off[n] + j];
+        const size_t bc = static_cast<size_t>(b) * a.N + cn;
+        const int x = a.tokens[bc];
+        double px = 0.0, qx = 0.0;
+        const bool tok_ok = (x >= 0 && x < V);
+        if (tok_ok) {
+            px = exp2(static_cast<double>(E::load_one(zt + x)) * kd - rt.A);
+            qx = exp2(static_cast<double>(E::load_one(zd + x)) * kd - rd.A);
+        } else if (threadIdx.x == 0) {
+            atomicAdd(&a.counters[MPV_COUNTER_BAD_TOKEN], 1u);
+        }
+        const double Px = fmax(px - c * qx, 0.0) / W;     // current distribution at x
+        double w_child;
+        if (METHOD == MPV_METHOD_TRAVERSAL) {
+            // block-verification weight recursion (Sec. 3.1) with the current a and P
+            if (!(wa > 0.0) || !(Px > 0.0)) w_child = 0.0;
+            else if (qx > 0.0) w_child = fmin(1.0, wa * Px / qx);
+            else w_child = 1.0;
+        } else {
+            // App. B Alg. 4: accept x with min(1, p(x)/q(x))
+            if (qx > 0.0) w_child = fmin(1.0, Px / qx);
+            else w_child = (Px > 0.0) ? 1.0 : 0.0;
+        }
+        if (threadIdx.x == 0) {
+            if (METHOD == MPV_METHOD_TRAVERSAL) {
+                ws.a0[bc] = w_child;
+                if (tree.nchild[cn] == 0) ws.atest[bc] = w_child;   // leaves are tested as they are
+            } else {
+                ws.atest[bc] = w_child;
+            }
+            if (a.dbg_edge) {
+                a.dbg_edge[bc * 2] = static_cast<float>(px);
+                a.dbg_edge[bc * 2 + 1] = static_cast<float>(qx);
+            }
+        }
+
+        // ---- the child (SpecInfer) or its whole subtree (Traversal) is rejected:
+        //      P <- norm (a P - q)_+ ,  i.e.  c <- c + W/a ,  W <- W(c)
+        if (METHOD == MPV_METHOD_TRAVERSAL && !(wa > 0.0)) continue;   // (0*P - q)_+ = 0: nothing changes
+        const double c2 = c + W / wa;
+        const ResidualConsts rc = residual_consts(rt.A, rd.A, c2);
+        ResidualMassF<E> f;
+        f.init();
+        f.k32 = k32; f.nAt = rc.nAt; f.nAd = rc.nAd; f.rho = rc.rho;
+        sweep_pair<E, kTaskBlock, kTaskUnroll>(zt, zd, V, f);
+        const double W2 = rc.scale * block_sum<kTaskBlock>(static_cast<double>(f.acc0) + static_cast<double>(f.acc1), scratch);
+        if (W2 > 0.0) {
+            if (METHOD == MPV_METHOD_TRAVERSAL) {
+                const double S = (wa / W) * W2;
+                wa = S / (S + (1.0 - wa));
+            }
+            c = c2;
+            W = W2;
+        } else {
+            if (METHOD == MPV_METHOD_TRAVERSAL) wa = (wa >= 1.0) ? 1.0 : 0.0;
+            if (threadIdx.x == 0) atomicAdd(&a.counters[MPV_COUNTER_ZERO_MASS], 1u);
+        }
+    }
+
+    if (threadIdx.x == 0) {
+        ws.At[bn] = rt.A;
+        ws.Ad[bn] = rd.A;
+        ws.mt[bn] = rt.m;
+        ws.md[bn] = rd.m;
+        ws.cfin[bn] = c;
+        ws.Wfin[bn] = W;
+        if (METHOD == MPV_METHOD_TRAVERSAL && n != 0) ws.atest[bn] = wa;
+    }
+}
+
+// ------------------------------------------------------------------ walk
+
+template <int METHOD>
+__global__ void walk_kernel(TreeDesc tree, Workspace ws, Args a) {
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= a.B) return;
+    const size_t base = static_cast<size_t>(b) * a.N;
+    const float* u = a.uniforms + base;
+    const double* at = ws.atest + base;
+    unsigned near = 0;
+    int stop = 0;
+
+    if (METHOD == MPV_METHOD_SPECINFER) {
+        // top-down: try the children in order, move to the first accepted one
+        int n = 0;
+        for (;;) {
+            int next = -1;
+            for (int j = 0; j < tree.nchild[n]; ++j) {
+                const int cn = tree.child_list[tree.child_off[n] + j];
+                const double uu = static_cast<double>(u[cn]);
+                if (fabs(at[cn] - uu) < 1e-6) ++near;
+                if (uu < at[cn]) { next = cn; break; }
+            }
+            if (next < 0) break;
+            n = next;
+        }
+        stop = n;
+    } else {
+        // bottom-up: depth-first, children before their parent; first accepted node wins
+        uint8_t next_child[MPV_MAX_NODES];
+        int n = 0;
+        next_child[0] = 0;
+        for (;;) {
+            if (next_child[n] < tree.nchild[n]) {
+                const int cn = tree.child_list[tree.child_off[n] + next_child[n]];
+                ++next_child[n];
+                next_child[cn] = 0;
+                n = cn;
+                continue;
+            }
+            if (n == 0) { stop = 0; break; }
+            const double uu = static_cast<double>(u[n]);
+            if (fabs(at[n] - uu) < 1e-6) ++near;
+            if (uu < at[n]) { stop = n; break; }
+            n = tree.parent[n];
+        }
+    }
+
+    // accepted path, root to stop
+    const int len = tree.depth[stop];
+    a.accept_len[b] = len;
+    int32_t* pn = a.path_nodes + static_cast<size_t>(b) * a.max_depth;
+    int32_t* pt = a.path_tokens + static_cast<size_t>(b) * a.max_depth;
+    for (int i = len; i < a.max_depth; ++i) { pn[i] = -1; pt[i] = -1; }
+    for (int n = stop, i = len - 1; n > 0; n = tree.parent[n], --i) {
+        pn[i] = n;
+        pt[i] = a.tokens[base + n];
+    }
+    ws.stop[b] = stop;
+    if (near) atomicAdd(&a.counters[MPV_COUNTER_NEAR_TIE_ACCEPT], near);
+    if (a.dbg_accept) {
+        for (int n = 0; n < a.N; ++n) a.dbg_accept[base + n] = static_cast<float>(at[n]);
+    }
+}
+
+// ------------------------------------------------------------------ bonus sample
+
+// r_v = (p_v - c q_v)_+ up to the common factor 2^-At_lo, for the VEC elements a
+// lane owns in tile `tile` (zero beyond V).  Vector loads when the rows are
+// 16-byte aligned, element loads otherwise.
+template <class E>
+struct ResidualTile {
+    static constexpr int PER_LANE = kTile / kWave;    // 8
+    const typename E::T* zt;
+    const typename E::T* zd;
+    int V;
+    bool aligned, use_d;
+    float k32, nAt, nAd, rho;
+
+    __device__ __forceinline__ void load(int tile, int lane, float (&r)[PER_LANE]) const {
+        const int e0 = tile * kTile + lane * PER_LANE;
+        float t[PER_LANE], d[PER_LANE];
+        if (aligned && e0 + PER_LANE <= V) {
+#pragma unroll
+            for (int q = 0; q < PER_LANE / E::VEC; ++q) {
+                float tv[E::VEC], dv[E::VEC];
+                E::load_vec(zt + e0 + q * E::VEC, tv);
+                if (use_d) E::load_vec(zd + e0 + q * E::VEC, dv);
+#pragma unroll
+                for (int i = 0; i < E::VEC; ++i) { t[q * E::VEC + i] = tv[i]; d[q * E::VEC + i] = use_d ? dv[i] : 0.f; }
+            }
+#pragma unroll
+            for (int i = 0; i < PER_LANE; ++i) r[i] = term(t[i], d[i]);
+        } else {
+#pragma unroll
+            for (int i = 0; i < PER_LANE; ++i) {
+                const int e = e0 + i;
+                if (e < V) {
+                    t[i] = E::load_one(zt + e);
+                    d[i] = use_d ? E::load_one(zd + e) : 0.f;
+                    r[i] = term(t[i], d[i]);
+                } else {
+                    r[i] = 0.f;
+                }
+            }
+        }
+    }
+    __device__ __forceinline__ float term(float t, float d) const {
+        const float et = fast_exp2(fmaf(t, k32, nAt));
+        if (!use_d) return et;
+        const float ed = fast_exp2(fmaf(d, k32, nAd));
+        return fmaxf(fmaf(-rho, ed, et), 0.f);
+    }
+};
+
+template <class E>
+__global__ __launch_bounds__(kSampleBlock) void sample_kernel(TreeDesc tree, Workspace ws, Args a) {
+    using T = typename E::T;
+    constexpr int NW = kSampleBlock / kWave;
+    constexpr int PER_LANE = kTile / kWave;
+    __shared__ double tile_sum[kMaxTiles];
+    __shared__ double scratch[2 * NW];
+    __shared__ int sh_tile;
+    __shared__ double sh_before, sh_total, sh_target;
+
+    const int b = blockIdx.x;
+    const int n = ws.stop[b];
+    const size_t bn = static_cast<size_t>(b) * a.N + n;
+    const T* zt = static_cast<const T*>(a.zt) + bn * a.V;
+    const T* zd = static_cast<const T*>(a.zd) + bn * a.V;
+    const int V = a.V;
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+
+    double At, Ad = 0.0, c = 0.0;
+    if (tree.nchild[n] == 0) {
+        // a leaf: its target row has not been touched yet; the bonus is drawn from p itself
+        RowStatsF<E> f;
+        f.t.init(); f.k32 = a.k32;
+        sweep_row<E, kSampleBlock, kTaskUnroll>(zt, V, f);
+        OnlineLse none; none.init();
+        RowStat rt, rd;
+        finish_stats2<kSampleBlock>(f.t, none, rt, rd, scratch);
+        At = rt.A;
+        if (threadIdx.x == 0) { ws.At[bn] = rt.A; ws.mt[bn] = rt.m; }
+    } else {
+        At = ws.At[bn];
+        Ad = ws.Ad[bn];
+        c = ws.cfin[bn];
+    }
+
+    ResidualTile<E> rt_;
+    rt_.zt = zt; rt_.zd = zd; rt_.V = V;
+    rt_.aligned = ((reinterpret_cast<uintptr_t>(zt) & 15u) == 0);
+    rt_.use_d = (c > 0.0);
+    rt_.k32 = a.k32;
+    if (rt_.use_d) {
+        const ResidualConsts rc = residual_consts(At, Ad, c);
+        rt_.nAt = rc.nAt; rt_.nAd = rc.nAd; rt_.rho = rc.rho;
+    } else {
+        rt_.nAt = -static_cast<float>(At); rt_.nAd = 0.f; rt_.rho = 0.f;
+    }
+
+    // ---- pass 1: mass of every 512-element tile, in vocabulary order
+    const int ntiles = (V + kTile - 1) / kTile;
+    for (int t = wave; t < ntiles; t += NW) {
+        float r[PER_LANE];
+        rt_.load(t, lane, r);
+        float ls = 0.f;
+#pragma unroll
+        for (int i = 0; i < PER_LANE; ++i) ls += r[i];
+        const double s = wave_sum(static_cast<double>(ls));
+        if (lane == 0) tile_sum[t] = s;
+    }
+    __syncthreads();
+
+    // ---- locate the tile that contains u * R (wave 0; each lane owns a run of tiles)
+    if (wave == 0) {
+        const int per = (ntiles + kWave - 1) / kWave;
+        const int t0 = lane * per, t1 = min(t0 + per, ntiles);
+        double run = 0.0;
+        for (int t = t0; t < t1; ++t) run += tile_sum[t];
+        const double incl = wave_inclusive_scan(run);
+        const double total = __shfl(incl, kWave - 1, kWave);
+        const double target = static_cast<double>(a.uniforms[static_cast<size_t>(b) * a.N]) * total;
+        const unsigned long long hit = __ballot(incl > target && run > 0.0);
+        int owner = hit ? (__ffsll(static_cast<long long>(hit)) - 1) : -1;
+        if (owner < 0) {           // rounding only: last lane that has mass
+            const unsigned long long any = __ballot(run > 0.0);
+            owner = any ? (63 - __clzll(static_cast<long long>(any))) : 0;
+        }
+        if (lane == owner) {
+            double acc = incl - run;
+            int found = -1, last_mass = t0;
+            double before = acc;
+            for (int t = t0; t < t1; ++t) {
+                const double ts = tile_sum[t];
+                if (ts > 0.0) last_mass = t;
+                if (found < 0 && acc + ts > target && ts > 0.0) { found = t; before = acc; }
+                acc += ts;
+            }
+            if (found < 0) {       // rounding only: last tile of the run that has mass
+                found = last_mass;
+                before = incl - run;
+                for (int t = t0; t < last_mass; ++t) before += tile_sum[t];
+            }
+            sh_tile = found;
+            sh_before = before;
+            sh_total = total;
+            sh_target = target;
+        }
+    }
+    __syncthreads();
+
+    // ---- pass 2: inside that tile (wave 0)
+    if (wave == 0) {
+        const int t = sh_tile;
+        const double rem = sh_target - sh_before;       // mass to cover inside the tile
+        float r[PER_LANE];
+        rt_.load(t, lane, r);
+        float ls = 0.f;
+#pragma unroll
+        for (int i = 0; i < PER_LANE; ++i) ls += r[i];
+        const double lsd = static_cast<double>(ls);
+        const double incl = wave_inclusive_scan(lsd);
+        const unsigned long long hit = __ballot(incl > rem && ls > 0.f);
+        int owner = hit ? (__ffsll(static_cast<long long>(hit)) - 1) : -1;
+        if (owner < 0) {
+            const unsigned long long any = __ballot(ls > 0.f);
+            owner = any ? (63 - __clzll(static_cast<long long>(any))) : 0;
+        }
+        if (lane == owner) {
+            double acc = incl - lsd;
+            int found = -1, last_mass = 0;
+            double lo = acc, hi = acc;
+            for (int i = 0; i < PER_LANE; ++i) {
+                const double ri = static_cast<double>(r[i]);
+                if (ri > 0.0) last_mass = i;
+                if (found < 0 && ri > 0.0 && acc + ri > rem) { found = i; lo = acc; hi = acc + ri; }
+                acc += ri;
+            }
+            if (found < 0) { found = last_mass; lo = rem; hi = rem; }
+            int tok = t * kTile + lane * PER_LANE + found;
+            if (tok >= V) tok = V - 1;
+            a.bonus[b] = tok;
+            const double gap = fmin(fabs(rem - lo), fabs(hi - rem));
+            if (gap < 1e-6 * sh_total) atomicAdd(&a.counters[MPV_COUNTER_NEAR_TIE_BONUS], 1u);
+        }
+    }
+
+    // ---- optional: the normalised distribution itself
+    if (a.dbg_resid) {
+        const double inv = 1.0 / sh_total;
+        float* out = a.dbg_resid + static_cast<size_t>(b) * V;
+        for (int t = wave; t < ntiles; t += NW) {
+            float r[PER_LANE];
+            rt_.load(t, lane, r);
+#pragma unroll
+            for (int i = 0; i < PER_LANE; ++i) {
+                const int e = t * kTile + lane * PER_LANE + i;
+                if (e < V) out[e] = static_cast<float>(static_cast<double>(r[i]) * inv);
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------ stand-alone row statistics
+
+template <class E>
+__global__ __launch_bounds__(kTaskBlock) void row_stats_kernel(const typename E::T* z, int64_t rows, int V,
+                                                              float k32, float invT, float* out) {
+    __shared__ double scratch[2 * (kTaskBlock / kWave)];
+    const int64_t r = blockIdx.x;
+    RowStatsF<E> f;
+    f.t.init(); f.k32 = k32;
+    sweep_row<E, kTaskBlock, kTaskUnroll>(z + r * V, V, f);
+    OnlineLse none; none.init();
+    RowStat rt, rd;
+    finish_stats2<kTaskBlock>(f.t, none, rt, rd, scratch);
+    if (threadIdx.x == 0) {
+        out[2 * r] = rt.m;
+        // ln sum exp((z-m)/T) = ln2 * (A - m*k32)
+        out[2 * r + 1] = static_cast<float>(0.6931471805599453 * (rt.A - static_cast<double>(rt.m) * static_cast<double>(k32)));
+    }
+}
+
+// Debug statistics [B,N,4] from the workspace (internal nodes, stopping leaves) --
+// rows the path never touched are computed here.
+template <class E>
+__global__ __launch_bounds__(kTaskBlock) void debug_stats_kernel(TreeDesc tree, Args a) {
+    using T = typename E::T;
+    __shared__ double scratch[2 * (kTaskBlock / kWave)];
+    const int64_t bn = blockIdx.x;
+    const int n = static_cast<int>(bn % a.N);
+    const T* zt = static_cast<const T*>(a.zt) + bn * a.V;
+    const T* zd = static_cast<const T*>(a.zd) + bn * a.V;
+    const bool leaf = tree.nchild[n] == 0;
+    RowStat rt, rd;
+    if (leaf) {
+        RowStatsF<E> f;
+        f.t.init(); f.k32 = a.k32;
+        sweep_row<E, kTaskBlock, kTaskUnroll>(zt, a.V, f);
+        OnlineLse none; none.init();
+        finish_stats2<kTaskBlock>(f.t, none, rt, rd, scratch);
+    } else {
+        PairStatsF<E, kTaskBlock, kTaskUnroll> f;
+        f.t.init(); f.d.init(); f.k32 = a.k32;
+        sweep_pair<E, kTaskBlock, kTaskUnroll>(zt, zd, a.V, f);
+        finish_stats2<kTaskBlock>(f.t, f.d, rt, rd, scratch);
+    }
+    if (threadIdx.x == 0) {
+        const double kd = static_cast<double>(a.k32);
+        float* o = a.dbg_stats + bn * 4;
+        o[0] = rt.m;
+        o[1] = static_cast<float>(0.6931471805599453 * (rt.A - static_cast<double>(rt.m) * kd));
+        o[2] = leaf ? NAN : rd.m;
+        o[3] = leaf ? NAN : static_cast<float>(0.6931471805599453 * (rd.A - static_cast<double>(rd.m) * kd));
+    }
+}
+
+// ------------------------------------------------------------------ uniforms
+
+__global__ void fill_uniforms_kernel(uint64_t seed, int64_t count, float* out) {
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (i >= count) return;
+    uint64_t z = seed + static_cast<uint64_t>(i + 1) * 0x9E3779B97F4A7C15ull;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    z = z ^ (z >> 31);
+    out[i] = static_cast<float>(z >> 40) * (1.0f / 16777216.0f);
+}
+
+// ------------------------------------------------------------------ host side
+
+thread_local int g_last_hip_error = 0;
+
+static bool hip_ok(hipError_t e) {
+    if (e == hipSuccess) return true;
+    g_last_hip_error = static_cast<int>(e);
+    return false;
+}
+
+struct Plan {
+    TreeDesc tree;
+    int max_tree_depth;
+    int n_internal;
+};
+
+static int validate(const mpv_problem* p, Plan* plan) {
+    if (!p) return MPV_ERR_NULL;
+    if (p->B < 0 || p->N < 1 || p->V < 1) return MPV_ERR_BAD_SHAPE;
+    if (p->N > MPV_MAX_NODES || p->V > MPV_MAX_VOCAB) return MPV_ERR_UNSUPPORTED;
+    if (p->method != MPV_METHOD_SPECINFER && p->method != MPV_METHOD_TRAVERSAL) return MPV_ERR_BAD_METHOD;
+    if (p->logit_dtype != MPV_DTYPE_F32 && p->logit_dtype != MPV_DTYPE_BF16) return MPV_ERR_BAD_DTYPE;
+    if (!(p->temperature > 0.0f) || !isfinite(p->temperature)) return MPV_ERR_BAD_TEMPERATURE;
+    if (!p->parent) return MPV_ERR_NULL;
+    if (p->parent[0] != -1) return MPV_ERR_BAD_TREE;
+    TreeDesc& t = plan->tree;
+    memset(&t, 0, sizeof(t));
+    t.N = p->N;
+    t.parent[0] = -1;
+    int nch[MPV_MAX_NODES] = {0};
+    for (int n = 1; n < p->N; ++n) {
+        const int par = p->parent[n];
+        if (par < 0 || par >= n) return MPV_ERR_BAD_TREE;
+        t.parent[n] = static_cast<int8_t>(par);
+        t.depth[n] = static_cast<uint8_t>(t.depth[par] + 1);
+        ++nch[par];
+    }
+    int off = 0, maxd = 0, internal = 0;
+    for (int n = 0; n < p->N; ++n) {
+        if (nch[n] > MPV_MAX_CHILDREN) return MPV_ERR_UNSUPPORTED;
+        t.nchild[n] = static_cast<uint8_t>(nch[n]);
+        t.child_off[n] = static_cast<uint8_t>(off);
+        off += nch[n];
+        if (t.depth[n] > maxd) maxd = t.depth[n];
+        if (nch[n]) ++internal;
+    }
+    int fill[MPV_MAX_NODES] = {0};
+    for (int n = 1; n < p->N; ++n) {
+        const int par = t.parent[n];
+        t.child_list[t.child_off[par] + fill[par]++] = static_cast<uint8_t>(n);
+    }
+    plan->max_tree_depth = maxd;
+    plan->n_internal = internal;
+    if (p->max_depth < maxd) return MPV_ERR_BAD_SHAPE;
+    return MPV_OK;
+}
+
+static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+static size_t carve(const mpv_problem* p, void* base, Workspace* ws) {
+    const size_t bn = static_cast<size_t>(p->B) * p->N;
+    size_t off = 0;
+    char* b = static_cast<char*>(base);
+    auto take = [&](size_t bytes) { void* q = b ? b + off : nullptr; off = align_up(off + bytes, 256); return q; };
+    double* At = static_cast<double*>(take(bn * 8));
+    double* Ad = static_cast<double*>(take(bn * 8));
+    double* cf = static_cast<double*>(take(bn * 8));
+    double* Wf = static_cast<double*>(take(bn * 8));
+    double* a0 = static_cast<double*>(take(bn * 8));
+    double* at = static_cast<double*>(take(bn * 8));
+    float* mt = static_cast<float*>(take(bn * 4));
+    float* md = static_cast<float*>(take(bn * 4));
+    int32_t* st = static_cast<int32_t*>(take(static_cast<size_t>(p->B) * 4));
+    if (ws) { ws->At = At; ws->Ad = Ad; ws->cfin = cf; ws->Wfin = Wf; ws->a0 = a0; ws->atest = at; ws->mt = mt; ws->md = md; ws->stop = st; }
+    return off < 256 ? 256 : off;
+}
+
+template <class E>
+static int launch_all(const mpv_problem* p, const Plan& plan, const Workspace& ws, const Args& a, hipStream_t s) {
+    const TreeDesc& tree = plan.tree;
+    {
+        const int threads = 256;
+        const int blocks = (max(p->B, 4) + threads - 1) / threads;
+        hipLaunchKernelGGL(init_kernel, dim3(blocks), dim3(threads), 0, s, ws, a);
+    }
+    if (p->method == MPV_METHOD_SPECINFER) {
+        NodeList list; list.count = 0;
+        // nodes with many children first: they are the long tasks
+        for (int kk = MPV_MAX_CHILDREN; kk >= 1; --kk)
+            for (int n = 0; n < p->N; ++n)
+                if (tree.nchild[n] == kk) list.nodes[list.count++] = static_cast<uint8_t>(n);
+        if (list.count) {
+            hipLaunchKernelGGL((node_task_kernel<E, MPV_METHOD_SPECINFER>),
+                               dim3(static_cast<unsigned>(p->B) * list.count), dim3(kTaskBlock), 0, s, tree, list, ws, a);
+        }
+    } else {
+        for (int d = 0; d < plan.max_tree_depth; ++d) {
+            NodeList list; list.count = 0;
+            for (int kk = MPV_MAX_CHILDREN; kk >= 1; --kk)
+                for (int n = 0; n < p->N; ++n)
+                    if (tree.depth[n] == d && tree.nchild[n] == kk) list.nodes[list.count++] = static_cast<uint8_t>(n);
+            if (list.count) {
+                hipLaunchKernelGGL((node_task_kernel<E, MPV_METHOD_TRAVERSAL>),
+                                   dim3(static_cast<unsigned>(p->B) * list.count), dim3(kTaskBlock), 0, s, tree, list, ws, a);
+            }
+        }
+    }
+    {
+        const int threads = 64;
+        const int blocks = (p->B + threads - 1) / threads;
+        if (p->method == MPV_METHOD_SPECINFER)
+            hipLaunchKernelGGL((walk_kernel<MPV_METHOD_SPECINFER>), dim3(blocks), dim3(threads), 0, s, tree, ws, a);
+        else
+            hipLaunchKernelGGL((walk_kernel<MPV_METHOD_TRAVERSAL>), dim3(blocks), dim3(threads), 0, s, tree, ws, a);
+    }
+    hipLaunchKernelGGL((sample_kernel<E>), dim3(p->B), dim3(kSampleBlock), 0, s, tree, ws, a);
+    if (a.dbg_stats) {
+        hipLaunchKernelGGL((debug_stats_kernel<E>), dim3(static_cast<unsigned>(p->B) * p->N), dim3(kTaskBlock), 0, s, tree, a);
+    }
+    return hip_ok(hipGetLastError()) ? MPV_OK : MPV_ERR_HIP;
+}
+
+}  // namespace mpv
+
+// ------------------------------------------------------------------ C ABI
+
+extern "C" {
+
+int mpv_version(void) { return MPV_ABI_VERSION; }
+
+const char* mpv_strerror(int code) {
+    switch (code) {
+        case MPV_OK: return "success";
+        case MPV_ERR_NULL: return "a required pointer is NULL";
+        case MPV_ERR_BAD_SHAPE: return "invalid B, N, V or max_depth smaller than the tree depth";
+        case MPV_ERR_BAD_TREE: return "invalid parent array (need parent[0] = -1 and 0 <= parent[n] < n)";
+        case MPV_ERR_BAD_TEMPERATURE: return "temperature must be a finite number > 0";
+        case MPV_ERR_BAD_METHOD: return "unknown method id";
+        case MPV_ERR_BAD_DTYPE: return "unknown logit dtype";
+        case MPV_ERR_WORKSPACE: return "workspace is NULL, not 256-byte aligned or too small";
+        case MPV_ERR_UNSUPPORTED: return "problem exceeds MPV_MAX_NODES / MPV_MAX_CHILDREN / MPV_MAX_VOCAB";
+        case MPV_ERR_HIP: return "a HIP call failed (see mpv_last_hip_error)";
+        case MPV_ERR_ALIGNMENT: return "logit base pointers must be 16-byte aligned";
+        default: return "unknown error code";
+    }
+}
+
+int mpv_last_hip_error(void) { return mpv::g_last_hip_error; }
+
+int mpv_workspace_bytes(const mpv_problem* problem, size_t* out) {
+    if (!out) return MPV_ERR_NULL;
+    mpv::Plan plan;
+    const int rc = mpv::validate(problem, &plan);
+    if (rc != MPV_OK) return rc;
+    *out = mpv::carve(problem, nullptr, nullptr);
+    return MPV_OK;
+}
+
+int mpv_verify(const mpv_problem* problem, const mpv_buffers* buf, void* workspace,
+               size_t workspace_bytes, void* hip_stream) {
+    mpv::Plan plan;
+    const int rc = mpv::validate(problem, &plan);
+    if (rc != MPV_OK) return rc;
+    if (!buf) return MPV_ERR_NULL;
+    if (problem->B == 0) return MPV_OK;
+    if (!buf->target_logits || !buf->draft_logits || !buf->tokens || !buf->uniforms || !buf->accept_len ||
+        !buf->path_nodes || !buf->path_tokens || !buf->bonus_token || !buf->counters)
+        return MPV_ERR_NULL;
+    if ((reinterpret_cast<uintptr_t>(buf->target_logits) & 15u) || (reinterpret_cast<uintptr_t>(buf->draft_logits) & 15u))
+        return MPV_ERR_ALIGNMENT;
+    const size_t need = mpv::carve(problem, nullptr, nullptr);
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) || workspace_bytes < need) return MPV_ERR_WORKSPACE;
+
+    mpv::Workspace ws;
+    mpv::carve(problem, workspace, &ws);
+    mpv::Args a;
+    a.zt = buf->target_logits; a.zd = buf->draft_logits; a.tokens = buf->tokens; a.uniforms = buf->uniforms;
+    a.accept_len = buf->accept_len; a.path_nodes = buf->path_nodes; a.path_tokens = buf->path_tokens;
+    a.bonus = buf->bonus_token; a.counters = buf->counters;
+    a.dbg_stats = buf->stats; a.dbg_edge = buf->edge_probs; a.dbg_accept = buf->accept_prob; a.dbg_resid = buf->final_residual;
+    a.B = problem->B; a.N = problem->N; a.V = problem->V; a.max_depth = problem->max_depth;
+    a.k32 = static_cast<float>(1.4426950408889634 / static_cast<double>(problem->temperature));
+    a.invT = 1.0f / problem->temperature;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    if (problem->logit_dtype == MPV_DTYPE_F32) return mpv::launch_all<mpv::ElemF32>(problem, plan, ws, a, s);
+    return mpv::launch_all<mpv::ElemBF16>(problem, plan, ws, a, s);
+}
+
+int mpv_row_stats(const void* logits, int32_t logit_dtype, int64_t rows, int32_t V, float temperature,
+                  float* out, void* hip_stream) {
+    if (!logits || !out) return MPV_ERR_NULL;
+    if (rows < 0 || V < 1 || rows > 0x7fffffffLL) return MPV_ERR_BAD_SHAPE;
+    if (V > MPV_MAX_VOCAB) return MPV_ERR_UNSUPPORTED;
+    if (!(temperature > 0.0f) || !isfinite(temperature)) return MPV_ERR_BAD_TEMPERATURE;
+    if (logit_dtype != MPV_DTYPE_F32 && logit_dtype != MPV_DTYPE_BF16) return MPV_ERR_BAD_DTYPE;
+    if (rows == 0) return MPV_OK;
+    const float k32 = static_cast<float>(1.4426950408889634 / static_cast<double>(temperature));
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    if (logit_dtype == MPV_DTYPE_F32)
+        hipLaunchKernelGGL((mpv::row_stats_kernel<mpv::ElemF32>), dim3(static_cast<unsigned>(rows)), dim3(mpv::kTaskBlock), 0, s,
+                           static_cast<const float*>(logits), rows, V, k32, 1.0f / temperature, out);
+    else
+        hipLaunchKernelGGL((mpv::row_stats_kernel<mpv::ElemBF16>), dim3(static_cast<unsigned>(rows)), dim3(mpv::kTaskBlock), 0, s,
+                           static_cast<const uint16_t*>(logits), rows, V, k32, 1.0f / temperature, out);
+    return mpv::hip_ok(hipGetLastError()) ? MPV_OK : MPV_ERR_HIP;
+}
+
+int mpv_fill_uniforms(uint64_t seed, int64_t count, float* d_u, void* hip_stream) {
+    if (count < 0) return MPV_ERR_BAD_SHAPE;
+    if (count == 0) return MPV_OK;
+    if (!d_u) return MPV_ERR_NULL;
+    const int threads = 256;
+    const int64_t blocks = (count + threads - 1) / threads;
+    if (blocks > 0x7fffffffLL) return MPV_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL(mpv::fill_uniforms_kernel, dim3(static_cast<unsigned>(blocks)), dim3(threads), 0,
+                       static_cast<hipStream_t>(hip_stream), seed, count, d_u);
+    return mpv::hip_ok(hipGetLastError()) ? MPV_OK : MPV_ERR_HIP;
+}
+
+}  // extern "C"

@@ -1,0 +1,266 @@
+"""Parity of the HIP library with the fp64 oracle (needs an MI355X).
+
+Every test goes through the C ABI (ctypes binding -> libmpv.so).  Each case
+prints its name and shape before touching the GPU.
+"""
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2602_16994_amd as mpv
+import workloads
+from oracle import mpv_oracle as orc
+from tests.parity_util import check_properties, compare_with_oracle, result_to_host
+
+pytestmark = pytest.mark.gpu
+
+SI, TV = mpv.MPV_METHOD_SPECINFER, mpv.MPV_METHOD_TRAVERSAL
+METHOD_NAME = {SI: "specinfer", TV: "traversal"}
+
+
+def announce(*a):
+    print("[case]", *a, flush=True)
+
+
+def run_library(inputs, T, method, debug=True):
+    res = mpv.mpv_verify(inputs["parent"], inputs["tokens"], inputs["target"], inputs["draft"], T,
+                         inputs["uniforms"], method, debug=debug)
+    torch.cuda.synchronize()
+    return result_to_host(res)
+
+
+def run_case(cfg, method, trees=None, debug=True):
+    announce(cfg.name, METHOD_NAME[method], f"B={cfg.B} N={cfg.N} V={cfg.V} {cfg.dtype} T={cfg.T}")
+    inputs = workloads.make_inputs(cfg, "cuda")
+    got = run_library(inputs, cfg.T, method, debug)
+    host = workloads.to_host(inputs)
+    check_properties(host["parent"], cfg.V, got, host["tokens"])
+    rep = compare_with_oracle(method, host, cfg.T, got, trees=trees, check_debug=debug)
+    print("[report]", rep, "counters", got["counters"].tolist(), flush=True)
+    return rep, got
+
+
+# ---------------------------------------------------------------- the five configurations
+
+@pytest.mark.parametrize("method", [SI, TV])
+def test_config1_tiny(method):
+    run_case(workloads.CONFIGS["tiny"], method)
+
+
+def test_config2_v32k_root_specinfer():
+    # full vocabulary and tree, 6 of the 64 trees
+    run_case(workloads.scaled(workloads.CONFIGS["v32k_root"], B=6), SI)
+
+
+@pytest.mark.parametrize("method", [SI, TV])
+def test_config3_v128k_delayed(method):
+    run_case(workloads.scaled(workloads.CONFIGS["v128k_delayed"], B=4), method)
+
+
+def test_config4_v152k_root_traversal_small_batch():
+    run_case(workloads.scaled(workloads.CONFIGS["v152k_root"], B=3), TV)
+
+
+@pytest.mark.parametrize("method", [SI, TV])
+def test_config5_v262k_delayed(method):
+    run_case(workloads.scaled(workloads.CONFIGS["v262k_delayed"], B=2), method)
+
+
+def test_config4_full_size_sampled_trees():
+    """The benchmark configuration at full size, in the launch configuration the
+    benchmark times (no debug outputs): properties for every tree, the oracle on
+    a sample of trees."""
+    cfg = workloads.CONFIGS["v152k_root"]
+    announce(cfg.name, "full size", f"B={cfg.B} N={cfg.N} V={cfg.V}")
+    inputs = workloads.make_inputs(cfg, "cuda")
+    got = run_library(inputs, cfg.T, TV, debug=False)
+    sample = [0, 1, 37, 100, 128, 200, 254, 255]
+    host = {
+        "parent": inputs["parent"],
+        "tokens": inputs["tokens"].cpu().numpy(),
+        "uniforms": inputs["uniforms"].cpu().numpy(),
+    }
+    check_properties(host["parent"], cfg.V, got, host["tokens"])
+    # copy only the sampled trees' logits to the host
+    tgt = {b: inputs["target"][b].float().cpu().numpy() for b in sample}
+    drf = {b: inputs["draft"][b].float().cpu().numpy() for b in sample}
+
+    host["target"], host["draft"] = tgt, drf
+    rep = compare_with_oracle(TV, host, cfg.T, got, trees=sample, check_debug=False)
+    print("[report]", rep, "counters", got["counters"].tolist(),
+          "mean accepted length (all trees)", float(got["accept_len"].mean()), flush=True)
+    # and the debug probabilities for two of them, run as a separate small batch
+    sub = {k: (v[[0, 255]].contiguous() if torch.is_tensor(v) else v) for k, v in inputs.items()}
+    got2 = run_library(sub, cfg.T, TV, debug=True)
+    rep2 = compare_with_oracle(TV, workloads.to_host(sub), cfg.T, got2)
+    assert np.array_equal(got2["accept_len"], got["accept_len"][[0, 255]])
+    assert np.array_equal(got2["bonus_token"], got["bonus_token"][[0, 255]])
+    print("[report]", rep2, flush=True)
+
+
+# ---------------------------------------------------------------- shapes, tails, edge cases
+
+RAGGED = [
+    # (V, dtype, K, L1, L2, B, T)
+    (1000, "f32", 3, 0, 2, 5, 1.0),       # V % 4 == 0 but rows of 4000 B
+    (1023, "f32", 2, 1, 2, 4, 0.7),       # rows misaligned to 16 B
+    (1001, "bf16", 3, 1, 1, 4, 1.2),      # odd V: rows start at 2-byte offsets
+    (50257, "bf16", 4, 0, 3, 3, 0.8),     # several tiles and a ragged tail
+    (50257, "f32", 2, 2, 2, 2, 0.2),      # cold temperature
+    (7, "f32", 2, 0, 2, 9, 1.0),          # vocabulary smaller than a vector tile
+    (1, "bf16", 2, 0, 1, 2, 1.0),         # a single token
+    (4096, "bf16", 16, 0, 1, 3, 1.0),     # maximum children under one node
+    (2048, "f32", 1, 0, 12, 3, 1.0),      # one deep chain (single path)
+    (8192, "bf16", 1, 5, 0, 3, 1.0),      # trunk only (K=1, L2=0)
+    (3000, "bf16", 4, 3, 4, 2, 1.0),      # N = 20
+]
+
+
+@pytest.mark.parametrize("method", [SI, TV])
+@pytest.mark.parametrize("V,dtype,K,L1,L2,B,T", RAGGED)
+def test_ragged_shapes(method, V, dtype, K, L1, L2, B, T):
+    cfg = workloads.Config(f"ragged_V{V}_{dtype}_K{K}_{L1}_{L2}", B=B, V=V, K=K, L1=L1, L2=L2, dtype=dtype,
+                           T=T, methods=[method], draft_sigma=2.0, target_sigma=1.0, seed=V + 31 * K + L1)
+    run_case(cfg, method)
+
+
+@pytest.mark.parametrize("method", [SI, TV])
+def test_root_only_tree(method):
+    # N = 1: nothing to verify, the bonus token is a plain sample from p(.|root)
+    cfg = workloads.Config("root_only", B=5, V=5000, K=1, L1=0, L2=0, dtype="bf16", T=1.0,
+                           methods=[method], draft_sigma=2.0, target_sigma=1.0, seed=99)
+    rep, got = run_case(cfg, method)
+    assert np.all(got["accept_len"] == 0)
+
+
+@pytest.mark.parametrize("method", [SI, TV])
+def test_irregular_tree(method):
+    parent = [-1, 0, 0, 1, 1, 2, 5, 5, 0, 8, 9]
+    announce("irregular tree", METHOD_NAME[method])
+    cfg = workloads.Config("irregular", B=6, V=2500, K=1, L1=0, L2=0, dtype="f32", T=0.9,
+                           methods=[method], draft_sigma=2.0, target_sigma=1.2, seed=5)
+    cfg.parent = parent
+    inputs = workloads.make_inputs(cfg, "cuda")
+    got = run_library(inputs, cfg.T, method)
+    rep = compare_with_oracle(method, workloads.to_host(inputs), cfg.T, got)
+    print("[report]", rep, flush=True)
+
+
+@pytest.mark.parametrize("method", [SI, TV])
+def test_identical_models_accept_first_leaf(method):
+    announce("p == q", METHOD_NAME[method])
+    cfg = workloads.Config("same", B=4, V=3000, K=3, L1=1, L2=2, dtype="bf16", T=1.0,
+                           methods=[method], draft_sigma=2.0, target_sigma=0.0, seed=17)
+    inputs = workloads.make_inputs(cfg, "cuda")
+    inputs["target"] = inputs["draft"].clone()
+    got = run_library(inputs, cfg.T, method)
+    assert np.all(got["accept_len"] == 3)
+    assert np.all(got["path_nodes"] == np.array([1, 2, 3]))
+    compare_with_oracle(method, workloads.to_host(inputs), cfg.T, got)
+
+
+@pytest.mark.parametrize("method", [SI, TV])
+def test_duplicate_sibling_tokens_and_masked_vocabulary(method):
+    # equal tokens under one parent are separate nodes; -inf logits have zero mass
+    announce("duplicates + -inf", METHOD_NAME[method])
+    cfg = workloads.Config("dups", B=8, V=640, K=4, L1=0, L2=2, dtype="f32", T=1.0,
+                           methods=[method], draft_sigma=1.5, target_sigma=1.5, seed=23)
+    inputs = workloads.make_inputs(cfg, "cuda")
+    inputs["tokens"][:, 3] = inputs["tokens"][:, 1]          # chains 1 and 2 start with the same token
+    inputs["tokens"][:, 5] = inputs["tokens"][:, 1]
+    inputs["target"][:, :, 100:200] = float("-inf")           # tokens the target can never emit
+    got = run_library(inputs, cfg.T, method)
+    host = workloads.to_host(inputs)
+    compare_with_oracle(method, host, cfg.T, got)
+    assert not np.any((got["bonus_token"] >= 100) & (got["bonus_token"] < 200))
+    for b in range(cfg.B):
+        for t in got["path_tokens"][b][: got["accept_len"][b]]:
+            assert not (100 <= t < 200)
+
+
+def test_out_of_range_tokens_are_counted_not_followed():
+    announce("bad tokens")
+    cfg = workloads.Config("badtok", B=3, V=500, K=2, L1=0, L2=2, dtype="f32", T=1.0,
+                           methods=[SI], draft_sigma=1.0, target_sigma=1.0, seed=3)
+    inputs = workloads.make_inputs(cfg, "cuda")
+    inputs["tokens"][:, 1] = cfg.V + 5
+    inputs["tokens"][:, 3] = -2
+    for method in (SI, TV):
+        got = run_library(inputs, cfg.T, method, debug=False)
+        assert got["counters"][3] == 2 * cfg.B
+        assert np.all(got["accept_len"] == 0)
+
+
+def test_empty_batch_is_a_no_op():
+    announce("B = 0")
+    z = torch.empty(0, 3, 16, device="cuda")
+    res = mpv.mpv_verify([-1, 0, 0], torch.empty(0, 3, dtype=torch.int32, device="cuda"), z, z, 1.0,
+                         torch.empty(0, 3, device="cuda"), SI, max_depth=1)
+    torch.cuda.synchronize()
+    assert res.accept_len.numel() == 0
+
+
+def test_results_are_bitwise_reproducible():
+    announce("determinism")
+    cfg = workloads.scaled(workloads.CONFIGS["v128k_delayed"], B=8, V=40000)
+    inputs = workloads.make_inputs(cfg, "cuda")
+    a = run_library(inputs, cfg.T, TV)
+    b = run_library(inputs, cfg.T, TV)
+    for k in a:
+        if a[k] is not None:
+            assert np.array_equal(a[k], b[k], equal_nan=True), k
+
+
+def test_every_uniform_decides_as_the_oracle_does():
+    """Many decisions on few logits: one tree's rows are shared by 512 batch
+    entries that differ only in their uniforms, so every branch of both rules is
+    exercised against the oracle (whose per-node probabilities are computed once)."""
+    announce("uniform sweep")
+    cfg = workloads.Config("usweep", B=1, V=1500, K=3, L1=1, L2=2, dtype="bf16", T=1.0,
+                           methods=[SI, TV], draft_sigma=2.0, target_sigma=1.5, seed=41)
+    one = workloads.make_inputs(cfg, "cuda")
+    B = 512
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(7)
+    inputs = {
+        "parent": one["parent"],
+        "tokens": one["tokens"].expand(B, -1).contiguous(),
+        "target": one["target"].expand(B, -1, -1).contiguous(),
+        "draft": one["draft"].expand(B, -1, -1).contiguous(),
+        "uniforms": torch.rand(B, cfg.N, generator=gen, device="cuda"),
+    }
+    host = workloads.to_host(inputs)
+    for method in (SI, TV):
+        got = run_library(inputs, cfg.T, method, debug=False)
+        rep = compare_with_oracle(method, host, cfg.T, got, check_debug=False)
+        stops = {tuple(r[:l]) for r, l in zip(got["path_nodes"].tolist(), got["accept_len"].tolist())}
+        print("[report]", METHOD_NAME[method], rep, "distinct accepted paths", len(stops), flush=True)
+        assert len(stops) >= 4
+
+
+# ---------------------------------------------------------------- the other entry points
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("V", [1, 5, 1024, 4099, 151936])
+def test_row_stats(dtype, V):
+    announce("row_stats", dtype, V)
+    rows = 7
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(V)
+    z = (torch.randn(rows, V, generator=gen, device="cuda") * 4).to(dtype)
+    for T in (0.2, 1.0, 1.2):
+        out = mpv.mpv_row_stats(z, T).cpu().numpy().astype(np.float64)
+        zz = z.float().cpu().numpy().astype(np.float64)
+        m = zz.max(axis=1)
+        lz = np.log(np.exp((zz - m[:, None]) / T).sum(axis=1))
+        assert np.array_equal(out[:, 0], m)
+        np.testing.assert_allclose(out[:, 1], lz, atol=1e-5)
+
+
+def test_fill_uniforms_matches_the_documented_generator():
+    announce("fill_uniforms")
+    for seed, count in [(0, 1), (12345, 1000), (2 ** 63 + 11, 257)]:
+        got = mpv.mpv_fill_uniforms(seed, count).cpu().numpy()
+        want = orc.uniforms_from_seed(seed, count)
+        assert got.dtype == np.float32 and np.array_equal(got, want)
