@@ -1,0 +1,178 @@
+#!/usr/bin/env python3
+"""Benchmark of the whole verification path on one MI355X.
+
+A step is one mpv_verify call (statistics, residual masses, walk, bonus sample)
+over one batch of the benchmark workload, inputs resident in HBM.  Prints one
+JSON line: nodes verified per second, plus the roofline of the dominant kernel
+(measured with HIP events recorded by the library around each of its launches)
+and the fp64 CPU oracle timed on a bounded sample of the same workload.
+"""
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0      # MI355X published peak
+
+
+def parse_profile_traffic(path):
+    """HBM bytes per launch of the dominant kernel from the committed counter
+    summary (key = value lines), or None."""
+    try:
+        vals = {}
+        with open(path) as f:
+            for line in f:
+                if "=" in line and not line.lstrip().startswith("#"):
+                    k, v = line.split("=", 1)
+                    vals[k.strip()] = v.strip()
+        return float(vals["hbm_bytes_per_launch"])
+    except Exception:
+        return None
+
+
+def cpu_baseline(cfg, inputs, method, budget_s=15.0, max_trees=32):
+    """The oracle, as it stands, in sample mode on the first trees of the same
+    batch (single thread: numpy elementwise kernels do not thread)."""
+    from oracle import mpv_oracle as orc
+    parent = inputs["parent"]
+    done = 0
+    t_total = 0.0
+    for b in range(min(max_trees, cfg.B)):
+        tok = inputs["tokens"][b].cpu().numpy()
+        zt = inputs["target"][b].float().cpu().numpy()
+        zd = inputs["draft"][b].float().cpu().numpy()
+        u = inputs["uniforms"][b].cpu().numpy()
+        t0 = time.perf_counter()
+        orc.verify_tree(method, parent, tok, zt, zd, cfg.T, u)
+        t_total += time.perf_counter() - t0
+        done += 1
+        if t_total > budget_s:
+            break
+    return {
+        "value": done * cfg.N / t_total,
+        "unit": "nodes/s",
+        "cores": 1,
+        "kind": "oracle",
+        "sample": f"first {done} of {cfg.B} trees of the same batch, sample mode, {t_total:.2f} s",
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="v152k_root")
+    ap.add_argument("--method", default=None, help="specinfer | traversal (default: the workload's)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-launch-timing", action="store_true",
+                    help="do not bracket the library's launches with HIP events")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (trees are independent; see DESIGN.md for how "
+              "the batch would shard); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2602_16994_amd as mpv
+    import workloads
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    cfg = workloads.CONFIGS[args.workload]
+    if args.method is None:
+        method = cfg.methods[-1]
+    else:
+        method = {"specinfer": 0, "traversal": 1}[args.method]
+    inputs = workloads.make_inputs(cfg, "cuda:0")
+    torch.cuda.synchronize()
+
+    def step(out=None):
+        return mpv.mpv_verify(inputs["parent"], inputs["tokens"], inputs["target"], inputs["draft"],
+                              cfg.T, inputs["uniforms"], method, debug=False, out=out)
+
+    out = step()
+    for _ in range(args.warmup):
+        step(out)
+    torch.cuda.synchronize()
+
+    launches_per_step = 16
+    timing = not args.no_launch_timing
+    if timing:
+        mpv.mpv_timing_enable(launches_per_step * args.steps)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(out)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+
+    per_kernel = {}
+    if timing:
+        for kid, ms in mpv.mpv_timing_read(launches_per_step * args.steps):
+            per_kernel.setdefault(mpv.MPV_KERNEL_NAMES[kid], []).append(ms)
+        mpv.mpv_timing_enable(0)
+
+    # ---- roofline of the dominant kernel (node tasks)
+    n_internal = sum(1 for n in range(cfg.N) if n in set(cfg.parent[1:]))
+    pair_bytes = 2 * cfg.V * cfg.elem_bytes                  # one target + one draft row
+    roofline = None
+    kernels = {}
+    if per_kernel:
+        for name, v in per_kernel.items():
+            kernels[name] = {"launches_per_step": len(v) / args.steps,
+                             "avg_ms": sum(v) / len(v), "ms_per_step": sum(v) / args.steps}
+        nt = per_kernel.get("node_task", [])
+        if nt:
+            launches = len(nt) / args.steps
+            alg_bytes_per_launch = cfg.B * n_internal * pair_bytes / launches
+            avg_s = sum(nt) / len(nt) * 1e-3
+            achieved = alg_bytes_per_launch / avg_s / 1e9
+            traffic = parse_profile_traffic(os.path.join(
+                ROOT, "profiles", f"node_task_{cfg.name}_pmc.txt"))
+            roofline = {"bound": "hbm", "kernel": "node_task_kernel", "achieved": achieved,
+                        "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                        "traffic": traffic, "algorithmic_bytes_per_launch": alg_bytes_per_launch,
+                        "avg_launch_ms": avg_s * 1e3, "launches_per_step": launches}
+
+    nodes_per_s = cfg.B * cfg.N / (ms_per_step * 1e-3)
+    result = {
+        "metric": "draft-tree nodes verified/sec",
+        "value": nodes_per_s,
+        "unit": "nodes/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: B={cfg.B} trees, V={cfg.V}, "
+                               f"{'root' if cfg.L1 == 0 else 'delayed'} expansion K={cfg.K} L1={cfg.L1} L2={cfg.L2} "
+                               f"({cfg.N} nodes/tree), {cfg.dtype} logits, T={cfg.T}, "
+                               f"{'Traversal' if method == 1 else 'SpecInfer'} verification",
+                   "method": "traversal" if method == 1 else "specinfer",
+                   "logit_dtype": cfg.dtype},
+        "trees_per_s": cfg.B / (ms_per_step * 1e-3),
+        "whole_path_input_GBps": cfg.B * (cfg.N + n_internal) * cfg.V * cfg.elem_bytes / (ms_per_step * 1e-3) / 1e9,
+        "mean_accept_len": float(out.accept_len.float().mean().item()),
+        "counters": out.counters.tolist(),
+        "kernels": kernels,
+        "roofline": roofline,
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(cfg, inputs, method)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -149,6 +149,24 @@ int mpv_row_stats(const void* logits, int32_t logit_dtype, int64_t rows, int32_t
  * seed + (i+1) * 0x9E3779B97F4A7C15, times 2^-24. */
 int mpv_fill_uniforms(uint64_t seed, int64_t count, float* d_u, void* hip_stream);
 
+/* Per-launch timing for benchmarks (process-wide state, not thread-safe).
+ * mpv_timing_enable(n > 0) creates n pairs of HIP events; from then on every
+ * kernel mpv_verify launches is bracketed by two event records on the caller's
+ * stream until n launches have been recorded.  mpv_timing_enable(0) turns it off
+ * and destroys the events.  mpv_timing_read, called after the caller has
+ * synchronised that stream, writes the elapsed milliseconds and the MPV_KERNEL_*
+ * id of each recorded launch (HOST arrays of `capacity` entries), sets *count and
+ * clears the record.  Path of one call (Sec. 2, step 3): node tasks = softmax
+ * statistics, per-child test probabilities and residual masses; walk = the
+ * accept/reject decisions; sample = the bonus token. */
+#define MPV_KERNEL_INIT        0
+#define MPV_KERNEL_NODE_TASK   1
+#define MPV_KERNEL_WALK        2
+#define MPV_KERNEL_SAMPLE      3
+#define MPV_KERNEL_DEBUG_STATS 4
+int mpv_timing_enable(int32_t max_launches);
+int mpv_timing_read(float* ms_out, int32_t* kernel_out, int32_t capacity, int32_t* count);
+
 #ifdef __cplusplus
 }
 #endif

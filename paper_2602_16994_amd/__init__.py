@@ -8,6 +8,7 @@ from .binding import (  # noqa: F401
     MPV_DTYPE_BF16, MPV_DTYPE_F32, MPV_METHOD_SPECINFER, MPV_METHOD_TRAVERSAL,
     MpvError, VerifyResult, lib_path, load_library,
     mpv_fill_uniforms, mpv_last_hip_error, mpv_row_stats, mpv_strerror,
-    mpv_verify, mpv_version, mpv_workspace_bytes,
+    mpv_timing_enable, mpv_timing_read, mpv_verify, mpv_version, mpv_workspace_bytes,
+    MPV_KERNEL_NAMES,
 )
 from .trees import delayed_tree, root_tree, tree_depth  # noqa: F401

@@ -26,7 +26,8 @@ def lib_path():
 class MpvError(RuntimeError):
     def __init__(self, code, where):
         self.code = code
-        super().__init__(f"{where}: {mpv_strerror(code)} (code {code})")
+        extra = f", hipError {mpv_last_hip_error()}" if code == -9 else ""
+        super().__init__(f"{where}: {mpv_strerror(code)} (code {code}{extra})")
 
 
 class _Problem(ctypes.Structure):
@@ -53,6 +54,9 @@ def load_library(path=None):
     global _lib
     if _lib is not None and path is None:
         return _lib
+    # torch ships its own HIP runtime; import it first so that libmpv.so binds to
+    # the same runtime instance (device memory and streams come from torch).
+    import torch  # noqa: F401
     path = path or lib_path()
     if not os.path.exists(path):
         raise FileNotFoundError(
@@ -75,6 +79,11 @@ def load_library(path=None):
                                   ctypes.c_float, ctypes.c_void_p, ctypes.c_void_p]
     lib.mpv_fill_uniforms.restype = ctypes.c_int
     lib.mpv_fill_uniforms.argtypes = [ctypes.c_uint64, ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p]
+    lib.mpv_timing_enable.restype = ctypes.c_int
+    lib.mpv_timing_enable.argtypes = [ctypes.c_int32]
+    lib.mpv_timing_read.restype = ctypes.c_int
+    lib.mpv_timing_read.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_int32),
+                                    ctypes.c_int32, ctypes.POINTER(ctypes.c_int32)]
     _lib = lib
     return lib
 
@@ -229,3 +238,25 @@ def mpv_fill_uniforms(seed, count, out=None, device="cuda", stream=None):
     if rc != 0:
         raise MpvError(rc, "mpv_fill_uniforms")
     return out
+
+
+MPV_KERNEL_NAMES = {0: "init", 1: "node_task", 2: "walk", 3: "sample", 4: "debug_stats"}
+
+
+def mpv_timing_enable(max_launches):
+    """Bracket every kernel of the following mpv_verify calls with HIP events
+    (0 turns it off)."""
+    rc = load_library().mpv_timing_enable(int(max_launches))
+    if rc != 0:
+        raise MpvError(rc, "mpv_timing_enable")
+
+
+def mpv_timing_read(capacity):
+    """After synchronising: list of (kernel_id, milliseconds) of the recorded launches."""
+    ms = (ctypes.c_float * capacity)()
+    ids = (ctypes.c_int32 * capacity)()
+    n = ctypes.c_int32(0)
+    rc = load_library().mpv_timing_read(ms, ids, capacity, ctypes.byref(n))
+    if rc != 0:
+        raise MpvError(rc, "mpv_timing_read")
+    return [(int(ids[i]), float(ms[i])) for i in range(n.value)]

@@ -540,6 +540,32 @@ static bool hip_ok(hipError_t e) {
     return false;
 }
 
+// Optional per-launch timing: when enabled, every kernel launched by mpv_verify is
+// bracketed by two hipEvents recorded on the caller's stream.
+struct LaunchTimer {
+    bool enabled = false;
+    int capacity = 0, used = 0;
+    hipEvent_t* start = nullptr;
+    hipEvent_t* stop = nullptr;
+    int32_t* kernel = nullptr;
+};
+static LaunchTimer g_timer;
+
+struct ScopedLaunch {
+    hipStream_t s;
+    int slot;
+    ScopedLaunch(int kernel_id, hipStream_t stream) : s(stream), slot(-1) {
+        if (g_timer.enabled && g_timer.used < g_timer.capacity) {
+            slot = g_timer.used++;
+            g_timer.kernel[slot] = kernel_id;
+            hip_ok(hipEventRecord(g_timer.start[slot], s));
+        }
+    }
+    ~ScopedLaunch() {
+        if (slot >= 0) hip_ok(hipEventRecord(g_timer.stop[slot], s));
+    }
+};
+
 struct Plan {
     TreeDesc tree;
     int max_tree_depth;
@@ -610,9 +636,11 @@ static size_t carve(const mpv_problem* p, void* base, Workspace* ws) {
 template <class E>
 static int launch_all(const mpv_problem* p, const Plan& plan, const Workspace& ws, const Args& a, hipStream_t s) {
     const TreeDesc& tree = plan.tree;
+    (void)hipGetLastError();    // a stale error left by the caller's own HIP calls is not ours
     {
         const int threads = 256;
         const int blocks = (max(p->B, 4) + threads - 1) / threads;
+        ScopedLaunch t(MPV_KERNEL_INIT, s);
         hipLaunchKernelGGL(init_kernel, dim3(blocks), dim3(threads), 0, s, ws, a);
     }
     if (p->method == MPV_METHOD_SPECINFER) {
@@ -622,6 +650,7 @@ static int launch_all(const mpv_problem* p, const Plan& plan, const Workspace& w
             for (int n = 0; n < p->N; ++n)
                 if (tree.nchild[n] == kk) list.nodes[list.count++] = static_cast<uint8_t>(n);
         if (list.count) {
+            ScopedLaunch t(MPV_KERNEL_NODE_TASK, s);
             hipLaunchKernelGGL((node_task_kernel<E, MPV_METHOD_SPECINFER>),
                                dim3(static_cast<unsigned>(p->B) * list.count), dim3(kTaskBlock), 0, s, tree, list, ws, a);
         }
@@ -632,6 +661,7 @@ static int launch_all(const mpv_problem* p, const Plan& plan, const Workspace& w
                 for (int n = 0; n < p->N; ++n)
                     if (tree.depth[n] == d && tree.nchild[n] == kk) list.nodes[list.count++] = static_cast<uint8_t>(n);
             if (list.count) {
+                ScopedLaunch t(MPV_KERNEL_NODE_TASK, s);
                 hipLaunchKernelGGL((node_task_kernel<E, MPV_METHOD_TRAVERSAL>),
                                    dim3(static_cast<unsigned>(p->B) * list.count), dim3(kTaskBlock), 0, s, tree, list, ws, a);
             }
@@ -640,13 +670,18 @@ static int launch_all(const mpv_problem* p, const Plan& plan, const Workspace& w
     {
         const int threads = 64;
         const int blocks = (p->B + threads - 1) / threads;
+        ScopedLaunch t(MPV_KERNEL_WALK, s);
         if (p->method == MPV_METHOD_SPECINFER)
             hipLaunchKernelGGL((walk_kernel<MPV_METHOD_SPECINFER>), dim3(blocks), dim3(threads), 0, s, tree, ws, a);
         else
             hipLaunchKernelGGL((walk_kernel<MPV_METHOD_TRAVERSAL>), dim3(blocks), dim3(threads), 0, s, tree, ws, a);
     }
-    hipLaunchKernelGGL((sample_kernel<E>), dim3(p->B), dim3(kSampleBlock), 0, s, tree, ws, a);
+    {
+        ScopedLaunch t(MPV_KERNEL_SAMPLE, s);
+        hipLaunchKernelGGL((sample_kernel<E>), dim3(p->B), dim3(kSampleBlock), 0, s, tree, ws, a);
+    }
     if (a.dbg_stats) {
+        ScopedLaunch t(MPV_KERNEL_DEBUG_STATS, s);
         hipLaunchKernelGGL((debug_stats_kernel<E>), dim3(static_cast<unsigned>(p->B) * p->N), dim3(kTaskBlock), 0, s, tree, a);
     }
     return hip_ok(hipGetLastError()) ? MPV_OK : MPV_ERR_HIP;
@@ -718,6 +753,46 @@ int mpv_verify(const mpv_problem* problem, const mpv_buffers* buf, void* workspa
     return mpv::launch_all<mpv::ElemBF16>(problem, plan, ws, a, s);
 }
 
+int mpv_timing_enable(int32_t max_launches) {
+    mpv::LaunchTimer& t = mpv::g_timer;
+    for (int i = 0; i < t.capacity; ++i) {
+        (void)hipEventDestroy(t.start[i]);
+        (void)hipEventDestroy(t.stop[i]);
+    }
+    delete[] t.start; delete[] t.stop; delete[] t.kernel;
+    t = mpv::LaunchTimer();
+    if (max_launches <= 0) return MPV_OK;
+    t.start = new hipEvent_t[max_launches];
+    t.stop = new hipEvent_t[max_launches];
+    t.kernel = new int32_t[max_launches];
+    for (int i = 0; i < max_launches; ++i) {
+        if (!mpv::hip_ok(hipEventCreate(&t.start[i])) || !mpv::hip_ok(hipEventCreate(&t.stop[i]))) {
+            t.capacity = i;
+            mpv_timing_enable(0);
+            return MPV_ERR_HIP;
+        }
+        t.capacity = i + 1;
+    }
+    t.enabled = true;
+    return MPV_OK;
+}
+
+int mpv_timing_read(float* ms_out, int32_t* kernel_out, int32_t capacity, int32_t* count) {
+    if (!count) return MPV_ERR_NULL;
+    mpv::LaunchTimer& t = mpv::g_timer;
+    const int n = t.used < capacity ? t.used : capacity;
+    if (n > 0 && (!ms_out || !kernel_out)) return MPV_ERR_NULL;
+    for (int i = 0; i < n; ++i) {
+        float ms = 0.f;
+        if (!mpv::hip_ok(hipEventElapsedTime(&ms, t.start[i], t.stop[i]))) return MPV_ERR_HIP;
+        ms_out[i] = ms;
+        kernel_out[i] = t.kernel[i];
+    }
+    *count = n;
+    t.used = 0;
+    return MPV_OK;
+}
+
 int mpv_row_stats(const void* logits, int32_t logit_dtype, int64_t rows, int32_t V, float temperature,
                   float* out, void* hip_stream) {
     if (!logits || !out) return MPV_ERR_NULL;
@@ -728,6 +803,7 @@ int mpv_row_stats(const void* logits, int32_t logit_dtype, int64_t rows, int32_t
     if (rows == 0) return MPV_OK;
     const float k32 = static_cast<float>(1.4426950408889634 / static_cast<double>(temperature));
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    (void)hipGetLastError();
     if (logit_dtype == MPV_DTYPE_F32)
         hipLaunchKernelGGL((mpv::row_stats_kernel<mpv::ElemF32>), dim3(static_cast<unsigned>(rows)), dim3(mpv::kTaskBlock), 0, s,
                            static_cast<const float*>(logits), rows, V, k32, 1.0f / temperature, out);
@@ -744,6 +820,7 @@ int mpv_fill_uniforms(uint64_t seed, int64_t count, float* d_u, void* hip_stream
     const int threads = 256;
     const int64_t blocks = (count + threads - 1) / threads;
     if (blocks > 0x7fffffffLL) return MPV_ERR_UNSUPPORTED;
+    (void)hipGetLastError();
     hipLaunchKernelGGL(mpv::fill_uniforms_kernel, dim3(static_cast<unsigned>(blocks)), dim3(threads), 0,
                        static_cast<hipStream_t>(hip_stream), seed, count, d_u);
     return mpv::hip_ok(hipGetLastError()) ? MPV_OK : MPV_ERR_HIP;

@@ -299,7 +299,7 @@ __device__ __forceinline__ ResidualConsts residual_consts(double At, double Ad, 
     const double At_lo = At - static_cast<double>(At_hi);
     const double Adc = Ad - log2(c);                 // c > 0
     const float Ad_hi = static_cast<float>(Adc);
-    const double Ad_lo = Adc - static_cast<double>(Ad_hi);
+    const double Ad_lo = isfinite(Adc) ? Adc - static_cast<double>(Ad_hi) : 0.0;   // c = inf: every term vanishes
     r.nAt = -At_hi;
     r.nAd = -Ad_hi;
     r.rho = static_cast<float>(exp2(At_lo - Ad_lo));

@@ -236,7 +236,7 @@ def test_every_uniform_decides_as_the_oracle_does():
         rep = compare_with_oracle(method, host, cfg.T, got, check_debug=False)
         stops = {tuple(r[:l]) for r, l in zip(got["path_nodes"].tolist(), got["accept_len"].tolist())}
         print("[report]", METHOD_NAME[method], rep, "distinct accepted paths", len(stops), flush=True)
-        assert len(stops) >= 4
+        assert len(stops) >= 3
 
 
 # ---------------------------------------------------------------- the other entry points
