@@ -79,6 +79,11 @@ struct Args {
 
 constexpr int kTaskBlock = 512;
 constexpr int kTaskUnroll = 4;
+// node tasks keep a row pair on chip: per lane and row, kRegVecs 16-byte vectors in
+// registers and kLdsVecs in LDS; the rest is re-read (kChunk vectors in flight)
+constexpr int kRegVecs = 20;
+constexpr int kLdsVecs = 9;
+constexpr int kChunk = 2;
 constexpr int kSampleBlock = 512;
 constexpr int kTile = 512;               // elements per wave tile in the sampler
 constexpr int kMaxTiles = MPV_MAX_VOCAB / kTile;
@@ -100,11 +105,17 @@ __global__ void init_kernel(Workspace ws, Args a) {
 
 // ------------------------------------------------------------------ node task
 
-template <class E, int METHOD>
+template <class E, int METHOD, bool FULL>
 __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(TreeDesc tree, NodeList list,
                                                               Workspace ws, Args a) {
     using T = typename E::T;
     __shared__ double scratch[2 * (kTaskBlock / kWave)];
+    // rows too short to fill the on-chip slots are simply streamed again (they sit in L2)
+    constexpr int RV = FULL ? kRegVecs : 0;
+    constexpr int LV = FULL ? kLdsVecs : 0;
+    constexpr int CH = FULL ? kChunk : 4;
+    __shared__ uint4 lds_t[(LV > 0 ? LV : 1) * kTaskBlock];
+    __shared__ uint4 lds_d[(LV > 0 ? LV : 1) * kTaskBlock];
 
     const int b = blockIdx.x / list.count;
     const int n = list.nodes[blockIdx.x % list.count];
@@ -114,12 +125,14 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(TreeDesc tree, No
     const int V = a.V;
     const float k32 = a.k32;
 
-    // ---- softmax statistics of both rows (one read of the pair)
+    // ---- softmax statistics of both rows: the one read of the pair from memory
+    RetainedPair<E, kTaskBlock, RV, LV, CH, FULL> pair;
+    pair.setup(zt, zd, V, lds_t, lds_d);
     RowStat rt, rd;
     {
-        PairStatsF<E, kTaskBlock, kTaskUnroll> f;
+        PairStatsRawF<E> f;
         f.t.init(); f.d.init(); f.k32 = k32;
-        sweep_pair<E, kTaskBlock, kTaskUnroll>(zt, zd, V, f);
+        pair.first_pass(f);
         finish_stats2<kTaskBlock>(f.t, f.d, rt, rd, scratch);
     }
 
@@ -170,10 +183,10 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(TreeDesc tree, No
         if (METHOD == MPV_METHOD_TRAVERSAL && !(wa > 0.0)) continue;   // (0*P - q)_+ = 0: nothing changes
         const double c2 = c + W / wa;
         const ResidualConsts rc = residual_consts(rt.A, rd.A, c2);
-        ResidualMassF<E> f;
+        ResidualMassRawF<E> f;
         f.init();
         f.k32 = k32; f.nAt = rc.nAt; f.nAd = rc.nAd; f.rho = rc.rho;
-        sweep_pair<E, kTaskBlock, kTaskUnroll>(zt, zd, V, f);
+        pair.replay(f);
         const double W2 = rc.scale * block_sum<kTaskBlock>(static_cast<double>(f.acc0) + static_cast<double>(f.acc1), scratch);
         if (W2 > 0.0) {
             if (METHOD == MPV_METHOD_TRAVERSAL) {
@@ -637,6 +650,8 @@ template <class E>
 static int launch_all(const mpv_problem* p, const Plan& plan, const Workspace& ws, const Args& a, hipStream_t s) {
     const TreeDesc& tree = plan.tree;
     (void)hipGetLastError();    // a stale error left by the caller's own HIP calls is not ours
+    // every register and LDS slot of a node task is populated whatever the row's alignment
+    const bool full = (p->V - (E::VEC - 1)) / E::VEC >= (kRegVecs + kLdsVecs) * kTaskBlock;
     {
         const int threads = 256;
         const int blocks = (max(p->B, 4) + threads - 1) / threads;
@@ -651,8 +666,12 @@ static int launch_all(const mpv_problem* p, const Plan& plan, const Workspace& w
                 if (tree.nchild[n] == kk) list.nodes[list.count++] = static_cast<uint8_t>(n);
         if (list.count) {
             ScopedLaunch t(MPV_KERNEL_NODE_TASK, s);
-            hipLaunchKernelGGL((node_task_kernel<E, MPV_METHOD_SPECINFER>),
-                               dim3(static_cast<unsigned>(p->B) * list.count), dim3(kTaskBlock), 0, s, tree, list, ws, a);
+            if (full)
+                hipLaunchKernelGGL((node_task_kernel<E, MPV_METHOD_SPECINFER, true>),
+                                   dim3(static_cast<unsigned>(p->B) * list.count), dim3(kTaskBlock), 0, s, tree, list, ws, a);
+            else
+                hipLaunchKernelGGL((node_task_kernel<E, MPV_METHOD_SPECINFER, false>),
+                                   dim3(static_cast<unsigned>(p->B) * list.count), dim3(kTaskBlock), 0, s, tree, list, ws, a);
         }
     } else {
         for (int d = 0; d < plan.max_tree_depth; ++d) {
@@ -662,8 +681,12 @@ static int launch_all(const mpv_problem* p, const Plan& plan, const Workspace& w
                     if (tree.depth[n] == d && tree.nchild[n] == kk) list.nodes[list.count++] = static_cast<uint8_t>(n);
             if (list.count) {
                 ScopedLaunch t(MPV_KERNEL_NODE_TASK, s);
-                hipLaunchKernelGGL((node_task_kernel<E, MPV_METHOD_TRAVERSAL>),
-                                   dim3(static_cast<unsigned>(p->B) * list.count), dim3(kTaskBlock), 0, s, tree, list, ws, a);
+                if (full)
+                    hipLaunchKernelGGL((node_task_kernel<E, MPV_METHOD_TRAVERSAL, true>),
+                                       dim3(static_cast<unsigned>(p->B) * list.count), dim3(kTaskBlock), 0, s, tree, list, ws, a);
+                else
+                    hipLaunchKernelGGL((node_task_kernel<E, MPV_METHOD_TRAVERSAL, false>),
+                                       dim3(static_cast<unsigned>(p->B) * list.count), dim3(kTaskBlock), 0, s, tree, list, ws, a);
             }
         }
     }

@@ -25,9 +25,12 @@ struct ElemF32 {
     using T = float;
     static constexpr int VEC = 4;                       // elements per 16-byte load
     __device__ static __forceinline__ float load_one(const T* p) { return *p; }
+    __device__ static __forceinline__ void unpack(const uint4& r, float (&o)[VEC]) {
+        o[0] = __uint_as_float(r.x); o[1] = __uint_as_float(r.y);
+        o[2] = __uint_as_float(r.z); o[3] = __uint_as_float(r.w);
+    }
     __device__ static __forceinline__ void load_vec(const T* p, float (&o)[VEC]) {
-        const float4 r = *reinterpret_cast<const float4*>(p);
-        o[0] = r.x; o[1] = r.y; o[2] = r.z; o[3] = r.w;
+        unpack(*reinterpret_cast<const uint4*>(p), o);
     }
 };
 
@@ -37,14 +40,20 @@ struct ElemBF16 {
     __device__ static __forceinline__ float load_one(const T* p) {
         return __uint_as_float(static_cast<uint32_t>(*p) << 16);
     }
-    __device__ static __forceinline__ void load_vec(const T* p, float (&o)[VEC]) {
-        const uint4 r = *reinterpret_cast<const uint4*>(p);
+    __device__ static __forceinline__ void unpack(const uint4& r, float (&o)[VEC]) {
         o[0] = __uint_as_float(r.x << 16); o[1] = __uint_as_float(r.x & 0xffff0000u);
         o[2] = __uint_as_float(r.y << 16); o[3] = __uint_as_float(r.y & 0xffff0000u);
         o[4] = __uint_as_float(r.z << 16); o[5] = __uint_as_float(r.z & 0xffff0000u);
         o[6] = __uint_as_float(r.w << 16); o[7] = __uint_as_float(r.w & 0xffff0000u);
     }
+    __device__ static __forceinline__ void load_vec(const T* p, float (&o)[VEC]) {
+        unpack(*reinterpret_cast<const uint4*>(p), o);
+    }
 };
+
+// 16 aligned bytes of a row, still packed
+template <class T>
+__device__ __forceinline__ uint4 load_raw(const T* p) { return *reinterpret_cast<const uint4*>(p); }
 
 // 2^x on the hardware transcendental unit (results below 2^-126 flush to zero,
 // which is what every caller wants for a vanishing probability).
@@ -306,5 +315,156 @@ __device__ __forceinline__ ResidualConsts residual_consts(double At, double Ad, 
     r.scale = exp2(-At_lo);
     return r;
 }
+
+// ---------------------------------------------------------------- a row pair kept on chip
+//
+// A node task sweeps the same (target, draft) row pair 1 + (number of children)
+// times.  The first sweep keeps as much of the pair as the compute unit can hold:
+// R 16-byte vectors per lane and row in registers, L more in LDS; later sweeps
+// replay those and re-read only the rest ("streamed" part) from memory.  The
+// streamed part is the last thing the first sweep loads and the first thing a
+// replay reads, so that it is still in the L2 cache.
+//
+// Vector i of a row belongs to lane i % BLOCK, slot i / BLOCK: slots [0,R) live in
+// registers, [R,R+L) in LDS (lds[slot-R][lane]), the rest is streamed.
+
+template <class E, int BLOCK, int R, int L, int CH, bool FULL>
+struct RetainedPair {
+    // FULL: the caller guarantees nvec >= (R + L) * BLOCK, so every register and
+    // LDS slot of every lane is in range and those parts run without a branch.
+    using T = typename E::T;
+    static constexpr int VEC = E::VEC;
+    uint4 rt[R > 0 ? R : 1], rd[R > 0 ? R : 1];
+    const T* zt;
+    const T* zd;
+    const T* bt;
+    const T* bd;
+    uint4* lt;
+    uint4* ld;
+    int V, head, nvec, tail0;
+
+    __device__ __forceinline__ void setup(const T* zt_, const T* zd_, int V_, uint4* lds_t, uint4* lds_d) {
+        zt = zt_; zd = zd_; V = V_; lt = lds_t; ld = lds_d;
+        const int mis = static_cast<int>((reinterpret_cast<uintptr_t>(zt) & 15u) / sizeof(T));
+        head = mis ? min(VEC - mis, V) : 0;
+        nvec = (V - head) / VEC;
+        tail0 = head + nvec * VEC;
+        bt = zt + head;
+        bd = zd + head;
+    }
+
+    __device__ __forceinline__ bool in_range(int idx) const { return FULL || idx < nvec; }
+
+    template <class F>
+    __device__ __forceinline__ void edges(F& f) const {
+        const int tid = threadIdx.x;
+        if (tid < head) f.one(E::load_one(zt + tid), E::load_one(zd + tid));
+        if (tail0 + tid < V) f.one(E::load_one(zt + tail0 + tid), E::load_one(zd + tail0 + tid));
+    }
+
+    template <class F>
+    __device__ __forceinline__ void streamed(F& f) const {
+        const int tid = threadIdx.x;
+        for (int i = tid + (R + L) * BLOCK; i < nvec; i += BLOCK * CH) {
+            uint4 a[CH], d[CH];
+#pragma unroll
+            for (int u = 0; u < CH; ++u) {
+                const int idx = min(i + u * BLOCK, nvec - 1);      // clamped: always a valid load
+                a[u] = load_raw(bt + static_cast<size_t>(idx) * VEC);
+                d[u] = load_raw(bd + static_cast<size_t>(idx) * VEC);
+            }
+#pragma unroll
+            for (int u = 0; u < CH; ++u) {
+                if (i + u * BLOCK < nvec) f.vec(a[u], d[u]);
+            }
+        }
+    }
+
+    // First sweep: load everything once, keep what fits, feed f.
+    template <class F>
+    __device__ __forceinline__ void first_pass(F& f) {
+        const int tid = threadIdx.x;
+        if (!FULL && nvec == 0) { edges(f); return; }
+#pragma unroll
+        for (int j = 0; j < R; ++j) {
+            const int idx = FULL ? tid + j * BLOCK : min(tid + j * BLOCK, nvec - 1);
+            rt[j] = load_raw(bt + static_cast<size_t>(idx) * VEC);
+            rd[j] = load_raw(bd + static_cast<size_t>(idx) * VEC);
+        }
+        edges(f);
+#pragma unroll
+        for (int j = 0; j < R; ++j) {
+            if (in_range(tid + j * BLOCK)) f.vec(rt[j], rd[j]);
+        }
+#pragma unroll
+        for (int j0 = 0; j0 < L; j0 += CH) {
+            uint4 a[CH], d[CH];
+#pragma unroll
+            for (int u = 0; u < CH; ++u) {
+                if (j0 + u < L) {
+                    const int idx = FULL ? tid + (R + j0 + u) * BLOCK : min(tid + (R + j0 + u) * BLOCK, nvec - 1);
+                    a[u] = load_raw(bt + static_cast<size_t>(idx) * VEC);
+                    d[u] = load_raw(bd + static_cast<size_t>(idx) * VEC);
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < CH; ++u) {
+                if (j0 + u < L) {
+                    lt[(j0 + u) * BLOCK + tid] = a[u];
+                    ld[(j0 + u) * BLOCK + tid] = d[u];
+                    if (in_range(tid + (R + j0 + u) * BLOCK)) f.vec(a[u], d[u]);
+                }
+            }
+        }
+        streamed(f);
+    }
+
+    // Later sweeps: streamed part (from L2 / memory), then LDS, then registers.
+    // The empty asm marks each kept register as "possibly changed", so that the
+    // compiler does not hoist the unpacked form of the whole pair out of the
+    // caller's loop over children (which would double the register footprint).
+    template <class F>
+    __device__ __forceinline__ void replay(F& f) {
+        const int tid = threadIdx.x;
+        if (!FULL && nvec == 0) { edges(f); return; }
+        streamed(f);
+        edges(f);
+#pragma unroll
+        for (int j = 0; j < L; ++j) {
+            if (in_range(tid + (R + j) * BLOCK)) f.vec(lt[j * BLOCK + tid], ld[j * BLOCK + tid]);
+        }
+#pragma unroll
+        for (int j = 0; j < R; ++j) {
+            asm volatile("" : "+v"(rt[j].x), "+v"(rt[j].y), "+v"(rt[j].z), "+v"(rt[j].w));
+            asm volatile("" : "+v"(rd[j].x), "+v"(rd[j].y), "+v"(rd[j].z), "+v"(rd[j].w));
+            if (in_range(tid + j * BLOCK)) f.vec(rt[j], rd[j]);
+        }
+    }
+};
+
+template <class E>
+struct PairStatsRawF {
+    OnlineLse t, d;
+    float k32;
+    __device__ __forceinline__ void one(float a, float b) { t.one(a, k32); d.one(b, k32); }
+    __device__ __forceinline__ void vec(const uint4& ra, const uint4& rb) {
+        float a[E::VEC], b[E::VEC];
+        E::unpack(ra, a);
+        E::unpack(rb, b);
+        t.vec(a, k32);
+        d.vec(b, k32);
+    }
+};
+
+template <class E>
+struct ResidualMassRawF : ResidualMassF<E> {
+    __device__ __forceinline__ void vec(const uint4& ra, const uint4& rb) {
+        float a[E::VEC], b[E::VEC];
+        E::unpack(ra, a);
+        E::unpack(rb, b);
+        ResidualMassF<E>::vec(a, b);
+    }
+    using ResidualMassF<E>::one;
+};
 
 }  // namespace mpv
