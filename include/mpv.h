@@ -157,8 +157,9 @@ int mpv_fill_uniforms(uint64_t seed, int64_t count, float* d_u, void* hip_stream
  * synchronised that stream, writes the elapsed milliseconds and the MPV_KERNEL_*
  * id of each recorded launch (HOST arrays of `capacity` entries), sets *count and
  * clears the record.  Path of one call (Sec. 2, step 3): node tasks = softmax
- * statistics, per-child test probabilities and residual masses; walk = the
- * accept/reject decisions; sample = the bonus token. */
+ * statistics, per-child test probabilities and residual masses; sample = the
+ * accept/reject walk followed by the bonus token (MPV_KERNEL_WALK is no longer
+ * a launch of its own; the id stays reserved). */
 #define MPV_KERNEL_INIT        0
 #define MPV_KERNEL_NODE_TASK   1
 #define MPV_KERNEL_WALK        2

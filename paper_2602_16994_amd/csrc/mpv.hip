@@ -10,9 +10,9 @@
 //                          SpecInfer: one launch over all internal nodes
 //                          Traversal: one launch per tree depth (a node's initial
 //                            weight comes from its parent's task)
-//   walk_kernel            one lane per tree: the uniform-dependent walk
-//   sample_kernel          one workgroup per tree: inverse-CDF bonus draw from the
-//                          residual of the stopping node
+//   sample_kernel          one workgroup per tree: its first wave does the
+//                          uniform-dependent walk, then the workgroup draws the bonus
+//                          token by inverse CDF from the residual of the stopping node
 //
 // Why this is the same computation as the step-by-step rules: every distribution
 // either rule draws from is (p - c q)_+ / W(c) for one scalar c per node state
@@ -22,6 +22,7 @@
 #include <hip/hip_runtime.h>
 #include <math.h>
 #include <stdint.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include "mpv.h"
@@ -31,18 +32,20 @@ namespace mpv {
 
 // ------------------------------------------------------------------ host/device tree tables
 
+// 32-bit entries: a lookup with a wave-uniform index then compiles to a scalar load.
 struct TreeDesc {
     int32_t N;
-    int8_t parent[MPV_MAX_NODES];
-    uint8_t nchild[MPV_MAX_NODES];
-    uint8_t child_off[MPV_MAX_NODES];    // start of the node's children in child_list
-    uint8_t child_list[MPV_MAX_NODES];   // children of node 0, of node 1, ... ascending
-    uint8_t depth[MPV_MAX_NODES];
+    int32_t parent[MPV_MAX_NODES];
+    int32_t nchild[MPV_MAX_NODES];
+    int32_t child_off[MPV_MAX_NODES];    // start of the node's children in child_list
+    int32_t child_list[MPV_MAX_NODES];   // children of node 0, of node 1, ... ascending
+    int32_t depth[MPV_MAX_NODES];
+    int32_t postorder[MPV_MAX_NODES];    // depth-first, children (in list order) before their parent; root last
 };
 
 struct NodeList {
     int32_t count;
-    uint8_t nodes[MPV_MAX_NODES];
+    int32_t nodes[MPV_MAX_NODES];
 };
 
 // Per-(tree,node) scalars kept in the workspace, all double, each [B*N].
@@ -75,13 +78,15 @@ struct Args {
     int32_t B, N, V, max_depth;
     float k32;       // float(log2(e)/T)
     float invT;
+    int32_t stagger_blocks;   // the first this-many workgroups of a node-task launch start late ...
+    int32_t stagger_ticks;    // ... by (group of 8 workgroups mod 8) * this many 10 ns ticks
 };
 
 constexpr int kTaskBlock = 512;
 constexpr int kTaskUnroll = 4;
 // node tasks keep a row pair on chip: per lane and row, kRegVecs 16-byte vectors in
 // registers and kLdsVecs in LDS; the rest is re-read (kChunk vectors in flight)
-constexpr int kRegVecs = 20;
+constexpr int kRegVecs = 18;
 constexpr int kLdsVecs = 9;
 constexpr int kChunk = 2;
 constexpr int kSampleBlock = 512;
@@ -125,31 +130,71 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(TreeDesc tree, No
     const int V = a.V;
     const float k32 = a.k32;
 
+    // Every task alternates a memory-bound sweep with compute-bound replays, and all
+    // tasks take about the same time: started together, the compute units would all
+    // load at the same moments and all leave memory idle at the same moments.
+    // Spreading the start of the first wave of workgroups keeps them out of phase.
+    if (static_cast<int>(blockIdx.x) < a.stagger_blocks) {
+        const long long wait = static_cast<long long>((blockIdx.x >> 3) & 7) * a.stagger_ticks;
+        const long long t0 = wall_clock64();
+        while (wall_clock64() - t0 < wait) __builtin_amdgcn_s_sleep(16);    // the clock always advances: bounded
+    }
+#ifdef MPV_PROFILE_PHASES
+    long long tstamp[8]; int nts = 0;
+    { __builtin_amdgcn_sched_barrier(0); tstamp[nts++] = wall_clock64(); __builtin_amdgcn_sched_barrier(0); }
+#endif
+    // ---- the children's tokens and this node's starting weight: fetched now, so that
+    //      their latency hides behind the sweep (lane j looks after child j)
+    __shared__ int ch_tok[MPV_MAX_CHILDREN];
+    __shared__ float ch_zt[MPV_MAX_CHILDREN], ch_zd[MPV_MAX_CHILDREN];
+    __shared__ double sh_a0;
+    const int k = tree.nchild[n];
+    int pf_x = -1;
+    if (threadIdx.x < k)
+        pf_x = a.tokens[static_cast<size_t>(b) * a.N + tree.child_list[tree.child_off[n] + threadIdx.x]];
+    double pf_a0 = 1.0;
+    if (METHOD == MPV_METHOD_TRAVERSAL && threadIdx.x == 0 && n != 0) pf_a0 = ws.a0[bn];
+
     // ---- softmax statistics of both rows: the one read of the pair from memory
     RetainedPair<E, kTaskBlock, RV, LV, CH, FULL> pair;
     pair.setup(zt, zd, V, lds_t, lds_d);
+    pair.issue_register_loads();
+    T pf_t = 0, pf_d = 0;       // kept as stored until the sweep is over: touching them now would wait for every load above
+    if (pf_x >= 0 && pf_x < V) {
+        pf_t = zt[pf_x];
+        pf_d = zd[pf_x];
+    }
     RowStat rt, rd;
     {
         PairStatsRawF<E> f;
         f.t.init(); f.d.init(); f.k32 = k32;
         pair.first_pass(f);
-        finish_stats2<kTaskBlock>(f.t, f.d, rt, rd, scratch);
+#ifdef MPV_PROFILE_PHASES
+        { __builtin_amdgcn_sched_barrier(0); tstamp[nts++] = wall_clock64(); __builtin_amdgcn_sched_barrier(0); }
+#endif
+        if (threadIdx.x < k) { ch_tok[threadIdx.x] = pf_x; ch_zt[threadIdx.x] = E::load_one(&pf_t); ch_zd[threadIdx.x] = E::load_one(&pf_d); }
+        if (threadIdx.x == 0) sh_a0 = pf_a0;
+        finish_stats2<kTaskBlock, false>(f.t, f.d, rt, rd, scratch);     // its barriers publish the above
+        rt.A = uniform_f64(rt.A);
+        rd.A = uniform_f64(rd.A);
     }
+#ifdef MPV_PROFILE_PHASES
+    { __builtin_amdgcn_sched_barrier(0); tstamp[nts++] = wall_clock64(); __builtin_amdgcn_sched_barrier(0); }
+#endif
 
     // ---- per-child scalars and one residual-mass reduction per child
-    double wa = (METHOD == MPV_METHOD_TRAVERSAL) ? ws.a0[bn] : 1.0;   // node weight a
+    double wa = (METHOD == MPV_METHOD_TRAVERSAL) ? uniform_f64(sh_a0) : 1.0;   // node weight a
     double c = 0.0, W = 1.0;
-    const int k = tree.nchild[n];
     const double kd = static_cast<double>(k32);
     for (int j = 0; j < k; ++j) {
         const int cn = tree.child_list[tree.child_off[n] + j];
         const size_t bc = static_cast<size_t>(b) * a.N + cn;
-        const int x = a.tokens[bc];
+        const int x = ch_tok[j];
         double px = 0.0, qx = 0.0;
         const bool tok_ok = (x >= 0 && x < V);
         if (tok_ok) {
-            px = exp2(static_cast<double>(E::load_one(zt + x)) * kd - rt.A);
-            qx = exp2(static_cast<double>(E::load_one(zd + x)) * kd - rd.A);
+            px = exp2(static_cast<double>(ch_zt[j]) * kd - rt.A);
+            qx = exp2(static_cast<double>(ch_zd[j]) * kd - rd.A);
         } else if (threadIdx.x == 0) {
             atomicAdd(&a.counters[MPV_COUNTER_BAD_TOKEN], 1u);
         }
@@ -181,17 +226,24 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(TreeDesc tree, No
         // ---- the child (SpecInfer) or its whole subtree (Traversal) is rejected:
         //      P <- norm (a P - q)_+ ,  i.e.  c <- c + W/a ,  W <- W(c)
         if (METHOD == MPV_METHOD_TRAVERSAL && !(wa > 0.0)) continue;   // (0*P - q)_+ = 0: nothing changes
-        const double c2 = c + W / wa;
+        const double c2 = uniform_f64(c + W / wa);
         const ResidualConsts rc = residual_consts(rt.A, rd.A, c2);
+        const double scale = uniform_f64(rc.scale);
         ResidualMassRawF<E> f;
         f.init();
-        f.k32 = k32; f.nAt = rc.nAt; f.nAd = rc.nAd; f.rho = rc.rho;
+        f.k32 = k32; f.nAt = rc.nAt; f.nAd = rc.nAd; f.rho = uniform_f32(rc.rho);
+#ifdef MPV_PROFILE_PHASES
+        if (j == 0) { __builtin_amdgcn_sched_barrier(0); tstamp[nts++] = wall_clock64(); __builtin_amdgcn_sched_barrier(0); }
+#endif
         pair.replay(f);
-        const double W2 = rc.scale * block_sum<kTaskBlock>(static_cast<double>(f.acc0) + static_cast<double>(f.acc1), scratch);
+#ifdef MPV_PROFILE_PHASES
+        if (j == 0) { __builtin_amdgcn_sched_barrier(0); tstamp[nts++] = wall_clock64(); __builtin_amdgcn_sched_barrier(0); }
+#endif
+        const double W2 = uniform_f64(scale * block_sum<kTaskBlock>(static_cast<double>(f.acc0) + static_cast<double>(f.acc1), scratch));
         if (W2 > 0.0) {
             if (METHOD == MPV_METHOD_TRAVERSAL) {
                 const double S = (wa / W) * W2;
-                wa = S / (S + (1.0 - wa));
+                wa = uniform_f64(S / (S + (1.0 - wa)));
             }
             c = c2;
             W = W2;
@@ -201,6 +253,15 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(TreeDesc tree, No
         }
     }
 
+#ifdef MPV_PROFILE_PHASES
+    { __builtin_amdgcn_sched_barrier(0); tstamp[nts++] = wall_clock64(); __builtin_amdgcn_sched_barrier(0); }
+    // bounds: needs (256*8)*20 floats <= B*N*4, checked by the probe script before it enables this build
+    if ((threadIdx.x & 63) == 0 && a.dbg_stats && blockIdx.x < 256 && static_cast<size_t>(a.B) * a.N * 4 >= 256 * 8 * 20) {
+        float* o = a.dbg_stats + (static_cast<size_t>(blockIdx.x) * 8 + threadIdx.x / 64) * 20;
+        for (int i = 0; i < 6; ++i) o[i] = static_cast<float>(tstamp[i] - tstamp[0]);
+        for (int i = 0; i < 9; ++i) o[6 + i] = static_cast<float>(pair.ts[i] - tstamp[0]);
+    }
+#endif
     if (threadIdx.x == 0) {
         ws.At[bn] = rt.A;
         ws.Ad[bn] = rd.A;
@@ -213,68 +274,68 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(TreeDesc tree, No
 }
 
 // ------------------------------------------------------------------ walk
-
+//
+// The uniform-dependent part of both rules, run by the first wave of the sampling
+// workgroup: lane n compares u[n] with the probability node n is tested with
+// (which does not depend on the uniforms), the 64 outcomes become a bit mask, and
+// the walk itself is a few scalar steps over that mask.
+//   SpecInfer (Sec. 3.2 walk + App. B Alg. 4): from the root, move to the first
+//     accepted child in list order; stop where no child is accepted.
+//   Traversal: nodes are tested in depth-first post-order; the first accepted one
+//     wins, the root is accepted unconditionally.
+// Returns the stopping node (the same value in every lane) and writes the path.
 template <int METHOD>
-__global__ void walk_kernel(TreeDesc tree, Workspace ws, Args a) {
-    const int b = blockIdx.x * blockDim.x + threadIdx.x;
-    if (b >= a.B) return;
+__device__ __forceinline__ int walk_wave(const TreeDesc& tree, const Workspace& ws, const Args& a, int b) {
+    const int lane = threadIdx.x & (kWave - 1);
     const size_t base = static_cast<size_t>(b) * a.N;
-    const float* u = a.uniforms + base;
-    const double* at = ws.atest + base;
-    unsigned near = 0;
+    bool acc = false, near = false;
+    if (lane > 0 && lane < a.N) {
+        const double at = ws.atest[base + lane];
+        const double uu = static_cast<double>(a.uniforms[base + lane]);
+        acc = uu < at;
+        near = fabs(at - uu) < 1e-6;
+        if (a.dbg_accept) a.dbg_accept[base + lane] = static_cast<float>(at);
+    }
+    if (lane == 0 && a.dbg_accept) a.dbg_accept[base] = 1.f;
+    const unsigned long long accm = __ballot(acc);
+    const unsigned long long nearm = __ballot(near);
+    unsigned long long tested = 0ull;
     int stop = 0;
-
     if (METHOD == MPV_METHOD_SPECINFER) {
-        // top-down: try the children in order, move to the first accepted one
         int n = 0;
         for (;;) {
             int next = -1;
-            for (int j = 0; j < tree.nchild[n]; ++j) {
-                const int cn = tree.child_list[tree.child_off[n] + j];
-                const double uu = static_cast<double>(u[cn]);
-                if (fabs(at[cn] - uu) < 1e-6) ++near;
-                if (uu < at[cn]) { next = cn; break; }
+            const int k = tree.nchild[n], off = tree.child_off[n];
+            for (int j = 0; j < k; ++j) {
+                const int cn = tree.child_list[off + j];
+                tested |= 1ull << cn;
+                if ((accm >> cn) & 1ull) { next = cn; break; }
             }
             if (next < 0) break;
             n = next;
         }
         stop = n;
     } else {
-        // bottom-up: depth-first, children before their parent; first accepted node wins
-        uint8_t next_child[MPV_MAX_NODES];
-        int n = 0;
-        next_child[0] = 0;
-        for (;;) {
-            if (next_child[n] < tree.nchild[n]) {
-                const int cn = tree.child_list[tree.child_off[n] + next_child[n]];
-                ++next_child[n];
-                next_child[cn] = 0;
-                n = cn;
-                continue;
-            }
-            if (n == 0) { stop = 0; break; }
-            const double uu = static_cast<double>(u[n]);
-            if (fabs(at[n] - uu) < 1e-6) ++near;
-            if (uu < at[n]) { stop = n; break; }
-            n = tree.parent[n];
+        for (int i = 0; i + 1 < a.N; ++i) {
+            const int n = tree.postorder[i];
+            tested |= 1ull << n;
+            if ((accm >> n) & 1ull) { stop = n; break; }
         }
     }
-
-    // accepted path, root to stop
-    const int len = tree.depth[stop];
-    a.accept_len[b] = len;
-    int32_t* pn = a.path_nodes + static_cast<size_t>(b) * a.max_depth;
-    int32_t* pt = a.path_tokens + static_cast<size_t>(b) * a.max_depth;
-    for (int i = len; i < a.max_depth; ++i) { pn[i] = -1; pt[i] = -1; }
-    for (int n = stop, i = len - 1; n > 0; n = tree.parent[n], --i) {
-        pn[i] = n;
-        pt[i] = a.tokens[base + n];
+    if (lane == 0) {
+        const int len = tree.depth[stop];
+        a.accept_len[b] = len;
+        int32_t* pn = a.path_nodes + static_cast<size_t>(b) * a.max_depth;
+        int32_t* pt = a.path_tokens + static_cast<size_t>(b) * a.max_depth;
+        for (int i = len; i < a.max_depth; ++i) { pn[i] = -1; pt[i] = -1; }
+        for (int n = stop, i = len - 1; n > 0; n = tree.parent[n], --i) {
+            pn[i] = n;
+            pt[i] = a.tokens[base + n];
+        }
+        const int nn = __popcll(nearm & tested);
+        if (nn) atomicAdd(&a.counters[MPV_COUNTER_NEAR_TIE_ACCEPT], static_cast<unsigned>(nn));
     }
-    ws.stop[b] = stop;
-    if (near) atomicAdd(&a.counters[MPV_COUNTER_NEAR_TIE_ACCEPT], near);
-    if (a.dbg_accept) {
-        for (int n = 0; n < a.N; ++n) a.dbg_accept[base + n] = static_cast<float>(at[n]);
-    }
+    return stop;
 }
 
 // ------------------------------------------------------------------ bonus sample
@@ -327,7 +388,7 @@ struct ResidualTile {
     }
 };
 
-template <class E>
+template <class E, int METHOD>
 __global__ __launch_bounds__(kSampleBlock) void sample_kernel(TreeDesc tree, Workspace ws, Args a) {
     using T = typename E::T;
     constexpr int NW = kSampleBlock / kWave;
@@ -337,13 +398,19 @@ __global__ __launch_bounds__(kSampleBlock) void sample_kernel(TreeDesc tree, Wor
     __shared__ int sh_tile;
     __shared__ double sh_before, sh_total, sh_target;
 
+    __shared__ int sh_stop;
     const int b = blockIdx.x;
-    const int n = ws.stop[b];
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    if (wave == 0) {
+        const int stop = walk_wave<METHOD>(tree, ws, a, b);
+        if (lane == 0) sh_stop = stop;
+    }
+    __syncthreads();
+    const int n = sh_stop;
     const size_t bn = static_cast<size_t>(b) * a.N + n;
     const T* zt = static_cast<const T*>(a.zt) + bn * a.V;
     const T* zd = static_cast<const T*>(a.zd) + bn * a.V;
     const int V = a.V;
-    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
 
     double At, Ad = 0.0, c = 0.0;
     if (tree.nchild[n] == 0) {
@@ -602,15 +669,15 @@ static int validate(const mpv_problem* p, Plan* plan) {
     for (int n = 1; n < p->N; ++n) {
         const int par = p->parent[n];
         if (par < 0 || par >= n) return MPV_ERR_BAD_TREE;
-        t.parent[n] = static_cast<int8_t>(par);
-        t.depth[n] = static_cast<uint8_t>(t.depth[par] + 1);
+        t.parent[n] = par;
+        t.depth[n] = t.depth[par] + 1;
         ++nch[par];
     }
     int off = 0, maxd = 0, internal = 0;
     for (int n = 0; n < p->N; ++n) {
         if (nch[n] > MPV_MAX_CHILDREN) return MPV_ERR_UNSUPPORTED;
-        t.nchild[n] = static_cast<uint8_t>(nch[n]);
-        t.child_off[n] = static_cast<uint8_t>(off);
+        t.nchild[n] = nch[n];
+        t.child_off[n] = off;
         off += nch[n];
         if (t.depth[n] > maxd) maxd = t.depth[n];
         if (nch[n]) ++internal;
@@ -618,7 +685,20 @@ static int validate(const mpv_problem* p, Plan* plan) {
     int fill[MPV_MAX_NODES] = {0};
     for (int n = 1; n < p->N; ++n) {
         const int par = t.parent[n];
-        t.child_list[t.child_off[par] + fill[par]++] = static_cast<uint8_t>(n);
+        t.child_list[t.child_off[par] + fill[par]++] = n;
+    }
+    {   // depth-first post-order without recursion
+        int next_child[MPV_MAX_NODES] = {0};
+        int n = 0, out = 0;
+        for (;;) {
+            if (next_child[n] < t.nchild[n]) {
+                n = t.child_list[t.child_off[n] + next_child[n]++];
+                continue;
+            }
+            t.postorder[out++] = n;
+            if (n == 0) break;
+            n = t.parent[n];
+        }
     }
     plan->max_tree_depth = maxd;
     plan->n_internal = internal;
@@ -646,8 +726,33 @@ static size_t carve(const mpv_problem* p, void* base, Workspace* ws) {
     return off < 256 ? 256 : off;
 }
 
+static int compute_units() {
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
+            cus = n;
+        else
+            cus = 256;
+    }
+    return cus;
+}
+
+// Start-up spread for a node-task launch of `blocks` workgroups (see the kernel).
+static void set_stagger(Args& a, long long blocks) {
+    static int us = -1;
+    if (us < 0) {
+        const char* e = getenv("MPV_STAGGER_US");
+        us = e ? atoi(e) : 0;
+    }
+    const int cus = compute_units();
+    if (us > 0 && blocks >= 3ll * cus) { a.stagger_blocks = cus; a.stagger_ticks = us * 100 / 8; }
+    else { a.stagger_blocks = 0; a.stagger_ticks = 0; }
+}
+
 template <class E>
-static int launch_all(const mpv_problem* p, const Plan& plan, const Workspace& ws, const Args& a, hipStream_t s) {
+static int launch_all(const mpv_problem* p, const Plan& plan, const Workspace& ws, Args a, hipStream_t s) {
     const TreeDesc& tree = plan.tree;
     (void)hipGetLastError();    // a stale error left by the caller's own HIP calls is not ours
     // every register and LDS slot of a node task is populated whatever the row's alignment
@@ -663,8 +768,9 @@ static int launch_all(const mpv_problem* p, const Plan& plan, const Workspace& w
         // nodes with many children first: they are the long tasks
         for (int kk = MPV_MAX_CHILDREN; kk >= 1; --kk)
             for (int n = 0; n < p->N; ++n)
-                if (tree.nchild[n] == kk) list.nodes[list.count++] = static_cast<uint8_t>(n);
+                if (tree.nchild[n] == kk) list.nodes[list.count++] = n;
         if (list.count) {
+            set_stagger(a, static_cast<long long>(p->B) * list.count);
             ScopedLaunch t(MPV_KERNEL_NODE_TASK, s);
             if (full)
                 hipLaunchKernelGGL((node_task_kernel<E, MPV_METHOD_SPECINFER, true>),
@@ -678,8 +784,9 @@ static int launch_all(const mpv_problem* p, const Plan& plan, const Workspace& w
             NodeList list; list.count = 0;
             for (int kk = MPV_MAX_CHILDREN; kk >= 1; --kk)
                 for (int n = 0; n < p->N; ++n)
-                    if (tree.depth[n] == d && tree.nchild[n] == kk) list.nodes[list.count++] = static_cast<uint8_t>(n);
+                    if (tree.depth[n] == d && tree.nchild[n] == kk) list.nodes[list.count++] = n;
             if (list.count) {
+                set_stagger(a, static_cast<long long>(p->B) * list.count);
                 ScopedLaunch t(MPV_KERNEL_NODE_TASK, s);
                 if (full)
                     hipLaunchKernelGGL((node_task_kernel<E, MPV_METHOD_TRAVERSAL, true>),
@@ -691,22 +798,18 @@ static int launch_all(const mpv_problem* p, const Plan& plan, const Workspace& w
         }
     }
     {
-        const int threads = 64;
-        const int blocks = (p->B + threads - 1) / threads;
-        ScopedLaunch t(MPV_KERNEL_WALK, s);
-        if (p->method == MPV_METHOD_SPECINFER)
-            hipLaunchKernelGGL((walk_kernel<MPV_METHOD_SPECINFER>), dim3(blocks), dim3(threads), 0, s, tree, ws, a);
-        else
-            hipLaunchKernelGGL((walk_kernel<MPV_METHOD_TRAVERSAL>), dim3(blocks), dim3(threads), 0, s, tree, ws, a);
-    }
-    {
         ScopedLaunch t(MPV_KERNEL_SAMPLE, s);
-        hipLaunchKernelGGL((sample_kernel<E>), dim3(p->B), dim3(kSampleBlock), 0, s, tree, ws, a);
+        if (p->method == MPV_METHOD_SPECINFER)
+            hipLaunchKernelGGL((sample_kernel<E, MPV_METHOD_SPECINFER>), dim3(p->B), dim3(kSampleBlock), 0, s, tree, ws, a);
+        else
+            hipLaunchKernelGGL((sample_kernel<E, MPV_METHOD_TRAVERSAL>), dim3(p->B), dim3(kSampleBlock), 0, s, tree, ws, a);
     }
+#ifndef MPV_PROFILE_PHASES
     if (a.dbg_stats) {
         ScopedLaunch t(MPV_KERNEL_DEBUG_STATS, s);
         hipLaunchKernelGGL((debug_stats_kernel<E>), dim3(static_cast<unsigned>(p->B) * p->N), dim3(kTaskBlock), 0, s, tree, a);
     }
+#endif
     return hip_ok(hipGetLastError()) ? MPV_OK : MPV_ERR_HIP;
 }
 
@@ -771,6 +874,8 @@ int mpv_verify(const mpv_problem* problem, const mpv_buffers* buf, void* workspa
     a.B = problem->B; a.N = problem->N; a.V = problem->V; a.max_depth = problem->max_depth;
     a.k32 = static_cast<float>(1.4426950408889634 / static_cast<double>(problem->temperature));
     a.invT = 1.0f / problem->temperature;
+    a.stagger_blocks = 0;
+    a.stagger_ticks = 0;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     if (problem->logit_dtype == MPV_DTYPE_F32) return mpv::launch_all<mpv::ElemF32>(problem, plan, ws, a, s);
     return mpv::launch_all<mpv::ElemBF16>(problem, plan, ws, a, s);

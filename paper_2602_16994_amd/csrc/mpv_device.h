@@ -15,6 +15,12 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#ifdef MPV_PROFILE_PHASES
+#define MPV_TS(slot) do { __builtin_amdgcn_sched_barrier(0); ts[slot] = wall_clock64(); __builtin_amdgcn_sched_barrier(0); } while (0)
+#else
+#define MPV_TS(slot) do {} while (0)
+#endif
+
 namespace mpv {
 
 constexpr int kWave = 64;
@@ -54,10 +60,26 @@ struct ElemBF16 {
 // 16 aligned bytes of a row, still packed
 template <class T>
 __device__ __forceinline__ uint4 load_raw(const T* p) { return *reinterpret_cast<const uint4*>(p); }
+// vector number `vec` (16-byte units) after a wave-uniform base: 32-bit offset arithmetic
+template <class T>
+__device__ __forceinline__ uint4 load_raw_at(const T* base, int vec) {
+    return *reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(base) + (static_cast<unsigned>(vec) << 4));
+}
 
 // 2^x on the hardware transcendental unit (results below 2^-126 flush to zero,
 // which is what every caller wants for a vanishing probability).
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// Tell the compiler a value is the same in every lane (it then lives in scalar
+// registers instead of occupying a vector register per lane).
+__device__ __forceinline__ float uniform_f32(float x) {
+    return __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(x)));
+}
+__device__ __forceinline__ double uniform_f64(double x) {
+    const int lo = __builtin_amdgcn_readfirstlane(__double2loint(x));
+    const int hi = __builtin_amdgcn_readfirstlane(__double2hiint(x));
+    return __hiloint2double(hi, lo);
+}
 
 // ---------------------------------------------------------------- reductions
 
@@ -200,32 +222,36 @@ __device__ __forceinline__ void sweep_row(const typename E::T* __restrict__ z, i
 // known float, lane partials combine exactly as s * 2^(mk - MK).
 
 struct OnlineLse {
+    // The reference starts at a huge negative but finite value, so that a row (or a
+    // vector) of -inf logits needs no special case: fma(-inf, k, big) = -inf -> 2^-inf = 0.
+    static constexpr float kFloor = -1e30f;
     float m, mk, s;
-    __device__ __forceinline__ void init() { m = -INFINITY; mk = -INFINITY; s = 0.f; }
+    __device__ __forceinline__ void init() { m = -INFINITY; mk = kFloor; s = 0.f; }
     __device__ __forceinline__ void raise(float lm, float k32) {
-        if (lm > m) {
-            const float nmk = lm * k32;
-            s *= fast_exp2(mk - nmk);        // first time: 2^-inf = 0, s stays 0
-            m = lm;
+        m = fmaxf(m, lm);                    // dead code unless the caller asks for the maximum
+        const float nmk = fmaxf(lm * k32, kFloor);
+        if (nmk > mk) {
+            s *= fast_exp2(mk - nmk);        // first time: 2^-huge = 0, s stays 0
             mk = nmk;
         }
     }
     __device__ __forceinline__ void one(float z, float k32) {
         raise(z, k32);
-        if (z > -INFINITY) s += fast_exp2(fmaf(z, k32, -mk));
+        s += fast_exp2(fmaf(z, k32, -mk));
     }
     template <int VEC>
     __device__ __forceinline__ void vec(const float (&z)[VEC], float k32) {
-        float lm = z[0];
+        float lm = fmaxf(z[0], z[1]);
 #pragma unroll
-        for (int i = 1; i < VEC; ++i) lm = fmaxf(lm, z[i]);
+        for (int i = 2; i < VEC; ++i) lm = fmaxf(lm, z[i]);
         raise(lm, k32);
-        if (m > -INFINITY) {
-            float t = 0.f;
+        float t0 = 0.f, t1 = 0.f;
 #pragma unroll
-            for (int i = 0; i < VEC; ++i) t += fast_exp2(fmaf(z[i], k32, -mk));
-            s += t;
+        for (int i = 0; i < VEC; i += 2) {
+            t0 += fast_exp2(fmaf(z[i], k32, -mk));
+            t1 += fast_exp2(fmaf(z[i + 1], k32, -mk));
         }
+        s += t0 + t1;
     }
 };
 
@@ -235,14 +261,15 @@ struct RowStat {
     double A;     // log2 sum_v 2^(z_v k32)
 };
 
-// Combine the lanes' OnlineLse states of two rows into their RowStats.
-template <int BLOCK>
+// Combine the lanes' OnlineLse states of two rows into their RowStats (the row
+// maxima only if WANT_MAX; the path itself needs A alone).
+template <int BLOCK, bool WANT_MAX = true>
 __device__ __forceinline__ void finish_stats2(const OnlineLse& t, const OnlineLse& d,
                                               RowStat& rt, RowStat& rd, double* scratch) {
     float Mt = t.mk, Md = d.mk;
     block_max2<BLOCK>(Mt, Md, scratch);
     float mt = t.m, md = d.m;
-    block_max2<BLOCK>(mt, md, scratch);
+    if (WANT_MAX) block_max2<BLOCK>(mt, md, scratch);
     double st = (t.s > 0.f) ? static_cast<double>(t.s * fast_exp2(t.mk - Mt)) : 0.0;
     double sd = (d.s > 0.f) ? static_cast<double>(d.s * fast_exp2(d.mk - Md)) : 0.0;
     block_sum2<BLOCK>(st, sd, scratch);
@@ -311,8 +338,11 @@ __device__ __forceinline__ ResidualConsts residual_consts(double At, double Ad, 
     const double Ad_lo = isfinite(Adc) ? Adc - static_cast<double>(Ad_hi) : 0.0;   // c = inf: every term vanishes
     r.nAt = -At_hi;
     r.nAd = -Ad_hi;
-    r.rho = static_cast<float>(exp2(At_lo - Ad_lo));
-    r.scale = exp2(-At_lo);
+    // 2^x for |x| < 2^-17 (the float rounding remainders): two terms of the series are exact to 1e-16
+    const double ln2 = 0.6931471805599453;
+    const double x = (At_lo - Ad_lo) * ln2, y = -At_lo * ln2;
+    r.rho = static_cast<float>(1.0 + x + 0.5 * x * x);
+    r.scale = 1.0 + y + 0.5 * y * y;
     return r;
 }
 
@@ -328,12 +358,22 @@ __device__ __forceinline__ ResidualConsts residual_consts(double At, double Ad, 
 // Vector i of a row belongs to lane i % BLOCK, slot i / BLOCK: slots [0,R) live in
 // registers, [R,R+L) in LDS (lds[slot-R][lane]), the rest is streamed.
 
+// 16 bytes per lane from global memory straight into LDS (no register in between):
+// the wave's 64 lanes fill 1 KB starting at the wave-uniform address `lds_wave_base`.
+__device__ __forceinline__ void load_to_lds_16B(const void* gptr, uint4* lds_wave_base) {
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gptr,
+                                     (__attribute__((address_space(3))) void*)lds_wave_base, 16, 0, 0);
+}
+
 template <class E, int BLOCK, int R, int L, int CH, bool FULL>
 struct RetainedPair {
     // FULL: the caller guarantees nvec >= (R + L) * BLOCK, so every register and
     // LDS slot of every lane is in range and those parts run without a branch.
+    // The streamed slots are software-pipelined through two small buffers: the
+    // loads of the next two slots are in flight while kept data is being processed.
     using T = typename E::T;
     static constexpr int VEC = E::VEC;
+    static constexpr int PIPED = 10;            // streamed slots covered by the fixed pipeline
     uint4 rt[R > 0 ? R : 1], rd[R > 0 ? R : 1];
     const T* zt;
     const T* zd;
@@ -342,6 +382,11 @@ struct RetainedPair {
     uint4* lt;
     uint4* ld;
     int V, head, nvec, tail0;
+#ifdef MPV_PROFILE_PHASES
+    long long ts[16];
+#endif
+
+    struct Chunk { uint4 a[2], d[2]; };
 
     __device__ __forceinline__ void setup(const T* zt_, const T* zd_, int V_, uint4* lds_t, uint4* lds_d) {
         zt = zt_; zd = zd_; V = V_; lt = lds_t; ld = lds_d;
@@ -353,8 +398,6 @@ struct RetainedPair {
         bd = zd + head;
     }
 
-    __device__ __forceinline__ bool in_range(int idx) const { return FULL || idx < nvec; }
-
     template <class F>
     __device__ __forceinline__ void edges(F& f) const {
         const int tid = threadIdx.x;
@@ -362,16 +405,17 @@ struct RetainedPair {
         if (tail0 + tid < V) f.one(E::load_one(zt + tail0 + tid), E::load_one(zd + tail0 + tid));
     }
 
+    // streamed slots s0, s0+CH, ... with CH loads in flight (no pipelining across iterations)
     template <class F>
-    __device__ __forceinline__ void streamed(F& f) const {
+    __device__ __forceinline__ void streamed_from(int s0, F& f) const {
         const int tid = threadIdx.x;
-        for (int i = tid + (R + L) * BLOCK; i < nvec; i += BLOCK * CH) {
+        for (int i = tid + (R + L + s0) * BLOCK; i < nvec; i += BLOCK * CH) {
             uint4 a[CH], d[CH];
 #pragma unroll
             for (int u = 0; u < CH; ++u) {
                 const int idx = min(i + u * BLOCK, nvec - 1);      // clamped: always a valid load
-                a[u] = load_raw(bt + static_cast<size_t>(idx) * VEC);
-                d[u] = load_raw(bd + static_cast<size_t>(idx) * VEC);
+                a[u] = load_raw_at(bt, idx);
+                d[u] = load_raw_at(bd, idx);
             }
 #pragma unroll
             for (int u = 0; u < CH; ++u) {
@@ -380,65 +424,126 @@ struct RetainedPair {
         }
     }
 
-    // First sweep: load everything once, keep what fits, feed f.
+    // two streamed slots s, s+1 into a buffer / out of it
+    __device__ __forceinline__ void issue(Chunk& c, int s) const {
+        int tid = threadIdx.x;
+        asm volatile("" : "+v"(tid));       // recompute the addresses here: keeping them live across sweeps costs registers
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const int idx = min(tid + (R + L + s + u) * BLOCK, nvec - 1);
+            c.a[u] = load_raw_at(bt, idx);
+            c.d[u] = load_raw_at(bd, idx);
+        }
+    }
+    template <class F>
+    __device__ __forceinline__ void consume(const Chunk& c, int s, F& f) const {
+        const int tid = threadIdx.x;
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            if (tid + (R + L + s + u) * BLOCK < nvec) f.vec(c.a[u], c.d[u]);
+        }
+    }
+
+    static constexpr int DIST = 6;              // slots of loads kept ahead of the compute in the first sweep
+
+    __device__ __forceinline__ void load_register_slot(int j) {
+        const int tid = threadIdx.x;
+        rt[j] = load_raw_at(bt, tid + j * BLOCK);
+        rd[j] = load_raw_at(bd, tid + j * BLOCK);
+    }
+    __device__ __forceinline__ void load_lds_slot(int j) {
+        const int tid = threadIdx.x;
+        const int wave0 = (tid / kWave) * kWave;
+        load_to_lds_16B(bt + static_cast<size_t>(tid + (R + j) * BLOCK) * VEC, lt + j * BLOCK + wave0);
+        load_to_lds_16B(bd + static_cast<size_t>(tid + (R + j) * BLOCK) * VEC, ld + j * BLOCK + wave0);
+    }
+
+    // First sweep, part 1: put the loads of the first register slots in flight.
+    __device__ __forceinline__ void issue_register_loads() {
+        if (!FULL) return;
+#pragma unroll
+        for (int j = 0; j < DIST && j < R; ++j) load_register_slot(j);
+    }
+
+    // First sweep, part 2: load the rest once, keep what fits, feed f with everything.
+    // A wave that has issued a load cannot compute until the memory pipeline has
+    // accepted it, so loads are issued DIST slots ahead of the slot being processed
+    // instead of all at once: arrival and arithmetic then overlap.  The streamed
+    // chunks (two slots each, one buffer) are spread over the sweep, one every
+    // GAP kept slots, so that each has GAP slots of arithmetic to arrive behind.
+    static constexpr int GAP = (R + L) / 5 > 0 ? (R + L) / 5 : 1;
+
+    template <class F>
+    __device__ __forceinline__ void chunk_step(int c, Chunk& A, F& f) const {
+        // called before kept slot c is processed (c counts kept slots in processing order)
+        if (c % GAP == 0 && c / GAP < 5) {
+            if (c > 0) consume(A, 2 * (c / GAP) - 2, f);
+            issue(A, 2 * (c / GAP));
+        }
+    }
+
     template <class F>
     __device__ __forceinline__ void first_pass(F& f) {
-        const int tid = threadIdx.x;
-        if (!FULL && nvec == 0) { edges(f); return; }
-#pragma unroll
-        for (int j = 0; j < R; ++j) {
-            const int idx = FULL ? tid + j * BLOCK : min(tid + j * BLOCK, nvec - 1);
-            rt[j] = load_raw(bt + static_cast<size_t>(idx) * VEC);
-            rd[j] = load_raw(bd + static_cast<size_t>(idx) * VEC);
+        if (!FULL) {
+            edges(f);
+            if (nvec > 0) streamed_from(0, f);
+            return;
         }
+        const int tid = threadIdx.x;
+        Chunk A;
+        MPV_TS(0);
         edges(f);
 #pragma unroll
         for (int j = 0; j < R; ++j) {
-            if (in_range(tid + j * BLOCK)) f.vec(rt[j], rd[j]);
+            const int ahead = j + DIST;
+            if (ahead < R) load_register_slot(ahead);
+            else if (ahead < R + L) load_lds_slot(ahead - R);
+            chunk_step(j, A, f);
+            f.vec(rt[j], rd[j]);
+            if (j == 0) MPV_TS(1);
         }
+        MPV_TS(4);
 #pragma unroll
-        for (int j0 = 0; j0 < L; j0 += CH) {
-            uint4 a[CH], d[CH];
-#pragma unroll
-            for (int u = 0; u < CH; ++u) {
-                if (j0 + u < L) {
-                    const int idx = FULL ? tid + (R + j0 + u) * BLOCK : min(tid + (R + j0 + u) * BLOCK, nvec - 1);
-                    a[u] = load_raw(bt + static_cast<size_t>(idx) * VEC);
-                    d[u] = load_raw(bd + static_cast<size_t>(idx) * VEC);
-                }
-            }
-#pragma unroll
-            for (int u = 0; u < CH; ++u) {
-                if (j0 + u < L) {
-                    lt[(j0 + u) * BLOCK + tid] = a[u];
-                    ld[(j0 + u) * BLOCK + tid] = d[u];
-                    if (in_range(tid + (R + j0 + u) * BLOCK)) f.vec(a[u], d[u]);
-                }
-            }
+        for (int j = 0; j < L; ++j) {
+            const int ahead = R + j + DIST;
+            if (ahead < R + L) load_lds_slot(ahead - R);
+            chunk_step(R + j, A, f);
+            f.vec(lt[j * BLOCK + tid], ld[j * BLOCK + tid]);
         }
-        streamed(f);
+        MPV_TS(6);
+        consume(A, 8, f);
+        MPV_TS(7);
+        streamed_from(PIPED, f);
+        MPV_TS(8);
     }
 
-    // Later sweeps: streamed part (from L2 / memory), then LDS, then registers.
-    // The empty asm marks each kept register as "possibly changed", so that the
-    // compiler does not hoist the unpacked form of the whole pair out of the
-    // caller's loop over children (which would double the register footprint).
+    // Later sweeps.  The empty asm marks each kept register as "possibly changed",
+    // so that the compiler does not hoist the unpacked form of the whole pair out
+    // of the caller's loop over children (which would double the register footprint).
     template <class F>
     __device__ __forceinline__ void replay(F& f) {
+        if (!FULL) {
+            edges(f);
+            if (nvec > 0) streamed_from(0, f);
+            return;
+        }
         const int tid = threadIdx.x;
-        if (!FULL && nvec == 0) { edges(f); return; }
-        streamed(f);
+        Chunk A;
         edges(f);
 #pragma unroll
         for (int j = 0; j < L; ++j) {
-            if (in_range(tid + (R + j) * BLOCK)) f.vec(lt[j * BLOCK + tid], ld[j * BLOCK + tid]);
+            chunk_step(j, A, f);
+            f.vec(lt[j * BLOCK + tid], ld[j * BLOCK + tid]);
         }
 #pragma unroll
         for (int j = 0; j < R; ++j) {
+            chunk_step(L + j, A, f);
             asm volatile("" : "+v"(rt[j].x), "+v"(rt[j].y), "+v"(rt[j].z), "+v"(rt[j].w));
             asm volatile("" : "+v"(rd[j].x), "+v"(rd[j].y), "+v"(rd[j].z), "+v"(rd[j].w));
-            if (in_range(tid + j * BLOCK)) f.vec(rt[j], rd[j]);
+            f.vec(rt[j], rd[j]);
         }
+        consume(A, 8, f);
+        streamed_from(PIPED, f);
     }
 };
 
