@@ -101,7 +101,7 @@ typedef struct mpv_buffers {
     int32_t*  path_nodes;          /* [B,max_depth] node indices root-to-accepted, -1 padded  */
     int32_t*  path_tokens;         /* [B,max_depth] their tokens, -1 padded                   */
     int32_t*  bonus_token;         /* [B]   the correction token                              */
-    uint32_t* counters;            /* [4]   see MPV_COUNTER_*; zeroed by the call             */
+    uint32_t* counters;            /* [MPV_COUNTER_COUNT] see MPV_COUNTER_*; zeroed by the call */
     /* optional debug outputs (NULL = not wanted) */
     float* stats;                  /* [B,N,4] m_t, logZ_t, m_d, logZ_d: row maximum and
                                       ln sum exp((z-m)/T); draft entries of leaves are NaN    */
@@ -114,6 +114,9 @@ typedef struct mpv_buffers {
 #define MPV_COUNTER_NEAR_TIE_BONUS  1  /* bonus draws within 1e-6 (relative) of a CDF step   */
 #define MPV_COUNTER_ZERO_MASS       2  /* residual updates that found zero mass              */
 #define MPV_COUNTER_BAD_TOKEN       3  /* tokens outside [0,V) (treated as never accepted)   */
+#define MPV_COUNTER_DEPENDENCY_TIMEOUT 4 /* must stay 0: a node task gave up waiting for its
+                                            parent's result (results of that tree are invalid) */
+#define MPV_COUNTER_COUNT           8  /* length of the counters array (rest reserved)       */
 
 /* ABI version of the loaded library (MPV_ABI_VERSION it was built with). */
 int mpv_version(void);

@@ -180,7 +180,7 @@ def mpv_verify(parent, tokens, target_logits, draft_logits, temperature, uniform
             path_nodes=torch.empty(B, max_depth, **i32),
             path_tokens=torch.empty(B, max_depth, **i32),
             bonus_token=torch.empty(B, **i32),
-            counters=torch.empty(4, dtype=torch.int32, device=dev),
+            counters=torch.empty(8, dtype=torch.int32, device=dev),
         )
         if debug:
             f32 = dict(dtype=torch.float32, device=dev)

@@ -22,7 +22,6 @@
 #include <hip/hip_runtime.h>
 #include <math.h>
 #include <stdint.h>
-#include <stdlib.h>
 #include <string.h>
 
 #include "mpv.h"
@@ -43,8 +42,14 @@ struct TreeDesc {
     int32_t postorder[MPV_MAX_NODES];    // depth-first, children (in list order) before their parent; root last
 };
 
-struct NodeList {
-    int32_t count;
+// The node tasks of one call, grouped in levels.  Level l occupies the blocks
+// [block_start[l], block_start[l+1]) of the launch, B blocks per listed node, tree-major.
+// SpecInfer has one level (its tasks are independent); Traversal has one level per
+// tree depth, and a task waits for the flag its parent's task raises.
+struct TaskList {
+    int32_t nlevels;
+    int32_t block_start[MPV_MAX_NODES + 1];
+    int32_t node_off[MPV_MAX_NODES + 1];     // level l lists nodes[node_off[l] .. node_off[l+1])
     int32_t nodes[MPV_MAX_NODES];
 };
 
@@ -54,11 +59,10 @@ struct Workspace {
     double* Ad;      // same for the draft row
     double* cfin;    // c of the node's final state (all children rejected)
     double* Wfin;    // W(c) of that state
-    double* a0;      // Traversal: weight the node starts with
+    double* a0;      // Traversal: weight the node starts with (kNotReady until its parent's task publishes it)
     double* atest;   // probability the node is tested with
     float* mt;       // row maxima (for the debug statistics)
     float* md;
-    int32_t* stop;   // [B] stopping node
 };
 
 struct Args {
@@ -78,8 +82,6 @@ struct Args {
     int32_t B, N, V, max_depth;
     float k32;       // float(log2(e)/T)
     float invT;
-    int32_t stagger_blocks;   // the first this-many workgroups of a node-task launch start late ...
-    int32_t stagger_ticks;    // ... by (group of 8 workgroups mod 8) * this many 10 ns ticks
 };
 
 constexpr int kTaskBlock = 512;
@@ -89,6 +91,10 @@ constexpr int kTaskUnroll = 4;
 constexpr int kRegVecs = 18;
 constexpr int kLdsVecs = 9;
 constexpr int kChunk = 2;
+// upper bound on the polls of a dependency flag (about a second); see node_task_kernel
+constexpr int kMaxSpins = 1 << 20;
+// bit pattern (a NaN) of a starting weight that has not been published yet
+constexpr unsigned long long kNotReady = ~0ull;
 constexpr int kSampleBlock = 512;
 constexpr int kTile = 512;               // elements per wave tile in the sampler
 constexpr int kMaxTiles = MPV_MAX_VOCAB / kTile;
@@ -97,9 +103,9 @@ constexpr int kMaxTiles = MPV_MAX_VOCAB / kTile;
 
 __global__ void init_kernel(Workspace ws, Args a) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < 4) a.counters[i] = 0u;
+    if (i < MPV_COUNTER_COUNT) a.counters[i] = 0u;
+    if (i < a.B * a.N) reinterpret_cast<unsigned long long*>(ws.a0)[i] = kNotReady;
     if (i < a.B) {
-        ws.a0[static_cast<size_t>(i) * a.N] = 1.0;
         ws.atest[static_cast<size_t>(i) * a.N] = 1.0;
         if (a.dbg_edge) {
             a.dbg_edge[static_cast<size_t>(i) * a.N * 2] = 1.f;
@@ -111,7 +117,7 @@ __global__ void init_kernel(Workspace ws, Args a) {
 // ------------------------------------------------------------------ node task
 
 template <class E, int METHOD, bool FULL>
-__global__ __launch_bounds__(kTaskBlock) void node_task_kernel(TreeDesc tree, NodeList list,
+__global__ __launch_bounds__(kTaskBlock) void node_task_kernel(TreeDesc tree, TaskList list,
                                                               Workspace ws, Args a) {
     using T = typename E::T;
     __shared__ double scratch[2 * (kTaskBlock / kWave)];
@@ -122,23 +128,18 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(TreeDesc tree, No
     __shared__ uint4 lds_t[(LV > 0 ? LV : 1) * kTaskBlock];
     __shared__ uint4 lds_d[(LV > 0 ? LV : 1) * kTaskBlock];
 
-    const int b = blockIdx.x / list.count;
-    const int n = list.nodes[blockIdx.x % list.count];
+    int level = 0;
+    while (level + 1 < list.nlevels && static_cast<int>(blockIdx.x) >= list.block_start[level + 1]) ++level;
+    const int in_level = static_cast<int>(blockIdx.x) - list.block_start[level];
+    const int count = list.node_off[level + 1] - list.node_off[level];
+    const int b = in_level / count;
+    const int n = list.nodes[list.node_off[level] + in_level % count];
     const size_t bn = static_cast<size_t>(b) * a.N + n;
     const T* zt = static_cast<const T*>(a.zt) + bn * a.V;
     const T* zd = static_cast<const T*>(a.zd) + bn * a.V;
     const int V = a.V;
     const float k32 = a.k32;
 
-    // Every task alternates a memory-bound sweep with compute-bound replays, and all
-    // tasks take about the same time: started together, the compute units would all
-    // load at the same moments and all leave memory idle at the same moments.
-    // Spreading the start of the first wave of workgroups keeps them out of phase.
-    if (static_cast<int>(blockIdx.x) < a.stagger_blocks) {
-        const long long wait = static_cast<long long>((blockIdx.x >> 3) & 7) * a.stagger_ticks;
-        const long long t0 = wall_clock64();
-        while (wall_clock64() - t0 < wait) __builtin_amdgcn_s_sleep(16);    // the clock always advances: bounded
-    }
 #ifdef MPV_PROFILE_PHASES
     long long tstamp[8]; int nts = 0;
     { __builtin_amdgcn_sched_barrier(0); tstamp[nts++] = wall_clock64(); __builtin_amdgcn_sched_barrier(0); }
@@ -152,8 +153,6 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(TreeDesc tree, No
     int pf_x = -1;
     if (threadIdx.x < k)
         pf_x = a.tokens[static_cast<size_t>(b) * a.N + tree.child_list[tree.child_off[n] + threadIdx.x]];
-    double pf_a0 = 1.0;
-    if (METHOD == MPV_METHOD_TRAVERSAL && threadIdx.x == 0 && n != 0) pf_a0 = ws.a0[bn];
 
     // ---- softmax statistics of both rows: the one read of the pair from memory
     RetainedPair<E, kTaskBlock, RV, LV, CH, FULL> pair;
@@ -173,7 +172,29 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(TreeDesc tree, No
         { __builtin_amdgcn_sched_barrier(0); tstamp[nts++] = wall_clock64(); __builtin_amdgcn_sched_barrier(0); }
 #endif
         if (threadIdx.x < k) { ch_tok[threadIdx.x] = pf_x; ch_zt[threadIdx.x] = E::load_one(&pf_t); ch_zd[threadIdx.x] = E::load_one(&pf_d); }
-        if (threadIdx.x == 0) sh_a0 = pf_a0;
+        if (threadIdx.x == 0) {
+            // Traversal: the starting weight comes from the parent's task (an earlier block of
+            // this launch, or an earlier level); it has normally been there for a long time.
+            double a0 = 1.0;
+            if (METHOD == MPV_METHOD_TRAVERSAL && n != 0) {
+                // value and "ready" flag are one 64-bit word (a weight is never NaN), read and
+                // written with relaxed device-scope atomics: no fence, no cache invalidation
+                unsigned long long bits = kNotReady;
+                for (int spin = 0; spin < kMaxSpins; ++spin) {
+                    bits = __hip_atomic_load(reinterpret_cast<unsigned long long*>(&ws.a0[bn]), __ATOMIC_RELAXED,
+                                             __HIP_MEMORY_SCOPE_AGENT);
+                    if (bits != kNotReady) break;
+                    __builtin_amdgcn_s_sleep(32);
+                }
+                if (bits != kNotReady) {
+                    a0 = __longlong_as_double(static_cast<long long>(bits));
+                } else {            // cannot happen while blocks are dispatched in index order; never hang
+                    a0 = 0.0;
+                    atomicAdd(&a.counters[MPV_COUNTER_DEPENDENCY_TIMEOUT], 1u);
+                }
+            }
+            sh_a0 = a0;
+        }
         finish_stats2<kTaskBlock, false>(f.t, f.d, rt, rd, scratch);     // its barriers publish the above
         rt.A = uniform_f64(rt.A);
         rd.A = uniform_f64(rd.A);
@@ -212,8 +233,13 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(TreeDesc tree, No
         }
         if (threadIdx.x == 0) {
             if (METHOD == MPV_METHOD_TRAVERSAL) {
-                ws.a0[bc] = w_child;
-                if (tree.nchild[cn] == 0) ws.atest[bc] = w_child;   // leaves are tested as they are
+                if (tree.nchild[cn] == 0) {
+                    ws.atest[bc] = w_child;                          // leaves are tested as they are
+                } else {
+                    __hip_atomic_store(reinterpret_cast<unsigned long long*>(&ws.a0[bc]),
+                                       static_cast<unsigned long long>(__double_as_longlong(w_child)),
+                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
             } else {
                 ws.atest[bc] = w_child;
             }
@@ -255,11 +281,16 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(TreeDesc tree, No
 
 #ifdef MPV_PROFILE_PHASES
     { __builtin_amdgcn_sched_barrier(0); tstamp[nts++] = wall_clock64(); __builtin_amdgcn_sched_barrier(0); }
-    // bounds: needs (256*8)*20 floats <= B*N*4, checked by the probe script before it enables this build
-    if ((threadIdx.x & 63) == 0 && a.dbg_stats && blockIdx.x < 256 && static_cast<size_t>(a.B) * a.N * 4 >= 256 * 8 * 20) {
-        float* o = a.dbg_stats + (static_cast<size_t>(blockIdx.x) * 8 + threadIdx.x / 64) * 20;
-        for (int i = 0; i < 6; ++i) o[i] = static_cast<float>(tstamp[i] - tstamp[0]);
-        for (int i = 0; i < 9; ++i) o[6 + i] = static_cast<float>(pair.ts[i] - tstamp[0]);
+    // bounds: (blocks - B) * 5 floats <= B*N*4 for the benchmark tree (checked by the probe script)
+    if (threadIdx.x == 0 && a.dbg_stats && static_cast<int>(blockIdx.x) >= a.B &&
+        (static_cast<size_t>(gridDim.x) - a.B) * 5 <= static_cast<size_t>(a.B) * a.N * 4) {
+        float* o = a.dbg_stats + (static_cast<size_t>(blockIdx.x) - a.B) * 5;
+        const unsigned hw = __builtin_amdgcn_s_getreg(0xF804), xcc = __builtin_amdgcn_s_getreg(0x1814);
+        o[0] = static_cast<float>(tstamp[0] & 0xffffff);          // absolute start, 10 ns ticks (low 24 bits)
+        o[1] = static_cast<float>(((xcc & 15u) << 8) | (((hw >> 13) & 7u) << 5) | (((hw >> 12) & 1u) << 4) | ((hw >> 8) & 15u));
+        o[2] = static_cast<float>(tstamp[2] - tstamp[0]);         // statistics reduced
+        o[3] = static_cast<float>(nts >= 6 ? tstamp[4] - tstamp[0] : -1);   // first replay done
+        o[4] = static_cast<float>(tstamp[nts - 1] - tstamp[0]);   // task done
     }
 #endif
     if (threadIdx.x == 0) {
@@ -721,79 +752,52 @@ static size_t carve(const mpv_problem* p, void* base, Workspace* ws) {
     double* at = static_cast<double*>(take(bn * 8));
     float* mt = static_cast<float*>(take(bn * 4));
     float* md = static_cast<float*>(take(bn * 4));
-    int32_t* st = static_cast<int32_t*>(take(static_cast<size_t>(p->B) * 4));
-    if (ws) { ws->At = At; ws->Ad = Ad; ws->cfin = cf; ws->Wfin = Wf; ws->a0 = a0; ws->atest = at; ws->mt = mt; ws->md = md; ws->stop = st; }
+    if (ws) { ws->At = At; ws->Ad = Ad; ws->cfin = cf; ws->Wfin = Wf; ws->a0 = a0; ws->atest = at; ws->mt = mt; ws->md = md; }
     return off < 256 ? 256 : off;
 }
 
-static int compute_units() {
-    static int cus = 0;
-    if (cus == 0) {
-        int dev = 0, n = 0;
-        if (hipGetDevice(&dev) == hipSuccess &&
-            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
-            cus = n;
-        else
-            cus = 256;
-    }
-    return cus;
-}
-
-// Start-up spread for a node-task launch of `blocks` workgroups (see the kernel).
-static void set_stagger(Args& a, long long blocks) {
-    static int us = -1;
-    if (us < 0) {
-        const char* e = getenv("MPV_STAGGER_US");
-        us = e ? atoi(e) : 0;
-    }
-    const int cus = compute_units();
-    if (us > 0 && blocks >= 3ll * cus) { a.stagger_blocks = cus; a.stagger_ticks = us * 100 / 8; }
-    else { a.stagger_blocks = 0; a.stagger_ticks = 0; }
-}
-
 template <class E>
-static int launch_all(const mpv_problem* p, const Plan& plan, const Workspace& ws, Args a, hipStream_t s) {
+static int launch_all(const mpv_problem* p, const Plan& plan, const Workspace& ws, const Args& a, hipStream_t s) {
     const TreeDesc& tree = plan.tree;
     (void)hipGetLastError();    // a stale error left by the caller's own HIP calls is not ours
     // every register and LDS slot of a node task is populated whatever the row's alignment
     const bool full = (p->V - (E::VEC - 1)) / E::VEC >= (kRegVecs + kLdsVecs) * kTaskBlock;
     {
         const int threads = 256;
-        const int blocks = (max(p->B, 4) + threads - 1) / threads;
+        const int blocks = (max(p->B * p->N, MPV_COUNTER_COUNT) + threads - 1) / threads;
         ScopedLaunch t(MPV_KERNEL_INIT, s);
         hipLaunchKernelGGL(init_kernel, dim3(blocks), dim3(threads), 0, s, ws, a);
     }
-    if (p->method == MPV_METHOD_SPECINFER) {
-        NodeList list; list.count = 0;
-        // nodes with many children first: they are the long tasks
-        for (int kk = MPV_MAX_CHILDREN; kk >= 1; --kk)
-            for (int n = 0; n < p->N; ++n)
-                if (tree.nchild[n] == kk) list.nodes[list.count++] = n;
-        if (list.count) {
-            set_stagger(a, static_cast<long long>(p->B) * list.count);
-            ScopedLaunch t(MPV_KERNEL_NODE_TASK, s);
-            if (full)
-                hipLaunchKernelGGL((node_task_kernel<E, MPV_METHOD_SPECINFER, true>),
-                                   dim3(static_cast<unsigned>(p->B) * list.count), dim3(kTaskBlock), 0, s, tree, list, ws, a);
-            else
-                hipLaunchKernelGGL((node_task_kernel<E, MPV_METHOD_SPECINFER, false>),
-                                   dim3(static_cast<unsigned>(p->B) * list.count), dim3(kTaskBlock), 0, s, tree, list, ws, a);
-        }
-    } else {
-        for (int d = 0; d < plan.max_tree_depth; ++d) {
-            NodeList list; list.count = 0;
+    {
+        // levels: SpecInfer one (tasks are independent), Traversal one per depth; inside a
+        // level the nodes with many children come first (they are the long tasks)
+        TaskList list;
+        memset(&list, 0, sizeof(list));
+        int nn = 0, blocks = 0;
+        const int nlev = (p->method == MPV_METHOD_SPECINFER) ? 1 : plan.max_tree_depth;
+        for (int d = 0; d < nlev; ++d) {
+            const int first = nn;
             for (int kk = MPV_MAX_CHILDREN; kk >= 1; --kk)
                 for (int n = 0; n < p->N; ++n)
-                    if (tree.depth[n] == d && tree.nchild[n] == kk) list.nodes[list.count++] = n;
-            if (list.count) {
-                set_stagger(a, static_cast<long long>(p->B) * list.count);
-                ScopedLaunch t(MPV_KERNEL_NODE_TASK, s);
-                if (full)
-                    hipLaunchKernelGGL((node_task_kernel<E, MPV_METHOD_TRAVERSAL, true>),
-                                       dim3(static_cast<unsigned>(p->B) * list.count), dim3(kTaskBlock), 0, s, tree, list, ws, a);
-                else
-                    hipLaunchKernelGGL((node_task_kernel<E, MPV_METHOD_TRAVERSAL, false>),
-                                       dim3(static_cast<unsigned>(p->B) * list.count), dim3(kTaskBlock), 0, s, tree, list, ws, a);
+                    if (tree.nchild[n] == kk && (p->method == MPV_METHOD_SPECINFER || tree.depth[n] == d))
+                        list.nodes[nn++] = n;
+            if (nn == first) continue;                 // no internal node at this depth
+            list.node_off[list.nlevels] = first;
+            list.block_start[list.nlevels] = blocks;
+            blocks += p->B * (nn - first);
+            ++list.nlevels;
+        }
+        list.node_off[list.nlevels] = nn;
+        list.block_start[list.nlevels] = blocks;
+        if (blocks > 0) {
+            ScopedLaunch t(MPV_KERNEL_NODE_TASK, s);
+            const dim3 grid(static_cast<unsigned>(blocks)), block(kTaskBlock);
+            if (p->method == MPV_METHOD_SPECINFER) {
+                if (full) hipLaunchKernelGGL((node_task_kernel<E, MPV_METHOD_SPECINFER, true>), grid, block, 0, s, tree, list, ws, a);
+                else hipLaunchKernelGGL((node_task_kernel<E, MPV_METHOD_SPECINFER, false>), grid, block, 0, s, tree, list, ws, a);
+            } else {
+                if (full) hipLaunchKernelGGL((node_task_kernel<E, MPV_METHOD_TRAVERSAL, true>), grid, block, 0, s, tree, list, ws, a);
+                else hipLaunchKernelGGL((node_task_kernel<E, MPV_METHOD_TRAVERSAL, false>), grid, block, 0, s, tree, list, ws, a);
             }
         }
     }
@@ -874,8 +878,6 @@ int mpv_verify(const mpv_problem* problem, const mpv_buffers* buf, void* workspa
     a.B = problem->B; a.N = problem->N; a.V = problem->V; a.max_depth = problem->max_depth;
     a.k32 = static_cast<float>(1.4426950408889634 / static_cast<double>(problem->temperature));
     a.invT = 1.0f / problem->temperature;
-    a.stagger_blocks = 0;
-    a.stagger_ticks = 0;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     if (problem->logit_dtype == MPV_DTYPE_F32) return mpv::launch_all<mpv::ElemF32>(problem, plan, ws, a, s);
     return mpv::launch_all<mpv::ElemBF16>(problem, plan, ws, a, s);
