@@ -116,6 +116,8 @@ typedef struct mpv_buffers {
 #define MPV_COUNTER_BAD_TOKEN       3  /* tokens outside [0,V) (treated as never accepted)   */
 #define MPV_COUNTER_DEPENDENCY_TIMEOUT 4 /* must stay 0: a node task gave up waiting for its
                                             parent's result (results of that tree are invalid) */
+#define MPV_COUNTER_NODE_TASKS_RUN   5  /* (tree, internal node) pairs whose logit rows were
+                                          read; the others were proved irrelevant first      */
 #define MPV_COUNTER_COUNT           8  /* length of the counters array (rest reserved)       */
 
 /* ABI version of the loaded library (MPV_ABI_VERSION it was built with). */

@@ -43,7 +43,7 @@ struct TreeDesc {
 };
 
 // The node tasks of one call, grouped in levels.  Level l occupies the blocks
-// [block_start[l], block_start[l+1]) of the launch, B blocks per listed node, tree-major.
+// [block_start[l], block_start[l+1]) of the launch, B blocks per listed node, node-major.
 // SpecInfer has one level (its tasks are independent); Traversal has one level per
 // tree depth, and a task waits for the flag its parent's task raises.
 struct TaskList {
@@ -82,6 +82,7 @@ struct Args {
     int32_t B, N, V, max_depth;
     float k32;       // float(log2(e)/T)
     float invT;
+    int32_t prune;   // skip node tasks whose node has weight 0 (off when per-edge debug output is wanted)
 };
 
 constexpr int kTaskBlock = 512;
@@ -131,9 +132,11 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(TreeDesc tree, Ta
     int level = 0;
     while (level + 1 < list.nlevels && static_cast<int>(blockIdx.x) >= list.block_start[level + 1]) ++level;
     const int in_level = static_cast<int>(blockIdx.x) - list.block_start[level];
-    const int count = list.node_off[level + 1] - list.node_off[level];
-    const int b = in_level / count;
-    const int n = list.nodes[list.node_off[level] + in_level % count];
+    // node-major inside a level: consecutive blocks (which the hardware deals out to the
+    // 8 XCDs in turn) are the same node of consecutive trees, so every XCD gets the same mix
+    // of long and short tasks
+    const int b = in_level % a.B;
+    const int n = list.nodes[list.node_off[level] + in_level / a.B];
     const size_t bn = static_cast<size_t>(b) * a.N + n;
     const T* zt = static_cast<const T*>(a.zt) + bn * a.V;
     const T* zd = static_cast<const T*>(a.zd) + bn * a.V;
@@ -144,12 +147,42 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(TreeDesc tree, Ta
     long long tstamp[8]; int nts = 0;
     { __builtin_amdgcn_sched_barrier(0); tstamp[nts++] = wall_clock64(); __builtin_amdgcn_sched_barrier(0); }
 #endif
+    // ---- Traversal: a node whose starting weight is already known to be 0 can never be
+    //      accepted, nor can anything below it (every weight in its subtree is a product with
+    //      that 0), and no bonus token is ever drawn from it: its rows need not be read at all.
+    //      One look at the parent's word, no waiting; if it is not there yet, carry on.
+    const int k = tree.nchild[n];
+    if (METHOD == MPV_METHOD_TRAVERSAL && n != 0 && a.prune) {
+        __shared__ int sh_dead;
+        if (threadIdx.x == 0) {
+            const unsigned long long bits = __hip_atomic_load(reinterpret_cast<unsigned long long*>(&ws.a0[bn]),
+                                                              __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            sh_dead = (bits != kNotReady && !(__longlong_as_double(static_cast<long long>(bits)) > 0.0)) ? 1 : 0;
+        }
+        __syncthreads();
+        if (sh_dead) {
+            if (threadIdx.x < k) {
+                const int cn = tree.child_list[tree.child_off[n] + threadIdx.x];
+                const size_t bc = static_cast<size_t>(b) * a.N + cn;
+                if (tree.nchild[cn] == 0) ws.atest[bc] = 0.0;
+                else __hip_atomic_store(reinterpret_cast<unsigned long long*>(&ws.a0[bc]), 0ull, __ATOMIC_RELAXED,
+                                        __HIP_MEMORY_SCOPE_AGENT);           // the bits of +0.0
+            }
+            if (threadIdx.x == 0) {
+                ws.atest[bn] = 0.0;
+                ws.cfin[bn] = 0.0;
+                ws.Wfin[bn] = 1.0;
+            }
+            return;
+        }
+    }
+    if (threadIdx.x == 0) atomicAdd(&a.counters[MPV_COUNTER_NODE_TASKS_RUN], 1u);
+
     // ---- the children's tokens and this node's starting weight: fetched now, so that
     //      their latency hides behind the sweep (lane j looks after child j)
     __shared__ int ch_tok[MPV_MAX_CHILDREN];
     __shared__ float ch_zt[MPV_MAX_CHILDREN], ch_zd[MPV_MAX_CHILDREN];
     __shared__ double sh_a0;
-    const int k = tree.nchild[n];
     int pf_x = -1;
     if (threadIdx.x < k)
         pf_x = a.tokens[static_cast<size_t>(b) * a.N + tree.child_list[tree.child_off[n] + threadIdx.x]];
@@ -878,6 +911,7 @@ int mpv_verify(const mpv_problem* problem, const mpv_buffers* buf, void* workspa
     a.B = problem->B; a.N = problem->N; a.V = problem->V; a.max_depth = problem->max_depth;
     a.k32 = static_cast<float>(1.4426950408889634 / static_cast<double>(problem->temperature));
     a.invT = 1.0f / problem->temperature;
+    a.prune = (buf->edge_probs == nullptr) ? 1 : 0;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     if (problem->logit_dtype == MPV_DTYPE_F32) return mpv::launch_all<mpv::ElemF32>(problem, plan, ws, a, s);
     return mpv::launch_all<mpv::ElemBF16>(problem, plan, ws, a, s);

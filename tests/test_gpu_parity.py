@@ -34,6 +34,13 @@ def run_case(cfg, method, trees=None, debug=True):
     announce(cfg.name, METHOD_NAME[method], f"B={cfg.B} N={cfg.N} V={cfg.V} {cfg.dtype} T={cfg.T}")
     inputs = workloads.make_inputs(cfg, "cuda")
     got = run_library(inputs, cfg.T, method, debug)
+    if debug:
+        # the production path (no debug outputs: irrelevant node tasks are skipped) must decide alike
+        lean = run_library(inputs, cfg.T, method, debug=False)
+        for key in ("accept_len", "path_nodes", "path_tokens", "bonus_token"):
+            assert np.array_equal(got[key], lean[key]), f"{key} differs between debug and production runs"
+        assert lean["counters"][4] == 0 and got["counters"][4] == 0, "dependency wait timed out"
+        assert lean["counters"][5] <= got["counters"][5]
     host = workloads.to_host(inputs)
     check_properties(host["parent"], cfg.V, got, host["tokens"])
     rep = compare_with_oracle(method, host, cfg.T, got, trees=trees, check_debug=debug)
