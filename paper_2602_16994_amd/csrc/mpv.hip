@@ -117,6 +117,7 @@ __global__ void init_kernel(Workspace ws, Args a) {
 
 // ------------------------------------------------------------------ node task
 
+
 template <class E, int METHOD, bool FULL>
 __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(TreeDesc tree, TaskList list,
                                                               Workspace ws, Args a) {

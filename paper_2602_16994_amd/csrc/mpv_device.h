@@ -227,10 +227,17 @@ struct OnlineLse {
     static constexpr float kFloor = -1e30f;
     float m, mk, s;
     __device__ __forceinline__ void init() { m = -INFINITY; mk = kFloor; s = 0.f; }
+    // The reference follows the running maximum only in steps: it is moved when the
+    // new maximum lies more than kSlack binary orders above it.  Terms then reach at most
+    // 2^kSlack (their exponent argument is still exact to 2^-22), and after the first few
+    // vectors of a row no lane of a wave moves its reference any more, so the whole
+    // block below is skipped by a wave-level branch.
+    static constexpr float kSlack = 4.f;
     __device__ __forceinline__ void raise(float lm, float k32) {
         m = fmaxf(m, lm);                    // dead code unless the caller asks for the maximum
-        const float nmk = fmaxf(lm * k32, kFloor);
-        if (nmk > mk) {
+        const float nmk = lm * k32;
+        if (nmk > mk + kSlack) {
+            asm volatile("" ::: "memory");   // keep this a branch: if-converted, it would run for every vector
             s *= fast_exp2(mk - nmk);        // first time: 2^-huge = 0, s stays 0
             mk = nmk;
         }
@@ -492,13 +499,13 @@ struct RetainedPair {
         const int tid = threadIdx.x;
         Chunk A;
         MPV_TS(0);
-        edges(f);
 #pragma unroll
         for (int j = 0; j < R; ++j) {
             const int ahead = j + DIST;
             if (ahead < R) load_register_slot(ahead);
             else if (ahead < R + L) load_lds_slot(ahead - R);
             chunk_step(j, A, f);
+            if (j == 0) f.begin(rt[0], rd[0]);
             f.vec(rt[j], rd[j]);
             if (j == 0) MPV_TS(1);
         }
@@ -514,6 +521,7 @@ struct RetainedPair {
         consume(A, 8, f);
         MPV_TS(7);
         streamed_from(PIPED, f);
+        edges(f);
         MPV_TS(8);
     }
 
@@ -551,6 +559,7 @@ template <class E>
 struct PairStatsRawF {
     OnlineLse t, d;
     float k32;
+    __device__ __forceinline__ void begin(const uint4&, const uint4&) {}
     __device__ __forceinline__ void one(float a, float b) { t.one(a, k32); d.one(b, k32); }
     __device__ __forceinline__ void vec(const uint4& ra, const uint4& rb) {
         float a[E::VEC], b[E::VEC];

@@ -186,6 +186,30 @@ def test_duplicate_sibling_tokens_and_masked_vocabulary(method):
             assert not (100 <= t < 200)
 
 
+@pytest.mark.parametrize("method", [SI, TV])
+@pytest.mark.parametrize("T", [0.2, 1.0])
+def test_peaked_rows_long_vocabulary(method, T):
+    """Rows kept on chip use a per-lane reference fixed at the start of the sweep;
+    a few logits far above everything else (40 units, T = 0.2: 288 binary orders)
+    overflow that form and must take the online repeat."""
+    announce("peaked rows", METHOD_NAME[method], T)
+    cfg = workloads.Config("peaked", B=3, V=131072, K=3, L1=1, L2=1, dtype="bf16", T=T,
+                           methods=[method], draft_sigma=1.0, target_sigma=0.7, seed=77)
+    inputs = workloads.make_inputs(cfg, "cuda")
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(5)
+    for name, boost in (("draft", 40.0), ("target", 38.0)):
+        idx = torch.randint(4096, cfg.V, (cfg.B, cfg.N, 3), generator=gen, device="cuda")
+        inputs[name].scatter_add_(2, idx, torch.full(idx.shape, boost, device="cuda", dtype=inputs[name].dtype))
+    # draft tokens must still come from the (now peaked) draft rows
+    for n in range(1, cfg.N):
+        q = torch.softmax(inputs["draft"][:, cfg.parent[n]].float() / T, dim=-1)
+        inputs["tokens"][:, n] = torch.multinomial(q, 1, generator=gen).squeeze(1).to(torch.int32)
+    got = run_library(inputs, T, method)
+    rep = compare_with_oracle(method, workloads.to_host(inputs), T, got)
+    print("[report]", rep, flush=True)
+
+
 def test_out_of_range_tokens_are_counted_not_followed():
     announce("bad tokens")
     cfg = workloads.Config("badtok", B=3, V=500, K=2, L1=0, L2=2, dtype="f32", T=1.0,
