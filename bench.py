@@ -36,14 +36,16 @@ def parse_profile_traffic(path):
         return None
 
 
-def cpu_baseline(cfg, inputs, method, budget_s=15.0, max_trees=32):
-    """The oracle, as it stands, in sample mode on the first trees of the same
-    batch (single thread: numpy elementwise kernels do not thread)."""
+def cpu_baseline(cfg, inputs, method, budget_s=20.0):
+    """The oracle, as it stands, in sample mode on trees of the same batch, in order,
+    until the time budget is used (single thread: numpy elementwise kernels do not
+    thread).  If the whole batch fits in the budget it is walked again from the start."""
     from oracle import mpv_oracle as orc
     parent = inputs["parent"]
     done = 0
     t_total = 0.0
-    for b in range(min(max_trees, cfg.B)):
+    b = 0
+    while t_total < budget_s:
         tok = inputs["tokens"][b].cpu().numpy()
         zt = inputs["target"][b].float().cpu().numpy()
         zd = inputs["draft"][b].float().cpu().numpy()
@@ -52,14 +54,14 @@ def cpu_baseline(cfg, inputs, method, budget_s=15.0, max_trees=32):
         orc.verify_tree(method, parent, tok, zt, zd, cfg.T, u)
         t_total += time.perf_counter() - t0
         done += 1
-        if t_total > budget_s:
-            break
+        b = (b + 1) % cfg.B
     return {
         "value": done * cfg.N / t_total,
         "unit": "nodes/s",
         "cores": 1,
         "kind": "oracle",
-        "sample": f"first {done} of {cfg.B} trees of the same batch, sample mode, {t_total:.2f} s",
+        "sample": f"{done} trees of the same batch (in order, wrapping around after {cfg.B}), "
+                  f"sample mode, {t_total:.1f} s of oracle time",
     }
 
 
@@ -73,6 +75,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-launch-timing", action="store_true",
                     help="do not bracket the library's launches with HIP events")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (a known-size kernel to scale profiler byte counters by)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (trees are independent; see DESIGN.md for how "
@@ -97,12 +101,19 @@ def main():
         return mpv.mpv_verify(inputs["parent"], inputs["tokens"], inputs["target"], inputs["draft"],
                               cfg.T, inputs["uniforms"], method, debug=False, out=out)
 
+    if args.calibration_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0").fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)                     # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
+
     out = step()
     for _ in range(args.warmup):
         step(out)
     torch.cuda.synchronize()
 
-    launches_per_step = 16
+    launches_per_step = 8
     timing = not args.no_launch_timing
     if timing:
         mpv.mpv_timing_enable(launches_per_step * args.steps)
@@ -120,9 +131,14 @@ def main():
             per_kernel.setdefault(mpv.MPV_KERNEL_NAMES[kid], []).append(ms)
         mpv.mpv_timing_enable(0)
 
-    # ---- roofline of the dominant kernel (node tasks)
+    # ---- roofline of the dominant kernel (node tasks).  Algorithmic bytes: one read of the
+    # target and the draft row of every (tree, internal node) whose rows the rule needs,
+    # i.e. the tasks the kernel counted as run (Traversal proves the others irrelevant:
+    # a node of weight 0 can neither be accepted nor pass weight on).
     n_internal = sum(1 for n in range(cfg.N) if n in set(cfg.parent[1:]))
     pair_bytes = 2 * cfg.V * cfg.elem_bytes                  # one target + one draft row
+    counters = out.counters.tolist()
+    tasks_run = counters[5]
     roofline = None
     kernels = {}
     if per_kernel:
@@ -132,7 +148,7 @@ def main():
         nt = per_kernel.get("node_task", [])
         if nt:
             launches = len(nt) / args.steps
-            alg_bytes_per_launch = cfg.B * n_internal * pair_bytes / launches
+            alg_bytes_per_launch = tasks_run * pair_bytes / launches
             avg_s = sum(nt) / len(nt) * 1e-3
             achieved = alg_bytes_per_launch / avg_s / 1e9
             traffic = parse_profile_traffic(os.path.join(
@@ -140,6 +156,8 @@ def main():
             roofline = {"bound": "hbm", "kernel": "node_task_kernel", "achieved": achieved,
                         "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                         "traffic": traffic, "algorithmic_bytes_per_launch": alg_bytes_per_launch,
+                        "node_tasks_run": tasks_run, "node_tasks_total": cfg.B * n_internal,
+                        "bytes_per_node_task": pair_bytes,
                         "avg_launch_ms": avg_s * 1e3, "launches_per_step": launches}
 
     nodes_per_s = cfg.B * cfg.N / (ms_per_step * 1e-3)
@@ -163,9 +181,9 @@ def main():
                    "method": "traversal" if method == 1 else "specinfer",
                    "logit_dtype": cfg.dtype},
         "trees_per_s": cfg.B / (ms_per_step * 1e-3),
-        "whole_path_input_GBps": cfg.B * (cfg.N + n_internal) * cfg.V * cfg.elem_bytes / (ms_per_step * 1e-3) / 1e9,
+        "dense_input_GBps_equivalent": cfg.B * (cfg.N + n_internal) * cfg.V * cfg.elem_bytes / (ms_per_step * 1e-3) / 1e9,
         "mean_accept_len": float(out.accept_len.float().mean().item()),
-        "counters": out.counters.tolist(),
+        "counters": counters,
         "kernels": kernels,
         "roofline": roofline,
     }
