@@ -1,7 +1,7 @@
 // mpv.hip -- kernels and C ABI of the tree-verification library (gfx950 only).
 //
 // Path of one mpv_verify call (all on the caller's stream):
-//   init_kernel            zero counters, root weight = 1
+//   init_kernel            zero counters, fill the first level of the task queue
 //   node_task_kernel       one workgroup per (tree, internal node):
 //                            softmax statistics of the node's target and draft rows,
 //                            then, for each child in list order, the probability
@@ -42,10 +42,11 @@ struct TreeDesc {
     int32_t postorder[MPV_MAX_NODES];    // depth-first, children (in list order) before their parent; root last
 };
 
-// The node tasks of one call, grouped in levels.  Level l occupies the blocks
-// [block_start[l], block_start[l+1]) of the launch, B blocks per listed node, node-major.
-// SpecInfer has one level (its tasks are independent); Traversal has one level per
-// tree depth, and a task waits for the flag its parent's task raises.
+// The node tasks of one call, grouped in levels.  Level l owns the entries
+// [block_start[l], block_start[l+1]) of the task queue, room for B tasks per listed node.
+// SpecInfer has one level, filled up front (its tasks are independent).  Traversal has one
+// level per tree depth: level 0 (the roots) is filled up front, and a finished task appends
+// those of its children that still matter to the next level.
 struct TaskList {
     int32_t nlevels;
     int32_t block_start[MPV_MAX_NODES + 1];
@@ -63,6 +64,10 @@ struct Workspace {
     double* atest;   // probability the node is tested with
     float* mt;       // row maxima (for the debug statistics)
     float* md;
+    int32_t* queue;      // task queue, entry = tree * N + node, -1 = not written yet
+    int32_t* head;       // [levels] next ticket to hand out
+    int32_t* tail;       // [levels] tasks appended so far
+    int32_t* completed;  // [levels] tasks finished
 };
 
 struct Args {
@@ -102,17 +107,79 @@ constexpr int kMaxTiles = MPV_MAX_VOCAB / kTile;
 
 // ------------------------------------------------------------------ init
 
-__global__ void init_kernel(Workspace ws, Args a) {
+__global__ void init_kernel(TaskList list, Workspace ws, Args a, int method) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < MPV_COUNTER_COUNT) a.counters[i] = 0u;
-    if (i < a.B * a.N) reinterpret_cast<unsigned long long*>(ws.a0)[i] = kNotReady;
-    if (i < a.B) {
-        ws.atest[static_cast<size_t>(i) * a.N] = 1.0;
-        if (a.dbg_edge) {
-            a.dbg_edge[static_cast<size_t>(i) * a.N * 2] = 1.f;
-            a.dbg_edge[static_cast<size_t>(i) * a.N * 2 + 1] = 1.f;
+    if (i < MPV_MAX_NODES) {
+        ws.head[i] = 0;
+        ws.completed[i] = 0;
+        ws.tail[i] = (i == 0) ? list.block_start[1] : 0;     // level 0 is complete from the start
+    }
+    if (i < a.B * a.N) {
+        reinterpret_cast<unsigned long long*>(ws.a0)[i] = kNotReady;
+        // a node no task ever reaches (Traversal: weight 0) is tested with probability 0
+        ws.atest[i] = (i % a.N == 0) ? 1.0 : 0.0;
+        ws.cfin[i] = 0.0;
+        ws.Wfin[i] = 1.0;
+        // queue: level 0 node-major (same node of consecutive trees), the rest empty
+        const int total = list.block_start[list.nlevels];
+        if (i < total) {
+            const int level0 = list.block_start[1];
+            ws.queue[i] = (i < level0) ? (i % a.B) * a.N + list.nodes[i / a.B] : -1;
         }
     }
+    if (i < a.B && a.dbg_edge) {
+        a.dbg_edge[static_cast<size_t>(i) * a.N * 2] = 1.f;
+        a.dbg_edge[static_cast<size_t>(i) * a.N * 2 + 1] = 1.f;
+    }
+}
+
+// ------------------------------------------------------------------ task queue
+//
+// node_task_kernel is launched with about one workgroup per compute unit; each workgroup
+// keeps taking tasks until none are left.  A workgroup draws a ticket h at a level (one
+// atomic add on head[level]); the ticket is good for queue entry h of that level if that
+// entry ever gets written.  It will be written iff h < final tail[level]; tail[level] is
+// final once every task of level-1 has finished (completed[level-1] == tail[level-1]; by
+// induction that tail is final too, because a workgroup only moves up a level after it has
+// seen the level below finished).  A task's appends (returning atomic adds on tail) are
+// performed before its completed++ is issued, so whoever sees the level below finished
+// then reads final tails.  Any resident workgroup can run any task, so nothing here depends
+// on which or how many workgroups are resident.  All waits are bounded.
+
+__device__ __forceinline__ int ld_relaxed(const int32_t* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Next task for this workgroup (called by one lane).  Returns tree*N+node, or -1 when there is
+// nothing left; `level` is updated to the level the task belongs to.
+__device__ int next_task(const TaskList& list, const Workspace& ws, const Args& a, int& level) {
+    while (level < list.nlevels) {
+        const int h = atomicAdd(&ws.head[level], 1);
+        bool mine = false;
+        for (int spin = 0; spin < kMaxSpins; ++spin) {
+            if (h < ld_relaxed(&ws.tail[level])) { mine = true; break; }
+            if (level == 0) break;                                   // tail[0] never grows
+            if (ld_relaxed(&ws.completed[level - 1]) == ld_relaxed(&ws.tail[level - 1])) {
+                mine = h < ld_relaxed(&ws.tail[level]);              // now final
+                break;
+            }
+            __builtin_amdgcn_s_sleep(32);
+            if (spin == kMaxSpins - 1) atomicAdd(&a.counters[MPV_COUNTER_DEPENDENCY_TIMEOUT], 1u);
+        }
+        if (mine) {
+            const int32_t* e = ws.queue + list.block_start[level] + h;
+            for (int spin = 0; spin < kMaxSpins; ++spin) {
+                const int t = ld_relaxed(e);
+                if (t >= 0) return t;
+                __builtin_amdgcn_s_sleep(8);
+            }
+            atomicAdd(&a.counters[MPV_COUNTER_DEPENDENCY_TIMEOUT], 1u);
+            return -1;
+        }
+        ++level;
+    }
+    return -1;
 }
 
 // ------------------------------------------------------------------ node task
@@ -130,14 +197,20 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(TreeDesc tree, Ta
     __shared__ uint4 lds_t[(LV > 0 ? LV : 1) * kTaskBlock];
     __shared__ uint4 lds_d[(LV > 0 ? LV : 1) * kTaskBlock];
 
+    __shared__ int sh_task, sh_level;
     int level = 0;
-    while (level + 1 < list.nlevels && static_cast<int>(blockIdx.x) >= list.block_start[level + 1]) ++level;
-    const int in_level = static_cast<int>(blockIdx.x) - list.block_start[level];
-    // node-major inside a level: consecutive blocks (which the hardware deals out to the
-    // 8 XCDs in turn) are the same node of consecutive trees, so every XCD gets the same mix
-    // of long and short tasks
-    const int b = in_level % a.B;
-    const int n = list.nodes[list.node_off[level] + in_level / a.B];
+    for (;;) {
+    __syncthreads();                                  // the previous task is done with LDS
+    if (threadIdx.x == 0) {
+        sh_task = next_task(list, ws, a, level);
+        sh_level = level;
+    }
+    __syncthreads();
+    const int task = sh_task;
+    if (task < 0) break;
+    level = sh_level;
+    const int b = task / a.N;
+    const int n = task % a.N;
     const size_t bn = static_cast<size_t>(b) * a.N + n;
     const T* zt = static_cast<const T*>(a.zt) + bn * a.V;
     const T* zd = static_cast<const T*>(a.zd) + bn * a.V;
@@ -148,40 +221,14 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(TreeDesc tree, Ta
     long long tstamp[8]; int nts = 0;
     { __builtin_amdgcn_sched_barrier(0); tstamp[nts++] = wall_clock64(); __builtin_amdgcn_sched_barrier(0); }
 #endif
-    // ---- Traversal: a node whose starting weight is already known to be 0 can never be
-    //      accepted, nor can anything below it (every weight in its subtree is a product with
-    //      that 0), and no bonus token is ever drawn from it: its rows need not be read at all.
-    //      One look at the parent's word, no waiting; if it is not there yet, carry on.
     const int k = tree.nchild[n];
-    if (METHOD == MPV_METHOD_TRAVERSAL && n != 0 && a.prune) {
-        __shared__ int sh_dead;
-        if (threadIdx.x == 0) {
-            const unsigned long long bits = __hip_atomic_load(reinterpret_cast<unsigned long long*>(&ws.a0[bn]),
-                                                              __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            sh_dead = (bits != kNotReady && !(__longlong_as_double(static_cast<long long>(bits)) > 0.0)) ? 1 : 0;
-        }
-        __syncthreads();
-        if (sh_dead) {
-            if (threadIdx.x < k) {
-                const int cn = tree.child_list[tree.child_off[n] + threadIdx.x];
-                const size_t bc = static_cast<size_t>(b) * a.N + cn;
-                if (tree.nchild[cn] == 0) ws.atest[bc] = 0.0;
-                else __hip_atomic_store(reinterpret_cast<unsigned long long*>(&ws.a0[bc]), 0ull, __ATOMIC_RELAXED,
-                                        __HIP_MEMORY_SCOPE_AGENT);           // the bits of +0.0
-            }
-            if (threadIdx.x == 0) {
-                ws.atest[bn] = 0.0;
-                ws.cfin[bn] = 0.0;
-                ws.Wfin[bn] = 1.0;
-            }
-            return;
-        }
-    }
     if (threadIdx.x == 0) atomicAdd(&a.counters[MPV_COUNTER_NODE_TASKS_RUN], 1u);
 
     // ---- the children's tokens and this node's starting weight: fetched now, so that
     //      their latency hides behind the sweep (lane j looks after child j)
     __shared__ int ch_tok[MPV_MAX_CHILDREN];
+    __shared__ int ch_push[MPV_MAX_CHILDREN];
+    if (threadIdx.x < MPV_MAX_CHILDREN) ch_push[threadIdx.x] = 0;
     __shared__ float ch_zt[MPV_MAX_CHILDREN], ch_zd[MPV_MAX_CHILDREN];
     __shared__ double sh_a0;
     int pf_x = -1;
@@ -190,7 +237,9 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(TreeDesc tree, Ta
 
     // ---- softmax statistics of both rows: the one read of the pair from memory
     RetainedPair<E, kTaskBlock, RV, LV, CH, FULL> pair;
-    pair.setup(zt, zd, V, lds_t, lds_d);
+    int tid_l = threadIdx.x;
+    asm volatile("" : "+v"(tid_l));     // per-task copy: nothing derived from it is kept across tasks
+    pair.setup(zt, zd, V, lds_t, lds_d, tid_l);
     pair.issue_register_loads();
     T pf_t = 0, pf_d = 0;       // kept as stored until the sweep is over: touching them now would wait for every load above
     if (pf_x >= 0 && pf_x < V) {
@@ -273,6 +322,11 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(TreeDesc tree, Ta
                     __hip_atomic_store(reinterpret_cast<unsigned long long*>(&ws.a0[bc]),
                                        static_cast<unsigned long long>(__double_as_longlong(w_child)),
                                        __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    // A child of weight 0 can never be accepted, passes weight 0 to its whole subtree
+                    // and never provides a bonus distribution: its task (and its subtree's) is not
+                    // queued, its rows are never read.  (Queued all the same when per-edge debug
+                    // output is wanted.)
+                    ch_push[j] = (w_child > 0.0 || !a.prune) ? 1 : 0;
                 }
             } else {
                 ws.atest[bc] = w_child;
@@ -336,6 +390,19 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(TreeDesc tree, Ta
         ws.Wfin[bn] = W;
         if (METHOD == MPV_METHOD_TRAVERSAL && n != 0) ws.atest[bn] = wa;
     }
+    if (METHOD == MPV_METHOD_TRAVERSAL) {
+        // append the children that still matter to the next level, then report this task finished
+        __syncthreads();                              // ch_push written by lane 0 above
+        if (threadIdx.x < k && ch_push[threadIdx.x]) {
+            const int cn = tree.child_list[tree.child_off[n] + threadIdx.x];
+            const int slot = atomicAdd(&ws.tail[level + 1], 1);
+            __hip_atomic_store(&ws.queue[list.block_start[level + 1] + slot], b * a.N + cn, __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_AGENT);
+        }
+        __syncthreads();                              // every append has returned its slot
+        if (threadIdx.x == 0) atomicAdd(&ws.completed[level], 1);
+    }
+    }   // task loop
 }
 
 // ------------------------------------------------------------------ walk
@@ -786,8 +853,25 @@ static size_t carve(const mpv_problem* p, void* base, Workspace* ws) {
     double* at = static_cast<double*>(take(bn * 8));
     float* mt = static_cast<float*>(take(bn * 4));
     float* md = static_cast<float*>(take(bn * 4));
-    if (ws) { ws->At = At; ws->Ad = Ad; ws->cfin = cf; ws->Wfin = Wf; ws->a0 = a0; ws->atest = at; ws->mt = mt; ws->md = md; }
+    int32_t* qu = static_cast<int32_t*>(take(bn * 4));
+    int32_t* hd = static_cast<int32_t*>(take(MPV_MAX_NODES * 4));
+    int32_t* tl = static_cast<int32_t*>(take(MPV_MAX_NODES * 4));
+    int32_t* cp = static_cast<int32_t*>(take(MPV_MAX_NODES * 4));
+    if (ws) { ws->At = At; ws->Ad = Ad; ws->cfin = cf; ws->Wfin = Wf; ws->a0 = a0; ws->atest = at; ws->mt = mt; ws->md = md; ws->queue = qu; ws->head = hd; ws->tail = tl; ws->completed = cp; }
     return off < 256 ? 256 : off;
+}
+
+static int compute_units() {
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
+            cus = n;
+        else
+            cus = 256;
+    }
+    return cus;
 }
 
 template <class E>
@@ -796,43 +880,43 @@ static int launch_all(const mpv_problem* p, const Plan& plan, const Workspace& w
     (void)hipGetLastError();    // a stale error left by the caller's own HIP calls is not ours
     // every register and LDS slot of a node task is populated whatever the row's alignment
     const bool full = (p->V - (E::VEC - 1)) / E::VEC >= (kRegVecs + kLdsVecs) * kTaskBlock;
+    // levels: SpecInfer one (tasks are independent), Traversal one per depth; inside a
+    // level the nodes with many children come first (they are the long tasks)
+    TaskList list;
+    memset(&list, 0, sizeof(list));
+    int nn = 0, tasks = 0;
+    const int nlev = (p->method == MPV_METHOD_SPECINFER) ? 1 : plan.max_tree_depth;
+    for (int d = 0; d < nlev; ++d) {
+        const int first = nn;
+        for (int kk = MPV_MAX_CHILDREN; kk >= 1; --kk)
+            for (int n = 0; n < p->N; ++n)
+                if (tree.nchild[n] == kk && (p->method == MPV_METHOD_SPECINFER || tree.depth[n] == d))
+                    list.nodes[nn++] = n;
+        if (nn == first) continue;                 // no internal node at this depth
+        list.node_off[list.nlevels] = first;
+        list.block_start[list.nlevels] = tasks;
+        tasks += p->B * (nn - first);
+        ++list.nlevels;
+    }
+    list.node_off[list.nlevels] = nn;
+    list.block_start[list.nlevels] = tasks;
     {
         const int threads = 256;
-        const int blocks = (max(p->B * p->N, MPV_COUNTER_COUNT) + threads - 1) / threads;
+        const int blocks = (max(p->B * p->N, MPV_MAX_NODES) + threads - 1) / threads;
         ScopedLaunch t(MPV_KERNEL_INIT, s);
-        hipLaunchKernelGGL(init_kernel, dim3(blocks), dim3(threads), 0, s, ws, a);
+        hipLaunchKernelGGL(init_kernel, dim3(blocks), dim3(threads), 0, s, list, ws, a, p->method);
     }
-    {
-        // levels: SpecInfer one (tasks are independent), Traversal one per depth; inside a
-        // level the nodes with many children come first (they are the long tasks)
-        TaskList list;
-        memset(&list, 0, sizeof(list));
-        int nn = 0, blocks = 0;
-        const int nlev = (p->method == MPV_METHOD_SPECINFER) ? 1 : plan.max_tree_depth;
-        for (int d = 0; d < nlev; ++d) {
-            const int first = nn;
-            for (int kk = MPV_MAX_CHILDREN; kk >= 1; --kk)
-                for (int n = 0; n < p->N; ++n)
-                    if (tree.nchild[n] == kk && (p->method == MPV_METHOD_SPECINFER || tree.depth[n] == d))
-                        list.nodes[nn++] = n;
-            if (nn == first) continue;                 // no internal node at this depth
-            list.node_off[list.nlevels] = first;
-            list.block_start[list.nlevels] = blocks;
-            blocks += p->B * (nn - first);
-            ++list.nlevels;
-        }
-        list.node_off[list.nlevels] = nn;
-        list.block_start[list.nlevels] = blocks;
-        if (blocks > 0) {
-            ScopedLaunch t(MPV_KERNEL_NODE_TASK, s);
-            const dim3 grid(static_cast<unsigned>(blocks)), block(kTaskBlock);
-            if (p->method == MPV_METHOD_SPECINFER) {
-                if (full) hipLaunchKernelGGL((node_task_kernel<E, MPV_METHOD_SPECINFER, true>), grid, block, 0, s, tree, list, ws, a);
-                else hipLaunchKernelGGL((node_task_kernel<E, MPV_METHOD_SPECINFER, false>), grid, block, 0, s, tree, list, ws, a);
-            } else {
-                if (full) hipLaunchKernelGGL((node_task_kernel<E, MPV_METHOD_TRAVERSAL, true>), grid, block, 0, s, tree, list, ws, a);
-                else hipLaunchKernelGGL((node_task_kernel<E, MPV_METHOD_TRAVERSAL, false>), grid, block, 0, s, tree, list, ws, a);
-            }
+    if (tasks > 0) {
+        // about one workgroup per compute unit (a node task fills one); fewer if there is less to do
+        const int wgs = tasks < compute_units() ? tasks : compute_units();
+        ScopedLaunch t(MPV_KERNEL_NODE_TASK, s);
+        const dim3 grid(static_cast<unsigned>(wgs)), block(kTaskBlock);
+        if (p->method == MPV_METHOD_SPECINFER) {
+            if (full) hipLaunchKernelGGL((node_task_kernel<E, MPV_METHOD_SPECINFER, true>), grid, block, 0, s, tree, list, ws, a);
+            else hipLaunchKernelGGL((node_task_kernel<E, MPV_METHOD_SPECINFER, false>), grid, block, 0, s, tree, list, ws, a);
+        } else {
+            if (full) hipLaunchKernelGGL((node_task_kernel<E, MPV_METHOD_TRAVERSAL, true>), grid, block, 0, s, tree, list, ws, a);
+            else hipLaunchKernelGGL((node_task_kernel<E, MPV_METHOD_TRAVERSAL, false>), grid, block, 0, s, tree, list, ws, a);
         }
     }
     {

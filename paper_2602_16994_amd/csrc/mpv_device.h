@@ -65,6 +65,15 @@ template <class T>
 __device__ __forceinline__ uint4 load_raw_at(const T* base, int vec) {
     return *reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(base) + (static_cast<unsigned>(vec) << 4));
 }
+// the same, marked non-temporal: data that will not be read from memory again (it is kept on
+// chip) should not push re-read data out of the L2 cache
+template <class T>
+__device__ __forceinline__ uint4 load_raw_at_nt(const T* base, int vec) {
+    typedef unsigned v4u __attribute__((ext_vector_type(4)));
+    const v4u t = __builtin_nontemporal_load(
+        reinterpret_cast<const v4u*>(reinterpret_cast<const char*>(base) + (static_cast<unsigned>(vec) << 4)));
+    return make_uint4(t.x, t.y, t.z, t.w);
+}
 
 // 2^x on the hardware transcendental unit (results below 2^-126 flush to zero,
 // which is what every caller wants for a vanishing probability).
@@ -389,14 +398,15 @@ struct RetainedPair {
     uint4* lt;
     uint4* ld;
     int V, head, nvec, tail0;
+    int tid;                                    // this lane's index, as handed to setup()
 #ifdef MPV_PROFILE_PHASES
     long long ts[16];
 #endif
 
     struct Chunk { uint4 a[2], d[2]; };
 
-    __device__ __forceinline__ void setup(const T* zt_, const T* zd_, int V_, uint4* lds_t, uint4* lds_d) {
-        zt = zt_; zd = zd_; V = V_; lt = lds_t; ld = lds_d;
+    __device__ __forceinline__ void setup(const T* zt_, const T* zd_, int V_, uint4* lds_t, uint4* lds_d, int tid_) {
+        zt = zt_; zd = zd_; V = V_; lt = lds_t; ld = lds_d; tid = tid_;
         const int mis = static_cast<int>((reinterpret_cast<uintptr_t>(zt) & 15u) / sizeof(T));
         head = mis ? min(VEC - mis, V) : 0;
         nvec = (V - head) / VEC;
@@ -407,7 +417,6 @@ struct RetainedPair {
 
     template <class F>
     __device__ __forceinline__ void edges(F& f) const {
-        const int tid = threadIdx.x;
         if (tid < head) f.one(E::load_one(zt + tid), E::load_one(zd + tid));
         if (tail0 + tid < V) f.one(E::load_one(zt + tail0 + tid), E::load_one(zd + tail0 + tid));
     }
@@ -415,7 +424,6 @@ struct RetainedPair {
     // streamed slots s0, s0+CH, ... with CH loads in flight (no pipelining across iterations)
     template <class F>
     __device__ __forceinline__ void streamed_from(int s0, F& f) const {
-        const int tid = threadIdx.x;
         for (int i = tid + (R + L + s0) * BLOCK; i < nvec; i += BLOCK * CH) {
             uint4 a[CH], d[CH];
 #pragma unroll
@@ -433,7 +441,7 @@ struct RetainedPair {
 
     // two streamed slots s, s+1 into a buffer / out of it
     __device__ __forceinline__ void issue(Chunk& c, int s) const {
-        int tid = threadIdx.x;
+        int tid = this->tid;
         asm volatile("" : "+v"(tid));       // recompute the addresses here: keeping them live across sweeps costs registers
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
@@ -444,7 +452,6 @@ struct RetainedPair {
     }
     template <class F>
     __device__ __forceinline__ void consume(const Chunk& c, int s, F& f) const {
-        const int tid = threadIdx.x;
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
             if (tid + (R + L + s + u) * BLOCK < nvec) f.vec(c.a[u], c.d[u]);
@@ -454,12 +461,10 @@ struct RetainedPair {
     static constexpr int DIST = 6;              // slots of loads kept ahead of the compute in the first sweep
 
     __device__ __forceinline__ void load_register_slot(int j) {
-        const int tid = threadIdx.x;
-        rt[j] = load_raw_at(bt, tid + j * BLOCK);
-        rd[j] = load_raw_at(bd, tid + j * BLOCK);
+        rt[j] = load_raw_at_nt(bt, tid + j * BLOCK);
+        rd[j] = load_raw_at_nt(bd, tid + j * BLOCK);
     }
     __device__ __forceinline__ void load_lds_slot(int j) {
-        const int tid = threadIdx.x;
         const int wave0 = (tid / kWave) * kWave;
         load_to_lds_16B(bt + static_cast<size_t>(tid + (R + j) * BLOCK) * VEC, lt + j * BLOCK + wave0);
         load_to_lds_16B(bd + static_cast<size_t>(tid + (R + j) * BLOCK) * VEC, ld + j * BLOCK + wave0);
@@ -496,7 +501,6 @@ struct RetainedPair {
             if (nvec > 0) streamed_from(0, f);
             return;
         }
-        const int tid = threadIdx.x;
         Chunk A;
         MPV_TS(0);
 #pragma unroll
@@ -535,7 +539,6 @@ struct RetainedPair {
             if (nvec > 0) streamed_from(0, f);
             return;
         }
-        const int tid = threadIdx.x;
         Chunk A;
         edges(f);
 #pragma unroll
