@@ -1,15 +1,15 @@
 // mpv.hip -- kernels and C ABI of the tree-verification library (gfx950 only).
 //
 // Path of one mpv_verify call (all on the caller's stream):
-//   init_kernel            zero counters, fill the first level of the task queue
+//   init_kernel            zero counters, queue the initial tasks
 //   node_task_kernel       one workgroup per (tree, internal node):
 //                            softmax statistics of the node's target and draft rows,
 //                            then, for each child in list order, the probability
 //                            the child is tested with and the residual mass after
 //                            its rejection (a V-wide reduction per child)
-//                          SpecInfer: one launch over all internal nodes
-//                          Traversal: one launch per tree depth (a node's initial
-//                            weight comes from its parent's task)
+//                          run by persistent workgroups that take tasks from a queue;
+//                          SpecInfer: all tasks queued up front; Traversal: the roots,
+//                            then each task queues its children of positive weight
 //   sample_kernel          one workgroup per tree: its first wave does the
 //                          uniform-dependent walk, then the workgroup draws the bonus
 //                          token by inverse CDF from the residual of the stopping node
@@ -42,15 +42,13 @@ struct TreeDesc {
     int32_t postorder[MPV_MAX_NODES];    // depth-first, children (in list order) before their parent; root last
 };
 
-// The node tasks of one call, grouped in levels.  Level l owns the entries
-// [block_start[l], block_start[l+1]) of the task queue, room for B tasks per listed node.
-// SpecInfer has one level, filled up front (its tasks are independent).  Traversal has one
-// level per tree depth: level 0 (the roots) is filled up front, and a finished task appends
-// those of its children that still matter to the next level.
+// The node tasks a call starts with: B tasks per listed node, node-major (the same node of
+// consecutive trees next to each other).  SpecInfer lists every internal node (its tasks are
+// independent).  Traversal lists the root only: a finished task appends those of its
+// children that still matter.
 struct TaskList {
-    int32_t nlevels;
-    int32_t block_start[MPV_MAX_NODES + 1];
-    int32_t node_off[MPV_MAX_NODES + 1];     // level l lists nodes[node_off[l] .. node_off[l+1])
+    int32_t count;                       // listed nodes
+    int32_t capacity;                    // queue entries available (B * internal nodes)
     int32_t nodes[MPV_MAX_NODES];
 };
 
@@ -64,10 +62,8 @@ struct Workspace {
     double* atest;   // probability the node is tested with
     float* mt;       // row maxima (for the debug statistics)
     float* md;
-    int32_t* queue;      // task queue, entry = tree * N + node, -1 = not written yet
-    int32_t* head;       // [levels] next ticket to hand out
-    int32_t* tail;       // [levels] tasks appended so far
-    int32_t* completed;  // [levels] tasks finished
+    int32_t* queue;      // task queue (first in, first out), entry = tree * N + node, -1 = not written yet
+    int32_t* qctl;       // [0] head: next ticket, [1] tail: tasks appended, [2] completed: tasks finished
 };
 
 struct Args {
@@ -88,6 +84,7 @@ struct Args {
     float k32;       // float(log2(e)/T)
     float invT;
     int32_t prune;   // skip node tasks whose node has weight 0 (off when per-edge debug output is wanted)
+    int32_t stagger_ticks;   // start-up spread of the persistent workgroups, in 10 ns ticks per step (8 steps)
 };
 
 constexpr int kTaskBlock = 512;
@@ -107,26 +104,18 @@ constexpr int kMaxTiles = MPV_MAX_VOCAB / kTile;
 
 // ------------------------------------------------------------------ init
 
-__global__ void init_kernel(TaskList list, Workspace ws, Args a, int method) {
+__global__ void init_kernel(TaskList list, Workspace ws, Args a) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < MPV_COUNTER_COUNT) a.counters[i] = 0u;
-    if (i < MPV_MAX_NODES) {
-        ws.head[i] = 0;
-        ws.completed[i] = 0;
-        ws.tail[i] = (i == 0) ? list.block_start[1] : 0;     // level 0 is complete from the start
-    }
+    const int prefilled = list.count * a.B;
+    if (i == 0) { ws.qctl[0] = 0; ws.qctl[1] = prefilled; ws.qctl[2] = 0; }
     if (i < a.B * a.N) {
         reinterpret_cast<unsigned long long*>(ws.a0)[i] = kNotReady;
         // a node no task ever reaches (Traversal: weight 0) is tested with probability 0
         ws.atest[i] = (i % a.N == 0) ? 1.0 : 0.0;
         ws.cfin[i] = 0.0;
         ws.Wfin[i] = 1.0;
-        // queue: level 0 node-major (same node of consecutive trees), the rest empty
-        const int total = list.block_start[list.nlevels];
-        if (i < total) {
-            const int level0 = list.block_start[1];
-            ws.queue[i] = (i < level0) ? (i % a.B) * a.N + list.nodes[i / a.B] : -1;
-        }
+        if (i < list.capacity) ws.queue[i] = (i < prefilled) ? (i % a.B) * a.N + list.nodes[i / a.B] : -1;
     }
     if (i < a.B && a.dbg_edge) {
         a.dbg_edge[static_cast<size_t>(i) * a.N * 2] = 1.f;
@@ -137,48 +126,41 @@ __global__ void init_kernel(TaskList list, Workspace ws, Args a, int method) {
 // ------------------------------------------------------------------ task queue
 //
 // node_task_kernel is launched with about one workgroup per compute unit; each workgroup
-// keeps taking tasks until none are left.  A workgroup draws a ticket h at a level (one
-// atomic add on head[level]); the ticket is good for queue entry h of that level if that
-// entry ever gets written.  It will be written iff h < final tail[level]; tail[level] is
-// final once every task of level-1 has finished (completed[level-1] == tail[level-1]; by
-// induction that tail is final too, because a workgroup only moves up a level after it has
-// seen the level below finished).  A task's appends (returning atomic adds on tail) are
-// performed before its completed++ is issued, so whoever sees the level below finished
-// then reads final tails.  Any resident workgroup can run any task, so nothing here depends
-// on which or how many workgroups are resident.  All waits are bounded.
+// keeps taking tasks until none are left.  One first-in-first-out queue: a task is appended
+// only when everything it needs has been published, so every queued task can run at once.
+// A workgroup draws a ticket h (atomic add on head) and waits until entry h is written, or
+// until nothing is left: completed == tail, read between two equal reads of tail, means that
+// at that moment no task was running, so nothing can be appended any more.  A task's appends
+// (returning atomic adds on tail) have been performed before its completed++ is issued.
+// Any resident workgroup can run any task, so nothing depends on which or how many
+// workgroups are resident.  Waits are bounded.
 
 __device__ __forceinline__ int ld_relaxed(const int32_t* p) {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// Next task for this workgroup (called by one lane).  Returns tree*N+node, or -1 when there is
-// nothing left; `level` is updated to the level the task belongs to.
-__device__ int next_task(const TaskList& list, const Workspace& ws, const Args& a, int& level) {
-    while (level < list.nlevels) {
-        const int h = atomicAdd(&ws.head[level], 1);
-        bool mine = false;
-        for (int spin = 0; spin < kMaxSpins; ++spin) {
-            if (h < ld_relaxed(&ws.tail[level])) { mine = true; break; }
-            if (level == 0) break;                                   // tail[0] never grows
-            if (ld_relaxed(&ws.completed[level - 1]) == ld_relaxed(&ws.tail[level - 1])) {
-                mine = h < ld_relaxed(&ws.tail[level]);              // now final
-                break;
-            }
-            __builtin_amdgcn_s_sleep(32);
-            if (spin == kMaxSpins - 1) atomicAdd(&a.counters[MPV_COUNTER_DEPENDENCY_TIMEOUT], 1u);
-        }
-        if (mine) {
-            const int32_t* e = ws.queue + list.block_start[level] + h;
-            for (int spin = 0; spin < kMaxSpins; ++spin) {
-                const int t = ld_relaxed(e);
+// Next task for this workgroup (called by one lane): tree*N+node, or -1 when there is none left.
+__device__ int next_task(const Workspace& ws, const Args& a) {
+    const int h = atomicAdd(&ws.qctl[0], 1);
+    for (int spin = 0; spin < kMaxSpins; ++spin) {
+        const int t1 = ld_relaxed(&ws.qctl[1]);
+        if (h < t1) {
+            for (int spin2 = 0; spin2 < kMaxSpins; ++spin2) {
+                const int t = ld_relaxed(&ws.queue[h]);
                 if (t >= 0) return t;
                 __builtin_amdgcn_s_sleep(8);
             }
-            atomicAdd(&a.counters[MPV_COUNTER_DEPENDENCY_TIMEOUT], 1u);
-            return -1;
+            break;
         }
-        ++level;
+        // the three reads must be performed in this order: t1 was needed for the branch above;
+        // wait for `completed` to arrive before the second read of tail is issued
+        const int c = ld_relaxed(&ws.qctl[2]);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        const int t2 = ld_relaxed(&ws.qctl[1]);
+        if (c == t1 && t1 == t2) return -1;
+        __builtin_amdgcn_s_sleep(32);
     }
+    atomicAdd(&a.counters[MPV_COUNTER_DEPENDENCY_TIMEOUT], 1u);     // must never happen
     return -1;
 }
 
@@ -197,18 +179,22 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(TreeDesc tree, Ta
     __shared__ uint4 lds_t[(LV > 0 ? LV : 1) * kTaskBlock];
     __shared__ uint4 lds_d[(LV > 0 ? LV : 1) * kTaskBlock];
 
-    __shared__ int sh_task, sh_level;
-    int level = 0;
+    __shared__ int sh_task;
+    // Every task alternates a memory-bound sweep with compute-bound replays and all tasks of a
+    // kind take the same time, so workgroups started together stay in step: all load at once
+    // (sharing the memory bandwidth), then all leave memory idle.  Spreading their start over
+    // a fraction of a task keeps them out of phase for the rest of the launch.
+    if (a.stagger_ticks > 0) {
+        const long long wait = static_cast<long long>((blockIdx.x >> 3) & 7) * a.stagger_ticks;
+        const long long t0 = wall_clock64();
+        while (wall_clock64() - t0 < wait) __builtin_amdgcn_s_sleep(16);    // the clock always advances: bounded
+    }
     for (;;) {
     __syncthreads();                                  // the previous task is done with LDS
-    if (threadIdx.x == 0) {
-        sh_task = next_task(list, ws, a, level);
-        sh_level = level;
-    }
+    if (threadIdx.x == 0) sh_task = next_task(ws, a);
     __syncthreads();
     const int task = sh_task;
     if (task < 0) break;
-    level = sh_level;
     const int b = task / a.N;
     const int n = task % a.N;
     const size_t bn = static_cast<size_t>(b) * a.N + n;
@@ -217,10 +203,6 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(TreeDesc tree, Ta
     const int V = a.V;
     const float k32 = a.k32;
 
-#ifdef MPV_PROFILE_PHASES
-    long long tstamp[8]; int nts = 0;
-    { __builtin_amdgcn_sched_barrier(0); tstamp[nts++] = wall_clock64(); __builtin_amdgcn_sched_barrier(0); }
-#endif
     const int k = tree.nchild[n];
     if (threadIdx.x == 0) atomicAdd(&a.counters[MPV_COUNTER_NODE_TASKS_RUN], 1u);
 
@@ -251,13 +233,10 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(TreeDesc tree, Ta
         PairStatsRawF<E> f;
         f.t.init(); f.d.init(); f.k32 = k32;
         pair.first_pass(f);
-#ifdef MPV_PROFILE_PHASES
-        { __builtin_amdgcn_sched_barrier(0); tstamp[nts++] = wall_clock64(); __builtin_amdgcn_sched_barrier(0); }
-#endif
         if (threadIdx.x < k) { ch_tok[threadIdx.x] = pf_x; ch_zt[threadIdx.x] = E::load_one(&pf_t); ch_zd[threadIdx.x] = E::load_one(&pf_d); }
         if (threadIdx.x == 0) {
-            // Traversal: the starting weight comes from the parent's task (an earlier block of
-            // this launch, or an earlier level); it has normally been there for a long time.
+            // Traversal: the starting weight comes from the parent's task, which published it
+            // before it queued this task; the two stores may still arrive in either order.
             double a0 = 1.0;
             if (METHOD == MPV_METHOD_TRAVERSAL && n != 0) {
                 // value and "ready" flag are one 64-bit word (a weight is never NaN), read and
@@ -282,9 +261,6 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(TreeDesc tree, Ta
         rt.A = uniform_f64(rt.A);
         rd.A = uniform_f64(rd.A);
     }
-#ifdef MPV_PROFILE_PHASES
-    { __builtin_amdgcn_sched_barrier(0); tstamp[nts++] = wall_clock64(); __builtin_amdgcn_sched_barrier(0); }
-#endif
 
     // ---- per-child scalars and one residual-mass reduction per child
     double wa = (METHOD == MPV_METHOD_TRAVERSAL) ? uniform_f64(sh_a0) : 1.0;   // node weight a
@@ -346,13 +322,7 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(TreeDesc tree, Ta
         ResidualMassRawF<E> f;
         f.init();
         f.k32 = k32; f.nAt = rc.nAt; f.nAd = rc.nAd; f.rho = uniform_f32(rc.rho);
-#ifdef MPV_PROFILE_PHASES
-        if (j == 0) { __builtin_amdgcn_sched_barrier(0); tstamp[nts++] = wall_clock64(); __builtin_amdgcn_sched_barrier(0); }
-#endif
         pair.replay(f);
-#ifdef MPV_PROFILE_PHASES
-        if (j == 0) { __builtin_amdgcn_sched_barrier(0); tstamp[nts++] = wall_clock64(); __builtin_amdgcn_sched_barrier(0); }
-#endif
         const double W2 = uniform_f64(scale * block_sum<kTaskBlock>(static_cast<double>(f.acc0) + static_cast<double>(f.acc1), scratch));
         if (W2 > 0.0) {
             if (METHOD == MPV_METHOD_TRAVERSAL) {
@@ -367,20 +337,6 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(TreeDesc tree, Ta
         }
     }
 
-#ifdef MPV_PROFILE_PHASES
-    { __builtin_amdgcn_sched_barrier(0); tstamp[nts++] = wall_clock64(); __builtin_amdgcn_sched_barrier(0); }
-    // bounds: (blocks - B) * 5 floats <= B*N*4 for the benchmark tree (checked by the probe script)
-    if (threadIdx.x == 0 && a.dbg_stats && static_cast<int>(blockIdx.x) >= a.B &&
-        (static_cast<size_t>(gridDim.x) - a.B) * 5 <= static_cast<size_t>(a.B) * a.N * 4) {
-        float* o = a.dbg_stats + (static_cast<size_t>(blockIdx.x) - a.B) * 5;
-        const unsigned hw = __builtin_amdgcn_s_getreg(0xF804), xcc = __builtin_amdgcn_s_getreg(0x1814);
-        o[0] = static_cast<float>(tstamp[0] & 0xffffff);          // absolute start, 10 ns ticks (low 24 bits)
-        o[1] = static_cast<float>(((xcc & 15u) << 8) | (((hw >> 13) & 7u) << 5) | (((hw >> 12) & 1u) << 4) | ((hw >> 8) & 15u));
-        o[2] = static_cast<float>(tstamp[2] - tstamp[0]);         // statistics reduced
-        o[3] = static_cast<float>(nts >= 6 ? tstamp[4] - tstamp[0] : -1);   // first replay done
-        o[4] = static_cast<float>(tstamp[nts - 1] - tstamp[0]);   // task done
-    }
-#endif
     if (threadIdx.x == 0) {
         ws.At[bn] = rt.A;
         ws.Ad[bn] = rd.A;
@@ -390,18 +346,16 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(TreeDesc tree, Ta
         ws.Wfin[bn] = W;
         if (METHOD == MPV_METHOD_TRAVERSAL && n != 0) ws.atest[bn] = wa;
     }
-    if (METHOD == MPV_METHOD_TRAVERSAL) {
-        // append the children that still matter to the next level, then report this task finished
-        __syncthreads();                              // ch_push written by lane 0 above
-        if (threadIdx.x < k && ch_push[threadIdx.x]) {
-            const int cn = tree.child_list[tree.child_off[n] + threadIdx.x];
-            const int slot = atomicAdd(&ws.tail[level + 1], 1);
-            __hip_atomic_store(&ws.queue[list.block_start[level + 1] + slot], b * a.N + cn, __ATOMIC_RELAXED,
-                               __HIP_MEMORY_SCOPE_AGENT);
-        }
-        __syncthreads();                              // every append has returned its slot
-        if (threadIdx.x == 0) atomicAdd(&ws.completed[level], 1);
+    // append the children that still matter (Traversal), then report this task finished
+    __syncthreads();                                  // ch_push written by lane 0 above
+    if (METHOD == MPV_METHOD_TRAVERSAL && threadIdx.x < k && ch_push[threadIdx.x]) {
+        const int cn = tree.child_list[tree.child_off[n] + threadIdx.x];
+        const int slot = atomicAdd(&ws.qctl[1], 1);
+        if (slot < list.capacity)
+            __hip_atomic_store(&ws.queue[slot], b * a.N + cn, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
+    __syncthreads();                                  // every append has returned its slot
+    if (threadIdx.x == 0) atomicAdd(&ws.qctl[2], 1);
     }   // task loop
 }
 
@@ -854,10 +808,8 @@ static size_t carve(const mpv_problem* p, void* base, Workspace* ws) {
     float* mt = static_cast<float*>(take(bn * 4));
     float* md = static_cast<float*>(take(bn * 4));
     int32_t* qu = static_cast<int32_t*>(take(bn * 4));
-    int32_t* hd = static_cast<int32_t*>(take(MPV_MAX_NODES * 4));
-    int32_t* tl = static_cast<int32_t*>(take(MPV_MAX_NODES * 4));
-    int32_t* cp = static_cast<int32_t*>(take(MPV_MAX_NODES * 4));
-    if (ws) { ws->At = At; ws->Ad = Ad; ws->cfin = cf; ws->Wfin = Wf; ws->a0 = a0; ws->atest = at; ws->mt = mt; ws->md = md; ws->queue = qu; ws->head = hd; ws->tail = tl; ws->completed = cp; }
+    int32_t* qc = static_cast<int32_t*>(take(4 * 4));
+    if (ws) { ws->At = At; ws->Ad = Ad; ws->cfin = cf; ws->Wfin = Wf; ws->a0 = a0; ws->atest = at; ws->mt = mt; ws->md = md; ws->queue = qu; ws->qctl = qc; }
     return off < 256 ? 256 : off;
 }
 
@@ -880,31 +832,21 @@ static int launch_all(const mpv_problem* p, const Plan& plan, const Workspace& w
     (void)hipGetLastError();    // a stale error left by the caller's own HIP calls is not ours
     // every register and LDS slot of a node task is populated whatever the row's alignment
     const bool full = (p->V - (E::VEC - 1)) / E::VEC >= (kRegVecs + kLdsVecs) * kTaskBlock;
-    // levels: SpecInfer one (tasks are independent), Traversal one per depth; inside a
-    // level the nodes with many children come first (they are the long tasks)
+    // initial tasks: every internal node for SpecInfer (nodes with many children first: they are
+    // the long tasks), the root alone for Traversal
     TaskList list;
     memset(&list, 0, sizeof(list));
-    int nn = 0, tasks = 0;
-    const int nlev = (p->method == MPV_METHOD_SPECINFER) ? 1 : plan.max_tree_depth;
-    for (int d = 0; d < nlev; ++d) {
-        const int first = nn;
-        for (int kk = MPV_MAX_CHILDREN; kk >= 1; --kk)
-            for (int n = 0; n < p->N; ++n)
-                if (tree.nchild[n] == kk && (p->method == MPV_METHOD_SPECINFER || tree.depth[n] == d))
-                    list.nodes[nn++] = n;
-        if (nn == first) continue;                 // no internal node at this depth
-        list.node_off[list.nlevels] = first;
-        list.block_start[list.nlevels] = tasks;
-        tasks += p->B * (nn - first);
-        ++list.nlevels;
-    }
-    list.node_off[list.nlevels] = nn;
-    list.block_start[list.nlevels] = tasks;
+    for (int kk = MPV_MAX_CHILDREN; kk >= 1; --kk)
+        for (int n = 0; n < p->N; ++n)
+            if (tree.nchild[n] == kk && (p->method == MPV_METHOD_SPECINFER || n == 0))
+                list.nodes[list.count++] = n;
+    list.capacity = p->B * plan.n_internal;
+    const int tasks = list.capacity;
     {
         const int threads = 256;
         const int blocks = (max(p->B * p->N, MPV_MAX_NODES) + threads - 1) / threads;
         ScopedLaunch t(MPV_KERNEL_INIT, s);
-        hipLaunchKernelGGL(init_kernel, dim3(blocks), dim3(threads), 0, s, list, ws, a, p->method);
+        hipLaunchKernelGGL(init_kernel, dim3(blocks), dim3(threads), 0, s, list, ws, a);
     }
     if (tasks > 0) {
         // about one workgroup per compute unit (a node task fills one); fewer if there is less to do
@@ -926,12 +868,10 @@ static int launch_all(const mpv_problem* p, const Plan& plan, const Workspace& w
         else
             hipLaunchKernelGGL((sample_kernel<E, MPV_METHOD_TRAVERSAL>), dim3(p->B), dim3(kSampleBlock), 0, s, tree, ws, a);
     }
-#ifndef MPV_PROFILE_PHASES
     if (a.dbg_stats) {
         ScopedLaunch t(MPV_KERNEL_DEBUG_STATS, s);
         hipLaunchKernelGGL((debug_stats_kernel<E>), dim3(static_cast<unsigned>(p->B) * p->N), dim3(kTaskBlock), 0, s, tree, a);
     }
-#endif
     return hip_ok(hipGetLastError()) ? MPV_OK : MPV_ERR_HIP;
 }
 
@@ -997,6 +937,15 @@ int mpv_verify(const mpv_problem* problem, const mpv_buffers* buf, void* workspa
     a.k32 = static_cast<float>(1.4426950408889634 / static_cast<double>(problem->temperature));
     a.invT = 1.0f / problem->temperature;
     a.prune = (buf->edge_probs == nullptr) ? 1 : 0;
+    {
+        // start-up spread of the persistent workgroups: about the time one workgroup needs to
+        // read a row pair when every compute unit is reading (its share of ~6.3 TB/s), only
+        // for rows long enough to be kept on chip (short rows finish before it would matter)
+        const double pair_bytes = 2.0 * problem->V * (problem->logit_dtype == MPV_DTYPE_F32 ? 4 : 2);
+        const double share_bytes_per_us = 6.3e6 / mpv::compute_units();
+        const double us = pair_bytes / share_bytes_per_us;
+        a.stagger_ticks = (pair_bytes >= 400e3) ? static_cast<int32_t>(us * 100.0 / 8.0) : 0;
+    }
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     if (problem->logit_dtype == MPV_DTYPE_F32) return mpv::launch_all<mpv::ElemF32>(problem, plan, ws, a, s);
     return mpv::launch_all<mpv::ElemBF16>(problem, plan, ws, a, s);

@@ -15,12 +15,6 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
-#ifdef MPV_PROFILE_PHASES
-#define MPV_TS(slot) do { __builtin_amdgcn_sched_barrier(0); ts[slot] = wall_clock64(); __builtin_amdgcn_sched_barrier(0); } while (0)
-#else
-#define MPV_TS(slot) do {} while (0)
-#endif
-
 namespace mpv {
 
 constexpr int kWave = 64;
@@ -399,9 +393,6 @@ struct RetainedPair {
     uint4* ld;
     int V, head, nvec, tail0;
     int tid;                                    // this lane's index, as handed to setup()
-#ifdef MPV_PROFILE_PHASES
-    long long ts[16];
-#endif
 
     struct Chunk { uint4 a[2], d[2]; };
 
@@ -502,7 +493,6 @@ struct RetainedPair {
             return;
         }
         Chunk A;
-        MPV_TS(0);
 #pragma unroll
         for (int j = 0; j < R; ++j) {
             const int ahead = j + DIST;
@@ -511,9 +501,7 @@ struct RetainedPair {
             chunk_step(j, A, f);
             if (j == 0) f.begin(rt[0], rd[0]);
             f.vec(rt[j], rd[j]);
-            if (j == 0) MPV_TS(1);
         }
-        MPV_TS(4);
 #pragma unroll
         for (int j = 0; j < L; ++j) {
             const int ahead = R + j + DIST;
@@ -521,12 +509,9 @@ struct RetainedPair {
             chunk_step(R + j, A, f);
             f.vec(lt[j * BLOCK + tid], ld[j * BLOCK + tid]);
         }
-        MPV_TS(6);
         consume(A, 8, f);
-        MPV_TS(7);
         streamed_from(PIPED, f);
         edges(f);
-        MPV_TS(8);
     }
 
     // Later sweeps.  The empty asm marks each kept register as "possibly changed",

@@ -210,6 +210,27 @@ def test_peaked_rows_long_vocabulary(method, T):
     print("[report]", rep, flush=True)
 
 
+@pytest.mark.parametrize("method", [SI, TV])
+def test_many_small_tasks_through_the_queue(method):
+    """Far more node tasks than workgroups, short rows, a bushy tree: the task queue hands out
+    thousands of tasks, Traversal appends children level after level.  Decisions of every tree
+    are compared with the oracle; per-node probabilities on a sample."""
+    announce("queue stress", METHOD_NAME[method])
+    cfg = workloads.Config("queue_stress", B=1500, V=96, K=1, L1=0, L2=0, dtype="f32", T=1.0,
+                           methods=[method], draft_sigma=1.0, target_sigma=0.7, seed=404)
+    cfg.parent = [-1, 0, 0, 0, 1, 1, 2, 4, 4, 5, 6, 6, 7, 9, 9, 10, 12, 13]
+    inputs = workloads.make_inputs(cfg, "cuda")
+    host = workloads.to_host(inputs)
+    lean = run_library(inputs, cfg.T, method, debug=False)
+    assert lean["counters"][4] == 0
+    rep = compare_with_oracle(method, host, cfg.T, lean, check_debug=False)
+    print("[report]", rep, "counters", lean["counters"].tolist(), flush=True)
+    full = run_library(inputs, cfg.T, method, debug=True)
+    compare_with_oracle(method, host, cfg.T, full, trees=range(0, cfg.B, 50))
+    for key in ("accept_len", "path_nodes", "path_tokens", "bonus_token"):
+        assert np.array_equal(full[key], lean[key])
+
+
 def test_out_of_range_tokens_are_counted_not_followed():
     announce("bad tokens")
     cfg = workloads.Config("badtok", B=3, V=500, K=2, L1=0, L2=2, dtype="f32", T=1.0,
