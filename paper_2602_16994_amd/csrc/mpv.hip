@@ -2,17 +2,18 @@
 //
 // Path of one mpv_verify call (all on the caller's stream):
 //   init_kernel            zero counters, queue the initial tasks
-//   node_task_kernel       one workgroup per (tree, internal node):
+//   node_task_kernel       persistent workgroups that take tasks from a queue.
+//                          Node task, one per (tree, internal node):
 //                            softmax statistics of the node's target and draft rows,
 //                            then, for each child in list order, the probability
 //                            the child is tested with and the residual mass after
-//                            its rejection (a V-wide reduction per child)
-//                          run by persistent workgroups that take tasks from a queue;
-//                          SpecInfer: all tasks queued up front; Traversal: the roots,
-//                            then each task queues its children of positive weight
-//   sample_kernel          one workgroup per tree: its first wave does the
-//                          uniform-dependent walk, then the workgroup draws the bonus
-//                          token by inverse CDF from the residual of the stopping node
+//                            its rejection (a V-wide reduction per child).
+//                            SpecInfer: all queued up front; Traversal: the roots,
+//                            then each task queues its children of positive weight.
+//                          Sampling task, one per tree, queued by the tree's last node
+//                            task: the first wave does the uniform-dependent walk, then
+//                            the workgroup draws the bonus token by inverse CDF from
+//                            the residual of the stopping node.
 //
 // Why this is the same computation as the step-by-step rules: every distribution
 // either rule draws from is (p - c q)_+ / W(c) for one scalar c per node state
@@ -48,7 +49,7 @@ struct TreeDesc {
 // children that still matter.
 struct TaskList {
     int32_t count;                       // listed nodes
-    int32_t capacity;                    // queue entries available (B * internal nodes)
+    int32_t capacity;                    // queue entries available (B * internal nodes + B sampling tasks)
     int32_t nodes[MPV_MAX_NODES];
 };
 
@@ -64,6 +65,7 @@ struct Workspace {
     float* md;
     int32_t* queue;      // task queue (first in, first out), entry = tree * N + node, -1 = not written yet
     int32_t* qctl;       // [0] head: next ticket, [1] tail: tasks appended, [2] completed: tasks finished
+    int32_t* pending;    // [B] node tasks of the tree queued or running; 0: the tree can be sampled
 };
 
 struct Args {
@@ -98,24 +100,30 @@ constexpr int kChunk = 2;
 constexpr int kMaxSpins = 1 << 20;
 // bit pattern (a NaN) of a starting weight that has not been published yet
 constexpr unsigned long long kNotReady = ~0ull;
-constexpr int kSampleBlock = 512;
-constexpr int kTile = 512;               // elements per wave tile in the sampler
-constexpr int kMaxTiles = MPV_MAX_VOCAB / kTile;
+constexpr int kSampleBlock = kTaskBlock;     // sampling tasks run on the node tasks' workgroups
+// wave tiles of the bonus sampler: 64 16-byte vectors; float rows have the smallest tiles
+constexpr int kMaxTiles = MPV_MAX_VOCAB / (kWave * 4);
 
 // ------------------------------------------------------------------ init
 
 __global__ void init_kernel(TaskList list, Workspace ws, Args a) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < MPV_COUNTER_COUNT) a.counters[i] = 0u;
-    const int prefilled = list.count * a.B;
+    // a tree without internal nodes has nothing but its sampling task
+    const int prefilled = (list.count > 0 ? list.count : 1) * a.B;
     if (i == 0) { ws.qctl[0] = 0; ws.qctl[1] = prefilled; ws.qctl[2] = 0; }
+    if (i < a.B) ws.pending[i] = list.count;
     if (i < a.B * a.N) {
         reinterpret_cast<unsigned long long*>(ws.a0)[i] = kNotReady;
         // a node no task ever reaches (Traversal: weight 0) is tested with probability 0
         ws.atest[i] = (i % a.N == 0) ? 1.0 : 0.0;
         ws.cfin[i] = 0.0;
         ws.Wfin[i] = 1.0;
-        if (i < list.capacity) ws.queue[i] = (i < prefilled) ? (i % a.B) * a.N + list.nodes[i / a.B] : -1;
+        if (i < list.capacity) {
+            int entry = -1;
+            if (i < prefilled) entry = list.count > 0 ? (i % a.B) * a.N + list.nodes[i / a.B] : a.B * a.N + i;
+            ws.queue[i] = entry;
+        }
     }
     if (i < a.B && a.dbg_edge) {
         a.dbg_edge[static_cast<size_t>(i) * a.N * 2] = 1.f;
@@ -139,7 +147,22 @@ __device__ __forceinline__ int ld_relaxed(const int32_t* p) {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// Next task for this workgroup (called by one lane): tree*N+node, or -1 when there is none left.
+// Results one task leaves for another task of the same launch (which may run on another
+// chiplet, behind another L2 cache): written through and read past the caches with relaxed
+// device-scope atomics.  Order between them is the writer's business: it waits for its stores
+// to be acknowledged (s_waitcnt vmcnt(0)) before the atomic that lets the reader start.
+__device__ __forceinline__ void st_shared_f64(double* p, double v) {
+    __hip_atomic_store(reinterpret_cast<unsigned long long*>(p),
+                       static_cast<unsigned long long>(__double_as_longlong(v)), __ATOMIC_RELAXED,
+                       __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ double ld_shared_f64(const double* p) {
+    return __longlong_as_double(static_cast<long long>(__hip_atomic_load(
+        reinterpret_cast<const unsigned long long*>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)));
+}
+
+// Next task for this workgroup (called by one lane): tree*N+node (node task) or B*N+tree
+// (sampling task), or -1 when there is none left.
 __device__ int next_task(const Workspace& ws, const Args& a) {
     const int h = atomicAdd(&ws.qctl[0], 1);
     for (int spin = 0; spin < kMaxSpins; ++spin) {
@@ -166,6 +189,10 @@ __device__ int next_task(const Workspace& ws, const Args& a) {
 
 // ------------------------------------------------------------------ node task
 
+// (defined below) walk and bonus token of tree b, by the whole workgroup
+template <class E, int METHOD>
+__device__ void sample_task(const TreeDesc& tree, const Workspace& ws, const Args& a, int b,
+                            float* tile_sum, double* scratch);
 
 template <class E, int METHOD, bool FULL>
 __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(TreeDesc tree, TaskList list,
@@ -178,6 +205,10 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(TreeDesc tree, Ta
     constexpr int CH = FULL ? kChunk : 4;
     __shared__ uint4 lds_t[(LV > 0 ? LV : 1) * kTaskBlock];
     __shared__ uint4 lds_d[(LV > 0 ? LV : 1) * kTaskBlock];
+
+    // the sampling task's table of tile masses shares the LDS the kept rows use
+    static_assert(!FULL || sizeof(lds_t) >= kMaxTiles * sizeof(float), "tile masses do not fit in the kept-row LDS");
+    __shared__ float own_tile_mass[FULL ? 1 : kMaxTiles];
 
     __shared__ int sh_task;
     // Every task alternates a memory-bound sweep with compute-bound replays and all tasks of a
@@ -195,6 +226,13 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(TreeDesc tree, Ta
     __syncthreads();
     const int task = sh_task;
     if (task < 0) break;
+    if (task >= a.B * a.N) {
+        // the tree's node tasks are all done: walk and bonus token
+        float* tile_mass = FULL ? reinterpret_cast<float*>(lds_t) : own_tile_mass;
+        sample_task<E, METHOD>(tree, ws, a, task - a.B * a.N, tile_mass, scratch);
+        if (threadIdx.x == 0) atomicAdd(&ws.qctl[2], 1);
+        continue;
+    }
     const int b = task / a.N;
     const int n = task % a.N;
     const size_t bn = static_cast<size_t>(b) * a.N + n;
@@ -293,7 +331,7 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(TreeDesc tree, Ta
         if (threadIdx.x == 0) {
             if (METHOD == MPV_METHOD_TRAVERSAL) {
                 if (tree.nchild[cn] == 0) {
-                    ws.atest[bc] = w_child;                          // leaves are tested as they are
+                    st_shared_f64(&ws.atest[bc], w_child);           // leaves are tested as they are
                 } else {
                     __hip_atomic_store(reinterpret_cast<unsigned long long*>(&ws.a0[bc]),
                                        static_cast<unsigned long long>(__double_as_longlong(w_child)),
@@ -305,7 +343,7 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(TreeDesc tree, Ta
                     ch_push[j] = (w_child > 0.0 || !a.prune) ? 1 : 0;
                 }
             } else {
-                ws.atest[bc] = w_child;
+                st_shared_f64(&ws.atest[bc], w_child);
             }
             if (a.dbg_edge) {
                 a.dbg_edge[bc * 2] = static_cast<float>(px);
@@ -323,7 +361,8 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(TreeDesc tree, Ta
         f.init();
         f.k32 = k32; f.nAt = rc.nAt; f.nAd = rc.nAd; f.rho = uniform_f32(rc.rho);
         pair.replay(f);
-        const double W2 = uniform_f64(scale * block_sum<kTaskBlock>(static_cast<double>(f.acc0) + static_cast<double>(f.acc1), scratch));
+        const double lane_mass = static_cast<double>(f.acc0) + static_cast<double>(f.acc1);
+        const double W2 = uniform_f64(scale * block_sum<kTaskBlock>(lane_mass, scratch));
         if (W2 > 0.0) {
             if (METHOD == MPV_METHOD_TRAVERSAL) {
                 const double S = (wa / W) * W2;
@@ -337,22 +376,37 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(TreeDesc tree, Ta
         }
     }
 
+    __shared__ int sh_tree_done;
     if (threadIdx.x == 0) {
-        ws.At[bn] = rt.A;
-        ws.Ad[bn] = rd.A;
-        ws.mt[bn] = rt.m;
+        st_shared_f64(&ws.At[bn], rt.A);
+        st_shared_f64(&ws.Ad[bn], rd.A);
+        st_shared_f64(&ws.cfin[bn], c);
+        if (METHOD == MPV_METHOD_TRAVERSAL && n != 0) st_shared_f64(&ws.atest[bn], wa);
+        ws.mt[bn] = rt.m;                             // read by later launches only
         ws.md[bn] = rd.m;
-        ws.cfin[bn] = c;
         ws.Wfin[bn] = W;
-        if (METHOD == MPV_METHOD_TRAVERSAL && n != 0) ws.atest[bn] = wa;
+        // Tasks of this tree still queued or running, once this one's children are counted and
+        // it is not: at 0 the tree is complete and its sampling task is queued.  The count is
+        // updated before the children are queued (none of them can finish before it is counted)
+        // and after every result above has been written through.
+        int npush = 0;
+        for (int j = 0; j < k; ++j) npush += ch_push[j];
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        const int left = atomicAdd(&ws.pending[b], npush - 1) + npush - 1;
+        sh_tree_done = (left == 0) ? 1 : 0;
     }
-    // append the children that still matter (Traversal), then report this task finished
-    __syncthreads();                                  // ch_push written by lane 0 above
+    __syncthreads();
+    // append the children that still matter (Traversal) or the sampling task, then report this task finished
     if (METHOD == MPV_METHOD_TRAVERSAL && threadIdx.x < k && ch_push[threadIdx.x]) {
         const int cn = tree.child_list[tree.child_off[n] + threadIdx.x];
         const int slot = atomicAdd(&ws.qctl[1], 1);
         if (slot < list.capacity)
             __hip_atomic_store(&ws.queue[slot], b * a.N + cn, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    if (threadIdx.x == 0 && sh_tree_done) {
+        const int slot = atomicAdd(&ws.qctl[1], 1);
+        if (slot < list.capacity)
+            __hip_atomic_store(&ws.queue[slot], a.B * a.N + b, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     __syncthreads();                                  // every append has returned its slot
     if (threadIdx.x == 0) atomicAdd(&ws.qctl[2], 1);
@@ -376,7 +430,7 @@ __device__ __forceinline__ int walk_wave(const TreeDesc& tree, const Workspace& 
     const size_t base = static_cast<size_t>(b) * a.N;
     bool acc = false, near = false;
     if (lane > 0 && lane < a.N) {
-        const double at = ws.atest[base + lane];
+        const double at = ld_shared_f64(&ws.atest[base + lane]);
         const double uu = static_cast<double>(a.uniforms[base + lane]);
         acc = uu < at;
         near = fabs(at - uu) < 1e-6;
@@ -426,12 +480,13 @@ __device__ __forceinline__ int walk_wave(const TreeDesc& tree, const Workspace& 
 
 // ------------------------------------------------------------------ bonus sample
 
-// r_v = (p_v - c q_v)_+ up to the common factor 2^-At_lo, for the VEC elements a
-// lane owns in tile `tile` (zero beyond V).  Vector loads when the rows are
-// 16-byte aligned, element loads otherwise.
+// r_v = (p_v - c q_v)_+ up to the common factor 2^-At_lo, for the VEC elements a lane
+// owns in wave tile `tile` (elements [tile * 64 * VEC, (tile + 1) * 64 * VEC); zero beyond V).
+// A vector load when the rows are 16-byte aligned, element loads otherwise.
 template <class E>
 struct ResidualTile {
-    static constexpr int PER_LANE = kTile / kWave;    // 8
+    static constexpr int PER_LANE = E::VEC;
+    static constexpr int TILE = kWave * E::VEC;
     const typename E::T* zt;
     const typename E::T* zd;
     int V;
@@ -439,30 +494,18 @@ struct ResidualTile {
     float k32, nAt, nAd, rho;
 
     __device__ __forceinline__ void load(int tile, int lane, float (&r)[PER_LANE]) const {
-        const int e0 = tile * kTile + lane * PER_LANE;
-        float t[PER_LANE], d[PER_LANE];
+        const int e0 = tile * TILE + lane * PER_LANE;
         if (aligned && e0 + PER_LANE <= V) {
+            float t[PER_LANE], d[PER_LANE];
+            E::load_vec(zt + e0, t);
+            if (use_d) E::load_vec(zd + e0, d);
 #pragma unroll
-            for (int q = 0; q < PER_LANE / E::VEC; ++q) {
-                float tv[E::VEC], dv[E::VEC];
-                E::load_vec(zt + e0 + q * E::VEC, tv);
-                if (use_d) E::load_vec(zd + e0 + q * E::VEC, dv);
-#pragma unroll
-                for (int i = 0; i < E::VEC; ++i) { t[q * E::VEC + i] = tv[i]; d[q * E::VEC + i] = use_d ? dv[i] : 0.f; }
-            }
-#pragma unroll
-            for (int i = 0; i < PER_LANE; ++i) r[i] = term(t[i], d[i]);
+            for (int i = 0; i < PER_LANE; ++i) r[i] = term(t[i], use_d ? d[i] : 0.f);
         } else {
 #pragma unroll
             for (int i = 0; i < PER_LANE; ++i) {
                 const int e = e0 + i;
-                if (e < V) {
-                    t[i] = E::load_one(zt + e);
-                    d[i] = use_d ? E::load_one(zd + e) : 0.f;
-                    r[i] = term(t[i], d[i]);
-                } else {
-                    r[i] = 0.f;
-                }
+                r[i] = (e < V) ? term(E::load_one(zt + e), use_d ? E::load_one(zd + e) : 0.f) : 0.f;
             }
         }
     }
@@ -474,18 +517,20 @@ struct ResidualTile {
     }
 };
 
+
+// tile_sum: kMaxTiles floats of LDS; scratch: 2 doubles per wave.  Everything it reads from
+// the workspace was written by node tasks of this launch (see st_shared_f64).
 template <class E, int METHOD>
-__global__ __launch_bounds__(kSampleBlock) void sample_kernel(TreeDesc tree, Workspace ws, Args a) {
+__device__ void sample_task(const TreeDesc& tree, const Workspace& ws, const Args& a, int b,
+                            float* tile_sum, double* scratch) {
     using T = typename E::T;
     constexpr int NW = kSampleBlock / kWave;
-    constexpr int PER_LANE = kTile / kWave;
-    __shared__ double tile_sum[kMaxTiles];
-    __shared__ double scratch[2 * NW];
+    constexpr int PER_LANE = ResidualTile<E>::PER_LANE;
+    constexpr int TILE = ResidualTile<E>::TILE;
     __shared__ int sh_tile;
     __shared__ double sh_before, sh_total, sh_target;
 
     __shared__ int sh_stop;
-    const int b = blockIdx.x;
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
     if (wave == 0) {
         const int stop = walk_wave<METHOD>(tree, ws, a, b);
@@ -497,22 +542,23 @@ __global__ __launch_bounds__(kSampleBlock) void sample_kernel(TreeDesc tree, Wor
     const T* zt = static_cast<const T*>(a.zt) + bn * a.V;
     const T* zd = static_cast<const T*>(a.zd) + bn * a.V;
     const int V = a.V;
+    const int ntiles = (V + TILE - 1) / TILE;
 
     double At, Ad = 0.0, c = 0.0;
     if (tree.nchild[n] == 0) {
         // a leaf: its target row has not been touched yet; the bonus is drawn from p itself
         RowStatsF<E> f;
         f.t.init(); f.k32 = a.k32;
-        sweep_row<E, kSampleBlock, kTaskUnroll>(zt, V, f);
+        sweep_row<E, kSampleBlock, 4 * kTaskUnroll>(zt, V, f);     // alone on its compute unit: many loads in flight
         OnlineLse none; none.init();
         RowStat rt, rd;
         finish_stats2<kSampleBlock>(f.t, none, rt, rd, scratch);
         At = rt.A;
         if (threadIdx.x == 0) { ws.At[bn] = rt.A; ws.mt[bn] = rt.m; }
     } else {
-        At = ws.At[bn];
-        Ad = ws.Ad[bn];
-        c = ws.cfin[bn];
+        At = ld_shared_f64(&ws.At[bn]);
+        Ad = ld_shared_f64(&ws.Ad[bn]);
+        c = ld_shared_f64(&ws.cfin[bn]);
     }
 
     ResidualTile<E> rt_;
@@ -527,16 +573,49 @@ __global__ __launch_bounds__(kSampleBlock) void sample_kernel(TreeDesc tree, Wor
         rt_.nAt = -static_cast<float>(At); rt_.nAd = 0.f; rt_.rho = 0.f;
     }
 
-    // ---- pass 1: mass of every 512-element tile, in vocabulary order
-    const int ntiles = (V + kTile - 1) / kTile;
-    for (int t = wave; t < ntiles; t += NW) {
-        float r[PER_LANE];
-        rt_.load(t, lane, r);
-        float ls = 0.f;
+    // ---- pass 1: mass of every wave tile, in vocabulary order
+    {
+        // Whole, aligned tiles are taken U at a time per wave with all their loads issued
+        // before the first use: one workgroup per compute unit hides memory latency only by
+        // the loads each wave keeps in flight.
+        int t_next = wave;
+        constexpr int U = 8;
+        const int whole = rt_.aligned ? V / TILE : 0;
+        for (; t_next + (U - 1) * NW < whole; t_next += U * NW) {
+            uint4 qt[U], qd[U];
 #pragma unroll
-        for (int i = 0; i < PER_LANE; ++i) ls += r[i];
-        const double s = wave_sum(static_cast<double>(ls));
-        if (lane == 0) tile_sum[t] = s;
+            for (int j = 0; j < U; ++j) {
+                const int e0 = (t_next + j * NW) * TILE + lane * PER_LANE;
+                qt[j] = load_raw(zt + e0);
+                if (rt_.use_d) qd[j] = load_raw(zd + e0);
+            }
+            float s[U];
+#pragma unroll
+            for (int j = 0; j < U; ++j) {
+                float tv[PER_LANE], dv[PER_LANE];
+                E::unpack(qt[j], tv);
+                if (rt_.use_d) E::unpack(qd[j], dv);
+                float ls = 0.f;                       // same order of additions as pass 2
+#pragma unroll
+                for (int i = 0; i < PER_LANE; ++i) ls += rt_.term(tv[i], rt_.use_d ? dv[i] : 0.f);
+                s[j] = ls;
+            }
+#pragma unroll
+            for (int j = 0; j < U; ++j) s[j] = wave_sum_f32(s[j]);
+            if (lane == 0) {
+#pragma unroll
+                for (int j = 0; j < U; ++j) tile_sum[t_next + j * NW] = s[j];
+            }
+        }
+        for (int t = t_next; t < ntiles; t += NW) {
+            float r[PER_LANE];
+            rt_.load(t, lane, r);
+            float ls = 0.f;
+#pragma unroll
+            for (int i = 0; i < PER_LANE; ++i) ls += r[i];
+            const float w = wave_sum_f32(ls);
+            if (lane == 0) tile_sum[t] = w;
+        }
     }
     __syncthreads();
 
@@ -606,7 +685,7 @@ __global__ __launch_bounds__(kSampleBlock) void sample_kernel(TreeDesc tree, Wor
                 acc += ri;
             }
             if (found < 0) { found = last_mass; lo = rem; hi = rem; }
-            int tok = t * kTile + lane * PER_LANE + found;
+            int tok = t * TILE + lane * PER_LANE + found;
             if (tok >= V) tok = V - 1;
             a.bonus[b] = tok;
             const double gap = fmin(fabs(rem - lo), fabs(hi - rem));
@@ -623,7 +702,7 @@ __global__ __launch_bounds__(kSampleBlock) void sample_kernel(TreeDesc tree, Wor
             rt_.load(t, lane, r);
 #pragma unroll
             for (int i = 0; i < PER_LANE; ++i) {
-                const int e = t * kTile + lane * PER_LANE + i;
+                const int e = t * TILE + lane * PER_LANE + i;
                 if (e < V) out[e] = static_cast<float>(static_cast<double>(r[i]) * inv);
             }
         }
@@ -809,7 +888,8 @@ static size_t carve(const mpv_problem* p, void* base, Workspace* ws) {
     float* md = static_cast<float*>(take(bn * 4));
     int32_t* qu = static_cast<int32_t*>(take(bn * 4));
     int32_t* qc = static_cast<int32_t*>(take(4 * 4));
-    if (ws) { ws->At = At; ws->Ad = Ad; ws->cfin = cf; ws->Wfin = Wf; ws->a0 = a0; ws->atest = at; ws->mt = mt; ws->md = md; ws->queue = qu; ws->qctl = qc; }
+    int32_t* pe = static_cast<int32_t*>(take(static_cast<size_t>(p->B) * 4));
+    if (ws) { ws->At = At; ws->Ad = Ad; ws->cfin = cf; ws->Wfin = Wf; ws->a0 = a0; ws->atest = at; ws->mt = mt; ws->md = md; ws->queue = qu; ws->qctl = qc; ws->pending = pe; }
     return off < 256 ? 256 : off;
 }
 
@@ -840,7 +920,7 @@ static int launch_all(const mpv_problem* p, const Plan& plan, const Workspace& w
         for (int n = 0; n < p->N; ++n)
             if (tree.nchild[n] == kk && (p->method == MPV_METHOD_SPECINFER || n == 0))
                 list.nodes[list.count++] = n;
-    list.capacity = p->B * plan.n_internal;
+    list.capacity = p->B * plan.n_internal + p->B;      // node tasks + one sampling task per tree
     const int tasks = list.capacity;
     {
         const int threads = 256;
@@ -860,13 +940,6 @@ static int launch_all(const mpv_problem* p, const Plan& plan, const Workspace& w
             if (full) hipLaunchKernelGGL((node_task_kernel<E, MPV_METHOD_TRAVERSAL, true>), grid, block, 0, s, tree, list, ws, a);
             else hipLaunchKernelGGL((node_task_kernel<E, MPV_METHOD_TRAVERSAL, false>), grid, block, 0, s, tree, list, ws, a);
         }
-    }
-    {
-        ScopedLaunch t(MPV_KERNEL_SAMPLE, s);
-        if (p->method == MPV_METHOD_SPECINFER)
-            hipLaunchKernelGGL((sample_kernel<E, MPV_METHOD_SPECINFER>), dim3(p->B), dim3(kSampleBlock), 0, s, tree, ws, a);
-        else
-            hipLaunchKernelGGL((sample_kernel<E, MPV_METHOD_TRAVERSAL>), dim3(p->B), dim3(kSampleBlock), 0, s, tree, ws, a);
     }
     if (a.dbg_stats) {
         ScopedLaunch t(MPV_KERNEL_DEBUG_STATS, s);
