@@ -118,6 +118,8 @@ typedef struct mpv_buffers {
                                             parent's result (results of that tree are invalid) */
 #define MPV_COUNTER_NODE_TASKS_RUN   5  /* (tree, internal node) pairs whose logit rows were
                                           read; the others were proved irrelevant first      */
+#define MPV_COUNTER_NODE_TASKS_CANCELLED 6 /* node tasks that had been queued ahead of need and
+                                          were dropped unread once their tree was settled     */
 #define MPV_COUNTER_COUNT           8  /* length of the counters array (rest reserved)       */
 
 /* ABI version of the loaded library (MPV_ABI_VERSION it was built with). */

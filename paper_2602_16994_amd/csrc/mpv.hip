@@ -41,16 +41,27 @@ struct TreeDesc {
     int32_t child_list[MPV_MAX_NODES];   // children of node 0, of node 1, ... ascending
     int32_t depth[MPV_MAX_NODES];
     int32_t postorder[MPV_MAX_NODES];    // depth-first, children (in list order) before their parent; root last
+    int32_t rank[MPV_MAX_NODES];         // position of the node in postorder
+    int32_t sub_lo[MPV_MAX_NODES];       // the node's subtree is postorder[sub_lo[n] .. rank[n]]
+    int32_t cls[MPV_MAX_NODES];          // priority class of the node's task (see QueuePlan)
 };
 
-// The node tasks a call starts with: B tasks per listed node, node-major (the same node of
-// consecutive trees next to each other).  SpecInfer lists every internal node (its tasks are
-// independent).  Traversal lists the root only: a finished task appends those of its
-// children that still matter.
-struct TaskList {
-    int32_t count;                       // listed nodes
-    int32_t capacity;                    // queue entries available (B * internal nodes + B sampling tasks)
-    int32_t nodes[MPV_MAX_NODES];
+constexpr int kMaxClasses = MPV_MAX_CHILDREN + 1;
+
+// The task queue is one first-in-first-out queue per priority class; a free workgroup is
+// given the oldest task of the lowest class that has one.  Class 0: the nodes from the root down to
+// the first node that branches, and every sampling task.  Class 1 + j: the subtree of that
+// node's j-th child.  A rule examines the subtrees in this order and stops at the first node
+// it accepts, so work on an earlier subtree is more likely to be needed than work on a later
+// one; later classes are run ahead, speculatively, by workgroups that would otherwise idle.
+struct QueuePlan {
+    int32_t nclass;
+    int32_t off[kMaxClasses + 1];        // class c owns queue[off[c] .. off[c+1])
+    int32_t init_tail[kMaxClasses];      // entries of class c written by init_kernel
+    int32_t init_slot[MPV_MAX_NODES];    // -1, or the node's index among the prequeued nodes of its class
+    int32_t init_total;                  // prequeued tasks
+    int32_t root_is_leaf;                // no node task at all: the sampling tasks are prequeued
+    int32_t workers;                     // workgroups of the launch; the first prequeued tasks of class 0 go straight to them
 };
 
 // Per-(tree,node) scalars kept in the workspace, all double, each [B*N].
@@ -63,9 +74,19 @@ struct Workspace {
     double* atest;   // probability the node is tested with
     float* mt;       // row maxima (for the debug statistics)
     float* md;
-    int32_t* queue;      // task queue (first in, first out), entry = tree * N + node, -1 = not written yet
-    int32_t* qctl;       // [0] head: next ticket, [1] tail: tasks appended, [2] completed: tasks finished
-    int32_t* pending;    // [B] node tasks of the tree queued or running; 0: the tree can be sampled
+    int32_t* queue;      // entry = tree * N + node (node task) or B * N + tree (sampling task), -1 = not written yet
+    // [0] appended: tasks ever queued or started directly, [1] completed: tasks finished or cancelled,
+    // [2] exit: set when nothing is left, [3] lock: held by the workgroup that is dispatching,
+    // [4 + c] tail of class c: entries appended, [4 + kMaxClasses + c] head of class c: entries handed out
+    int32_t* qctl;
+    int32_t* mailbox;    // [workgroups] kMailboxWaiting, or the task handed to that workgroup
+    // Per tree, one bit per node at the node's position in postorder: `known` = the outcome of
+    // the node's test is settled, `acc` = it is "accepted" (valid once known).  `decided` = the
+    // sampling task has been queued (and, when only what the rule needs is computed, the
+    // tree's remaining node tasks are cancelled).
+    unsigned long long* known;
+    unsigned long long* acc;
+    int32_t* decided;
 };
 
 struct Args {
@@ -85,7 +106,7 @@ struct Args {
     int32_t B, N, V, max_depth;
     float k32;       // float(log2(e)/T)
     float invT;
-    int32_t prune;   // skip node tasks whose node has weight 0 (off when per-edge debug output is wanted)
+    int32_t lazy;    // compute only what the rule needs (off when per-node debug output is wanted: then every node task runs)
     int32_t stagger_ticks;   // start-up spread of the persistent workgroups, in 10 ns ticks per step (8 steps)
 };
 
@@ -103,26 +124,52 @@ constexpr unsigned long long kNotReady = ~0ull;
 constexpr int kSampleBlock = kTaskBlock;     // sampling tasks run on the node tasks' workgroups
 // wave tiles of the bonus sampler: 64 16-byte vectors; float rows have the smallest tiles
 constexpr int kMaxTiles = MPV_MAX_VOCAB / (kWave * 4);
+// task hand-over between the dispatcher and the workers (see "task queue")
+constexpr int kMailboxWaiting = -1;
+constexpr int kTaskExit = -1;                         // what a worker's wait returns when all is done
+constexpr int kWorkerSlots = 8;                       // mailboxes per dispatcher lane
+constexpr int kMaxWorkgroups = kWave * kWorkerSlots;
 
 // ------------------------------------------------------------------ init
 
-__global__ void init_kernel(TaskList list, Workspace ws, Args a) {
+__global__ void init_kernel(QueuePlan q, TreeDesc tree, Workspace ws, Args a) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < MPV_COUNTER_COUNT) a.counters[i] = 0u;
-    // a tree without internal nodes has nothing but its sampling task
-    const int prefilled = (list.count > 0 ? list.count : 1) * a.B;
-    if (i == 0) { ws.qctl[0] = 0; ws.qctl[1] = prefilled; ws.qctl[2] = 0; }
-    if (i < a.B) ws.pending[i] = list.count;
+    if (i == 0) { ws.qctl[0] = q.init_total; ws.qctl[1] = 0; ws.qctl[2] = 0; ws.qctl[3] = 0; }
+    if (i < kMaxClasses) {
+        ws.qctl[4 + i] = (i < q.nclass) ? q.init_tail[i] : 0;
+        ws.qctl[4 + kMaxClasses + i] = (i == 0) ? min(q.workers, q.init_tail[0]) : 0;
+    }
+    // every worker starts out waiting; the first class-0 entries are handed over below
+    if (i < kMaxWorkgroups && i >= q.init_tail[0]) ws.mailbox[i] = kMailboxWaiting;
+    if (i < a.B) {
+        // the root is never tested: it counts as accepted from the start
+        ws.known[i] = 1ull << (a.N - 1);
+        ws.acc[i] = 1ull << (a.N - 1);
+        ws.decided[i] = 0;
+    }
     if (i < a.B * a.N) {
         reinterpret_cast<unsigned long long*>(ws.a0)[i] = kNotReady;
-        // a node no task ever reaches (Traversal: weight 0) is tested with probability 0
+        // a node no task ever reaches is tested with probability 0
         ws.atest[i] = (i % a.N == 0) ? 1.0 : 0.0;
         ws.cfin[i] = 0.0;
         ws.Wfin[i] = 1.0;
-        if (i < list.capacity) {
-            int entry = -1;
-            if (i < prefilled) entry = list.count > 0 ? (i % a.B) * a.N + list.nodes[i / a.B] : a.B * a.N + i;
-            ws.queue[i] = entry;
+        // queue: the prequeued node tasks, node-major inside their class (the same node of
+        // consecutive trees next to each other); everything else "not written yet"
+        if (i < q.off[q.nclass]) {
+            int c = 0;
+            while (c + 1 < q.nclass && i >= q.off[c + 1]) ++c;
+            if (i - q.off[c] >= q.init_tail[c]) ws.queue[i] = -1;
+        }
+        const int n = i / a.B, b = i % a.B;
+        if (q.init_slot[n] >= 0) {
+            const int slot = q.init_slot[n] * a.B + b;
+            ws.queue[q.off[tree.cls[n]] + slot] = b * a.N + n;
+            if (tree.cls[n] == 0 && slot < kMaxWorkgroups) ws.mailbox[slot] = b * a.N + n;
+        }
+        if (q.root_is_leaf && i < a.B) {
+            ws.queue[q.off[0] + i] = a.B * a.N + i;
+            if (i < kMaxWorkgroups) ws.mailbox[i] = a.B * a.N + i;
         }
     }
     if (i < a.B && a.dbg_edge) {
@@ -133,18 +180,176 @@ __global__ void init_kernel(TaskList list, Workspace ws, Args a) {
 
 // ------------------------------------------------------------------ task queue
 //
-// node_task_kernel is launched with about one workgroup per compute unit; each workgroup
-// keeps taking tasks until none are left.  One first-in-first-out queue: a task is appended
-// only when everything it needs has been published, so every queued task can run at once.
-// A workgroup draws a ticket h (atomic add on head) and waits until entry h is written, or
-// until nothing is left: completed == tail, read between two equal reads of tail, means that
-// at that moment no task was running, so nothing can be appended any more.  A task's appends
-// (returning atomic adds on tail) have been performed before its completed++ is issued.
-// Any resident workgroup can run any task, so nothing depends on which or how many
-// workgroups are resident.  Waits are bounded.
+// node_task_kernel is launched with about one workgroup per compute unit; each runs tasks
+// until told to exit.  A task is appended only when everything it needs has been published,
+// so every queued task can run at once, on any workgroup: nothing depends on which or how
+// many workgroups are resident.
+//   append:   appended++, then slot = tail++ of the class, then the entry is written.
+//   request:  mailbox[w] = waiting.  A workgroup asks before the last sweep of its current
+//             task when it can, so the answer is usually there when it is done.
+//   dispatch: a workgroup that has nothing to do takes the dispatcher lock if it is free and,
+//             with its first wave, hands queued tasks to waiting workgroups (itself included)
+//             in priority order (class, then age), until it has a task of its own; then it
+//             releases the lock.  Those that find the lock taken poll their mailbox.  If every
+//             workgroup is busy nobody dispatches, and nobody needs to.  Node tasks of trees
+//             whose outcome is settled are dropped here when only what is needed is computed.
+//   end:      nothing queued and completed == appended, with appended read before and after
+//             completed and unchanged: no task is queued, handed out or running, so nothing
+//             can be appended any more; the dispatching workgroup sets the exit flag.  A
+//             task's appends are performed before its completed++.
+// A workgroup may also run a task it has produced itself straight away (counted in appended,
+// never queued).  Every wait is bounded.
 
 __device__ __forceinline__ int ld_relaxed(const int32_t* p) {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ unsigned long long ld_relaxed(const unsigned long long* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void st_relaxed(int32_t* p, int v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// all loads, stores and atomics issued so far by this lane have been performed
+__device__ __forceinline__ void wait_memory() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+// One lane: ask for a task.
+__device__ __forceinline__ void request_task(const Workspace& ws) {
+    st_relaxed(&ws.mailbox[blockIdx.x], kMailboxWaiting);
+}
+
+// Append one task to class c (one lane).  The caller's earlier stores have been waited for.
+__device__ __forceinline__ void append_task(const QueuePlan& q, const Workspace& ws, int c, int entry) {
+    (void)atomicAdd(&ws.qctl[0], 1);
+    wait_memory();                                    // counted before it can be handed out (and finished)
+    const int slot = atomicAdd(&ws.qctl[4 + c], 1);
+    if (slot < q.off[c + 1] - q.off[c]) st_relaxed(&ws.queue[q.off[c] + slot], entry);
+}
+
+// One round of dispatching, by a whole wave that holds the lock.  Lane c keeps the head of
+// class c in `head`; lane l looks after the workgroups l, l + 64, ...  Returns true when
+// everything is finished (the exit flag has been set).
+__device__ bool dispatch_round(const QueuePlan& q, const Workspace& ws, const Args& a, bool drop_settled,
+                               int& head, long long t_begin) {
+    __shared__ int sh_head[kMaxClasses], sh_before[kMaxClasses + 1];
+    const int lane = threadIdx.x;
+    const int workers = static_cast<int>(gridDim.x);
+    // who is waiting, what is queued
+    unsigned waiting = 0u;
+#pragma unroll
+    for (int sl = 0; sl < kWorkerSlots; ++sl) {
+        const int w = lane + kWave * sl;
+        if (w < workers && ld_relaxed(&ws.mailbox[w]) == kMailboxWaiting) waiting |= 1u << sl;
+    }
+    const int tail = (lane < q.nclass) ? ld_relaxed(&ws.qctl[4 + lane]) : 0;
+    const int avail = (lane < q.nclass) ? tail - head : 0;
+    const int my_waiting = __popc(waiting);
+    const int waiting_incl = wave_inclusive_scan_i32(my_waiting);
+    const int avail_incl = wave_inclusive_scan_i32(avail);
+    const int total_waiting = __shfl(waiting_incl, kWave - 1, kWave);
+    const int total_avail = __shfl(avail_incl, kWave - 1, kWave);
+    if (total_avail == 0) {
+        int done = 0;
+        if (lane == 0) {
+            const int a1 = ld_relaxed(&ws.qctl[0]);
+            wait_memory();
+            const int co = ld_relaxed(&ws.qctl[1]);
+            wait_memory();
+            const int a2 = ld_relaxed(&ws.qctl[0]);
+            done = (co == a1 && a1 == a2) ? 1 : 0;
+            // a queue entry that never arrives, a task that never ends: give up after 2 s (must never happen)
+            if (!done && wall_clock64() - t_begin > 200000000ll) {
+                atomicAdd(&a.counters[MPV_COUNTER_DEPENDENCY_TIMEOUT], 1u);
+                done = 1;
+            }
+            if (done) {
+                st_relaxed(&ws.qctl[2], 1);
+                wait_memory();
+            }
+        }
+        if (__builtin_amdgcn_readfirstlane(done)) return true;
+    }
+    if (total_avail == 0 || total_waiting == 0) {
+        __builtin_amdgcn_s_sleep(8);
+        return false;
+    }
+    // waiting workgroup number r (in lane, slot order) gets queued task number r (in class, age order)
+    if (lane < q.nclass) { sh_head[lane] = head; sh_before[lane + 1] = avail_incl; }
+    if (lane == 0) sh_before[0] = 0;
+    __builtin_amdgcn_wave_barrier();
+    int r = waiting_incl - my_waiting;
+    for (int sl = 0; sl < kWorkerSlots; ++sl) {
+        if (!((waiting >> sl) & 1u)) continue;
+        const int mine = r++;
+        if (mine >= total_avail) break;
+        int c = 0;
+        while (mine >= sh_before[c + 1]) ++c;         // ends: mine < total_avail = sh_before[nclass]
+        const int32_t* slot = &ws.queue[q.off[c] + sh_head[c] + (mine - sh_before[c])];
+        int entry = -1;
+        for (int spin = 0; spin < kMaxSpins; ++spin) {          // the entry follows its tail count closely
+            entry = ld_relaxed(slot);
+            if (entry >= 0) break;
+            __builtin_amdgcn_s_sleep(2);
+        }
+        if (entry < 0) {                              // must never happen: counted as finished, nobody runs it
+            atomicAdd(&a.counters[MPV_COUNTER_DEPENDENCY_TIMEOUT], 1u);
+            atomicAdd(&ws.qctl[1], 1);
+        } else if (drop_settled && entry < a.B * a.N && ld_relaxed(&ws.decided[entry / a.N]) != 0) {
+            atomicAdd(&a.counters[MPV_COUNTER_NODE_TASKS_CANCELLED], 1u);
+            atomicAdd(&ws.qctl[1], 1);
+        } else {
+            st_relaxed(&ws.mailbox[lane + kWave * sl], entry);
+        }
+    }
+    if (lane < q.nclass) {
+        const int before = avail_incl - avail;
+        head += max(0, min(avail, total_waiting - before));
+    }
+    __builtin_amdgcn_wave_barrier();                  // sh_head / sh_before are rewritten next time round
+    wait_memory();
+    return false;
+}
+
+// The next task of this workgroup, or kTaskExit; called by every lane of the first wave, returns
+// the same value in each.  The workgroup has asked (its mailbox says "waiting" or already holds
+// the answer).  `previous` is the task it took from the mailbox last: until the request has
+// reached memory the mailbox may still show it (no entry is ever handed out twice, so the
+// value is unambiguous).
+__device__ int acquire_task(const QueuePlan& q, const Workspace& ws, const Args& a, int previous, bool drop_settled) {
+    const int lane = threadIdx.x;
+    int32_t* const box = &ws.mailbox[blockIdx.x];
+    for (int spin = 0; spin < kMaxSpins; ++spin) {
+        int t = 0, ex = 0, lk = 1;
+        if (lane == 0) {
+            t = ld_relaxed(box);
+            ex = ld_relaxed(&ws.qctl[2]);
+            lk = ld_relaxed(&ws.qctl[3]);
+        }
+        t = __builtin_amdgcn_readfirstlane(t);
+        if (t != kMailboxWaiting && t != previous) return t;
+        if (__builtin_amdgcn_readfirstlane(ex)) return kTaskExit;
+        int got = 0;
+        if (lane == 0 && lk == 0) got = (atomicCAS(&ws.qctl[3], 0, 1) == 0) ? 1 : 0;
+        if (__builtin_amdgcn_readfirstlane(got)) {
+            // the previous holder wrote the heads before it released the lock
+            int head = (lane < q.nclass) ? ld_relaxed(&ws.qctl[4 + kMaxClasses + lane]) : 0;
+            const long long t_begin = wall_clock64();
+            int result = kTaskExit;
+            for (;;) {
+                const bool finished = dispatch_round(q, ws, a, drop_settled, head, t_begin);
+                if (finished) break;
+                int mine = (lane == 0) ? ld_relaxed(box) : 0;
+                mine = __builtin_amdgcn_readfirstlane(mine);
+                if (mine != kMailboxWaiting && mine != previous) { result = mine; break; }
+            }
+            if (lane < q.nclass) st_relaxed(&ws.qctl[4 + kMaxClasses + lane], head);
+            wait_memory();
+            if (lane == 0) st_relaxed(&ws.qctl[3], 0);
+            return result;
+        }
+        __builtin_amdgcn_s_sleep(8);
+    }
+    if (lane == 0) atomicAdd(&a.counters[MPV_COUNTER_DEPENDENCY_TIMEOUT], 1u);     // must never happen
+    return kTaskExit;
 }
 
 // Results one task leaves for another task of the same launch (which may run on another
@@ -195,7 +400,7 @@ __device__ void sample_task(const TreeDesc& tree, const Workspace& ws, const Arg
                             float* tile_sum, double* scratch);
 
 template <class E, int METHOD, bool FULL>
-__global__ __launch_bounds__(kTaskBlock) void node_task_kernel(TreeDesc tree, TaskList list,
+__global__ __launch_bounds__(kTaskBlock) void node_task_kernel(TreeDesc tree, QueuePlan q,
                                                               Workspace ws, Args a) {
     using T = typename E::T;
     __shared__ double scratch[2 * (kTaskBlock / kWave)];
@@ -220,17 +425,40 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(TreeDesc tree, Ta
         const long long t0 = wall_clock64();
         while (wall_clock64() - t0 < wait) __builtin_amdgcn_s_sleep(16);    // the clock always advances: bounded
     }
+    const bool drop_settled = METHOD == MPV_METHOD_TRAVERSAL && a.lazy != 0;
+    int previous_task = -3;                           // last task taken from the mailbox: none yet
+    bool asked = true;                                // the launch starts with every mailbox waiting or filled
+    int own_task = -1;                                // a task this workgroup produced for itself
     for (;;) {
     __syncthreads();                                  // the previous task is done with LDS
-    if (threadIdx.x == 0) sh_task = next_task(ws, a);
-    __syncthreads();
-    const int task = sh_task;
-    if (task < 0) break;
+    int task;
+    if (own_task >= 0) {
+        task = own_task;
+        own_task = -1;
+    } else {
+        if (threadIdx.x < kWave) {
+            if (!asked) {
+                if (threadIdx.x == 0) request_task(ws);
+                wait_memory();
+            }
+            const int t = acquire_task(q, ws, a, previous_task, drop_settled);
+            if (threadIdx.x == 0) sh_task = t;
+        }
+        __syncthreads();
+        task = sh_task;
+        previous_task = task;
+        asked = false;
+        if (task == kTaskExit) break;
+    }
     if (task >= a.B * a.N) {
-        // the tree's node tasks are all done: walk and bonus token
+        // the tree's outcome is settled: walk and bonus token
+        if (!asked) {
+            if (threadIdx.x == 0) request_task(ws);
+            asked = true;
+        }
         float* tile_mass = FULL ? reinterpret_cast<float*>(lds_t) : own_tile_mass;
         sample_task<E, METHOD>(tree, ws, a, task - a.B * a.N, tile_mass, scratch);
-        if (threadIdx.x == 0) atomicAdd(&ws.qctl[2], 1);
+        if (threadIdx.x == 0) atomicAdd(&ws.qctl[1], 1);
         continue;
     }
     const int b = task / a.N;
@@ -250,10 +478,17 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(TreeDesc tree, Ta
     __shared__ int ch_push[MPV_MAX_CHILDREN];
     if (threadIdx.x < MPV_MAX_CHILDREN) ch_push[threadIdx.x] = 0;
     __shared__ float ch_zt[MPV_MAX_CHILDREN], ch_zd[MPV_MAX_CHILDREN];
+    __shared__ float ch_u[MPV_MAX_CHILDREN];
     __shared__ double sh_a0;
+    __shared__ float sh_un;
     int pf_x = -1;
-    if (threadIdx.x < k)
-        pf_x = a.tokens[static_cast<size_t>(b) * a.N + tree.child_list[tree.child_off[n] + threadIdx.x]];
+    float pf_u = 2.f;
+    if (threadIdx.x < k) {
+        const size_t bc = static_cast<size_t>(b) * a.N + tree.child_list[tree.child_off[n] + threadIdx.x];
+        pf_x = a.tokens[bc];
+        pf_u = a.uniforms[bc];
+    }
+    if (threadIdx.x == kWave) pf_u = a.uniforms[bn];        // the node's own uniform
 
     // ---- softmax statistics of both rows: the one read of the pair from memory
     RetainedPair<E, kTaskBlock, RV, LV, CH, FULL> pair;
@@ -271,7 +506,8 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(TreeDesc tree, Ta
         PairStatsRawF<E> f;
         f.t.init(); f.d.init(); f.k32 = k32;
         pair.first_pass(f);
-        if (threadIdx.x < k) { ch_tok[threadIdx.x] = pf_x; ch_zt[threadIdx.x] = E::load_one(&pf_t); ch_zd[threadIdx.x] = E::load_one(&pf_d); }
+        if (threadIdx.x < k) { ch_tok[threadIdx.x] = pf_x; ch_u[threadIdx.x] = pf_u; ch_zt[threadIdx.x] = E::load_one(&pf_t); ch_zd[threadIdx.x] = E::load_one(&pf_d); }
+        if (threadIdx.x == kWave) sh_un = pf_u;
         if (threadIdx.x == 0) {
             // Traversal: the starting weight comes from the parent's task, which published it
             // before it queued this task; the two stores may still arrive in either order.
@@ -304,6 +540,10 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(TreeDesc tree, Ta
     double wa = (METHOD == MPV_METHOD_TRAVERSAL) ? uniform_f64(sh_a0) : 1.0;   // node weight a
     double c = 0.0, W = 1.0;
     const double kd = static_cast<double>(k32);
+    // test outcomes this task settles, one bit per node at its position in postorder
+    unsigned long long settled_bits = 0ull, accepted_bits = 0ull;
+    int next_node = -1;                               // SpecInfer, only what is needed: the accepted child
+    int own_child = -1;                               // Traversal: index of the first child whose task is to be run
     for (int j = 0; j < k; ++j) {
         const int cn = tree.child_list[tree.child_off[n] + j];
         const size_t bc = static_cast<size_t>(b) * a.N + cn;
@@ -328,6 +568,32 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(TreeDesc tree, Ta
             if (qx > 0.0) w_child = fmin(1.0, Px / qx);
             else w_child = (Px > 0.0) ? 1.0 : 0.0;
         }
+        // the same comparison the walk makes
+        const bool child_accepted = static_cast<double>(ch_u[j]) < w_child;
+        const unsigned long long child_bit = 1ull << tree.rank[cn];
+        if (METHOD == MPV_METHOD_SPECINFER) {
+            settled_bits |= child_bit;
+        } else if (tree.nchild[cn] == 0) {
+            settled_bits |= child_bit;
+            if (child_accepted) accepted_bits |= child_bit;
+        } else if (a.lazy && !(w_child > 0.0)) {
+            // A child of weight 0 can never be accepted, passes weight 0 to its whole subtree
+            // and never provides a bonus distribution: its task (and its subtree's) is not
+            // queued, its rows are never read; the whole subtree counts as rejected.
+            const int hi = tree.rank[cn], lo = tree.sub_lo[cn];
+            const unsigned long long upto = (hi >= 63) ? ~0ull : ((1ull << (hi + 1)) - 1ull);
+            settled_bits |= upto & ~((1ull << lo) - 1ull);
+        }
+        // Traversal: the child's own task is needed unless its weight is 0 (see above)
+        const bool run_child = METHOD == MPV_METHOD_TRAVERSAL && tree.nchild[cn] > 0 && (w_child > 0.0 || !a.lazy);
+        if (run_child && own_child < 0) own_child = j;
+        // One more sweep to go at most: time to ask for the next task, unless this workgroup
+        // already knows what it will run next (a child's task).
+        if (j == k - 1 && !asked && own_child < 0 &&
+            !(METHOD == MPV_METHOD_SPECINFER && a.lazy && child_accepted && tree.nchild[cn] > 0)) {
+            if (threadIdx.x == 0) request_task(ws);
+            asked = true;
+        }
         if (threadIdx.x == 0) {
             if (METHOD == MPV_METHOD_TRAVERSAL) {
                 if (tree.nchild[cn] == 0) {
@@ -336,11 +602,7 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(TreeDesc tree, Ta
                     __hip_atomic_store(reinterpret_cast<unsigned long long*>(&ws.a0[bc]),
                                        static_cast<unsigned long long>(__double_as_longlong(w_child)),
                                        __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    // A child of weight 0 can never be accepted, passes weight 0 to its whole subtree
-                    // and never provides a bonus distribution: its task (and its subtree's) is not
-                    // queued, its rows are never read.  (Queued all the same when per-edge debug
-                    // output is wanted.)
-                    ch_push[j] = (w_child > 0.0 || !a.prune) ? 1 : 0;
+                    ch_push[j] = run_child ? 1 : 0;
                 }
             } else {
                 st_shared_f64(&ws.atest[bc], w_child);
@@ -349,6 +611,13 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(TreeDesc tree, Ta
                 a.dbg_edge[bc * 2] = static_cast<float>(px);
                 a.dbg_edge[bc * 2 + 1] = static_cast<float>(qx);
             }
+        }
+
+        // SpecInfer moves into the first child it accepts: later children and this node's
+        // residual are not needed (the same in every lane: no lane is left behind)
+        if (METHOD == MPV_METHOD_SPECINFER && a.lazy && child_accepted) {
+            next_node = cn;
+            break;
         }
 
         // ---- the child (SpecInfer) or its whole subtree (Traversal) is rejected:
@@ -376,7 +645,7 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(TreeDesc tree, Ta
         }
     }
 
-    __shared__ int sh_tree_done;
+    __shared__ int sh_push_sample, sh_settled;
     if (threadIdx.x == 0) {
         st_shared_f64(&ws.At[bn], rt.A);
         st_shared_f64(&ws.Ad[bn], rd.A);
@@ -385,31 +654,70 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(TreeDesc tree, Ta
         ws.mt[bn] = rt.m;                             // read by later launches only
         ws.md[bn] = rd.m;
         ws.Wfin[bn] = W;
-        // Tasks of this tree still queued or running, once this one's children are counted and
-        // it is not: at 0 the tree is complete and its sampling task is queued.  The count is
-        // updated before the children are queued (none of them can finish before it is counted)
-        // and after every result above has been written through.
-        int npush = 0;
-        for (int j = 0; j < k; ++j) npush += ch_push[j];
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        const int left = atomicAdd(&ws.pending[b], npush - 1) + npush - 1;
-        sh_tree_done = (left == 0) ? 1 : 0;
+        bool push_sample, settled_tree = false;
+        if (METHOD == MPV_METHOD_SPECINFER && a.lazy) {
+            // the walk ends here (no child accepted) or in the accepted leaf
+            push_sample = next_node < 0 || tree.nchild[next_node] == 0;
+            wait_memory();                            // results written through before anything else is started
+        } else {
+            // Announce the outcomes settled here, then see whether the tree's outcome is settled:
+            //   only what is needed: in postorder, the first node that is not known to be
+            //     rejected is known (then it is the accepted one: the walk stops there);
+            //   everything: every node is known.
+            // `acc` is written before `known`, so the acc bits of known nodes are final.  Of
+            // the tasks that see a settled tree, the first to flip `decided` starts the sampling.
+            if (METHOD == MPV_METHOD_TRAVERSAL && n != 0) {
+                const unsigned long long own = 1ull << tree.rank[n];
+                settled_bits |= own;
+                if (static_cast<double>(sh_un) < wa) accepted_bits |= own;
+            }
+            wait_memory();                            // results written through before they are announced
+            if (accepted_bits) {
+                (void)atomicOr(&ws.acc[b], accepted_bits);
+                wait_memory();
+            }
+            const unsigned long long known = atomicOr(&ws.known[b], settled_bits) | settled_bits;
+            wait_memory();
+            const unsigned long long acc = ld_relaxed(&ws.acc[b]);
+            bool settled;
+            if (a.lazy) {
+                const unsigned long long open = ~(known & ~acc);          // not known to be rejected
+                const int first = __ffsll(static_cast<long long>(open)) - 1;   // the root's bit is always set
+                settled = ((known >> first) & 1ull) != 0ull;
+            } else {
+                const unsigned long long all = (a.N >= 64) ? ~0ull : ((1ull << a.N) - 1ull);
+                settled = known == all;
+            }
+            push_sample = settled && atomicCAS(&ws.decided[b], 0, 1) == 0;
+            // only what is needed: once a tree is settled (here or by another task) the rest of
+            // its node tasks are pointless
+            settled_tree = a.lazy && (settled || ld_relaxed(&ws.decided[b]) != 0);
+        }
+        sh_push_sample = push_sample ? 1 : 0;
+        sh_settled = settled_tree ? 1 : 0;
     }
     __syncthreads();
-    // append the children that still matter (Traversal) or the sampling task, then report this task finished
-    if (METHOD == MPV_METHOD_TRAVERSAL && threadIdx.x < k && ch_push[threadIdx.x]) {
+    // What follows from this task.  One task is run by this workgroup itself, next (no queue,
+    // no waiting): the sampling if this task settled the tree, else the first child that needs
+    // its own task (Traversal) or the accepted child (SpecInfer).  The other children are queued.
+    if (sh_push_sample) {
+        own_task = a.B * a.N + b;
+    } else if (METHOD == MPV_METHOD_TRAVERSAL) {
+        if (own_child >= 0 && !sh_settled) own_task = b * a.N + tree.child_list[tree.child_off[n] + own_child];
+    } else if (a.lazy && next_node >= 0 && tree.nchild[next_node] > 0) {
+        own_task = b * a.N + next_node;
+    }
+    if (threadIdx.x == 0 && own_task >= 0) {
+        (void)atomicAdd(&ws.qctl[0], 1);
+        wait_memory();
+    }
+    if (METHOD == MPV_METHOD_TRAVERSAL && !sh_settled && threadIdx.x < k && ch_push[threadIdx.x] &&
+        static_cast<int>(threadIdx.x) != own_child) {
         const int cn = tree.child_list[tree.child_off[n] + threadIdx.x];
-        const int slot = atomicAdd(&ws.qctl[1], 1);
-        if (slot < list.capacity)
-            __hip_atomic_store(&ws.queue[slot], b * a.N + cn, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        append_task(q, ws, tree.cls[cn], b * a.N + cn);
     }
-    if (threadIdx.x == 0 && sh_tree_done) {
-        const int slot = atomicAdd(&ws.qctl[1], 1);
-        if (slot < list.capacity)
-            __hip_atomic_store(&ws.queue[slot], a.B * a.N + b, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
-    __syncthreads();                                  // every append has returned its slot
-    if (threadIdx.x == 0) atomicAdd(&ws.qctl[2], 1);
+    __syncthreads();                                  // every new task has been counted
+    if (threadIdx.x == 0) atomicAdd(&ws.qctl[1], 1);
     }   // task loop
 }
 
@@ -815,6 +1123,7 @@ struct Plan {
     TreeDesc tree;
     int max_tree_depth;
     int n_internal;
+    int nclass;
 };
 
 static int validate(const mpv_problem* p, Plan* plan) {
@@ -865,6 +1174,20 @@ static int validate(const mpv_problem* p, Plan* plan) {
             n = t.parent[n];
         }
     }
+    for (int r = 0; r < p->N; ++r) t.rank[t.postorder[r]] = r;
+    for (int r = 0; r < p->N; ++r) {                  // children come before their parent
+        const int n = t.postorder[r];
+        t.sub_lo[n] = t.nchild[n] ? t.sub_lo[t.child_list[t.child_off[n]]] : r;
+    }
+    {   // priority classes: 0 from the root down to the first node that branches, then one per child of that node
+        int branch = 0;
+        while (t.nchild[branch] == 1) branch = t.child_list[t.child_off[branch]];
+        for (int n = 0; n < p->N; ++n) t.cls[n] = 0;
+        for (int j = 0; j < t.nchild[branch]; ++j) t.cls[t.child_list[t.child_off[branch] + j]] = 1 + j;
+        for (int n = 1; n < p->N; ++n)                // parents come before their children
+            if (t.depth[n] > t.depth[branch] + 1) t.cls[n] = t.cls[t.parent[n]];
+        plan->nclass = 1 + t.nchild[branch];
+    }
     plan->max_tree_depth = maxd;
     plan->n_internal = internal;
     if (p->max_depth < maxd) return MPV_ERR_BAD_SHAPE;
@@ -887,9 +1210,12 @@ static size_t carve(const mpv_problem* p, void* base, Workspace* ws) {
     float* mt = static_cast<float*>(take(bn * 4));
     float* md = static_cast<float*>(take(bn * 4));
     int32_t* qu = static_cast<int32_t*>(take(bn * 4));
-    int32_t* qc = static_cast<int32_t*>(take(4 * 4));
-    int32_t* pe = static_cast<int32_t*>(take(static_cast<size_t>(p->B) * 4));
-    if (ws) { ws->At = At; ws->Ad = Ad; ws->cfin = cf; ws->Wfin = Wf; ws->a0 = a0; ws->atest = at; ws->mt = mt; ws->md = md; ws->queue = qu; ws->qctl = qc; ws->pending = pe; }
+    int32_t* qc = static_cast<int32_t*>(take((4 + 2 * kMaxClasses) * 4));
+    int32_t* mb = static_cast<int32_t*>(take(kMaxWorkgroups * 4));
+    unsigned long long* kn = static_cast<unsigned long long*>(take(static_cast<size_t>(p->B) * 8));
+    unsigned long long* ac = static_cast<unsigned long long*>(take(static_cast<size_t>(p->B) * 8));
+    int32_t* de = static_cast<int32_t*>(take(static_cast<size_t>(p->B) * 4));
+    if (ws) { ws->At = At; ws->Ad = Ad; ws->cfin = cf; ws->Wfin = Wf; ws->a0 = a0; ws->atest = at; ws->mt = mt; ws->md = md; ws->queue = qu; ws->qctl = qc; ws->mailbox = mb; ws->known = kn; ws->acc = ac; ws->decided = de; }
     return off < 256 ? 256 : off;
 }
 
@@ -912,33 +1238,54 @@ static int launch_all(const mpv_problem* p, const Plan& plan, const Workspace& w
     (void)hipGetLastError();    // a stale error left by the caller's own HIP calls is not ours
     // every register and LDS slot of a node task is populated whatever the row's alignment
     const bool full = (p->V - (E::VEC - 1)) / E::VEC >= (kRegVecs + kLdsVecs) * kTaskBlock;
-    // initial tasks: every internal node for SpecInfer (nodes with many children first: they are
-    // the long tasks), the root alone for Traversal
-    TaskList list;
-    memset(&list, 0, sizeof(list));
+    // Queue layout and initial tasks.  Computing only what is needed, both rules start from the
+    // root: SpecInfer queues the accepted child, Traversal the children of positive weight.
+    // Computing everything (debug outputs), SpecInfer's node tasks are independent and all
+    // queued up front, nodes with many children (the long tasks) first.
+    QueuePlan q;
+    memset(&q, 0, sizeof(q));
+    q.nclass = plan.nclass;
+    int in_class[kMaxClasses] = {0};
+    for (int n = 0; n < p->N; ++n)
+        if (tree.nchild[n]) ++in_class[tree.cls[n]];
+    for (int c = 0; c < q.nclass; ++c)
+        q.off[c + 1] = q.off[c] + p->B * (in_class[c] + (c == 0 ? 1 : 0));     // class 0 also holds the sampling tasks
+    int prequeued[kMaxClasses] = {0};
+    for (int n = 0; n < p->N; ++n) q.init_slot[n] = -1;
+    const bool all_up_front = (p->method == MPV_METHOD_SPECINFER && !a.lazy);
     for (int kk = MPV_MAX_CHILDREN; kk >= 1; --kk)
         for (int n = 0; n < p->N; ++n)
-            if (tree.nchild[n] == kk && (p->method == MPV_METHOD_SPECINFER || n == 0))
-                list.nodes[list.count++] = n;
-    list.capacity = p->B * plan.n_internal + p->B;      // node tasks + one sampling task per tree
-    const int tasks = list.capacity;
+            if (tree.nchild[n] == kk && (all_up_front || n == 0))
+                q.init_slot[n] = prequeued[tree.cls[n]]++;
+    for (int c = 0; c < q.nclass; ++c) {
+        q.init_tail[c] = prequeued[c] * p->B;
+        q.init_total += q.init_tail[c];
+    }
+    if (tree.nchild[0] == 0) {
+        q.root_is_leaf = 1;
+        q.init_tail[0] = p->B;
+        q.init_total = p->B;
+    }
+    const int tasks = q.off[q.nclass];
+    // about one workgroup per compute unit (a node task fills one); fewer if there is less to do
+    int wgs = tasks < compute_units() ? tasks : compute_units();
+    if (wgs > kMaxWorkgroups) wgs = kMaxWorkgroups;
+    q.workers = wgs;
     {
         const int threads = 256;
         const int blocks = (max(p->B * p->N, MPV_MAX_NODES) + threads - 1) / threads;
         ScopedLaunch t(MPV_KERNEL_INIT, s);
-        hipLaunchKernelGGL(init_kernel, dim3(blocks), dim3(threads), 0, s, list, ws, a);
+        hipLaunchKernelGGL(init_kernel, dim3(blocks), dim3(threads), 0, s, q, tree, ws, a);
     }
     if (tasks > 0) {
-        // about one workgroup per compute unit (a node task fills one); fewer if there is less to do
-        const int wgs = tasks < compute_units() ? tasks : compute_units();
         ScopedLaunch t(MPV_KERNEL_NODE_TASK, s);
         const dim3 grid(static_cast<unsigned>(wgs)), block(kTaskBlock);
         if (p->method == MPV_METHOD_SPECINFER) {
-            if (full) hipLaunchKernelGGL((node_task_kernel<E, MPV_METHOD_SPECINFER, true>), grid, block, 0, s, tree, list, ws, a);
-            else hipLaunchKernelGGL((node_task_kernel<E, MPV_METHOD_SPECINFER, false>), grid, block, 0, s, tree, list, ws, a);
+            if (full) hipLaunchKernelGGL((node_task_kernel<E, MPV_METHOD_SPECINFER, true>), grid, block, 0, s, tree, q, ws, a);
+            else hipLaunchKernelGGL((node_task_kernel<E, MPV_METHOD_SPECINFER, false>), grid, block, 0, s, tree, q, ws, a);
         } else {
-            if (full) hipLaunchKernelGGL((node_task_kernel<E, MPV_METHOD_TRAVERSAL, true>), grid, block, 0, s, tree, list, ws, a);
-            else hipLaunchKernelGGL((node_task_kernel<E, MPV_METHOD_TRAVERSAL, false>), grid, block, 0, s, tree, list, ws, a);
+            if (full) hipLaunchKernelGGL((node_task_kernel<E, MPV_METHOD_TRAVERSAL, true>), grid, block, 0, s, tree, q, ws, a);
+            else hipLaunchKernelGGL((node_task_kernel<E, MPV_METHOD_TRAVERSAL, false>), grid, block, 0, s, tree, q, ws, a);
         }
     }
     if (a.dbg_stats) {
@@ -1009,7 +1356,7 @@ int mpv_verify(const mpv_problem* problem, const mpv_buffers* buf, void* workspa
     a.B = problem->B; a.N = problem->N; a.V = problem->V; a.max_depth = problem->max_depth;
     a.k32 = static_cast<float>(1.4426950408889634 / static_cast<double>(problem->temperature));
     a.invT = 1.0f / problem->temperature;
-    a.prune = (buf->edge_probs == nullptr) ? 1 : 0;
+    a.lazy = (buf->edge_probs == nullptr && buf->accept_prob == nullptr && buf->stats == nullptr) ? 1 : 0;
     {
         // start-up spread of the persistent workgroups: about the time one workgroup needs to
         // read a row pair when every compute unit is reading (its share of ~6.3 TB/s), only

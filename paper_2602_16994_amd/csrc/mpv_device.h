@@ -143,6 +143,16 @@ __device__ __forceinline__ double wave_inclusive_scan(double v) {
     return v;
 }
 
+__device__ __forceinline__ int wave_inclusive_scan_i32(int v) {
+    const int lane = threadIdx.x & (kWave - 1);
+#pragma unroll
+    for (int o = 1; o < kWave; o <<= 1) {
+        const int t = __shfl_up(v, o, kWave);
+        if (lane >= o) v += t;
+    }
+    return v;
+}
+
 // Block-wide reductions of two values at once; every thread gets the result.
 // `scratch` must hold 2 * (BLOCK / 64) doubles and may be reused after return.
 template <int BLOCK>
