@@ -120,7 +120,10 @@ typedef struct mpv_buffers {
                                           read; the others were proved irrelevant first      */
 #define MPV_COUNTER_NODE_TASKS_CANCELLED 6 /* node tasks that had been queued ahead of need and
                                           were dropped unread once their tree was settled     */
-#define MPV_COUNTER_COUNT           8  /* length of the counters array (rest reserved)       */
+#define MPV_COUNTER_NODE_TASKS_RESUMED 7 /* second reads of a row pair: where a tree branches, a
+                                          node may first explore its first child's subtree and
+                                          come back for the rest only if nothing was accepted  */
+#define MPV_COUNTER_COUNT           8  /* length of the counters array        */
 
 /* ABI version of the loaded library (MPV_ABI_VERSION it was built with). */
 int mpv_version(void);

@@ -46,14 +46,15 @@ struct TreeDesc {
     int32_t cls[MPV_MAX_NODES];          // priority class of the node's task (see QueuePlan)
 };
 
-constexpr int kMaxClasses = MPV_MAX_CHILDREN + 1;
+constexpr int kMaxClasses = 4;
 
 // The task queue is one first-in-first-out queue per priority class; a free workgroup is
-// given the oldest task of the lowest class that has one.  Class 0: the nodes from the root down to
-// the first node that branches, and every sampling task.  Class 1 + j: the subtree of that
-// node's j-th child.  A rule examines the subtrees in this order and stops at the first node
-// it accepts, so work on an earlier subtree is more likely to be needed than work on a later
-// one; later classes are run ahead, speculatively, by workgroups that would otherwise idle.
+// given the oldest task of the lowest class that has one.  Class 0: the nodes from the root down
+// to the first node that branches (every tree needs them).  Class 1: the nodes below it, which
+// a settled tree no longer needs.  (More classes are possible: the dispatcher takes any number
+// up to kMaxClasses.  Ranking the subtrees of the branching node by the order in which the rule
+// visits them was tried and lost to plain age order: it starves the later subtrees of the
+// trees that end up needing all of them, and those trees decide when the launch ends.)
 struct QueuePlan {
     int32_t nclass;
     int32_t off[kMaxClasses + 1];        // class c owns queue[off[c] .. off[c+1])
@@ -62,6 +63,12 @@ struct QueuePlan {
     int32_t init_total;                  // prequeued tasks
     int32_t root_is_leaf;                // no node task at all: the sampling tasks are prequeued
     int32_t workers;                     // workgroups of the launch; the first prequeued tasks of class 0 go straight to them
+    // Traversal, only what is needed, no workgroup to spare: the node where the tree branches
+    // (-1: not used) first handles its first child only; the rest of its work (a second task:
+    // "resumed") is started when that child's subtree, split_mask in postorder positions, turns
+    // out to be rejected as a whole.
+    int32_t split_node;
+    unsigned long long split_mask;
 };
 
 // Per-(tree,node) scalars kept in the workspace, all double, each [B*N].
@@ -77,7 +84,8 @@ struct Workspace {
     int32_t* queue;      // entry = tree * N + node (node task) or B * N + tree (sampling task), -1 = not written yet
     // [0] appended: tasks ever queued or started directly, [1] completed: tasks finished or cancelled,
     // [2] exit: set when nothing is left, [3] lock: held by the workgroup that is dispatching,
-    // [4 + c] tail of class c: entries appended, [4 + kMaxClasses + c] head of class c: entries handed out
+    // [4 + c] tail of class c: entries appended, [4 + kMaxClasses + c] head of class c: entries handed out,
+    // [4 + 2 kMaxClasses] workgroups left waiting after the last round of dispatching (a hint)
     int32_t* qctl;
     int32_t* mailbox;    // [workgroups] kMailboxWaiting, or the task handed to that workgroup
     // Per tree, one bit per node at the node's position in postorder: `known` = the outcome of
@@ -125,7 +133,8 @@ constexpr int kSampleBlock = kTaskBlock;     // sampling tasks run on the node t
 // wave tiles of the bonus sampler: 64 16-byte vectors; float rows have the smallest tiles
 constexpr int kMaxTiles = MPV_MAX_VOCAB / (kWave * 4);
 // task hand-over between the dispatcher and the workers (see "task queue")
-constexpr int kMailboxWaiting = -1;
+constexpr int kMailboxWaiting = -1;                  // the workgroup is idle
+constexpr int kMailboxSoon = -2;                     // the workgroup has asked ahead: it will be free shortly
 constexpr int kTaskExit = -1;                         // what a worker's wait returns when all is done
 constexpr int kWorkerSlots = 8;                       // mailboxes per dispatcher lane
 constexpr int kMaxWorkgroups = kWave * kWorkerSlots;
@@ -135,7 +144,7 @@ constexpr int kMaxWorkgroups = kWave * kWorkerSlots;
 __global__ void init_kernel(QueuePlan q, TreeDesc tree, Workspace ws, Args a) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < MPV_COUNTER_COUNT) a.counters[i] = 0u;
-    if (i == 0) { ws.qctl[0] = q.init_total; ws.qctl[1] = 0; ws.qctl[2] = 0; ws.qctl[3] = 0; }
+    if (i == 0) { ws.qctl[0] = q.init_total; ws.qctl[1] = 0; ws.qctl[2] = 0; ws.qctl[3] = 0; ws.qctl[4 + 2 * kMaxClasses] = 0; }
     if (i < kMaxClasses) {
         ws.qctl[4 + i] = (i < q.nclass) ? q.init_tail[i] : 0;
         ws.qctl[4 + kMaxClasses + i] = (i == 0) ? min(q.workers, q.init_tail[0]) : 0;
@@ -185,8 +194,9 @@ __global__ void init_kernel(QueuePlan q, TreeDesc tree, Workspace ws, Args a) {
 // so every queued task can run at once, on any workgroup: nothing depends on which or how
 // many workgroups are resident.
 //   append:   appended++, then slot = tail++ of the class, then the entry is written.
-//   request:  mailbox[w] = waiting.  A workgroup asks before the last sweep of its current
-//             task when it can, so the answer is usually there when it is done.
+//   request:  mailbox[w] = "soon" when a workgroup asks ahead, before the last sweep of its
+//             current task (the answer is then usually there when it is done), "waiting" once
+//             it has nothing to do.  Idle workgroups are served before those that asked ahead.
 //   dispatch: a workgroup that has nothing to do takes the dispatcher lock if it is free and,
 //             with its first wave, hands queued tasks to waiting workgroups (itself included)
 //             in priority order (class, then age), until it has a task of its own; then it
@@ -212,9 +222,9 @@ __device__ __forceinline__ void st_relaxed(int32_t* p, int v) {
 // all loads, stores and atomics issued so far by this lane have been performed
 __device__ __forceinline__ void wait_memory() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
-// One lane: ask for a task.
+// One lane: ask for a task ahead of time.
 __device__ __forceinline__ void request_task(const Workspace& ws) {
-    st_relaxed(&ws.mailbox[blockIdx.x], kMailboxWaiting);
+    st_relaxed(&ws.mailbox[blockIdx.x], kMailboxSoon);
 }
 
 // Append one task to class c (one lane).  The caller's earlier stores have been waited for.
@@ -234,18 +244,24 @@ __device__ bool dispatch_round(const QueuePlan& q, const Workspace& ws, const Ar
     const int lane = threadIdx.x;
     const int workers = static_cast<int>(gridDim.x);
     // who is waiting, what is queued
-    unsigned waiting = 0u;
+    unsigned waiting = 0u, soon = 0u;
 #pragma unroll
     for (int sl = 0; sl < kWorkerSlots; ++sl) {
         const int w = lane + kWave * sl;
-        if (w < workers && ld_relaxed(&ws.mailbox[w]) == kMailboxWaiting) waiting |= 1u << sl;
+        if (w < workers) {
+            const int m = ld_relaxed(&ws.mailbox[w]);
+            if (m == kMailboxWaiting) waiting |= 1u << sl;
+            if (m == kMailboxSoon) soon |= 1u << sl;
+        }
     }
     const int tail = (lane < q.nclass) ? ld_relaxed(&ws.qctl[4 + lane]) : 0;
     const int avail = (lane < q.nclass) ? tail - head : 0;
-    const int my_waiting = __popc(waiting);
+    const int my_waiting = __popc(waiting), my_soon = __popc(soon);
     const int waiting_incl = wave_inclusive_scan_i32(my_waiting);
+    const int soon_incl = wave_inclusive_scan_i32(my_soon);
     const int avail_incl = wave_inclusive_scan_i32(avail);
-    const int total_waiting = __shfl(waiting_incl, kWave - 1, kWave);
+    const int total_idle = __shfl(waiting_incl, kWave - 1, kWave);
+    const int total_waiting = total_idle + __shfl(soon_incl, kWave - 1, kWave);
     const int total_avail = __shfl(avail_incl, kWave - 1, kWave);
     if (total_avail == 0) {
         int done = 0;
@@ -268,19 +284,26 @@ __device__ bool dispatch_round(const QueuePlan& q, const Workspace& ws, const Ar
         }
         if (__builtin_amdgcn_readfirstlane(done)) return true;
     }
+    // how many will still be waiting after this round: tasks look at it to decide whether work
+    // that may turn out useless is worth queueing
+    if (lane == 0) st_relaxed(&ws.qctl[4 + 2 * kMaxClasses], max(0, total_idle - total_avail));
     if (total_avail == 0 || total_waiting == 0) {
         __builtin_amdgcn_s_sleep(8);
         return false;
     }
-    // waiting workgroup number r (in lane, slot order) gets queued task number r (in class, age order)
+    // Requester number r gets queued task number r (in class, age order); the idle workgroups
+    // come first (in lane, slot order), then those that asked ahead.
     if (lane < q.nclass) { sh_head[lane] = head; sh_before[lane + 1] = avail_incl; }
     if (lane == 0) sh_before[0] = 0;
     __builtin_amdgcn_wave_barrier();
-    int r = waiting_incl - my_waiting;
+    int r_idle = waiting_incl - my_waiting;
+    int r_soon = total_idle + soon_incl - my_soon;
     for (int sl = 0; sl < kWorkerSlots; ++sl) {
-        if (!((waiting >> sl) & 1u)) continue;
-        const int mine = r++;
-        if (mine >= total_avail) break;
+        int mine;
+        if ((waiting >> sl) & 1u) mine = r_idle++;
+        else if ((soon >> sl) & 1u) mine = r_soon++;
+        else continue;
+        if (mine >= total_avail) continue;
         int c = 0;
         while (mine >= sh_before[c + 1]) ++c;         // ends: mine < total_avail = sh_before[nclass]
         const int32_t* slot = &ws.queue[q.off[c] + sh_head[c] + (mine - sh_before[c])];
@@ -320,12 +343,13 @@ __device__ int acquire_task(const QueuePlan& q, const Workspace& ws, const Args&
     for (int spin = 0; spin < kMaxSpins; ++spin) {
         int t = 0, ex = 0, lk = 1;
         if (lane == 0) {
-            t = ld_relaxed(box);
+            // nothing to do any more: from "soon" to "waiting" (unless the answer has arrived)
+            t = (spin == 0) ? static_cast<int>(atomicCAS(box, kMailboxSoon, kMailboxWaiting)) : ld_relaxed(box);
             ex = ld_relaxed(&ws.qctl[2]);
             lk = ld_relaxed(&ws.qctl[3]);
         }
         t = __builtin_amdgcn_readfirstlane(t);
-        if (t != kMailboxWaiting && t != previous) return t;
+        if (t >= 0 && t != previous) return t;
         if (__builtin_amdgcn_readfirstlane(ex)) return kTaskExit;
         int got = 0;
         if (lane == 0 && lk == 0) got = (atomicCAS(&ws.qctl[3], 0, 1) == 0) ? 1 : 0;
@@ -339,7 +363,7 @@ __device__ int acquire_task(const QueuePlan& q, const Workspace& ws, const Args&
                 if (finished) break;
                 int mine = (lane == 0) ? ld_relaxed(box) : 0;
                 mine = __builtin_amdgcn_readfirstlane(mine);
-                if (mine != kMailboxWaiting && mine != previous) { result = mine; break; }
+                if (mine >= 0 && mine != previous) { result = mine; break; }
             }
             if (lane < q.nclass) st_relaxed(&ws.qctl[4 + kMaxClasses + lane], head);
             wait_memory();
@@ -438,7 +462,7 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(TreeDesc tree, Qu
     } else {
         if (threadIdx.x < kWave) {
             if (!asked) {
-                if (threadIdx.x == 0) request_task(ws);
+                if (threadIdx.x == 0) st_relaxed(&ws.mailbox[blockIdx.x], kMailboxWaiting);
                 wait_memory();
             }
             const int t = acquire_task(q, ws, a, previous_task, drop_settled);
@@ -450,7 +474,7 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(TreeDesc tree, Qu
         asked = false;
         if (task == kTaskExit) break;
     }
-    if (task >= a.B * a.N) {
+    if (task >= a.B * a.N && task < a.B * a.N + a.B) {
         // the tree's outcome is settled: walk and bonus token
         if (!asked) {
             if (threadIdx.x == 0) request_task(ws);
@@ -461,8 +485,10 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(TreeDesc tree, Qu
         if (threadIdx.x == 0) atomicAdd(&ws.qctl[1], 1);
         continue;
     }
-    const int b = task / a.N;
-    const int n = task % a.N;
+    // a node task, or the resumed task of the node where the tree branches
+    const bool resumed = task >= a.B * a.N + a.B;
+    const int b = resumed ? task - (a.B * a.N + a.B) : task / a.N;
+    const int n = resumed ? q.split_node : task % a.N;
     const size_t bn = static_cast<size_t>(b) * a.N + n;
     const T* zt = static_cast<const T*>(a.zt) + bn * a.V;
     const T* zd = static_cast<const T*>(a.zd) + bn * a.V;
@@ -470,13 +496,12 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(TreeDesc tree, Qu
     const float k32 = a.k32;
 
     const int k = tree.nchild[n];
-    if (threadIdx.x == 0) atomicAdd(&a.counters[MPV_COUNTER_NODE_TASKS_RUN], 1u);
+    if (threadIdx.x == 0) atomicAdd(&a.counters[resumed ? MPV_COUNTER_NODE_TASKS_RESUMED : MPV_COUNTER_NODE_TASKS_RUN], 1u);
+    const bool split_here = METHOD == MPV_METHOD_TRAVERSAL && a.lazy && !resumed && n == q.split_node;
 
     // ---- the children's tokens and this node's starting weight: fetched now, so that
     //      their latency hides behind the sweep (lane j looks after child j)
     __shared__ int ch_tok[MPV_MAX_CHILDREN];
-    __shared__ int ch_push[MPV_MAX_CHILDREN];
-    if (threadIdx.x < MPV_MAX_CHILDREN) ch_push[threadIdx.x] = 0;
     __shared__ float ch_zt[MPV_MAX_CHILDREN], ch_zd[MPV_MAX_CHILDREN];
     __shared__ float ch_u[MPV_MAX_CHILDREN];
     __shared__ double sh_a0;
@@ -489,6 +514,10 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(TreeDesc tree, Qu
         pf_u = a.uniforms[bc];
     }
     if (threadIdx.x == kWave) pf_u = a.uniforms[bn];        // the node's own uniform
+    // are workgroups idle (as of the last round of dispatching)?
+    __shared__ int sh_idle, sh_ahead;
+    int pf_idle = 0;
+    if (threadIdx.x == 0) pf_idle = ld_relaxed(&ws.qctl[4 + 2 * kMaxClasses]);
 
     // ---- softmax statistics of both rows: the one read of the pair from memory
     RetainedPair<E, kTaskBlock, RV, LV, CH, FULL> pair;
@@ -501,6 +530,21 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(TreeDesc tree, Qu
         pf_t = zt[pf_x];
         pf_d = zd[pf_x];
     }
+    // Traversal, only what is needed, and idle workgroups about: an only child's task is queued
+    // now, ahead of its starting weight.  It reads its rows while this task reads its own and
+    // then finds the weight published (or waits a moment for it), so that a chain of nodes
+    // takes little more than one task's time.  If the weight turns out to be 0 it gives up.
+    if (threadIdx.x == 0) {
+        int ahead = 0;
+        if (METHOD == MPV_METHOD_TRAVERSAL && a.lazy && k == 1 && !split_here && pf_idle != 0) {
+            const int cn = tree.child_list[tree.child_off[n]];
+            if (tree.nchild[cn] > 0) {
+                append_task(q, ws, tree.cls[cn], b * a.N + cn);
+                ahead = 1;
+            }
+        }
+        sh_ahead = ahead;
+    }
     RowStat rt, rd;
     {
         PairStatsRawF<E> f;
@@ -508,6 +552,7 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(TreeDesc tree, Qu
         pair.first_pass(f);
         if (threadIdx.x < k) { ch_tok[threadIdx.x] = pf_x; ch_u[threadIdx.x] = pf_u; ch_zt[threadIdx.x] = E::load_one(&pf_t); ch_zd[threadIdx.x] = E::load_one(&pf_d); }
         if (threadIdx.x == kWave) sh_un = pf_u;
+        if (threadIdx.x == 0) sh_idle = pf_idle;
         if (threadIdx.x == 0) {
             // Traversal: the starting weight comes from the parent's task, which published it
             // before it queued this task; the two stores may still arrive in either order.
@@ -538,13 +583,35 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(TreeDesc tree, Qu
 
     // ---- per-child scalars and one residual-mass reduction per child
     double wa = (METHOD == MPV_METHOD_TRAVERSAL) ? uniform_f64(sh_a0) : 1.0;   // node weight a
+    const bool child_ahead = sh_ahead != 0;
+    if (METHOD == MPV_METHOD_TRAVERSAL && a.lazy && n != 0 && !(wa > 0.0)) {
+        // queued ahead of its weight, which is 0: the parent has written off the whole subtree.
+        // Nothing to do but to pass the news on to an only child queued ahead in turn.
+        if (threadIdx.x == 0) {
+            if (child_ahead) {
+                const size_t bc = static_cast<size_t>(b) * a.N + tree.child_list[tree.child_off[n]];
+                __hip_atomic_store(reinterpret_cast<unsigned long long*>(&ws.a0[bc]),
+                                   static_cast<unsigned long long>(__double_as_longlong(0.0)),
+                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+            wait_memory();
+            atomicAdd(&ws.qctl[1], 1);
+        }
+        continue;
+    }
     double c = 0.0, W = 1.0;
     const double kd = static_cast<double>(k32);
     // test outcomes this task settles, one bit per node at its position in postorder
     unsigned long long settled_bits = 0ull, accepted_bits = 0ull;
     int next_node = -1;                               // SpecInfer, only what is needed: the accepted child
     int own_child = -1;                               // Traversal: index of the first child whose task is to be run
+    bool paused = false;
+    bool own_given = false;                           // that child's task was queued after all (some workgroup is idle)
+    const bool idle_seen = sh_idle != 0;
     for (int j = 0; j < k; ++j) {
+        // a resumed task repeats the arithmetic of the first child (whose task has long run)
+        // to get at the residual that follows its rejection
+        const bool redone = resumed && j == 0;
         const int cn = tree.child_list[tree.child_off[n] + j];
         const size_t bc = static_cast<size_t>(b) * a.N + cn;
         const int x = ch_tok[j];
@@ -571,7 +638,8 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(TreeDesc tree, Qu
         // the same comparison the walk makes
         const bool child_accepted = static_cast<double>(ch_u[j]) < w_child;
         const unsigned long long child_bit = 1ull << tree.rank[cn];
-        if (METHOD == MPV_METHOD_SPECINFER) {
+        if (redone) {
+        } else if (METHOD == MPV_METHOD_SPECINFER) {
             settled_bits |= child_bit;
         } else if (tree.nchild[cn] == 0) {
             settled_bits |= child_bit;
@@ -585,16 +653,21 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(TreeDesc tree, Qu
             settled_bits |= upto & ~((1ull << lo) - 1ull);
         }
         // Traversal: the child's own task is needed unless its weight is 0 (see above)
-        const bool run_child = METHOD == MPV_METHOD_TRAVERSAL && tree.nchild[cn] > 0 && (w_child > 0.0 || !a.lazy);
-        if (run_child && own_child < 0) own_child = j;
+        const bool run_child = METHOD == MPV_METHOD_TRAVERSAL && !redone && tree.nchild[cn] > 0 && (w_child > 0.0 || !a.lazy);
+        const bool first_to_run = run_child && own_child < 0;
+        if (first_to_run) {
+            // kept for this workgroup if it is the last thing this task finds out and nobody is idle
+            own_child = j;
+            own_given = (idle_seen || j < k - 1 || child_ahead) && !(split_here && j == 0);
+        }
         // One more sweep to go at most: time to ask for the next task, unless this workgroup
         // already knows what it will run next (a child's task).
-        if (j == k - 1 && !asked && own_child < 0 &&
+        if (j == k - 1 && !asked && (own_child < 0 || own_given) &&
             !(METHOD == MPV_METHOD_SPECINFER && a.lazy && child_accepted && tree.nchild[cn] > 0)) {
             if (threadIdx.x == 0) request_task(ws);
             asked = true;
         }
-        if (threadIdx.x == 0) {
+        if (threadIdx.x == 0 && !redone) {
             if (METHOD == MPV_METHOD_TRAVERSAL) {
                 if (tree.nchild[cn] == 0) {
                     st_shared_f64(&ws.atest[bc], w_child);           // leaves are tested as they are
@@ -602,7 +675,13 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(TreeDesc tree, Qu
                     __hip_atomic_store(reinterpret_cast<unsigned long long*>(&ws.a0[bc]),
                                        static_cast<unsigned long long>(__double_as_longlong(w_child)),
                                        __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    ch_push[j] = run_child ? 1 : 0;
+                    // The first child that needs a task is kept for this workgroup (run next,
+                    // no queue) unless some workgroup is idle; every other one is queued now,
+                    // while this task goes on with the sweeps that follow.
+                    if (run_child && (!first_to_run || own_given) && !child_ahead) {
+                        wait_memory();                    // its starting weight has been written
+                        append_task(q, ws, tree.cls[cn], b * a.N + cn);
+                    }
                 }
             } else {
                 st_shared_f64(&ws.atest[bc], w_child);
@@ -611,6 +690,13 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(TreeDesc tree, Qu
                 a.dbg_edge[bc * 2] = static_cast<float>(px);
                 a.dbg_edge[bc * 2 + 1] = static_cast<float>(qx);
             }
+        }
+
+        // Where the tree branches and no workgroup is to spare, the first child's subtree is
+        // explored first: most walks end there, and then nothing else of this node is needed.
+        if (split_here && j == 0 && run_child) {
+            paused = true;
+            break;
         }
 
         // SpecInfer moves into the first child it accepts: later children and this node's
@@ -645,7 +731,17 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(TreeDesc tree, Qu
         }
     }
 
-    __shared__ int sh_push_sample, sh_settled;
+    if (paused) {
+        // nothing is settled yet; the first child's task is run next by this workgroup
+        own_task = b * a.N + tree.child_list[tree.child_off[n]];
+        if (threadIdx.x == 0) {
+            (void)atomicAdd(&ws.qctl[0], 1);
+            wait_memory();                            // counted (and the child's weight written) before this task counts as finished
+            atomicAdd(&ws.qctl[1], 1);
+        }
+        continue;
+    }
+    __shared__ int sh_push_sample, sh_settled, sh_resume;
     if (threadIdx.x == 0) {
         st_shared_f64(&ws.At[bn], rt.A);
         st_shared_f64(&ws.Ad[bn], rd.A);
@@ -654,7 +750,7 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(TreeDesc tree, Qu
         ws.mt[bn] = rt.m;                             // read by later launches only
         ws.md[bn] = rd.m;
         ws.Wfin[bn] = W;
-        bool push_sample, settled_tree = false;
+        bool push_sample, settled_tree = false, resume = false;
         if (METHOD == MPV_METHOD_SPECINFER && a.lazy) {
             // the walk ends here (no child accepted) or in the accepted leaf
             push_sample = next_node < 0 || tree.nchild[next_node] == 0;
@@ -676,7 +772,8 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(TreeDesc tree, Qu
                 (void)atomicOr(&ws.acc[b], accepted_bits);
                 wait_memory();
             }
-            const unsigned long long known = atomicOr(&ws.known[b], settled_bits) | settled_bits;
+            const unsigned long long known_before = atomicOr(&ws.known[b], settled_bits);
+            const unsigned long long known = known_before | settled_bits;
             wait_memory();
             const unsigned long long acc = ld_relaxed(&ws.acc[b]);
             bool settled;
@@ -692,9 +789,18 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(TreeDesc tree, Qu
             // only what is needed: once a tree is settled (here or by another task) the rest of
             // its node tasks are pointless
             settled_tree = a.lazy && (settled || ld_relaxed(&ws.decided[b]) != 0);
+            // The subtree that was explored first has just turned out to be rejected as a whole
+            // (this task supplied its last missing outcome): time for the rest of the node
+            // where the tree branches.
+            if (METHOD == MPV_METHOD_TRAVERSAL && a.lazy && q.split_node >= 0 && !settled_tree &&
+                ((q.split_mask >> tree.rank[n]) & 1ull) != 0ull) {          // this node lies in that subtree
+                const unsigned long long m = q.split_mask;
+                resume = (known & m) == m && (known_before & m) != m && (acc & m) == 0ull;
+            }
         }
         sh_push_sample = push_sample ? 1 : 0;
         sh_settled = settled_tree ? 1 : 0;
+        sh_resume = resume ? 1 : 0;
     }
     __syncthreads();
     // What follows from this task.  One task is run by this workgroup itself, next (no queue,
@@ -702,19 +808,23 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(TreeDesc tree, Qu
     // its own task (Traversal) or the accepted child (SpecInfer).  The other children are queued.
     if (sh_push_sample) {
         own_task = a.B * a.N + b;
+    } else if (sh_resume) {
+        own_task = a.B * a.N + a.B + b;
     } else if (METHOD == MPV_METHOD_TRAVERSAL) {
-        if (own_child >= 0 && !sh_settled) own_task = b * a.N + tree.child_list[tree.child_off[n] + own_child];
+        if (own_child >= 0 && !own_given && !sh_settled) own_task = b * a.N + tree.child_list[tree.child_off[n] + own_child];
     } else if (a.lazy && next_node >= 0 && tree.nchild[next_node] > 0) {
         own_task = b * a.N + next_node;
     }
-    if (threadIdx.x == 0 && own_task >= 0) {
-        (void)atomicAdd(&ws.qctl[0], 1);
-        wait_memory();
-    }
-    if (METHOD == MPV_METHOD_TRAVERSAL && !sh_settled && threadIdx.x < k && ch_push[threadIdx.x] &&
-        static_cast<int>(threadIdx.x) != own_child) {
-        const int cn = tree.child_list[tree.child_off[n] + threadIdx.x];
-        append_task(q, ws, tree.cls[cn], b * a.N + cn);
+    if (threadIdx.x == 0) {
+        if (own_task >= 0) {
+            (void)atomicAdd(&ws.qctl[0], 1);
+            wait_memory();
+        }
+        // (cannot happen: a task that settles the tree or completes a subtree has no child left to run)
+        if (METHOD == MPV_METHOD_TRAVERSAL && own_child >= 0 && !own_given && !sh_settled && (sh_push_sample || sh_resume)) {
+            const int cn = tree.child_list[tree.child_off[n] + own_child];
+            append_task(q, ws, tree.cls[cn], b * a.N + cn);
+        }
     }
     __syncthreads();                                  // every new task has been counted
     if (threadIdx.x == 0) atomicAdd(&ws.qctl[1], 1);
@@ -1179,14 +1289,11 @@ static int validate(const mpv_problem* p, Plan* plan) {
         const int n = t.postorder[r];
         t.sub_lo[n] = t.nchild[n] ? t.sub_lo[t.child_list[t.child_off[n]]] : r;
     }
-    {   // priority classes: 0 from the root down to the first node that branches, then one per child of that node
+    {   // priority classes: 0 from the root down to the first node that branches, 1 below it
         int branch = 0;
         while (t.nchild[branch] == 1) branch = t.child_list[t.child_off[branch]];
-        for (int n = 0; n < p->N; ++n) t.cls[n] = 0;
-        for (int j = 0; j < t.nchild[branch]; ++j) t.cls[t.child_list[t.child_off[branch] + j]] = 1 + j;
-        for (int n = 1; n < p->N; ++n)                // parents come before their children
-            if (t.depth[n] > t.depth[branch] + 1) t.cls[n] = t.cls[t.parent[n]];
-        plan->nclass = 1 + t.nchild[branch];
+        for (int n = 0; n < p->N; ++n) t.cls[n] = (t.depth[n] <= t.depth[branch]) ? 0 : 1;
+        plan->nclass = t.nchild[branch] ? 2 : 1;
     }
     plan->max_tree_depth = maxd;
     plan->n_internal = internal;
@@ -1210,7 +1317,7 @@ static size_t carve(const mpv_problem* p, void* base, Workspace* ws) {
     float* mt = static_cast<float*>(take(bn * 4));
     float* md = static_cast<float*>(take(bn * 4));
     int32_t* qu = static_cast<int32_t*>(take(bn * 4));
-    int32_t* qc = static_cast<int32_t*>(take((4 + 2 * kMaxClasses) * 4));
+    int32_t* qc = static_cast<int32_t*>(take((5 + 2 * kMaxClasses) * 4));
     int32_t* mb = static_cast<int32_t*>(take(kMaxWorkgroups * 4));
     unsigned long long* kn = static_cast<unsigned long long*>(take(static_cast<size_t>(p->B) * 8));
     unsigned long long* ac = static_cast<unsigned long long*>(take(static_cast<size_t>(p->B) * 8));
@@ -1271,6 +1378,20 @@ static int launch_all(const mpv_problem* p, const Plan& plan, const Workspace& w
     int wgs = tasks < compute_units() ? tasks : compute_units();
     if (wgs > kMaxWorkgroups) wgs = kMaxWorkgroups;
     q.workers = wgs;
+    q.split_node = -1;
+    if (p->method == MPV_METHOD_TRAVERSAL && a.lazy && p->B >= wgs) {
+        int branch = 0;
+        while (tree.nchild[branch] == 1) branch = tree.child_list[tree.child_off[branch]];
+        if (tree.nchild[branch] >= 2) {
+            const int first = tree.child_list[tree.child_off[branch]];
+            if (tree.nchild[first] > 0) {
+                const int hi = tree.rank[first], lo = tree.sub_lo[first];
+                const unsigned long long upto = (hi >= 63) ? ~0ull : ((1ull << (hi + 1)) - 1ull);
+                q.split_node = branch;
+                q.split_mask = upto & ~((1ull << lo) - 1ull);
+            }
+        }
+    }
     {
         const int threads = 256;
         const int blocks = (max(p->B * p->N, MPV_MAX_NODES) + threads - 1) / threads;
