@@ -166,10 +166,12 @@ int mpv_fill_uniforms(uint64_t seed, int64_t count, float* d_u, void* hip_stream
  * and destroys the events.  mpv_timing_read, called after the caller has
  * synchronised that stream, writes the elapsed milliseconds and the MPV_KERNEL_*
  * id of each recorded launch (HOST arrays of `capacity` entries), sets *count and
- * clears the record.  Path of one call (Sec. 2, step 3): node tasks = softmax
- * statistics, per-child test probabilities and residual masses; sample = the
- * accept/reject walk followed by the bonus token (MPV_KERNEL_WALK is no longer
- * a launch of its own; the id stays reserved). */
+ * clears the record.  One call is two launches: MPV_KERNEL_INIT (counters, queue) and
+ * MPV_KERNEL_NODE_TASK, whose persistent workgroups run every node task (softmax
+ * statistics, per-child test probabilities, residual masses) and every sampling task
+ * (accept/reject walk, bonus token) of the batch (Sec. 2, step 3); MPV_KERNEL_DEBUG_STATS
+ * follows when `stats` is requested.  MPV_KERNEL_WALK and MPV_KERNEL_SAMPLE are no longer
+ * launches of their own; the ids stay reserved. */
 #define MPV_KERNEL_INIT        0
 #define MPV_KERNEL_NODE_TASK   1
 #define MPV_KERNEL_WALK        2

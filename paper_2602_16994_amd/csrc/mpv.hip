@@ -76,11 +76,8 @@ struct Workspace {
     double* At;      // log2-partition of the target row (internal nodes)
     double* Ad;      // same for the draft row
     double* cfin;    // c of the node's final state (all children rejected)
-    double* Wfin;    // W(c) of that state
     double* a0;      // Traversal: weight the node starts with (kNotReady until its parent's task publishes it)
     double* atest;   // probability the node is tested with
-    float* mt;       // row maxima (for the debug statistics)
-    float* md;
     int32_t* queue;      // entry = tree * N + node (node task) or B * N + tree (sampling task), -1 = not written yet
     // [0] appended: tasks ever queued or started directly, [1] completed: tasks finished or cancelled,
     // [2] exit: set when nothing is left, [3] lock: held by the workgroup that is dispatching,
@@ -162,7 +159,6 @@ __global__ void init_kernel(QueuePlan q, TreeDesc tree, Workspace ws, Args a) {
         // a node no task ever reaches is tested with probability 0
         ws.atest[i] = (i % a.N == 0) ? 1.0 : 0.0;
         ws.cfin[i] = 0.0;
-        ws.Wfin[i] = 1.0;
         // queue: the prequeued node tasks, node-major inside their class (the same node of
         // consecutive trees next to each other); everything else "not written yet"
         if (i < q.off[q.nclass]) {
@@ -747,9 +743,6 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(TreeDesc tree, Qu
         st_shared_f64(&ws.Ad[bn], rd.A);
         st_shared_f64(&ws.cfin[bn], c);
         if (METHOD == MPV_METHOD_TRAVERSAL && n != 0) st_shared_f64(&ws.atest[bn], wa);
-        ws.mt[bn] = rt.m;                             // read by later launches only
-        ws.md[bn] = rd.m;
-        ws.Wfin[bn] = W;
         bool push_sample, settled_tree = false, resume = false;
         if (METHOD == MPV_METHOD_SPECINFER && a.lazy) {
             // the walk ends here (no child accepted) or in the accepted leaf
@@ -972,7 +965,7 @@ __device__ void sample_task(const TreeDesc& tree, const Workspace& ws, const Arg
         RowStat rt, rd;
         finish_stats2<kSampleBlock>(f.t, none, rt, rd, scratch);
         At = rt.A;
-        if (threadIdx.x == 0) { ws.At[bn] = rt.A; ws.mt[bn] = rt.m; }
+        if (threadIdx.x == 0) ws.At[bn] = rt.A;
     } else {
         At = ld_shared_f64(&ws.At[bn]);
         Ad = ld_shared_f64(&ws.Ad[bn]);
@@ -1311,18 +1304,15 @@ static size_t carve(const mpv_problem* p, void* base, Workspace* ws) {
     double* At = static_cast<double*>(take(bn * 8));
     double* Ad = static_cast<double*>(take(bn * 8));
     double* cf = static_cast<double*>(take(bn * 8));
-    double* Wf = static_cast<double*>(take(bn * 8));
     double* a0 = static_cast<double*>(take(bn * 8));
     double* at = static_cast<double*>(take(bn * 8));
-    float* mt = static_cast<float*>(take(bn * 4));
-    float* md = static_cast<float*>(take(bn * 4));
     int32_t* qu = static_cast<int32_t*>(take(bn * 4));
     int32_t* qc = static_cast<int32_t*>(take((5 + 2 * kMaxClasses) * 4));
     int32_t* mb = static_cast<int32_t*>(take(kMaxWorkgroups * 4));
     unsigned long long* kn = static_cast<unsigned long long*>(take(static_cast<size_t>(p->B) * 8));
     unsigned long long* ac = static_cast<unsigned long long*>(take(static_cast<size_t>(p->B) * 8));
     int32_t* de = static_cast<int32_t*>(take(static_cast<size_t>(p->B) * 4));
-    if (ws) { ws->At = At; ws->Ad = Ad; ws->cfin = cf; ws->Wfin = Wf; ws->a0 = a0; ws->atest = at; ws->mt = mt; ws->md = md; ws->queue = qu; ws->qctl = qc; ws->mailbox = mb; ws->known = kn; ws->acc = ac; ws->decided = de; }
+    if (ws) { ws->At = At; ws->Ad = Ad; ws->cfin = cf; ws->a0 = a0; ws->atest = at; ws->queue = qu; ws->qctl = qc; ws->mailbox = mb; ws->known = kn; ws->acc = ac; ws->decided = de; }
     return off < 256 ? 256 : off;
 }
 

@@ -231,6 +231,30 @@ def test_many_small_tasks_through_the_queue(method):
         assert np.array_equal(full[key], lean[key])
 
 
+@pytest.mark.parametrize("method", [SI, TV])
+def test_more_trees_than_workgroups_delayed_tree(method):
+    """More trees than workgroups, a trunk before the branching node: Traversal then handles the
+    first branch before the rest of the branching node (which gets a second task only if
+    nothing in that branch is accepted), SpecInfer runs only the nodes on the accepted path.
+    Decisions of every tree against the oracle, and against the run that computes every node."""
+    announce("many trees, delayed tree", METHOD_NAME[method])
+    cfg = workloads.Config("many_delayed", B=700, V=1536, K=3, L1=2, L2=2, dtype="bf16", T=0.9,
+                           methods=[method], draft_sigma=1.5, target_sigma=1.0, seed=808)
+    inputs = workloads.make_inputs(cfg, "cuda")
+    host = workloads.to_host(inputs)
+    lean = run_library(inputs, cfg.T, method, debug=False)
+    assert lean["counters"][4] == 0
+    rep = compare_with_oracle(method, host, cfg.T, lean, check_debug=False)
+    print("[report]", rep, "counters", lean["counters"].tolist(), flush=True)
+    full = run_library(inputs, cfg.T, method, debug=True)
+    compare_with_oracle(method, host, cfg.T, full, trees=range(0, cfg.B, 35))
+    for key in ("accept_len", "path_nodes", "path_tokens", "bonus_token"):
+        assert np.array_equal(full[key], lean[key])
+    n_internal = 3 + 3                                   # root, trunk, branching node, first node of each branch
+    assert full["counters"][5] == cfg.B * n_internal     # every node task ran
+    assert lean["counters"][5] < full["counters"][5]     # not so when only decisions are wanted
+
+
 def test_out_of_range_tokens_are_counted_not_followed():
     announce("bad tokens")
     cfg = workloads.Config("badtok", B=3, V=500, K=2, L1=0, L2=2, dtype="f32", T=1.0,
