@@ -161,8 +161,9 @@ int mpv_fill_uniforms(uint64_t seed, int64_t count, float* d_u, void* hip_stream
 
 /* Per-launch timing for benchmarks (process-wide state, not thread-safe).
  * mpv_timing_enable(n > 0) creates n pairs of HIP events; from then on every
- * kernel mpv_verify launches is bracketed by two event records on the caller's
- * stream until n launches have been recorded.  mpv_timing_enable(0) turns it off
+ * kernel mpv_verify launches carries one pair, which the runtime stamps with the
+ * start and the end of that dispatch (nothing extra is put into the caller's
+ * stream), until n launches have been recorded.  mpv_timing_enable(0) turns it off
  * and destroys the events.  mpv_timing_read, called after the caller has
  * synchronised that stream, writes the elapsed milliseconds and the MPV_KERNEL_*
  * id of each recorded launch (HOST arrays of `capacity` entries), sets *count and

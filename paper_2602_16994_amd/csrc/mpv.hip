@@ -21,6 +21,7 @@
 // one possible history, so its test probability does not depend on the uniforms.
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <math.h>
 #include <stdint.h>
 #include <string.h>
@@ -1196,8 +1197,9 @@ static bool hip_ok(hipError_t e) {
     return false;
 }
 
-// Optional per-launch timing: when enabled, every kernel launched by mpv_verify is
-// bracketed by two hipEvents recorded on the caller's stream.
+// Optional per-launch timing: when enabled, every kernel launched by mpv_verify carries a pair
+// of hipEvents that the runtime stamps with the start and the end of that dispatch itself
+// (hipExtLaunchKernelGGL): no extra packet goes into the stream, the launches stay back to back.
 struct LaunchTimer {
     bool enabled = false;
     int capacity = 0, used = 0;
@@ -1207,20 +1209,17 @@ struct LaunchTimer {
 };
 static LaunchTimer g_timer;
 
-struct ScopedLaunch {
-    hipStream_t s;
-    int slot;
-    ScopedLaunch(int kernel_id, hipStream_t stream) : s(stream), slot(-1) {
-        if (g_timer.enabled && g_timer.used < g_timer.capacity) {
-            slot = g_timer.used++;
-            g_timer.kernel[slot] = kernel_id;
-            hip_ok(hipEventRecord(g_timer.start[slot], s));
-        }
+template <typename... Params, typename... Args>
+static void launch(int kernel_id, void (*kernel)(Params...), dim3 grid, dim3 block, hipStream_t s, Args... args) {
+    if (g_timer.enabled && g_timer.used < g_timer.capacity) {
+        const int slot = g_timer.used++;
+        g_timer.kernel[slot] = kernel_id;
+        hipExtLaunchKernelGGL(kernel, grid, block, 0, s, g_timer.start[slot], g_timer.stop[slot], 0,
+                              static_cast<Params>(args)...);
+    } else {
+        hipLaunchKernelGGL(kernel, grid, block, 0, s, static_cast<Params>(args)...);
     }
-    ~ScopedLaunch() {
-        if (slot >= 0) hip_ok(hipEventRecord(g_timer.stop[slot], s));
-    }
-};
+}
 
 struct Plan {
     TreeDesc tree;
@@ -1385,23 +1384,20 @@ static int launch_all(const mpv_problem* p, const Plan& plan, const Workspace& w
     {
         const int threads = 256;
         const int blocks = (max(p->B * p->N, MPV_MAX_NODES) + threads - 1) / threads;
-        ScopedLaunch t(MPV_KERNEL_INIT, s);
-        hipLaunchKernelGGL(init_kernel, dim3(blocks), dim3(threads), 0, s, q, tree, ws, a);
+        launch(MPV_KERNEL_INIT, init_kernel, dim3(blocks), dim3(threads), s, q, tree, ws, a);
     }
     if (tasks > 0) {
-        ScopedLaunch t(MPV_KERNEL_NODE_TASK, s);
         const dim3 grid(static_cast<unsigned>(wgs)), block(kTaskBlock);
         if (p->method == MPV_METHOD_SPECINFER) {
-            if (full) hipLaunchKernelGGL((node_task_kernel<E, MPV_METHOD_SPECINFER, true>), grid, block, 0, s, tree, q, ws, a);
-            else hipLaunchKernelGGL((node_task_kernel<E, MPV_METHOD_SPECINFER, false>), grid, block, 0, s, tree, q, ws, a);
+            if (full) launch(MPV_KERNEL_NODE_TASK, node_task_kernel<E, MPV_METHOD_SPECINFER, true>, grid, block, s, tree, q, ws, a);
+            else launch(MPV_KERNEL_NODE_TASK, node_task_kernel<E, MPV_METHOD_SPECINFER, false>, grid, block, s, tree, q, ws, a);
         } else {
-            if (full) hipLaunchKernelGGL((node_task_kernel<E, MPV_METHOD_TRAVERSAL, true>), grid, block, 0, s, tree, q, ws, a);
-            else hipLaunchKernelGGL((node_task_kernel<E, MPV_METHOD_TRAVERSAL, false>), grid, block, 0, s, tree, q, ws, a);
+            if (full) launch(MPV_KERNEL_NODE_TASK, node_task_kernel<E, MPV_METHOD_TRAVERSAL, true>, grid, block, s, tree, q, ws, a);
+            else launch(MPV_KERNEL_NODE_TASK, node_task_kernel<E, MPV_METHOD_TRAVERSAL, false>, grid, block, s, tree, q, ws, a);
         }
     }
     if (a.dbg_stats) {
-        ScopedLaunch t(MPV_KERNEL_DEBUG_STATS, s);
-        hipLaunchKernelGGL((debug_stats_kernel<E>), dim3(static_cast<unsigned>(p->B) * p->N), dim3(kTaskBlock), 0, s, tree, a);
+        launch(MPV_KERNEL_DEBUG_STATS, debug_stats_kernel<E>, dim3(static_cast<unsigned>(p->B) * p->N), dim3(kTaskBlock), s, tree, a);
     }
     return hip_ok(hipGetLastError()) ? MPV_OK : MPV_ERR_HIP;
 }

@@ -493,7 +493,10 @@ struct RetainedPair {
         }
     }
 
-    static constexpr int DIST = 6;              // slots of loads kept ahead of the compute in the first sweep
+#ifndef MPV_DIST
+#define MPV_DIST 6
+#endif
+    static constexpr int DIST = MPV_DIST;             // slots of loads kept ahead of the compute in the first sweep
 
     __device__ __forceinline__ void load_register_slot(int j) {
         rt[j] = load_raw_at_nt(bt, tid + j * BLOCK);
