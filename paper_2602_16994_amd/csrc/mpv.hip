@@ -770,6 +770,7 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(TreeDesc tree, Qu
             const unsigned long long known = known_before | settled_bits;
             wait_memory();
             const unsigned long long acc = ld_relaxed(&ws.acc[b]);
+            const int decided_before = ld_relaxed(&ws.decided[b]);      // issued with the load above: one round trip
             bool settled;
             if (a.lazy) {
                 const unsigned long long open = ~(known & ~acc);          // not known to be rejected
@@ -779,10 +780,10 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(TreeDesc tree, Qu
                 const unsigned long long all = (a.N >= 64) ? ~0ull : ((1ull << a.N) - 1ull);
                 settled = known == all;
             }
-            push_sample = settled && atomicCAS(&ws.decided[b], 0, 1) == 0;
+            push_sample = settled && decided_before == 0 && atomicCAS(&ws.decided[b], 0, 1) == 0;
             // only what is needed: once a tree is settled (here or by another task) the rest of
             // its node tasks are pointless
-            settled_tree = a.lazy && (settled || ld_relaxed(&ws.decided[b]) != 0);
+            settled_tree = a.lazy && (settled || decided_before != 0);
             // The subtree that was explored first has just turned out to be rejected as a whole
             // (this task supplied its last missing outcome): time for the rest of the node
             // where the tree branches.
