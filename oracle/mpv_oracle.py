@@ -26,6 +26,13 @@ What it computes (citations are to the paper's sections / algorithms):
   to the original Traversal paper beyond these properties is PARITY UNPINNED.
 * bonus token: inverse-CDF sample from the final residual (Algorithm 4, last
   two lines; Sec. 2 step 3 "correction token").
+* NSS and NaiveTree verification: the same top-down walk of Sec. 3.2 with the
+  NSS solver (App. B, Alg. 1: Y ~ p, draft tokens ignored) or the Naive solver
+  (App. B, Alg. 2: the first child is tested with min(1, p/q); otherwise
+  Y ~ (p-q)_+).  With these solvers the token the solver outputs can be one of
+  the other draft tokens: the walk then moves to that child (Sec. 3.2: "progress
+  to the child if t is among x_1..x_k, terminate otherwise"); with equal-token
+  siblings, to the first of them in list order.
 
 Conventions (each listed as a reading in the design notes):
 * accept iff u < a (strict), u in [0,1): a = 0 never accepts, a = 1 always.
@@ -33,7 +40,8 @@ Conventions (each listed as a reading in the design notes):
 * zero residual mass: the distribution is left unchanged; in Traversal the
   parent's weight becomes 1 if it was 1, else 0.
 * one uniform per node: u[n] (n >= 1) is used only for the test of node n;
-  u[0] draws the bonus token.
+  u[0] draws the bonus token.  NSS and NaiveTree draw a token at every node
+  they visit: the draw at node n uses u_draw[n], a second array.
 
 Three drivers share the same step functions:
 * verify_tree(...)          sample mode: consumes the uniforms.
@@ -49,6 +57,8 @@ import numpy as np
 
 SPECINFER = 0
 TRAVERSAL = 1
+NSS = 2
+NAIVE = 3
 
 
 # --------------------------------------------------------------------------
@@ -225,6 +235,59 @@ _RULES = {SPECINFER: specinfer_rule, TRAVERSAL: traversal_rule}
 
 
 # --------------------------------------------------------------------------
+# solvers whose output token can be another draft token: NSS and Naive, and the
+# walk that follows the drawn token (Sec. 3.2)
+# --------------------------------------------------------------------------
+
+def nss_solver(P, Q, xs, decide):
+    """NSS OTLP solver (App. B, Alg. 1): no test; Y is drawn from p."""
+    return None, np.array(P, dtype=np.float64)
+
+
+def naive_solver(P, Q, xs, decide):
+    """Naive OTLP solver (App. B, Alg. 2): only the first draft token is tested,
+    with min(1, p/q); otherwise Y is drawn from (p - q)_+ (normalised by the draw)."""
+    P = np.array(P, dtype=np.float64)
+    if xs:
+        x = xs[0]
+        if decide(0, _ratio(P[x], Q[x])):
+            return 0, P
+        r = np.maximum(P - Q, 0.0)
+        if np.sum(r) > 0.0:                     # zero mass: p = q, the test above cannot fail
+            P = r
+    return None, P
+
+
+_SOLVERS = {NSS: nss_solver, NAIVE: naive_solver}
+
+
+def token_walk(solver, children, tokens, p_of, q_of, decide, draw):
+    """Top-down walk (Sec. 3.2) for solvers whose output can be any token.
+
+    At node n the solver either accepts a child or hands back the (unnormalised)
+    vector Y is drawn from; draw(n, r) returns the drawn token.  If that token is
+    the token of a child (the first such child in list order) the walk moves
+    there, otherwise it ends.  A leaf has no draft tokens: Y ~ p, and the walk
+    ends.  Returns (stop_node, final_token, r_last): the node the walk ended in,
+    the token drawn there and the vector it was drawn from.
+    """
+    n = 0
+    while True:
+        ch = children[n]
+        xs = [int(tokens[c]) for c in ch]
+        i, r = solver(p_of(n), np.asarray(q_of(n), dtype=np.float64) if ch else None, xs,
+                      lambda i, a: decide(ch[i], a))
+        if i is not None:
+            n = ch[i]
+            continue
+        y = draw(n, r)
+        match = [c for c, x in zip(ch, xs) if x == y]
+        if not match:
+            return n, int(y), r
+        n = match[0]
+
+
+# --------------------------------------------------------------------------
 # drivers
 # --------------------------------------------------------------------------
 
@@ -242,29 +305,41 @@ class _RowCache:
         return self.rows[n]
 
 
-def verify_tree(method, parent, tokens, target_logits, draft_logits, T, u):
+def verify_tree(method, parent, tokens, target_logits, draft_logits, T, u, u_draw=None):
     """Sample mode for ONE tree.
 
     parent: [N] ints; tokens: [N] ints (tokens[0] ignored); target_logits,
     draft_logits: [N, V] arrays holding the exact stored logit values;
-    u: [N] uniforms in [0,1).  Returns a dict with
+    u: [N] uniforms in [0,1); u_draw: [N] more uniforms, needed by NSS and NAIVE
+    only (the draw at node n).  Returns a dict with
       stop_node, accept_len, path_nodes, path_tokens, bonus_token,
       residual (float64 [V], normalised), decisions [(node, a, u, accepted)],
       min_margin (smallest |a - u| over decisions with a < 1, or inf),
-      bonus_gap (see sample_index).
+      bonus_gap (see sample_index; the smallest over the draws of the walk),
+      draws [(node, token, gap)] (NSS and NAIVE: every draw of the walk).
     """
     children = children_lists(parent)
     p_of = _RowCache(target_logits, T)
     q_of = _RowCache(draft_logits, T)
     decisions = []
+    draws = []
 
     def decide(c, a):
         ok = bool(float(u[c]) < a)
         decisions.append((int(c), float(a), float(u[c]), ok))
         return ok
 
-    stop, P = _RULES[method](children, tokens, p_of, q_of, decide)
-    bonus, gap = sample_index(P, u[0])
+    if method in _SOLVERS:
+        def draw(n, r):
+            t, g = sample_index(r, u_draw[n])
+            draws.append((int(n), int(t), float(g)))
+            return t
+
+        stop, bonus, P = token_walk(_SOLVERS[method], children, tokens, p_of, q_of, decide, draw)
+        gap = min(g for (_, _, g) in draws)
+    else:
+        stop, P = _RULES[method](children, tokens, p_of, q_of, decide)
+        bonus, gap = sample_index(P, u[0])
     nodes = path_to(parent, stop)
     margins = [abs(a - uu) for (_, a, uu, _) in decisions]
     return {
@@ -277,13 +352,15 @@ def verify_tree(method, parent, tokens, target_logits, draft_logits, T, u):
         "decisions": decisions,
         "min_margin": min(margins) if margins else float("inf"),
         "bonus_gap": gap,
+        "draws": draws,
     }
 
 
-def verify_batch(method, parent, tokens, target_logits, draft_logits, T, u):
-    """Sample mode for a batch: tokens [B,N], logits [B,N,V], u [B,N]."""
+def verify_batch(method, parent, tokens, target_logits, draft_logits, T, u, u_draw=None):
+    """Sample mode for a batch: tokens [B,N], logits [B,N,V], u [B,N] (u_draw likewise)."""
     return [
-        verify_tree(method, parent, tokens[b], target_logits[b], draft_logits[b], T, u[b])
+        verify_tree(method, parent, tokens[b], target_logits[b], draft_logits[b], T, u[b],
+                    None if u_draw is None else u_draw[b])
         for b in range(len(tokens))
     ]
 
@@ -296,6 +373,8 @@ def enumerate_outcomes(method, parent, tokens, p_of, q_of):
     (prob, stop_node, P) whose probs sum to 1.
     """
     children = children_lists(parent)
+    if method in _SOLVERS:
+        return _enumerate_token_walk(_SOLVERS[method], children, tokens, p_of, q_of)
     rule = _RULES[method]
     outcomes = []
     pending = [[]]                      # decision scripts still to run
@@ -318,6 +397,46 @@ def enumerate_outcomes(method, parent, tokens, p_of, q_of):
         for i in range(len(script), len(taken)):
             if taken[i][0] < 1.0:       # the opposite branch has weight > 0
                 pending.append([d for (_, d) in taken[:i]] + [False])
+    return outcomes
+
+
+def _enumerate_token_walk(solver, children, tokens, p_of, q_of):
+    """Probability mode of token_walk: every test is branched as in
+    enumerate_outcomes, every draw into one branch per token of positive mass.
+    Returns (prob, stop_node, final_token) triples (the final token in place of
+    a distribution: here the draws are part of the walk)."""
+    outcomes = []
+    pending = [[]]                      # scripts of choices: booleans for tests, tokens for draws
+    while pending:
+        script = pending.pop()
+        made = []                       # (choice, its probability, choices not explored yet)
+
+        def decide(c, a, script=script, made=made):
+            i = len(made)
+            d = script[i] if i < len(script) else True
+            others = [False] if (i >= len(script) and a < 1.0) else []
+            made.append((d, float(a) if d else 1.0 - float(a), others))
+            return d
+
+        def draw(n, r, script=script, made=made):
+            i = len(made)
+            r = np.asarray(r, dtype=np.float64)
+            support = [int(t) for t in np.nonzero(r > 0)[0]]
+            y = script[i] if i < len(script) else support[0]
+            others = [t for t in support if t != y] if i >= len(script) else []
+            made.append((y, float(r[y] / np.sum(r)), others))
+            return y
+
+        stop, y, _ = token_walk(solver, children, tokens, p_of, q_of, decide, draw)
+        prob = 1.0
+        for _, w, _ in made:
+            prob *= w
+        if prob > 0.0:
+            outcomes.append((prob, int(stop), int(y)))
+        prefix = [m[0] for m in made]
+        for i in range(len(script), len(made)):
+            for other in made[i][2]:
+                pending.append(prefix[:i] + [other])
     return outcomes
 
 

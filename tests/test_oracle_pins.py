@@ -17,6 +17,7 @@ from oracle import mpv_oracle as orc
 
 GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
 METHODS = [orc.SPECINFER, orc.TRAVERSAL]
+TOKEN_WALK_METHODS = [orc.NSS, orc.NAIVE]          # the solver's output token may be another draft token
 
 
 # --------------------------------------------------------------------------
@@ -95,6 +96,10 @@ def output_distribution(method, parent, model):
             method, parent, tokens, lambda n: model.p[ctx[n]], lambda n: model.q[ctx[n]])
         assert abs(sum(pr for pr, _, _ in outcomes) - 1.0) < 1e-12
         for pr, stop, P in outcomes:
+            if method in TOKEN_WALK_METHODS:    # the draw is part of the walk: P is the final token
+                seq = ctx[stop] + (int(P),)
+                out[seq] = out.get(seq, 0.0) + tree_prob * pr
+                continue
             assert np.all(P >= 0) and abs(P.sum() - 1.0) < 1e-12
             for y in range(V):
                 if P[y] > 0:
@@ -131,7 +136,7 @@ LOSSLESS_SHAPES = [
 ]
 
 
-@pytest.mark.parametrize("method", METHODS)
+@pytest.mark.parametrize("method", METHODS + TOKEN_WALK_METHODS)
 @pytest.mark.parametrize("V,K,L1,L2", LOSSLESS_SHAPES)
 def test_T1_output_follows_target_distribution(method, V, K, L1, L2):
     rng = np.random.default_rng(1000 * V + 100 * K + 10 * L1 + L2)
@@ -149,9 +154,87 @@ def test_T1_irregular_tree_is_lossless_too():
     parent = [-1, 0, 0, 1, 1, 2]
     rng = np.random.default_rng(77)
     model = ContextModel(rng, 3, 2, zero_frac=0.2)
-    for method in METHODS:
+    for method in METHODS + TOKEN_WALK_METHODS:
         out = output_distribution(method, parent, model)
         assert losslessness_error(out, model, 3) < 1e-13
+
+
+# --------------------------------------------------------------------------
+# NSS and Naive: acceptance rates of App. C (Alg. 6, Alg. 7), reductions
+# --------------------------------------------------------------------------
+
+def walk_acceptance_rate(method, p, q, k):
+    """P(the walk leaves the root) on a depth-1 tree with k i.i.d. children from q, exactly."""
+    V = len(p)
+    parent = [-1] + [0] * k
+    rate = 0.0
+    for xs in itertools.product(range(V), repeat=k):
+        w = 1.0
+        for x in xs:
+            w *= q[x]
+        if w == 0.0:
+            continue
+        outs = orc.enumerate_outcomes(method, parent, (0,) + xs, lambda n: p, lambda n: q)
+        rate += w * sum(pr for pr, stop, _ in outs if stop != 0)
+    return rate
+
+
+@pytest.mark.parametrize("V,k", [(4, 1), (4, 2), (5, 3), (3, 4)])
+def test_nss_acceptance_rate_matches_appendix_C(V, k):
+    # App. C, "NSS Acceptance": sum_t p(t) (1 - (1 - q(t))^k)
+    rng = np.random.default_rng(31 * V + k)
+    p, q = random_dist(rng, V, 0.2), random_dist(rng, V)
+    want = float(np.sum(p * (1.0 - (1.0 - q) ** k)))
+    assert abs(walk_acceptance_rate(orc.NSS, p, q, k) - want) < 1e-13
+
+
+@pytest.mark.parametrize("V,k", [(4, 1), (4, 2), (5, 3), (3, 4)])
+def test_naive_acceptance_rate_matches_appendix_C(V, k):
+    # App. C, "Naive Acceptance": sum min(p,q) + sum (p-q)_+ (1 - (1-q)^(k-1))
+    rng = np.random.default_rng(57 * V + k)
+    p, q = random_dist(rng, V, 0.2), random_dist(rng, V)
+    want = float(np.sum(np.minimum(p, q)) + np.sum(np.maximum(p - q, 0.0) * (1.0 - (1.0 - q) ** (k - 1))))
+    assert abs(walk_acceptance_rate(orc.NAIVE, p, q, k) - want) < 1e-13
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_naive_on_a_single_path_decides_as_specinfer(seed):
+    # App. B: SpecInfer (and SpecTr) reduce to Naive when k = 1.  Same tests, same residual; with the
+    # draw uniform of the stopping node set to SpecInfer's bonus uniform, the same bonus token.
+    rng = np.random.default_rng(500 + seed)
+    V, L = 9, 4
+    parent = list(range(-1, L))
+    zt, zd = rng.normal(size=(L + 1, V)), rng.normal(size=(L + 1, V))
+    tokens = np.concatenate([[0], rng.integers(V, size=L)])
+    u = rng.random(L + 1)
+    si = orc.verify_tree(orc.SPECINFER, parent, tokens, zt, zd, 0.9, u)
+    nv = orc.verify_tree(orc.NAIVE, parent, tokens, zt, zd, 0.9, u, np.full(L + 1, u[0]))
+    assert nv["stop_node"] == si["stop_node"] and nv["bonus_token"] == si["bonus_token"]
+    assert [d[:2] for d in nv["decisions"]] == [d[:2] for d in si["decisions"]]
+    np.testing.assert_allclose(nv["residual"], si["residual"], atol=1e-15)
+
+
+def test_nss_ignores_the_draft_distribution_and_follows_drawn_tokens():
+    # App. B, Alg. 1: Y ~ p whatever q is; Sec. 3.2: the walk follows Y if it is a child's token
+    rng = np.random.default_rng(9)
+    V = 6
+    parent = [-1, 0, 0, 1, 2]
+    zt = rng.normal(size=(5, V))
+    tokens = np.array([0, 2, 4, 1, 3])
+    u, ud = rng.random(5), rng.random(5)
+    a = orc.verify_tree(orc.NSS, parent, tokens, zt, rng.normal(size=(5, V)), 1.0, u, ud)
+    b = orc.verify_tree(orc.NSS, parent, tokens, zt, rng.normal(size=(5, V)), 1.0, u, ud)
+    assert a["stop_node"] == b["stop_node"] and a["bonus_token"] == b["bonus_token"] and not a["decisions"]
+    # replay by hand: draw at the root from p(root), move while the drawn token is a child's token
+    n = 0
+    ch = orc.children_lists(parent)
+    while True:
+        y, _ = orc.sample_index(scipy.special.softmax(zt[n]), ud[n])
+        nxt = [c for c in ch[n] if tokens[c] == y]
+        if not nxt:
+            break
+        n = nxt[0]
+    assert (a["stop_node"], a["bonus_token"]) == (n, y)
 
 
 # --------------------------------------------------------------------------
