@@ -19,6 +19,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0      # MI355X published peak
+METHOD_LABEL = {0: "SpecInfer", 1: "Traversal", 2: "NSS", 3: "Naive"}
 
 
 def parse_profile_traffic(path):
@@ -50,8 +51,9 @@ def cpu_baseline(cfg, inputs, method, budget_s=20.0):
         zt = inputs["target"][b].float().cpu().numpy()
         zd = inputs["draft"][b].float().cpu().numpy()
         u = inputs["uniforms"][b].cpu().numpy()
+        ud = inputs["draw_uniforms"][b].cpu().numpy()
         t0 = time.perf_counter()
-        orc.verify_tree(method, parent, tok, zt, zd, cfg.T, u)
+        orc.verify_tree(method, parent, tok, zt, zd, cfg.T, u, ud)
         t_total += time.perf_counter() - t0
         done += 1
         b = (b + 1) % cfg.B
@@ -71,7 +73,8 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="v152k_root")
-    ap.add_argument("--method", default=None, help="specinfer | traversal (default: the workload's)")
+    ap.add_argument("--method", default=None,
+                    help="specinfer | traversal | nss | naive (default: the workload's)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-launch-timing", action="store_true",
                     help="do not bracket the library's launches with HIP events")
@@ -93,13 +96,14 @@ def main():
     if args.method is None:
         method = cfg.methods[-1]
     else:
-        method = {"specinfer": 0, "traversal": 1}[args.method]
+        method = {"specinfer": 0, "traversal": 1, "nss": 2, "naive": 3}[args.method]
     inputs = workloads.make_inputs(cfg, "cuda:0")
     torch.cuda.synchronize()
 
     def step(out=None):
         return mpv.mpv_verify(inputs["parent"], inputs["tokens"], inputs["target"], inputs["draft"],
-                              cfg.T, inputs["uniforms"], method, debug=False, out=out)
+                              cfg.T, inputs["uniforms"], method, debug=False, out=out,
+                              draw_uniforms=inputs["draw_uniforms"])
 
     if args.calibration_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0").fill_(1)
@@ -177,8 +181,8 @@ def main():
         "config": {"workload": f"{cfg.name}: B={cfg.B} trees, V={cfg.V}, "
                                f"{'root' if cfg.L1 == 0 else 'delayed'} expansion K={cfg.K} L1={cfg.L1} L2={cfg.L2} "
                                f"({cfg.N} nodes/tree), {cfg.dtype} logits, T={cfg.T}, "
-                               f"{'Traversal' if method == 1 else 'SpecInfer'} verification",
-                   "method": "traversal" if method == 1 else "specinfer",
+                               f"{METHOD_LABEL[method]} verification",
+                   "method": {0: "specinfer", 1: "traversal", 2: "nss", 3: "naive"}[method],
                    "logit_dtype": cfg.dtype},
         "trees_per_s": cfg.B / (ms_per_step * 1e-3),
         "dense_input_GBps_equivalent": cfg.B * (cfg.N + n_internal) * cfg.V * cfg.elem_bytes / (ms_per_step * 1e-3) / 1e9,

@@ -30,11 +30,21 @@
  *                         is rejected the node's weight a and distribution P become
  *                         S/(S+1-a) and (a*P - q)_+/S with S = sum (a*P - q)_+.
  *                         The root is always accepted when reached.
+ *   MPV_METHOD_NSS        top-down walk of Sec. 3.2 with the NSS solver of App. B,
+ *                         Alg. 1: at every node a token is drawn from p; if it is
+ *                         the token of a child the walk moves there (to the first
+ *                         such child in list order), otherwise it ends and the
+ *                         drawn token is the bonus token.  Draft logits are unused.
+ *   MPV_METHOD_NAIVE      the same walk with the Naive solver of App. B, Alg. 2: the
+ *                         first child x is accepted with min(1, p(x)/q(x)); otherwise
+ *                         a token is drawn from (p - q)_+ and followed as above.
  *
  * Randomness: the caller supplies one uniform in [0,1) per node and tree.
  * uniforms[b,n] (n >= 1) is used only by the test of node n ("accept iff u < a");
  * uniforms[b,0] draws the bonus token by inverse CDF in vocabulary order
  * (smallest t whose cumulative residual mass exceeds u times the total).
+ * NSS and NAIVE draw a token at every node they visit: the draw at node n uses
+ * draw_uniforms[b,n], a second array of the same shape.
  *
  * All calls are thread-compatible, not thread-safe per stream.  No call
  * allocates or frees device memory or synchronises the device.
@@ -49,7 +59,7 @@
 extern "C" {
 #endif
 
-#define MPV_ABI_VERSION 1
+#define MPV_ABI_VERSION 2
 
 /* limits (larger requests return MPV_ERR_UNSUPPORTED) */
 #define MPV_MAX_NODES    64   /* nodes per tree, root included            */
@@ -58,6 +68,8 @@ extern "C" {
 
 #define MPV_METHOD_SPECINFER 0
 #define MPV_METHOD_TRAVERSAL 1
+#define MPV_METHOD_NSS       2
+#define MPV_METHOD_NAIVE     3
 
 #define MPV_DTYPE_F32  0      /* IEEE binary32 logits                      */
 #define MPV_DTYPE_BF16 1      /* bfloat16 logits (upper half of binary32)  */
@@ -72,7 +84,7 @@ extern "C" {
 #define MPV_ERR_BAD_METHOD      -5
 #define MPV_ERR_BAD_DTYPE       -6
 #define MPV_ERR_WORKSPACE       -7   /* workspace NULL, misaligned or too small       */
-#define MPV_ERR_UNSUPPORTED     -8   /* beyond MPV_MAX_*                              */
+#define MPV_ERR_UNSUPPORTED     -8   /* beyond MPV_MAX_*; stats / edge_probs with NSS, NAIVE */
 #define MPV_ERR_HIP             -9   /* a HIP call failed; see mpv_last_hip_error()   */
 #define MPV_ERR_ALIGNMENT      -10   /* a logit base pointer is not element-aligned   */
 
@@ -108,6 +120,8 @@ typedef struct mpv_buffers {
     float* edge_probs;             /* [B,N,2] p(x_n), q(x_n) under the parent's softmax; n=0: 1,1 */
     float* accept_prob;            /* [B,N] probability node n is tested with when reached; n=0: 1 */
     float* final_residual;         /* [B,V] normalised distribution the bonus token is drawn from */
+    /* input of MPV_METHOD_NSS and MPV_METHOD_NAIVE only (else ignored, may be NULL) */
+    const float*   draw_uniforms;  /* [B,N] in [0,1): the draw at node n                          */
 } mpv_buffers;
 
 #define MPV_COUNTER_NEAR_TIE_ACCEPT 0  /* tests on the accepted walk with |a - u| < 1e-6     */

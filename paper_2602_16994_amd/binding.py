@@ -13,6 +13,8 @@ from typing import Optional
 
 MPV_METHOD_SPECINFER = 0
 MPV_METHOD_TRAVERSAL = 1
+MPV_METHOD_NSS = 2
+MPV_METHOD_NAIVE = 3
 MPV_DTYPE_F32 = 0
 MPV_DTYPE_BF16 = 1
 
@@ -43,7 +45,7 @@ class _Buffers(ctypes.Structure):
     _fields_ = [(name, ctypes.c_void_p) for name in (
         "target_logits", "draft_logits", "tokens", "uniforms",
         "accept_len", "path_nodes", "path_tokens", "bonus_token", "counters",
-        "stats", "edge_probs", "accept_prob", "final_residual")]
+        "stats", "edge_probs", "accept_prob", "final_residual", "draw_uniforms")]
 
 
 _lib = None
@@ -148,13 +150,15 @@ class VerifyResult:
 
 
 def mpv_verify(parent, tokens, target_logits, draft_logits, temperature, uniforms, method,
-               max_depth=None, debug=False, out=None, workspace=None, stream=None):
+               max_depth=None, debug=False, out=None, workspace=None, stream=None, draw_uniforms=None):
     """Enqueue one batched verification on the current (or given) torch stream.
 
     parent: list of N ints (host).  tokens int32 [B,N], target_logits / draft_logits
     [B,N,V] float32 or bfloat16, uniforms float32 [B,N]: CUDA tensors, contiguous.
     Returns a VerifyResult of CUDA tensors (asynchronous; synchronise before reading
     on the host).  `out` may be a previous VerifyResult whose buffers are reused.
+    draw_uniforms float32 [B,N] is needed by MPV_METHOD_NSS and MPV_METHOD_NAIVE (the draw at
+    each visited node); with those methods debug=True provides accept_prob and final_residual only.
     """
     import torch
     from .trees import tree_depth
@@ -169,6 +173,10 @@ def mpv_verify(parent, tokens, target_logits, draft_logits, temperature, uniform
         raise ValueError("target and draft logits must have the same shape and dtype")
     if tuple(tokens.shape) != (B, N) or tuple(uniforms.shape) != (B, N):
         raise ValueError("tokens and uniforms must be [B,N]")
+    if draw_uniforms is not None:
+        if (not draw_uniforms.is_cuda or not draw_uniforms.is_contiguous() or draw_uniforms.dtype != torch.float32
+                or tuple(draw_uniforms.shape) != (B, N)):
+            raise ValueError("draw_uniforms must be a contiguous float32 CUDA tensor [B,N]")
     if max_depth is None:
         max_depth = max(1, tree_depth(list(parent)) if len(parent) == N and N > 0 else 1)
     dev = target_logits.device
@@ -184,8 +192,9 @@ def mpv_verify(parent, tokens, target_logits, draft_logits, temperature, uniform
         )
         if debug:
             f32 = dict(dtype=torch.float32, device=dev)
-            out.stats = torch.empty(B, N, 4, **f32)
-            out.edge_probs = torch.empty(B, N, 2, **f32)
+            if method in (MPV_METHOD_SPECINFER, MPV_METHOD_TRAVERSAL):
+                out.stats = torch.empty(B, N, 4, **f32)
+                out.edge_probs = torch.empty(B, N, 2, **f32)
             out.accept_prob = torch.empty(B, N, **f32)
             out.final_residual = torch.empty(B, V, **f32)
     lib = load_library()
@@ -205,7 +214,8 @@ def mpv_verify(parent, tokens, target_logits, draft_logits, temperature, uniform
     bufs = _Buffers(ptr(target_logits), ptr(draft_logits), ptr(tokens), ptr(uniforms),
                     ptr(out.accept_len), ptr(out.path_nodes), ptr(out.path_tokens),
                     ptr(out.bonus_token), ptr(out.counters),
-                    ptr(out.stats), ptr(out.edge_probs), ptr(out.accept_prob), ptr(out.final_residual))
+                    ptr(out.stats), ptr(out.edge_probs), ptr(out.accept_prob), ptr(out.final_residual),
+                    ptr(draw_uniforms))
     rc = lib.mpv_verify(ctypes.byref(prob), ctypes.byref(bufs), ptr(workspace),
                         ctypes.c_size_t(workspace.numel()), _stream_ptr(stream))
     if rc != 0:

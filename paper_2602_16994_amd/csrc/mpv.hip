@@ -93,6 +93,7 @@ struct Workspace {
     unsigned long long* known;
     unsigned long long* acc;
     int32_t* decided;
+    int32_t* cur;        // [B] token-following walks: the node the walk has reached
 };
 
 struct Args {
@@ -100,6 +101,7 @@ struct Args {
     const void* zd;
     const int32_t* tokens;
     const float* uniforms;
+    const float* draw_uniforms;      // walks that draw a token at every node they visit
     int32_t* accept_len;
     int32_t* path_nodes;
     int32_t* path_tokens;
@@ -112,6 +114,8 @@ struct Args {
     int32_t B, N, V, max_depth;
     float k32;       // float(log2(e)/T)
     float invT;
+    int32_t walk;    // 0: the rule names the stopping node (SpecInfer, Traversal); a token is drawn at every
+                     // visited node and followed if it is a child's: 1 from p (NSS), 2 after the Naive test
     int32_t lazy;    // compute only what the rule needs (off when per-node debug output is wanted: then every node task runs)
     int32_t stagger_ticks;   // start-up spread of the persistent workgroups, in 10 ns ticks per step (8 steps)
 };
@@ -154,6 +158,7 @@ __global__ void init_kernel(QueuePlan q, TreeDesc tree, Workspace ws, Args a) {
         ws.known[i] = 1ull << (a.N - 1);
         ws.acc[i] = 1ull << (a.N - 1);
         ws.decided[i] = 0;
+        ws.cur[i] = 0;
     }
     if (i < a.B * a.N) {
         reinterpret_cast<unsigned long long*>(ws.a0)[i] = kNotReady;
@@ -415,10 +420,11 @@ __device__ int next_task(const Workspace& ws, const Args& a) {
 
 // ------------------------------------------------------------------ node task
 
-// (defined below) walk and bonus token of tree b, by the whole workgroup
+// (defined below) walk and bonus token of tree b, or one draw of a token-following walk, by the
+// whole workgroup; returns the task that follows from it (-1: none; the same in every lane)
 template <class E, int METHOD>
-__device__ void sample_task(const TreeDesc& tree, const Workspace& ws, const Args& a, int b,
-                            float* tile_sum, double* scratch);
+__device__ int sample_task(const TreeDesc& tree, const Workspace& ws, const Args& a, int b,
+                           float* tile_sum, double* scratch);
 
 template <class E, int METHOD, bool FULL>
 __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(TreeDesc tree, QueuePlan q,
@@ -478,8 +484,15 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(TreeDesc tree, Qu
             asked = true;
         }
         float* tile_mass = FULL ? reinterpret_cast<float*>(lds_t) : own_tile_mass;
-        sample_task<E, METHOD>(tree, ws, a, task - a.B * a.N, tile_mass, scratch);
-        if (threadIdx.x == 0) atomicAdd(&ws.qctl[1], 1);
+        const int next = sample_task<E, METHOD>(tree, ws, a, task - a.B * a.N, tile_mass, scratch);
+        if (next >= 0) own_task = next;               // a token-following walk goes on
+        if (threadIdx.x == 0) {
+            if (next >= 0) {
+                (void)atomicAdd(&ws.qctl[0], 1);
+                wait_memory();                        // counted (and the walk's position written) first
+            }
+            atomicAdd(&ws.qctl[1], 1);
+        }
         continue;
     }
     // a node task, or the resumed task of the node where the tree branches
@@ -696,10 +709,18 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(TreeDesc tree, Qu
             break;
         }
 
+        if (METHOD == MPV_METHOD_SPECINFER && a.walk == 2 && threadIdx.x == 0 &&
+            fabs(w_child - static_cast<double>(ch_u[j])) < 1e-6)
+            atomicAdd(&a.counters[MPV_COUNTER_NEAR_TIE_ACCEPT], 1u);     // (the other rules count these in their walk)
         // SpecInfer moves into the first child it accepts: later children and this node's
         // residual are not needed (the same in every lane: no lane is left behind)
         if (METHOD == MPV_METHOD_SPECINFER && a.lazy && child_accepted) {
             next_node = cn;
+            break;
+        }
+        // Naive (App. B, Alg. 2) tests the first child only; the token then drawn comes from (p - q)_+
+        if (METHOD == MPV_METHOD_SPECINFER && a.walk == 2) {
+            c = 1.0;
             break;
         }
 
@@ -748,6 +769,7 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(TreeDesc tree, Qu
         if (METHOD == MPV_METHOD_SPECINFER && a.lazy) {
             // the walk ends here (no child accepted) or in the accepted leaf
             push_sample = next_node < 0 || tree.nchild[next_node] == 0;
+            if (a.walk) st_relaxed(&ws.cur[b], next_node >= 0 ? next_node : n);     // where the next token is drawn
             wait_memory();                            // results written through before anything else is started
         } else {
             // Announce the outcomes settled here, then see whether the tree's outcome is settled:
@@ -837,6 +859,20 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(TreeDesc tree, Qu
 //   Traversal: nodes are tested in depth-first post-order; the first accepted one
 //     wins, the root is accepted unconditionally.
 // Returns the stopping node (the same value in every lane) and writes the path.
+// accepted length and path of a walk that ended in `stop` (one lane)
+__device__ __forceinline__ void write_path(const TreeDesc& tree, const Args& a, int b, int stop) {
+    const size_t base = static_cast<size_t>(b) * a.N;
+    const int len = tree.depth[stop];
+    a.accept_len[b] = len;
+    int32_t* pn = a.path_nodes + static_cast<size_t>(b) * a.max_depth;
+    int32_t* pt = a.path_tokens + static_cast<size_t>(b) * a.max_depth;
+    for (int i = len; i < a.max_depth; ++i) { pn[i] = -1; pt[i] = -1; }
+    for (int n = stop, i = len - 1; n > 0; n = tree.parent[n], --i) {
+        pn[i] = n;
+        pt[i] = a.tokens[base + n];
+    }
+}
+
 template <int METHOD>
 __device__ __forceinline__ int walk_wave(const TreeDesc& tree, const Workspace& ws, const Args& a, int b) {
     const int lane = threadIdx.x & (kWave - 1);
@@ -876,15 +912,7 @@ __device__ __forceinline__ int walk_wave(const TreeDesc& tree, const Workspace& 
         }
     }
     if (lane == 0) {
-        const int len = tree.depth[stop];
-        a.accept_len[b] = len;
-        int32_t* pn = a.path_nodes + static_cast<size_t>(b) * a.max_depth;
-        int32_t* pt = a.path_tokens + static_cast<size_t>(b) * a.max_depth;
-        for (int i = len; i < a.max_depth; ++i) { pn[i] = -1; pt[i] = -1; }
-        for (int n = stop, i = len - 1; n > 0; n = tree.parent[n], --i) {
-            pn[i] = n;
-            pt[i] = a.tokens[base + n];
-        }
+        write_path(tree, a, b, stop);
         const int nn = __popcll(nearm & tested);
         if (nn) atomicAdd(&a.counters[MPV_COUNTER_NEAR_TIE_ACCEPT], static_cast<unsigned>(nn));
     }
@@ -934,8 +962,8 @@ struct ResidualTile {
 // tile_sum: kMaxTiles floats of LDS; scratch: 2 doubles per wave.  Everything it reads from
 // the workspace was written by node tasks of this launch (see st_shared_f64).
 template <class E, int METHOD>
-__device__ void sample_task(const TreeDesc& tree, const Workspace& ws, const Args& a, int b,
-                            float* tile_sum, double* scratch) {
+__device__ int sample_task(const TreeDesc& tree, const Workspace& ws, const Args& a, int b,
+                           float* tile_sum, double* scratch) {
     using T = typename E::T;
     constexpr int NW = kSampleBlock / kWave;
     constexpr int PER_LANE = ResidualTile<E>::PER_LANE;
@@ -943,11 +971,13 @@ __device__ void sample_task(const TreeDesc& tree, const Workspace& ws, const Arg
     __shared__ int sh_tile;
     __shared__ double sh_before, sh_total, sh_target;
 
-    __shared__ int sh_stop;
+    __shared__ int sh_stop, sh_next;
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
     if (wave == 0) {
-        const int stop = walk_wave<METHOD>(tree, ws, a, b);
-        if (lane == 0) sh_stop = stop;
+        // where the token is drawn: the node the rule stops in, or the node a token-following
+        // walk has reached
+        const int stop = a.walk ? ld_relaxed(&ws.cur[b]) : walk_wave<METHOD>(tree, ws, a, b);
+        if (lane == 0) { sh_stop = stop; sh_next = -1; }
     }
     __syncthreads();
     const int n = sh_stop;
@@ -958,8 +988,8 @@ __device__ void sample_task(const TreeDesc& tree, const Workspace& ws, const Arg
     const int ntiles = (V + TILE - 1) / TILE;
 
     double At, Ad = 0.0, c = 0.0;
-    if (tree.nchild[n] == 0) {
-        // a leaf: its target row has not been touched yet; the bonus is drawn from p itself
+    if (tree.nchild[n] == 0 || a.walk == 1) {
+        // a leaf (its target row has not been touched yet) or an NSS draw: from p itself
         RowStatsF<E> f;
         f.t.init(); f.k32 = a.k32;
         sweep_row<E, kSampleBlock, 4 * kTaskUnroll>(zt, V, f);     // alone on its compute unit: many loads in flight
@@ -1040,7 +1070,8 @@ __device__ void sample_task(const TreeDesc& tree, const Workspace& ws, const Arg
         for (int t = t0; t < t1; ++t) run += tile_sum[t];
         const double incl = wave_inclusive_scan(run);
         const double total = __shfl(incl, kWave - 1, kWave);
-        const double target = static_cast<double>(a.uniforms[static_cast<size_t>(b) * a.N]) * total;
+        const float u_draw = a.walk ? a.draw_uniforms[bn] : a.uniforms[static_cast<size_t>(b) * a.N];
+        const double target = static_cast<double>(u_draw) * total;
         const unsigned long long hit = __ballot(incl > target && run > 0.0);
         int owner = hit ? (__ffsll(static_cast<long long>(hit)) - 1) : -1;
         if (owner < 0) {           // rounding only: last lane that has mass
@@ -1101,8 +1132,32 @@ __device__ void sample_task(const TreeDesc& tree, const Workspace& ws, const Arg
             int tok = t * TILE + lane * PER_LANE + found;
             if (tok >= V) tok = V - 1;
             a.bonus[b] = tok;
+            sh_tile = tok;                            // (the tile number is no longer needed)
             const double gap = fmin(fabs(rem - lo), fabs(hi - rem));
             if (gap < 1e-6 * sh_total) atomicAdd(&a.counters[MPV_COUNTER_NEAR_TIE_BONUS], 1u);
+        }
+        if (a.walk) {
+            // Sec. 3.2: if the drawn token is a child's token the walk moves to that child (the
+            // first such child in list order), otherwise it ends here
+            __builtin_amdgcn_wave_barrier();
+            const int tok = *reinterpret_cast<volatile int*>(&sh_tile);
+            const int k = tree.nchild[n];
+            bool same = false;
+            if (lane < k) same = a.tokens[static_cast<size_t>(b) * a.N + tree.child_list[tree.child_off[n] + lane]] == tok;
+            const unsigned long long m = __ballot(same);
+            if (m) {
+                const int to = tree.child_list[tree.child_off[n] + __ffsll(static_cast<long long>(m)) - 1];
+                if (lane == 0) {
+                    st_relaxed(&ws.cur[b], to);
+                    // Naive tests the first child of an inner node before it draws there; NSS and leaves draw at once
+                    sh_next = (a.walk == 2 && tree.nchild[to] > 0) ? b * a.N + to : a.B * a.N + b;
+                }
+            } else {
+                if (lane == 0) write_path(tree, a, b, n);
+                if (a.dbg_accept && lane < a.N)
+                    a.dbg_accept[static_cast<size_t>(b) * a.N + lane] =
+                        lane == 0 ? 1.f : static_cast<float>(ld_shared_f64(&ws.atest[static_cast<size_t>(b) * a.N + lane]));
+            }
         }
     }
 
@@ -1120,6 +1175,8 @@ __device__ void sample_task(const TreeDesc& tree, const Workspace& ws, const Arg
             }
         }
     }
+    __syncthreads();
+    return sh_next;
 }
 
 // ------------------------------------------------------------------ stand-alone row statistics
@@ -1233,7 +1290,7 @@ static int validate(const mpv_problem* p, Plan* plan) {
     if (!p) return MPV_ERR_NULL;
     if (p->B < 0 || p->N < 1 || p->V < 1) return MPV_ERR_BAD_SHAPE;
     if (p->N > MPV_MAX_NODES || p->V > MPV_MAX_VOCAB) return MPV_ERR_UNSUPPORTED;
-    if (p->method != MPV_METHOD_SPECINFER && p->method != MPV_METHOD_TRAVERSAL) return MPV_ERR_BAD_METHOD;
+    if (p->method < MPV_METHOD_SPECINFER || p->method > MPV_METHOD_NAIVE) return MPV_ERR_BAD_METHOD;
     if (p->logit_dtype != MPV_DTYPE_F32 && p->logit_dtype != MPV_DTYPE_BF16) return MPV_ERR_BAD_DTYPE;
     if (!(p->temperature > 0.0f) || !isfinite(p->temperature)) return MPV_ERR_BAD_TEMPERATURE;
     if (!p->parent) return MPV_ERR_NULL;
@@ -1312,7 +1369,8 @@ static size_t carve(const mpv_problem* p, void* base, Workspace* ws) {
     unsigned long long* kn = static_cast<unsigned long long*>(take(static_cast<size_t>(p->B) * 8));
     unsigned long long* ac = static_cast<unsigned long long*>(take(static_cast<size_t>(p->B) * 8));
     int32_t* de = static_cast<int32_t*>(take(static_cast<size_t>(p->B) * 4));
-    if (ws) { ws->At = At; ws->Ad = Ad; ws->cfin = cf; ws->a0 = a0; ws->atest = at; ws->queue = qu; ws->qctl = qc; ws->mailbox = mb; ws->known = kn; ws->acc = ac; ws->decided = de; }
+    int32_t* cu = static_cast<int32_t*>(take(static_cast<size_t>(p->B) * 4));
+    if (ws) { ws->At = At; ws->Ad = Ad; ws->cfin = cf; ws->a0 = a0; ws->atest = at; ws->queue = qu; ws->qctl = qc; ws->mailbox = mb; ws->known = kn; ws->acc = ac; ws->decided = de; ws->cur = cu; }
     return off < 256 ? 256 : off;
 }
 
@@ -1352,13 +1410,13 @@ static int launch_all(const mpv_problem* p, const Plan& plan, const Workspace& w
     const bool all_up_front = (p->method == MPV_METHOD_SPECINFER && !a.lazy);
     for (int kk = MPV_MAX_CHILDREN; kk >= 1; --kk)
         for (int n = 0; n < p->N; ++n)
-            if (tree.nchild[n] == kk && (all_up_front || n == 0))
+            if (tree.nchild[n] == kk && (all_up_front || n == 0) && a.walk != 1)      // NSS has no node tasks
                 q.init_slot[n] = prequeued[tree.cls[n]]++;
     for (int c = 0; c < q.nclass; ++c) {
         q.init_tail[c] = prequeued[c] * p->B;
         q.init_total += q.init_tail[c];
     }
-    if (tree.nchild[0] == 0) {
+    if (tree.nchild[0] == 0 || a.walk == 1) {
         q.root_is_leaf = 1;
         q.init_tail[0] = p->B;
         q.init_total = p->B;
@@ -1389,7 +1447,7 @@ static int launch_all(const mpv_problem* p, const Plan& plan, const Workspace& w
     }
     if (tasks > 0) {
         const dim3 grid(static_cast<unsigned>(wgs)), block(kTaskBlock);
-        if (p->method == MPV_METHOD_SPECINFER) {
+        if (p->method != MPV_METHOD_TRAVERSAL) {      // NSS and Naive are variants of the top-down kernel
             if (full) launch(MPV_KERNEL_NODE_TASK, node_task_kernel<E, MPV_METHOD_SPECINFER, true>, grid, block, s, tree, q, ws, a);
             else launch(MPV_KERNEL_NODE_TASK, node_task_kernel<E, MPV_METHOD_SPECINFER, false>, grid, block, s, tree, q, ws, a);
         } else {
@@ -1421,7 +1479,7 @@ const char* mpv_strerror(int code) {
         case MPV_ERR_BAD_METHOD: return "unknown method id";
         case MPV_ERR_BAD_DTYPE: return "unknown logit dtype";
         case MPV_ERR_WORKSPACE: return "workspace is NULL, not 256-byte aligned or too small";
-        case MPV_ERR_UNSUPPORTED: return "problem exceeds MPV_MAX_NODES / MPV_MAX_CHILDREN / MPV_MAX_VOCAB";
+        case MPV_ERR_UNSUPPORTED: return "problem exceeds MPV_MAX_NODES / MPV_MAX_CHILDREN / MPV_MAX_VOCAB, or a debug output this method does not provide was requested";
         case MPV_ERR_HIP: return "a HIP call failed (see mpv_last_hip_error)";
         case MPV_ERR_ALIGNMENT: return "logit base pointers must be 16-byte aligned";
         default: return "unknown error code";
@@ -1457,14 +1515,18 @@ int mpv_verify(const mpv_problem* problem, const mpv_buffers* buf, void* workspa
     mpv::Workspace ws;
     mpv::carve(problem, workspace, &ws);
     mpv::Args a;
+    const int walk = problem->method == MPV_METHOD_NSS ? 1 : problem->method == MPV_METHOD_NAIVE ? 2 : 0;
+    if (walk && !buf->draw_uniforms) return MPV_ERR_NULL;
+    if (walk && (buf->stats || buf->edge_probs)) return MPV_ERR_UNSUPPORTED;
     a.zt = buf->target_logits; a.zd = buf->draft_logits; a.tokens = buf->tokens; a.uniforms = buf->uniforms;
+    a.draw_uniforms = buf->draw_uniforms; a.walk = walk;
     a.accept_len = buf->accept_len; a.path_nodes = buf->path_nodes; a.path_tokens = buf->path_tokens;
     a.bonus = buf->bonus_token; a.counters = buf->counters;
     a.dbg_stats = buf->stats; a.dbg_edge = buf->edge_probs; a.dbg_accept = buf->accept_prob; a.dbg_resid = buf->final_residual;
     a.B = problem->B; a.N = problem->N; a.V = problem->V; a.max_depth = problem->max_depth;
     a.k32 = static_cast<float>(1.4426950408889634 / static_cast<double>(problem->temperature));
     a.invT = 1.0f / problem->temperature;
-    a.lazy = (buf->edge_probs == nullptr && buf->accept_prob == nullptr && buf->stats == nullptr) ? 1 : 0;
+    a.lazy = (walk || (buf->edge_probs == nullptr && buf->accept_prob == nullptr && buf->stats == nullptr)) ? 1 : 0;
     {
         // start-up spread of the persistent workgroups: about the time one workgroup needs to
         // read a row pair when every compute unit is reading (its share of ~6.3 TB/s), only

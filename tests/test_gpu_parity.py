@@ -16,7 +16,9 @@ from tests.parity_util import check_properties, compare_with_oracle, result_to_h
 pytestmark = pytest.mark.gpu
 
 SI, TV = mpv.MPV_METHOD_SPECINFER, mpv.MPV_METHOD_TRAVERSAL
-METHOD_NAME = {SI: "specinfer", TV: "traversal"}
+NSS, NAIVE = mpv.MPV_METHOD_NSS, mpv.MPV_METHOD_NAIVE
+METHOD_NAME = {SI: "specinfer", TV: "traversal", NSS: "nss", NAIVE: "naive"}
+ALL_METHODS = [SI, TV, NSS, NAIVE]
 
 
 def announce(*a):
@@ -25,7 +27,7 @@ def announce(*a):
 
 def run_library(inputs, T, method, debug=True):
     res = mpv.mpv_verify(inputs["parent"], inputs["tokens"], inputs["target"], inputs["draft"], T,
-                         inputs["uniforms"], method, debug=debug)
+                         inputs["uniforms"], method, debug=debug, draw_uniforms=inputs.get("draw_uniforms"))
     torch.cuda.synchronize()
     return result_to_host(res)
 
@@ -50,7 +52,7 @@ def run_case(cfg, method, trees=None, debug=True):
 
 # ---------------------------------------------------------------- the five configurations
 
-@pytest.mark.parametrize("method", [SI, TV])
+@pytest.mark.parametrize("method", ALL_METHODS)
 def test_config1_tiny(method):
     run_case(workloads.CONFIGS["tiny"], method)
 
@@ -60,7 +62,7 @@ def test_config2_v32k_root_specinfer():
     run_case(workloads.scaled(workloads.CONFIGS["v32k_root"], B=6), SI)
 
 
-@pytest.mark.parametrize("method", [SI, TV])
+@pytest.mark.parametrize("method", ALL_METHODS)
 def test_config3_v128k_delayed(method):
     run_case(workloads.scaled(workloads.CONFIGS["v128k_delayed"], B=4), method)
 
@@ -69,9 +71,28 @@ def test_config4_v152k_root_traversal_small_batch():
     run_case(workloads.scaled(workloads.CONFIGS["v152k_root"], B=3), TV)
 
 
-@pytest.mark.parametrize("method", [SI, TV])
+@pytest.mark.parametrize("method", ALL_METHODS)
 def test_config5_v262k_delayed(method):
     run_case(workloads.scaled(workloads.CONFIGS["v262k_delayed"], B=2), method)
+
+
+@pytest.mark.parametrize("method", [NSS, NAIVE])
+def test_config2_and_4_token_following_walks(method):
+    # the two root-expanded configurations with the solvers whose output token may be another draft token
+    run_case(workloads.scaled(workloads.CONFIGS["v32k_root"], B=6), method)
+    run_case(workloads.scaled(workloads.CONFIGS["v152k_root"], B=3), method)
+
+
+@pytest.mark.parametrize("method", [NSS, NAIVE])
+@pytest.mark.parametrize("V,dtype", [(12, "bf16"), (37, "f32")])
+def test_drawn_tokens_are_followed_in_small_vocabularies(method, V, dtype):
+    """With a dozen tokens the drawn token is a child's token most of the time (and equal-token
+    siblings are common): the walk must move to the first such child, draw again there, and so on."""
+    cfg = workloads.Config(f"follow_V{V}", B=300, V=V, K=4, L1=0, L2=3, dtype=dtype, T=1.1,
+                           methods=[method], draft_sigma=1.0, target_sigma=0.6, seed=4242 + V)
+    rep, got = run_case(cfg, method)
+    assert rep["mean_accept_len"] > 0.1               # the walks do get somewhere
+    assert np.any(got["accept_len"] >= 2)             # and some follow more than one token
 
 
 def test_config4_full_size_sampled_trees():
@@ -124,7 +145,7 @@ RAGGED = [
 ]
 
 
-@pytest.mark.parametrize("method", [SI, TV])
+@pytest.mark.parametrize("method", ALL_METHODS)
 @pytest.mark.parametrize("V,dtype,K,L1,L2,B,T", RAGGED)
 def test_ragged_shapes(method, V, dtype, K, L1, L2, B, T):
     cfg = workloads.Config(f"ragged_V{V}_{dtype}_K{K}_{L1}_{L2}", B=B, V=V, K=K, L1=L1, L2=L2, dtype=dtype,
@@ -132,7 +153,7 @@ def test_ragged_shapes(method, V, dtype, K, L1, L2, B, T):
     run_case(cfg, method)
 
 
-@pytest.mark.parametrize("method", [SI, TV])
+@pytest.mark.parametrize("method", ALL_METHODS)
 def test_root_only_tree(method):
     # N = 1: nothing to verify, the bonus token is a plain sample from p(.|root)
     cfg = workloads.Config("root_only", B=5, V=5000, K=1, L1=0, L2=0, dtype="bf16", T=1.0,
@@ -141,7 +162,7 @@ def test_root_only_tree(method):
     assert np.all(got["accept_len"] == 0)
 
 
-@pytest.mark.parametrize("method", [SI, TV])
+@pytest.mark.parametrize("method", ALL_METHODS)
 def test_irregular_tree(method):
     parent = [-1, 0, 0, 1, 1, 2, 5, 5, 0, 8, 9]
     announce("irregular tree", METHOD_NAME[method])
@@ -167,7 +188,7 @@ def test_identical_models_accept_first_leaf(method):
     compare_with_oracle(method, workloads.to_host(inputs), cfg.T, got)
 
 
-@pytest.mark.parametrize("method", [SI, TV])
+@pytest.mark.parametrize("method", ALL_METHODS)
 def test_duplicate_sibling_tokens_and_masked_vocabulary(method):
     # equal tokens under one parent are separate nodes; -inf logits have zero mass
     announce("duplicates + -inf", METHOD_NAME[method])
@@ -186,7 +207,7 @@ def test_duplicate_sibling_tokens_and_masked_vocabulary(method):
             assert not (100 <= t < 200)
 
 
-@pytest.mark.parametrize("method", [SI, TV])
+@pytest.mark.parametrize("method", ALL_METHODS)
 @pytest.mark.parametrize("T", [0.2, 1.0])
 def test_peaked_rows_long_vocabulary(method, T):
     """Rows kept on chip use a per-lane reference fixed at the start of the sweep;
@@ -210,7 +231,7 @@ def test_peaked_rows_long_vocabulary(method, T):
     print("[report]", rep, flush=True)
 
 
-@pytest.mark.parametrize("method", [SI, TV])
+@pytest.mark.parametrize("method", ALL_METHODS)
 def test_many_small_tasks_through_the_queue(method):
     """Far more node tasks than workgroups, short rows, a bushy tree: the task queue hands out
     thousands of tasks, Traversal appends children level after level.  Decisions of every tree

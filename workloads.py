@@ -22,6 +22,8 @@ from paper_2602_16994_amd.trees import delayed_tree
 
 SPECINFER = 0
 TRAVERSAL = 1
+NSS = 2
+NAIVE = 3
 
 
 @dataclass
@@ -107,7 +109,8 @@ def _rows(cfg, rows, gen, device):
 
 
 def make_inputs(cfg, device="cuda", trees_per_chunk=8):
-    """Returns dict(parent, tokens[B,N] int32, target[B,N,V], draft[B,N,V], uniforms[B,N] f32).
+    """Returns dict(parent, tokens[B,N] int32, target[B,N,V], draft[B,N,V], uniforms[B,N] f32,
+    draw_uniforms[B,N] f32 (the second set, for the methods that draw a token at every node)).
 
     Logits are generated chunk by chunk in float32 and stored in cfg's dtype.
     """
@@ -138,16 +141,22 @@ def make_inputs(cfg, device="cuda", trees_per_chunk=8):
     gen_u = torch.Generator(device=dev)
     gen_u.manual_seed(cfg.seed + 2)
     uniforms = torch.rand(B, N, generator=gen_u, device=dev, dtype=torch.float32)
+    gen_d = torch.Generator(device=dev)
+    gen_d.manual_seed(cfg.seed + 3)
+    draw_uniforms = torch.rand(B, N, generator=gen_d, device=dev, dtype=torch.float32)
     return {"parent": list(cfg.parent), "tokens": tokens, "target": target, "draft": draft,
-            "uniforms": uniforms}
+            "uniforms": uniforms, "draw_uniforms": draw_uniforms}
 
 
 def to_host(inputs):
     """numpy copies for the oracle (bfloat16 widened to float32, which is exact)."""
-    return {
+    host = {
         "parent": inputs["parent"],
         "tokens": inputs["tokens"].cpu().numpy(),
         "target": inputs["target"].float().cpu().numpy(),
         "draft": inputs["draft"].float().cpu().numpy(),
         "uniforms": inputs["uniforms"].cpu().numpy(),
     }
+    if "draw_uniforms" in inputs:
+        host["draw_uniforms"] = inputs["draw_uniforms"].cpu().numpy()
+    return host
