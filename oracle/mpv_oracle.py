@@ -33,6 +33,10 @@ What it computes (citations are to the paper's sections / algorithms):
   the other draft tokens: the walk then moves to that child (Sec. 3.2: "progress
   to the child if t is among x_1..x_k, terminate otherwise"); with equal-token
   siblings, to the first of them in list order.
+* SpecTr verification: the same walk with the K-SEQ solver (App. B, Alg. 3):
+  division factor rho* = root of p_acc(rho) - rho*beta(rho) on [1,k] by binary
+  search (64 halvings: the paper gives no stopping rule), children tested in
+  list order with min(1, p/(rho* q)), then Y ~ (p - gamma*min(p/rho*, q))_+.
 
 Conventions (each listed as a reading in the design notes):
 * accept iff u < a (strict), u in [0,1): a = 0 never accepts, a = 1 always.
@@ -59,6 +63,7 @@ SPECINFER = 0
 TRAVERSAL = 1
 NSS = 2
 NAIVE = 3
+SPECTR = 4
 
 
 # --------------------------------------------------------------------------
@@ -258,7 +263,47 @@ def naive_solver(P, Q, xs, decide):
     return None, P
 
 
-_SOLVERS = {NSS: nss_solver, NAIVE: naive_solver}
+def spectr_beta(P, Q, rho):
+    """beta(rho) = sum_x min(p(x)/rho, q(x))  (App. B, SpecTr)."""
+    return float(np.sum(np.minimum(P / rho, Q)))
+
+
+def spectr_division_factor(P, Q, k):
+    """rho*: the root of rho -> p_acc(rho) - rho*beta(rho), p_acc = 1-(1-beta)^k, on [1,k].
+
+    The map is monotone decreasing with a value >= 0 at 1 and <= 0 at k (App. B); binary
+    search as the paper says, run until float64 is exhausted."""
+    lo, hi = 1.0, float(k)
+    for _ in range(64):
+        mid = 0.5 * (lo + hi)
+        b = spectr_beta(P, Q, mid)
+        if (1.0 - (1.0 - b) ** k) - mid * b > 0.0:
+            lo = mid
+        else:
+            hi = mid
+    return 0.5 * (lo + hi)
+
+
+def spectr_solver(P, Q, xs, decide):
+    """SpecTr OTLP solver, K-SEQ (App. B, Alg. 3), children in list order."""
+    P = np.array(P, dtype=np.float64)
+    k = len(xs)
+    if k == 0:
+        return None, P
+    rho = spectr_division_factor(P, Q, k)
+    beta = spectr_beta(P, Q, rho)
+    p_acc = 1.0 - (1.0 - beta) ** k
+    gamma = p_acc / beta if beta > 0.0 else 0.0
+    for i, x in enumerate(xs):
+        if decide(i, _ratio(P[x], rho * Q[x])):     # Alg. 3: rho* U <= p(x)/q(x)
+            return i, P
+    r = np.maximum(P - np.minimum(P / rho, Q) * gamma, 0.0)
+    if np.sum(r) > 0.0:
+        P = r
+    return None, P
+
+
+_SOLVERS = {NSS: nss_solver, NAIVE: naive_solver, SPECTR: spectr_solver}
 
 
 def token_walk(solver, children, tokens, p_of, q_of, decide, draw):

@@ -17,7 +17,7 @@ from oracle import mpv_oracle as orc
 
 GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
 METHODS = [orc.SPECINFER, orc.TRAVERSAL]
-TOKEN_WALK_METHODS = [orc.NSS, orc.NAIVE]          # the solver's output token may be another draft token
+TOKEN_WALK_METHODS = [orc.NSS, orc.NAIVE, orc.SPECTR]          # the solver's output token may be another draft token
 
 
 # --------------------------------------------------------------------------
@@ -195,6 +195,40 @@ def test_naive_acceptance_rate_matches_appendix_C(V, k):
     p, q = random_dist(rng, V, 0.2), random_dist(rng, V)
     want = float(np.sum(np.minimum(p, q)) + np.sum(np.maximum(p - q, 0.0) * (1.0 - (1.0 - q) ** (k - 1))))
     assert abs(walk_acceptance_rate(orc.NAIVE, p, q, k) - want) < 1e-13
+
+
+@pytest.mark.parametrize("V,k", [(4, 1), (4, 2), (5, 3), (3, 4)])
+def test_spectr_acceptance_rate_matches_appendix_C(V, k):
+    # App. C, "SpecTr Acceptance": p_acc + (1 - p_acc) sum_t p_res(t) (1 - (1 - r(t))^k),
+    # r = (q - p/rho*)_+ / (1 - beta)
+    rng = np.random.default_rng(91 * V + k)
+    p, q = random_dist(rng, V, 0.2), random_dist(rng, V)
+    rho = orc.spectr_division_factor(p, q, k)
+    beta = orc.spectr_beta(p, q, rho)
+    p_acc = 1.0 - (1.0 - beta) ** k
+    # rho* solves p_acc(rho) = rho beta(rho) (App. B)
+    assert abs(p_acc - rho * beta) < 1e-12 and 1.0 <= rho <= k
+    res = np.maximum(p - np.minimum(p / rho, q) * (p_acc / beta), 0.0)
+    res = res / res.sum() if res.sum() > 0 else res
+    r = np.maximum(q - p / rho, 0.0) / (1.0 - beta)
+    want = p_acc + (1.0 - p_acc) * float(np.sum(res * (1.0 - (1.0 - r) ** k)))
+    assert abs(walk_acceptance_rate(orc.SPECTR, p, q, k) - want) < 1e-12
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_spectr_with_one_draft_token_is_naive(seed):
+    # App. B: "This OTLP solver precisely reduces to the Naive solver when k = 1"
+    rng = np.random.default_rng(700 + seed)
+    V, L = 9, 4
+    parent = list(range(-1, L))
+    zt, zd = rng.normal(size=(L + 1, V)), rng.normal(size=(L + 1, V))
+    tokens = np.concatenate([[0], rng.integers(V, size=L)])
+    u, ud = rng.random(L + 1), rng.random(L + 1)
+    a = orc.verify_tree(orc.NAIVE, parent, tokens, zt, zd, 0.8, u, ud)
+    b = orc.verify_tree(orc.SPECTR, parent, tokens, zt, zd, 0.8, u, ud)
+    assert (a["stop_node"], a["bonus_token"]) == (b["stop_node"], b["bonus_token"])
+    np.testing.assert_allclose([d[1] for d in a["decisions"]], [d[1] for d in b["decisions"]], atol=1e-15)
+    np.testing.assert_allclose(a["residual"], b["residual"], atol=1e-14)
 
 
 @pytest.mark.parametrize("seed", range(10))
