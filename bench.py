@@ -19,7 +19,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0      # MI355X published peak
-METHOD_LABEL = {0: "SpecInfer", 1: "Traversal", 2: "NSS", 3: "Naive"}
+METHOD_LABEL = {0: "SpecInfer", 1: "Traversal", 2: "NSS", 3: "Naive", 4: "SpecTr"}
 
 
 def parse_profile_traffic(path):
@@ -74,7 +74,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="v152k_root")
     ap.add_argument("--method", default=None,
-                    help="specinfer | traversal | nss | naive (default: the workload's)")
+                    help="specinfer | traversal | nss | naive | spectr (default: the workload's)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-launch-timing", action="store_true",
                     help="do not bracket the library's launches with HIP events")
@@ -96,7 +96,7 @@ def main():
     if args.method is None:
         method = cfg.methods[-1]
     else:
-        method = {"specinfer": 0, "traversal": 1, "nss": 2, "naive": 3}[args.method]
+        method = {"specinfer": 0, "traversal": 1, "nss": 2, "naive": 3, "spectr": 4}[args.method]
     inputs = workloads.make_inputs(cfg, "cuda:0")
     torch.cuda.synchronize()
 
@@ -182,7 +182,7 @@ def main():
                                f"{'root' if cfg.L1 == 0 else 'delayed'} expansion K={cfg.K} L1={cfg.L1} L2={cfg.L2} "
                                f"({cfg.N} nodes/tree), {cfg.dtype} logits, T={cfg.T}, "
                                f"{METHOD_LABEL[method]} verification",
-                   "method": {0: "specinfer", 1: "traversal", 2: "nss", 3: "naive"}[method],
+                   "method": {0: "specinfer", 1: "traversal", 2: "nss", 3: "naive", 4: "spectr"}[method],
                    "logit_dtype": cfg.dtype},
         "trees_per_s": cfg.B / (ms_per_step * 1e-3),
         "dense_input_GBps_equivalent": cfg.B * (cfg.N + n_internal) * cfg.V * cfg.elem_bytes / (ms_per_step * 1e-3) / 1e9,

@@ -38,12 +38,17 @@
  *   MPV_METHOD_NAIVE      the same walk with the Naive solver of App. B, Alg. 2: the
  *                         first child x is accepted with min(1, p(x)/q(x)); otherwise
  *                         a token is drawn from (p - q)_+ and followed as above.
+ *   MPV_METHOD_SPECTR     the same walk with the SpecTr solver (K-SEQ) of App. B, Alg. 3:
+ *                         with rho* the root of 1 - (1 - beta(rho))^k = rho beta(rho) on [1,k],
+ *                         beta(rho) = sum min(p/rho, q), the children are tested in list order
+ *                         with min(1, p(x)/(rho* q(x))); otherwise a token is drawn from
+ *                         (p - gamma min(p/rho*, q))_+, gamma = (1 - (1 - beta)^k)/beta.
  *
  * Randomness: the caller supplies one uniform in [0,1) per node and tree.
  * uniforms[b,n] (n >= 1) is used only by the test of node n ("accept iff u < a");
  * uniforms[b,0] draws the bonus token by inverse CDF in vocabulary order
  * (smallest t whose cumulative residual mass exceeds u times the total).
- * NSS and NAIVE draw a token at every node they visit: the draw at node n uses
+ * NSS, NAIVE and SPECTR draw a token at every node they visit: the draw at node n uses
  * draw_uniforms[b,n], a second array of the same shape.
  *
  * All calls are thread-compatible, not thread-safe per stream.  No call
@@ -70,6 +75,7 @@ extern "C" {
 #define MPV_METHOD_TRAVERSAL 1
 #define MPV_METHOD_NSS       2
 #define MPV_METHOD_NAIVE     3
+#define MPV_METHOD_SPECTR    4
 
 #define MPV_DTYPE_F32  0      /* IEEE binary32 logits                      */
 #define MPV_DTYPE_BF16 1      /* bfloat16 logits (upper half of binary32)  */
@@ -84,7 +90,7 @@ extern "C" {
 #define MPV_ERR_BAD_METHOD      -5
 #define MPV_ERR_BAD_DTYPE       -6
 #define MPV_ERR_WORKSPACE       -7   /* workspace NULL, misaligned or too small       */
-#define MPV_ERR_UNSUPPORTED     -8   /* beyond MPV_MAX_*; stats / edge_probs with NSS, NAIVE */
+#define MPV_ERR_UNSUPPORTED     -8   /* beyond MPV_MAX_*; stats / edge_probs with methods >= 2 */
 #define MPV_ERR_HIP             -9   /* a HIP call failed; see mpv_last_hip_error()   */
 #define MPV_ERR_ALIGNMENT      -10   /* a logit base pointer is not element-aligned   */
 
@@ -120,7 +126,7 @@ typedef struct mpv_buffers {
     float* edge_probs;             /* [B,N,2] p(x_n), q(x_n) under the parent's softmax; n=0: 1,1 */
     float* accept_prob;            /* [B,N] probability node n is tested with when reached; n=0: 1 */
     float* final_residual;         /* [B,V] normalised distribution the bonus token is drawn from */
-    /* input of MPV_METHOD_NSS and MPV_METHOD_NAIVE only (else ignored, may be NULL) */
+    /* input of MPV_METHOD_NSS, MPV_METHOD_NAIVE and MPV_METHOD_SPECTR only (else ignored, may be NULL) */
     const float*   draw_uniforms;  /* [B,N] in [0,1): the draw at node n                          */
 } mpv_buffers;
 

@@ -284,6 +284,26 @@ def spectr_division_factor(P, Q, k):
     return 0.5 * (lo + hi)
 
 
+def spectr_conditioning(P, Q, k, rho):
+    """|d ln rho* / d ln beta|: how much a relative error in the sum beta moves the root.
+
+    From f(rho) = 1 - (1 - beta(rho))^k - rho*beta(rho) with beta(rho) scaled by (1 + e):
+    d rho*/d e = -(df/dbeta * beta) / f'(rho).  Large when rho* is close to 1 and p is close
+    to q (f is then nearly flat).  Used by the parity tests to turn the accuracy of a
+    float32 sum into a tolerance on SpecTr's test probabilities; no verification step uses it.
+    """
+    if k <= 1:
+        return 0.0
+    beta = spectr_beta(P, Q, rho)
+    df_dbeta = k * (1.0 - beta) ** (k - 1) - rho
+    low = np.asarray(P) / rho < np.asarray(Q)                     # where min picks p/rho
+    dbeta_drho = -float(np.sum(np.asarray(P)[low])) / (rho * rho)
+    f_prime = df_dbeta * dbeta_drho - beta
+    if f_prime == 0.0:
+        return float("inf")
+    return abs(df_dbeta * beta / (f_prime * rho))
+
+
 def spectr_solver(P, Q, xs, decide):
     """SpecTr OTLP solver, K-SEQ (App. B, Alg. 3), children in list order."""
     P = np.array(P, dtype=np.float64)

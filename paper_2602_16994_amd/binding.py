@@ -15,6 +15,7 @@ MPV_METHOD_SPECINFER = 0
 MPV_METHOD_TRAVERSAL = 1
 MPV_METHOD_NSS = 2
 MPV_METHOD_NAIVE = 3
+MPV_METHOD_SPECTR = 4
 MPV_DTYPE_F32 = 0
 MPV_DTYPE_BF16 = 1
 
@@ -157,7 +158,7 @@ def mpv_verify(parent, tokens, target_logits, draft_logits, temperature, uniform
     [B,N,V] float32 or bfloat16, uniforms float32 [B,N]: CUDA tensors, contiguous.
     Returns a VerifyResult of CUDA tensors (asynchronous; synchronise before reading
     on the host).  `out` may be a previous VerifyResult whose buffers are reused.
-    draw_uniforms float32 [B,N] is needed by MPV_METHOD_NSS and MPV_METHOD_NAIVE (the draw at
+    draw_uniforms float32 [B,N] is needed by MPV_METHOD_NSS, MPV_METHOD_NAIVE and MPV_METHOD_SPECTR (the draw at
     each visited node); with those methods debug=True provides accept_prob and final_residual only.
     """
     import torch

@@ -45,9 +45,11 @@ struct TreeDesc {
     int32_t rank[MPV_MAX_NODES];         // position of the node in postorder
     int32_t sub_lo[MPV_MAX_NODES];       // the node's subtree is postorder[sub_lo[n] .. rank[n]]
     int32_t cls[MPV_MAX_NODES];          // priority class of the node's task (see QueuePlan)
+    int32_t class_off[8];                // QueuePlan::off again, for the kernels that read the tables from memory
 };
 
 constexpr int kMaxClasses = 4;
+static_assert(kMaxClasses + 1 <= 8, "TreeDesc::class_off is too short");
 
 // The task queue is one first-in-first-out queue per priority class; a free workgroup is
 // given the oldest task of the lowest class that has one.  Class 0: the nodes from the root down
@@ -76,7 +78,8 @@ struct QueuePlan {
 struct Workspace {
     double* At;      // log2-partition of the target row (internal nodes)
     double* Ad;      // same for the draft row
-    double* cfin;    // c of the node's final state (all children rejected)
+    double* cfin;    // c of the node's final state (all children rejected); SpecTr: the division factor rho*
+    double* aux;     // SpecTr: gamma = p_acc / beta of the node
     double* a0;      // Traversal: weight the node starts with (kNotReady until its parent's task publishes it)
     double* atest;   // probability the node is tested with
     int32_t* queue;      // entry = tree * N + node (node task) or B * N + tree (sampling task), -1 = not written yet
@@ -94,6 +97,7 @@ struct Workspace {
     unsigned long long* acc;
     int32_t* decided;
     int32_t* cur;        // [B] token-following walks: the node the walk has reached
+    TreeDesc* tree;      // the tree tables, written by init_kernel for the kernel that follows
 };
 
 struct Args {
@@ -115,7 +119,8 @@ struct Args {
     float k32;       // float(log2(e)/T)
     float invT;
     int32_t walk;    // 0: the rule names the stopping node (SpecInfer, Traversal); a token is drawn at every
-                     // visited node and followed if it is a child's: 1 from p (NSS), 2 after the Naive test
+                     // visited node and followed if it is a child's: 1 from p (NSS), 2 after the Naive test,
+                     // 3 after the SpecTr tests
     int32_t lazy;    // compute only what the rule needs (off when per-node debug output is wanted: then every node task runs)
     int32_t stagger_ticks;   // start-up spread of the persistent workgroups, in 10 ns ticks per step (8 steps)
 };
@@ -143,49 +148,67 @@ constexpr int kMaxWorkgroups = kWave * kWorkerSlots;
 
 // ------------------------------------------------------------------ init
 
+// Grid: x covers the trees (and the few per-launch words), y the nodes, so that every table
+// lookup by node has a workgroup-uniform index.
 __global__ void init_kernel(QueuePlan q, TreeDesc tree, Workspace ws, Args a) {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < MPV_COUNTER_COUNT) a.counters[i] = 0u;
-    if (i == 0) { ws.qctl[0] = q.init_total; ws.qctl[1] = 0; ws.qctl[2] = 0; ws.qctl[3] = 0; ws.qctl[4 + 2 * kMaxClasses] = 0; }
-    if (i < kMaxClasses) {
-        ws.qctl[4 + i] = (i < q.nclass) ? q.init_tail[i] : 0;
-        ws.qctl[4 + kMaxClasses + i] = (i == 0) ? min(q.workers, q.init_tail[0]) : 0;
-    }
-    // every worker starts out waiting; the first class-0 entries are handed over below
-    if (i < kMaxWorkgroups && i >= q.init_tail[0]) ws.mailbox[i] = kMailboxWaiting;
-    if (i < a.B) {
-        // the root is never tested: it counts as accepted from the start
-        ws.known[i] = 1ull << (a.N - 1);
-        ws.acc[i] = 1ull << (a.N - 1);
-        ws.decided[i] = 0;
-        ws.cur[i] = 0;
-    }
-    if (i < a.B * a.N) {
-        reinterpret_cast<unsigned long long*>(ws.a0)[i] = kNotReady;
-        // a node no task ever reaches is tested with probability 0
-        ws.atest[i] = (i % a.N == 0) ? 1.0 : 0.0;
-        ws.cfin[i] = 0.0;
-        // queue: the prequeued node tasks, node-major inside their class (the same node of
-        // consecutive trees next to each other); everything else "not written yet"
-        if (i < q.off[q.nclass]) {
-            int c = 0;
-            while (c + 1 < q.nclass && i >= q.off[c + 1]) ++c;
-            if (i - q.off[c] >= q.init_tail[c]) ws.queue[i] = -1;
-        }
-        const int n = i / a.B, b = i % a.B;
-        if (q.init_slot[n] >= 0) {
-            const int slot = q.init_slot[n] * a.B + b;
-            ws.queue[q.off[tree.cls[n]] + slot] = b * a.N + n;
-            if (tree.cls[n] == 0 && slot < kMaxWorkgroups) ws.mailbox[slot] = b * a.N + n;
-        }
-        if (q.root_is_leaf && i < a.B) {
-            ws.queue[q.off[0] + i] = a.B * a.N + i;
-            if (i < kMaxWorkgroups) ws.mailbox[i] = a.B * a.N + i;
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;      // tree, or word number
+    const int n = blockIdx.y;
+    {   // the tree tables for the next kernel, a few words per workgroup (the word number is the
+        // same in every lane: scalar loads from the kernel arguments)
+        const int* src = reinterpret_cast<const int*>(&tree);
+        int* dst = reinterpret_cast<int*>(ws.tree);
+        const int groups = gridDim.x * gridDim.y;
+        for (int w = blockIdx.y * gridDim.x + blockIdx.x; w < static_cast<int>(sizeof(TreeDesc) / sizeof(int)); w += groups) {
+            const int v = src[w];
+            if (threadIdx.x == 0) dst[w] = v;
         }
     }
-    if (i < a.B && a.dbg_edge) {
-        a.dbg_edge[static_cast<size_t>(i) * a.N * 2] = 1.f;
-        a.dbg_edge[static_cast<size_t>(i) * a.N * 2 + 1] = 1.f;
+    if (n == 0) {
+        if (i < MPV_COUNTER_COUNT) a.counters[i] = 0u;
+        if (i == 0) { ws.qctl[0] = q.init_total; ws.qctl[1] = 0; ws.qctl[2] = 0; ws.qctl[3] = 0; ws.qctl[4 + 2 * kMaxClasses] = 0; }
+        for (int c = 0; c < kMaxClasses; ++c)
+            if (i == 0) {
+                ws.qctl[4 + c] = (c < q.nclass) ? q.init_tail[c] : 0;
+                ws.qctl[4 + kMaxClasses + c] = (c == 0) ? min(q.workers, q.init_tail[0]) : 0;
+            }
+        // every worker starts out waiting; the first class-0 entries are handed over below
+        for (int w = i; w < kMaxWorkgroups; w += gridDim.x * blockDim.x)
+            if (w >= q.init_tail[0]) ws.mailbox[w] = kMailboxWaiting;
+        if (i < a.B) {
+            // the root is never tested: it counts as accepted from the start
+            ws.known[i] = 1ull << (a.N - 1);
+            ws.acc[i] = 1ull << (a.N - 1);
+            ws.decided[i] = 0;
+            ws.cur[i] = 0;
+            if (a.dbg_edge) {
+                a.dbg_edge[static_cast<size_t>(i) * a.N * 2] = 1.f;
+                a.dbg_edge[static_cast<size_t>(i) * a.N * 2 + 1] = 1.f;
+            }
+            if (q.root_is_leaf) {
+                ws.queue[q.off[0] + i] = a.B * a.N + i;
+                if (i < kMaxWorkgroups) ws.mailbox[i] = a.B * a.N + i;
+            }
+        }
+    }
+    if (i >= a.B) return;
+    const int b = i;
+    const size_t bn = static_cast<size_t>(b) * a.N + n;
+    reinterpret_cast<unsigned long long*>(ws.a0)[bn] = kNotReady;
+    // a node no task ever reaches is tested with probability 0
+    ws.atest[bn] = (n == 0) ? 1.0 : 0.0;
+    ws.cfin[bn] = 0.0;
+    // queue: the prequeued node tasks, node-major inside their class (the same node of
+    // consecutive trees next to each other); everything else "not written yet"
+    const int at = n * a.B + b;                               // this thread's share of the queue words
+    if (at < q.off[q.nclass]) {
+        int c = 0;
+        while (c + 1 < q.nclass && at >= q.off[c + 1]) ++c;
+        if (at - q.off[c] >= q.init_tail[c]) ws.queue[at] = -1;
+    }
+    if (q.init_slot[n] >= 0) {
+        const int slot = q.init_slot[n] * a.B + b;
+        ws.queue[q.off[tree.cls[n]] + slot] = b * a.N + n;
+        if (tree.cls[n] == 0 && slot < kMaxWorkgroups) ws.mailbox[slot] = b * a.N + n;
     }
 }
 
@@ -230,17 +253,18 @@ __device__ __forceinline__ void request_task(const Workspace& ws) {
 }
 
 // Append one task to class c (one lane).  The caller's earlier stores have been waited for.
-__device__ __forceinline__ void append_task(const QueuePlan& q, const Workspace& ws, int c, int entry) {
+__device__ __forceinline__ void append_task(const TreeDesc& tree, const Workspace& ws, int c, int entry) {
     (void)atomicAdd(&ws.qctl[0], 1);
     wait_memory();                                    // counted before it can be handed out (and finished)
     const int slot = atomicAdd(&ws.qctl[4 + c], 1);
-    if (slot < q.off[c + 1] - q.off[c]) st_relaxed(&ws.queue[q.off[c] + slot], entry);
+    const int first = tree.class_off[c], end = tree.class_off[c + 1];
+    if (slot < end - first) st_relaxed(&ws.queue[first + slot], entry);
 }
 
 // One round of dispatching, by a whole wave that holds the lock.  Lane c keeps the head of
 // class c in `head`; lane l looks after the workgroups l, l + 64, ...  Returns true when
 // everything is finished (the exit flag has been set).
-__device__ bool dispatch_round(const QueuePlan& q, const Workspace& ws, const Args& a, bool drop_settled,
+__device__ __forceinline__ bool dispatch_round(const QueuePlan& q, const TreeDesc& tree, const Workspace& ws, const Args& a, bool drop_settled,
                                int& head, long long t_begin) {
     __shared__ int sh_head[kMaxClasses], sh_before[kMaxClasses + 1];
     const int lane = threadIdx.x;
@@ -308,7 +332,7 @@ __device__ bool dispatch_round(const QueuePlan& q, const Workspace& ws, const Ar
         if (mine >= total_avail) continue;
         int c = 0;
         while (mine >= sh_before[c + 1]) ++c;         // ends: mine < total_avail = sh_before[nclass]
-        const int32_t* slot = &ws.queue[q.off[c] + sh_head[c] + (mine - sh_before[c])];
+        const int32_t* slot = &ws.queue[tree.class_off[c] + sh_head[c] + (mine - sh_before[c])];
         int entry = -1;
         for (int spin = 0; spin < kMaxSpins; ++spin) {          // the entry follows its tail count closely
             entry = ld_relaxed(slot);
@@ -339,7 +363,7 @@ __device__ bool dispatch_round(const QueuePlan& q, const Workspace& ws, const Ar
 // the answer).  `previous` is the task it took from the mailbox last: until the request has
 // reached memory the mailbox may still show it (no entry is ever handed out twice, so the
 // value is unambiguous).
-__device__ int acquire_task(const QueuePlan& q, const Workspace& ws, const Args& a, int previous, bool drop_settled) {
+__device__ __forceinline__ int acquire_task(const QueuePlan& q, const TreeDesc& tree, const Workspace& ws, const Args& a, int previous, bool drop_settled) {
     const int lane = threadIdx.x;
     int32_t* const box = &ws.mailbox[blockIdx.x];
     for (int spin = 0; spin < kMaxSpins; ++spin) {
@@ -361,7 +385,7 @@ __device__ int acquire_task(const QueuePlan& q, const Workspace& ws, const Args&
             const long long t_begin = wall_clock64();
             int result = kTaskExit;
             for (;;) {
-                const bool finished = dispatch_round(q, ws, a, drop_settled, head, t_begin);
+                const bool finished = dispatch_round(q, tree, ws, a, drop_settled, head, t_begin);
                 if (finished) break;
                 int mine = (lane == 0) ? ld_relaxed(box) : 0;
                 mine = __builtin_amdgcn_readfirstlane(mine);
@@ -392,43 +416,16 @@ __device__ __forceinline__ double ld_shared_f64(const double* p) {
         reinterpret_cast<const unsigned long long*>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)));
 }
 
-// Next task for this workgroup (called by one lane): tree*N+node (node task) or B*N+tree
-// (sampling task), or -1 when there is none left.
-__device__ int next_task(const Workspace& ws, const Args& a) {
-    const int h = atomicAdd(&ws.qctl[0], 1);
-    for (int spin = 0; spin < kMaxSpins; ++spin) {
-        const int t1 = ld_relaxed(&ws.qctl[1]);
-        if (h < t1) {
-            for (int spin2 = 0; spin2 < kMaxSpins; ++spin2) {
-                const int t = ld_relaxed(&ws.queue[h]);
-                if (t >= 0) return t;
-                __builtin_amdgcn_s_sleep(8);
-            }
-            break;
-        }
-        // the three reads must be performed in this order: t1 was needed for the branch above;
-        // wait for `completed` to arrive before the second read of tail is issued
-        const int c = ld_relaxed(&ws.qctl[2]);
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        const int t2 = ld_relaxed(&ws.qctl[1]);
-        if (c == t1 && t1 == t2) return -1;
-        __builtin_amdgcn_s_sleep(32);
-    }
-    atomicAdd(&a.counters[MPV_COUNTER_DEPENDENCY_TIMEOUT], 1u);     // must never happen
-    return -1;
-}
-
 // ------------------------------------------------------------------ node task
 
 // (defined below) walk and bonus token of tree b, or one draw of a token-following walk, by the
 // whole workgroup; returns the task that follows from it (-1: none; the same in every lane)
 template <class E, int METHOD>
-__device__ int sample_task(const TreeDesc& tree, const Workspace& ws, const Args& a, int b,
+__device__ __forceinline__ int sample_task(const TreeDesc& tree, const Workspace& ws, const Args& a, int b,
                            float* tile_sum, double* scratch);
 
 template <class E, int METHOD, bool FULL>
-__global__ __launch_bounds__(kTaskBlock) void node_task_kernel(TreeDesc tree, QueuePlan q,
-                                                              Workspace ws, Args a) {
+__global__ __launch_bounds__(kTaskBlock) void node_task_kernel(QueuePlan q, Workspace ws, Args a) {
     using T = typename E::T;
     __shared__ double scratch[2 * (kTaskBlock / kWave)];
     // rows too short to fill the on-chip slots are simply streamed again (they sit in L2)
@@ -443,6 +440,14 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(TreeDesc tree, Qu
     __shared__ float own_tile_mass[FULL ? 1 : kMaxTiles];
 
     __shared__ int sh_task;
+    // The tree tables are read from LDS, copied there from the workspace (init_kernel put them
+    // there), not from the kernel arguments: a table that is a kernel argument and is indexed
+    // with a value the compiler keeps in a vector register is copied, whole, into every lane's
+    // private memory.
+    __shared__ TreeDesc sh_tree;
+    for (int w = threadIdx.x; w < static_cast<int>(sizeof(TreeDesc) / sizeof(int)); w += kTaskBlock)
+        reinterpret_cast<int*>(&sh_tree)[w] = reinterpret_cast<const int*>(ws.tree)[w];
+    const TreeDesc& tree = sh_tree;               // the task loop starts with a barrier
     // Every task alternates a memory-bound sweep with compute-bound replays and all tasks of a
     // kind take the same time, so workgroups started together stay in step: all load at once
     // (sharing the memory bandwidth), then all leave memory idle.  Spreading their start over
@@ -468,7 +473,7 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(TreeDesc tree, Qu
                 if (threadIdx.x == 0) st_relaxed(&ws.mailbox[blockIdx.x], kMailboxWaiting);
                 wait_memory();
             }
-            const int t = acquire_task(q, ws, a, previous_task, drop_settled);
+            const int t = acquire_task(q, tree, ws, a, previous_task, drop_settled);
             if (threadIdx.x == 0) sh_task = t;
         }
         __syncthreads();
@@ -477,6 +482,7 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(TreeDesc tree, Qu
         asked = false;
         if (task == kTaskExit) break;
     }
+    task = __builtin_amdgcn_readfirstlane(task);
     if (task >= a.B * a.N && task < a.B * a.N + a.B) {
         // the tree's outcome is settled: walk and bonus token
         if (!asked) {
@@ -496,9 +502,10 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(TreeDesc tree, Qu
         continue;
     }
     // a node task, or the resumed task of the node where the tree branches
+    // (explicitly scalar: the tree tables below are kernel arguments, read with scalar loads)
     const bool resumed = task >= a.B * a.N + a.B;
-    const int b = resumed ? task - (a.B * a.N + a.B) : task / a.N;
-    const int n = resumed ? q.split_node : task % a.N;
+    const int b = __builtin_amdgcn_readfirstlane(resumed ? task - (a.B * a.N + a.B) : task / a.N);
+    const int n = __builtin_amdgcn_readfirstlane(resumed ? q.split_node : task % a.N);
     const size_t bn = static_cast<size_t>(b) * a.N + n;
     const T* zt = static_cast<const T*>(a.zt) + bn * a.V;
     const T* zd = static_cast<const T*>(a.zd) + bn * a.V;
@@ -549,7 +556,7 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(TreeDesc tree, Qu
         if (METHOD == MPV_METHOD_TRAVERSAL && a.lazy && k == 1 && !split_here && pf_idle != 0) {
             const int cn = tree.child_list[tree.child_off[n]];
             if (tree.nchild[cn] > 0) {
-                append_task(q, ws, tree.cls[cn], b * a.N + cn);
+                append_task(tree, ws, tree.cls[cn], b * a.N + cn);
                 ahead = 1;
             }
         }
@@ -618,6 +625,46 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(TreeDesc tree, Qu
     bool paused = false;
     bool own_given = false;                           // that child's task was queued after all (some workgroup is idle)
     const bool idle_seen = sh_idle != 0;
+    // SpecTr (App. B, Alg. 3): the division factor rho* is the root of
+    //   f(rho) = p_acc(rho) - rho beta(rho),  p_acc = 1 - (1 - beta)^k,  beta(rho) = sum_v min(p_v/rho, q_v)
+    // on [1, k]; f decreases, f(1) >= 0 >= f(k).  Each beta is one sweep over the pair on chip.  The
+    // paper's binary search is replaced by a bracketing secant search (Illinois rule): the same root,
+    // reached in about ten sweeps instead of thirty.
+    double sp_rho = 1.0, sp_gamma = 1.0;
+    if (METHOD == MPV_METHOD_SPECINFER && a.walk == 3) {
+        double lo = 1.0, hi = static_cast<double>(k), flo = 0.0, fhi = 0.0, beta = 0.0;
+        int side = 0;
+        const int evals = (k > 1) ? 40 : 1;
+        for (int it = 0; it < evals; ++it) {
+            double x;
+            if (it == 0) x = lo;
+            else if (it == 1) x = hi;
+            else x = uniform_f64((lo * fhi - hi * flo) / (fhi - flo));
+            const ResidualConsts rc = residual_consts(rt.A + log2(x), rd.A, 1.0);
+            MinMassRawF<E> f;
+            f.init();
+            f.k32 = k32; f.nAt = rc.nAt; f.nAd = rc.nAd; f.rho = uniform_f32(rc.rho);
+            pair.replay(f);
+            const double lane_mass = static_cast<double>(f.acc0) + static_cast<double>(f.acc1);
+            beta = uniform_f64(uniform_f64(rc.scale) * block_sum<kTaskBlock>(lane_mass, scratch));
+            const double fx = (1.0 - pow(1.0 - fmin(beta, 1.0), static_cast<double>(k))) - x * beta;
+            sp_rho = x;
+            if (it == 0) {
+                flo = fx;
+                if (!(fx > 0.0)) break;               // the root is 1 (also when k = 1)
+            } else if (it == 1) {
+                fhi = fx;
+                if (!(fx < 0.0)) break;               // the root is k
+            } else {
+                if (fx > 0.0) { lo = x; flo = fx; if (side == 1) fhi *= 0.5; side = 1; }
+                else if (fx < 0.0) { hi = x; fhi = fx; if (side == 2) flo *= 0.5; side = 2; }
+                else break;
+                if (hi - lo <= 1e-9 * hi || fabs(fx) <= 1e-12) break;
+            }
+        }
+        const double p_acc = 1.0 - pow(1.0 - fmin(beta, 1.0), static_cast<double>(k));
+        sp_gamma = beta > 0.0 ? p_acc / beta : 0.0;
+    }
     for (int j = 0; j < k; ++j) {
         // a resumed task repeats the arithmetic of the first child (whose task has long run)
         // to get at the residual that follows its rejection
@@ -640,6 +687,10 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(TreeDesc tree, Qu
             if (!(wa > 0.0) || !(Px > 0.0)) w_child = 0.0;
             else if (qx > 0.0) w_child = fmin(1.0, wa * Px / qx);
             else w_child = 1.0;
+        } else if (a.walk == 3) {
+            // App. B Alg. 3: accept x if rho* U <= p(x)/q(x)
+            if (qx > 0.0) w_child = fmin(1.0, px / (sp_rho * qx));
+            else w_child = (px > 0.0) ? 1.0 : 0.0;
         } else {
             // App. B Alg. 4: accept x with min(1, p(x)/q(x))
             if (qx > 0.0) w_child = fmin(1.0, Px / qx);
@@ -690,7 +741,7 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(TreeDesc tree, Qu
                     // while this task goes on with the sweeps that follow.
                     if (run_child && (!first_to_run || own_given) && !child_ahead) {
                         wait_memory();                    // its starting weight has been written
-                        append_task(q, ws, tree.cls[cn], b * a.N + cn);
+                        append_task(tree, ws, tree.cls[cn], b * a.N + cn);
                     }
                 }
             } else {
@@ -709,7 +760,7 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(TreeDesc tree, Qu
             break;
         }
 
-        if (METHOD == MPV_METHOD_SPECINFER && a.walk == 2 && threadIdx.x == 0 &&
+        if (METHOD == MPV_METHOD_SPECINFER && a.walk >= 2 && threadIdx.x == 0 &&
             fabs(w_child - static_cast<double>(ch_u[j])) < 1e-6)
             atomicAdd(&a.counters[MPV_COUNTER_NEAR_TIE_ACCEPT], 1u);     // (the other rules count these in their walk)
         // SpecInfer moves into the first child it accepts: later children and this node's
@@ -722,6 +773,11 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(TreeDesc tree, Qu
         if (METHOD == MPV_METHOD_SPECINFER && a.walk == 2) {
             c = 1.0;
             break;
+        }
+        // SpecTr tests every child against the same p; its residual is formed once, by the draw
+        if (METHOD == MPV_METHOD_SPECINFER && a.walk == 3) {
+            c = sp_rho;
+            continue;
         }
 
         // ---- the child (SpecInfer) or its whole subtree (Traversal) is rejected:
@@ -764,6 +820,7 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(TreeDesc tree, Qu
         st_shared_f64(&ws.At[bn], rt.A);
         st_shared_f64(&ws.Ad[bn], rd.A);
         st_shared_f64(&ws.cfin[bn], c);
+        if (METHOD == MPV_METHOD_SPECINFER && a.walk == 3) st_shared_f64(&ws.aux[bn], sp_gamma);
         if (METHOD == MPV_METHOD_TRAVERSAL && n != 0) st_shared_f64(&ws.atest[bn], wa);
         bool push_sample, settled_tree = false, resume = false;
         if (METHOD == MPV_METHOD_SPECINFER && a.lazy) {
@@ -840,7 +897,7 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(TreeDesc tree, Qu
         // (cannot happen: a task that settles the tree or completes a subtree has no child left to run)
         if (METHOD == MPV_METHOD_TRAVERSAL && own_child >= 0 && !own_given && !sh_settled && (sh_push_sample || sh_resume)) {
             const int cn = tree.child_list[tree.child_off[n] + own_child];
-            append_task(q, ws, tree.cls[cn], b * a.N + cn);
+            append_task(tree, ws, tree.cls[cn], b * a.N + cn);
         }
     }
     __syncthreads();                                  // every new task has been counted
@@ -932,7 +989,9 @@ struct ResidualTile {
     const typename E::T* zd;
     int V;
     bool aligned, use_d;
+    bool spectr;                    // r = (p - gamma min(p/rho*, q))_+ (App. B, Alg. 3) instead of (p - c q)_+
     float k32, nAt, nAd, rho;
+    float gamma, inv_rho;           // SpecTr only; rho above is then 2^(remainder difference), about 1
 
     __device__ __forceinline__ void load(int tile, int lane, float (&r)[PER_LANE]) const {
         const int e0 = tile * TILE + lane * PER_LANE;
@@ -954,6 +1013,7 @@ struct ResidualTile {
         const float et = fast_exp2(fmaf(t, k32, nAt));
         if (!use_d) return et;
         const float ed = fast_exp2(fmaf(d, k32, nAd));
+        if (spectr) return fmaxf(fmaf(-gamma, fminf(et * inv_rho, rho * ed), et), 0.f);
         return fmaxf(fmaf(-rho, ed, et), 0.f);
     }
 };
@@ -962,7 +1022,7 @@ struct ResidualTile {
 // tile_sum: kMaxTiles floats of LDS; scratch: 2 doubles per wave.  Everything it reads from
 // the workspace was written by node tasks of this launch (see st_shared_f64).
 template <class E, int METHOD>
-__device__ int sample_task(const TreeDesc& tree, const Workspace& ws, const Args& a, int b,
+__device__ __forceinline__ int sample_task(const TreeDesc& tree, const Workspace& ws, const Args& a, int b,
                            float* tile_sum, double* scratch) {
     using T = typename E::T;
     constexpr int NW = kSampleBlock / kWave;
@@ -980,7 +1040,7 @@ __device__ int sample_task(const TreeDesc& tree, const Workspace& ws, const Args
         if (lane == 0) { sh_stop = stop; sh_next = -1; }
     }
     __syncthreads();
-    const int n = sh_stop;
+    const int n = __builtin_amdgcn_readfirstlane(sh_stop);
     const size_t bn = static_cast<size_t>(b) * a.N + n;
     const T* zt = static_cast<const T*>(a.zt) + bn * a.V;
     const T* zd = static_cast<const T*>(a.zd) + bn * a.V;
@@ -1009,7 +1069,15 @@ __device__ int sample_task(const TreeDesc& tree, const Workspace& ws, const Args
     rt_.aligned = ((reinterpret_cast<uintptr_t>(zt) & 15u) == 0);
     rt_.use_d = (c > 0.0);
     rt_.k32 = a.k32;
-    if (rt_.use_d) {
+    rt_.spectr = false; rt_.gamma = 0.f; rt_.inv_rho = 0.f;
+    if (rt_.use_d && a.walk == 3) {
+        // c holds rho*; the vector drawn from is (p - gamma min(p/rho*, q))_+
+        const ResidualConsts rc = residual_consts(At, Ad, 1.0);
+        rt_.nAt = rc.nAt; rt_.nAd = rc.nAd; rt_.rho = rc.rho;
+        rt_.spectr = true;
+        rt_.gamma = static_cast<float>(ld_shared_f64(&ws.aux[bn]));
+        rt_.inv_rho = static_cast<float>(1.0 / c);
+    } else if (rt_.use_d) {
         const ResidualConsts rc = residual_consts(At, Ad, c);
         rt_.nAt = rc.nAt; rt_.nAd = rc.nAd; rt_.rho = rc.rho;
     } else {
@@ -1149,8 +1217,8 @@ __device__ int sample_task(const TreeDesc& tree, const Workspace& ws, const Args
                 const int to = tree.child_list[tree.child_off[n] + __ffsll(static_cast<long long>(m)) - 1];
                 if (lane == 0) {
                     st_relaxed(&ws.cur[b], to);
-                    // Naive tests the first child of an inner node before it draws there; NSS and leaves draw at once
-                    sh_next = (a.walk == 2 && tree.nchild[to] > 0) ? b * a.N + to : a.B * a.N + b;
+                    // Naive and SpecTr test children of an inner node before they draw there; NSS and leaves draw at once
+                    sh_next = (a.walk >= 2 && tree.nchild[to] > 0) ? b * a.N + to : a.B * a.N + b;
                 }
             } else {
                 if (lane == 0) write_path(tree, a, b, n);
@@ -1290,7 +1358,7 @@ static int validate(const mpv_problem* p, Plan* plan) {
     if (!p) return MPV_ERR_NULL;
     if (p->B < 0 || p->N < 1 || p->V < 1) return MPV_ERR_BAD_SHAPE;
     if (p->N > MPV_MAX_NODES || p->V > MPV_MAX_VOCAB) return MPV_ERR_UNSUPPORTED;
-    if (p->method < MPV_METHOD_SPECINFER || p->method > MPV_METHOD_NAIVE) return MPV_ERR_BAD_METHOD;
+    if (p->method < MPV_METHOD_SPECINFER || p->method > MPV_METHOD_SPECTR) return MPV_ERR_BAD_METHOD;
     if (p->logit_dtype != MPV_DTYPE_F32 && p->logit_dtype != MPV_DTYPE_BF16) return MPV_ERR_BAD_DTYPE;
     if (!(p->temperature > 0.0f) || !isfinite(p->temperature)) return MPV_ERR_BAD_TEMPERATURE;
     if (!p->parent) return MPV_ERR_NULL;
@@ -1361,6 +1429,7 @@ static size_t carve(const mpv_problem* p, void* base, Workspace* ws) {
     double* At = static_cast<double*>(take(bn * 8));
     double* Ad = static_cast<double*>(take(bn * 8));
     double* cf = static_cast<double*>(take(bn * 8));
+    double* ax = static_cast<double*>(take(bn * 8));
     double* a0 = static_cast<double*>(take(bn * 8));
     double* at = static_cast<double*>(take(bn * 8));
     int32_t* qu = static_cast<int32_t*>(take(bn * 4));
@@ -1370,7 +1439,8 @@ static size_t carve(const mpv_problem* p, void* base, Workspace* ws) {
     unsigned long long* ac = static_cast<unsigned long long*>(take(static_cast<size_t>(p->B) * 8));
     int32_t* de = static_cast<int32_t*>(take(static_cast<size_t>(p->B) * 4));
     int32_t* cu = static_cast<int32_t*>(take(static_cast<size_t>(p->B) * 4));
-    if (ws) { ws->At = At; ws->Ad = Ad; ws->cfin = cf; ws->a0 = a0; ws->atest = at; ws->queue = qu; ws->qctl = qc; ws->mailbox = mb; ws->known = kn; ws->acc = ac; ws->decided = de; ws->cur = cu; }
+    TreeDesc* tr = static_cast<TreeDesc*>(take(sizeof(TreeDesc)));
+    if (ws) { ws->At = At; ws->Ad = Ad; ws->cfin = cf; ws->aux = ax; ws->a0 = a0; ws->atest = at; ws->queue = qu; ws->qctl = qc; ws->mailbox = mb; ws->known = kn; ws->acc = ac; ws->decided = de; ws->cur = cu; ws->tree = tr; }
     return off < 256 ? 256 : off;
 }
 
@@ -1389,7 +1459,7 @@ static int compute_units() {
 
 template <class E>
 static int launch_all(const mpv_problem* p, const Plan& plan, const Workspace& ws, const Args& a, hipStream_t s) {
-    const TreeDesc& tree = plan.tree;
+    TreeDesc tree = plan.tree;
     (void)hipGetLastError();    // a stale error left by the caller's own HIP calls is not ours
     // every register and LDS slot of a node task is populated whatever the row's alignment
     const bool full = (p->V - (E::VEC - 1)) / E::VEC >= (kRegVecs + kLdsVecs) * kTaskBlock;
@@ -1421,6 +1491,7 @@ static int launch_all(const mpv_problem* p, const Plan& plan, const Workspace& w
         q.init_tail[0] = p->B;
         q.init_total = p->B;
     }
+    for (int c = 0; c <= q.nclass; ++c) tree.class_off[c] = q.off[c];
     const int tasks = q.off[q.nclass];
     // about one workgroup per compute unit (a node task fills one); fewer if there is less to do
     int wgs = tasks < compute_units() ? tasks : compute_units();
@@ -1442,17 +1513,17 @@ static int launch_all(const mpv_problem* p, const Plan& plan, const Workspace& w
     }
     {
         const int threads = 256;
-        const int blocks = (max(p->B * p->N, MPV_MAX_NODES) + threads - 1) / threads;
-        launch(MPV_KERNEL_INIT, init_kernel, dim3(blocks), dim3(threads), s, q, tree, ws, a);
+        const int blocks = (max(p->B, 64) + threads - 1) / threads;
+        launch(MPV_KERNEL_INIT, init_kernel, dim3(blocks, p->N), dim3(threads), s, q, tree, ws, a);
     }
     if (tasks > 0) {
         const dim3 grid(static_cast<unsigned>(wgs)), block(kTaskBlock);
         if (p->method != MPV_METHOD_TRAVERSAL) {      // NSS and Naive are variants of the top-down kernel
-            if (full) launch(MPV_KERNEL_NODE_TASK, node_task_kernel<E, MPV_METHOD_SPECINFER, true>, grid, block, s, tree, q, ws, a);
-            else launch(MPV_KERNEL_NODE_TASK, node_task_kernel<E, MPV_METHOD_SPECINFER, false>, grid, block, s, tree, q, ws, a);
+            if (full) launch(MPV_KERNEL_NODE_TASK, node_task_kernel<E, MPV_METHOD_SPECINFER, true>, grid, block, s, q, ws, a);
+            else launch(MPV_KERNEL_NODE_TASK, node_task_kernel<E, MPV_METHOD_SPECINFER, false>, grid, block, s, q, ws, a);
         } else {
-            if (full) launch(MPV_KERNEL_NODE_TASK, node_task_kernel<E, MPV_METHOD_TRAVERSAL, true>, grid, block, s, tree, q, ws, a);
-            else launch(MPV_KERNEL_NODE_TASK, node_task_kernel<E, MPV_METHOD_TRAVERSAL, false>, grid, block, s, tree, q, ws, a);
+            if (full) launch(MPV_KERNEL_NODE_TASK, node_task_kernel<E, MPV_METHOD_TRAVERSAL, true>, grid, block, s, q, ws, a);
+            else launch(MPV_KERNEL_NODE_TASK, node_task_kernel<E, MPV_METHOD_TRAVERSAL, false>, grid, block, s, q, ws, a);
         }
     }
     if (a.dbg_stats) {
@@ -1515,7 +1586,8 @@ int mpv_verify(const mpv_problem* problem, const mpv_buffers* buf, void* workspa
     mpv::Workspace ws;
     mpv::carve(problem, workspace, &ws);
     mpv::Args a;
-    const int walk = problem->method == MPV_METHOD_NSS ? 1 : problem->method == MPV_METHOD_NAIVE ? 2 : 0;
+    const int walk = problem->method == MPV_METHOD_NSS ? 1 : problem->method == MPV_METHOD_NAIVE ? 2
+                   : problem->method == MPV_METHOD_SPECTR ? 3 : 0;
     if (walk && !buf->draw_uniforms) return MPV_ERR_NULL;
     if (walk && (buf->stats || buf->edge_probs)) return MPV_ERR_UNSUPPORTED;
     a.zt = buf->target_logits; a.zd = buf->draft_logits; a.tokens = buf->tokens; a.uniforms = buf->uniforms;

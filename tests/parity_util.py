@@ -6,7 +6,7 @@ Bars (written here so every parity test uses the same ones):
   |a - u| < DECISION_BAND may take the other branch, and a bonus token may
   differ when u*R lies within BONUS_BAND (relative to R) of a CDF step.  Such
   trees are counted and returned, never silently accepted beyond the band.
-  For the methods that draw a token at every node they visit (NSS, Naive) any
+  For the methods that draw a token at every node they visit (NSS, Naive, SpecTr) any
   of the walk's draws within BONUS_BAND of a CDF step may send the walk elsewhere.
 * probabilities (edge probabilities, per-node test probabilities, the final
   normalised residual) must agree within PROB_ATOL absolute.
@@ -20,6 +20,20 @@ from oracle import mpv_oracle as orc
 DECISION_BAND = 1e-6
 BONUS_BAND = 1e-6
 PROB_ATOL = 1e-5
+# SpecTr's division factor is the root of a function of the V-wide sum beta; where that function is
+# flat (rho* near 1, p close to q) a relative error e in the sum moves the root, and with it every
+# test probability p/(rho* q), by kappa * e, kappa = oracle.spectr_conditioning.  The paper gives
+# no stopping rule for its binary search; the library's root is exact up to the accuracy of its
+# float32 sums, taken as 3e-7 relative here (three times the 1e-7 the design notes derive).
+SUM_REL_ERR = 3e-7
+
+
+def spectr_slack(host, b, node_parent, T, k):
+    """Extra tolerance on the test probabilities of the children of node_parent (SpecTr)."""
+    P = orc.softmax_T(host["target"][b][node_parent], T)
+    Q = orc.softmax_T(host["draft"][b][node_parent], T)
+    rho = orc.spectr_division_factor(P, Q, k)
+    return SUM_REL_ERR * orc.spectr_conditioning(P, Q, k, rho)
 
 
 def result_to_host(res):
@@ -47,7 +61,7 @@ def compare_with_oracle(method, host, T, got, trees=None, check_debug=True):
     for b in trees:
         tok = host["tokens"][b]
         zt, zd, u = host["target"][b], host["draft"][b], host["uniforms"][b]
-        token_walk = method in (orc.NSS, orc.NAIVE)
+        token_walk = method in (orc.NSS, orc.NAIVE, orc.SPECTR)
         ref = orc.verify_tree(method, parent, tok, zt, zd, T, u,
                               host["draw_uniforms"][b] if token_walk else None)
         report["trees"] += 1
@@ -63,8 +77,19 @@ def compare_with_oracle(method, host, T, got, trees=None, check_debug=True):
         assert g_toks == [int(tok[n]) for n in g_nodes], f"tree {b}: path tokens"
         assert depth[stop_g] == g_len
         same_path = (g_nodes == ref["path_nodes"])
-        if not same_path and token_walk and ref["bonus_gap"] < BONUS_BAND:
+        slack = {}
+        if method == orc.SPECTR:
+            for node, _, _, _ in ref["decisions"]:
+                par = parent[node]
+                if par not in slack:
+                    slack[par] = spectr_slack(host, b, par, T, len(children[par]))
+        close_call = any(abs(a_ref - uu) < DECISION_BAND + slack.get(parent[node], 0.0)
+                         for node, a_ref, uu, _ in ref["decisions"])
+        worst_slack = max(slack.values(), default=0.0)
+        if not same_path and token_walk and ref["bonus_gap"] < BONUS_BAND + worst_slack:
             report["near_tie_bonus"] += 1           # a draw on the way was within the band of a CDF step
+        elif not same_path and close_call:
+            report["near_tie_paths"] += 1
         elif not same_path:
             assert ref["min_margin"] < DECISION_BAND, (
                 f"tree {b}: path {g_nodes} != oracle {ref['path_nodes']} and no oracle decision within "
@@ -73,14 +98,14 @@ def compare_with_oracle(method, host, T, got, trees=None, check_debug=True):
         else:
             g_bonus = int(got["bonus_token"][b])
             if g_bonus != ref["bonus_token"]:
-                assert ref["bonus_gap"] < BONUS_BAND, (
+                assert ref["bonus_gap"] < BONUS_BAND + worst_slack, (
                     f"tree {b}: bonus {g_bonus} != oracle {ref['bonus_token']}, "
                     f"gap to CDF step {ref['bonus_gap']:.3e}")
                 report["near_tie_bonus"] += 1
             if check_debug and got.get("final_residual") is not None:
                 err = float(np.max(np.abs(got["final_residual"][b].astype(np.float64) - ref["residual"])))
                 report["max_resid_err"] = max(report["max_resid_err"], err)
-                assert err <= PROB_ATOL, f"tree {b}: final residual differs by {err:.3e}"
+                assert err <= PROB_ATOL + worst_slack, f"tree {b}: final residual differs by {err:.3e}"
         if not check_debug:
             continue
         if token_walk:
@@ -88,8 +113,10 @@ def compare_with_oracle(method, host, T, got, trees=None, check_debug=True):
             if got.get("accept_prob") is not None and same_path:
                 for node, a_ref, _, _ in ref["decisions"]:
                     err = abs(float(got["accept_prob"][b][node]) - a_ref)
+                    tol = PROB_ATOL + slack.get(parent[node], 0.0)
                     report["max_prob_err"] = max(report["max_prob_err"], err)
-                    assert err <= PROB_ATOL, f"tree {b} node {node}: test probability differs by {err:.3e}"
+                    assert err <= tol, (f"tree {b} node {node}: test probability differs by {err:.3e} "
+                                        f"(allowed {tol:.3e})")
             continue
         if got.get("accept_prob") is not None:
             probs, _ = orc.all_test_probs(method, parent, tok, zt, zd, T)

@@ -80,9 +80,9 @@ def test_problem_validation(lib):
     assert ws_bytes(lib, problem(T=-1.0))[0] == code("MPV_ERR_BAD_TEMPERATURE")
     assert ws_bytes(lib, problem(T=float("nan")))[0] == code("MPV_ERR_BAD_TEMPERATURE")
     assert ws_bytes(lib, problem(T=float("inf")))[0] == code("MPV_ERR_BAD_TEMPERATURE")
-    assert ws_bytes(lib, problem(method=4))[0] == code("MPV_ERR_BAD_METHOD")
+    assert ws_bytes(lib, problem(method=5))[0] == code("MPV_ERR_BAD_METHOD")
     assert ws_bytes(lib, problem(method=-1))[0] == code("MPV_ERR_BAD_METHOD")
-    assert ws_bytes(lib, problem(method=3))[0] == 0
+    assert ws_bytes(lib, problem(method=4))[0] == 0
     assert ws_bytes(lib, problem(dtype=5))[0] == code("MPV_ERR_BAD_DTYPE")
     assert lib.mpv_workspace_bytes(None, ctypes.byref(ctypes.c_size_t(0))) == code("MPV_ERR_NULL")
     assert lib.mpv_workspace_bytes(ctypes.byref(problem()), None) == code("MPV_ERR_NULL")

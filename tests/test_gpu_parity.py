@@ -16,9 +16,9 @@ from tests.parity_util import check_properties, compare_with_oracle, result_to_h
 pytestmark = pytest.mark.gpu
 
 SI, TV = mpv.MPV_METHOD_SPECINFER, mpv.MPV_METHOD_TRAVERSAL
-NSS, NAIVE = mpv.MPV_METHOD_NSS, mpv.MPV_METHOD_NAIVE
-METHOD_NAME = {SI: "specinfer", TV: "traversal", NSS: "nss", NAIVE: "naive"}
-ALL_METHODS = [SI, TV, NSS, NAIVE]
+NSS, NAIVE, SPECTR = mpv.MPV_METHOD_NSS, mpv.MPV_METHOD_NAIVE, mpv.MPV_METHOD_SPECTR
+METHOD_NAME = {SI: "specinfer", TV: "traversal", NSS: "nss", NAIVE: "naive", SPECTR: "spectr"}
+ALL_METHODS = [SI, TV, NSS, NAIVE, SPECTR]
 
 
 def announce(*a):
@@ -76,14 +76,14 @@ def test_config5_v262k_delayed(method):
     run_case(workloads.scaled(workloads.CONFIGS["v262k_delayed"], B=2), method)
 
 
-@pytest.mark.parametrize("method", [NSS, NAIVE])
+@pytest.mark.parametrize("method", [NSS, NAIVE, SPECTR])
 def test_config2_and_4_token_following_walks(method):
     # the two root-expanded configurations with the solvers whose output token may be another draft token
     run_case(workloads.scaled(workloads.CONFIGS["v32k_root"], B=6), method)
     run_case(workloads.scaled(workloads.CONFIGS["v152k_root"], B=3), method)
 
 
-@pytest.mark.parametrize("method", [NSS, NAIVE])
+@pytest.mark.parametrize("method", [NSS, NAIVE, SPECTR])
 @pytest.mark.parametrize("V,dtype", [(12, "bf16"), (37, "f32")])
 def test_drawn_tokens_are_followed_in_small_vocabularies(method, V, dtype):
     """With a dozen tokens the drawn token is a child's token most of the time (and equal-token

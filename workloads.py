@@ -24,6 +24,7 @@ SPECINFER = 0
 TRAVERSAL = 1
 NSS = 2
 NAIVE = 3
+SPECTR = 4
 
 
 @dataclass
