@@ -67,6 +67,41 @@ def cpu_baseline(cfg, inputs, method, budget_s=20.0):
     }
 
 
+def side_measurements(mpv, torch, cfg, inputs, method, pair_bytes, steps=5):
+    """Two reference points for the roofline, outside the timed region.
+    every_node_task: the same call with the per-node test probabilities requested, which makes the
+    library run the task of every internal node instead of only those the rule needs.
+    softmax_statistics_only: step S2 alone (mpv_row_stats) over every target row of the batch."""
+    def timed(fn):
+        for _ in range(2):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / steps
+
+    res = {}
+    kw = dict(draw_uniforms=inputs["draw_uniforms"])
+    out = mpv.mpv_verify(inputs["parent"], inputs["tokens"], inputs["target"], inputs["draft"],
+                         cfg.T, inputs["uniforms"], method, debug=False, **kw)
+    out.accept_prob = torch.empty(cfg.B, cfg.N, dtype=torch.float32, device=inputs["target"].device)
+    s = timed(lambda: mpv.mpv_verify(inputs["parent"], inputs["tokens"], inputs["target"], inputs["draft"],
+                                     cfg.T, inputs["uniforms"], method, debug=False, out=out, **kw))
+    tasks = out.counters.tolist()[5]
+    gbs = tasks * pair_bytes / s / 1e9
+    res["every_node_task"] = {"ms_per_step": s * 1e3, "node_tasks_run": tasks,
+                              "algorithmic_GBps": gbs, "frac_of_hbm_peak": gbs / HBM_PEAK_GBS}
+    rows = inputs["target"].view(cfg.B * cfg.N, cfg.V)
+    st = mpv.mpv_row_stats(rows, cfg.T)
+    s = timed(lambda: mpv.mpv_row_stats(rows, cfg.T, out=st))
+    gbs = rows.numel() * rows.element_size() / s / 1e9
+    res["softmax_statistics_only"] = {"ms_per_step": s * 1e3, "rows": cfg.B * cfg.N,
+                                      "algorithmic_GBps": gbs, "frac_of_hbm_peak": gbs / HBM_PEAK_GBS}
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -78,6 +113,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-launch-timing", action="store_true",
                     help="do not bracket the library's launches with HIP events")
+    ap.add_argument("--no-extra", action="store_true",
+                    help="skip the two side measurements (every node task run; softmax statistics alone)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (a known-size kernel to scale profiler byte counters by)")
     args = ap.parse_args()
@@ -191,6 +228,8 @@ def main():
         "kernels": kernels,
         "roofline": roofline,
     }
+    if not args.no_extra:
+        result["also_measured"] = side_measurements(mpv, torch, cfg, inputs, method, pair_bytes)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, inputs, method)
     print(json.dumps(result))
