@@ -64,7 +64,7 @@
 extern "C" {
 #endif
 
-#define MPV_ABI_VERSION 2
+#define MPV_ABI_VERSION 3
 
 /* limits (larger requests return MPV_ERR_UNSUPPORTED) */
 #define MPV_MAX_NODES    64   /* nodes per tree, root included            */
@@ -167,6 +167,27 @@ int mpv_workspace_bytes(const mpv_problem* problem, size_t* out);
  * buffers must be ordered by the caller (same stream, or events). */
 int mpv_verify(const mpv_problem* problem, const mpv_buffers* buffers,
                void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Expected block efficiency of every tree of the batch with the verification's own
+ * randomness integrated out (Sec. 5, Eq. 1-3; branching probabilities of Def. 5.3 by
+ * the listings of App. D; averaging `expected` over the s trees sampled for one context
+ * gives the paper's estimate).  For each tree b:
+ *   reach_prob[b,n] = P(node n lies on the accepted path of the rule `problem->method`),
+ *                     root: 1  (DEVICE, float32 [B,N]; may be NULL);
+ *   expected[b]     = sum_n reach_prob[b,n] = E[tau + 1 | tree b]  (DEVICE, float32 [B]).
+ * Top-down rules: the product, along the path, of the probability of moving from a node to
+ * the child (an accepted child is moved to itself; a drawn token leads to the first sibling
+ * that carries it; SpecInfer tries the children in list order).  Traversal: the nodes are
+ * tested in depth-first post-order, each after everything before it was rejected.
+ * No uniforms are read and nothing is sampled; every internal node's rows are read once.
+ * problem, target_logits, draft_logits, tokens, workspace, hip_stream: as for mpv_verify
+ * (same layouts, alignment and workspace size; problem->max_depth is not used beyond its
+ * validation).  counters: DEVICE uint32 [MPV_COUNTER_COUNT], zeroed by the call; only
+ * ZERO_MASS, BAD_TOKEN, DEPENDENCY_TIMEOUT and NODE_TASKS_RUN are meaningful.
+ * Errors: as mpv_verify. */
+int mpv_block_efficiency(const mpv_problem* problem, const void* target_logits, const void* draft_logits,
+                         const int32_t* tokens, void* workspace, size_t workspace_bytes,
+                         float* reach_prob, float* expected, uint32_t* counters, void* hip_stream);
 
 /* Softmax statistics of `rows` contiguous logit rows of length V (the first step
  * of the path, exposed on its own): out[r] = { max_v z, ln sum_v exp((z - max)/T) }

@@ -272,12 +272,19 @@ def spectr_division_factor(P, Q, k):
     """rho*: the root of rho -> p_acc(rho) - rho*beta(rho), p_acc = 1-(1-beta)^k, on [1,k].
 
     The map is monotone decreasing with a value >= 0 at 1 and <= 0 at k (App. B); binary
-    search as the paper says, run until float64 is exhausted."""
+    search as the paper says, run until float64 is exhausted.  The function is evaluated as
+        sum (p - rho q)_+  -  (sum (q - p/rho)_+)^k ,
+    which is the same number: rho*beta = sum min(p, rho q) = 1 - sum (p - rho q)_+ and
+    1 - beta = sum (q - p/rho)_+.  Written with beta itself, both halves are 1 - (something
+    tiny) when p is close to q and the difference drowns in rounding."""
+    P = np.asarray(P, dtype=np.float64)
+    Q = np.asarray(Q, dtype=np.float64)
     lo, hi = 1.0, float(k)
     for _ in range(64):
         mid = 0.5 * (lo + hi)
-        b = spectr_beta(P, Q, mid)
-        if (1.0 - (1.0 - b) ** k) - mid * b > 0.0:
+        excess = float(np.sum(np.maximum(P - mid * Q, 0.0)))
+        deficit = float(np.sum(np.maximum(Q - P / mid, 0.0)))
+        if excess - deficit ** k > 0.0:
             lo = mid
         else:
             hi = mid

@@ -77,6 +77,10 @@ def load_library(path=None):
     lib.mpv_verify.restype = ctypes.c_int
     lib.mpv_verify.argtypes = [ctypes.POINTER(_Problem), ctypes.POINTER(_Buffers),
                                ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+    lib.mpv_block_efficiency.restype = ctypes.c_int
+    lib.mpv_block_efficiency.argtypes = [ctypes.POINTER(_Problem), ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                         ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p,
+                                         ctypes.c_void_p, ctypes.c_void_p]
     lib.mpv_row_stats.restype = ctypes.c_int
     lib.mpv_row_stats.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_int32,
                                   ctypes.c_float, ctypes.c_void_p, ctypes.c_void_p]
@@ -221,6 +225,56 @@ def mpv_verify(parent, tokens, target_logits, draft_logits, temperature, uniform
                         ctypes.c_size_t(workspace.numel()), _stream_ptr(stream))
     if rc != 0:
         raise MpvError(rc, "mpv_verify")
+    return out
+
+
+@dataclass
+class BlockEfficiencyResult:
+    expected: "object"          # float32 [B]    E[tau + 1 | tree]
+    reach_prob: "object"        # float32 [B,N]  P(node on the accepted path)
+    counters: "object"
+    workspace: Optional["object"] = None
+
+
+def mpv_block_efficiency(parent, tokens, target_logits, draft_logits, temperature, method,
+                         out=None, stream=None):
+    """Expected block efficiency of every tree of the batch (see include/mpv.h): enqueued on the
+    current (or given) torch stream; returns a BlockEfficiencyResult of CUDA tensors.  Arguments as
+    for mpv_verify, without uniforms.  `out` may be a previous result whose buffers are reused."""
+    import torch
+    from .trees import tree_depth
+    B, N, V = target_logits.shape
+    for t, name in ((tokens, "tokens"), (target_logits, "target_logits"), (draft_logits, "draft_logits")):
+        if not t.is_cuda or not t.is_contiguous():
+            raise ValueError(f"{name} must be a contiguous CUDA tensor")
+    if tokens.dtype != torch.int32 or tuple(tokens.shape) != (B, N):
+        raise TypeError("tokens must be int32 [B,N]")
+    if draft_logits.shape != target_logits.shape or draft_logits.dtype != target_logits.dtype:
+        raise ValueError("target and draft logits must have the same shape and dtype")
+    dev = target_logits.device
+    max_depth = max(1, tree_depth(list(parent)) if len(parent) == N and N > 0 else 1)
+    prob = _make_problem(B, N, V, method, _dtype_id(target_logits), temperature, max_depth, parent)
+    lib = load_library()
+    need = ctypes.c_size_t(0)
+    rc = lib.mpv_workspace_bytes(ctypes.byref(prob), ctypes.byref(need))
+    if rc != 0:
+        raise MpvError(rc, "mpv_workspace_bytes")
+    if out is None:
+        out = BlockEfficiencyResult(
+            expected=torch.empty(B, dtype=torch.float32, device=dev),
+            reach_prob=torch.empty(B, N, dtype=torch.float32, device=dev),
+            counters=torch.empty(8, dtype=torch.int32, device=dev))
+    if out.workspace is None or out.workspace.numel() < need.value:
+        out.workspace = torch.empty(max(need.value, 256), dtype=torch.uint8, device=dev)
+
+    def ptr(t):
+        return ctypes.c_void_p(t.data_ptr()) if t is not None else ctypes.c_void_p(0)
+
+    rc = lib.mpv_block_efficiency(ctypes.byref(prob), ptr(target_logits), ptr(draft_logits), ptr(tokens),
+                                  ptr(out.workspace), ctypes.c_size_t(out.workspace.numel()),
+                                  ptr(out.reach_prob), ptr(out.expected), ptr(out.counters), _stream_ptr(stream))
+    if rc != 0:
+        raise MpvError(rc, "mpv_block_efficiency")
     return out
 
 

@@ -78,8 +78,8 @@ struct QueuePlan {
 struct Workspace {
     double* At;      // log2-partition of the target row (internal nodes)
     double* Ad;      // same for the draft row
-    double* cfin;    // c of the node's final state (all children rejected); SpecTr: the division factor rho*
-    double* aux;     // SpecTr: gamma = p_acc / beta of the node
+    double* cfin;    // c of the node's final state (all children rejected); SpecTr: the division factor rho* (the token is drawn from (p - rho* q)_+)
+    double* aux;     // block-efficiency estimate, Naive and SpecTr: p_res at the node's token (see estimate_wave)
     double* a0;      // Traversal: weight the node starts with (kNotReady until its parent's task publishes it)
     double* atest;   // probability the node is tested with
     int32_t* queue;      // entry = tree * N + node (node task) or B * N + tree (sampling task), -1 = not written yet
@@ -123,6 +123,12 @@ struct Args {
                      // 3 after the SpecTr tests
     int32_t lazy;    // compute only what the rule needs (off when per-node debug output is wanted: then every node task runs)
     int32_t stagger_ticks;   // start-up spread of the persistent workgroups, in 10 ns ticks per step (8 steps)
+    // Expected block efficiency instead of a verification (Sec. 5, Eq. 1-3): every node task runs
+    // (lazy = 0), no uniforms are read, and what would be a tree's sampling task turns the per-node
+    // results into reach probabilities.  reach_prob [B,N] may be null; expected [B].
+    int32_t estimate;
+    float* reach_prob;
+    float* expected;
 };
 
 constexpr int kTaskBlock = 512;
@@ -424,6 +430,10 @@ template <class E, int METHOD>
 __device__ __forceinline__ int sample_task(const TreeDesc& tree, const Workspace& ws, const Args& a, int b,
                            float* tile_sum, double* scratch);
 
+// (defined below) expected block efficiency of tree b from the per-node results, by the first wave
+template <int METHOD>
+__device__ __forceinline__ void estimate_wave(const TreeDesc& tree, const Workspace& ws, const Args& a, int b);
+
 template <class E, int METHOD, bool FULL>
 __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(QueuePlan q, Workspace ws, Args a) {
     using T = typename E::T;
@@ -490,7 +500,12 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(QueuePlan q, Work
             asked = true;
         }
         float* tile_mass = FULL ? reinterpret_cast<float*>(lds_t) : own_tile_mass;
-        const int next = sample_task<E, METHOD>(tree, ws, a, task - a.B * a.N, tile_mass, scratch);
+        int next = -1;
+        if (a.estimate) {
+            if (threadIdx.x < kWave) estimate_wave<METHOD>(tree, ws, a, task - a.B * a.N);
+        } else {
+            next = sample_task<E, METHOD>(tree, ws, a, task - a.B * a.N, tile_mass, scratch);
+        }
         if (next >= 0) own_task = next;               // a token-following walk goes on
         if (threadIdx.x == 0) {
             if (next >= 0) {
@@ -528,9 +543,9 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(QueuePlan q, Work
     if (threadIdx.x < k) {
         const size_t bc = static_cast<size_t>(b) * a.N + tree.child_list[tree.child_off[n] + threadIdx.x];
         pf_x = a.tokens[bc];
-        pf_u = a.uniforms[bc];
+        if (!a.estimate) pf_u = a.uniforms[bc];
     }
-    if (threadIdx.x == kWave) pf_u = a.uniforms[bn];        // the node's own uniform
+    if (threadIdx.x == kWave && !a.estimate) pf_u = a.uniforms[bn];        // the node's own uniform
     // are workgroups idle (as of the last round of dispatching)?
     __shared__ int sh_idle, sh_ahead;
     int pf_idle = 0;
@@ -627,28 +642,80 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(QueuePlan q, Work
     const bool idle_seen = sh_idle != 0;
     // SpecTr (App. B, Alg. 3): the division factor rho* is the root of
     //   f(rho) = p_acc(rho) - rho beta(rho),  p_acc = 1 - (1 - beta)^k,  beta(rho) = sum_v min(p_v/rho, q_v)
-    // on [1, k]; f decreases, f(1) >= 0 >= f(k).  Each beta is one sweep over the pair on chip.  The
-    // paper's binary search is replaced by a bracketing secant search (Illinois rule): the same root,
-    // reached in about ten sweeps instead of thirty.
-    double sp_rho = 1.0, sp_gamma = 1.0;
+    // on [1, k]; f decreases, f(1) >= 0 >= f(k).  Written with the sums of positive terms
+    //   W(rho) = sum_v (p_v - rho q_v)_+   and   D(rho) = sum_v (q_v - p_v/rho)_+ = (W + rho - 1)/rho = 1 - beta,
+    // f = W - D^k: no cancellation, so the sign of f is right even where |f| is far below the
+    // rounding error of beta itself (p close to q, where f is nearly flat to the right of the root).
+    // Each W is one sweep over the pair on chip, the same reduction the other rules use.  At the
+    // root p_acc/beta = rho*, so the vector the token is drawn from, (p - gamma min(p/rho*, q))_+,
+    // is (p - rho* q)_+ : the node's final state is simply c = rho*.
+    // The paper's binary search is replaced by a bracketing secant search (Illinois rule) that
+    // halves the bracket whenever three steps have not (f has a kink where the largest token
+    // switches sides, and can be nearly flat beyond it) and, once two points nearly coincide,
+    // steps just across the last one to close the bracket: the same root, in about ten sweeps
+    // instead of thirty.
+    double sp_rho = 1.0, sp_W = 1.0;
     if (METHOD == MPV_METHOD_SPECINFER && a.walk == 3) {
-        double lo = 1.0, hi = static_cast<double>(k), flo = 0.0, fhi = 0.0, beta = 0.0;
+        constexpr double kTol = 3e-8;                 // relative width of the final bracket
+        double lo = 1.0, hi = static_cast<double>(k), flo = 0.0, fhi = 0.0;
+        double w1 = hi - lo, w2 = w1, w3 = w1;        // bracket widths one, two, three steps ago
+        double x_prev = 0.0;
         int side = 0;
-        const int evals = (k > 1) ? 40 : 1;
+        bool probe = false, last_positive = false;
+        // Where one token carries most of p and q, f has its kink at that token's ratio p/q and the
+        // root usually sits right on it; that token is then almost surely among the draft tokens.
+        // So the ratio of the most probable draft token is tried first, from both sides.
+        double kink = 0.0;
+        {
+            double q_best = -1.0;
+            for (int j = 0; j < k; ++j) {
+                const int xj = ch_tok[j];
+                if (xj < 0 || xj >= V) continue;
+                const double qj = exp2(static_cast<double>(ch_zd[j]) * kd - rd.A);
+                if (qj > q_best) { q_best = qj; kink = exp2(static_cast<double>(ch_zt[j]) * kd - rt.A) / qj; }
+            }
+            kink = uniform_f64(kink);
+        }
+        int kink_state = 0;                           // 0: not tried, 1: tried from the right, 2: done
+        const int evals = (k > 1) ? 64 : 1;
         for (int it = 0; it < evals; ++it) {
+            const double width = hi - lo;
             double x;
             if (it == 0) x = lo;
             else if (it == 1) x = hi;
-            else x = uniform_f64((lo * fhi - hi * flo) / (fhi - flo));
-            const ResidualConsts rc = residual_consts(rt.A + log2(x), rd.A, 1.0);
-            MinMassRawF<E> f;
+            else {
+                const double secant = (lo * fhi - hi * flo) / (fhi - flo);
+                const double right = kink * (1.0 + 0.45 * kTol), left = kink * (1.0 - 0.45 * kTol);
+                if (kink_state == 0 && right > lo && right < hi) {
+                    x = right;
+                    kink_state = 1;
+                } else if (kink_state == 1 && hi == right && left > lo) {
+                    x = left;                         // f < 0 just right of the kink: is it > 0 just left of it?
+                    kink_state = 2;
+                } else if (it >= 4 && width > 0.5 * w3) {
+                    x = 0.5 * (lo + hi);              // three steps have not halved the bracket
+                } else if (probe) {
+                    // the last two points nearly coincide: step just across, to close the bracket
+                    x = last_positive ? fmin(hi, x_prev * (1.0 + kTol)) : fmax(lo, x_prev * (1.0 - kTol));
+                    if (!(x > lo && x < hi)) x = secant;
+                } else {
+                    x = secant;
+                }
+                if (kink_state == 0 || (kink_state == 1 && x != right)) kink_state = 2;
+                x = uniform_f64(x);
+            }
+            w3 = w2; w2 = w1; w1 = width;
+            const ResidualConsts rc = residual_consts(rt.A, rd.A, x);
+            ResidualMassRawF<E> f;
             f.init();
             f.k32 = k32; f.nAt = rc.nAt; f.nAd = rc.nAd; f.rho = uniform_f32(rc.rho);
             pair.replay(f);
             const double lane_mass = static_cast<double>(f.acc0) + static_cast<double>(f.acc1);
-            beta = uniform_f64(uniform_f64(rc.scale) * block_sum<kTaskBlock>(lane_mass, scratch));
-            const double fx = (1.0 - pow(1.0 - fmin(beta, 1.0), static_cast<double>(k))) - x * beta;
+            const double Wx = uniform_f64(uniform_f64(rc.scale) * block_sum<kTaskBlock>(lane_mass, scratch));
+            const double Dx = fmin(fmax((Wx + x - 1.0) / x, 0.0), 1.0);
+            const double fx = Wx - pow(Dx, static_cast<double>(k));
             sp_rho = x;
+            sp_W = Wx;
             if (it == 0) {
                 flo = fx;
                 if (!(fx > 0.0)) break;               // the root is 1 (also when k = 1)
@@ -659,11 +726,12 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(QueuePlan q, Work
                 if (fx > 0.0) { lo = x; flo = fx; if (side == 1) fhi *= 0.5; side = 1; }
                 else if (fx < 0.0) { hi = x; fhi = fx; if (side == 2) flo *= 0.5; side = 2; }
                 else break;
-                if (hi - lo <= 1e-9 * hi || fabs(fx) <= 1e-12) break;
+                if (hi - lo <= kTol * hi) break;
+                probe = !probe && fabs(x - x_prev) <= 0.5 * kTol * x;
+                last_positive = fx > 0.0;
             }
+            x_prev = x;
         }
-        const double p_acc = 1.0 - pow(1.0 - fmin(beta, 1.0), static_cast<double>(k));
-        sp_gamma = beta > 0.0 ? p_acc / beta : 0.0;
     }
     for (int j = 0; j < k; ++j) {
         // a resumed task repeats the arithmetic of the first child (whose task has long run)
@@ -687,6 +755,9 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(QueuePlan q, Work
             if (!(wa > 0.0) || !(Px > 0.0)) w_child = 0.0;
             else if (qx > 0.0) w_child = fmin(1.0, wa * Px / qx);
             else w_child = 1.0;
+        } else if (a.walk == 1) {
+            // NSS tests nothing (App. B Alg. 1); the estimate wants p(x): the chance that Y ~ p is x
+            w_child = px;
         } else if (a.walk == 3) {
             // App. B Alg. 3: accept x if rho* U <= p(x)/q(x)
             if (qx > 0.0) w_child = fmin(1.0, px / (sp_rho * qx));
@@ -746,6 +817,11 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(QueuePlan q, Work
                 }
             } else {
                 st_shared_f64(&ws.atest[bc], w_child);
+                if (a.estimate && a.walk == 3) {
+                    // App. D, SpecTr Branching: p_res(x), p_res = norm (p - rho* q)_+ (see the search above)
+                    const double r = fmax(px - sp_rho * qx, 0.0);
+                    st_shared_f64(&ws.aux[bc], sp_W > 0.0 ? fmin(r / sp_W, 1.0) : px);
+                }
             }
             if (a.dbg_edge) {
                 a.dbg_edge[bc * 2] = static_cast<float>(px);
@@ -760,7 +836,7 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(QueuePlan q, Work
             break;
         }
 
-        if (METHOD == MPV_METHOD_SPECINFER && a.walk >= 2 && threadIdx.x == 0 &&
+        if (METHOD == MPV_METHOD_SPECINFER && a.walk >= 2 && !a.estimate && threadIdx.x == 0 &&
             fabs(w_child - static_cast<double>(ch_u[j])) < 1e-6)
             atomicAdd(&a.counters[MPV_COUNTER_NEAR_TIE_ACCEPT], 1u);     // (the other rules count these in their walk)
         // SpecInfer moves into the first child it accepts: later children and this node's
@@ -769,8 +845,10 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(QueuePlan q, Work
             next_node = cn;
             break;
         }
+        // NSS: nothing else to find out here
+        if (METHOD == MPV_METHOD_SPECINFER && a.walk == 1) continue;
         // Naive (App. B, Alg. 2) tests the first child only; the token then drawn comes from (p - q)_+
-        if (METHOD == MPV_METHOD_SPECINFER && a.walk == 2) {
+        if (METHOD == MPV_METHOD_SPECINFER && a.walk == 2 && !a.estimate) {
             c = 1.0;
             break;
         }
@@ -803,6 +881,25 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(QueuePlan q, Work
             if (METHOD == MPV_METHOD_TRAVERSAL) wa = (wa >= 1.0) ? 1.0 : 0.0;
             if (threadIdx.x == 0) atomicAdd(&a.counters[MPV_COUNTER_ZERO_MASS], 1u);
         }
+        if (METHOD == MPV_METHOD_SPECINFER && a.walk == 2) {
+            // Naive, estimate (App. D, Naive Branching): p_res(x_i) for every child, p_res = norm (p - q)_+
+            // (now c = 1 and W = its mass; p itself if the mass was zero: c = 0, W = 1)
+            for (int i = 0; i < k; ++i) {
+                const int ci = tree.child_list[tree.child_off[n] + i];
+                const int xi = ch_tok[i];
+                double r = 0.0;
+                if (xi >= 0 && xi < V)
+                    r = fmax(exp2(static_cast<double>(ch_zt[i]) * kd - rt.A) - c * exp2(static_cast<double>(ch_zd[i]) * kd - rd.A), 0.0) / W;
+                else if (i > 0 && threadIdx.x == 0)
+                    atomicAdd(&a.counters[MPV_COUNTER_BAD_TOKEN], 1u);
+                if (threadIdx.x == 0) {
+                    st_shared_f64(&ws.aux[static_cast<size_t>(b) * a.N + ci], r);
+                    if (i > 0) st_shared_f64(&ws.atest[static_cast<size_t>(b) * a.N + ci], 0.0);   // never tested
+                }
+                settled_bits |= 1ull << tree.rank[ci];
+            }
+            break;
+        }
     }
 
     if (paused) {
@@ -820,7 +917,6 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(QueuePlan q, Work
         st_shared_f64(&ws.At[bn], rt.A);
         st_shared_f64(&ws.Ad[bn], rd.A);
         st_shared_f64(&ws.cfin[bn], c);
-        if (METHOD == MPV_METHOD_SPECINFER && a.walk == 3) st_shared_f64(&ws.aux[bn], sp_gamma);
         if (METHOD == MPV_METHOD_TRAVERSAL && n != 0) st_shared_f64(&ws.atest[bn], wa);
         bool push_sample, settled_tree = false, resume = false;
         if (METHOD == MPV_METHOD_SPECINFER && a.lazy) {
@@ -976,6 +1072,88 @@ __device__ __forceinline__ int walk_wave(const TreeDesc& tree, const Workspace& 
     return stop;
 }
 
+// ------------------------------------------------------------------ expected block efficiency
+//
+// Sec. 5, Eq. 1-3: E[tau + 1 | tree] = sum over nodes of P(the node lies on the accepted path).
+// Lane n looks after node n.  Top-down rules: the probability of moving from a node to its
+// child is put together from the per-child results the node tasks left (App. D):
+//   SpecInfer  a_j prod_{l<j} (1 - a_l), a_l the probability sibling l is tested with;
+//   NSS        p(x_j) if no earlier sibling carries the same token (a drawn token leads to the
+//              first sibling that carries it), else 0;
+//   Naive      [j = 1] a_1 + (1 - a_1) p_res(x_j) [first carrier of x_j];
+//   SpecTr     a_j prod_{l<j} (1 - a_l) + p_res(x_j) prod_l (1 - a_l) [first carrier of x_j];
+// and a node's reach probability is the product along its path from the root.  Traversal: nodes
+// are tested in postorder, each after everything before it was rejected, so the node at position
+// r is the accepted one with a_r prod_{r'<r} (1 - a_r'), and a node is on the accepted path iff
+// the accepted node is in its subtree.
+template <int METHOD>
+__device__ __forceinline__ void estimate_wave(const TreeDesc& tree, const Workspace& ws, const Args& a, int b) {
+    __shared__ double sh_v[MPV_MAX_NODES], sh_w[MPV_MAX_NODES];
+    const int n = threadIdx.x & (kWave - 1);
+    const size_t base = static_cast<size_t>(b) * a.N;
+    const bool live = n < a.N;
+    double reach = 0.0;
+    if (METHOD == MPV_METHOD_TRAVERSAL) {
+        // sh_v[r]: test probability of the node at postorder position r (the root, last, is accepted)
+        if (live) {
+            const int node = tree.postorder[n];
+            sh_v[n] = (node == 0) ? 1.0 : ld_shared_f64(&ws.atest[base + node]);
+        }
+        __builtin_amdgcn_wave_barrier();
+        if (live) {
+            double none_before = 1.0;
+            for (int r = 0; r < n; ++r) none_before *= 1.0 - sh_v[r];
+            sh_w[n] = sh_v[n] * none_before;          // the node at position n is the accepted one
+        }
+        __builtin_amdgcn_wave_barrier();
+        if (live) {
+            if (n == 0) reach = 1.0;
+            else for (int r = tree.sub_lo[n]; r <= tree.rank[n]; ++r) reach += sh_w[r];
+        }
+    } else {
+        if (live) {
+            sh_v[n] = (n == 0) ? 1.0 : ld_shared_f64(&ws.atest[base + n]);
+            sh_w[n] = (n == 0 || a.walk < 2) ? 0.0 : ld_shared_f64(&ws.aux[base + n]);
+        }
+        __builtin_amdgcn_wave_barrier();
+        double step = 1.0;                            // from the parent to this node
+        if (live && n > 0) {
+            const int par = tree.parent[n], off = tree.child_off[par], k = tree.nchild[par];
+            const int x = a.tokens[base + n];
+            double none_before = 1.0, none_at_all = 1.0;
+            bool first_carrier = true;
+            int j = 0;
+            for (int l = 0; l < k; ++l) {
+                const int sib = tree.child_list[off + l];
+                if (sib == n) j = l;
+                if (sib < n) {                        // list order is node order
+                    none_before *= 1.0 - sh_v[sib];
+                    if (a.tokens[base + sib] == x) first_carrier = false;
+                }
+                none_at_all *= 1.0 - sh_v[sib];
+            }
+            if (a.walk == 0) step = sh_v[n] * none_before;
+            else if (a.walk == 1) step = first_carrier ? sh_v[n] : 0.0;
+            else if (a.walk == 2) {
+                const double a1 = sh_v[tree.child_list[off]];
+                step = (j == 0 ? a1 : 0.0) + (first_carrier ? (1.0 - a1) * sh_w[n] : 0.0);
+            } else {
+                step = sh_v[n] * none_before + (first_carrier ? sh_w[n] * none_at_all : 0.0);
+            }
+        }
+        __builtin_amdgcn_wave_barrier();              // everybody has read sh_v / sh_w
+        if (live) sh_v[n] = step;
+        __builtin_amdgcn_wave_barrier();
+        if (live) {
+            reach = 1.0;
+            for (int m = n; m > 0; m = tree.parent[m]) reach *= sh_v[m];
+        }
+    }
+    if (live && a.reach_prob) a.reach_prob[base + n] = static_cast<float>(reach);
+    const double total = wave_sum(live ? reach : 0.0);
+    if (n == 0) a.expected[b] = static_cast<float>(total);
+}
+
 // ------------------------------------------------------------------ bonus sample
 
 // r_v = (p_v - c q_v)_+ up to the common factor 2^-At_lo, for the VEC elements a lane
@@ -989,9 +1167,7 @@ struct ResidualTile {
     const typename E::T* zd;
     int V;
     bool aligned, use_d;
-    bool spectr;                    // r = (p - gamma min(p/rho*, q))_+ (App. B, Alg. 3) instead of (p - c q)_+
     float k32, nAt, nAd, rho;
-    float gamma, inv_rho;           // SpecTr only; rho above is then 2^(remainder difference), about 1
 
     __device__ __forceinline__ void load(int tile, int lane, float (&r)[PER_LANE]) const {
         const int e0 = tile * TILE + lane * PER_LANE;
@@ -1013,7 +1189,6 @@ struct ResidualTile {
         const float et = fast_exp2(fmaf(t, k32, nAt));
         if (!use_d) return et;
         const float ed = fast_exp2(fmaf(d, k32, nAd));
-        if (spectr) return fmaxf(fmaf(-gamma, fminf(et * inv_rho, rho * ed), et), 0.f);
         return fmaxf(fmaf(-rho, ed, et), 0.f);
     }
 };
@@ -1069,15 +1244,7 @@ __device__ __forceinline__ int sample_task(const TreeDesc& tree, const Workspace
     rt_.aligned = ((reinterpret_cast<uintptr_t>(zt) & 15u) == 0);
     rt_.use_d = (c > 0.0);
     rt_.k32 = a.k32;
-    rt_.spectr = false; rt_.gamma = 0.f; rt_.inv_rho = 0.f;
-    if (rt_.use_d && a.walk == 3) {
-        // c holds rho*; the vector drawn from is (p - gamma min(p/rho*, q))_+
-        const ResidualConsts rc = residual_consts(At, Ad, 1.0);
-        rt_.nAt = rc.nAt; rt_.nAd = rc.nAd; rt_.rho = rc.rho;
-        rt_.spectr = true;
-        rt_.gamma = static_cast<float>(ld_shared_f64(&ws.aux[bn]));
-        rt_.inv_rho = static_cast<float>(1.0 / c);
-    } else if (rt_.use_d) {
+    if (rt_.use_d) {
         const ResidualConsts rc = residual_consts(At, Ad, c);
         rt_.nAt = rc.nAt; rt_.nAd = rc.nAd; rt_.rho = rc.rho;
     } else {
@@ -1457,6 +1624,17 @@ static int compute_units() {
     return cus;
 }
 
+// Start-up spread of the persistent workgroups (Args::stagger_ticks): about the time one
+// workgroup needs to read a row pair when every compute unit is reading (its share of
+// ~6.3 TB/s), only for rows long enough to be kept on chip (short rows finish before it
+// would matter).
+static int32_t stagger_ticks(const mpv_problem* p) {
+    const double pair_bytes = 2.0 * p->V * (p->logit_dtype == MPV_DTYPE_F32 ? 4 : 2);
+    const double share_bytes_per_us = 6.3e6 / compute_units();
+    const double us = pair_bytes / share_bytes_per_us;
+    return (pair_bytes >= 400e3) ? static_cast<int32_t>(us * 100.0 / 8.0) : 0;
+}
+
 template <class E>
 static int launch_all(const mpv_problem* p, const Plan& plan, const Workspace& ws, const Args& a, hipStream_t s) {
     TreeDesc tree = plan.tree;
@@ -1477,16 +1655,16 @@ static int launch_all(const mpv_problem* p, const Plan& plan, const Workspace& w
         q.off[c + 1] = q.off[c] + p->B * (in_class[c] + (c == 0 ? 1 : 0));     // class 0 also holds the sampling tasks
     int prequeued[kMaxClasses] = {0};
     for (int n = 0; n < p->N; ++n) q.init_slot[n] = -1;
-    const bool all_up_front = (p->method == MPV_METHOD_SPECINFER && !a.lazy);
+    const bool all_up_front = (p->method != MPV_METHOD_TRAVERSAL && !a.lazy);
     for (int kk = MPV_MAX_CHILDREN; kk >= 1; --kk)
         for (int n = 0; n < p->N; ++n)
-            if (tree.nchild[n] == kk && (all_up_front || n == 0) && a.walk != 1)      // NSS has no node tasks
+            if (tree.nchild[n] == kk && (all_up_front || n == 0) && (a.walk != 1 || !a.lazy))      // NSS verification has no node tasks
                 q.init_slot[n] = prequeued[tree.cls[n]]++;
     for (int c = 0; c < q.nclass; ++c) {
         q.init_tail[c] = prequeued[c] * p->B;
         q.init_total += q.init_tail[c];
     }
-    if (tree.nchild[0] == 0 || a.walk == 1) {
+    if (tree.nchild[0] == 0 || (a.walk == 1 && a.lazy)) {
         q.root_is_leaf = 1;
         q.init_tail[0] = p->B;
         q.init_total = p->B;
@@ -1599,19 +1777,45 @@ int mpv_verify(const mpv_problem* problem, const mpv_buffers* buf, void* workspa
     a.k32 = static_cast<float>(1.4426950408889634 / static_cast<double>(problem->temperature));
     a.invT = 1.0f / problem->temperature;
     a.lazy = (walk || (buf->edge_probs == nullptr && buf->accept_prob == nullptr && buf->stats == nullptr)) ? 1 : 0;
-    {
-        // start-up spread of the persistent workgroups: about the time one workgroup needs to
-        // read a row pair when every compute unit is reading (its share of ~6.3 TB/s), only
-        // for rows long enough to be kept on chip (short rows finish before it would matter)
-        const double pair_bytes = 2.0 * problem->V * (problem->logit_dtype == MPV_DTYPE_F32 ? 4 : 2);
-        const double share_bytes_per_us = 6.3e6 / mpv::compute_units();
-        const double us = pair_bytes / share_bytes_per_us;
-        a.stagger_ticks = (pair_bytes >= 400e3) ? static_cast<int32_t>(us * 100.0 / 8.0) : 0;
-    }
+    a.estimate = 0; a.reach_prob = nullptr; a.expected = nullptr;
+    a.stagger_ticks = mpv::stagger_ticks(problem);
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     if (problem->logit_dtype == MPV_DTYPE_F32) return mpv::launch_all<mpv::ElemF32>(problem, plan, ws, a, s);
     return mpv::launch_all<mpv::ElemBF16>(problem, plan, ws, a, s);
 }
+
+int mpv_block_efficiency(const mpv_problem* problem, const void* target_logits, const void* draft_logits,
+                         const int32_t* tokens, void* workspace, size_t workspace_bytes,
+                         float* reach_prob, float* expected, uint32_t* counters, void* hip_stream) {
+    mpv::Plan plan;
+    const int rc = mpv::validate(problem, &plan);
+    if (rc != MPV_OK) return rc;
+    if (problem->B == 0) return MPV_OK;
+    if (!target_logits || !draft_logits || !tokens || !expected || !counters) return MPV_ERR_NULL;
+    if ((reinterpret_cast<uintptr_t>(target_logits) & 15u) || (reinterpret_cast<uintptr_t>(draft_logits) & 15u))
+        return MPV_ERR_ALIGNMENT;
+    const size_t need = mpv::carve(problem, nullptr, nullptr);
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) || workspace_bytes < need) return MPV_ERR_WORKSPACE;
+
+    mpv::Workspace ws;
+    mpv::carve(problem, workspace, &ws);
+    mpv::Args a;
+    memset(&a, 0, sizeof(a));
+    a.zt = target_logits; a.zd = draft_logits; a.tokens = tokens;
+    a.walk = problem->method == MPV_METHOD_NSS ? 1 : problem->method == MPV_METHOD_NAIVE ? 2
+           : problem->method == MPV_METHOD_SPECTR ? 3 : 0;
+    a.counters = counters;
+    a.B = problem->B; a.N = problem->N; a.V = problem->V; a.max_depth = problem->max_depth;
+    a.k32 = static_cast<float>(1.4426950408889634 / static_cast<double>(problem->temperature));
+    a.invT = 1.0f / problem->temperature;
+    a.lazy = 0;
+    a.estimate = 1; a.reach_prob = reach_prob; a.expected = expected;
+    a.stagger_ticks = mpv::stagger_ticks(problem);
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    if (problem->logit_dtype == MPV_DTYPE_F32) return mpv::launch_all<mpv::ElemF32>(problem, plan, ws, a, s);
+    return mpv::launch_all<mpv::ElemBF16>(problem, plan, ws, a, s);
+}
+
 
 int mpv_timing_enable(int32_t max_launches) {
     mpv::LaunchTimer& t = mpv::g_timer;

@@ -605,32 +605,6 @@ struct PairStatsRawF {
     }
 };
 
-// beta(rho) = sum_v min(p_v / rho, q_v) (App. B, SpecTr), in the same form as ResidualMassF:
-// with the constants of residual_consts(At + log2 rho, Ad, 1) a term is min(e_t, kappa e_d) and
-// the caller multiplies the sum by `scale`.
-template <class E>
-struct MinMassRawF {
-    float k32, nAt, nAd, rho;       // rho: the factor kappa = 2^(remainder difference), about 1
-    float acc0, acc1;
-    __device__ __forceinline__ void init() { acc0 = 0.f; acc1 = 0.f; }
-    __device__ __forceinline__ float term(float a, float b) const {
-        const float et = fast_exp2(fmaf(a, k32, nAt));
-        const float ed = fast_exp2(fmaf(b, k32, nAd));
-        return fminf(et, rho * ed);
-    }
-    __device__ __forceinline__ void one(float a, float b) { acc0 += term(a, b); }
-    __device__ __forceinline__ void vec(const uint4& ra, const uint4& rb) {
-        float a[E::VEC], b[E::VEC];
-        E::unpack(ra, a);
-        E::unpack(rb, b);
-#pragma unroll
-        for (int i = 0; i < E::VEC; i += 2) {
-            acc0 += term(a[i], b[i]);
-            acc1 += term(a[i + 1], b[i + 1]);
-        }
-    }
-};
-
 template <class E>
 struct ResidualMassRawF : ResidualMassF<E> {
     __device__ __forceinline__ void vec(const uint4& ra, const uint4& rb) {
