@@ -71,6 +71,7 @@ def side_measurements(mpv, torch, cfg, inputs, method, pair_bytes, steps=5):
     """Two reference points for the roofline, outside the timed region.
     every_node_task: the same call with the per-node test probabilities requested, which makes the
     library run the task of every internal node instead of only those the rule needs.
+    block_efficiency_estimate: mpv_block_efficiency (expected accepted length + 1 of every tree, no sampling).
     softmax_statistics_only: step S2 alone (mpv_row_stats) over every target row of the batch."""
     def timed(fn):
         for _ in range(2):
@@ -93,6 +94,14 @@ def side_measurements(mpv, torch, cfg, inputs, method, pair_bytes, steps=5):
     gbs = tasks * pair_bytes / s / 1e9
     res["every_node_task"] = {"ms_per_step": s * 1e3, "node_tasks_run": tasks,
                               "algorithmic_GBps": gbs, "frac_of_hbm_peak": gbs / HBM_PEAK_GBS}
+    be = mpv.mpv_block_efficiency(inputs["parent"], inputs["tokens"], inputs["target"], inputs["draft"], cfg.T, method)
+    s = timed(lambda: mpv.mpv_block_efficiency(inputs["parent"], inputs["tokens"], inputs["target"],
+                                               inputs["draft"], cfg.T, method, out=be))
+    tasks = be.counters.tolist()[5]
+    gbs = tasks * pair_bytes / s / 1e9
+    res["block_efficiency_estimate"] = {"ms_per_step": s * 1e3, "node_tasks_run": tasks,
+                                        "mean_expected_block_efficiency": float(be.expected.mean().item()),
+                                        "algorithmic_GBps": gbs, "frac_of_hbm_peak": gbs / HBM_PEAK_GBS}
     rows = inputs["target"].view(cfg.B * cfg.N, cfg.V)
     st = mpv.mpv_row_stats(rows, cfg.T)
     s = timed(lambda: mpv.mpv_row_stats(rows, cfg.T, out=st))

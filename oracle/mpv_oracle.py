@@ -292,23 +292,32 @@ def spectr_division_factor(P, Q, k):
 
 
 def spectr_conditioning(P, Q, k, rho):
-    """|d ln rho* / d ln beta|: how much a relative error in the sum beta moves the root.
+    """How much relative errors of size e in the V-wide sums move the root: |d ln rho*| <= kappa * e.
 
-    From f(rho) = 1 - (1 - beta(rho))^k - rho*beta(rho) with beta(rho) scaled by (1 + e):
-    d rho*/d e = -(df/dbeta * beta) / f'(rho).  Large when rho* is close to 1 and p is close
-    to q (f is then nearly flat).  Used by the parity tests to turn the accuracy of a
-    float32 sum into a tolerance on SpecTr's test probabilities; no verification step uses it.
+    With W = sum (p - rho q)_+, D = sum (q - p/rho)_+ = (W + rho - 1)/rho and f = W - D^k (see
+    spectr_division_factor): an error e in W and in the normalisation of p and q changes f by at
+    most e * (W + k D^(k-1) (W + 2)/rho), and f' = -sum_{p > rho q} q - k D^(k-1) sum_{p < rho q} p/rho^2.
+    The root often sits on, or within 1e-7 of, a kink of f (the ratio p/q of a dominant token), where
+    the slopes to the left and right differ by orders of magnitude: the slopes are taken 1e-6 to
+    either side (closer than float32 sums can tell apart) and the flatter one counts.  Used by the parity
+    tests to turn the accuracy of float32 sums into a tolerance on SpecTr's test probabilities; no
+    verification step uses it.
     """
     if k <= 1:
         return 0.0
-    beta = spectr_beta(P, Q, rho)
-    df_dbeta = k * (1.0 - beta) ** (k - 1) - rho
-    low = np.asarray(P) / rho < np.asarray(Q)                     # where min picks p/rho
-    dbeta_drho = -float(np.sum(np.asarray(P)[low])) / (rho * rho)
-    f_prime = df_dbeta * dbeta_drho - beta
-    if f_prime == 0.0:
+    P = np.asarray(P, dtype=np.float64)
+    Q = np.asarray(Q, dtype=np.float64)
+    W = float(np.sum(np.maximum(P - rho * Q, 0.0)))
+    D = float(np.sum(np.maximum(Q - P / rho, 0.0)))
+    df = W + k * D ** (k - 1) * (W + 2.0) / rho
+    slopes = []
+    for r in (rho * (1.0 - 1e-6), rho * (1.0 + 1e-6)):       # just left and just right of the root
+        up = P > r * Q
+        slopes.append(float(np.sum(Q[up])) + k * D ** (k - 1) * float(np.sum(P[~up])) / (r * r))
+    slope = min(slopes)
+    if slope <= 0.0:
         return float("inf")
-    return abs(df_dbeta * beta / (f_prime * rho))
+    return df / (slope * rho)
 
 
 def spectr_solver(P, Q, xs, decide):

@@ -20,11 +20,12 @@ from oracle import mpv_oracle as orc
 DECISION_BAND = 1e-6
 BONUS_BAND = 1e-6
 PROB_ATOL = 1e-5
-# SpecTr's division factor is the root of a function of the V-wide sum beta; where that function is
-# flat (rho* near 1, p close to q) a relative error e in the sum moves the root, and with it every
-# test probability p/(rho* q), by kappa * e, kappa = oracle.spectr_conditioning.  The paper gives
-# no stopping rule for its binary search; the library's root is exact up to the accuracy of its
-# float32 sums, taken as 3e-7 relative here (three times the 1e-7 the design notes derive).
+# SpecTr's division factor is the root of a function of V-wide sums; a relative error e in those
+# sums moves the root, and with it every test probability p/(rho* q), by up to kappa * e,
+# kappa = oracle.spectr_conditioning (large only where the function is flat on one side of the
+# root).  The paper gives no stopping rule for its binary search; the library's root is exact up
+# to the accuracy of its float32 sums, taken as 3e-7 relative here (three times the 1e-7 the
+# design notes derive).
 SUM_REL_ERR = 3e-7
 
 
