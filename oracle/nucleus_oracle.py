@@ -1,0 +1,67 @@
+"""fp64 CPU oracle for the nucleus (top-p) transform of a logit row.
+
+THIS IS TEST INFRASTRUCTURE, NOT THE PRODUCT (see mpv_oracle.py): only the tests,
+the smoke check and the benchmark's cpu_baseline leg may import it; it shares no
+code with the HIP library and never calls it.
+
+The paper evaluates two sampling settings with nucleus sampling (Sec. 4.1: top-p 0.9
+and 0.99 at temperature 1) and says nothing else about it.  The definition taken
+(a reading, listed in the design notes) is the usual one: with p = softmax(z / T),
+keep the smallest set of most probable tokens whose probabilities add up to at
+least top_p, drop the rest, renormalise.  Tokens with equal logits are kept or
+dropped together (the set is {v : z_v >= tau} for a threshold tau that is one of
+the row's values), so the result does not depend on the order of the vocabulary.
+Dropped tokens get the logit -inf: every later step then sees the renormalised
+distribution without knowing about the transform.  The same transform, with the
+same top_p, is applied to the target and the draft rows.
+"""
+
+from __future__ import annotations
+
+import numpy as np
+
+from . import mpv_oracle as base
+
+
+def nucleus_threshold(z, T, top_p):
+    """(tau, kept, margin) for one row of logits.
+
+    tau: the smallest kept logit; kept: how many tokens are kept;
+    margin: the smallest |mass of {z >= t} - top_p| over the row's values t (how close the
+    choice of tau came to going the other way)."""
+    z = np.asarray(z, dtype=np.float64)
+    p = base.softmax_T(z, T)
+    values = np.unique(z)[::-1]                     # distinct logits, largest first
+    tau, kept, margin = values[0], 0, np.inf
+    mass = 0.0
+    found = False
+    for t in values:
+        cls = z == t
+        mass += float(np.sum(p[cls]))               # mass of {z >= t}
+        margin = min(margin, abs(mass - float(top_p)))
+        if not found:
+            tau = t
+            kept += int(np.count_nonzero(cls))
+            if mass >= float(top_p):
+                found = True
+    return float(tau), kept, float(margin)
+
+
+def nucleus_mask(z, T, top_p):
+    """The row with every token outside the nucleus set to -inf (same dtype as float64 copy)."""
+    z = np.asarray(z, dtype=np.float64)
+    tau, _, _ = nucleus_threshold(z, T, top_p)
+    return np.where(z >= tau, z, -np.inf)
+
+
+def nucleus_mask_rows(z, T, top_p):
+    """Rows of a [rows, V] array; returns (masked float64 [rows, V], tau [rows], kept [rows], margin [rows])."""
+    z = np.asarray(z)
+    out = np.empty(z.shape, dtype=np.float64)
+    tau = np.empty(len(z))
+    kept = np.empty(len(z), dtype=np.int64)
+    margin = np.empty(len(z))
+    for r in range(len(z)):
+        tau[r], kept[r], margin[r] = nucleus_threshold(z[r], T, top_p)
+        out[r] = np.where(np.asarray(z[r], dtype=np.float64) >= tau[r], z[r], -np.inf)
+    return out, tau, kept, margin
