@@ -71,6 +71,7 @@ def side_measurements(mpv, torch, cfg, inputs, method, pair_bytes, steps=5):
     """Two reference points for the roofline, outside the timed region.
     every_node_task: the same call with the per-node test probabilities requested, which makes the
     library run the task of every internal node instead of only those the rule needs.
+    nucleus_mask_top_p_0.9: mpv_nucleus_mask over every target row of the batch (out of place).
     block_efficiency_estimate: mpv_block_efficiency (expected accepted length + 1 of every tree, no sampling).
     softmax_statistics_only: step S2 alone (mpv_row_stats) over every target row of the batch."""
     def timed(fn):
@@ -103,6 +104,12 @@ def side_measurements(mpv, torch, cfg, inputs, method, pair_bytes, steps=5):
                                         "mean_expected_block_efficiency": float(be.expected.mean().item()),
                                         "algorithmic_GBps": gbs, "frac_of_hbm_peak": gbs / HBM_PEAK_GBS}
     rows = inputs["target"].view(cfg.B * cfg.N, cfg.V)
+    masked = torch.empty_like(rows)
+    s = timed(lambda: mpv.mpv_nucleus_mask(rows, cfg.T, 0.9, out=masked))
+    gbs = 2 * rows.numel() * rows.element_size() / s / 1e9          # read once, written once
+    res["nucleus_mask_top_p_0.9"] = {"ms_per_step": s * 1e3, "rows": cfg.B * cfg.N,
+                                     "algorithmic_GBps": gbs, "frac_of_hbm_peak": gbs / HBM_PEAK_GBS}
+    del masked
     st = mpv.mpv_row_stats(rows, cfg.T)
     s = timed(lambda: mpv.mpv_row_stats(rows, cfg.T, out=st))
     gbs = rows.numel() * rows.element_size() / s / 1e9

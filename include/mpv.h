@@ -64,7 +64,7 @@
 extern "C" {
 #endif
 
-#define MPV_ABI_VERSION 3
+#define MPV_ABI_VERSION 4
 
 /* limits (larger requests return MPV_ERR_UNSUPPORTED) */
 #define MPV_MAX_NODES    64   /* nodes per tree, root included            */
@@ -93,6 +93,7 @@ extern "C" {
 #define MPV_ERR_UNSUPPORTED     -8   /* beyond MPV_MAX_*; stats / edge_probs with methods >= 2 */
 #define MPV_ERR_HIP             -9   /* a HIP call failed; see mpv_last_hip_error()   */
 #define MPV_ERR_ALIGNMENT      -10   /* a logit base pointer is not element-aligned   */
+#define MPV_ERR_BAD_TOP_P      -11   /* top_p is not in (0, 1]                        */
 
 /* Problem description.  Host memory, read during the call only. */
 typedef struct mpv_problem {
@@ -188,6 +189,22 @@ int mpv_verify(const mpv_problem* problem, const mpv_buffers* buffers,
 int mpv_block_efficiency(const mpv_problem* problem, const void* target_logits, const void* draft_logits,
                          const int32_t* tokens, void* workspace, size_t workspace_bytes,
                          float* reach_prob, float* expected, uint32_t* counters, void* hip_stream);
+
+/* Nucleus (top-p) transform of `rows` contiguous logit rows of length V (Sec. 4.1: two of the
+ * paper's eight sampling settings use nucleus sampling; the paper does not define it, the usual
+ * definition is taken).  With p = softmax(z / T), row by row: the smallest set {v : z_v >= tau},
+ * tau one of the row's values, whose mass reaches top_p, is kept; every other token gets the logit
+ * -inf, so that verification of the masked rows is verification with the truncated, renormalised
+ * distributions.  Tokens with equal logits are kept or dropped together; top_p = 1 keeps every
+ * token.  Apply it to the target and to the draft rows (and draw the draft tokens from the
+ * masked draft rows) before mpv_verify / mpv_block_efficiency.
+ * logits, out: DEVICE, [rows, V] of logit_dtype, 16-byte aligned bases; out may equal logits
+ * (in place), otherwise the buffers must not overlap.  Logits must be finite or -inf.
+ * threshold_out: DEVICE float32 [rows] or NULL: tau.  kept_out: DEVICE int32 [rows] or NULL: the
+ * number of tokens kept.  Errors: MPV_ERR_BAD_SHAPE (rows < 0, V < 1), _UNSUPPORTED (V or rows too
+ * large), _BAD_DTYPE, _BAD_TEMPERATURE, _BAD_TOP_P, _NULL, _ALIGNMENT, _HIP. */
+int mpv_nucleus_mask(const void* logits, void* out, int32_t logit_dtype, int64_t rows, int32_t V,
+                     float temperature, float top_p, float* threshold_out, int32_t* kept_out, void* hip_stream);
 
 /* Softmax statistics of `rows` contiguous logit rows of length V (the first step
  * of the path, exposed on its own): out[r] = { max_v z, ln sum_v exp((z - max)/T) }

@@ -31,20 +31,15 @@ def nucleus_threshold(z, T, top_p):
     choice of tau came to going the other way)."""
     z = np.asarray(z, dtype=np.float64)
     p = base.softmax_T(z, T)
-    values = np.unique(z)[::-1]                     # distinct logits, largest first
-    tau, kept, margin = values[0], 0, np.inf
-    mass = 0.0
-    found = False
-    for t in values:
-        cls = z == t
-        mass += float(np.sum(p[cls]))               # mass of {z >= t}
-        margin = min(margin, abs(mass - float(top_p)))
-        if not found:
-            tau = t
-            kept += int(np.count_nonzero(cls))
-            if mass >= float(top_p):
-                found = True
-    return float(tau), kept, float(margin)
+    order = np.argsort(-z, kind="stable")           # largest logit first
+    zs, ps = z[order], p[order]
+    upper_mass = np.cumsum(ps)                      # mass of the first i+1 tokens in that order
+    # a set {z >= t} ends where the sorted value changes (equal logits stay together)
+    ends = np.nonzero(np.append(zs[1:] != zs[:-1], True))[0]
+    mass = upper_mass[ends]                         # mass of {z >= zs[e]} for every distinct value
+    reached = np.nonzero(mass >= float(top_p))[0]
+    j = int(reached[0]) if len(reached) else len(ends) - 1      # top_p = 1 and a sum that rounds below 1: everything
+    return float(zs[ends[j]]), int(ends[j]) + 1, float(np.min(np.abs(mass - float(top_p))))
 
 
 def nucleus_mask(z, T, top_p):

@@ -81,6 +81,9 @@ def load_library(path=None):
     lib.mpv_block_efficiency.argtypes = [ctypes.POINTER(_Problem), ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                          ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p,
                                          ctypes.c_void_p, ctypes.c_void_p]
+    lib.mpv_nucleus_mask.restype = ctypes.c_int
+    lib.mpv_nucleus_mask.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_int32,
+                                     ctypes.c_float, ctypes.c_float, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
     lib.mpv_row_stats.restype = ctypes.c_int
     lib.mpv_row_stats.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_int32,
                                   ctypes.c_float, ctypes.c_void_p, ctypes.c_void_p]
@@ -276,6 +279,31 @@ def mpv_block_efficiency(parent, tokens, target_logits, draft_logits, temperatur
     if rc != 0:
         raise MpvError(rc, "mpv_block_efficiency")
     return out
+
+
+def mpv_nucleus_mask(logits, temperature, top_p, out=None, inplace=False, stream=None):
+    """Nucleus (top-p) transform of every row of a CUDA tensor [..., V] (see include/mpv.h): tokens
+    outside the nucleus get the logit -inf.  Returns (masked, threshold[...], kept[...]); with
+    inplace=True `masked` is `logits` itself."""
+    import torch
+    if not logits.is_cuda or not logits.is_contiguous() or logits.dim() < 1:
+        raise ValueError("logits must be a contiguous CUDA tensor")
+    V = logits.shape[-1]
+    rows = logits.numel() // V if V else 0
+    if inplace:
+        out = logits
+    elif out is None:
+        out = torch.empty_like(logits)
+    lead = tuple(logits.shape[:-1])
+    thr = torch.empty(lead, dtype=torch.float32, device=logits.device)
+    kept = torch.empty(lead, dtype=torch.int32, device=logits.device)
+    rc = load_library().mpv_nucleus_mask(ctypes.c_void_p(logits.data_ptr()), ctypes.c_void_p(out.data_ptr()),
+                                         _dtype_id(logits), rows, V, float(temperature), float(top_p),
+                                         ctypes.c_void_p(thr.data_ptr()), ctypes.c_void_p(kept.data_ptr()),
+                                         _stream_ptr(stream))
+    if rc != 0:
+        raise MpvError(rc, "mpv_nucleus_mask")
+    return out, thr, kept
 
 
 def mpv_row_stats(logits, temperature, out=None, stream=None):

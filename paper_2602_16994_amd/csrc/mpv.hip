@@ -28,6 +28,7 @@
 
 #include "mpv.h"
 #include "mpv_device.h"
+#include "mpv_nucleus.h"
 
 namespace mpv {
 
@@ -1731,6 +1732,7 @@ const char* mpv_strerror(int code) {
         case MPV_ERR_UNSUPPORTED: return "problem exceeds MPV_MAX_NODES / MPV_MAX_CHILDREN / MPV_MAX_VOCAB, or a debug output this method does not provide was requested";
         case MPV_ERR_HIP: return "a HIP call failed (see mpv_last_hip_error)";
         case MPV_ERR_ALIGNMENT: return "logit base pointers must be 16-byte aligned";
+        case MPV_ERR_BAD_TOP_P: return "top_p must lie in (0, 1]";
         default: return "unknown error code";
     }
 }
@@ -1874,6 +1876,31 @@ int mpv_row_stats(const void* logits, int32_t logit_dtype, int64_t rows, int32_t
     else
         hipLaunchKernelGGL((mpv::row_stats_kernel<mpv::ElemBF16>), dim3(static_cast<unsigned>(rows)), dim3(mpv::kTaskBlock), 0, s,
                            static_cast<const uint16_t*>(logits), rows, V, k32, 1.0f / temperature, out);
+    return mpv::hip_ok(hipGetLastError()) ? MPV_OK : MPV_ERR_HIP;
+}
+
+int mpv_nucleus_mask(const void* logits, void* out, int32_t logit_dtype, int64_t rows, int32_t V,
+                     float temperature, float top_p, float* threshold_out, int32_t* kept_out, void* hip_stream) {
+    if (rows < 0 || V < 1) return MPV_ERR_BAD_SHAPE;
+    if (V > MPV_MAX_VOCAB || rows > 0x7fffffffLL) return MPV_ERR_UNSUPPORTED;
+    if (logit_dtype != MPV_DTYPE_F32 && logit_dtype != MPV_DTYPE_BF16) return MPV_ERR_BAD_DTYPE;
+    if (!(temperature > 0.0f) || !isfinite(temperature)) return MPV_ERR_BAD_TEMPERATURE;
+    if (!(top_p > 0.0f) || !(top_p <= 1.0f)) return MPV_ERR_BAD_TOP_P;
+    if (rows == 0) return MPV_OK;
+    if (!logits || !out) return MPV_ERR_NULL;
+    if ((reinterpret_cast<uintptr_t>(logits) & 15u) || (reinterpret_cast<uintptr_t>(out) & 15u)) return MPV_ERR_ALIGNMENT;
+    const float k32 = static_cast<float>(1.4426950408889634 / static_cast<double>(temperature));
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    (void)hipGetLastError();
+    const dim3 grid(static_cast<unsigned>(rows)), block(mpv::kNucleusBlock);
+    // top_p = 1 keeps every token: a threshold no mass can miss
+    const float p = top_p < 1.0f ? top_p : 0.0f;
+    if (logit_dtype == MPV_DTYPE_F32)
+        hipLaunchKernelGGL((mpv::nucleus_kernel<mpv::ElemF32>), grid, block, 0, s, static_cast<const float*>(logits),
+                           static_cast<float*>(out), rows, V, k32, p, top_p < 1.0f ? 0 : 1, threshold_out, kept_out);
+    else
+        hipLaunchKernelGGL((mpv::nucleus_kernel<mpv::ElemBF16>), grid, block, 0, s, static_cast<const uint16_t*>(logits),
+                           static_cast<uint16_t*>(out), rows, V, k32, p, top_p < 1.0f ? 0 : 1, threshold_out, kept_out);
     return mpv::hip_ok(hipGetLastError()) ? MPV_OK : MPV_ERR_HIP;
 }
 

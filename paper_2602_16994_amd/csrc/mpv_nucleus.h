@@ -1,0 +1,178 @@
+// Nucleus (top-p) transform of logit rows: device code (included by mpv.hip).
+//
+// Sec. 4.1 names the setting (nucleus sampling with top-p 0.9 and 0.99); the definition taken
+// is the usual one.  With p = softmax(z / T): keep the smallest set {v : z_v >= tau}, tau one
+// of the row's values, whose mass reaches top_p; every other token gets the logit -inf, so that
+// whatever reads the row afterwards sees the renormalised truncated distribution.  Tokens with
+// equal logits are kept or dropped together.
+//
+// One workgroup per row:
+//   1. softmax statistics of the row (maximum, log2 of the partition sum);
+//   2. tau by bisection over the order-preserving integer keys of float values.  One sweep per
+//      step: the mass of {z >= cut} together with the nearest row values on either side of the
+//      cut, to which the bracket then snaps, so a step never lands between two row values
+//      twice.  At most 33 sweeps for float rows, 18 for bfloat16 rows; the row stays in L2;
+//   3. the row is written out, masked.
+// The masses are float sums in a fixed order (bitwise reproducible); "reaches top_p" is decided
+// against the sum of the whole row computed the same way.
+
+#pragma once
+
+#include "mpv_device.h"
+
+namespace mpv {
+
+constexpr int kNucleusBlock = 512;
+constexpr int kNucleusUnroll = 4;     // 16-byte loads in flight per lane
+
+// ascending unsigned key of a float (no NaN): negative values reversed, sign bit flipped
+__device__ __forceinline__ uint32_t float_key(float f) {
+    const uint32_t b = __float_as_uint(f + 0.0f);            // -0 -> +0
+    return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+__device__ __forceinline__ float key_float(uint32_t k) {
+    return __uint_as_float((k & 0x80000000u) ? (k & 0x7fffffffu) : ~k);
+}
+
+template <class E>
+struct NucleusProbeF {
+    float k32, nA;          // p_v = 2^(z_v k32 + nA), up to a factor common to the row
+    float cut;
+    float acc0, acc1;       // mass of {z >= cut}
+    float below, above;     // largest z < cut, smallest z >= cut
+    int count;              // |{z >= cut}|
+    __device__ __forceinline__ void init(float k, float na, float c) {
+        k32 = k; nA = na; cut = c; acc0 = 0.f; acc1 = 0.f; below = -INFINITY; above = INFINITY; count = 0;
+    }
+    __device__ __forceinline__ void item(float z, float& acc) {
+        const float e = fast_exp2(fmaf(z, k32, nA));
+        const bool in = z >= cut;
+        acc += in ? e : 0.f;
+        below = in ? below : fmaxf(below, z);
+        above = in ? fminf(above, z) : above;
+        count += in ? 1 : 0;
+    }
+    __device__ __forceinline__ void one(float z) { item(z, acc0); }
+    __device__ __forceinline__ void vec(const float (&z)[E::VEC]) {
+#pragma unroll
+        for (int i = 0; i < E::VEC; i += 2) { item(z[i], acc0); item(z[i + 1], acc1); }
+    }
+};
+
+struct NucleusProbeResult { double mass; float below, above; int count; };
+
+// Block-wide result of one probe sweep; the same values in every lane.
+template <class E>
+__device__ __forceinline__ NucleusProbeResult nucleus_probe(const typename E::T* z, int V, float k32, float nA, float cut,
+                                                            double* scratch, float* fscratch, int* iscratch) {
+    NucleusProbeF<E> f;
+    f.init(k32, nA, cut);
+    sweep_row<E, kNucleusBlock, kNucleusUnroll>(z, V, f);
+    constexpr int NW = kNucleusBlock / kWave;
+    const int w = threadIdx.x / kWave, lane = threadIdx.x & (kWave - 1);
+    const double m = wave_sum(static_cast<double>(f.acc0) + static_cast<double>(f.acc1));
+    const float lo = wave_max(f.below);
+    const float hi = -wave_max(-f.above);
+    const int c = wave_inclusive_scan_i32(f.count);          // lane 63 holds the wave's total
+    __syncthreads();                                          // the previous probe's results have been read
+    if (lane == kWave - 1) { scratch[w] = m; fscratch[2 * w] = lo; fscratch[2 * w + 1] = hi; iscratch[w] = c; }
+    __syncthreads();
+    NucleusProbeResult r;
+    r.mass = scratch[0]; r.below = fscratch[0]; r.above = fscratch[1]; r.count = iscratch[0];
+#pragma unroll
+    for (int i = 1; i < NW; ++i) {
+        r.mass += scratch[i];
+        r.below = fmaxf(r.below, fscratch[2 * i]);
+        r.above = fminf(r.above, fscratch[2 * i + 1]);
+        r.count += iscratch[i];
+    }
+    return r;
+}
+
+template <class E> struct MaskedStore;
+template <> struct MaskedStore<ElemF32> {
+    __device__ static __forceinline__ float one(float z, float tau) { return z >= tau ? z : -INFINITY; }
+    __device__ static __forceinline__ uint4 vec(const uint4& r, float tau) {
+        uint4 o;
+        o.x = __float_as_uint(one(__uint_as_float(r.x), tau)); o.y = __float_as_uint(one(__uint_as_float(r.y), tau));
+        o.z = __float_as_uint(one(__uint_as_float(r.z), tau)); o.w = __float_as_uint(one(__uint_as_float(r.w), tau));
+        return o;
+    }
+    __device__ static __forceinline__ float to_elem(float v) { return v; }
+};
+template <> struct MaskedStore<ElemBF16> {
+    static constexpr uint32_t kNegInf = 0xff80u;
+    __device__ static __forceinline__ uint32_t word(uint32_t w, float tau) {
+        const uint32_t lo = (__uint_as_float(w << 16) >= tau) ? (w & 0xffffu) : kNegInf;
+        const uint32_t hi = (__uint_as_float(w & 0xffff0000u) >= tau) ? (w & 0xffff0000u) : (kNegInf << 16);
+        return hi | lo;
+    }
+    __device__ static __forceinline__ uint4 vec(const uint4& r, float tau) {
+        uint4 o;
+        o.x = word(r.x, tau); o.y = word(r.y, tau); o.z = word(r.z, tau); o.w = word(r.w, tau);
+        return o;
+    }
+    __device__ static __forceinline__ uint16_t to_elem(float v) { return static_cast<uint16_t>(__float_as_uint(v) >> 16); }
+};
+
+// top_p in (0, 1): see the file header; keep_all: top_p = 1, nothing is dropped (tau = the row's
+// minimum).  threshold_out / kept_out may be null.
+template <class E>
+__global__ __launch_bounds__(kNucleusBlock) void nucleus_kernel(const typename E::T* in, typename E::T* out, int64_t rows,
+                                                                int V, float k32, float top_p, int keep_all,
+                                                                float* threshold_out, int32_t* kept_out) {
+    using T = typename E::T;
+    constexpr int NW = kNucleusBlock / kWave;
+    __shared__ double scratch[2 * NW];
+    __shared__ float fscratch[2 * NW];
+    __shared__ int iscratch[NW];
+    const int64_t r = blockIdx.x;
+    const T* z = in + r * V;
+    T* o = out + r * V;
+
+    // 1. statistics
+    RowStatsF<E> sf;
+    sf.t.init(); sf.k32 = k32;
+    sweep_row<E, kNucleusBlock, kNucleusUnroll>(z, V, sf);
+    OnlineLse none; none.init();
+    RowStat rt, rd;
+    finish_stats2<kNucleusBlock>(sf.t, none, rt, rd, scratch);
+    const float nA = -static_cast<float>(rt.A);
+
+    // 2. the whole row's mass (the same sum a probe forms when everything lies above the cut), then tau
+    NucleusProbeResult all = nucleus_probe<E>(z, V, k32, nA, -INFINITY, scratch, fscratch, iscratch);
+    const double want = static_cast<double>(top_p) * all.mass;
+    float tau = all.above;                                    // the row's minimum: its upper set is the whole row
+    int kept = all.count;
+    uint32_t lo_key = float_key(tau);
+    uint32_t hi_key = float_key(rt.m) + 1u;                   // cuts from here on leave nothing above them
+    for (int step = 0; step < 40 && hi_key - lo_key > 1u && !keep_all; ++step) {
+        const float cut = key_float(lo_key + (hi_key - lo_key) / 2u);      // tau < cut <= maximum
+        const NucleusProbeResult p = nucleus_probe<E>(z, V, k32, nA, cut, scratch, fscratch, iscratch);
+        if (p.mass >= want) {
+            tau = p.above;                                    // the same upper set, named by its smallest value
+            kept = p.count;
+            lo_key = float_key(tau);
+        } else {
+            hi_key = float_key(p.below) + 1u;                 // every cut above `below` has this upper set or less
+        }
+    }
+
+    // 3. masked copy (in place if out == in: every element is read and written by the same lane)
+    const int tid = threadIdx.x;
+    const int mis = static_cast<int>((reinterpret_cast<uintptr_t>(z) & 15u) / sizeof(T));
+    const int head = mis ? min(E::VEC - mis, V) : 0;
+    const int nvec = (V - head) / E::VEC;
+    const int tail0 = head + nvec * E::VEC;
+    if (tid < head) o[tid] = MaskedStore<E>::to_elem(MaskedStore<ElemF32>::one(E::load_one(z + tid), tau));
+    if (tail0 + tid < V) o[tail0 + tid] = MaskedStore<E>::to_elem(MaskedStore<ElemF32>::one(E::load_one(z + tail0 + tid), tau));
+    const uint4* zv = reinterpret_cast<const uint4*>(z + head);
+    uint4* ov = reinterpret_cast<uint4*>(o + head);
+    for (int i = tid; i < nvec; i += kNucleusBlock) ov[i] = MaskedStore<E>::vec(zv[i], tau);
+    if (tid == 0) {
+        if (threshold_out) threshold_out[r] = tau;
+        if (kept_out) kept_out[r] = kept;
+    }
+}
+
+}  // namespace mpv
