@@ -8,10 +8,12 @@
 //
 // One workgroup per row:
 //   1. softmax statistics of the row (maximum, log2 of the partition sum);
-//   2. tau by bisection over the order-preserving integer keys of float values.  One sweep per
+//   2. tau by bisection over the order-preserving integer keys of float values.  One probe per
 //      step: the mass of {z >= cut} together with the nearest row values on either side of the
 //      cut, to which the bracket then snaps, so a step never lands between two row values
-//      twice.  At most 33 sweeps for float rows, 18 for bfloat16 rows; the row stays in L2;
+//      twice (at most 33 steps for float rows, 18 for bfloat16 rows).  A first sweep copies the
+//      tokens whose probability is within 2^-12 of the largest into LDS; if they reach top_p
+//      and fit, the probes run over that copy, else over the row itself (which stays in L2);
 //   3. the row is written out, masked.
 // The masses are float sums in a fixed order (bitwise reproducible); "reaches top_p" is decided
 // against the sum of the whole row computed the same way.
@@ -61,19 +63,15 @@ struct NucleusProbeF {
 
 struct NucleusProbeResult { double mass; float below, above; int count; };
 
-// Block-wide result of one probe sweep; the same values in every lane.
-template <class E>
-__device__ __forceinline__ NucleusProbeResult nucleus_probe(const typename E::T* z, int V, float k32, float nA, float cut,
-                                                            double* scratch, float* fscratch, int* iscratch) {
-    NucleusProbeF<E> f;
-    f.init(k32, nA, cut);
-    sweep_row<E, kNucleusBlock, kNucleusUnroll>(z, V, f);
+// One value per workgroup of each of the four numbers of a probe; the same values in every lane.
+__device__ __forceinline__ NucleusProbeResult nucleus_reduce(double mass, float below, float above, int count,
+                                                             double* scratch, float* fscratch, int* iscratch) {
     constexpr int NW = kNucleusBlock / kWave;
     const int w = threadIdx.x / kWave, lane = threadIdx.x & (kWave - 1);
-    const double m = wave_sum(static_cast<double>(f.acc0) + static_cast<double>(f.acc1));
-    const float lo = wave_max(f.below);
-    const float hi = -wave_max(-f.above);
-    const int c = wave_inclusive_scan_i32(f.count);          // lane 63 holds the wave's total
+    const double m = wave_sum(mass);
+    const float lo = wave_max(below);
+    const float hi = -wave_max(-above);
+    const int c = wave_inclusive_scan_i32(count);            // lane 63 holds the wave's total
     __syncthreads();                                          // the previous probe's results have been read
     if (lane == kWave - 1) { scratch[w] = m; fscratch[2 * w] = lo; fscratch[2 * w + 1] = hi; iscratch[w] = c; }
     __syncthreads();
@@ -87,6 +85,80 @@ __device__ __forceinline__ NucleusProbeResult nucleus_probe(const typename E::T*
         r.count += iscratch[i];
     }
     return r;
+}
+
+// Probe over the whole row in memory.
+template <class E>
+__device__ __forceinline__ NucleusProbeResult nucleus_probe(const typename E::T* z, int V, float k32, float nA, float cut,
+                                                            double* scratch, float* fscratch, int* iscratch) {
+    NucleusProbeF<E> f;
+    f.init(k32, nA, cut);
+    sweep_row<E, kNucleusBlock, kNucleusUnroll>(z, V, f);
+    return nucleus_reduce(static_cast<double>(f.acc0) + static_cast<double>(f.acc1), f.below, f.above, f.count,
+                          scratch, fscratch, iscratch);
+}
+
+// The tokens that can matter are usually few: those whose probability is within 2^-kNucleusSpan of
+// the largest.  One sweep copies them (value and mass) into LDS; if they hold enough mass and fit,
+// tau is found among them without touching the row again.
+constexpr int kNucleusCap = 8192;
+constexpr float kNucleusSpan = 12.f;
+// candidate masses are added as integers (units of 2^-40, exact in a double): the order in which
+// the waves append their candidates does not change any sum
+constexpr double kNucleusUnit = 1099511627776.0;
+
+template <class E>
+struct NucleusCollectF {
+    float k32, nA, cut;
+    float* cand_z;
+    float* cand_e;
+    int* cand_n;
+    float acc0, acc1, below, above;
+    int count;
+    __device__ __forceinline__ void init(float k, float na, float c, float* cz, float* ce, int* cn) {
+        k32 = k; nA = na; cut = c; cand_z = cz; cand_e = ce; cand_n = cn;
+        acc0 = 0.f; acc1 = 0.f; below = -INFINITY; above = INFINITY; count = 0;
+    }
+    __device__ __forceinline__ void item(float z, float& acc) {
+        const float e = fast_exp2(fmaf(z, k32, nA));
+        const bool in = z >= cut;
+        acc += in ? e : 0.f;
+        below = in ? below : fmaxf(below, z);
+        above = in ? fminf(above, z) : above;
+        count += in ? 1 : 0;
+        const unsigned long long m = __ballot(in);            // lanes of this wave that are here and have one
+        if (m) {
+            const int lane = threadIdx.x & (kWave - 1);
+            const int leader = __ffsll(static_cast<long long>(m)) - 1;
+            int base = 0;
+            if (lane == leader) base = atomicAdd(cand_n, __popcll(m));
+            base = __shfl(base, leader, kWave);
+            const int idx = base + __popcll(m & ((1ull << lane) - 1ull));
+            if (in && idx < kNucleusCap) { cand_z[idx] = z; cand_e[idx] = e; }
+        }
+    }
+    __device__ __forceinline__ void one(float z) { item(z, acc0); }
+    __device__ __forceinline__ void vec(const float (&z)[E::VEC]) {
+#pragma unroll
+        for (int i = 0; i < E::VEC; i += 2) { item(z[i], acc0); item(z[i + 1], acc1); }
+    }
+};
+
+// Probe over the n candidates in LDS; masses in units of 2^-40.
+__device__ __forceinline__ NucleusProbeResult nucleus_probe_candidates(const float* cand_z, const float* cand_e, int n, float cut,
+                                                                       double* scratch, float* fscratch, int* iscratch) {
+    double mass = 0.0;
+    float below = -INFINITY, above = INFINITY;
+    int count = 0;
+    for (int i = threadIdx.x; i < n; i += kNucleusBlock) {
+        const float z = cand_z[i];
+        const bool in = z >= cut;
+        mass += in ? floor(static_cast<double>(cand_e[i]) * kNucleusUnit) : 0.0;
+        below = in ? below : fmaxf(below, z);
+        above = in ? fminf(above, z) : above;
+        count += in ? 1 : 0;
+    }
+    return nucleus_reduce(mass, below, above, count, scratch, fscratch, iscratch);
 }
 
 template <class E> struct MaskedStore;
@@ -126,6 +198,8 @@ __global__ __launch_bounds__(kNucleusBlock) void nucleus_kernel(const typename E
     __shared__ double scratch[2 * NW];
     __shared__ float fscratch[2 * NW];
     __shared__ int iscratch[NW];
+    __shared__ float cand_z[kNucleusCap], cand_e[kNucleusCap];
+    __shared__ int cand_n;
     const int64_t r = blockIdx.x;
     const T* z = in + r * V;
     T* o = out + r * V;
@@ -139,22 +213,66 @@ __global__ __launch_bounds__(kNucleusBlock) void nucleus_kernel(const typename E
     finish_stats2<kNucleusBlock>(sf.t, none, rt, rd, scratch);
     const float nA = -static_cast<float>(rt.A);
 
-    // 2. the whole row's mass (the same sum a probe forms when everything lies above the cut), then tau
-    NucleusProbeResult all = nucleus_probe<E>(z, V, k32, nA, -INFINITY, scratch, fscratch, iscratch);
-    const double want = static_cast<double>(top_p) * all.mass;
-    float tau = all.above;                                    // the row's minimum: its upper set is the whole row
-    int kept = all.count;
-    uint32_t lo_key = float_key(tau);
-    uint32_t hi_key = float_key(rt.m) + 1u;                   // cuts from here on leave nothing above them
-    for (int step = 0; step < 40 && hi_key - lo_key > 1u && !keep_all; ++step) {
-        const float cut = key_float(lo_key + (hi_key - lo_key) / 2u);      // tau < cut <= maximum
-        const NucleusProbeResult p = nucleus_probe<E>(z, V, k32, nA, cut, scratch, fscratch, iscratch);
-        if (p.mass >= want) {
-            tau = p.above;                                    // the same upper set, named by its smallest value
-            kept = p.count;
+    // 2. tau.  The masses a probe adds up are 2^(z k32 + nA); over the whole row they add up to S.
+    const double S = exp2(rt.A + static_cast<double>(nA));
+    const double want = static_cast<double>(top_p) * S;
+    float tau = -INFINITY;                                    // so far: everything is kept
+    int kept = V;
+    if (!keep_all) {
+        if (threadIdx.x == 0) cand_n = 0;
+        __syncthreads();
+        const float cut0 = rt.m - kNucleusSpan / k32;
+        NucleusCollectF<E> cf;
+        cf.init(k32, nA, cut0, cand_z, cand_e, &cand_n);
+        sweep_row<E, kNucleusBlock, kNucleusUnroll>(z, V, cf);
+        const NucleusProbeResult first = nucleus_reduce(static_cast<double>(cf.acc0) + static_cast<double>(cf.acc1),
+                                                        cf.below, cf.above, cf.count, scratch, fscratch, iscratch);
+        uint32_t lo_key, hi_key = float_key(rt.m) + 1u;       // cuts from hi_key on leave nothing above them
+        bool in_lds = false;
+        if (first.mass >= want) {                             // tau >= cut0
+            tau = first.above;                                // the upper set of cut0, named by its smallest value
+            kept = first.count;
             lo_key = float_key(tau);
-        } else {
-            hi_key = float_key(p.below) + 1u;                 // every cut above `below` has this upper set or less
+            in_lds = first.count <= kNucleusCap;
+        } else {                                              // tau < cut0: the candidates are not enough
+            lo_key = float_key(-INFINITY);
+            hi_key = float_key(first.below) + 1u;
+        }
+        if (in_lds) {
+            const int n = first.count;
+            const double want_units = want * kNucleusUnit;
+            // everything at or above cut0 is in LDS; is it still enough counted in units?
+            const NucleusProbeResult c0 = nucleus_probe_candidates(cand_z, cand_e, n, cut0, scratch, fscratch, iscratch);
+            if (c0.mass >= want_units) {
+                for (int step = 0; step < 40 && hi_key - lo_key > 1u; ++step) {
+                    const float cut = key_float(lo_key + (hi_key - lo_key) / 2u);      // tau < cut <= maximum
+                    const NucleusProbeResult p = nucleus_probe_candidates(cand_z, cand_e, n, cut, scratch, fscratch, iscratch);
+                    if (p.mass >= want_units) {
+                        tau = p.above;                        // the same upper set, named by its smallest value
+                        kept = p.count;
+                        lo_key = float_key(tau);
+                    } else {
+                        hi_key = float_key(p.below) + 1u;     // every cut above `below` has this upper set or less
+                    }
+                }
+                hi_key = lo_key;                              // done
+            } else {                                          // within rounding of top_p at cut0: decide in memory
+                tau = -INFINITY;
+                kept = V;
+                lo_key = float_key(-INFINITY);
+                hi_key = float_key(rt.m) + 1u;
+            }
+        }
+        for (int step = 0; step < 40 && hi_key - lo_key > 1u; ++step) {
+            const float cut = key_float(lo_key + (hi_key - lo_key) / 2u);
+            const NucleusProbeResult p = nucleus_probe<E>(z, V, k32, nA, cut, scratch, fscratch, iscratch);
+            if (p.mass >= want) {
+                tau = p.above;
+                kept = p.count;
+                lo_key = float_key(tau);
+            } else {
+                hi_key = float_key(p.below) + 1u;
+            }
         }
     }
 
