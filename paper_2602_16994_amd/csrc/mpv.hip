@@ -118,7 +118,6 @@ struct Args {
     float* dbg_resid;
     int32_t B, N, V, max_depth;
     float k32;       // float(log2(e)/T)
-    float invT;
     int32_t walk;    // 0: the rule names the stopping node (SpecInfer, Traversal); a token is drawn at every
                      // visited node and followed if it is a child's: 1 from p (NSS), 2 after the Naive test,
                      // 3 after the SpecTr tests
@@ -518,7 +517,7 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(QueuePlan q, Work
         continue;
     }
     // a node task, or the resumed task of the node where the tree branches
-    // (explicitly scalar: the tree tables below are kernel arguments, read with scalar loads)
+    // (tree, node: made scalar explicitly, so that the table lookups below have uniform addresses)
     const bool resumed = task >= a.B * a.N + a.B;
     const int b = __builtin_amdgcn_readfirstlane(resumed ? task - (a.B * a.N + a.B) : task / a.N);
     const int n = __builtin_amdgcn_readfirstlane(resumed ? q.split_node : task % a.N);
@@ -1419,7 +1418,7 @@ __device__ __forceinline__ int sample_task(const TreeDesc& tree, const Workspace
 
 template <class E>
 __global__ __launch_bounds__(kTaskBlock) void row_stats_kernel(const typename E::T* z, int64_t rows, int V,
-                                                              float k32, float invT, float* out) {
+                                                              float k32, float* out) {
     __shared__ double scratch[2 * (kTaskBlock / kWave)];
     const int64_t r = blockIdx.x;
     RowStatsF<E> f;
@@ -1777,7 +1776,6 @@ int mpv_verify(const mpv_problem* problem, const mpv_buffers* buf, void* workspa
     a.dbg_stats = buf->stats; a.dbg_edge = buf->edge_probs; a.dbg_accept = buf->accept_prob; a.dbg_resid = buf->final_residual;
     a.B = problem->B; a.N = problem->N; a.V = problem->V; a.max_depth = problem->max_depth;
     a.k32 = static_cast<float>(1.4426950408889634 / static_cast<double>(problem->temperature));
-    a.invT = 1.0f / problem->temperature;
     a.lazy = (walk || (buf->edge_probs == nullptr && buf->accept_prob == nullptr && buf->stats == nullptr)) ? 1 : 0;
     a.estimate = 0; a.reach_prob = nullptr; a.expected = nullptr;
     a.stagger_ticks = mpv::stagger_ticks(problem);
@@ -1809,7 +1807,6 @@ int mpv_block_efficiency(const mpv_problem* problem, const void* target_logits, 
     a.counters = counters;
     a.B = problem->B; a.N = problem->N; a.V = problem->V; a.max_depth = problem->max_depth;
     a.k32 = static_cast<float>(1.4426950408889634 / static_cast<double>(problem->temperature));
-    a.invT = 1.0f / problem->temperature;
     a.lazy = 0;
     a.estimate = 1; a.reach_prob = reach_prob; a.expected = expected;
     a.stagger_ticks = mpv::stagger_ticks(problem);
@@ -1872,10 +1869,10 @@ int mpv_row_stats(const void* logits, int32_t logit_dtype, int64_t rows, int32_t
     (void)hipGetLastError();
     if (logit_dtype == MPV_DTYPE_F32)
         hipLaunchKernelGGL((mpv::row_stats_kernel<mpv::ElemF32>), dim3(static_cast<unsigned>(rows)), dim3(mpv::kTaskBlock), 0, s,
-                           static_cast<const float*>(logits), rows, V, k32, 1.0f / temperature, out);
+                           static_cast<const float*>(logits), rows, V, k32, out);
     else
         hipLaunchKernelGGL((mpv::row_stats_kernel<mpv::ElemBF16>), dim3(static_cast<unsigned>(rows)), dim3(mpv::kTaskBlock), 0, s,
-                           static_cast<const uint16_t*>(logits), rows, V, k32, 1.0f / temperature, out);
+                           static_cast<const uint16_t*>(logits), rows, V, k32, out);
     return mpv::hip_ok(hipGetLastError()) ? MPV_OK : MPV_ERR_HIP;
 }
 

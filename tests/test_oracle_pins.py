@@ -13,6 +13,7 @@ import numpy as np
 import pytest
 import scipy.special
 
+from oracle import acceptance_oracle as acceptance
 from oracle import mpv_oracle as orc
 
 GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
@@ -186,6 +187,7 @@ def test_nss_acceptance_rate_matches_appendix_C(V, k):
     p, q = random_dist(rng, V, 0.2), random_dist(rng, V)
     want = float(np.sum(p * (1.0 - (1.0 - q) ** k)))
     assert abs(walk_acceptance_rate(orc.NSS, p, q, k) - want) < 1e-13
+    assert abs(acceptance.nss_acceptance(p, q, k) - want) < 1e-14
 
 
 @pytest.mark.parametrize("V,k", [(4, 1), (4, 2), (5, 3), (3, 4)])
@@ -195,6 +197,7 @@ def test_naive_acceptance_rate_matches_appendix_C(V, k):
     p, q = random_dist(rng, V, 0.2), random_dist(rng, V)
     want = float(np.sum(np.minimum(p, q)) + np.sum(np.maximum(p - q, 0.0) * (1.0 - (1.0 - q) ** (k - 1))))
     assert abs(walk_acceptance_rate(orc.NAIVE, p, q, k) - want) < 1e-13
+    assert abs(acceptance.naive_acceptance(p, q, k) - want) < 1e-14
 
 
 @pytest.mark.parametrize("V,k", [(4, 1), (4, 2), (5, 3), (3, 4)])
@@ -213,6 +216,7 @@ def test_spectr_acceptance_rate_matches_appendix_C(V, k):
     r = np.maximum(q - p / rho, 0.0) / (1.0 - beta)
     want = p_acc + (1.0 - p_acc) * float(np.sum(res * (1.0 - (1.0 - r) ** k)))
     assert abs(walk_acceptance_rate(orc.SPECTR, p, q, k) - want) < 1e-12
+    assert abs(acceptance.spectr_acceptance(p, q, k) - walk_acceptance_rate(orc.SPECTR, p, q, k)) < 1e-12
 
 
 @pytest.mark.parametrize("seed", range(10))
@@ -425,8 +429,51 @@ def test_T4_specinfer_acceptance_rate(V, k):
         alpha += w * sum(d[t] for t in set(xs))
         marginal += w * d
     assert alpha == pytest.approx(specinfer_acceptance_formula(p, q, k), abs=1e-13)
+    assert alpha == pytest.approx(acceptance.specinfer_acceptance(p, q, k), abs=1e-13)
     # Def. 3.2: the solver's output follows p
     np.testing.assert_allclose(marginal, p, atol=1e-13)
+
+
+@pytest.mark.parametrize("V,k", [(4, 1), (6, 2), (5, 3), (7, 4), (9, 8)])
+def test_residual_terms_of_the_specinfer_and_spectr_acceptance_rates_vanish(V, k):
+    # App. C adds, to the probability that some draft token is accepted, the probability that the
+    # token drawn from the final residual is one of the (rejected) draft tokens.  For SpecInfer
+    # and SpecTr that term is zero: the residual has no mass where a draft token can have been
+    # rejected.  So  SpecInfer: alpha = 1 - prod_i (1 - r_i) = 1 - W(c_{k+1}),  SpecTr: alpha = p_acc.
+    # (The library computes the two rates that way.)
+    for seed in range(5):
+        rng = np.random.default_rng(300 + 10 * V + k + 100 * seed)
+        p, q = random_dist(rng, V, 0.2), random_dist(rng, V)
+        # SpecInfer: mass of the k-times updated residual (p - c q)_+, c <- c + W
+        c, W = 0.0, 1.0
+        for _ in range(k):
+            c = c + W
+            W = float(np.sum(np.maximum(p - c * q, 0.0)))
+        assert acceptance.specinfer_acceptance(p, q, k) == pytest.approx(1.0 - W, abs=1e-12)
+        rho = orc.spectr_division_factor(p, q, k)
+        p_acc = 1.0 - (1.0 - orc.spectr_beta(p, q, rho)) ** k
+        assert acceptance.spectr_acceptance(p, q, k) == pytest.approx(p_acc, abs=1e-12)
+
+
+def test_acceptance_rates_of_a_tree_use_each_node_s_own_rows_and_child_count():
+    parent = delayed_parent(3, 1, 2)                    # node 1 has three children, the others one or none
+    rng = np.random.default_rng(12)
+    N, V, T = len(parent), 11, 0.7
+    zt = rng.normal(0, 2, size=(N, V))
+    zd = rng.normal(0, 2, size=(N, V))
+    children = orc.children_lists(parent)
+    for method, fn in ((orc.SPECINFER, acceptance.specinfer_acceptance), (orc.NSS, acceptance.nss_acceptance),
+                       (orc.NAIVE, acceptance.naive_acceptance), (orc.SPECTR, acceptance.spectr_acceptance)):
+        got = acceptance.acceptance_rates(method, parent, zt, zd, T)
+        for n in range(N):
+            if children[n]:
+                assert got[n] == fn(orc.softmax_T(zt[n], T), orc.softmax_T(zd[n], T), len(children[n]))
+                assert 0.0 <= got[n] <= 1.0 + 1e-12
+            else:
+                assert got[n] == 0.0
+    # identical models: every rule but NSS accepts with certainty
+    for method in (orc.SPECINFER, orc.NAIVE, orc.SPECTR):
+        assert np.allclose(acceptance.acceptance_rates(method, parent, zd, zd, T)[[0, 1, 2]], 1.0, atol=1e-12)
 
 
 def test_T6_k1_acceptance_is_overlap_mass():
