@@ -64,7 +64,7 @@
 extern "C" {
 #endif
 
-#define MPV_ABI_VERSION 4
+#define MPV_ABI_VERSION 5
 
 /* limits (larger requests return MPV_ERR_UNSUPPORTED) */
 #define MPV_MAX_NODES    64   /* nodes per tree, root included            */
@@ -189,6 +189,18 @@ int mpv_verify(const mpv_problem* problem, const mpv_buffers* buffers,
 int mpv_block_efficiency(const mpv_problem* problem, const void* target_logits, const void* draft_logits,
                          const int32_t* tokens, void* workspace, size_t workspace_bytes,
                          float* reach_prob, float* expected, uint32_t* counters, void* hip_stream);
+
+/* Acceptance rates of the OTLP solver `problem->method` at every internal node of every tree
+ * (Sec. 3.2; the listings of App. C): alpha[b,n] = the probability, over k draft tokens drawn
+ * i.i.d. from the node's draft distribution (k = the node's number of children in `parent`) and
+ * over the solver's own randomness, that the solver's output token is one of the draft tokens.
+ * Depends on the node's two logit rows and on k only: no tokens, no uniforms.
+ * alpha: DEVICE float32 [B,N]; leaves get 0.  Methods: SPECINFER, NSS, NAIVE, SPECTR;
+ * MPV_METHOD_TRAVERSAL returns MPV_ERR_UNSUPPORTED (it is not an OTLP solver; App. C has no rate
+ * for it).  Everything else as for mpv_block_efficiency. */
+int mpv_acceptance_rates(const mpv_problem* problem, const void* target_logits, const void* draft_logits,
+                         void* workspace, size_t workspace_bytes, float* alpha, uint32_t* counters,
+                         void* hip_stream);
 
 /* Nucleus (top-p) transform of `rows` contiguous logit rows of length V (Sec. 4.1: two of the
  * paper's eight sampling settings use nucleus sampling; the paper does not define it, the usual

@@ -81,6 +81,9 @@ def load_library(path=None):
     lib.mpv_block_efficiency.argtypes = [ctypes.POINTER(_Problem), ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                          ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p,
                                          ctypes.c_void_p, ctypes.c_void_p]
+    lib.mpv_acceptance_rates.restype = ctypes.c_int
+    lib.mpv_acceptance_rates.argtypes = [ctypes.POINTER(_Problem), ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                         ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
     lib.mpv_nucleus_mask.restype = ctypes.c_int
     lib.mpv_nucleus_mask.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_int32,
                                      ctypes.c_float, ctypes.c_float, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
@@ -279,6 +282,37 @@ def mpv_block_efficiency(parent, tokens, target_logits, draft_logits, temperatur
     if rc != 0:
         raise MpvError(rc, "mpv_block_efficiency")
     return out
+
+
+def mpv_acceptance_rates(parent, target_logits, draft_logits, temperature, method, stream=None):
+    """Acceptance rate of the solver `method` at every internal node (see include/mpv.h): returns
+    (alpha float32 [B,N], counters) as CUDA tensors; leaves get 0."""
+    import torch
+    from .trees import tree_depth
+    B, N, V = target_logits.shape
+    for t, name in ((target_logits, "target_logits"), (draft_logits, "draft_logits")):
+        if not t.is_cuda or not t.is_contiguous():
+            raise ValueError(f"{name} must be a contiguous CUDA tensor")
+    if draft_logits.shape != target_logits.shape or draft_logits.dtype != target_logits.dtype:
+        raise ValueError("target and draft logits must have the same shape and dtype")
+    dev = target_logits.device
+    max_depth = max(1, tree_depth(list(parent)) if len(parent) == N and N > 0 else 1)
+    prob = _make_problem(B, N, V, method, _dtype_id(target_logits), temperature, max_depth, parent)
+    lib = load_library()
+    need = ctypes.c_size_t(0)
+    rc = lib.mpv_workspace_bytes(ctypes.byref(prob), ctypes.byref(need))
+    if rc != 0:
+        raise MpvError(rc, "mpv_workspace_bytes")
+    workspace = torch.empty(max(need.value, 256), dtype=torch.uint8, device=dev)
+    alpha = torch.empty(B, N, dtype=torch.float32, device=dev)
+    counters = torch.empty(8, dtype=torch.int32, device=dev)
+    rc = lib.mpv_acceptance_rates(ctypes.byref(prob), ctypes.c_void_p(target_logits.data_ptr()),
+                                  ctypes.c_void_p(draft_logits.data_ptr()), ctypes.c_void_p(workspace.data_ptr()),
+                                  ctypes.c_size_t(workspace.numel()), ctypes.c_void_p(alpha.data_ptr()),
+                                  ctypes.c_void_p(counters.data_ptr()), _stream_ptr(stream))
+    if rc != 0:
+        raise MpvError(rc, "mpv_acceptance_rates")
+    return alpha, counters
 
 
 def mpv_nucleus_mask(logits, temperature, top_p, out=None, inplace=False, stream=None):

@@ -101,34 +101,38 @@ struct Workspace {
     TreeDesc* tree;      // the tree tables, written by init_kernel for the kernel that follows
 };
 
+// Every field has a default (null / 0): what a call does not set stays off.
 struct Args {
-    const void* zt;
-    const void* zd;
-    const int32_t* tokens;
-    const float* uniforms;
-    const float* draw_uniforms;      // walks that draw a token at every node they visit
-    int32_t* accept_len;
-    int32_t* path_nodes;
-    int32_t* path_tokens;
-    int32_t* bonus;
-    uint32_t* counters;
-    float* dbg_stats;
-    float* dbg_edge;
-    float* dbg_accept;
-    float* dbg_resid;
-    int32_t B, N, V, max_depth;
-    float k32;       // float(log2(e)/T)
-    int32_t walk;    // 0: the rule names the stopping node (SpecInfer, Traversal); a token is drawn at every
+    const void* zt = nullptr;
+    const void* zd = nullptr;
+    const int32_t* tokens = nullptr;
+    const float* uniforms = nullptr;
+    const float* draw_uniforms = nullptr;      // walks that draw a token at every node they visit
+    int32_t* accept_len = nullptr;
+    int32_t* path_nodes = nullptr;
+    int32_t* path_tokens = nullptr;
+    int32_t* bonus = nullptr;
+    uint32_t* counters = nullptr;
+    float* dbg_stats = nullptr;
+    float* dbg_edge = nullptr;
+    float* dbg_accept = nullptr;
+    float* dbg_resid = nullptr;
+    int32_t B = 0, N = 0, V = 0, max_depth = 0;
+    float k32 = 0.f;       // float(log2(e)/T)
+    int32_t walk = 0;    // 0: the rule names the stopping node (SpecInfer, Traversal); a token is drawn at every
                      // visited node and followed if it is a child's: 1 from p (NSS), 2 after the Naive test,
                      // 3 after the SpecTr tests
-    int32_t lazy;    // compute only what the rule needs (off when per-node debug output is wanted: then every node task runs)
-    int32_t stagger_ticks;   // start-up spread of the persistent workgroups, in 10 ns ticks per step (8 steps)
+    int32_t lazy = 0;    // compute only what the rule needs (off when per-node debug output is wanted: then every node task runs)
+    int32_t stagger_ticks = 0;   // start-up spread of the persistent workgroups, in 10 ns ticks per step (8 steps)
     // Expected block efficiency instead of a verification (Sec. 5, Eq. 1-3): every node task runs
     // (lazy = 0), no uniforms are read, and what would be a tree's sampling task turns the per-node
     // results into reach probabilities.  reach_prob [B,N] may be null; expected [B].
-    int32_t estimate;
-    float* reach_prob;
-    float* expected;
+    // estimate = 2: acceptance rates instead (App. C): per internal node, from its two rows and its
+    // number of children alone; no tokens are read, nothing follows the node tasks.  alpha [B,N].
+    int32_t estimate = 0;
+    float* reach_prob = nullptr;
+    float* expected = nullptr;
+    float* alpha = nullptr;
 };
 
 constexpr int kTaskBlock = 512;
@@ -151,6 +155,7 @@ constexpr int kMailboxSoon = -2;                     // the workgroup has asked 
 constexpr int kTaskExit = -1;                         // what a worker's wait returns when all is done
 constexpr int kWorkerSlots = 8;                       // mailboxes per dispatcher lane
 constexpr int kMaxWorkgroups = kWave * kWorkerSlots;
+constexpr int kKindAcceptance = 100;                   // node_task_kernel instantiation for the acceptance rates (see there)
 
 // ------------------------------------------------------------------ init
 
@@ -200,6 +205,7 @@ __global__ void init_kernel(QueuePlan q, TreeDesc tree, Workspace ws, Args a) {
     const int b = i;
     const size_t bn = static_cast<size_t>(b) * a.N + n;
     reinterpret_cast<unsigned long long*>(ws.a0)[bn] = kNotReady;
+    if (a.alpha) a.alpha[bn] = 0.f;                          // leaves have no acceptance rate
     // a node no task ever reaches is tested with probability 0
     ws.atest[bn] = (n == 0) ? 1.0 : 0.0;
     ws.cfin[bn] = 0.0;
@@ -434,9 +440,14 @@ __device__ __forceinline__ int sample_task(const TreeDesc& tree, const Workspace
 template <int METHOD>
 __device__ __forceinline__ void estimate_wave(const TreeDesc& tree, const Workspace& ws, const Args& a, int b);
 
-template <class E, int METHOD, bool FULL>
+template <class E, int KIND, bool FULL>
 __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(QueuePlan q, Workspace ws, Args a) {
     using T = typename E::T;
+    // KIND: MPV_METHOD_SPECINFER (all top-down rules) or MPV_METHOD_TRAVERSAL, or kKindAcceptance: the
+    // top-down kernel reduced to what the acceptance rates need (an instantiation of its own, so that
+    // its extra sweeps do not weigh on the register allocation of the verification kernels)
+    constexpr bool ACCEPT = KIND == kKindAcceptance;
+    constexpr int METHOD = ACCEPT ? MPV_METHOD_SPECINFER : KIND;
     __shared__ double scratch[2 * (kTaskBlock / kWave)];
     // rows too short to fill the on-chip slots are simply streamed again (they sit in L2)
     constexpr int RV = FULL ? kRegVecs : 0;
@@ -501,7 +512,9 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(QueuePlan q, Work
         }
         float* tile_mass = FULL ? reinterpret_cast<float*>(lds_t) : own_tile_mass;
         int next = -1;
-        if (a.estimate) {
+        if (ACCEPT) {
+            // acceptance rates: nothing follows the node tasks (a root without children has none at all)
+        } else if (a.estimate) {
             if (threadIdx.x < kWave) estimate_wave<METHOD>(tree, ws, a, task - a.B * a.N);
         } else {
             next = sample_task<E, METHOD>(tree, ws, a, task - a.B * a.N, tile_mass, scratch);
@@ -540,7 +553,7 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(QueuePlan q, Work
     __shared__ float sh_un;
     int pf_x = -1;
     float pf_u = 2.f;
-    if (threadIdx.x < k) {
+    if (threadIdx.x < k && a.tokens) {
         const size_t bc = static_cast<size_t>(b) * a.N + tree.child_list[tree.child_off[n] + threadIdx.x];
         pf_x = a.tokens[bc];
         if (!a.estimate) pf_u = a.uniforms[bc];
@@ -732,6 +745,47 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(QueuePlan q, Work
             }
             x_prev = x;
         }
+    }
+    if (ACCEPT) {
+        // Acceptance rate of this node (App. C): the chance that the solver's output is one of k draft
+        // tokens drawn i.i.d. from q.  For SpecInfer and SpecTr the part of App. C's formulas that
+        // covers a hit by the token drawn from the final residual is zero (the residual has no mass
+        // where a draft token can have been rejected), which leaves 1 - (mass of that residual):
+        //   SpecInfer  1 - W(c_{k+1}),  c_1 = 0, c_{i+1} = c_i + W(c_i)      (k sweeps)
+        //   SpecTr     p_acc = 1 - (1 - beta(rho*))^k                          (the search above)
+        //   NSS        sum_t p (1 - (1-q)^k)                                    (one sweep)
+        //   Naive      sum_t min(p,q) + sum_t (p-q)_+ (1 - (1-q)^(k-1))         (one sweep)
+        double alpha;
+        if (a.walk == 3) {
+            const double D = fmin(fmax((sp_W + sp_rho - 1.0) / sp_rho, 0.0), 1.0);
+            alpha = 1.0 - pow(D, static_cast<double>(k));
+        } else if (a.walk == 0) {
+            double cc = 0.0, Wc = 1.0;
+            for (int j = 0; j < k && Wc > 0.0; ++j) {
+                cc = uniform_f64(cc + Wc);
+                const ResidualConsts rc = residual_consts(rt.A, rd.A, cc);
+                ResidualMassRawF<E> f;
+                f.init();
+                f.k32 = k32; f.nAt = rc.nAt; f.nAd = rc.nAd; f.rho = uniform_f32(rc.rho);
+                pair.replay(f);
+                const double lane_mass = static_cast<double>(f.acc0) + static_cast<double>(f.acc1);
+                Wc = uniform_f64(uniform_f64(rc.scale) * block_sum<kTaskBlock>(lane_mass, scratch));
+            }
+            alpha = 1.0 - Wc;
+        } else {
+            AcceptanceF<E> f;
+            const float At_hi = static_cast<float>(rt.A), Ad_hi = static_cast<float>(rd.A);
+            f.init(k32, -At_hi, -Ad_hi, static_cast<float>(exp2(static_cast<double>(At_hi) - rt.A)),
+                   static_cast<float>(exp2(static_cast<double>(Ad_hi) - rd.A)), a.walk == 1 ? k : k - 1, a.walk == 2);
+            sweep_pair<E, kTaskBlock, kTaskUnroll>(zt, zd, V, f);
+            const double lane_sum = static_cast<double>(f.acc0) + static_cast<double>(f.acc1);
+            alpha = uniform_f64(block_sum<kTaskBlock>(lane_sum, scratch));
+        }
+        if (threadIdx.x == 0) {
+            a.alpha[bn] = static_cast<float>(fmin(fmax(alpha, 0.0), 1.0));
+            atomicAdd(&ws.qctl[1], 1);
+        }
+        continue;
     }
     for (int j = 0; j < k; ++j) {
         // a resumed task repeats the arithmetic of the first child (whose task has long run)
@@ -1151,7 +1205,7 @@ __device__ __forceinline__ void estimate_wave(const TreeDesc& tree, const Worksp
     }
     if (live && a.reach_prob) a.reach_prob[base + n] = static_cast<float>(reach);
     const double total = wave_sum(live ? reach : 0.0);
-    if (n == 0) a.expected[b] = static_cast<float>(total);
+    if (n == 0 && a.expected) a.expected[b] = static_cast<float>(total);
 }
 
 // ------------------------------------------------------------------ bonus sample
@@ -1696,7 +1750,10 @@ static int launch_all(const mpv_problem* p, const Plan& plan, const Workspace& w
     }
     if (tasks > 0) {
         const dim3 grid(static_cast<unsigned>(wgs)), block(kTaskBlock);
-        if (p->method != MPV_METHOD_TRAVERSAL) {      // NSS and Naive are variants of the top-down kernel
+        if (a.estimate == 2) {
+            if (full) launch(MPV_KERNEL_NODE_TASK, node_task_kernel<E, kKindAcceptance, true>, grid, block, s, q, ws, a);
+            else launch(MPV_KERNEL_NODE_TASK, node_task_kernel<E, kKindAcceptance, false>, grid, block, s, q, ws, a);
+        } else if (p->method != MPV_METHOD_TRAVERSAL) {      // NSS, Naive and SpecTr are variants of the top-down kernel
             if (full) launch(MPV_KERNEL_NODE_TASK, node_task_kernel<E, MPV_METHOD_SPECINFER, true>, grid, block, s, q, ws, a);
             else launch(MPV_KERNEL_NODE_TASK, node_task_kernel<E, MPV_METHOD_SPECINFER, false>, grid, block, s, q, ws, a);
         } else {
@@ -1800,7 +1857,6 @@ int mpv_block_efficiency(const mpv_problem* problem, const void* target_logits, 
     mpv::Workspace ws;
     mpv::carve(problem, workspace, &ws);
     mpv::Args a;
-    memset(&a, 0, sizeof(a));
     a.zt = target_logits; a.zd = draft_logits; a.tokens = tokens;
     a.walk = problem->method == MPV_METHOD_NSS ? 1 : problem->method == MPV_METHOD_NAIVE ? 2
            : problem->method == MPV_METHOD_SPECTR ? 3 : 0;
@@ -1815,6 +1871,36 @@ int mpv_block_efficiency(const mpv_problem* problem, const void* target_logits, 
     return mpv::launch_all<mpv::ElemBF16>(problem, plan, ws, a, s);
 }
 
+
+int mpv_acceptance_rates(const mpv_problem* problem, const void* target_logits, const void* draft_logits,
+                         void* workspace, size_t workspace_bytes, float* alpha, uint32_t* counters, void* hip_stream) {
+    mpv::Plan plan;
+    const int rc = mpv::validate(problem, &plan);
+    if (rc != MPV_OK) return rc;
+    if (problem->method == MPV_METHOD_TRAVERSAL) return MPV_ERR_UNSUPPORTED;     // not an OTLP solver: App. C has no rate for it
+    if (problem->B == 0) return MPV_OK;
+    if (!target_logits || !draft_logits || !alpha || !counters) return MPV_ERR_NULL;
+    if ((reinterpret_cast<uintptr_t>(target_logits) & 15u) || (reinterpret_cast<uintptr_t>(draft_logits) & 15u))
+        return MPV_ERR_ALIGNMENT;
+    const size_t need = mpv::carve(problem, nullptr, nullptr);
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) || workspace_bytes < need) return MPV_ERR_WORKSPACE;
+
+    mpv::Workspace ws;
+    mpv::carve(problem, workspace, &ws);
+    mpv::Args a;
+    a.zt = target_logits; a.zd = draft_logits;
+    a.walk = problem->method == MPV_METHOD_NSS ? 1 : problem->method == MPV_METHOD_NAIVE ? 2
+           : problem->method == MPV_METHOD_SPECTR ? 3 : 0;
+    a.counters = counters;
+    a.B = problem->B; a.N = problem->N; a.V = problem->V; a.max_depth = problem->max_depth;
+    a.k32 = static_cast<float>(1.4426950408889634 / static_cast<double>(problem->temperature));
+    a.lazy = 0;
+    a.estimate = 2; a.alpha = alpha;
+    a.stagger_ticks = mpv::stagger_ticks(problem);
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    if (problem->logit_dtype == MPV_DTYPE_F32) return mpv::launch_all<mpv::ElemF32>(problem, plan, ws, a, s);
+    return mpv::launch_all<mpv::ElemBF16>(problem, plan, ws, a, s);
+}
 
 int mpv_timing_enable(int32_t max_launches) {
     mpv::LaunchTimer& t = mpv::g_timer;

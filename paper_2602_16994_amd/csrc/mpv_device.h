@@ -605,6 +605,49 @@ struct PairStatsRawF {
     }
 };
 
+// ---------------------------------------------------------------- acceptance rates (App. C)
+//
+// 1 - (1 - q)^m, the chance that one of m tokens drawn from q is a given token of probability q.
+// Small q: three terms of the binomial series (1 - q itself would round q away); else directly.
+__device__ __forceinline__ float hit_probability(float q, float m, float c2, float c3) {
+    const float series = q * (m - q * (c2 - q * c3));
+    const float direct = 1.f - fast_exp2(m * __builtin_amdgcn_logf(fmaxf(1.f - q, 0.f)));     // q = 1: 2^-inf = 0
+    return q < 0x1p-12f ? series : direct;
+}
+
+// NSS:   sum_t p (1 - (1-q)^m)                                  (m = k)
+// Naive: sum_t min(p,q) + sum_t (p-q)_+ (1 - (1-q)^m)           (m = k - 1)
+// p = 2^(zt k32 + nAt) sp and q = 2^(zd k32 + nAd) sq are the normalised probabilities themselves.
+// (A sweep over the rows in memory, not a replay of the pair kept on chip: with this much arithmetic
+// per element the compiler no longer keeps the replayed vectors in registers.)
+template <class E>
+struct AcceptanceF {
+    float k32, nAt, nAd, sp, sq, m, c2, c3;
+    bool naive;
+    float acc0, acc1;
+    __device__ __forceinline__ void init(float k, float nat, float nad, float sp_, float sq_, int m_, bool naive_) {
+        k32 = k; nAt = nat; nAd = nad; sp = sp_; sq = sq_; naive = naive_;
+        m = static_cast<float>(m_);
+        c2 = 0.5f * m * (m - 1.f);
+        c3 = c2 * (m - 2.f) * (1.f / 3.f);
+        acc0 = 0.f; acc1 = 0.f;
+    }
+    __device__ __forceinline__ float term(float a, float b) const {
+        const float p = fast_exp2(fmaf(a, k32, nAt)) * sp;
+        const float q = fast_exp2(fmaf(b, k32, nAd)) * sq;
+        const float hit = (m > 0.f) ? hit_probability(q, m, c2, c3) : 0.f;
+        return naive ? fminf(p, q) + fmaxf(p - q, 0.f) * hit : p * hit;
+    }
+    __device__ __forceinline__ void one(float a, float b) { acc0 += term(a, b); }
+    __device__ __forceinline__ void vec(const float (&a)[E::VEC], const float (&b)[E::VEC]) {
+#pragma unroll
+        for (int i = 0; i < E::VEC; i += 2) {
+            acc0 += term(a[i], b[i]);
+            acc1 += term(a[i + 1], b[i + 1]);
+        }
+    }
+};
+
 template <class E>
 struct ResidualMassRawF : ResidualMassF<E> {
     __device__ __forceinline__ void vec(const uint4& ra, const uint4& rb) {

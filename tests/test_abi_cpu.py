@@ -28,7 +28,7 @@ def test_library_exports_every_declared_symbol(lib):
     text = re.sub(r"/\*.*?\*/", "", header_text(), flags=re.S)
     names = set(re.findall(r"\b(mpv_[a-z_]+)\s*\(", text))
     assert {"mpv_version", "mpv_strerror", "mpv_last_hip_error", "mpv_workspace_bytes",
-            "mpv_verify", "mpv_block_efficiency", "mpv_nucleus_mask", "mpv_row_stats", "mpv_fill_uniforms", "mpv_timing_enable",
+            "mpv_verify", "mpv_block_efficiency", "mpv_acceptance_rates", "mpv_nucleus_mask", "mpv_row_stats", "mpv_fill_uniforms", "mpv_timing_enable",
             "mpv_timing_read"} <= names
     for name in names:
         assert getattr(lib, name) is not None, name
