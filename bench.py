@@ -71,6 +71,7 @@ def side_measurements(mpv, torch, cfg, inputs, method, pair_bytes, steps=5):
     """Two reference points for the roofline, outside the timed region.
     every_node_task: the same call with the per-node test probabilities requested, which makes the
     library run the task of every internal node instead of only those the rule needs.
+    acceptance_rates: mpv_acceptance_rates (App. C) for every internal node.
     nucleus_mask_top_p_0.9: mpv_nucleus_mask over every target row of the batch (out of place).
     block_efficiency_estimate: mpv_block_efficiency (expected accepted length + 1 of every tree, no sampling).
     softmax_statistics_only: step S2 alone (mpv_row_stats) over every target row of the batch."""
@@ -103,6 +104,14 @@ def side_measurements(mpv, torch, cfg, inputs, method, pair_bytes, steps=5):
     res["block_efficiency_estimate"] = {"ms_per_step": s * 1e3, "node_tasks_run": tasks,
                                         "mean_expected_block_efficiency": float(be.expected.mean().item()),
                                         "algorithmic_GBps": gbs, "frac_of_hbm_peak": gbs / HBM_PEAK_GBS}
+    solver = method if method != 1 else 0               # Traversal is not an OTLP solver: time SpecInfer's rates
+    s = timed(lambda: mpv.mpv_acceptance_rates(inputs["parent"], inputs["target"], inputs["draft"], cfg.T, solver))
+    alpha, cnt = mpv.mpv_acceptance_rates(inputs["parent"], inputs["target"], inputs["draft"], cfg.T, solver)
+    tasks = cnt.tolist()[5]
+    gbs = tasks * pair_bytes / s / 1e9
+    res["acceptance_rates"] = {"ms_per_step": s * 1e3, "solver": METHOD_LABEL[solver], "node_tasks_run": tasks,
+                               "mean_rate_at_the_root": float(alpha[:, 0].mean().item()),
+                               "algorithmic_GBps": gbs, "frac_of_hbm_peak": gbs / HBM_PEAK_GBS}
     rows = inputs["target"].view(cfg.B * cfg.N, cfg.V)
     masked = torch.empty_like(rows)
     s = timed(lambda: mpv.mpv_nucleus_mask(rows, cfg.T, 0.9, out=masked))
