@@ -144,8 +144,8 @@ def main():
                     help="also run one plain 1 GiB device copy (a known-size kernel to scale profiler byte counters by)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (trees are independent; see DESIGN.md for how "
-              "the batch would shard); run with --gpus 1", file=sys.stderr)
+        print("bench.py: this build runs on one GPU only (trees are independent: a batch shards by trees, with "
+              "nothing to exchange); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
 
     import torch

@@ -10,13 +10,13 @@ What it computes (citations are to the paper's sections / algorithms):
 
 * node distributions: p = softmax(z_target / T), q = softmax(z_draft / T)
   (Sec. 3: p(.|c), q(.|c) are next-token distributions; Sec. 4.1: sampling at a
-  temperature; the same T is applied to the draft row, see the readings list in
-  the design notes).
+  temperature; the paper does not say what the draft row is divided by: the
+  same T, a reading).
 * SpecInfer verification: the top-down walk of Sec. 3.2 ("OT-based algorithms")
   driving the SpecInfer OTLP solver of Appendix B, Algorithm 4, with children
   taken in ascending node index instead of uniformly at random.
 * Traversal Verification: the bottom-up method cited in Sec. 3.2; the paper
-  gives no listing, so this follows the reading stated in the design notes:
+  gives no listing, so this follows a reading of its description:
   chain weights w = min(1, w_parent * p/q) (the block-verification recursion of
   Sec. 3.1), leaves tested first in depth-first order, and on the rejection of a
   whole child subtree the parent's weight a and target distribution P are
@@ -38,7 +38,7 @@ What it computes (citations are to the paper's sections / algorithms):
   search (64 halvings: the paper gives no stopping rule), children tested in
   list order with min(1, p/(rho* q)), then Y ~ (p - gamma*min(p/rho*, q))_+.
 
-Conventions (each listed as a reading in the design notes):
+Conventions (each a reading where the paper is silent or loose):
 * accept iff u < a (strict), u in [0,1): a = 0 never accepts, a = 1 always.
 * inverse CDF: smallest t with cumsum(r)[t] > u * sum(r); never a zero-mass t.
 * zero residual mass: the distribution is left unchanged; in Traversal the

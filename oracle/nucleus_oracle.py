@@ -6,7 +6,7 @@ code with the HIP library and never calls it.
 
 The paper evaluates two sampling settings with nucleus sampling (Sec. 4.1: top-p 0.9
 and 0.99 at temperature 1) and says nothing else about it.  The definition taken
-(a reading, listed in the design notes) is the usual one: with p = softmax(z / T),
+(a reading: the paper only names the setting) is the usual one: with p = softmax(z / T),
 keep the smallest set of most probable tokens whose probabilities add up to at
 least top_p, drop the rest, renormalise.  Tokens with equal logits are kept or
 dropped together (the set is {v : z_v >= tau} for a threshold tau that is one of

@@ -26,8 +26,8 @@ PROB_ATOL = 1e-5
 # sums moves the root, and with it every test probability p/(rho* q), by up to kappa * e,
 # kappa = oracle.spectr_conditioning (large only where the function is flat on one side of the
 # root).  The paper gives no stopping rule for its binary search; the library's root is exact up
-# to the accuracy of its float32 sums, taken as 3e-7 relative here (three times the 1e-7 the
-# design notes derive).
+# to the accuracy of its float32 sums, taken as 3e-7 relative here (three times the 1e-7 that one
+# v_exp_f32 and the rounding of its argument give a term).
 SUM_REL_ERR = 3e-7
 
 
