@@ -225,3 +225,26 @@ def test_batch_driver_shapes():
     e, reach = beo.expected_block_efficiency_batch(orc.SPECTR, parent, tokens, zt, zd, 1.0)
     assert e.shape == (B,) and reach.shape == (B, N)
     np.testing.assert_allclose(e, reach.sum(axis=1))
+
+
+@pytest.mark.parametrize("name,method", [("specinfer", orc.SPECINFER), ("traversal", orc.TRAVERSAL)])
+def test_hand_derived_worked_example(name, method):
+    # tests/golden/worked_example_v3.json: stopping probabilities and block efficiency derived by hand, in fractions
+    import json
+    import os
+    from fractions import Fraction
+    with open(os.path.join(os.path.dirname(__file__), "golden", "worked_example_v3.json")) as f:
+        g = json.load(f)
+    parent, tokens = g["parent"], g["tokens"]
+    p = [np.array(r) if r is not None else None for r in g["p"]]
+    q = [np.array(r) if r is not None else None for r in g["q"]]
+    reach = beo.reach_probabilities(method, parent, tokens, lambda n: p[n], lambda n: q[n])
+    assert float(reach.sum()) == pytest.approx(float(Fraction(g[name]["block_efficiency"])), abs=1e-14)
+    # a node is on the accepted path iff the rule stops at it or below it
+    stop = {int(s): float(Fraction(fr)) for s, fr in g[name]["stop_prob"].items()}
+    want = np.zeros(len(parent))
+    for s, w in stop.items():
+        want[0] += w
+        for n in orc.path_to(parent, s):
+            want[n] += w
+    np.testing.assert_allclose(reach, want, atol=1e-14)
