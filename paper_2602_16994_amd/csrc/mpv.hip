@@ -662,88 +662,56 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(QueuePlan q, Work
     // Each W is one sweep over the pair on chip, the same reduction the other rules use.  At the
     // root p_acc/beta = rho*, so the vector the token is drawn from, (p - gamma min(p/rho*, q))_+,
     // is (p - rho* q)_+ : the node's final state is simply c = rho*.
-    // The paper's binary search is replaced by a bracketing secant search (Illinois rule) that
-    // halves the bracket whenever three steps have not (f has a kink where the largest token
-    // switches sides, and can be nearly flat beyond it) and, once two points nearly coincide,
-    // steps just across the last one to close the bracket: the same root, in about ten sweeps
-    // instead of thirty.
+    // The paper's binary search is replaced by Newton's method from rho = 1, kept inside the
+    // bracket [last rho with f > 0, first rho with f < 0] (a step that leaves it is replaced by the
+    // midpoint); the sweep returns the slope with the value: W'(rho) = -sum_{p > rho q} q, and
+    // D' = (W' + 1 - D)/rho.  Once a step is shorter than the tolerance the next point is put
+    // just across, to close the bracket.  The same root in about seven sweeps instead of thirty
+    // (f has a kink where the largest token switches sides and can be nearly flat beyond it:
+    // there it takes more).
     double sp_rho = 1.0, sp_W = 1.0;
     if (METHOD == MPV_METHOD_SPECINFER && a.walk == 3) {
         constexpr double kTol = 3e-8;                 // relative width of the final bracket
-        double lo = 1.0, hi = static_cast<double>(k), flo = 0.0, fhi = 0.0;
-        double w1 = hi - lo, w2 = w1, w3 = w1;        // bracket widths one, two, three steps ago
-        double x_prev = 0.0;
-        int side = 0;
-        bool probe = false, last_positive = false;
-        // Where one token carries most of p and q, f has its kink at that token's ratio p/q and the
-        // root usually sits right on it; that token is then almost surely among the draft tokens.
-        // So the ratio of the most probable draft token is tried first, from both sides.
-        double kink = 0.0;
-        {
-            double q_best = -1.0;
-            for (int j = 0; j < k; ++j) {
-                const int xj = ch_tok[j];
-                if (xj < 0 || xj >= V) continue;
-                const double qj = exp2(static_cast<double>(ch_zd[j]) * kd - rd.A);
-                if (qj > q_best) { q_best = qj; kink = exp2(static_cast<double>(ch_zt[j]) * kd - rt.A) / qj; }
-            }
-            kink = uniform_f64(kink);
-        }
-        int kink_state = 0;                           // 0: not tried, 1: tried from the right, 2: done
+        double lo = 1.0, hi = static_cast<double>(k);
+        double x = 1.0, fx = 0.0, dfx = 0.0;
         const int evals = (k > 1) ? 64 : 1;
         for (int it = 0; it < evals; ++it) {
-            const double width = hi - lo;
-            double x;
-            if (it == 0) x = lo;
-            else if (it == 1) x = hi;
-            else {
-                const double secant = (lo * fhi - hi * flo) / (fhi - flo);
-                const double right = kink * (1.0 + 0.45 * kTol), left = kink * (1.0 - 0.45 * kTol);
-                if (kink_state == 0 && right > lo && right < hi) {
-                    x = right;
-                    kink_state = 1;
-                } else if (kink_state == 1 && hi == right && left > lo) {
-                    x = left;                         // f < 0 just right of the kink: is it > 0 just left of it?
-                    kink_state = 2;
-                } else if (it >= 4 && width > 0.5 * w3) {
-                    x = 0.5 * (lo + hi);              // three steps have not halved the bracket
-                } else if (probe) {
-                    // the last two points nearly coincide: step just across, to close the bracket
-                    x = last_positive ? fmin(hi, x_prev * (1.0 + kTol)) : fmax(lo, x_prev * (1.0 - kTol));
-                    if (!(x > lo && x < hi)) x = secant;
-                } else {
-                    x = secant;
+            if (it > 0) {
+                double cand = 0.0;                    // outside the bracket: "no candidate"
+                if (dfx < 0.0) {
+                    const double step = -fx / dfx;
+                    cand = x + step;
+                    if (fabs(step) <= 0.5 * kTol * x) cand = fx > 0.0 ? x * (1.0 + kTol) : x * (1.0 - kTol);
                 }
-                if (kink_state == 0 || (kink_state == 1 && x != right)) kink_state = 2;
-                x = uniform_f64(x);
+                if (!(cand > lo && cand < hi)) cand = 0.5 * (lo + hi);
+                x = uniform_f64(cand);
             }
-            w3 = w2; w2 = w1; w1 = width;
             const ResidualConsts rc = residual_consts(rt.A, rd.A, x);
-            ResidualMassRawF<E> f;
+            ResidualMassSlopeRawF<E> f;
             f.init();
             f.k32 = k32; f.nAt = rc.nAt; f.nAd = rc.nAd; f.rho = uniform_f32(rc.rho);
             pair.replay(f);
-            const double lane_mass = static_cast<double>(f.acc0) + static_cast<double>(f.acc1);
-            const double Wx = uniform_f64(uniform_f64(rc.scale) * block_sum<kTaskBlock>(lane_mass, scratch));
+            double lane_mass = static_cast<double>(f.acc0) + static_cast<double>(f.acc1);
+            double lane_draft = static_cast<double>(f.q0) + static_cast<double>(f.q1);
+            block_sum2<kTaskBlock>(lane_mass, lane_draft, scratch);
+            const double scale = uniform_f64(rc.scale);
+            const double Wx = uniform_f64(scale * lane_mass);
+            const double dWx = -uniform_f64(scale * lane_draft) / x;       // the sweep added up rho q over {p > rho q}
             const double Dx = fmin(fmax((Wx + x - 1.0) / x, 0.0), 1.0);
-            const double fx = Wx - pow(Dx, static_cast<double>(k));
+            const double dDx = (dWx + 1.0 - Dx) / x;
+            const double kk = static_cast<double>(k);
+            fx = Wx - pow(Dx, kk);
+            dfx = dWx - kk * pow(Dx, kk - 1.0) * dDx;
             sp_rho = x;
             sp_W = Wx;
             if (it == 0) {
-                flo = fx;
                 if (!(fx > 0.0)) break;               // the root is 1 (also when k = 1)
-            } else if (it == 1) {
-                fhi = fx;
-                if (!(fx < 0.0)) break;               // the root is k
             } else {
-                if (fx > 0.0) { lo = x; flo = fx; if (side == 1) fhi *= 0.5; side = 1; }
-                else if (fx < 0.0) { hi = x; fhi = fx; if (side == 2) flo *= 0.5; side = 2; }
+                if (fx > 0.0) lo = x;
+                else if (fx < 0.0) hi = x;
                 else break;
                 if (hi - lo <= kTol * hi) break;
-                probe = !probe && fabs(x - x_prev) <= 0.5 * kTol * x;
-                last_positive = fx > 0.0;
             }
-            x_prev = x;
         }
     }
     if (ACCEPT) {

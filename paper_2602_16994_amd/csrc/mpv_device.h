@@ -605,6 +605,33 @@ struct PairStatsRawF {
     }
 };
 
+// W(c) = sum_v (p_v - c q_v)_+ together with  sum_{p_v > c q_v} c q_v  (so that dW/dc = -that / c):
+// value and slope from one sweep, for SpecTr's root search.
+template <class E>
+struct ResidualMassSlopeRawF {
+    float k32, nAt, nAd, rho;
+    float acc0, acc1, q0, q1;
+    __device__ __forceinline__ void init() { acc0 = 0.f; acc1 = 0.f; q0 = 0.f; q1 = 0.f; }
+    __device__ __forceinline__ void term(float a, float b, float& acc, float& q) const {
+        const float et = fast_exp2(fmaf(a, k32, nAt));
+        const float ed = rho * fast_exp2(fmaf(b, k32, nAd));
+        const float diff = et - ed;
+        acc += fmaxf(diff, 0.f);
+        q += diff > 0.f ? ed : 0.f;
+    }
+    __device__ __forceinline__ void one(float a, float b) { term(a, b, acc0, q0); }
+    __device__ __forceinline__ void vec(const uint4& ra, const uint4& rb) {
+        float a[E::VEC], b[E::VEC];
+        E::unpack(ra, a);
+        E::unpack(rb, b);
+#pragma unroll
+        for (int i = 0; i < E::VEC; i += 2) {
+            term(a[i], b[i], acc0, q0);
+            term(a[i + 1], b[i + 1], acc1, q1);
+        }
+    }
+};
+
 // ---------------------------------------------------------------- acceptance rates (App. C)
 //
 // 1 - (1 - q)^m, the chance that one of m tokens drawn from q is a given token of probability q.
