@@ -42,7 +42,10 @@
  *                         with rho* the root of 1 - (1 - beta(rho))^k = rho beta(rho) on [1,k],
  *                         beta(rho) = sum min(p/rho, q), the children are tested in list order
  *                         with min(1, p(x)/(rho* q(x))); otherwise a token is drawn from
- *                         (p - gamma min(p/rho*, q))_+, gamma = (1 - (1 - beta)^k)/beta.
+ *                         (p - gamma min(p/rho*, q))_+, gamma = (1 - (1 - beta)^k)/beta, which at
+ *                         rho* (where gamma = rho*) is (p - rho* q)_+.  The equation is solved in the
+ *                         form sum (p - rho q)_+ = (sum (q - p/rho)_+)^k, the same numbers without
+ *                         cancellation, by Newton's method to a relative 3e-8.
  *
  * Randomness: the caller supplies one uniform in [0,1) per node and tree.
  * uniforms[b,n] (n >= 1) is used only by the test of node n ("accept iff u < a");
@@ -90,9 +93,10 @@ extern "C" {
 #define MPV_ERR_BAD_METHOD      -5
 #define MPV_ERR_BAD_DTYPE       -6
 #define MPV_ERR_WORKSPACE       -7   /* workspace NULL, misaligned or too small       */
-#define MPV_ERR_UNSUPPORTED     -8   /* beyond MPV_MAX_*; stats / edge_probs with methods >= 2 */
+#define MPV_ERR_UNSUPPORTED     -8   /* beyond MPV_MAX_*; stats / edge_probs with methods >= 2;
+                                        acceptance rates of MPV_METHOD_TRAVERSAL        */
 #define MPV_ERR_HIP             -9   /* a HIP call failed; see mpv_last_hip_error()   */
-#define MPV_ERR_ALIGNMENT      -10   /* a logit base pointer is not element-aligned   */
+#define MPV_ERR_ALIGNMENT      -10   /* a logit base pointer is not 16-byte aligned   */
 #define MPV_ERR_BAD_TOP_P      -11   /* top_p is not in (0, 1]                        */
 
 /* Problem description.  Host memory, read during the call only. */
