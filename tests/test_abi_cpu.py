@@ -182,3 +182,44 @@ def test_workload_generator_is_seeded_and_shaped():
     # the five configurations have the node counts the benchmark definition states
     assert [workloads.CONFIGS[k].N for k in ("tiny", "v32k_root", "v128k_delayed", "v152k_root", "v262k_delayed")] \
         == [7, 17, 15, 41, 28]
+
+
+def test_estimator_entry_points_reject_bad_arguments_before_any_launch(lib):
+    prob = problem()
+    fake = ctypes.c_void_p(4096)
+    null = ctypes.c_void_p(0)
+    # expected block efficiency: null inputs / outputs, alignment, workspace, invalid problem, empty batch
+    be = lib.mpv_block_efficiency
+    assert be(ctypes.byref(prob), null, fake, fake, fake, 1 << 20, fake, fake, fake, None) == code("MPV_ERR_NULL")
+    assert be(ctypes.byref(prob), fake, fake, fake, fake, 1 << 20, fake, null, fake, None) == code("MPV_ERR_NULL")
+    assert be(ctypes.byref(prob), fake, fake, fake, fake, 1 << 20, fake, fake, null, None) == code("MPV_ERR_NULL")
+    assert be(ctypes.byref(prob), ctypes.c_void_p(4100), fake, fake, fake, 1 << 20, fake, fake, fake, None) == code("MPV_ERR_ALIGNMENT")
+    assert be(ctypes.byref(prob), fake, fake, fake, null, 1 << 20, fake, fake, fake, None) == code("MPV_ERR_WORKSPACE")
+    assert be(ctypes.byref(prob), fake, fake, fake, fake, 16, fake, fake, fake, None) == code("MPV_ERR_WORKSPACE")
+    assert be(ctypes.byref(problem(method=7)), fake, fake, fake, fake, 1 << 20, fake, fake, fake, None) == code("MPV_ERR_BAD_METHOD")
+    assert be(ctypes.byref(problem(B=0)), null, null, null, null, 0, null, null, null, None) == 0
+    # acceptance rates: the same, and Traversal is not an OTLP solver
+    ar = lib.mpv_acceptance_rates
+    assert ar(ctypes.byref(problem(method=1)), fake, fake, fake, 1 << 20, fake, fake, None) == code("MPV_ERR_UNSUPPORTED")
+    assert ar(ctypes.byref(prob), fake, null, fake, 1 << 20, fake, fake, None) == code("MPV_ERR_NULL")
+    assert ar(ctypes.byref(prob), fake, fake, fake, 1 << 20, null, fake, None) == code("MPV_ERR_NULL")
+    assert ar(ctypes.byref(prob), fake, fake, fake, 8, fake, fake, None) == code("MPV_ERR_WORKSPACE")
+    assert ar(ctypes.byref(problem(B=0)), null, null, null, 0, null, null, None) == 0
+
+
+def test_nucleus_entry_point_rejects_bad_arguments_before_any_launch(lib):
+    nm = lib.mpv_nucleus_mask
+    fake = ctypes.c_void_p(4096)
+    null = ctypes.c_void_p(0)
+    f = ctypes.c_float
+    assert nm(fake, fake, 0, -1, 8, f(1.0), f(0.9), null, null, None) == code("MPV_ERR_BAD_SHAPE")
+    assert nm(fake, fake, 0, 1, 0, f(1.0), f(0.9), null, null, None) == code("MPV_ERR_BAD_SHAPE")
+    assert nm(fake, fake, 0, 1, header_constant("MPV_MAX_VOCAB") + 1, f(1.0), f(0.9), null, null, None) == code("MPV_ERR_UNSUPPORTED")
+    assert nm(fake, fake, 9, 1, 8, f(1.0), f(0.9), null, null, None) == code("MPV_ERR_BAD_DTYPE")
+    assert nm(fake, fake, 0, 1, 8, f(0.0), f(0.9), null, null, None) == code("MPV_ERR_BAD_TEMPERATURE")
+    for bad in (0.0, -1.0, 1.0001, float("nan"), float("inf")):
+        assert nm(fake, fake, 0, 1, 8, f(1.0), f(bad), null, null, None) == code("MPV_ERR_BAD_TOP_P")
+    assert nm(null, fake, 0, 1, 8, f(1.0), f(0.9), null, null, None) == code("MPV_ERR_NULL")
+    assert nm(fake, null, 0, 1, 8, f(1.0), f(0.9), null, null, None) == code("MPV_ERR_NULL")
+    assert nm(ctypes.c_void_p(4100), fake, 0, 1, 8, f(1.0), f(0.9), null, null, None) == code("MPV_ERR_ALIGNMENT")
+    assert nm(null, null, 0, 0, 8, f(1.0), f(0.9), null, null, None) == 0          # no rows: nothing to do
