@@ -1,19 +1,25 @@
 // mpv.hip -- kernels and C ABI of the tree-verification library (gfx950 only).
 //
 // Path of one mpv_verify call (all on the caller's stream):
-//   init_kernel            zero counters, queue the initial tasks
-//   node_task_kernel       persistent workgroups that take tasks from a queue.
-//                          Node task, one per (tree, internal node):
-//                            softmax statistics of the node's target and draft rows,
-//                            then, for each child in list order, the probability
-//                            the child is tested with and the residual mass after
-//                            its rejection (a V-wide reduction per child).
-//                            SpecInfer: all queued up front; Traversal: the roots,
-//                            then each task queues its children of positive weight.
-//                          Sampling task, one per tree, queued by the tree's last node
-//                            task: the first wave does the uniform-dependent walk, then
-//                            the workgroup draws the bonus token by inverse CDF from
-//                            the residual of the stopping node.
+//   init_kernel            zero counters, default the per-node results, queue the first tasks
+//   node_task_kernel       persistent workgroups, about one per compute unit, that take tasks
+//                          from a queue until none are left.
+//                          Node task, one per (tree, internal node) the rule needs:
+//                            softmax statistics of the node's target and draft rows, then,
+//                            for each child in list order, the probability the child is
+//                            tested with (or, Traversal, its starting weight) and the residual
+//                            mass after its rejection (a V-wide reduction per child, over the
+//                            row pair kept on chip).  A task starts the tasks that follow
+//                            from it: SpecInfer the accepted child, Traversal the children of
+//                            positive weight; tasks of trees whose outcome is settled are
+//                            dropped.  With per-node debug outputs every node's task runs.
+//                          Sampling task, one per tree, started by the task that settles the
+//                            tree: the first wave does the uniform-dependent walk, then the
+//                            workgroup draws the bonus token by inverse CDF from the residual
+//                            of the stopping node.  (NSS, Naive, SpecTr: one per draw of the
+//                            token-following walk.)
+// mpv_block_efficiency and mpv_acceptance_rates run the same kernels with every node task and
+// no uniforms (see Args::estimate); mpv_nucleus_mask is a kernel of its own (mpv_nucleus.h).
 //
 // Why this is the same computation as the step-by-step rules: every distribution
 // either rule draws from is (p - c q)_+ / W(c) for one scalar c per node state
@@ -1025,7 +1031,7 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(QueuePlan q, Work
 
 // ------------------------------------------------------------------ walk
 //
-// The uniform-dependent part of both rules, run by the first wave of the sampling
+// The uniform-dependent part of SpecInfer and Traversal, run by the first wave of the sampling
 // workgroup: lane n compares u[n] with the probability node n is tested with
 // (which does not depend on the uniforms), the 64 outcomes become a bit mask, and
 // the walk itself is a few scalar steps over that mask.
