@@ -73,6 +73,7 @@ extern "C" {
 #define MPV_MAX_NODES    64   /* nodes per tree, root included            */
 #define MPV_MAX_CHILDREN 16   /* children of one node                      */
 #define MPV_MAX_VOCAB    (1 << 21)
+/* and B * (N + 2) <= 2^30 */
 
 #define MPV_METHOD_SPECINFER 0
 #define MPV_METHOD_TRAVERSAL 1

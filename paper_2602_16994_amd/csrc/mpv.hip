@@ -1553,6 +1553,8 @@ static int validate(const mpv_problem* p, Plan* plan) {
     if (!p) return MPV_ERR_NULL;
     if (p->B < 0 || p->N < 1 || p->V < 1) return MPV_ERR_BAD_SHAPE;
     if (p->N > MPV_MAX_NODES || p->V > MPV_MAX_VOCAB) return MPV_ERR_UNSUPPORTED;
+    // task numbers (tree * N + node, and two more per tree) are 32-bit
+    if (static_cast<int64_t>(p->B) * (p->N + 2) > (1ll << 30)) return MPV_ERR_UNSUPPORTED;
     if (p->method < MPV_METHOD_SPECINFER || p->method > MPV_METHOD_SPECTR) return MPV_ERR_BAD_METHOD;
     if (p->logit_dtype != MPV_DTYPE_F32 && p->logit_dtype != MPV_DTYPE_BF16) return MPV_ERR_BAD_DTYPE;
     if (!(p->temperature > 0.0f) || !isfinite(p->temperature)) return MPV_ERR_BAD_TEMPERATURE;

@@ -101,6 +101,8 @@ def test_limits(lib):
     assert ws_bytes(lib, problem(N=len(star), parent=star, max_depth=1))[0] == code("MPV_ERR_UNSUPPORTED")
     assert ws_bytes(lib, problem(V=max_vocab))[0] == 0
     assert ws_bytes(lib, problem(V=max_vocab + 1))[0] == code("MPV_ERR_UNSUPPORTED")
+    assert ws_bytes(lib, problem(B=(1 << 30) // 5))[0] == 0                      # B * (N + 2) = 2^30 at N = 3
+    assert ws_bytes(lib, problem(B=(1 << 30) // 5 + 1))[0] == code("MPV_ERR_UNSUPPORTED")
 
 
 def test_workspace_size_scales_with_batch_and_nodes(lib):
