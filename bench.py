@@ -210,7 +210,8 @@ def main():
     if per_kernel:
         for name, v in per_kernel.items():
             kernels[name] = {"launches_per_step": len(v) / args.steps,
-                             "avg_ms": sum(v) / len(v), "ms_per_step": sum(v) / args.steps}
+                             "avg_ms": sum(v) / len(v), "median_ms": sorted(v)[len(v) // 2], "min_ms": min(v),
+                             "ms_per_step": sum(v) / args.steps}
         nt = per_kernel.get("node_task", [])
         if nt:
             launches = len(nt) / args.steps
@@ -221,7 +222,11 @@ def main():
                 ROOT, "profiles", f"node_task_{cfg.name}_pmc.txt"))
             roofline = {"bound": "hbm", "kernel": "node_task_kernel", "achieved": achieved,
                         "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                        "traffic": traffic, "algorithmic_bytes_per_launch": alg_bytes_per_launch,
+                        "traffic": traffic,
+                        # the counted bytes (profiles/) over the launch time measured here
+                        "traffic_GBps": None if traffic is None else traffic / avg_s / 1e9,
+                        "traffic_frac": None if traffic is None else traffic / avg_s / 1e9 / HBM_PEAK_GBS,
+                        "algorithmic_bytes_per_launch": alg_bytes_per_launch,
                         "node_tasks_run": tasks_run, "node_tasks_total": cfg.B * n_internal,
                         "bytes_per_node_task": pair_bytes,
                         "avg_launch_ms": avg_s * 1e3, "launches_per_step": launches}
