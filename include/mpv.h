@@ -67,7 +67,7 @@
 extern "C" {
 #endif
 
-#define MPV_ABI_VERSION 5
+#define MPV_ABI_VERSION 6
 
 /* limits (larger requests return MPV_ERR_UNSUPPORTED) */
 #define MPV_MAX_NODES    64   /* nodes per tree, root included            */
@@ -173,6 +173,19 @@ int mpv_workspace_bytes(const mpv_problem* problem, size_t* out);
  * buffers must be ordered by the caller (same stream, or events). */
 int mpv_verify(const mpv_problem* problem, const mpv_buffers* buffers,
                void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* mpv_verify for callers that cannot allocate device memory or pass a workspace (code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the same operation,
+ * arguments, outputs and errors as mpv_verify, with the scratch in a device array of
+ * MPV_STATIC_WORKSPACE_BYTES that is part of the library itself (every GPU the library runs on
+ * holds its own copy until the process ends).  The call allocates nothing and frees nothing.
+ * A problem whose mpv_workspace_bytes() exceeds MPV_STATIC_WORKSPACE_BYTES is refused with
+ * MPV_ERR_WORKSPACE before anything is launched (B * N of about 60 000 nodes fits).
+ * Every call on one GPU uses that GPU's one array: calls that overlap in time on the same GPU
+ * (different streams, different threads) race and must be ordered by the caller.  The array keeps
+ * the previous call's contents; the call itself clears what it needs. */
+#define MPV_STATIC_WORKSPACE_BYTES (4u << 20)
+int mpv_verify_static(const mpv_problem* problem, const mpv_buffers* buffers, void* hip_stream);
 
 /* Expected block efficiency of every tree of the batch with the verification's own
  * randomness integrated out (Sec. 5, Eq. 1-3; branching probabilities of Def. 5.3 by

@@ -77,6 +77,8 @@ def load_library(path=None):
     lib.mpv_verify.restype = ctypes.c_int
     lib.mpv_verify.argtypes = [ctypes.POINTER(_Problem), ctypes.POINTER(_Buffers),
                                ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+    lib.mpv_verify_static.restype = ctypes.c_int
+    lib.mpv_verify_static.argtypes = [ctypes.POINTER(_Problem), ctypes.POINTER(_Buffers), ctypes.c_void_p]
     lib.mpv_block_efficiency.restype = ctypes.c_int
     lib.mpv_block_efficiency.argtypes = [ctypes.POINTER(_Problem), ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                          ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p,
@@ -161,7 +163,8 @@ class VerifyResult:
 
 
 def mpv_verify(parent, tokens, target_logits, draft_logits, temperature, uniforms, method,
-               max_depth=None, debug=False, out=None, workspace=None, stream=None, draw_uniforms=None):
+               max_depth=None, debug=False, out=None, workspace=None, stream=None, draw_uniforms=None,
+               static_scratch=False):
     """Enqueue one batched verification on the current (or given) torch stream.
 
     parent: list of N ints (host).  tokens int32 [B,N], target_logits / draft_logits
@@ -170,6 +173,7 @@ def mpv_verify(parent, tokens, target_logits, draft_logits, temperature, uniform
     on the host).  `out` may be a previous VerifyResult whose buffers are reused.
     draw_uniforms float32 [B,N] is needed by MPV_METHOD_NSS, MPV_METHOD_NAIVE and MPV_METHOD_SPECTR (the draw at
     each visited node); with those methods debug=True provides accept_prob and final_residual only.
+    static_scratch=True calls mpv_verify_static: no workspace tensor, the library's own device array.
     """
     import torch
     from .trees import tree_depth
@@ -209,28 +213,33 @@ def mpv_verify(parent, tokens, target_logits, draft_logits, temperature, uniform
             out.accept_prob = torch.empty(B, N, **f32)
             out.final_residual = torch.empty(B, V, **f32)
     lib = load_library()
-    need = ctypes.c_size_t(0)
-    rc = lib.mpv_workspace_bytes(ctypes.byref(prob), ctypes.byref(need))
-    if rc != 0:
-        raise MpvError(rc, "mpv_workspace_bytes")
-    if workspace is None:
-        workspace = out.workspace
-    if workspace is None or workspace.numel() < need.value:
-        workspace = torch.empty(max(need.value, 256), dtype=torch.uint8, device=dev)
-    out.workspace = workspace
 
     def ptr(t):
         return ctypes.c_void_p(t.data_ptr()) if t is not None else ctypes.c_void_p(0)
+
+    if not static_scratch:
+        need = ctypes.c_size_t(0)
+        rc = lib.mpv_workspace_bytes(ctypes.byref(prob), ctypes.byref(need))
+        if rc != 0:
+            raise MpvError(rc, "mpv_workspace_bytes")
+        if workspace is None:
+            workspace = out.workspace
+        if workspace is None or workspace.numel() < need.value:
+            workspace = torch.empty(max(need.value, 256), dtype=torch.uint8, device=dev)
+        out.workspace = workspace
 
     bufs = _Buffers(ptr(target_logits), ptr(draft_logits), ptr(tokens), ptr(uniforms),
                     ptr(out.accept_len), ptr(out.path_nodes), ptr(out.path_tokens),
                     ptr(out.bonus_token), ptr(out.counters),
                     ptr(out.stats), ptr(out.edge_probs), ptr(out.accept_prob), ptr(out.final_residual),
                     ptr(draw_uniforms))
-    rc = lib.mpv_verify(ctypes.byref(prob), ctypes.byref(bufs), ptr(workspace),
-                        ctypes.c_size_t(workspace.numel()), _stream_ptr(stream))
+    if static_scratch:
+        rc = lib.mpv_verify_static(ctypes.byref(prob), ctypes.byref(bufs), _stream_ptr(stream))
+    else:
+        rc = lib.mpv_verify(ctypes.byref(prob), ctypes.byref(bufs), ptr(workspace),
+                            ctypes.c_size_t(workspace.numel()), _stream_ptr(stream))
     if rc != 0:
-        raise MpvError(rc, "mpv_verify")
+        raise MpvError(rc, "mpv_verify_static" if static_scratch else "mpv_verify")
     return out
 
 

@@ -32,6 +32,8 @@
 #include <stdint.h>
 #include <string.h>
 
+#include <atomic>
+
 #include "mpv.h"
 #include "mpv_device.h"
 #include "mpv_nucleus.h"
@@ -1743,6 +1745,30 @@ static int launch_all(const mpv_problem* p, const Plan& plan, const Workspace& w
     return hip_ok(hipGetLastError()) ? MPV_OK : MPV_ERR_HIP;
 }
 
+// ------------------------------------------------------------------ static scratch
+
+// Scratch of mpv_verify_static: the workspace of one call, held by every device the library
+// runs on until the process ends.  In host code the array's name is only a handle; its device
+// address is looked up once per device (scratch_address) and only that pointer is ever used.
+static __device__ __align__(256) unsigned char scratch[MPV_STATIC_WORKSPACE_BYTES];
+
+constexpr int kMaxDevices = 64;
+static std::atomic<void*> g_scratch_ptr[kMaxDevices];
+
+// Device address of `scratch` on the current device (null + error code on failure).
+static int scratch_address(void** out) {
+    int dev = 0;
+    if (!hip_ok(hipGetDevice(&dev))) return MPV_ERR_HIP;
+    if (dev < 0 || dev >= kMaxDevices) return MPV_ERR_UNSUPPORTED;
+    void* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        if (!hip_ok(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch))) || !p) return MPV_ERR_HIP;
+        g_scratch_ptr[dev].store(p, std::memory_order_release);     // every thread finds the same address
+    }
+    *out = p;
+    return MPV_OK;
+}
+
 }  // namespace mpv
 
 // ------------------------------------------------------------------ C ABI
@@ -1780,8 +1806,27 @@ int mpv_workspace_bytes(const mpv_problem* problem, size_t* out) {
     return MPV_OK;
 }
 
+static int verify_with_workspace(const mpv_problem* problem, const mpv_buffers* buf, void* workspace,
+                                 size_t workspace_bytes, void* hip_stream);
+
 int mpv_verify(const mpv_problem* problem, const mpv_buffers* buf, void* workspace,
                size_t workspace_bytes, void* hip_stream) {
+    return verify_with_workspace(problem, buf, workspace, workspace_bytes, hip_stream);
+}
+
+int mpv_verify_static(const mpv_problem* problem, const mpv_buffers* buf, void* hip_stream) {
+    mpv::Plan plan;
+    const int rc = mpv::validate(problem, &plan);
+    if (rc != MPV_OK) return rc;
+    if (mpv::carve(problem, nullptr, nullptr) > MPV_STATIC_WORKSPACE_BYTES) return MPV_ERR_WORKSPACE;
+    void* ws = nullptr;
+    const int rs = mpv::scratch_address(&ws);
+    if (rs != MPV_OK) return rs;
+    return verify_with_workspace(problem, buf, ws, MPV_STATIC_WORKSPACE_BYTES, hip_stream);
+}
+
+static int verify_with_workspace(const mpv_problem* problem, const mpv_buffers* buf, void* workspace,
+                                 size_t workspace_bytes, void* hip_stream) {
     mpv::Plan plan;
     const int rc = mpv::validate(problem, &plan);
     if (rc != MPV_OK) return rc;

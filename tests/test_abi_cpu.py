@@ -28,7 +28,7 @@ def test_library_exports_every_declared_symbol(lib):
     text = re.sub(r"/\*.*?\*/", "", header_text(), flags=re.S)
     names = set(re.findall(r"\b(mpv_[a-z_]+)\s*\(", text))
     assert {"mpv_version", "mpv_strerror", "mpv_last_hip_error", "mpv_workspace_bytes",
-            "mpv_verify", "mpv_block_efficiency", "mpv_acceptance_rates", "mpv_nucleus_mask", "mpv_row_stats", "mpv_fill_uniforms", "mpv_timing_enable",
+            "mpv_verify", "mpv_verify_static", "mpv_block_efficiency", "mpv_acceptance_rates", "mpv_nucleus_mask", "mpv_row_stats", "mpv_fill_uniforms", "mpv_timing_enable",
             "mpv_timing_read"} <= names
     for name in names:
         assert getattr(lib, name) is not None, name
@@ -225,3 +225,16 @@ def test_nucleus_entry_point_rejects_bad_arguments_before_any_launch(lib):
     assert nm(fake, null, 0, 1, 8, f(1.0), f(0.9), null, null, None) == code("MPV_ERR_NULL")
     assert nm(ctypes.c_void_p(4100), fake, 0, 1, 8, f(1.0), f(0.9), null, null, None) == code("MPV_ERR_ALIGNMENT")
     assert nm(null, null, 0, 0, 8, f(1.0), f(0.9), null, null, None) == 0          # no rows: nothing to do
+
+
+def test_static_scratch_entry_point_refuses_what_does_not_fit(lib):
+    # validation and the size limit come before anything touches a device
+    B, N = 4096, 33
+    prob = problem(B=B, N=N, V=64, max_depth=N, parent=[-1] + list(range(N - 1)))
+    rc, need = ws_bytes(lib, prob)
+    limit = eval(re.search(r"#define MPV_STATIC_WORKSPACE_BYTES\s+\(([^)]+)\)", header_text()).group(1).replace("u", ""))
+    assert limit == 4 << 20
+    assert rc == 0 and need > limit
+    bufs = binding._Buffers(*([ctypes.c_void_p(256)] * 9), *([ctypes.c_void_p(0)] * 5))
+    assert lib.mpv_verify_static(ctypes.byref(prob), ctypes.byref(bufs), ctypes.c_void_p(0)) == code("MPV_ERR_WORKSPACE")
+    assert lib.mpv_verify_static(ctypes.byref(problem(T=0.0)), ctypes.byref(bufs), ctypes.c_void_p(0)) == code("MPV_ERR_BAD_TEMPERATURE")
