@@ -30,9 +30,9 @@ What it computes (citations are to the paper's sections / algorithms):
   NSS solver (App. B, Alg. 1: Y ~ p, draft tokens ignored) or the Naive solver
   (App. B, Alg. 2: the first child is tested with min(1, p/q); otherwise
   Y ~ (p-q)_+).  With these solvers the token the solver outputs can be one of
-  the other draft tokens: the walk then moves to that child (Sec. 3.2: "progress
-  to the child if t is among x_1..x_k, terminate otherwise"); with equal-token
-  siblings, to the first of them in list order.
+  the other draft tokens: the walk then moves to the child carrying it and ends
+  if no child does (Sec. 3.2, the top-down walk); with equal-token siblings, to
+  the first of them in list order.
 * SpecTr verification: the same walk with the K-SEQ solver (App. B, Alg. 3):
   division factor rho* = root of p_acc(rho) - rho*beta(rho) on [1,k] by binary
   search (64 halvings: the paper gives no stopping rule), children tested in
@@ -145,14 +145,15 @@ def _ratio(num, den):
 # the two verification rules, written against a `decide(node, a)` callback
 # --------------------------------------------------------------------------
 
-def specinfer_solver(P, Q, xs, decide):
+def specinfer_solver(P, Q, xs, decide, on_update=None):
     """SpecInfer OTLP solver (App. B, Alg. 4), children in list order.
 
     P, Q: target / draft distribution at the node; xs: the child tokens
     X_1..X_k; decide(i, a): is child i, tested with probability a, accepted?
     Returns (i, P): the accepted child's position (None if every child was
     rejected) and the current distribution, from which Y is drawn when i is
-    None.
+    None.  on_update(i, s), if given, is told the mass s of (p - q)_+ after the
+    rejection of child i (reporting only).
     """
     P = np.array(P, dtype=np.float64)
     for i, x in enumerate(xs):
@@ -161,6 +162,8 @@ def specinfer_solver(P, Q, xs, decide):
             return i, P
         r = np.maximum(P - Q, 0.0)              # Alg. 4: p <- norm (p-q)_+
         s = np.sum(r)
+        if on_update is not None:
+            on_update(i, float(s))
         if s > 0.0:
             P = r / s
     return None, P
@@ -187,12 +190,14 @@ def specinfer_rule(children, tokens, p_of, q_of, decide):
         n = ch[i]                               # progress to the child node
 
 
-def traversal_rule(children, tokens, p_of, q_of, decide, observe=None):
+def traversal_rule(children, tokens, p_of, q_of, decide, observe=None, on_update=None):
     """Bottom-up Traversal Verification (reading stated in the module header).
 
     Same callback protocol as specinfer_rule.  The root is accepted with
     probability 1 when the traversal comes back to it.  observe(n, a, P), if
-    given, is called just before node n is tested.
+    given, is called just before node n is tested.  on_update(n, c, a, S), if
+    given, is told the weight a node n had and the mass S of (a P - q)_+ when the
+    subtree of its child c was rejected (reporting only).
     """
     result = {}
 
@@ -208,6 +213,8 @@ def traversal_rule(children, tokens, p_of, q_of, decide, observe=None):
                 # the whole subtree of c was rejected: delete it, update n
                 r = np.maximum(a * P - Q, 0.0)
                 S = np.sum(r)
+                if on_update is not None:
+                    on_update(n, c, float(a), float(S))
                 if S > 0.0:
                     P = r / S
                     a = S / (S + (1.0 - a))
@@ -289,35 +296,6 @@ def spectr_division_factor(P, Q, k):
         else:
             hi = mid
     return 0.5 * (lo + hi)
-
-
-def spectr_conditioning(P, Q, k, rho):
-    """How much relative errors of size e in the V-wide sums move the root: |d ln rho*| <= kappa * e.
-
-    With W = sum (p - rho q)_+, D = sum (q - p/rho)_+ = (W + rho - 1)/rho and f = W - D^k (see
-    spectr_division_factor): an error e in W and in the normalisation of p and q changes f by at
-    most e * (W + k D^(k-1) (W + 2)/rho), and f' = -sum_{p > rho q} q - k D^(k-1) sum_{p < rho q} p/rho^2.
-    The root often sits on, or within 1e-7 of, a kink of f (the ratio p/q of a dominant token), where
-    the slopes to the left and right differ by orders of magnitude: the slopes are taken 1e-6 to
-    either side (closer than float32 sums can tell apart) and the flatter one counts.  Used by the parity
-    tests to turn the accuracy of float32 sums into a tolerance on SpecTr's test probabilities; no
-    verification step uses it.
-    """
-    if k <= 1:
-        return 0.0
-    P = np.asarray(P, dtype=np.float64)
-    Q = np.asarray(Q, dtype=np.float64)
-    W = float(np.sum(np.maximum(P - rho * Q, 0.0)))
-    D = float(np.sum(np.maximum(Q - P / rho, 0.0)))
-    df = W + k * D ** (k - 1) * (W + 2.0) / rho
-    slopes = []
-    for r in (rho * (1.0 - 1e-6), rho * (1.0 + 1e-6)):       # just left and just right of the root
-        up = P > r * Q
-        slopes.append(float(np.sum(Q[up])) + k * D ** (k - 1) * float(np.sum(P[~up])) / (r * r))
-    slope = min(slopes)
-    if slope <= 0.0:
-        return float("inf")
-    return df / (slope * rho)
 
 
 def spectr_solver(P, Q, xs, decide):
@@ -521,7 +499,7 @@ def _enumerate_token_walk(solver, children, tokens, p_of, q_of):
     return outcomes
 
 
-def all_test_probs(method, parent, tokens, target_logits, draft_logits, T):
+def all_test_probs(method, parent, tokens, target_logits, draft_logits, T, updates=None, rows=None):
     """Probability with which each node would be tested if it were reached.
 
     Because a node is only ever tested after one fixed history (SpecInfer:
@@ -529,12 +507,16 @@ def all_test_probs(method, parent, tokens, target_logits, draft_logits, T):
     the depth-first order rejected), that probability does not depend on the
     uniforms.  Entry 0 (the root) is 1.  Also returns, for every node, the
     normalised distribution a bonus token would be drawn from if the rule
-    stopped there.
+    stopped there.  updates, if a list, receives one (node, child, weight, mass)
+    per residual update made on the way: after the rejection of `child` (of its
+    whole subtree, Traversal) node `node`, of weight `weight` (1 for SpecInfer), had
+    the residual mass `mass`.  rows, if given, is a pair of callables (p_of, q_of) that
+    supply the node distributions in place of the softmax of the logits (the tests use it
+    to see how far the results move when the distributions are slightly off).
     """
     children = children_lists(parent)
     n_nodes = len(parent)
-    p_of = _RowCache(target_logits, T)
-    q_of = _RowCache(draft_logits, T)
+    p_of, q_of = rows if rows is not None else (_RowCache(target_logits, T), _RowCache(draft_logits, T))
     probs = np.full(n_nodes, np.nan)
     probs[0] = 1.0
     stop_dist = [None] * n_nodes
@@ -546,7 +528,8 @@ def all_test_probs(method, parent, tokens, target_logits, draft_logits, T):
                 probs[n] = a
             stop_dist[n] = P / np.sum(P)
 
-        traversal_rule(children, tokens, p_of, q_of, lambda c, a: False, observe)
+        on_update = None if updates is None else (lambda n, c, a, S: updates.append((n, c, a, S)))
+        traversal_rule(children, tokens, p_of, q_of, lambda c, a: False, observe, on_update)
         return probs, stop_dist
 
     # SpecInfer: run the solver at every node, rejecting every child.
@@ -560,7 +543,8 @@ def all_test_probs(method, parent, tokens, target_logits, draft_logits, T):
             probs[ch[i]] = a
             return False
 
-        _, P = specinfer_solver(p_of(n), q_of(n), [int(tokens[c]) for c in ch], decide)
+        on_update = None if updates is None else (lambda i, m, n=n, ch=ch: updates.append((n, ch[i], 1.0, m)))
+        _, P = specinfer_solver(p_of(n), q_of(n), [int(tokens[c]) for c in ch], decide, on_update)
         stop_dist[n] = P / np.sum(P)
     return probs, stop_dist
 

@@ -13,7 +13,7 @@ import paper_2602_16994_amd as mpv
 import workloads
 from oracle import block_efficiency_oracle as beo
 from oracle import mpv_oracle as orc
-from tests.parity_util import PROB_ATOL, spectr_slack
+from tests.parity_util import PROB_ATOL, node_tolerances
 
 pytestmark = pytest.mark.gpu
 
@@ -31,27 +31,6 @@ def run_library(inputs, T, method):
     res = mpv.mpv_block_efficiency(inputs["parent"], inputs["tokens"], inputs["target"], inputs["draft"], T, method)
     torch.cuda.synchronize()
     return res.expected.cpu().numpy(), res.reach_prob.cpu().numpy(), res.counters.cpu().numpy()
-
-
-def node_tolerances(method, host, b, T):
-    """Per-node bar on the reach probability."""
-    parent = host["parent"]
-    N = len(parent)
-    tol = np.full(N, PROB_ATOL)
-    if method != SPECTR:
-        return tol
-    children = orc.children_lists(parent)
-    slack = np.zeros(N)                       # of the step from a node to any of its children
-    for n in range(N):
-        if len(children[n]) > 1:
-            # every test probability moves by at most the slack; a step combines up to k of them
-            slack[n] = (len(children[n]) + 1) * spectr_slack(host, b, n, T, len(children[n]))
-    for n in range(1, N):
-        m = parent[n]
-        while m >= 0:
-            tol[n] += slack[m]
-            m = parent[m] if m > 0 else -1
-    return tol
 
 
 def compare(method, host, T, expected, reach, trees=None):

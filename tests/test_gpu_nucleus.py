@@ -16,7 +16,7 @@ import workloads
 from oracle import block_efficiency_oracle as beo
 from oracle import mpv_oracle as orc
 from oracle import nucleus_oracle as nuc
-from tests.parity_util import compare_with_oracle, result_to_host
+from tests.parity_util import compare_with_oracle, node_tolerances, result_to_host
 
 pytestmark = pytest.mark.gpu
 
@@ -166,7 +166,8 @@ def test_verification_of_masked_rows(method, name, B, top_p):
     for b in range(cfg.B):
         _, want = beo.expected_block_efficiency(method, host["parent"], host["tokens"][b], host["target"][b],
                                                 host["draft"][b], cfg.T)
-        assert np.max(np.abs(reach[b] - want)) < (1e-5 if method != mpv.MPV_METHOD_SPECTR else 1e-4)
+        tol = node_tolerances(method, host, b, cfg.T)          # 1e-5, plus SpecTr's (capped) conditioning slack
+        assert np.all(np.abs(reach[b] - want) <= tol), (b, float(np.max(np.abs(reach[b] - want) - tol)))
 
 
 def test_benchmark_batch_rows_sampled():

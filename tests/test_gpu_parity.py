@@ -50,37 +50,58 @@ def run_case(cfg, method, trees=None, debug=True):
     return rep, got
 
 
+def assert_everything_compared(cfg, rep):
+    """On the five benchmark configurations: every test that can be performed with probability above
+    1e-6 is compared at the flat bar (compare_with_oracle does that for every input).  The others
+    ("remote": they follow rejections that cannot happen, or the seventh and eighth rejection under
+    one node) are compared with the bar float32 terms allow for the residual mass they are computed
+    from; only where that mass is below float32 resolution, or at the zero-mass corner, is a number
+    left out (parity_util.remote_tolerance, fragile_tests), and those must stay a minority.
+    No SpecTr tolerance may hit its cap."""
+    left_out = rep["fragile_tests"] + rep["noise_tests"]
+    tests = rep["trees"] * (cfg.N - 1)
+    assert left_out <= rep["remote_tests"] + rep["fragile_tests"] and left_out < 0.5 * tests, rep
+    assert rep.get("capped_slacks", 0) == 0, rep
+
+
+def run_benchmark_config(cfg, method):
+    """One of the five benchmark configurations (possibly with fewer trees)."""
+    rep, got = run_case(cfg, method)
+    assert_everything_compared(cfg, rep)
+    return rep, got
+
+
 # ---------------------------------------------------------------- the five configurations
 
 @pytest.mark.parametrize("method", ALL_METHODS)
 def test_config1_tiny(method):
-    run_case(workloads.CONFIGS["tiny"], method)
+    run_benchmark_config(workloads.CONFIGS["tiny"], method)
 
 
 def test_config2_v32k_root_specinfer():
     # full vocabulary and tree, 6 of the 64 trees
-    run_case(workloads.scaled(workloads.CONFIGS["v32k_root"], B=6), SI)
+    run_benchmark_config(workloads.scaled(workloads.CONFIGS["v32k_root"], B=6), SI)
 
 
 @pytest.mark.parametrize("method", ALL_METHODS)
 def test_config3_v128k_delayed(method):
-    run_case(workloads.scaled(workloads.CONFIGS["v128k_delayed"], B=4), method)
+    run_benchmark_config(workloads.scaled(workloads.CONFIGS["v128k_delayed"], B=4), method)
 
 
 def test_config4_v152k_root_traversal_small_batch():
-    run_case(workloads.scaled(workloads.CONFIGS["v152k_root"], B=3), TV)
+    run_benchmark_config(workloads.scaled(workloads.CONFIGS["v152k_root"], B=3), TV)
 
 
 @pytest.mark.parametrize("method", ALL_METHODS)
 def test_config5_v262k_delayed(method):
-    run_case(workloads.scaled(workloads.CONFIGS["v262k_delayed"], B=2), method)
+    run_benchmark_config(workloads.scaled(workloads.CONFIGS["v262k_delayed"], B=2), method)
 
 
 @pytest.mark.parametrize("method", [NSS, NAIVE, SPECTR])
 def test_config2_and_4_token_following_walks(method):
     # the two root-expanded configurations with the solvers whose output token may be another draft token
-    run_case(workloads.scaled(workloads.CONFIGS["v32k_root"], B=6), method)
-    run_case(workloads.scaled(workloads.CONFIGS["v152k_root"], B=3), method)
+    run_benchmark_config(workloads.scaled(workloads.CONFIGS["v32k_root"], B=6), method)
+    run_benchmark_config(workloads.scaled(workloads.CONFIGS["v152k_root"], B=3), method)
 
 
 @pytest.mark.parametrize("method", [NSS, NAIVE, SPECTR])
@@ -95,36 +116,61 @@ def test_drawn_tokens_are_followed_in_small_vocabularies(method, V, dtype):
     assert np.any(got["accept_len"] >= 2)             # and some follow more than one token
 
 
-def test_config4_full_size_sampled_trees():
-    """The benchmark configuration at full size, in the launch configuration the
-    benchmark times (no debug outputs): properties for every tree, the oracle on
-    a sample of trees."""
-    cfg = workloads.CONFIGS["v152k_root"]
-    announce(cfg.name, "full size", f"B={cfg.B} N={cfg.N} V={cfg.V}")
+class TreeRows:
+    """host["target"] / host["draft"] for a batch too large to copy at once: tree b's rows are
+    copied to the host (widened to float32, which is exact) when the oracle asks for them."""
+
+    def __init__(self, tensor):
+        self.tensor = tensor
+        self.last = (None, None)
+
+    def __getitem__(self, b):
+        if self.last[0] != b:
+            self.last = (b, self.tensor[b].float().cpu().numpy())
+        return self.last[1]
+
+
+def full_size_case(cfg, method, debug_trees):
+    """A benchmark configuration at full size, in the launch configuration the benchmark times (no
+    debug outputs): every tree's decisions against the oracle; then the per-node probabilities of
+    `debug_trees`, run as a batch of their own with the debug outputs on, which must decide alike."""
+    announce(cfg.name, METHOD_NAME[method], "full size", f"B={cfg.B} N={cfg.N} V={cfg.V}")
     inputs = workloads.make_inputs(cfg, "cuda")
-    got = run_library(inputs, cfg.T, TV, debug=False)
-    sample = [0, 1, 37, 100, 128, 200, 254, 255]
+    got = run_library(inputs, cfg.T, method, debug=False)
+    assert got["counters"][4] == 0, "dependency wait timed out"
     host = {
         "parent": inputs["parent"],
         "tokens": inputs["tokens"].cpu().numpy(),
         "uniforms": inputs["uniforms"].cpu().numpy(),
+        "draw_uniforms": inputs["draw_uniforms"].cpu().numpy(),
+        "target": TreeRows(inputs["target"]),
+        "draft": TreeRows(inputs["draft"]),
     }
     check_properties(host["parent"], cfg.V, got, host["tokens"])
-    # copy only the sampled trees' logits to the host
-    tgt = {b: inputs["target"][b].float().cpu().numpy() for b in sample}
-    drf = {b: inputs["draft"][b].float().cpu().numpy() for b in sample}
-
-    host["target"], host["draft"] = tgt, drf
-    rep = compare_with_oracle(TV, host, cfg.T, got, trees=sample, check_debug=False)
+    rep = compare_with_oracle(method, host, cfg.T, got, check_debug=False)
+    assert rep["trees"] == cfg.B
     print("[report]", rep, "counters", got["counters"].tolist(),
           "mean accepted length (all trees)", float(got["accept_len"].mean()), flush=True)
-    # and the debug probabilities for two of them, run as a separate small batch
-    sub = {k: (v[[0, 255]].contiguous() if torch.is_tensor(v) else v) for k, v in inputs.items()}
-    got2 = run_library(sub, cfg.T, TV, debug=True)
-    rep2 = compare_with_oracle(TV, workloads.to_host(sub), cfg.T, got2)
-    assert np.array_equal(got2["accept_len"], got["accept_len"][[0, 255]])
-    assert np.array_equal(got2["bonus_token"], got["bonus_token"][[0, 255]])
+    sub = {k: (v[debug_trees].contiguous() if torch.is_tensor(v) else v) for k, v in inputs.items()}
+    got2 = run_library(sub, cfg.T, method, debug=True)
+    rep2 = compare_with_oracle(method, workloads.to_host(sub), cfg.T, got2)
+    if method in (SI, TV):
+        assert_everything_compared(cfg, rep2)
+    for key in ("accept_len", "path_nodes", "path_tokens", "bonus_token"):
+        assert np.array_equal(got2[key], got[key][debug_trees]), key
     print("[report]", rep2, flush=True)
+
+
+def test_config4_full_size_every_tree():
+    # the batch the benchmark times: all 256 trees against the oracle, per-node probabilities of 16
+    full_size_case(workloads.CONFIGS["v152k_root"], TV, list(range(0, 256, 16)))
+
+
+@pytest.mark.parametrize("name,method", [("v32k_root", SI), ("v128k_delayed", SI), ("v128k_delayed", TV),
+                                         ("v262k_delayed", SI), ("v262k_delayed", TV)])
+def test_configs_2_3_5_full_size_every_tree(name, method):
+    cfg = workloads.CONFIGS[name]
+    full_size_case(cfg, method, list(range(0, cfg.B, max(1, cfg.B // 4)))[:4])
 
 
 # ---------------------------------------------------------------- shapes, tails, edge cases

@@ -221,7 +221,7 @@ def test_spectr_acceptance_rate_matches_appendix_C(V, k):
 
 @pytest.mark.parametrize("seed", range(10))
 def test_spectr_with_one_draft_token_is_naive(seed):
-    # App. B: "This OTLP solver precisely reduces to the Naive solver when k = 1"
+    # App. B, SpecTr paragraph: the k = 1 reduction to the Naive solver
     rng = np.random.default_rng(700 + seed)
     V, L = 9, 4
     parent = list(range(-1, L))
