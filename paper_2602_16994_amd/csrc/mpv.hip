@@ -2,8 +2,12 @@
 //
 // Path of one mpv_verify call (all on the caller's stream):
 //   init_kernel            zero counters, default the per-node results, queue the first tasks
-//   node_task_kernel       persistent workgroups, about one per compute unit, that take tasks
-//                          from a queue until none are left.
+//   node_task_kernel       persistent workgroups of 256 lanes, four per compute unit, grouped in
+//                          TEAMS of G workgroups that take tasks from a queue until none are left.
+//                          A team splits every logit row by vocabulary range: each member keeps its
+//                          part of the task's (target, draft) row pair on chip (registers + LDS),
+//                          and every V-wide sum is a local partial plus one exchange of a few
+//                          words between the members (through memory; about a microsecond).
 //                          Node task, one per (tree, internal node) the rule needs:
 //                            softmax statistics of the node's target and draft rows, then,
 //                            for each child in list order, the probability the child is
@@ -14,10 +18,9 @@
 //                            positive weight; tasks of trees whose outcome is settled are
 //                            dropped.  With per-node debug outputs every node's task runs.
 //                          Sampling task, one per tree, started by the task that settles the
-//                            tree: the first wave does the uniform-dependent walk, then the
-//                            workgroup draws the bonus token by inverse CDF from the residual
-//                            of the stopping node.  (NSS, Naive, SpecTr: one per draw of the
-//                            token-following walk.)
+//                            tree: the uniform-dependent walk, then the team draws the bonus
+//                            token by inverse CDF from the residual of the stopping node.
+//                            (NSS, Naive, SpecTr: one per draw of the token-following walk.)
 // mpv_block_efficiency and mpv_acceptance_rates run the same kernels with every node task and
 // no uniforms (see Args::estimate); mpv_nucleus_mask is a kernel of its own (mpv_nucleus.h).
 //
@@ -60,7 +63,7 @@ struct TreeDesc {
 constexpr int kMaxClasses = 4;
 static_assert(kMaxClasses + 1 <= 8, "TreeDesc::class_off is too short");
 
-// The task queue is one first-in-first-out queue per priority class; a free workgroup is
+// The task queue is one first-in-first-out queue per priority class; a free team is
 // given the oldest task of the lowest class that has one.  Class 0: the nodes from the root down
 // to the first node that branches (every tree needs them).  Class 1: the nodes below it, which
 // a settled tree no longer needs.  (More classes are possible: the dispatcher takes any number
@@ -74,14 +77,21 @@ struct QueuePlan {
     int32_t init_slot[MPV_MAX_NODES];    // -1, or the node's index among the prequeued nodes of its class
     int32_t init_total;                  // prequeued tasks
     int32_t root_is_leaf;                // no node task at all: the sampling tasks are prequeued
-    int32_t workers;                     // workgroups of the launch; the first prequeued tasks of class 0 go straight to them
-    // Traversal, only what is needed, no workgroup to spare: the node where the tree branches
+    int32_t teams;                       // teams of the launch (the grid is teams * team_size workgroups)
+    int32_t team_size;                   // G: workgroups that share one task
+    int32_t part_vecs;                   // 16-byte vectors of a row per member (a multiple of 64)
+    int32_t same_xcd;                    // members of a team are 8 workgroup numbers apart (one chiplet, its L2)
+    // Traversal, only what is needed, no team to spare: the node where the tree branches
     // (-1: not used) first handles its first child only; the rest of its work (a second task:
     // "resumed") is started when that child's subtree, split_mask in postorder positions, turns
     // out to be rejected as a whole.
     int32_t split_node;
     unsigned long long split_mask;
 };
+
+constexpr int kMaxTeam = 16;                          // workgroups per team, at most
+constexpr int kExchWords = 8;                         // 64-bit words one member hands over per exchange
+constexpr int kMaxGrid = 1024;                        // workgroups of a launch, at most (four per compute unit)
 
 // Per-(tree,node) scalars kept in the workspace, all double, each [B*N].
 struct Workspace {
@@ -93,11 +103,12 @@ struct Workspace {
     double* atest;   // probability the node is tested with
     int32_t* queue;      // entry = tree * N + node (node task) or B * N + tree (sampling task), -1 = not written yet
     // [0] appended: tasks ever queued or started directly, [1] completed: tasks finished or cancelled,
-    // [2] exit: set when nothing is left, [3] lock: held by the workgroup that is dispatching,
+    // [2] exit: set when nothing is left, [3] lock: held by the team leader that is dispatching,
     // [4 + c] tail of class c: entries appended, [4 + kMaxClasses + c] head of class c: entries handed out,
-    // [4 + 2 kMaxClasses] workgroups left waiting after the last round of dispatching (a hint)
+    // [4 + 2 kMaxClasses] teams left waiting after the last round of dispatching (a hint)
     int32_t* qctl;
-    int32_t* mailbox;    // [workgroups] kMailboxWaiting, or the task handed to that workgroup
+    int32_t* mailbox;    // [teams] kMailboxAbsent until every member has started, then kMailboxWaiting /
+                         // kMailboxSoon, or the task handed to that team
     // Per tree, one bit per node at the node's position in postorder: `known` = the outcome of
     // the node's test is settled, `acc` = it is "accepted" (valid once known).  `decided` = the
     // sampling task has been queued (and, when only what the rule needs is computed, the
@@ -107,6 +118,13 @@ struct Workspace {
     int32_t* decided;
     int32_t* cur;        // [B] token-following walks: the node the walk has reached
     TreeDesc* tree;      // the tree tables, written by init_kernel for the kernel that follows
+    // Teams.  exch: [team][2][member][kExchWords] words of (sequence number << 32 | 32 bits of payload);
+    // team_task: [team][2] the task the leader has taken and its flags, same packing; arrived: members
+    // of the team that have started.
+    unsigned long long* exch;
+    unsigned long long* team_task;
+    int32_t* arrived;
+    struct Launch* launch;   // what node_task_kernel is launched with, written by init_kernel
 };
 
 // Every field has a default (null / 0): what a call does not set stays off.
@@ -131,7 +149,6 @@ struct Args {
                      // visited node and followed if it is a child's: 1 from p (NSS), 2 after the Naive test,
                      // 3 after the SpecTr tests
     int32_t lazy = 0;    // compute only what the rule needs (off when per-node debug output is wanted: then every node task runs)
-    int32_t stagger_ticks = 0;   // start-up spread of the persistent workgroups, in 10 ns ticks per step (8 steps)
     // Expected block efficiency instead of a verification (Sec. 5, Eq. 1-3): every node task runs
     // (lazy = 0), no uniforms are read, and what would be a tree's sampling task turns the per-node
     // results into reach probabilities.  reach_prob [B,N] may be null; expected [B].
@@ -143,27 +160,74 @@ struct Args {
     float* alpha = nullptr;
 };
 
-constexpr int kTaskBlock = 512;
+// Everything node_task_kernel needs to know, in one block of the workspace: the kernel and the
+// functions it calls read it through one pointer (as kernel arguments, passed on by reference, the
+// three structures were copied into every lane's private memory).
+struct Launch {
+    QueuePlan q;
+    Workspace ws;
+    Args a;
+};
+
+constexpr int kTaskBlock = 256;
+constexpr int kTaskWaves = kTaskBlock / kWave;
 constexpr int kTaskUnroll = 4;
-// node tasks keep a row pair on chip: per lane and row, kRegVecs 16-byte vectors in
-// registers and kLdsVecs in LDS; the rest is re-read (kChunk vectors in flight)
-constexpr int kRegVecs = 18;
-constexpr int kLdsVecs = 9;
-constexpr int kChunk = 2;
+// node tasks keep their part of a row pair on chip: per lane and row, kRegVecs 16-byte vectors in
+// registers and kLdsVecs in LDS
+constexpr int kRegVecs = 8;
+constexpr int kLdsVecs = 4;
+constexpr int kPartCapacity = (kRegVecs + kLdsVecs) * kTaskBlock;     // vectors of a row one member keeps
 // upper bound on the polls of a dependency flag (about a second); see node_task_kernel
 constexpr int kMaxSpins = 1 << 20;
+// no wait inside a launch outlasts this (wall clock, 100 MHz ticks: 2 s)
+constexpr long long kLaunchTimeoutTicks = 200000000ll;
 // bit pattern (a NaN) of a starting weight that has not been published yet
 constexpr unsigned long long kNotReady = ~0ull;
-constexpr int kSampleBlock = kTaskBlock;     // sampling tasks run on the node tasks' workgroups
 // wave tiles of the bonus sampler: 64 16-byte vectors; float rows have the smallest tiles
 constexpr int kMaxTiles = MPV_MAX_VOCAB / (kWave * 4);
-// task hand-over between the dispatcher and the workers (see "task queue")
-constexpr int kMailboxWaiting = -1;                  // the workgroup is idle
-constexpr int kMailboxSoon = -2;                     // the workgroup has asked ahead: it will be free shortly
-constexpr int kTaskExit = -1;                         // what a worker's wait returns when all is done
+// task hand-over between the dispatcher and the teams (see "task queue")
+constexpr int kMailboxWaiting = -1;                  // the team is idle
+constexpr int kMailboxSoon = -2;                     // the team has asked ahead: it will be free shortly
+constexpr int kMailboxAbsent = -3;                   // not every member of the team has started yet
+constexpr int kTaskExit = -1;                         // what a leader's wait returns when all is done
 constexpr int kWorkerSlots = 8;                       // mailboxes per dispatcher lane
-constexpr int kMaxWorkgroups = kWave * kWorkerSlots;
+constexpr int kMaxTeams = kWave * kWorkerSlots;
 constexpr int kKindAcceptance = 100;                   // node_task_kernel instantiation for the acceptance rates (see there)
+
+// LDS of node_task_kernel that the functions it calls use as well (file scope, so that they address
+// it as LDS and not through generic pointers)
+struct TaskShared {
+    double scratch[2 * kTaskWaves];
+    unsigned words[kMaxTeam * kExchWords];
+};
+__shared__ TaskShared g_sh;
+// the part of the row pair kept in LDS (target slots, then draft slots); the sampling task's table
+// of tile masses uses the same memory
+__shared__ uint4 g_rows[2 * kLdsVecs * kTaskBlock];
+static_assert(sizeof(g_rows) >= kMaxTiles * sizeof(float), "tile masses do not fit in the kept-row LDS");
+// the tree tables (copied from the workspace at the start of node_task_kernel)
+__shared__ TreeDesc g_tree;
+
+// A value that is the same in every lane, for the compiler to keep in scalar registers.  Needed
+// wherever a function that is not inlined receives it: arguments arrive in vector registers.
+__device__ __forceinline__ int uniform_i32(int x) { return __builtin_amdgcn_readfirstlane(x); }
+template <class P>
+__device__ __forceinline__ P* uniform_ptr(P* p) {
+    const unsigned long long v = reinterpret_cast<unsigned long long>(p);
+    const unsigned lo = static_cast<unsigned>(__builtin_amdgcn_readfirstlane(static_cast<int>(v)));
+    const unsigned hi = static_cast<unsigned>(__builtin_amdgcn_readfirstlane(static_cast<int>(v >> 32)));
+    return reinterpret_cast<P*>((static_cast<unsigned long long>(hi) << 32) | lo);
+}
+template <class S>
+__device__ __forceinline__ S uniform_struct(const S& s) {
+    static_assert(sizeof(S) % 4 == 0, "whole words only");
+    S out;
+    const int* src = reinterpret_cast<const int*>(&s);
+    int* dst = reinterpret_cast<int*>(&out);
+#pragma unroll
+    for (int i = 0; i < static_cast<int>(sizeof(S) / 4); ++i) dst[i] = __builtin_amdgcn_readfirstlane(src[i]);
+    return out;
+}
 
 // ------------------------------------------------------------------ init
 
@@ -182,17 +246,37 @@ __global__ void init_kernel(QueuePlan q, TreeDesc tree, Workspace ws, Args a) {
             if (threadIdx.x == 0) dst[w] = v;
         }
     }
+    {   // the launch block of the next kernel
+        struct Words { Launch l; };
+        const int groups = gridDim.x * gridDim.y;
+        int* dst = reinterpret_cast<int*>(ws.launch);
+        const int me = blockIdx.y * gridDim.x + blockIdx.x;
+        const int nq = static_cast<int>(sizeof(QueuePlan) / sizeof(int)), nw = static_cast<int>(sizeof(Workspace) / sizeof(int));
+        const int na = static_cast<int>(sizeof(Args) / sizeof(int));
+        static_assert(sizeof(QueuePlan) % 8 == 0 && sizeof(Workspace) % 8 == 0 && sizeof(Args) % 8 == 0, "Launch has no padding between its members");
+        for (int w = me; w < nq + nw + na; w += groups) {
+            int v;
+            if (w < nq) v = reinterpret_cast<const int*>(&q)[w];
+            else if (w < nq + nw) v = reinterpret_cast<const int*>(&ws)[w - nq];
+            else v = reinterpret_cast<const int*>(&a)[w - nq - nw];
+            if (threadIdx.x == 0) dst[w] = v;
+        }
+    }
+    {   // team words: every sequence number starts at 0, nobody has arrived
+        const int stride = gridDim.x * gridDim.y * blockDim.x;
+        const int me = (blockIdx.y * gridDim.x + blockIdx.x) * blockDim.x + threadIdx.x;
+        for (int w = me; w < kMaxGrid * 2 * kExchWords; w += stride) ws.exch[w] = 0ull;
+        for (int w = me; w < kMaxTeams * 2; w += stride) ws.team_task[w] = 0ull;
+        for (int w = me; w < kMaxTeams; w += stride) { ws.arrived[w] = 0; ws.mailbox[w] = kMailboxAbsent; }
+    }
     if (n == 0) {
         if (i < MPV_COUNTER_COUNT) a.counters[i] = 0u;
         if (i == 0) { ws.qctl[0] = q.init_total; ws.qctl[1] = 0; ws.qctl[2] = 0; ws.qctl[3] = 0; ws.qctl[4 + 2 * kMaxClasses] = 0; }
         for (int c = 0; c < kMaxClasses; ++c)
             if (i == 0) {
                 ws.qctl[4 + c] = (c < q.nclass) ? q.init_tail[c] : 0;
-                ws.qctl[4 + kMaxClasses + c] = (c == 0) ? min(q.workers, q.init_tail[0]) : 0;
+                ws.qctl[4 + kMaxClasses + c] = 0;
             }
-        // every worker starts out waiting; the first class-0 entries are handed over below
-        for (int w = i; w < kMaxWorkgroups; w += gridDim.x * blockDim.x)
-            if (w >= q.init_tail[0]) ws.mailbox[w] = kMailboxWaiting;
         if (i < a.B) {
             // the root is never tested: it counts as accepted from the start
             ws.known[i] = 1ull << (a.N - 1);
@@ -203,10 +287,7 @@ __global__ void init_kernel(QueuePlan q, TreeDesc tree, Workspace ws, Args a) {
                 a.dbg_edge[static_cast<size_t>(i) * a.N * 2] = 1.f;
                 a.dbg_edge[static_cast<size_t>(i) * a.N * 2 + 1] = 1.f;
             }
-            if (q.root_is_leaf) {
-                ws.queue[q.off[0] + i] = a.B * a.N + i;
-                if (i < kMaxWorkgroups) ws.mailbox[i] = a.B * a.N + i;
-            }
+            if (q.root_is_leaf) ws.queue[q.off[0] + i] = a.B * a.N + i;
         }
     }
     if (i >= a.B) return;
@@ -228,32 +309,32 @@ __global__ void init_kernel(QueuePlan q, TreeDesc tree, Workspace ws, Args a) {
     if (q.init_slot[n] >= 0) {
         const int slot = q.init_slot[n] * a.B + b;
         ws.queue[q.off[tree.cls[n]] + slot] = b * a.N + n;
-        if (tree.cls[n] == 0 && slot < kMaxWorkgroups) ws.mailbox[slot] = b * a.N + n;
     }
 }
 
 // ------------------------------------------------------------------ task queue
 //
-// node_task_kernel is launched with about one workgroup per compute unit; each runs tasks
-// until told to exit.  A task is appended only when everything it needs has been published,
-// so every queued task can run at once, on any workgroup: nothing depends on which or how
-// many workgroups are resident.
+// node_task_kernel is launched with four workgroups per compute unit at most, grouped in teams;
+// each team runs tasks until told to exit.  A team takes part only once every member has
+// started (the last to arrive opens the team's mailbox), so a task is only ever handed to
+// workgroups that are running, whatever else occupies the device.  A task is appended only when
+// everything it needs has been published, so every queued task can run at once, on any team.
 //   append:   appended++, then slot = tail++ of the class, then the entry is written.
-//   request:  mailbox[w] = "soon" when a workgroup asks ahead, before the last sweep of its
+//   request:  mailbox[team] = "soon" when a team asks ahead, before the last sweep of its
 //             current task (the answer is then usually there when it is done), "waiting" once
-//             it has nothing to do.  Idle workgroups are served before those that asked ahead.
-//   dispatch: a workgroup that has nothing to do takes the dispatcher lock if it is free and,
-//             with its first wave, hands queued tasks to waiting workgroups (itself included)
+//             it has nothing to do.  Idle teams are served before those that asked ahead.
+//   dispatch: a leader that has nothing to do takes the dispatcher lock if it is free and,
+//             with its first wave, hands queued tasks to waiting teams (its own included)
 //             in priority order (class, then age), until it has a task of its own; then it
 //             releases the lock.  Those that find the lock taken poll their mailbox.  If every
-//             workgroup is busy nobody dispatches, and nobody needs to.  Node tasks of trees
+//             team is busy nobody dispatches, and nobody needs to.  Node tasks of trees
 //             whose outcome is settled are dropped here when only what is needed is computed.
 //   end:      nothing queued and completed == appended, with appended read before and after
 //             completed and unchanged: no task is queued, handed out or running, so nothing
-//             can be appended any more; the dispatching workgroup sets the exit flag.  A
+//             can be appended any more; the dispatching leader sets the exit flag.  A
 //             task's appends are performed before its completed++.
-// A workgroup may also run a task it has produced itself straight away (counted in appended,
-// never queued).  Every wait is bounded.
+// A team may also run a task it has produced itself straight away (counted in appended,
+// never queued).  Every wait is bounded.  Only the leader (member 0) of a team talks to the queue.
 
 __device__ __forceinline__ int ld_relaxed(const int32_t* p) {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -264,13 +345,11 @@ __device__ __forceinline__ unsigned long long ld_relaxed(const unsigned long lon
 __device__ __forceinline__ void st_relaxed(int32_t* p, int v) {
     __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
+__device__ __forceinline__ void st_relaxed(unsigned long long* p, unsigned long long v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
 // all loads, stores and atomics issued so far by this lane have been performed
 __device__ __forceinline__ void wait_memory() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
-
-// One lane: ask for a task ahead of time.
-__device__ __forceinline__ void request_task(const Workspace& ws) {
-    st_relaxed(&ws.mailbox[blockIdx.x], kMailboxSoon);
-}
 
 // Append one task to class c (one lane).  The caller's earlier stores have been waited for.
 __device__ __forceinline__ void append_task(const TreeDesc& tree, const Workspace& ws, int c, int entry) {
@@ -282,13 +361,13 @@ __device__ __forceinline__ void append_task(const TreeDesc& tree, const Workspac
 }
 
 // One round of dispatching, by a whole wave that holds the lock.  Lane c keeps the head of
-// class c in `head`; lane l looks after the workgroups l, l + 64, ...  Returns true when
+// class c in `head`; lane l looks after the teams l, l + 64, ...  Returns true when
 // everything is finished (the exit flag has been set).
 __device__ __forceinline__ bool dispatch_round(const QueuePlan& q, const TreeDesc& tree, const Workspace& ws, const Args& a, bool drop_settled,
                                int& head, long long t_begin) {
     __shared__ int sh_head[kMaxClasses], sh_before[kMaxClasses + 1];
     const int lane = threadIdx.x;
-    const int workers = static_cast<int>(gridDim.x);
+    const int workers = q.teams;
     // who is waiting, what is queued
     unsigned waiting = 0u, soon = 0u;
 #pragma unroll
@@ -319,7 +398,7 @@ __device__ __forceinline__ bool dispatch_round(const QueuePlan& q, const TreeDes
             const int a2 = ld_relaxed(&ws.qctl[0]);
             done = (co == a1 && a1 == a2) ? 1 : 0;
             // a queue entry that never arrives, a task that never ends: give up after 2 s (must never happen)
-            if (!done && wall_clock64() - t_begin > 200000000ll) {
+            if (!done && wall_clock64() - t_begin > kLaunchTimeoutTicks) {
                 atomicAdd(&a.counters[MPV_COUNTER_DEPENDENCY_TIMEOUT], 1u);
                 done = 1;
             }
@@ -337,7 +416,7 @@ __device__ __forceinline__ bool dispatch_round(const QueuePlan& q, const TreeDes
         __builtin_amdgcn_s_sleep(8);
         return false;
     }
-    // Requester number r gets queued task number r (in class, age order); the idle workgroups
+    // Requester number r gets queued task number r (in class, age order); the idle teams
     // come first (in lane, slot order), then those that asked ahead.
     if (lane < q.nclass) { sh_head[lane] = head; sh_before[lane + 1] = avail_incl; }
     if (lane == 0) sh_before[0] = 0;
@@ -378,14 +457,21 @@ __device__ __forceinline__ bool dispatch_round(const QueuePlan& q, const TreeDes
     return false;
 }
 
-// The next task of this workgroup, or kTaskExit; called by every lane of the first wave, returns
-// the same value in each.  The workgroup has asked (its mailbox says "waiting" or already holds
+// The next task of this team, or kTaskExit; called by every lane of the leader's first wave, returns
+// the same value in each.  The team has asked (its mailbox says "waiting" or already holds
 // the answer).  `previous` is the task it took from the mailbox last: until the request has
 // reached memory the mailbox may still show it (no entry is ever handed out twice, so the
 // value is unambiguous).
-__device__ __forceinline__ int acquire_task(const QueuePlan& q, const TreeDesc& tree, const Workspace& ws, const Args& a, int previous, bool drop_settled) {
+__device__ __attribute__((noinline)) int acquire_task(const Launch* launch, int team_in, int previous_in, bool drop_settled_in, long long t_start) {
+    const Launch* const L = uniform_ptr(launch);
+    const Args a = uniform_struct(L->a);
+    const Workspace ws = uniform_struct(L->ws);
+    const QueuePlan q = uniform_struct(L->q);
+    const TreeDesc& tree = g_tree;
+    const int team = uniform_i32(team_in), previous = uniform_i32(previous_in);
+    const bool drop_settled = uniform_i32(drop_settled_in ? 1 : 0) != 0;
     const int lane = threadIdx.x;
-    int32_t* const box = &ws.mailbox[blockIdx.x];
+    int32_t* const box = &ws.mailbox[team];
     for (int spin = 0; spin < kMaxSpins; ++spin) {
         int t = 0, ex = 0, lk = 1;
         if (lane == 0) {
@@ -398,14 +484,14 @@ __device__ __forceinline__ int acquire_task(const QueuePlan& q, const TreeDesc& 
         if (t >= 0 && t != previous) return t;
         if (__builtin_amdgcn_readfirstlane(ex)) return kTaskExit;
         int got = 0;
-        if (lane == 0 && lk == 0) got = (atomicCAS(&ws.qctl[3], 0, 1) == 0) ? 1 : 0;
+        // (a team whose mailbox is still "absent" cannot be handed anything: it does not dispatch either)
+        if (lane == 0 && lk == 0 && t != kMailboxAbsent) got = (atomicCAS(&ws.qctl[3], 0, 1) == 0) ? 1 : 0;
         if (__builtin_amdgcn_readfirstlane(got)) {
             // the previous holder wrote the heads before it released the lock
             int head = (lane < q.nclass) ? ld_relaxed(&ws.qctl[4 + kMaxClasses + lane]) : 0;
-            const long long t_begin = wall_clock64();
             int result = kTaskExit;
             for (;;) {
-                const bool finished = dispatch_round(q, tree, ws, a, drop_settled, head, t_begin);
+                const bool finished = dispatch_round(q, tree, ws, a, drop_settled, head, t_start);
                 if (finished) break;
                 int mine = (lane == 0) ? ld_relaxed(box) : 0;
                 mine = __builtin_amdgcn_readfirstlane(mine);
@@ -416,6 +502,7 @@ __device__ __forceinline__ int acquire_task(const QueuePlan& q, const TreeDesc& 
             if (lane == 0) st_relaxed(&ws.qctl[3], 0);
             return result;
         }
+        if (wall_clock64() - t_start > kLaunchTimeoutTicks) break;
         __builtin_amdgcn_s_sleep(8);
     }
     if (lane == 0) atomicAdd(&a.counters[MPV_COUNTER_DEPENDENCY_TIMEOUT], 1u);     // must never happen
@@ -436,107 +523,220 @@ __device__ __forceinline__ double ld_shared_f64(const double* p) {
         reinterpret_cast<const unsigned long long*>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)));
 }
 
+// ------------------------------------------------------------------ teams
+//
+// The G members of a team run the same task in lockstep on different vocabulary ranges: they
+// execute the same scalar code on the same numbers (exchanged sums are added in member order
+// by every member, so they are bitwise equal everywhere) and therefore take the same branches;
+// side effects (results, queue, counters) are the leader's (member 0).  What the leader alone
+// can know (the task, whether teams are idle, a starting weight) travels with the task word or
+// with the first exchange of the task.
+// An exchange: every member writes up to kExchWords words into its own 64-byte line of the
+// team's area, each word tagged with the number of the exchange, and polls the other lines until
+// every word carries that number.  Two areas alternate: a member can be at most one exchange
+// ahead of the slowest (it needs everybody's words of exchange s to finish s), so the words
+// of exchange s are never overwritten before everybody has read them.
+
+struct Team {
+    int id, member, size;
+    unsigned seq;                    // exchanges done
+    unsigned tseq;                   // task words seen
+    unsigned long long* area;        // [2][size][kExchWords]
+    unsigned long long* task_word;   // [2]
+    long long t_start;               // wall clock at the start of the launch
+    int dead;                        // a partner never answered: results are invalid, every wait is skipped
+};
+
+// All lanes of the workgroup.  Lane w < kExchWords of the first wave brings `mine`, its 32 bits of
+// payload.  On return words[m * kExchWords + w] holds member m's word w.
+__device__ __forceinline__ void team_exchange(Team& t, unsigned mine, unsigned* words, const Workspace& ws, const Args& a) {
+    __shared__ int sh_dead;
+    t.seq++;
+    __syncthreads();                                  // earlier readers of `words` are done
+    if (t.size == 1) {
+        if (threadIdx.x < kExchWords) words[threadIdx.x] = mine;
+        __syncthreads();
+        return;
+    }
+    if (threadIdx.x < kWave) {
+        unsigned long long* base = t.area + static_cast<size_t>(t.seq & 1u) * t.size * kExchWords;
+        const unsigned long long tag = static_cast<unsigned long long>(t.seq) << 32;
+        if (threadIdx.x < kExchWords) st_relaxed(base + t.member * kExchWords + threadIdx.x, tag | mine);
+        int dead = t.dead;
+        for (int w = threadIdx.x; w < t.size * kExchWords; w += kWave) {
+            unsigned long long v = 0ull;
+            while (!dead) {
+                v = ld_relaxed(base + w);
+                if ((v >> 32) == (tag >> 32)) break;
+                if (wall_clock64() - t.t_start > kLaunchTimeoutTicks) { dead = 1; break; }
+                __builtin_amdgcn_s_sleep(1);
+            }
+            words[w] = dead ? 0u : static_cast<unsigned>(v);
+        }
+        const int any_dead = __ballot(dead != 0) != 0ull;
+        if (threadIdx.x == 0) {
+            sh_dead = any_dead;
+            if (any_dead && !t.dead) {
+                atomicAdd(&a.counters[MPV_COUNTER_DEPENDENCY_TIMEOUT], 1u);
+                st_relaxed(&ws.qctl[2], 1);            // everybody leaves at the next occasion
+            }
+        }
+    }
+    __syncthreads();
+    t.dead = sh_dead;
+}
+
+__device__ __forceinline__ unsigned half_of(double v, int hi) {
+    return static_cast<unsigned>(hi ? __double2hiint(v) : __double2loint(v));
+}
+__device__ __forceinline__ double double_at(const unsigned* words, int member, int pair) {
+    return __hiloint2double(static_cast<int>(words[member * kExchWords + 2 * pair + 1]),
+                            static_cast<int>(words[member * kExchWords + 2 * pair]));
+}
+
+// Sums of up to four per-member values over the team, added in member order; every lane of every
+// member gets the same bits.  v[i] must be the same in every lane of the workgroup.
+template <int COUNT>
+__device__ __forceinline__ void team_sum(Team& t, double (&v)[COUNT], unsigned* words, const Workspace& ws, const Args& a) {
+    static_assert(COUNT * 2 <= kExchWords, "too many values for one exchange");
+    unsigned mine = 0u;
+#pragma unroll
+    for (int i = 0; i < COUNT; ++i) {
+        if (threadIdx.x == 2 * i) mine = half_of(v[i], 0);
+        if (threadIdx.x == 2 * i + 1) mine = half_of(v[i], 1);
+    }
+    team_exchange(t, mine, words, ws, a);
+#pragma unroll
+    for (int i = 0; i < COUNT; ++i) {
+        double s = 0.0;
+        for (int m = 0; m < t.size; ++m) s += double_at(words, m, i);
+        v[i] = s;
+    }
+}
+
+// The leader tells the others which task it has taken.  Every task announced this way contains at
+// least one exchange, so the leader cannot announce the next before everybody has read this one.
+__device__ __forceinline__ void team_announce(Team& t, int task, int flags) {
+    t.tseq++;
+    if (t.size == 1) return;
+    if (threadIdx.x < 2) {
+        const unsigned long long tag = static_cast<unsigned long long>(t.tseq) << 32;
+        st_relaxed(t.task_word + threadIdx.x, tag | static_cast<unsigned>(threadIdx.x == 0 ? task : flags));
+    }
+}
+// The others wait for it (first wave; returns the same in every lane).  kTaskExit on a timeout.
+__device__ __forceinline__ int team_listen(Team& t, int& flags, const Workspace& ws) {
+    t.tseq++;
+    unsigned long long v = 0ull;
+    int ok = 1;
+    if (threadIdx.x < 2) {
+        for (;;) {
+            v = ld_relaxed(t.task_word + threadIdx.x);
+            if ((v >> 32) == t.tseq) break;
+            if (wall_clock64() - t.t_start > kLaunchTimeoutTicks) { ok = 0; break; }
+            __builtin_amdgcn_s_sleep(2);
+        }
+    }
+    const int all_ok = __ballot(!ok) == 0ull;
+    const int task = __builtin_amdgcn_readlane(static_cast<int>(static_cast<unsigned>(v)), 0);
+    flags = __builtin_amdgcn_readlane(static_cast<int>(static_cast<unsigned>(v)), 1);
+    return all_ok ? task : kTaskExit;
+}
+
 // ------------------------------------------------------------------ node task
 
+// Double-precision scalar steps between the sweeps, as calls: their registers are then theirs alone
+// and the part of the row pair a task keeps in registers stays where it is.
+__device__ __forceinline__ double cold_exp2(double x) { return exp2(x); }
+__device__ __forceinline__ double cold_log2(double x) { return log2(x); }
+__device__ __forceinline__ ResidualConsts cold_residual_consts(double At, double Ad, double c) { return residual_consts(At, Ad, c); }
+// x^k for a small whole k
+__device__ __forceinline__ double int_power(double x, int k) {
+    double r = 1.0;
+    for (int i = 0; i < k; ++i) r *= x;
+    return r;
+}
+
+// task word flags (leader -> members)
+constexpr int kFlagIdle = 1;          // teams were idle after the last round of dispatching
+
 // (defined below) walk and bonus token of tree b, or one draw of a token-following walk, by the
-// whole workgroup; returns the task that follows from it (-1: none; the same in every lane)
+// whole team; returns the task that follows from it (-1: none; the same in every lane of every member)
 template <class E, int METHOD>
-__device__ __forceinline__ int sample_task(const TreeDesc& tree, const Workspace& ws, const Args& a, int b,
-                           float* tile_sum, double* scratch);
+__device__ __attribute__((noinline)) int sample_task(const Launch* launch, Team& team_io, int b_in);
 
 // (defined below) expected block efficiency of tree b from the per-node results, by the first wave
 template <int METHOD>
 __device__ __forceinline__ void estimate_wave(const TreeDesc& tree, const Workspace& ws, const Args& a, int b);
 
-template <class E, int KIND, bool FULL>
-__global__ __launch_bounds__(kTaskBlock) void node_task_kernel(QueuePlan q, Workspace ws, Args a) {
+// Softmax statistics of the task's two rows from the lanes' states: block reduction, then one
+// exchange that also carries the node's starting weight from the leader (a0_leader; the value
+// the other members pass is ignored).  Every lane of every member gets the same bits.
+__device__ __forceinline__ void team_stats(Team& t, const OnlineLse& lt, const OnlineLse& ld, double a0_leader,
+                                           double& At, double& Ad, double& a0, const Workspace& ws, const Args& a) {
+    float Mt = lt.mk, Md = ld.mk;
+    block_max2<kTaskBlock>(Mt, Md, g_sh.scratch);
+    double st = (lt.s > 0.f) ? static_cast<double>(lt.s * fast_exp2(lt.mk - Mt)) : 0.0;
+    double sd = (ld.s > 0.f) ? static_cast<double>(ld.s * fast_exp2(ld.mk - Md)) : 0.0;
+    block_sum2<kTaskBlock>(st, sd, g_sh.scratch);
+    unsigned mine = 0u;
+    switch (threadIdx.x) {
+        case 0: mine = __float_as_uint(Mt); break;
+        case 1: mine = __float_as_uint(Md); break;
+        case 2: mine = half_of(st, 0); break;
+        case 3: mine = half_of(st, 1); break;
+        case 4: mine = half_of(sd, 0); break;
+        case 5: mine = half_of(sd, 1); break;
+        case 6: mine = half_of(a0_leader, 0); break;
+        case 7: mine = half_of(a0_leader, 1); break;
+        default: break;
+    }
+    team_exchange(t, mine, g_sh.words, ws, a);
+    float MT = OnlineLse::kFloor, MD = OnlineLse::kFloor;
+    for (int m = 0; m < t.size; ++m) {
+        MT = fmaxf(MT, __uint_as_float(g_sh.words[m * kExchWords]));
+        MD = fmaxf(MD, __uint_as_float(g_sh.words[m * kExchWords + 1]));
+    }
+    double ST = 0.0, SD = 0.0;
+    for (int m = 0; m < t.size; ++m) {
+        const double pt = double_at(g_sh.words, m, 1), pd = double_at(g_sh.words, m, 2);
+        if (pt > 0.0) ST += pt * cold_exp2(static_cast<double>(__uint_as_float(g_sh.words[m * kExchWords])) - static_cast<double>(MT));
+        if (pd > 0.0) SD += pd * cold_exp2(static_cast<double>(__uint_as_float(g_sh.words[m * kExchWords + 1])) - static_cast<double>(MD));
+    }
+    At = uniform_f64(static_cast<double>(MT) + cold_log2(ST));
+    Ad = uniform_f64(static_cast<double>(MD) + cold_log2(SD));
+    a0 = uniform_f64(double_at(g_sh.words, 0, 3));
+}
+
+// One node task (or the resumed task of the node where the tree branches), by every member of the
+// team.  A function of its own, not inlined: what it keeps in registers (its part of the row pair)
+// then competes only with its own scalar steps for registers, not with the dispatcher or the sampler.
+// asked / own_task: the leader's notes for the task loop (has the team asked for its next task; the
+// task it is to run next without asking).
+template <class E, int KIND>
+__device__ __attribute__((noinline)) void run_node_task(const Launch* launch, Team& team_io, int task_in, int flags_in,
+                                                        bool& asked_io, int& own_task_io) {
     using T = typename E::T;
-    // KIND: MPV_METHOD_SPECINFER (all top-down rules) or MPV_METHOD_TRAVERSAL, or kKindAcceptance: the
-    // top-down kernel reduced to what the acceptance rates need (an instantiation of its own, so that
-    // its extra sweeps do not weigh on the register allocation of the verification kernels)
     constexpr bool ACCEPT = KIND == kKindAcceptance;
     constexpr int METHOD = ACCEPT ? MPV_METHOD_SPECINFER : KIND;
-    __shared__ double scratch[2 * (kTaskBlock / kWave)];
-    // rows too short to fill the on-chip slots are simply streamed again (they sit in L2)
-    constexpr int RV = FULL ? kRegVecs : 0;
-    constexpr int LV = FULL ? kLdsVecs : 0;
-    constexpr int CH = FULL ? kChunk : 4;
-    __shared__ uint4 lds_t[(LV > 0 ? LV : 1) * kTaskBlock];
-    __shared__ uint4 lds_d[(LV > 0 ? LV : 1) * kTaskBlock];
-
-    // the sampling task's table of tile masses shares the LDS the kept rows use
-    static_assert(!FULL || sizeof(lds_t) >= kMaxTiles * sizeof(float), "tile masses do not fit in the kept-row LDS");
-    __shared__ float own_tile_mass[FULL ? 1 : kMaxTiles];
-
-    __shared__ int sh_task;
-    // The tree tables are read from LDS, copied there from the workspace (init_kernel put them
-    // there), not from the kernel arguments: a table that is a kernel argument and is indexed
-    // with a value the compiler keeps in a vector register is copied, whole, into every lane's
-    // private memory.
-    __shared__ TreeDesc sh_tree;
-    for (int w = threadIdx.x; w < static_cast<int>(sizeof(TreeDesc) / sizeof(int)); w += kTaskBlock)
-        reinterpret_cast<int*>(&sh_tree)[w] = reinterpret_cast<const int*>(ws.tree)[w];
-    const TreeDesc& tree = sh_tree;               // the task loop starts with a barrier
-    // Every task alternates a memory-bound sweep with compute-bound replays and all tasks of a
-    // kind take the same time, so workgroups started together stay in step: all load at once
-    // (sharing the memory bandwidth), then all leave memory idle.  Spreading their start over
-    // a fraction of a task keeps them out of phase for the rest of the launch.
-    if (a.stagger_ticks > 0) {
-        const long long wait = static_cast<long long>((blockIdx.x >> 3) & 7) * a.stagger_ticks;
-        const long long t0 = wall_clock64();
-        while (wall_clock64() - t0 < wait) __builtin_amdgcn_s_sleep(16);    // the clock always advances: bounded
-    }
-    const bool drop_settled = METHOD == MPV_METHOD_TRAVERSAL && a.lazy != 0;
-    int previous_task = -3;                           // last task taken from the mailbox: none yet
-    bool asked = true;                                // the launch starts with every mailbox waiting or filled
-    int own_task = -1;                                // a task this workgroup produced for itself
-    for (;;) {
-    __syncthreads();                                  // the previous task is done with LDS
-    int task;
-    if (own_task >= 0) {
-        task = own_task;
-        own_task = -1;
-    } else {
-        if (threadIdx.x < kWave) {
-            if (!asked) {
-                if (threadIdx.x == 0) st_relaxed(&ws.mailbox[blockIdx.x], kMailboxWaiting);
-                wait_memory();
-            }
-            const int t = acquire_task(q, tree, ws, a, previous_task, drop_settled);
-            if (threadIdx.x == 0) sh_task = t;
-        }
-        __syncthreads();
-        task = sh_task;
-        previous_task = task;
-        asked = false;
-        if (task == kTaskExit) break;
-    }
-    task = __builtin_amdgcn_readfirstlane(task);
-    if (task >= a.B * a.N && task < a.B * a.N + a.B) {
-        // the tree's outcome is settled: walk and bonus token
-        if (!asked) {
-            if (threadIdx.x == 0) request_task(ws);
-            asked = true;
-        }
-        float* tile_mass = FULL ? reinterpret_cast<float*>(lds_t) : own_tile_mass;
-        int next = -1;
-        if (ACCEPT) {
-            // acceptance rates: nothing follows the node tasks (a root without children has none at all)
-        } else if (a.estimate) {
-            if (threadIdx.x < kWave) estimate_wave<METHOD>(tree, ws, a, task - a.B * a.N);
-        } else {
-            next = sample_task<E, METHOD>(tree, ws, a, task - a.B * a.N, tile_mass, scratch);
-        }
-        if (next >= 0) own_task = next;               // a token-following walk goes on
-        if (threadIdx.x == 0) {
-            if (next >= 0) {
-                (void)atomicAdd(&ws.qctl[0], 1);
-                wait_memory();                        // counted (and the walk's position written) first
-            }
-            atomicAdd(&ws.qctl[1], 1);
-        }
-        continue;
-    }
+    // what arrives as an argument arrives in vector registers: back to scalar ones
+    const Launch* const L = uniform_ptr(launch);
+    const Args a = uniform_struct(L->a);
+    const Workspace ws = uniform_struct(L->ws);
+    const QueuePlan q = uniform_struct(L->q);
+    const TreeDesc& tree = g_tree;
+    const int task = uniform_i32(task_in), flags = uniform_i32(flags_in);
+    uint4* const lds_t = g_rows;
+    uint4* const lds_d = g_rows + kLdsVecs * kTaskBlock;
+    Team team = uniform_struct(team_io);               // in registers while the task runs
+    bool asked = asked_io;
+    int own_task = -1;
+    const bool leader = team.member == 0;
+    const bool lead = leader && threadIdx.x == 0;     // the one lane that talks to the rest of the launch
+    struct WriteBack {                                 // every way out hands the notes back
+        Team& t_out; Team& t; bool& a_out; bool& a; int& o_out; int& o;
+        __device__ ~WriteBack() { t_out = t; a_out = a; o_out = o; }
+    } write_back{team_io, team, asked_io, asked, own_task_io, own_task};
     // a node task, or the resumed task of the node where the tree branches
     // (tree, node: made scalar explicitly, so that the table lookups below have uniform addresses)
     const bool resumed = task >= a.B * a.N + a.B;
@@ -549,11 +749,19 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(QueuePlan q, Work
     const float k32 = a.k32;
 
     const int k = tree.nchild[n];
-    if (threadIdx.x == 0) atomicAdd(&a.counters[resumed ? MPV_COUNTER_NODE_TASKS_RESUMED : MPV_COUNTER_NODE_TASKS_RUN], 1u);
+    if (lead) atomicAdd(&a.counters[resumed ? MPV_COUNTER_NODE_TASKS_RESUMED : MPV_COUNTER_NODE_TASKS_RUN], 1u);
     const bool split_here = METHOD == MPV_METHOD_TRAVERSAL && a.lazy && !resumed && n == q.split_node;
+    const bool idle_seen = (flags & kFlagIdle) != 0;
 
-    // ---- the children's tokens and this node's starting weight: fetched now, so that
-    //      their latency hides behind the sweep (lane j looks after child j)
+    // ---- the part of the pair this member keeps: every load goes out now
+    RetainedPart<E, kTaskBlock, kRegVecs, kLdsVecs> pair;
+    int tid_l = threadIdx.x;
+    asm volatile("" : "+v"(tid_l));     // per-task copy: nothing derived from it is kept across tasks
+    pair.setup(zt, zd, V, lds_t, lds_d, tid_l, team.member, team.size, q.part_vecs);
+    pair.issue_loads();
+
+    // ---- the children's tokens and uniforms: fetched now, so that their latency hides behind
+    //      the sweep (lane j looks after child j; every member fetches them: they are inputs)
     __shared__ int ch_tok[MPV_MAX_CHILDREN];
     __shared__ float ch_zt[MPV_MAX_CHILDREN], ch_zd[MPV_MAX_CHILDREN];
     __shared__ float ch_u[MPV_MAX_CHILDREN];
@@ -567,90 +775,76 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(QueuePlan q, Work
         if (!a.estimate) pf_u = a.uniforms[bc];
     }
     if (threadIdx.x == kWave && !a.estimate) pf_u = a.uniforms[bn];        // the node's own uniform
-    // are workgroups idle (as of the last round of dispatching)?
-    __shared__ int sh_idle, sh_ahead;
-    int pf_idle = 0;
-    if (threadIdx.x == 0) pf_idle = ld_relaxed(&ws.qctl[4 + 2 * kMaxClasses]);
-
-    // ---- softmax statistics of both rows: the one read of the pair from memory
-    RetainedPair<E, kTaskBlock, RV, LV, CH, FULL> pair;
-    int tid_l = threadIdx.x;
-    asm volatile("" : "+v"(tid_l));     // per-task copy: nothing derived from it is kept across tasks
-    pair.setup(zt, zd, V, lds_t, lds_d, tid_l);
-    pair.issue_register_loads();
     T pf_t = 0, pf_d = 0;       // kept as stored until the sweep is over: touching them now would wait for every load above
     if (pf_x >= 0 && pf_x < V) {
         pf_t = zt[pf_x];
         pf_d = zd[pf_x];
     }
-    // Traversal, only what is needed, and idle workgroups about: an only child's task is queued
+    // Traversal, only what is needed, and idle teams about: an only child's task is queued
     // now, ahead of its starting weight.  It reads its rows while this task reads its own and
     // then finds the weight published (or waits a moment for it), so that a chain of nodes
     // takes little more than one task's time.  If the weight turns out to be 0 it gives up.
-    if (threadIdx.x == 0) {
-        int ahead = 0;
-        if (METHOD == MPV_METHOD_TRAVERSAL && a.lazy && k == 1 && !split_here && pf_idle != 0) {
-            const int cn = tree.child_list[tree.child_off[n]];
-            if (tree.nchild[cn] > 0) {
-                append_task(tree, ws, tree.cls[cn], b * a.N + cn);
-                ahead = 1;
-            }
+    bool child_ahead = false;
+    if (METHOD == MPV_METHOD_TRAVERSAL && a.lazy && k == 1 && !split_here && idle_seen) {
+        const int cn = tree.child_list[tree.child_off[n]];
+        if (tree.nchild[cn] > 0) {
+            child_ahead = true;
+            if (lead) append_task(tree, ws, tree.cls[cn], b * a.N + cn);
         }
-        sh_ahead = ahead;
     }
-    RowStat rt, rd;
+
+    // ---- softmax statistics of both rows: the one read of the pair from memory
+    double At, Ad, wa = 1.0;
     {
         PairStatsRawF<E> f;
         f.t.init(); f.d.init(); f.k32 = k32;
         pair.first_pass(f);
         if (threadIdx.x < k) { ch_tok[threadIdx.x] = pf_x; ch_u[threadIdx.x] = pf_u; ch_zt[threadIdx.x] = E::load_one(&pf_t); ch_zd[threadIdx.x] = E::load_one(&pf_d); }
         if (threadIdx.x == kWave) sh_un = pf_u;
-        if (threadIdx.x == 0) sh_idle = pf_idle;
         if (threadIdx.x == 0) {
             // Traversal: the starting weight comes from the parent's task, which published it
-            // before it queued this task; the two stores may still arrive in either order.
+            // before it queued this task (or publishes it shortly, if this task was queued ahead).
+            // The leader fetches it and passes it on with the statistics.
             double a0 = 1.0;
-            if (METHOD == MPV_METHOD_TRAVERSAL && n != 0) {
+            if (leader && METHOD == MPV_METHOD_TRAVERSAL && n != 0) {
                 // value and "ready" flag are one 64-bit word (a weight is never NaN), read and
                 // written with relaxed device-scope atomics: no fence, no cache invalidation
                 unsigned long long bits = kNotReady;
                 for (int spin = 0; spin < kMaxSpins; ++spin) {
-                    bits = __hip_atomic_load(reinterpret_cast<unsigned long long*>(&ws.a0[bn]), __ATOMIC_RELAXED,
-                                             __HIP_MEMORY_SCOPE_AGENT);
+                    bits = ld_relaxed(reinterpret_cast<const unsigned long long*>(&ws.a0[bn]));
                     if (bits != kNotReady) break;
+                    if (wall_clock64() - team.t_start > kLaunchTimeoutTicks) break;
                     __builtin_amdgcn_s_sleep(32);
                 }
                 if (bits != kNotReady) {
                     a0 = __longlong_as_double(static_cast<long long>(bits));
-                } else {            // cannot happen while blocks are dispatched in index order; never hang
+                } else {            // the parent's task never published it (must never happen): the subtree is written off
                     a0 = 0.0;
                     atomicAdd(&a.counters[MPV_COUNTER_DEPENDENCY_TIMEOUT], 1u);
                 }
             }
             sh_a0 = a0;
         }
-        finish_stats2<kTaskBlock, false>(f.t, f.d, rt, rd, scratch);     // its barriers publish the above
-        rt.A = uniform_f64(rt.A);
-        rd.A = uniform_f64(rd.A);
+        __syncthreads();
+        team_stats(team, f.t, f.d, sh_a0, At, Ad, wa, ws, a);
+        if (METHOD != MPV_METHOD_TRAVERSAL) wa = 1.0;
     }
+    RowStat rt, rd;
+    rt.A = At; rd.A = Ad; rt.m = 0.f; rd.m = 0.f;
 
     // ---- per-child scalars and one residual-mass reduction per child
-    double wa = (METHOD == MPV_METHOD_TRAVERSAL) ? uniform_f64(sh_a0) : 1.0;   // node weight a
-    const bool child_ahead = sh_ahead != 0;
     if (METHOD == MPV_METHOD_TRAVERSAL && a.lazy && n != 0 && !(wa > 0.0)) {
         // queued ahead of its weight, which is 0: the parent has written off the whole subtree.
         // Nothing to do but to pass the news on to an only child queued ahead in turn.
-        if (threadIdx.x == 0) {
+        if (lead) {
             if (child_ahead) {
                 const size_t bc = static_cast<size_t>(b) * a.N + tree.child_list[tree.child_off[n]];
-                __hip_atomic_store(reinterpret_cast<unsigned long long*>(&ws.a0[bc]),
-                                   static_cast<unsigned long long>(__double_as_longlong(0.0)),
-                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                st_relaxed(reinterpret_cast<unsigned long long*>(&ws.a0[bc]), static_cast<unsigned long long>(__double_as_longlong(0.0)));
             }
             wait_memory();
             atomicAdd(&ws.qctl[1], 1);
         }
-        continue;
+        return;
     }
     double c = 0.0, W = 1.0;
     const double kd = static_cast<double>(k32);
@@ -659,8 +853,7 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(QueuePlan q, Work
     int next_node = -1;                               // SpecInfer, only what is needed: the accepted child
     int own_child = -1;                               // Traversal: index of the first child whose task is to be run
     bool paused = false;
-    bool own_given = false;                           // that child's task was queued after all (some workgroup is idle)
-    const bool idle_seen = sh_idle != 0;
+    bool own_given = false;                           // that child's task was queued after all (some team is idle)
     // SpecTr (App. B, Alg. 3): the division factor rho* is the root of
     //   f(rho) = p_acc(rho) - rho beta(rho),  p_acc = 1 - (1 - beta)^k,  beta(rho) = sum_v min(p_v/rho, q_v)
     // on [1, k]; f decreases, f(1) >= 0 >= f(k).  Written with the sums of positive terms
@@ -694,24 +887,26 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(QueuePlan q, Work
                 if (!(cand > lo && cand < hi)) cand = 0.5 * (lo + hi);
                 x = uniform_f64(cand);
             }
-            const ResidualConsts rc = residual_consts(rt.A, rd.A, x);
+            const ResidualConsts rc = cold_residual_consts(rt.A, rd.A, x);
             ResidualMassSlopeRawF<E> f;
             f.init();
             f.k32 = k32; f.nAt = rc.nAt; f.nAd = rc.nAd; f.rho = uniform_f32(rc.rho);
             pair.replay(f);
-            double lane_mass = static_cast<double>(f.acc0) + static_cast<double>(f.acc1);
-            double lane_draft = static_cast<double>(f.q0) + static_cast<double>(f.q1);
-            block_sum2<kTaskBlock>(lane_mass, lane_draft, scratch);
+            double sums[2] = {static_cast<double>(f.acc0) + static_cast<double>(f.acc1),
+                              static_cast<double>(f.q0) + static_cast<double>(f.q1)};
+            block_sum2<kTaskBlock>(sums[0], sums[1], g_sh.scratch);
+            team_sum(team, sums, g_sh.words, ws, a);
             const double scale = uniform_f64(rc.scale);
-            const double Wx = uniform_f64(scale * lane_mass);
-            const double dWx = -uniform_f64(scale * lane_draft) / x;       // the sweep added up rho q over {p > rho q}
+            const double Wx = uniform_f64(scale * sums[0]);
+            const double dWx = -uniform_f64(scale * sums[1]) / x;       // the sweep added up rho q over {p > rho q}
             const double Dx = fmin(fmax((Wx + x - 1.0) / x, 0.0), 1.0);
             const double dDx = (dWx + 1.0 - Dx) / x;
             const double kk = static_cast<double>(k);
-            fx = Wx - pow(Dx, kk);
-            dfx = dWx - kk * pow(Dx, kk - 1.0) * dDx;
+            fx = Wx - int_power(Dx, k);
+            dfx = dWx - kk * int_power(Dx, k - 1) * dDx;
             sp_rho = x;
             sp_W = Wx;
+            if (team.dead) break;
             if (it == 0) {
                 if (!(fx > 0.0)) break;               // the root is 1 (also when k = 1)
             } else {
@@ -722,6 +917,17 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(QueuePlan q, Work
             }
         }
     }
+    // W(c) for one c: a sweep over the part on chip, block sum, team sum
+    auto residual_mass = [&](double cc) __attribute__((always_inline)) -> double {
+        const ResidualConsts rc = cold_residual_consts(rt.A, rd.A, cc);
+        ResidualMassRawF<E> f;
+        f.init();
+        f.k32 = k32; f.nAt = rc.nAt; f.nAd = rc.nAd; f.rho = uniform_f32(rc.rho);
+        pair.replay(f);
+        double sums[1] = {block_sum<kTaskBlock>(static_cast<double>(f.acc0) + static_cast<double>(f.acc1), g_sh.scratch)};
+        team_sum(team, sums, g_sh.words, ws, a);
+        return uniform_f64(uniform_f64(rc.scale) * sums[0]);
+    };
     if (ACCEPT) {
         // Acceptance rate of this node (App. C): the chance that the solver's output is one of k draft
         // tokens drawn i.i.d. from q.  For SpecInfer and SpecTr the part of App. C's formulas that
@@ -734,34 +940,29 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(QueuePlan q, Work
         double alpha;
         if (a.walk == 3) {
             const double D = fmin(fmax((sp_W + sp_rho - 1.0) / sp_rho, 0.0), 1.0);
-            alpha = 1.0 - pow(D, static_cast<double>(k));
+            alpha = 1.0 - int_power(D, k);
         } else if (a.walk == 0) {
             double cc = 0.0, Wc = 1.0;
-            for (int j = 0; j < k && Wc > 0.0; ++j) {
+            for (int j = 0; j < k && Wc > 0.0 && !team.dead; ++j) {
                 cc = uniform_f64(cc + Wc);
-                const ResidualConsts rc = residual_consts(rt.A, rd.A, cc);
-                ResidualMassRawF<E> f;
-                f.init();
-                f.k32 = k32; f.nAt = rc.nAt; f.nAd = rc.nAd; f.rho = uniform_f32(rc.rho);
-                pair.replay(f);
-                const double lane_mass = static_cast<double>(f.acc0) + static_cast<double>(f.acc1);
-                Wc = uniform_f64(uniform_f64(rc.scale) * block_sum<kTaskBlock>(lane_mass, scratch));
+                Wc = residual_mass(cc);
             }
             alpha = 1.0 - Wc;
         } else {
             AcceptanceF<E> f;
             const float At_hi = static_cast<float>(rt.A), Ad_hi = static_cast<float>(rd.A);
-            f.init(k32, -At_hi, -Ad_hi, static_cast<float>(exp2(static_cast<double>(At_hi) - rt.A)),
-                   static_cast<float>(exp2(static_cast<double>(Ad_hi) - rd.A)), a.walk == 1 ? k : k - 1, a.walk == 2);
-            sweep_pair<E, kTaskBlock, kTaskUnroll>(zt, zd, V, f);
-            const double lane_sum = static_cast<double>(f.acc0) + static_cast<double>(f.acc1);
-            alpha = uniform_f64(block_sum<kTaskBlock>(lane_sum, scratch));
+            f.init(k32, -At_hi, -Ad_hi, static_cast<float>(cold_exp2(static_cast<double>(At_hi) - rt.A)),
+                   static_cast<float>(cold_exp2(static_cast<double>(Ad_hi) - rd.A)), a.walk == 1 ? k : k - 1, a.walk == 2);
+            pair.replay(f);
+            double sums[1] = {block_sum<kTaskBlock>(static_cast<double>(f.acc0) + static_cast<double>(f.acc1), g_sh.scratch)};
+            team_sum(team, sums, g_sh.words, ws, a);
+            alpha = uniform_f64(sums[0]);
         }
-        if (threadIdx.x == 0) {
+        if (lead) {
             a.alpha[bn] = static_cast<float>(fmin(fmax(alpha, 0.0), 1.0));
             atomicAdd(&ws.qctl[1], 1);
         }
-        continue;
+        return;
     }
     for (int j = 0; j < k; ++j) {
         // a resumed task repeats the arithmetic of the first child (whose task has long run)
@@ -773,9 +974,9 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(QueuePlan q, Work
         double px = 0.0, qx = 0.0;
         const bool tok_ok = (x >= 0 && x < V);
         if (tok_ok) {
-            px = exp2(static_cast<double>(ch_zt[j]) * kd - rt.A);
-            qx = exp2(static_cast<double>(ch_zd[j]) * kd - rd.A);
-        } else if (threadIdx.x == 0) {
+            px = cold_exp2(static_cast<double>(ch_zt[j]) * kd - rt.A);
+            qx = cold_exp2(static_cast<double>(ch_zd[j]) * kd - rd.A);
+        } else if (lead) {
             atomicAdd(&a.counters[MPV_COUNTER_BAD_TOKEN], 1u);
         }
         const double Px = fmax(px - c * qx, 0.0) / W;     // current distribution at x
@@ -818,27 +1019,25 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(QueuePlan q, Work
         const bool run_child = METHOD == MPV_METHOD_TRAVERSAL && !redone && tree.nchild[cn] > 0 && (w_child > 0.0 || !a.lazy);
         const bool first_to_run = run_child && own_child < 0;
         if (first_to_run) {
-            // kept for this workgroup if it is the last thing this task finds out and nobody is idle
+            // kept for this team if it is the last thing this task finds out and nobody is idle
             own_child = j;
             own_given = (idle_seen || j < k - 1 || child_ahead) && !(split_here && j == 0);
         }
-        // One more sweep to go at most: time to ask for the next task, unless this workgroup
+        // One more sweep to go at most: time to ask for the next task, unless this team
         // already knows what it will run next (a child's task).
-        if (j == k - 1 && !asked && (own_child < 0 || own_given) &&
+        if (leader && j == k - 1 && !asked && (own_child < 0 || own_given) &&
             !(METHOD == MPV_METHOD_SPECINFER && a.lazy && child_accepted && tree.nchild[cn] > 0)) {
-            if (threadIdx.x == 0) request_task(ws);
+            if (threadIdx.x == 0) st_relaxed(&ws.mailbox[team.id], kMailboxSoon);
             asked = true;
         }
-        if (threadIdx.x == 0 && !redone) {
+        if (lead && !redone) {
             if (METHOD == MPV_METHOD_TRAVERSAL) {
                 if (tree.nchild[cn] == 0) {
                     st_shared_f64(&ws.atest[bc], w_child);           // leaves are tested as they are
                 } else {
-                    __hip_atomic_store(reinterpret_cast<unsigned long long*>(&ws.a0[bc]),
-                                       static_cast<unsigned long long>(__double_as_longlong(w_child)),
-                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    // The first child that needs a task is kept for this workgroup (run next,
-                    // no queue) unless some workgroup is idle; every other one is queued now,
+                    st_relaxed(reinterpret_cast<unsigned long long*>(&ws.a0[bc]), static_cast<unsigned long long>(__double_as_longlong(w_child)));
+                    // The first child that needs a task is kept for this team (run next,
+                    // no queue) unless some team is idle; every other one is queued now,
                     // while this task goes on with the sweeps that follow.
                     if (run_child && (!first_to_run || own_given) && !child_ahead) {
                         wait_memory();                    // its starting weight has been written
@@ -859,14 +1058,14 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(QueuePlan q, Work
             }
         }
 
-        // Where the tree branches and no workgroup is to spare, the first child's subtree is
+        // Where the tree branches and no team is to spare, the first child's subtree is
         // explored first: most walks end there, and then nothing else of this node is needed.
         if (split_here && j == 0 && run_child) {
             paused = true;
             break;
         }
 
-        if (METHOD == MPV_METHOD_SPECINFER && a.walk >= 2 && !a.estimate && threadIdx.x == 0 &&
+        if (METHOD == MPV_METHOD_SPECINFER && a.walk >= 2 && !a.estimate && lead &&
             fabs(w_child - static_cast<double>(ch_u[j])) < 1e-6)
             atomicAdd(&a.counters[MPV_COUNTER_NEAR_TIE_ACCEPT], 1u);     // (the other rules count these in their walk)
         // SpecInfer moves into the first child it accepts: later children and this node's
@@ -891,15 +1090,9 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(QueuePlan q, Work
         // ---- the child (SpecInfer) or its whole subtree (Traversal) is rejected:
         //      P <- norm (a P - q)_+ ,  i.e.  c <- c + W/a ,  W <- W(c)
         if (METHOD == MPV_METHOD_TRAVERSAL && !(wa > 0.0)) continue;   // (0*P - q)_+ = 0: nothing changes
+        if (team.dead) break;
         const double c2 = uniform_f64(c + W / wa);
-        const ResidualConsts rc = residual_consts(rt.A, rd.A, c2);
-        const double scale = uniform_f64(rc.scale);
-        ResidualMassRawF<E> f;
-        f.init();
-        f.k32 = k32; f.nAt = rc.nAt; f.nAd = rc.nAd; f.rho = uniform_f32(rc.rho);
-        pair.replay(f);
-        const double lane_mass = static_cast<double>(f.acc0) + static_cast<double>(f.acc1);
-        const double W2 = uniform_f64(scale * block_sum<kTaskBlock>(lane_mass, scratch));
+        const double W2 = residual_mass(c2);
         if (W2 > 0.0) {
             if (METHOD == MPV_METHOD_TRAVERSAL) {
                 const double S = (wa / W) * W2;
@@ -909,7 +1102,7 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(QueuePlan q, Work
             W = W2;
         } else {
             if (METHOD == MPV_METHOD_TRAVERSAL) wa = (wa >= 1.0) ? 1.0 : 0.0;
-            if (threadIdx.x == 0) atomicAdd(&a.counters[MPV_COUNTER_ZERO_MASS], 1u);
+            if (lead) atomicAdd(&a.counters[MPV_COUNTER_ZERO_MASS], 1u);
         }
         if (METHOD == MPV_METHOD_SPECINFER && a.walk == 2) {
             // Naive, estimate (App. D, Naive Branching): p_res(x_i) for every child, p_res = norm (p - q)_+
@@ -919,10 +1112,10 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(QueuePlan q, Work
                 const int xi = ch_tok[i];
                 double r = 0.0;
                 if (xi >= 0 && xi < V)
-                    r = fmax(exp2(static_cast<double>(ch_zt[i]) * kd - rt.A) - c * exp2(static_cast<double>(ch_zd[i]) * kd - rd.A), 0.0) / W;
-                else if (i > 0 && threadIdx.x == 0)
+                    r = fmax(cold_exp2(static_cast<double>(ch_zt[i]) * kd - rt.A) - c * cold_exp2(static_cast<double>(ch_zd[i]) * kd - rd.A), 0.0) / W;
+                else if (i > 0 && lead)
                     atomicAdd(&a.counters[MPV_COUNTER_BAD_TOKEN], 1u);
-                if (threadIdx.x == 0) {
+                if (lead) {
                     st_shared_f64(&ws.aux[static_cast<size_t>(b) * a.N + ci], r);
                     if (i > 0) st_shared_f64(&ws.atest[static_cast<size_t>(b) * a.N + ci], 0.0);   // never tested
                 }
@@ -932,15 +1125,17 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(QueuePlan q, Work
         }
     }
 
+    // ---- what follows from this task: the leader's business
+    if (!leader) return;
     if (paused) {
-        // nothing is settled yet; the first child's task is run next by this workgroup
+        // nothing is settled yet; the first child's task is run next by this team
         own_task = b * a.N + tree.child_list[tree.child_off[n]];
         if (threadIdx.x == 0) {
             (void)atomicAdd(&ws.qctl[0], 1);
             wait_memory();                            // counted (and the child's weight written) before this task counts as finished
             atomicAdd(&ws.qctl[1], 1);
         }
-        continue;
+        return;
     }
     __shared__ int sh_push_sample, sh_settled, sh_resume;
     if (threadIdx.x == 0) {
@@ -1003,7 +1198,7 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(QueuePlan q, Work
         sh_resume = resume ? 1 : 0;
     }
     __syncthreads();
-    // What follows from this task.  One task is run by this workgroup itself, next (no queue,
+    // What follows from this task.  One task is run by this team itself, next (no queue,
     // no waiting): the sampling if this task settled the tree, else the first child that needs
     // its own task (Traversal) or the accepted child (SpecInfer).  The other children are queued.
     if (sh_push_sample) {
@@ -1028,13 +1223,141 @@ __global__ __launch_bounds__(kTaskBlock) void node_task_kernel(QueuePlan q, Work
     }
     __syncthreads();                                  // every new task has been counted
     if (threadIdx.x == 0) atomicAdd(&ws.qctl[1], 1);
+}
+
+template <class E, int KIND>
+__global__ __launch_bounds__(kTaskBlock) __attribute__((amdgpu_waves_per_eu(4, 4)))
+void node_task_kernel(const Launch* __restrict__ launch) {
+    // KIND: MPV_METHOD_SPECINFER (all top-down rules) or MPV_METHOD_TRAVERSAL, or kKindAcceptance: the
+    // top-down kernel reduced to what the acceptance rates need (an instantiation of its own, so that
+    // its extra sweeps do not weigh on the register allocation of the verification kernels)
+    constexpr bool ACCEPT = KIND == kKindAcceptance;
+    constexpr int METHOD = ACCEPT ? MPV_METHOD_SPECINFER : KIND;
+    const QueuePlan& q = launch->q;
+    const Workspace& ws = launch->ws;
+    const Args& a = launch->a;
+
+    __shared__ int sh_task, sh_flags;
+    // The tree tables are read from LDS, copied there from the workspace (init_kernel put them
+    // there): a table that is indexed with a value the compiler keeps in a vector register
+    // would otherwise be copied, whole, into every lane's private memory.
+    for (int w = threadIdx.x; w < static_cast<int>(sizeof(TreeDesc) / sizeof(int)); w += kTaskBlock)
+        reinterpret_cast<int*>(&g_tree)[w] = reinterpret_cast<const int*>(ws.tree)[w];
+    const TreeDesc& tree = g_tree;                // the task loop starts with a barrier
+
+    // ---- this workgroup's place in its team
+    Team team;
+    team.size = q.team_size;
+    {
+        const int i = static_cast<int>(blockIdx.x);
+        if (q.same_xcd) {                         // workgroup i runs on chiplet i % 8: keep a team on one
+            const int r = i / 8;
+            team.id = (i % 8) + 8 * (r / team.size);
+            team.member = r % team.size;
+        } else {
+            team.id = i / team.size;
+            team.member = i % team.size;
+        }
+    }
+    team.seq = 0u; team.tseq = 0u; team.dead = 0;
+    team.area = ws.exch + static_cast<size_t>(team.id) * 2 * team.size * kExchWords;
+    team.task_word = ws.team_task + static_cast<size_t>(team.id) * 2;
+    team.t_start = wall_clock64();
+    const bool leader = team.member == 0;
+    if (threadIdx.x == 0) {
+        // the last member to arrive opens the team's mailbox: from then on the dispatcher may hand it tasks
+        const int n_arrived = atomicAdd(&ws.arrived[team.id], 1) + 1;
+        if (n_arrived == team.size) st_relaxed(&ws.mailbox[team.id], kMailboxWaiting);
+    }
+
+    const bool drop_settled = METHOD == MPV_METHOD_TRAVERSAL && a.lazy != 0;
+    int previous_task = -4;                           // last task taken from the mailbox: none yet
+    bool asked = true;                                // the team starts out waiting
+    int own_task = -1;                                // a task this team produced for itself
+    for (;;) {
+    __syncthreads();                                  // the previous task is done with LDS
+    if (team.dead) break;
+    int task, flags = 0;
+    if (leader) {
+        bool from_queue = false;
+        if (own_task >= 0) {
+            task = own_task;
+            own_task = -1;
+        } else {
+            if (threadIdx.x < kWave) {
+                if (!asked) {
+                    if (threadIdx.x == 0) st_relaxed(&ws.mailbox[team.id], kMailboxWaiting);
+                    wait_memory();
+                }
+                const int t = acquire_task(launch, team.id, previous_task, drop_settled, team.t_start);
+                if (threadIdx.x == 0) sh_task = t;
+            }
+            __syncthreads();
+            task = sh_task;
+            previous_task = task;
+            asked = false;
+            from_queue = true;
+        }
+        (void)from_queue;
+        // are teams idle (as of the last round of dispatching)?
+        if (threadIdx.x == 0) sh_flags = ld_relaxed(&ws.qctl[4 + 2 * kMaxClasses]) != 0 ? kFlagIdle : 0;
+        __syncthreads();
+        flags = sh_flags;
+        // tasks without any V-wide work are the leader's alone; everything else is announced
+        const bool solo = task != kTaskExit && task >= a.B * a.N && task < a.B * a.N + a.B && (ACCEPT || a.estimate);
+        if (!solo && threadIdx.x < kWave) team_announce(team, task, flags);
+        if (solo) {
+            if (!ACCEPT && threadIdx.x < kWave) estimate_wave<METHOD>(tree, ws, a, task - a.B * a.N);
+            if (threadIdx.x == 0) {
+                wait_memory();
+                atomicAdd(&ws.qctl[1], 1);
+            }
+            continue;
+        }
+        if (!(threadIdx.x < kWave)) team.tseq++;      // (the first wave counted it in team_announce)
+    } else {
+        if (threadIdx.x < kWave) {
+            int f = 0;
+            const int t = team_listen(team, f, ws);
+            if (threadIdx.x == 0) { sh_task = t; sh_flags = f; }
+        } else {
+            team.tseq++;
+        }
+        __syncthreads();
+        task = sh_task;
+        flags = sh_flags;
+    }
+    if (task == kTaskExit) break;
+    task = __builtin_amdgcn_readfirstlane(task);
+    flags = __builtin_amdgcn_readfirstlane(flags);
+    const bool lead = leader && threadIdx.x == 0;     // the one lane that talks to the rest of the launch
+    if (task >= a.B * a.N && task < a.B * a.N + a.B) {
+        // the tree's outcome is settled: walk and bonus token
+        if (leader && !asked) {
+            if (threadIdx.x == 0) st_relaxed(&ws.mailbox[team.id], kMailboxSoon);
+            asked = true;
+        }
+        const int next = sample_task<E, METHOD>(launch, team, task - a.B * a.N);
+        if (leader) {
+            if (next >= 0) own_task = next;           // a token-following walk goes on
+            if (threadIdx.x == 0) {
+                if (next >= 0) {
+                    (void)atomicAdd(&ws.qctl[0], 1);
+                    wait_memory();                    // counted (and the walk's position written) first
+                }
+                atomicAdd(&ws.qctl[1], 1);
+            }
+        }
+        continue;
+    }
+    run_node_task<E, KIND>(launch, team, task, flags, asked, own_task);
     }   // task loop
 }
 
 // ------------------------------------------------------------------ walk
 //
-// The uniform-dependent part of SpecInfer and Traversal, run by the first wave of the sampling
-// workgroup: lane n compares u[n] with the probability node n is tested with
+// The uniform-dependent part of SpecInfer and Traversal, run by the first wave of every member of
+// the sampling team (they all need the stopping node; the leader records the path): lane n compares u[n] with the probability node n is tested with
 // (which does not depend on the uniforms), the 64 outcomes become a bit mask, and
 // the walk itself is a few scalar steps over that mask.
 //   SpecInfer (Sec. 3.2 walk + App. B Alg. 4): from the root, move to the first
@@ -1057,7 +1380,7 @@ __device__ __forceinline__ void write_path(const TreeDesc& tree, const Args& a, 
 }
 
 template <int METHOD>
-__device__ __forceinline__ int walk_wave(const TreeDesc& tree, const Workspace& ws, const Args& a, int b) {
+__device__ __forceinline__ int walk_wave(const TreeDesc& tree, const Workspace& ws, const Args& a, int b, bool record) {
     const int lane = threadIdx.x & (kWave - 1);
     const size_t base = static_cast<size_t>(b) * a.N;
     bool acc = false, near = false;
@@ -1066,9 +1389,9 @@ __device__ __forceinline__ int walk_wave(const TreeDesc& tree, const Workspace& 
         const double uu = static_cast<double>(a.uniforms[base + lane]);
         acc = uu < at;
         near = fabs(at - uu) < 1e-6;
-        if (a.dbg_accept) a.dbg_accept[base + lane] = static_cast<float>(at);
+        if (a.dbg_accept && record) a.dbg_accept[base + lane] = static_cast<float>(at);
     }
-    if (lane == 0 && a.dbg_accept) a.dbg_accept[base] = 1.f;
+    if (lane == 0 && a.dbg_accept && record) a.dbg_accept[base] = 1.f;
     const unsigned long long accm = __ballot(acc);
     const unsigned long long nearm = __ballot(near);
     unsigned long long tested = 0ull;
@@ -1094,7 +1417,7 @@ __device__ __forceinline__ int walk_wave(const TreeDesc& tree, const Workspace& 
             if ((accm >> n) & 1ull) { stop = n; break; }
         }
     }
-    if (lane == 0) {
+    if (lane == 0 && record) {
         write_path(tree, a, b, stop);
         const int nn = __popcll(nearm & tested);
         if (nn) atomicAdd(&a.counters[MPV_COUNTER_NEAR_TIE_ACCEPT], static_cast<unsigned>(nn));
@@ -1224,24 +1547,39 @@ struct ResidualTile {
 };
 
 
-// tile_sum: kMaxTiles floats of LDS; scratch: 2 doubles per wave.  Everything it reads from
-// the workspace was written by node tasks of this launch (see st_shared_f64).
+// tile_sum: kMaxTiles floats of LDS.  Everything it reads from the workspace was written by node
+// tasks of this launch (see st_shared_f64) before the task that started this one was announced.
+// The vocabulary is split among the members in runs of whole wave tiles, in member order; each
+// member adds up the masses of its tiles, one exchange gives everybody every member's total, and
+// the member whose run contains u * R finds the token.
 template <class E, int METHOD>
-__device__ __forceinline__ int sample_task(const TreeDesc& tree, const Workspace& ws, const Args& a, int b,
-                           float* tile_sum, double* scratch) {
+__device__ __attribute__((noinline)) int sample_task(const Launch* launch, Team& team_io, int b_in) {
     using T = typename E::T;
-    constexpr int NW = kSampleBlock / kWave;
+    const Launch* const L = uniform_ptr(launch);
+    const Args a = uniform_struct(L->a);
+    const Workspace ws = uniform_struct(L->ws);
+    const TreeDesc& tree = g_tree;
+    const int b = uniform_i32(b_in);
+    float* const tile_sum = reinterpret_cast<float*>(g_rows);
+    Team team = uniform_struct(team_io);
+    struct WriteBack {
+        Team& t_out; Team& t;
+        __device__ ~WriteBack() { t_out = t; }
+    } write_back{team_io, team};
+    constexpr int NW = kTaskWaves;
     constexpr int PER_LANE = ResidualTile<E>::PER_LANE;
     constexpr int TILE = ResidualTile<E>::TILE;
     __shared__ int sh_tile;
-    __shared__ double sh_before, sh_total, sh_target;
+    __shared__ double sh_before, sh_local_total;
 
     __shared__ int sh_stop, sh_next;
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    const bool leader = team.member == 0;
+    const bool lead = leader && threadIdx.x == 0;
     if (wave == 0) {
         // where the token is drawn: the node the rule stops in, or the node a token-following
         // walk has reached
-        const int stop = a.walk ? ld_relaxed(&ws.cur[b]) : walk_wave<METHOD>(tree, ws, a, b);
+        const int stop = a.walk ? ld_relaxed(&ws.cur[b]) : walk_wave<METHOD>(tree, ws, a, b, leader);
         if (lane == 0) { sh_stop = stop; sh_next = -1; }
     }
     __syncthreads();
@@ -1251,18 +1589,22 @@ __device__ __forceinline__ int sample_task(const TreeDesc& tree, const Workspace
     const T* zd = static_cast<const T*>(a.zd) + bn * a.V;
     const int V = a.V;
     const int ntiles = (V + TILE - 1) / TILE;
+    // this member's run of tiles
+    const int per = (ntiles + team.size - 1) / team.size;
+    const int t_lo = min(team.member * per, ntiles), t_hi = min(t_lo + per, ntiles);
+    const int my_tiles = t_hi - t_lo;
 
     double At, Ad = 0.0, c = 0.0;
     if (tree.nchild[n] == 0 || a.walk == 1) {
         // a leaf (its target row has not been touched yet) or an NSS draw: from p itself
         RowStatsF<E> f;
         f.t.init(); f.k32 = a.k32;
-        sweep_row<E, kSampleBlock, 4 * kTaskUnroll>(zt, V, f);     // alone on its compute unit: many loads in flight
+        const int e_lo = t_lo * TILE, e_hi = min(V, t_hi * TILE);
+        if (e_hi > e_lo) sweep_row<E, kTaskBlock, 2 * kTaskUnroll>(zt + e_lo, e_hi - e_lo, f);
         OnlineLse none; none.init();
-        RowStat rt, rd;
-        finish_stats2<kSampleBlock>(f.t, none, rt, rd, scratch);
-        At = rt.A;
-        if (threadIdx.x == 0) ws.At[bn] = rt.A;
+        double unused_d, unused_a0;
+        team_stats(team, f.t, none, 0.0, At, unused_d, unused_a0, ws, a);
+        if (lead) ws.At[bn] = At;
     } else {
         At = ld_shared_f64(&ws.At[bn]);
         Ad = ld_shared_f64(&ws.Ad[bn]);
@@ -1281,14 +1623,14 @@ __device__ __forceinline__ int sample_task(const TreeDesc& tree, const Workspace
         rt_.nAt = -static_cast<float>(At); rt_.nAd = 0.f; rt_.rho = 0.f;
     }
 
-    // ---- pass 1: mass of every wave tile, in vocabulary order
+    // ---- pass 1: mass of every wave tile of this member's run, in vocabulary order
+    //      (tile_sum[i] belongs to tile t_lo + i)
     {
         // Whole, aligned tiles are taken U at a time per wave with all their loads issued
-        // before the first use: one workgroup per compute unit hides memory latency only by
-        // the loads each wave keeps in flight.
-        int t_next = wave;
+        // before the first use.
+        int t_next = t_lo + wave;
         constexpr int U = 8;
-        const int whole = rt_.aligned ? V / TILE : 0;
+        const int whole = min(rt_.aligned ? V / TILE : 0, t_hi);
         for (; t_next + (U - 1) * NW < whole; t_next += U * NW) {
             uint4 qt[U], qd[U];
 #pragma unroll
@@ -1312,100 +1654,138 @@ __device__ __forceinline__ int sample_task(const TreeDesc& tree, const Workspace
             for (int j = 0; j < U; ++j) s[j] = wave_sum_f32(s[j]);
             if (lane == 0) {
 #pragma unroll
-                for (int j = 0; j < U; ++j) tile_sum[t_next + j * NW] = s[j];
+                for (int j = 0; j < U; ++j) tile_sum[t_next + j * NW - t_lo] = s[j];
             }
         }
-        for (int t = t_next; t < ntiles; t += NW) {
+        for (int t = t_next; t < t_hi; t += NW) {
             float r[PER_LANE];
             rt_.load(t, lane, r);
             float ls = 0.f;
 #pragma unroll
             for (int i = 0; i < PER_LANE; ++i) ls += r[i];
             const float w = wave_sum_f32(ls);
-            if (lane == 0) tile_sum[t] = w;
+            if (lane == 0) tile_sum[t - t_lo] = w;
         }
     }
     __syncthreads();
 
-    // ---- locate the tile that contains u * R (wave 0; each lane owns a run of tiles)
+    // ---- this member's total (wave 0; each lane owns a run of the member's tiles), then everybody's
+    const int per_lane_tiles = (my_tiles + kWave - 1) / kWave;
+    const int l0 = min(lane * per_lane_tiles, my_tiles), l1 = min(l0 + per_lane_tiles, my_tiles);
+    double run = 0.0, incl = 0.0;
     if (wave == 0) {
-        const int per = (ntiles + kWave - 1) / kWave;
-        const int t0 = lane * per, t1 = min(t0 + per, ntiles);
-        double run = 0.0;
-        for (int t = t0; t < t1; ++t) run += tile_sum[t];
-        const double incl = wave_inclusive_scan(run);
-        const double total = __shfl(incl, kWave - 1, kWave);
-        const float u_draw = a.walk ? a.draw_uniforms[bn] : a.uniforms[static_cast<size_t>(b) * a.N];
-        const double target = static_cast<double>(u_draw) * total;
-        const unsigned long long hit = __ballot(incl > target && run > 0.0);
-        int owner = hit ? (__ffsll(static_cast<long long>(hit)) - 1) : -1;
-        if (owner < 0) {           // rounding only: last lane that has mass
-            const unsigned long long any = __ballot(run > 0.0);
-            owner = any ? (63 - __clzll(static_cast<long long>(any))) : 0;
+        for (int t = l0; t < l1; ++t) run += tile_sum[t];
+        incl = wave_inclusive_scan(run);
+        if (lane == kWave - 1) sh_local_total = incl;
+    }
+    __syncthreads();
+    const double local_total = sh_local_total;
+    {
+        unsigned mine = 0u;
+        if (threadIdx.x == 0) mine = half_of(local_total, 0);
+        if (threadIdx.x == 1) mine = half_of(local_total, 1);
+        team_exchange(team, mine, g_sh.words, ws, a);
+    }
+    double total = 0.0, before = 0.0;
+    for (int m = 0; m < team.size; ++m) {
+        if (m == team.member) before = total;
+        total += double_at(g_sh.words, m, 0);
+    }
+    const float u_draw = a.walk ? a.draw_uniforms[bn] : a.uniforms[static_cast<size_t>(b) * a.N];
+    const double target = static_cast<double>(u_draw) * total;
+    // the member whose run contains the target: the first whose running total exceeds it and that
+    // has mass; rounding only: the last one that has mass
+    int owner = -1, last_mass = 0;
+    {
+        double acc = 0.0;
+        for (int m = 0; m < team.size; ++m) {
+            const double tm = double_at(g_sh.words, m, 0);
+            if (tm > 0.0) last_mass = m;
+            if (owner < 0 && tm > 0.0 && acc + tm > target) owner = m;
+            acc += tm;
         }
-        if (lane == owner) {
+        if (owner < 0) owner = last_mass;
+    }
+    const bool mine_it = owner == team.member;
+    const double local_target = target - before;
+
+    // ---- the owner locates the tile that contains the target (wave 0) ...
+    if (mine_it && wave == 0) {
+        const unsigned long long hit = __ballot(incl > local_target && run > 0.0);
+        int lane_owner = hit ? (__ffsll(static_cast<long long>(hit)) - 1) : -1;
+        if (lane_owner < 0) {           // rounding only: last lane that has mass
+            const unsigned long long any = __ballot(run > 0.0);
+            lane_owner = any ? (63 - __clzll(static_cast<long long>(any))) : 0;
+        }
+        if (lane == lane_owner) {
             double acc = incl - run;
-            int found = -1, last_mass = t0;
-            double before = acc;
-            for (int t = t0; t < t1; ++t) {
+            int found = -1, last = l0;
+            double bef = acc;
+            for (int t = l0; t < l1; ++t) {
                 const double ts = tile_sum[t];
-                if (ts > 0.0) last_mass = t;
-                if (found < 0 && acc + ts > target && ts > 0.0) { found = t; before = acc; }
+                if (ts > 0.0) last = t;
+                if (found < 0 && acc + ts > local_target && ts > 0.0) { found = t; bef = acc; }
                 acc += ts;
             }
             if (found < 0) {       // rounding only: last tile of the run that has mass
-                found = last_mass;
-                before = incl - run;
-                for (int t = t0; t < last_mass; ++t) before += tile_sum[t];
+                found = last;
+                bef = incl - run;
+                for (int t = l0; t < last; ++t) bef += tile_sum[t];
             }
-            sh_tile = found;
-            sh_before = before;
-            sh_total = total;
-            sh_target = target;
+            sh_tile = t_lo + found;
+            sh_before = bef;
         }
     }
     __syncthreads();
 
-    // ---- pass 2: inside that tile (wave 0)
-    if (wave == 0) {
+    // ---- ... and the token inside that tile (wave 0)
+    int tok = 0;
+    if (mine_it && wave == 0) {
         const int t = sh_tile;
-        const double rem = sh_target - sh_before;       // mass to cover inside the tile
+        const double rem = local_target - sh_before;       // mass to cover inside the tile
         float r[PER_LANE];
         rt_.load(t, lane, r);
         float ls = 0.f;
 #pragma unroll
         for (int i = 0; i < PER_LANE; ++i) ls += r[i];
         const double lsd = static_cast<double>(ls);
-        const double incl = wave_inclusive_scan(lsd);
-        const unsigned long long hit = __ballot(incl > rem && ls > 0.f);
-        int owner = hit ? (__ffsll(static_cast<long long>(hit)) - 1) : -1;
-        if (owner < 0) {
+        const double incl2 = wave_inclusive_scan(lsd);
+        const unsigned long long hit = __ballot(incl2 > rem && ls > 0.f);
+        int lane_owner = hit ? (__ffsll(static_cast<long long>(hit)) - 1) : -1;
+        if (lane_owner < 0) {
             const unsigned long long any = __ballot(ls > 0.f);
-            owner = any ? (63 - __clzll(static_cast<long long>(any))) : 0;
+            lane_owner = any ? (63 - __clzll(static_cast<long long>(any))) : 0;
         }
-        if (lane == owner) {
-            double acc = incl - lsd;
-            int found = -1, last_mass = 0;
+        if (lane == lane_owner) {
+            double acc = incl2 - lsd;
+            int found = -1, last = 0;
             double lo = acc, hi = acc;
             for (int i = 0; i < PER_LANE; ++i) {
                 const double ri = static_cast<double>(r[i]);
-                if (ri > 0.0) last_mass = i;
+                if (ri > 0.0) last = i;
                 if (found < 0 && ri > 0.0 && acc + ri > rem) { found = i; lo = acc; hi = acc + ri; }
                 acc += ri;
             }
-            if (found < 0) { found = last_mass; lo = rem; hi = rem; }
-            int tok = t * TILE + lane * PER_LANE + found;
-            if (tok >= V) tok = V - 1;
-            a.bonus[b] = tok;
-            sh_tile = tok;                            // (the tile number is no longer needed)
+            if (found < 0) { found = last; lo = rem; hi = rem; }
+            int tk = t * TILE + lane * PER_LANE + found;
+            if (tk >= V) tk = V - 1;
+            a.bonus[b] = tk;
+            sh_tile = tk;                             // (the tile number is no longer needed)
             const double gap = fmin(fabs(rem - lo), fabs(hi - rem));
-            if (gap < 1e-6 * sh_total) atomicAdd(&a.counters[MPV_COUNTER_NEAR_TIE_BONUS], 1u);
+            if (gap < 1e-6 * total) atomicAdd(&a.counters[MPV_COUNTER_NEAR_TIE_BONUS], 1u);
         }
-        if (a.walk) {
-            // Sec. 3.2: if the drawn token is a child's token the walk moves to that child (the
-            // first such child in list order), otherwise it ends here
-            __builtin_amdgcn_wave_barrier();
-            const int tok = *reinterpret_cast<volatile int*>(&sh_tile);
+    }
+    if (a.walk) {
+        // Sec. 3.2: if the drawn token is a child's token the walk moves to that child (the
+        // first such child in list order), otherwise it ends here.  Everybody needs the token.
+        __syncthreads();
+        {
+            unsigned mine = 0u;
+            if (threadIdx.x == 0 && mine_it) mine = static_cast<unsigned>(sh_tile);
+            team_exchange(team, mine, g_sh.words, ws, a);
+        }
+        tok = static_cast<int>(g_sh.words[owner * kExchWords]);
+        if (wave == 0) {
             const int k = tree.nchild[n];
             bool same = false;
             if (lane < k) same = a.tokens[static_cast<size_t>(b) * a.N + tree.child_list[tree.child_off[n] + lane]] == tok;
@@ -1413,11 +1793,11 @@ __device__ __forceinline__ int sample_task(const TreeDesc& tree, const Workspace
             if (m) {
                 const int to = tree.child_list[tree.child_off[n] + __ffsll(static_cast<long long>(m)) - 1];
                 if (lane == 0) {
-                    st_relaxed(&ws.cur[b], to);
+                    if (leader) st_relaxed(&ws.cur[b], to);
                     // Naive and SpecTr test children of an inner node before they draw there; NSS and leaves draw at once
                     sh_next = (a.walk >= 2 && tree.nchild[to] > 0) ? b * a.N + to : a.B * a.N + b;
                 }
-            } else {
+            } else if (leader) {
                 if (lane == 0) write_path(tree, a, b, n);
                 if (a.dbg_accept && lane < a.N)
                     a.dbg_accept[static_cast<size_t>(b) * a.N + lane] =
@@ -1428,9 +1808,9 @@ __device__ __forceinline__ int sample_task(const TreeDesc& tree, const Workspace
 
     // ---- optional: the normalised distribution itself
     if (a.dbg_resid) {
-        const double inv = 1.0 / sh_total;
+        const double inv = 1.0 / total;
         float* out = a.dbg_resid + static_cast<size_t>(b) * V;
-        for (int t = wave; t < ntiles; t += NW) {
+        for (int t = t_lo + wave; t < t_hi; t += NW) {
             float r[PER_LANE];
             rt_.load(t, lane, r);
 #pragma unroll
@@ -1633,12 +2013,17 @@ static size_t carve(const mpv_problem* p, void* base, Workspace* ws) {
     double* at = static_cast<double*>(take(bn * 8));
     int32_t* qu = static_cast<int32_t*>(take(bn * 4));
     int32_t* qc = static_cast<int32_t*>(take((5 + 2 * kMaxClasses) * 4));
-    int32_t* mb = static_cast<int32_t*>(take(kMaxWorkgroups * 4));
+    int32_t* mb = static_cast<int32_t*>(take(kMaxTeams * 4));
     unsigned long long* kn = static_cast<unsigned long long*>(take(static_cast<size_t>(p->B) * 8));
     unsigned long long* ac = static_cast<unsigned long long*>(take(static_cast<size_t>(p->B) * 8));
     int32_t* de = static_cast<int32_t*>(take(static_cast<size_t>(p->B) * 4));
     int32_t* cu = static_cast<int32_t*>(take(static_cast<size_t>(p->B) * 4));
     TreeDesc* tr = static_cast<TreeDesc*>(take(sizeof(TreeDesc)));
+    unsigned long long* ex = static_cast<unsigned long long*>(take(static_cast<size_t>(kMaxGrid) * 2 * kExchWords * 8));
+    unsigned long long* tt = static_cast<unsigned long long*>(take(static_cast<size_t>(kMaxTeams) * 2 * 8));
+    int32_t* ar = static_cast<int32_t*>(take(kMaxTeams * 4));
+    Launch* la = static_cast<Launch*>(take(sizeof(Launch)));
+    if (ws) { ws->exch = ex; ws->team_task = tt; ws->arrived = ar; ws->launch = la; }
     if (ws) { ws->At = At; ws->Ad = Ad; ws->cfin = cf; ws->aux = ax; ws->a0 = a0; ws->atest = at; ws->queue = qu; ws->qctl = qc; ws->mailbox = mb; ws->known = kn; ws->acc = ac; ws->decided = de; ws->cur = cu; ws->tree = tr; }
     return off < 256 ? 256 : off;
 }
@@ -1656,23 +2041,36 @@ static int compute_units() {
     return cus;
 }
 
-// Start-up spread of the persistent workgroups (Args::stagger_ticks): about the time one
-// workgroup needs to read a row pair when every compute unit is reading (its share of
-// ~6.3 TB/s), only for rows long enough to be kept on chip (short rows finish before it
-// would matter).
-static int32_t stagger_ticks(const mpv_problem* p) {
-    const double pair_bytes = 2.0 * p->V * (p->logit_dtype == MPV_DTYPE_F32 ? 4 : 2);
-    const double share_bytes_per_us = 6.3e6 / compute_units();
-    const double us = pair_bytes / share_bytes_per_us;
-    return (pair_bytes >= 400e3) ? static_cast<int32_t>(us * 100.0 / 8.0) : 0;
+// How a launch is shaped: G workgroups per team so that a member's part of a row fits on chip
+// (a power of two, kMaxTeam at most: beyond that the rest of a part is re-read in every sweep),
+// as many teams as there can be tasks at once, four workgroups per compute unit at most.
+struct Shape { int team_size, teams, part_vecs, same_xcd; };
+
+template <class E>
+static Shape launch_shape(const mpv_problem* p, int tasks) {
+    Shape s;
+    const int nvec = (p->V + E::VEC - 1) / E::VEC;
+    int g = 1;
+    while (g < kMaxTeam && static_cast<long long>(g) * kPartCapacity < nvec) g *= 2;
+    const int slots = 4 * compute_units() < kMaxGrid ? 4 * compute_units() : kMaxGrid;      // workgroups that can be resident
+    int teams = slots / g;
+    if (teams > kMaxTeams) teams = kMaxTeams;
+    if (teams > tasks) teams = tasks;
+    if (teams < 1) teams = 1;
+    // workgroup i runs on chiplet i % 8: with a multiple of 8 teams every team can stay on one chiplet
+    s.same_xcd = (g > 1 && teams >= 8) ? 1 : 0;
+    if (s.same_xcd) teams -= teams % 8;
+    s.team_size = g;
+    s.teams = teams;
+    const int tiles = (nvec + kWave - 1) / kWave;                 // wave tiles of 64 vectors
+    s.part_vecs = ((tiles + g - 1) / g) * kWave;
+    return s;
 }
 
 template <class E>
 static int launch_all(const mpv_problem* p, const Plan& plan, const Workspace& ws, const Args& a, hipStream_t s) {
     TreeDesc tree = plan.tree;
     (void)hipGetLastError();    // a stale error left by the caller's own HIP calls is not ours
-    // every register and LDS slot of a node task is populated whatever the row's alignment
-    const bool full = (p->V - (E::VEC - 1)) / E::VEC >= (kRegVecs + kLdsVecs) * kTaskBlock;
     // Queue layout and initial tasks.  Computing only what is needed, both rules start from the
     // root: SpecInfer queues the accepted child, Traversal the children of positive weight.
     // Computing everything (debug outputs), SpecInfer's node tasks are independent and all
@@ -1703,12 +2101,13 @@ static int launch_all(const mpv_problem* p, const Plan& plan, const Workspace& w
     }
     for (int c = 0; c <= q.nclass; ++c) tree.class_off[c] = q.off[c];
     const int tasks = q.off[q.nclass];
-    // about one workgroup per compute unit (a node task fills one); fewer if there is less to do
-    int wgs = tasks < compute_units() ? tasks : compute_units();
-    if (wgs > kMaxWorkgroups) wgs = kMaxWorkgroups;
-    q.workers = wgs;
+    const Shape shape = launch_shape<E>(p, tasks);
+    q.teams = shape.teams;
+    q.team_size = shape.team_size;
+    q.part_vecs = shape.part_vecs;
+    q.same_xcd = shape.same_xcd;
     q.split_node = -1;
-    if (p->method == MPV_METHOD_TRAVERSAL && a.lazy && p->B >= wgs) {
+    if (p->method == MPV_METHOD_TRAVERSAL && a.lazy && p->B >= q.teams) {
         int branch = 0;
         while (tree.nchild[branch] == 1) branch = tree.child_list[tree.child_off[branch]];
         if (tree.nchild[branch] >= 2) {
@@ -1727,16 +2126,13 @@ static int launch_all(const mpv_problem* p, const Plan& plan, const Workspace& w
         launch(MPV_KERNEL_INIT, init_kernel, dim3(blocks, p->N), dim3(threads), s, q, tree, ws, a);
     }
     if (tasks > 0) {
-        const dim3 grid(static_cast<unsigned>(wgs)), block(kTaskBlock);
+        const dim3 grid(static_cast<unsigned>(q.teams * q.team_size)), block(kTaskBlock);
         if (a.estimate == 2) {
-            if (full) launch(MPV_KERNEL_NODE_TASK, node_task_kernel<E, kKindAcceptance, true>, grid, block, s, q, ws, a);
-            else launch(MPV_KERNEL_NODE_TASK, node_task_kernel<E, kKindAcceptance, false>, grid, block, s, q, ws, a);
+            launch(MPV_KERNEL_NODE_TASK, node_task_kernel<E, kKindAcceptance>, grid, block, s, const_cast<const Launch*>(ws.launch));
         } else if (p->method != MPV_METHOD_TRAVERSAL) {      // NSS, Naive and SpecTr are variants of the top-down kernel
-            if (full) launch(MPV_KERNEL_NODE_TASK, node_task_kernel<E, MPV_METHOD_SPECINFER, true>, grid, block, s, q, ws, a);
-            else launch(MPV_KERNEL_NODE_TASK, node_task_kernel<E, MPV_METHOD_SPECINFER, false>, grid, block, s, q, ws, a);
+            launch(MPV_KERNEL_NODE_TASK, node_task_kernel<E, MPV_METHOD_SPECINFER>, grid, block, s, const_cast<const Launch*>(ws.launch));
         } else {
-            if (full) launch(MPV_KERNEL_NODE_TASK, node_task_kernel<E, MPV_METHOD_TRAVERSAL, true>, grid, block, s, q, ws, a);
-            else launch(MPV_KERNEL_NODE_TASK, node_task_kernel<E, MPV_METHOD_TRAVERSAL, false>, grid, block, s, q, ws, a);
+            launch(MPV_KERNEL_NODE_TASK, node_task_kernel<E, MPV_METHOD_TRAVERSAL>, grid, block, s, const_cast<const Launch*>(ws.launch));
         }
     }
     if (a.dbg_stats) {
@@ -1856,7 +2252,6 @@ static int verify_with_workspace(const mpv_problem* problem, const mpv_buffers* 
     a.k32 = static_cast<float>(1.4426950408889634 / static_cast<double>(problem->temperature));
     a.lazy = (walk || (buf->edge_probs == nullptr && buf->accept_prob == nullptr && buf->stats == nullptr)) ? 1 : 0;
     a.estimate = 0; a.reach_prob = nullptr; a.expected = nullptr;
-    a.stagger_ticks = mpv::stagger_ticks(problem);
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     if (problem->logit_dtype == MPV_DTYPE_F32) return mpv::launch_all<mpv::ElemF32>(problem, plan, ws, a, s);
     return mpv::launch_all<mpv::ElemBF16>(problem, plan, ws, a, s);
@@ -1886,7 +2281,6 @@ int mpv_block_efficiency(const mpv_problem* problem, const void* target_logits, 
     a.k32 = static_cast<float>(1.4426950408889634 / static_cast<double>(problem->temperature));
     a.lazy = 0;
     a.estimate = 1; a.reach_prob = reach_prob; a.expected = expected;
-    a.stagger_ticks = mpv::stagger_ticks(problem);
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     if (problem->logit_dtype == MPV_DTYPE_F32) return mpv::launch_all<mpv::ElemF32>(problem, plan, ws, a, s);
     return mpv::launch_all<mpv::ElemBF16>(problem, plan, ws, a, s);
@@ -1917,7 +2311,6 @@ int mpv_acceptance_rates(const mpv_problem* problem, const void* target_logits, 
     a.k32 = static_cast<float>(1.4426950408889634 / static_cast<double>(problem->temperature));
     a.lazy = 0;
     a.estimate = 2; a.alpha = alpha;
-    a.stagger_ticks = mpv::stagger_ticks(problem);
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     if (problem->logit_dtype == MPV_DTYPE_F32) return mpv::launch_all<mpv::ElemF32>(problem, plan, ws, a, s);
     return mpv::launch_all<mpv::ElemBF16>(problem, plan, ws, a, s);

@@ -218,19 +218,21 @@ __device__ __forceinline__ void sweep_pair(const typename E::T* __restrict__ zt,
     const T* bt = zt + head;
     const T* bd = zd + head;
     for (int i = tid; i < nvec; i += BLOCK * UNROLL) {
-        float a[UNROLL][VEC], d[UNROLL][VEC];
+        uint4 ra[UNROLL], rd[UNROLL];             // kept packed until they are used
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) {
-            const int idx = i + u * BLOCK;
-            if (idx < nvec) {
-                E::load_vec(bt + static_cast<size_t>(idx) * VEC, a[u]);
-                E::load_vec(bd + static_cast<size_t>(idx) * VEC, d[u]);
-            }
+            const int idx = min(i + u * BLOCK, nvec - 1);       // clamped: always a valid load
+            ra[u] = load_raw_at(bt, idx);
+            rd[u] = load_raw_at(bd, idx);
         }
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) {
-            const int idx = i + u * BLOCK;
-            if (idx < nvec) f.vec(a[u], d[u]);
+            if (i + u * BLOCK < nvec) {
+                float a[VEC], d[VEC];
+                E::unpack(ra[u], a);
+                E::unpack(rd[u], d);
+                f.vec(a, d);
+            }
         }
     }
 }
@@ -248,16 +250,16 @@ __device__ __forceinline__ void sweep_row(const typename E::T* __restrict__ z, i
     if (tail0 + tid < V) f.one(E::load_one(z + tail0 + tid));
     const T* bz = z + head;
     for (int i = tid; i < nvec; i += BLOCK * UNROLL) {
-        float a[UNROLL][VEC];
+        uint4 ra[UNROLL];                         // kept packed until they are used
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) ra[u] = load_raw_at(bz, min(i + u * BLOCK, nvec - 1));   // clamped: always a valid load
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) {
-            const int idx = i + u * BLOCK;
-            if (idx < nvec) E::load_vec(bz + static_cast<size_t>(idx) * VEC, a[u]);
-        }
-#pragma unroll
-        for (int u = 0; u < UNROLL; ++u) {
-            const int idx = i + u * BLOCK;
-            if (idx < nvec) f.vec(a[u]);
+            if (i + u * BLOCK < nvec) {
+                float a[VEC];
+                E::unpack(ra[u], a);
+                f.vec(a);
+            }
         }
     }
 }
@@ -400,17 +402,17 @@ __device__ __forceinline__ ResidualConsts residual_consts(double At, double Ad, 
     return r;
 }
 
-// ---------------------------------------------------------------- a row pair kept on chip
+// ---------------------------------------------------------------- a part of a row pair kept on chip
 //
-// A node task sweeps the same (target, draft) row pair 1 + (number of children)
-// times.  The first sweep keeps as much of the pair as the compute unit can hold:
-// R 16-byte vectors per lane and row in registers, L more in LDS; later sweeps
-// replay those and re-read only the rest ("streamed" part) from memory.  The
-// streamed part is the last thing the first sweep loads and the first thing a
-// replay reads, so that it is still in the L2 cache.
+// A node task sweeps the same (target, draft) row pair 1 + (number of children) times.  The pair
+// is split by vocabulary range among the G workgroups of a team (G chosen so that a part fits):
+// each keeps its part on chip for the whole task, R 16-byte vectors per lane and row in
+// registers and up to L more in LDS, loaded once, and every sweep runs over those.  If a part is
+// larger than that (vocabularies beyond G_max parts), the rest is read again in every sweep.
 //
-// Vector i of a row belongs to lane i % BLOCK, slot i / BLOCK: slots [0,R) live in
-// registers, [R,R+L) in LDS (lds[slot-R][lane]), the rest is streamed.
+// Vector i of the part (i counted from the part's first vector) belongs to lane i % BLOCK,
+// slot i / BLOCK: slots [0,R) live in registers, [R,R+L) in LDS (lds[slot-R][lane]), the rest is
+// streamed.  Lanes past the end of the part hold -inf logits (probability zero in every sweep).
 
 // 16 bytes per lane from global memory straight into LDS (no register in between):
 // the wave's 64 lanes fill 1 KB starting at the wave-uniform address `lds_wave_base`.
@@ -419,28 +421,29 @@ __device__ __forceinline__ void load_to_lds_16B(const void* gptr, uint4* lds_wav
                                      (__attribute__((address_space(3))) void*)lds_wave_base, 16, 0, 0);
 }
 
-template <class E, int BLOCK, int R, int L, int CH, bool FULL>
-struct RetainedPair {
-    // FULL: the caller guarantees nvec >= (R + L) * BLOCK, so every register and
-    // LDS slot of every lane is in range and those parts run without a branch.
-    // The streamed slots are software-pipelined through two small buffers: the
-    // loads of the next two slots are in flight while kept data is being processed.
+template <class E> struct NegInfVec;
+template <> struct NegInfVec<ElemF32> { static __device__ __forceinline__ uint4 v() { return make_uint4(0xff800000u, 0xff800000u, 0xff800000u, 0xff800000u); } };
+template <> struct NegInfVec<ElemBF16> { static __device__ __forceinline__ uint4 v() { return make_uint4(0xff80ff80u, 0xff80ff80u, 0xff80ff80u, 0xff80ff80u); } };
+
+template <class E, int BLOCK, int R, int L>
+struct RetainedPart {
     using T = typename E::T;
     static constexpr int VEC = E::VEC;
-    static constexpr int PIPED = 10;            // streamed slots covered by the fixed pipeline
-    uint4 rt[R > 0 ? R : 1], rd[R > 0 ? R : 1];
-    const T* zt;
+    uint4 rt[R], rd[R];
+    const T* zt;                // the rows themselves (element 0)
     const T* zd;
-    const T* bt;
+    const T* bt;                // first 16-byte aligned vector of the rows
     const T* bd;
-    uint4* lt;
+    uint4* lt;                  // LDS, [L][BLOCK] each
     uint4* ld;
-    int V, head, nvec, tail0;
-    int tid;                                    // this lane's index, as handed to setup()
+    int V, head, nvec, tail0;   // row geometry: `head` elements, nvec vectors, then elements from tail0
+    int v0, nv, nslots;         // this part: vectors [v0, v0 + nv) of the row, ceil(nv / BLOCK) slots
+    int tid;
+    bool first_part, last_part; // who looks after the elements before / after the aligned vectors
 
-    struct Chunk { uint4 a[2], d[2]; };
-
-    __device__ __forceinline__ void setup(const T* zt_, const T* zd_, int V_, uint4* lds_t, uint4* lds_d, int tid_) {
+    // per: vectors per part (a multiple of 64: the bonus sampler's wave tiles never straddle parts)
+    __device__ __forceinline__ void setup(const T* zt_, const T* zd_, int V_, uint4* lds_t, uint4* lds_d, int tid_,
+                                          int member, int team_size, int per) {
         zt = zt_; zd = zd_; V = V_; lt = lds_t; ld = lds_d; tid = tid_;
         const int mis = static_cast<int>((reinterpret_cast<uintptr_t>(zt) & 15u) / sizeof(T));
         head = mis ? min(VEC - mis, V) : 0;
@@ -448,145 +451,107 @@ struct RetainedPair {
         tail0 = head + nvec * VEC;
         bt = zt + head;
         bd = zd + head;
+        v0 = min(member * per, nvec);
+        nv = min(per, nvec - v0);
+        nslots = (nv + BLOCK - 1) / BLOCK;
+        first_part = member == 0;
+        last_part = member == team_size - 1;
     }
 
     template <class F>
     __device__ __forceinline__ void edges(F& f) const {
-        if (tid < head) f.one(E::load_one(zt + tid), E::load_one(zd + tid));
-        if (tail0 + tid < V) f.one(E::load_one(zt + tail0 + tid), E::load_one(zd + tail0 + tid));
+        if (first_part && tid < head) f.one(E::load_one(zt + tid), E::load_one(zd + tid));
+        if (last_part && tail0 + tid < V) f.one(E::load_one(zt + tail0 + tid), E::load_one(zd + tail0 + tid));
     }
 
-    // streamed slots s0, s0+CH, ... with CH loads in flight (no pipelining across iterations)
+    // slot s of this lane: its vector number in the row (clamped into the part: always a valid
+    // address when the part is not empty) and whether it lies inside the part
+    __device__ __forceinline__ int vec_of(int s) const { return v0 + min(s * BLOCK + tid, nv - 1); }
+    __device__ __forceinline__ bool inside(int s) const { return s * BLOCK + tid < nv; }
+
+    // Put every load of the kept slots in flight (registers first: they are consumed first).
+    // An empty part (nv = 0) loads nothing.
+    __device__ __forceinline__ void issue_loads() {
+        if (nv <= 0) return;
+#pragma unroll
+        for (int j = 0; j < R; ++j) {
+            rt[j] = load_raw_at_nt(bt, vec_of(j));
+            rd[j] = load_raw_at_nt(bd, vec_of(j));
+        }
+        const int wave0 = (tid / kWave) * kWave;
+#pragma unroll
+        for (int j = 0; j < L; ++j) {
+            if (R + j < nslots) {
+                load_to_lds_16B(bt + static_cast<size_t>(vec_of(R + j)) * VEC, lt + j * BLOCK + wave0);
+                load_to_lds_16B(bd + static_cast<size_t>(vec_of(R + j)) * VEC, ld + j * BLOCK + wave0);
+            }
+        }
+    }
+
+    // slots beyond what is kept: read from memory, CH loads in flight
     template <class F>
-    __device__ __forceinline__ void streamed_from(int s0, F& f) const {
-        for (int i = tid + (R + L + s0) * BLOCK; i < nvec; i += BLOCK * CH) {
+    __device__ __forceinline__ void streamed(F& f) const {
+        constexpr int CH = 2;
+        for (int s = R + L; s < nslots; s += CH) {
             uint4 a[CH], d[CH];
 #pragma unroll
             for (int u = 0; u < CH; ++u) {
-                const int idx = min(i + u * BLOCK, nvec - 1);      // clamped: always a valid load
-                a[u] = load_raw_at(bt, idx);
-                d[u] = load_raw_at(bd, idx);
+                a[u] = load_raw_at(bt, vec_of(s + u));
+                d[u] = load_raw_at(bd, vec_of(s + u));
             }
 #pragma unroll
-            for (int u = 0; u < CH; ++u) {
-                if (i + u * BLOCK < nvec) f.vec(a[u], d[u]);
-            }
+            for (int u = 0; u < CH; ++u)
+                if (inside(s + u)) f.vec(a[u], d[u]);
         }
     }
 
-    // two streamed slots s, s+1 into a buffer / out of it
-    __device__ __forceinline__ void issue(Chunk& c, int s) const {
-        int tid = this->tid;
-        asm volatile("" : "+v"(tid));       // recompute the addresses here: keeping them live across sweeps costs registers
-#pragma unroll
-        for (int u = 0; u < 2; ++u) {
-            const int idx = min(tid + (R + L + s + u) * BLOCK, nvec - 1);
-            c.a[u] = load_raw_at(bt, idx);
-            c.d[u] = load_raw_at(bd, idx);
-        }
-    }
-    template <class F>
-    __device__ __forceinline__ void consume(const Chunk& c, int s, F& f) const {
-#pragma unroll
-        for (int u = 0; u < 2; ++u) {
-            if (tid + (R + L + s + u) * BLOCK < nvec) f.vec(c.a[u], c.d[u]);
-        }
-    }
-
-#ifndef MPV_DIST
-#define MPV_DIST 6
-#endif
-    static constexpr int DIST = MPV_DIST;             // slots of loads kept ahead of the compute in the first sweep
-
-    __device__ __forceinline__ void load_register_slot(int j) {
-        rt[j] = load_raw_at_nt(bt, tid + j * BLOCK);
-        rd[j] = load_raw_at_nt(bd, tid + j * BLOCK);
-    }
-    __device__ __forceinline__ void load_lds_slot(int j) {
-        const int wave0 = (tid / kWave) * kWave;
-        load_to_lds_16B(bt + static_cast<size_t>(tid + (R + j) * BLOCK) * VEC, lt + j * BLOCK + wave0);
-        load_to_lds_16B(bd + static_cast<size_t>(tid + (R + j) * BLOCK) * VEC, ld + j * BLOCK + wave0);
-    }
-
-    // First sweep, part 1: put the loads of the first register slots in flight.
-    __device__ __forceinline__ void issue_register_loads() {
-        if (!FULL) return;
-#pragma unroll
-        for (int j = 0; j < DIST && j < R; ++j) load_register_slot(j);
-    }
-
-    // First sweep, part 2: load the rest once, keep what fits, feed f with everything.
-    // A wave that has issued a load cannot compute until the memory pipeline has
-    // accepted it, so loads are issued DIST slots ahead of the slot being processed
-    // instead of all at once: arrival and arithmetic then overlap.  The streamed
-    // chunks (two slots each, one buffer) are spread over the sweep, one every
-    // GAP kept slots, so that each has GAP slots of arithmetic to arrive behind.
-    static constexpr int GAP = (R + L) / 5 > 0 ? (R + L) / 5 : 1;
-
-    template <class F>
-    __device__ __forceinline__ void chunk_step(int c, Chunk& A, F& f) const {
-        // called before kept slot c is processed (c counts kept slots in processing order)
-        if (c % GAP == 0 && c / GAP < 5) {
-            if (c > 0) consume(A, 2 * (c / GAP) - 2, f);
-            issue(A, 2 * (c / GAP));
-        }
-    }
-
+    // First sweep: consumes the loads of issue_loads() in the order they were issued, pads the
+    // lanes past the end of the part with -inf (kept that way for the later sweeps).
     template <class F>
     __device__ __forceinline__ void first_pass(F& f) {
-        if (!FULL) {
-            edges(f);
-            if (nvec > 0) streamed_from(0, f);
-            return;
-        }
-        Chunk A;
+        edges(f);
+        if (nv <= 0) return;
 #pragma unroll
         for (int j = 0; j < R; ++j) {
-            const int ahead = j + DIST;
-            if (ahead < R) load_register_slot(ahead);
-            else if (ahead < R + L) load_lds_slot(ahead - R);
-            chunk_step(j, A, f);
-            if (j == 0) f.begin(rt[0], rd[0]);
-            f.vec(rt[j], rd[j]);
+            if (j < nslots) {
+                if (!inside(j)) { rt[j] = NegInfVec<E>::v(); rd[j] = NegInfVec<E>::v(); }
+                f.vec(rt[j], rd[j]);
+            }
         }
 #pragma unroll
         for (int j = 0; j < L; ++j) {
-            const int ahead = R + j + DIST;
-            if (ahead < R + L) load_lds_slot(ahead - R);
-            chunk_step(R + j, A, f);
-            f.vec(lt[j * BLOCK + tid], ld[j * BLOCK + tid]);
+            if (R + j < nslots) {
+                uint4 a = lt[j * BLOCK + tid], d = ld[j * BLOCK + tid];
+                if (!inside(R + j)) {
+                    a = NegInfVec<E>::v(); d = NegInfVec<E>::v();
+                    lt[j * BLOCK + tid] = a; ld[j * BLOCK + tid] = d;        // the lane's own entry
+                }
+                f.vec(a, d);
+            }
         }
-        consume(A, 8, f);
-        streamed_from(PIPED, f);
-        edges(f);
+        streamed(f);
     }
 
-    // Later sweeps.  The empty asm marks each kept register as "possibly changed",
-    // so that the compiler does not hoist the unpacked form of the whole pair out
-    // of the caller's loop over children (which would double the register footprint).
+    // Later sweeps.  The empty asm marks each kept register as "possibly changed", so that the
+    // compiler does not hoist the unpacked form of the whole part out of the caller's loop over
+    // children (which would double the register footprint).
     template <class F>
     __device__ __forceinline__ void replay(F& f) {
-        if (!FULL) {
-            edges(f);
-            if (nvec > 0) streamed_from(0, f);
-            return;
-        }
-        Chunk A;
         edges(f);
+        if (nv <= 0) return;
 #pragma unroll
         for (int j = 0; j < L; ++j) {
-            chunk_step(j, A, f);
-            f.vec(lt[j * BLOCK + tid], ld[j * BLOCK + tid]);
+            if (R + j < nslots) f.vec(lt[j * BLOCK + tid], ld[j * BLOCK + tid]);
         }
 #pragma unroll
         for (int j = 0; j < R; ++j) {
-            chunk_step(L + j, A, f);
-            asm volatile("" : "+v"(rt[j].x), "+v"(rt[j].y), "+v"(rt[j].z), "+v"(rt[j].w));
-            asm volatile("" : "+v"(rd[j].x), "+v"(rd[j].y), "+v"(rd[j].z), "+v"(rd[j].w));
-            f.vec(rt[j], rd[j]);
+            if (j < nslots) {
+                asm volatile("" : "+v"(rt[j].x), "+v"(rt[j].y), "+v"(rt[j].z), "+v"(rt[j].w));
+                asm volatile("" : "+v"(rd[j].x), "+v"(rd[j].y), "+v"(rd[j].z), "+v"(rd[j].w));
+                f.vec(rt[j], rd[j]);
+            }
         }
-        consume(A, 8, f);
-        streamed_from(PIPED, f);
+        streamed(f);
     }
 };
 
@@ -594,7 +559,6 @@ template <class E>
 struct PairStatsRawF {
     OnlineLse t, d;
     float k32;
-    __device__ __forceinline__ void begin(const uint4&, const uint4&) {}
     __device__ __forceinline__ void one(float a, float b) { t.one(a, k32); d.one(b, k32); }
     __device__ __forceinline__ void vec(const uint4& ra, const uint4& rb) {
         float a[E::VEC], b[E::VEC];
@@ -645,8 +609,6 @@ __device__ __forceinline__ float hit_probability(float q, float m, float c2, flo
 // NSS:   sum_t p (1 - (1-q)^m)                                  (m = k)
 // Naive: sum_t min(p,q) + sum_t (p-q)_+ (1 - (1-q)^m)           (m = k - 1)
 // p = 2^(zt k32 + nAt) sp and q = 2^(zd k32 + nAd) sq are the normalised probabilities themselves.
-// (A sweep over the rows in memory, not a replay of the pair kept on chip: with this much arithmetic
-// per element the compiler no longer keeps the replayed vectors in registers.)
 template <class E>
 struct AcceptanceF {
     float k32, nAt, nAd, sp, sq, m, c2, c3;
@@ -672,6 +634,12 @@ struct AcceptanceF {
             acc0 += term(a[i], b[i]);
             acc1 += term(a[i + 1], b[i + 1]);
         }
+    }
+    __device__ __forceinline__ void vec(const uint4& ra, const uint4& rb) {
+        float a[E::VEC], b[E::VEC];
+        E::unpack(ra, a);
+        E::unpack(rb, b);
+        vec(a, b);
     }
 };
 
