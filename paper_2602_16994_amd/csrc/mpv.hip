@@ -2,7 +2,7 @@
 //
 // Path of one mpv_verify call (all on the caller's stream):
 //   init_kernel            zero counters, default the per-node results, queue the first tasks
-//   node_task_kernel       persistent workgroups of 256 lanes, four per compute unit, grouped in
+//   node_task_kernel       persistent workgroups of 256 lanes, three per compute unit, grouped in
 //                          TEAMS of G workgroups that take tasks from a queue until none are left.
 //                          A team splits every logit row by vocabulary range: each member keeps its
 //                          part of the task's (target, draft) row pair on chip (registers + LDS),
@@ -45,20 +45,23 @@ namespace mpv {
 
 // ------------------------------------------------------------------ host/device tree tables
 
-// 32-bit entries: a lookup with a wave-uniform index then compiles to a scalar load.
+// Node numbers are below MPV_MAX_NODES = 64: one byte each (the tables live in LDS, where the three
+// workgroups of a compute unit have 53 KB each).
 struct TreeDesc {
     int32_t N;
-    int32_t parent[MPV_MAX_NODES];
-    int32_t nchild[MPV_MAX_NODES];
-    int32_t child_off[MPV_MAX_NODES];    // start of the node's children in child_list
-    int32_t child_list[MPV_MAX_NODES];   // children of node 0, of node 1, ... ascending
-    int32_t depth[MPV_MAX_NODES];
-    int32_t postorder[MPV_MAX_NODES];    // depth-first, children (in list order) before their parent; root last
-    int32_t rank[MPV_MAX_NODES];         // position of the node in postorder
-    int32_t sub_lo[MPV_MAX_NODES];       // the node's subtree is postorder[sub_lo[n] .. rank[n]]
-    int32_t cls[MPV_MAX_NODES];          // priority class of the node's task (see QueuePlan)
+    int8_t parent[MPV_MAX_NODES];
+    int8_t nchild[MPV_MAX_NODES];
+    int8_t child_off[MPV_MAX_NODES];     // start of the node's children in child_list
+    int8_t child_list[MPV_MAX_NODES];    // children of node 0, of node 1, ... ascending
+    int8_t depth[MPV_MAX_NODES];
+    int8_t postorder[MPV_MAX_NODES];     // depth-first, children (in list order) before their parent; root last
+    int8_t rank[MPV_MAX_NODES];          // position of the node in postorder
+    int8_t sub_lo[MPV_MAX_NODES];        // the node's subtree is postorder[sub_lo[n] .. rank[n]]
+    int8_t cls[MPV_MAX_NODES];           // priority class of the node's task (see QueuePlan)
+    int8_t pad[MPV_MAX_NODES];
     int32_t class_off[8];                // QueuePlan::off again, for the kernels that read the tables from memory
 };
+static_assert(MPV_MAX_NODES <= 127 && sizeof(TreeDesc) % 4 == 0, "node numbers must fit a signed byte");
 
 constexpr int kMaxClasses = 4;
 static_assert(kMaxClasses + 1 <= 8, "TreeDesc::class_off is too short");
@@ -91,7 +94,7 @@ struct QueuePlan {
 
 constexpr int kMaxTeam = 16;                          // workgroups per team, at most
 constexpr int kExchWords = 8;                         // 64-bit words one member hands over per exchange
-constexpr int kMaxGrid = 1024;                        // workgroups of a launch, at most (four per compute unit)
+constexpr int kMaxGrid = 768;                        // workgroups of a launch, at most (four per compute unit)
 
 // Per-(tree,node) scalars kept in the workspace, all double, each [B*N].
 struct Workspace {
@@ -174,8 +177,8 @@ constexpr int kTaskWaves = kTaskBlock / kWave;
 constexpr int kTaskUnroll = 4;
 // node tasks keep their part of a row pair on chip: per lane and row, kRegVecs 16-byte vectors in
 // registers and kLdsVecs in LDS
-constexpr int kRegVecs = 8;
-constexpr int kLdsVecs = 4;
+constexpr int kRegVecs = 4;
+constexpr int kLdsVecs = 6;
 constexpr int kPartCapacity = (kRegVecs + kLdsVecs) * kTaskBlock;     // vectors of a row one member keeps
 // upper bound on the polls of a dependency flag (about a second); see node_task_kernel
 constexpr int kMaxSpins = 1 << 20;
@@ -197,10 +200,16 @@ constexpr int kKindAcceptance = 100;                   // node_task_kernel insta
 // LDS of node_task_kernel that the functions it calls use as well (file scope, so that they address
 // it as LDS and not through generic pointers)
 struct TaskShared {
-    double scratch[2 * kTaskWaves];
-    unsigned words[kMaxTeam * kExchWords];
+    double scratch[2 * kTaskWaves];               // block reductions of the stand-alone helpers
+    double part[kTaskWaves][4];                   // per-wave partial sums of a team reduction
+    float partf[kTaskWaves][2];                   // per-wave reference exponents of the statistics
+    unsigned words[kMaxTeam * kExchWords];        // what the members exchanged last
+    int dead;
 };
 __shared__ TaskShared g_sh;
+// the launch parameters (copied from the workspace at the start of node_task_kernel)
+__shared__ __align__(16) int g_launch_words[sizeof(Launch) / sizeof(int)];
+__device__ __forceinline__ const Launch& lds_launch() { return *reinterpret_cast<const Launch*>(g_launch_words); }
 // the part of the row pair kept in LDS (target slots, then draft slots); the sampling task's table
 // of tile masses uses the same memory
 __shared__ uint4 g_rows[2 * kLdsVecs * kTaskBlock];
@@ -314,7 +323,7 @@ __global__ void init_kernel(QueuePlan q, TreeDesc tree, Workspace ws, Args a) {
 
 // ------------------------------------------------------------------ task queue
 //
-// node_task_kernel is launched with four workgroups per compute unit at most, grouped in teams;
+// node_task_kernel is launched with three workgroups per compute unit at most, grouped in teams;
 // each team runs tasks until told to exit.  A team takes part only once every member has
 // started (the last to arrive opens the team's mailbox), so a task is only ever handed to
 // workgroups that are running, whatever else occupies the device.  A task is appended only when
@@ -462,11 +471,10 @@ __device__ __forceinline__ bool dispatch_round(const QueuePlan& q, const TreeDes
 // the answer).  `previous` is the task it took from the mailbox last: until the request has
 // reached memory the mailbox may still show it (no entry is ever handed out twice, so the
 // value is unambiguous).
-__device__ __attribute__((noinline)) int acquire_task(const Launch* launch, int team_in, int previous_in, bool drop_settled_in, long long t_start) {
-    const Launch* const L = uniform_ptr(launch);
-    const Args a = uniform_struct(L->a);
-    const Workspace ws = uniform_struct(L->ws);
-    const QueuePlan q = uniform_struct(L->q);
+__device__ __attribute__((noinline)) int acquire_task(int team_in, int previous_in, bool drop_settled_in, long long t_start) {
+    const Args& a = lds_launch().a;
+    const Workspace& ws = lds_launch().ws;
+    const QueuePlan& q = lds_launch().q;
     const TreeDesc& tree = g_tree;
     const int team = uniform_i32(team_in), previous = uniform_i32(previous_in);
     const bool drop_settled = uniform_i32(drop_settled_in ? 1 : 0) != 0;
@@ -547,43 +555,50 @@ struct Team {
     int dead;                        // a partner never answered: results are invalid, every wait is skipped
 };
 
-// All lanes of the workgroup.  Lane w < kExchWords of the first wave brings `mine`, its 32 bits of
-// payload.  On return words[m * kExchWords + w] holds member m's word w.
-__device__ __forceinline__ void team_exchange(Team& t, unsigned mine, unsigned* words, const Workspace& ws, const Args& a) {
-    __shared__ int sh_dead;
-    t.seq++;
-    __syncthreads();                                  // earlier readers of `words` are done
+// First wave only.  Lane w < kExchWords brings `mine`, its 32 bits of payload.  On return
+// g_sh.words[m * kExchWords + w] holds member m's word w (visible to the other waves after the
+// caller's next barrier) and g_sh.dead says whether a partner failed to answer.
+__device__ __forceinline__ void exchange_words(const Team& t, unsigned mine) {
+    const Workspace& ws = lds_launch().ws;
+    const Args& a = lds_launch().a;
+    const int lane = threadIdx.x;
     if (t.size == 1) {
-        if (threadIdx.x < kExchWords) words[threadIdx.x] = mine;
-        __syncthreads();
+        if (lane < kExchWords) g_sh.words[lane] = mine;
+        if (lane == 0) g_sh.dead = t.dead;
         return;
     }
-    if (threadIdx.x < kWave) {
-        unsigned long long* base = t.area + static_cast<size_t>(t.seq & 1u) * t.size * kExchWords;
-        const unsigned long long tag = static_cast<unsigned long long>(t.seq) << 32;
-        if (threadIdx.x < kExchWords) st_relaxed(base + t.member * kExchWords + threadIdx.x, tag | mine);
-        int dead = t.dead;
-        for (int w = threadIdx.x; w < t.size * kExchWords; w += kWave) {
-            unsigned long long v = 0ull;
-            while (!dead) {
-                v = ld_relaxed(base + w);
-                if ((v >> 32) == (tag >> 32)) break;
-                if (wall_clock64() - t.t_start > kLaunchTimeoutTicks) { dead = 1; break; }
-                __builtin_amdgcn_s_sleep(1);
-            }
-            words[w] = dead ? 0u : static_cast<unsigned>(v);
+    unsigned long long* base = t.area + static_cast<size_t>(t.seq & 1u) * t.size * kExchWords;
+    const unsigned long long tag = static_cast<unsigned long long>(t.seq) << 32;
+    if (lane < kExchWords) st_relaxed(base + t.member * kExchWords + lane, tag | mine);
+    int dead = t.dead;
+    for (int w = lane; w < t.size * kExchWords; w += kWave) {
+        unsigned long long v = 0ull;
+        while (!dead) {
+            v = ld_relaxed(base + w);
+            if ((v >> 32) == (tag >> 32)) break;
+            if (wall_clock64() - t.t_start > kLaunchTimeoutTicks) { dead = 1; break; }
+            __builtin_amdgcn_s_sleep(1);
         }
-        const int any_dead = __ballot(dead != 0) != 0ull;
-        if (threadIdx.x == 0) {
-            sh_dead = any_dead;
-            if (any_dead && !t.dead) {
-                atomicAdd(&a.counters[MPV_COUNTER_DEPENDENCY_TIMEOUT], 1u);
-                st_relaxed(&ws.qctl[2], 1);            // everybody leaves at the next occasion
-            }
+        g_sh.words[w] = dead ? 0u : static_cast<unsigned>(v);
+    }
+    const int any_dead = __ballot(dead != 0) != 0ull;
+    if (lane == 0) {
+        g_sh.dead = any_dead;
+        if (any_dead && !t.dead) {
+            atomicAdd(&a.counters[MPV_COUNTER_DEPENDENCY_TIMEOUT], 1u);
+            st_relaxed(&ws.qctl[2], 1);                // everybody leaves at the next occasion
         }
     }
+}
+
+// All lanes of the workgroup: one exchange of raw words (lane w < kExchWords of the first wave
+// brings `mine`); afterwards every lane may read g_sh.words.
+__device__ __forceinline__ void team_exchange(Team& t, unsigned mine) {
+    t.seq++;
+    __syncthreads();                                  // earlier readers of g_sh.words are done
+    if (threadIdx.x < kWave) exchange_words(t, mine);
     __syncthreads();
-    t.dead = sh_dead;
+    t.dead = g_sh.dead;
 }
 
 __device__ __forceinline__ unsigned half_of(double v, int hi) {
@@ -594,23 +609,38 @@ __device__ __forceinline__ double double_at(const unsigned* words, int member, i
                             static_cast<int>(words[member * kExchWords + 2 * pair]));
 }
 
-// Sums of up to four per-member values over the team, added in member order; every lane of every
-// member gets the same bits.  v[i] must be the same in every lane of the workgroup.
+// Sums of up to four per-lane values over every lane of every member of the team: wave sums, the
+// four waves and then the members added in a fixed order, so every lane of every member gets the
+// same bits.  Two barriers: wave partials -> (first wave: block total, exchange) -> everybody reads.
 template <int COUNT>
-__device__ __forceinline__ void team_sum(Team& t, double (&v)[COUNT], unsigned* words, const Workspace& ws, const Args& a) {
-    static_assert(COUNT * 2 <= kExchWords, "too many values for one exchange");
-    unsigned mine = 0u;
+__device__ __forceinline__ void team_sum(Team& t, double (&v)[COUNT]) {
+    static_assert(COUNT * 2 <= kExchWords && COUNT <= 4, "too many values for one exchange");
+    const int wave = threadIdx.x / kWave, lane = threadIdx.x & (kWave - 1);
+    t.seq++;
 #pragma unroll
     for (int i = 0; i < COUNT; ++i) {
-        if (threadIdx.x == 2 * i) mine = half_of(v[i], 0);
-        if (threadIdx.x == 2 * i + 1) mine = half_of(v[i], 1);
+        const double w = wave_sum(v[i]);
+        if (lane == 0) g_sh.part[wave][i] = w;
     }
-    team_exchange(t, mine, words, ws, a);
+    __syncthreads();
+    if (wave == 0) {
+        unsigned mine = 0u;
+        if (lane < 2 * COUNT) {
+            const int i = lane >> 1;
+            double b = g_sh.part[0][i];
+#pragma unroll
+            for (int w = 1; w < kTaskWaves; ++w) b += g_sh.part[w][i];
+            mine = half_of(b, lane & 1);
+        }
+        exchange_words(t, mine);
+    }
+    __syncthreads();
+    t.dead = g_sh.dead;
 #pragma unroll
     for (int i = 0; i < COUNT; ++i) {
         double s = 0.0;
-        for (int m = 0; m < t.size; ++m) s += double_at(words, m, i);
-        v[i] = s;
+        for (int m = 0; m < t.size; ++m) s += double_at(g_sh.words, m, i);
+        v[i] = uniform_f64(s);
     }
 }
 
@@ -663,35 +693,56 @@ constexpr int kFlagIdle = 1;          // teams were idle after the last round of
 // (defined below) walk and bonus token of tree b, or one draw of a token-following walk, by the
 // whole team; returns the task that follows from it (-1: none; the same in every lane of every member)
 template <class E, int METHOD>
-__device__ __attribute__((noinline)) int sample_task(const Launch* launch, Team& team_io, int b_in);
+__device__ __attribute__((noinline)) int sample_task(Team& team_io, int b_in);
 
 // (defined below) expected block efficiency of tree b from the per-node results, by the first wave
 template <int METHOD>
 __device__ __forceinline__ void estimate_wave(const TreeDesc& tree, const Workspace& ws, const Args& a, int b);
 
-// Softmax statistics of the task's two rows from the lanes' states: block reduction, then one
-// exchange that also carries the node's starting weight from the leader (a0_leader; the value
-// the other members pass is ignored).  Every lane of every member gets the same bits.
-__device__ __forceinline__ void team_stats(Team& t, const OnlineLse& lt, const OnlineLse& ld, double a0_leader,
-                                           double& At, double& Ad, double& a0, const Workspace& ws, const Args& a) {
-    float Mt = lt.mk, Md = ld.mk;
-    block_max2<kTaskBlock>(Mt, Md, g_sh.scratch);
-    double st = (lt.s > 0.f) ? static_cast<double>(lt.s * fast_exp2(lt.mk - Mt)) : 0.0;
-    double sd = (ld.s > 0.f) ? static_cast<double>(ld.s * fast_exp2(ld.mk - Md)) : 0.0;
-    block_sum2<kTaskBlock>(st, sd, g_sh.scratch);
-    unsigned mine = 0u;
-    switch (threadIdx.x) {
-        case 0: mine = __float_as_uint(Mt); break;
-        case 1: mine = __float_as_uint(Md); break;
-        case 2: mine = half_of(st, 0); break;
-        case 3: mine = half_of(st, 1); break;
-        case 4: mine = half_of(sd, 0); break;
-        case 5: mine = half_of(sd, 1); break;
-        case 6: mine = half_of(a0_leader, 0); break;
-        case 7: mine = half_of(a0_leader, 1); break;
-        default: break;
+// Softmax statistics of the task's two rows from the lanes' states (sum_v 2^(z_v k32 - mk) against
+// each lane's own reference mk): lanes are brought to their wave's largest reference, waves to the
+// workgroup's, members to the team's; one exchange, which also carries the node's starting weight
+// from the leader (*a0_lds, LDS, written before the call; what the other members pass is ignored).
+// Every lane of every member gets the same bits.
+__device__ __forceinline__ void team_stats(Team& t, const OnlineLse& lt, const OnlineLse& ld, const double* a0_lds,
+                                           double& At, double& Ad, double& a0) {
+    const int wave = threadIdx.x / kWave, lane = threadIdx.x & (kWave - 1);
+    t.seq++;
+    const float Mt_w = wave_max(lt.mk), Md_w = wave_max(ld.mk);
+    const double st_w = wave_sum((lt.s > 0.f) ? static_cast<double>(lt.s * fast_exp2(lt.mk - Mt_w)) : 0.0);
+    const double sd_w = wave_sum((ld.s > 0.f) ? static_cast<double>(ld.s * fast_exp2(ld.mk - Md_w)) : 0.0);
+    if (lane == 0) {
+        g_sh.partf[wave][0] = Mt_w; g_sh.partf[wave][1] = Md_w;
+        g_sh.part[wave][0] = st_w; g_sh.part[wave][1] = sd_w;
     }
-    team_exchange(t, mine, g_sh.words, ws, a);
+    __syncthreads();
+    if (wave == 0) {
+        float Mt = g_sh.partf[0][0], Md = g_sh.partf[0][1];
+#pragma unroll
+        for (int w = 1; w < kTaskWaves; ++w) { Mt = fmaxf(Mt, g_sh.partf[w][0]); Md = fmaxf(Md, g_sh.partf[w][1]); }
+        double st = 0.0, sd = 0.0;
+#pragma unroll
+        for (int w = 0; w < kTaskWaves; ++w) {
+            st += g_sh.part[w][0] * static_cast<double>(fast_exp2(g_sh.partf[w][0] - Mt));
+            sd += g_sh.part[w][1] * static_cast<double>(fast_exp2(g_sh.partf[w][1] - Md));
+        }
+        const double a0_mine = *a0_lds;
+        unsigned mine = 0u;
+        switch (lane) {
+            case 0: mine = __float_as_uint(Mt); break;
+            case 1: mine = __float_as_uint(Md); break;
+            case 2: mine = half_of(st, 0); break;
+            case 3: mine = half_of(st, 1); break;
+            case 4: mine = half_of(sd, 0); break;
+            case 5: mine = half_of(sd, 1); break;
+            case 6: mine = half_of(a0_mine, 0); break;
+            case 7: mine = half_of(a0_mine, 1); break;
+            default: break;
+        }
+        exchange_words(t, mine);
+    }
+    __syncthreads();
+    t.dead = g_sh.dead;
     float MT = OnlineLse::kFloor, MD = OnlineLse::kFloor;
     for (int m = 0; m < t.size; ++m) {
         MT = fmaxf(MT, __uint_as_float(g_sh.words[m * kExchWords]));
@@ -699,9 +750,8 @@ __device__ __forceinline__ void team_stats(Team& t, const OnlineLse& lt, const O
     }
     double ST = 0.0, SD = 0.0;
     for (int m = 0; m < t.size; ++m) {
-        const double pt = double_at(g_sh.words, m, 1), pd = double_at(g_sh.words, m, 2);
-        if (pt > 0.0) ST += pt * cold_exp2(static_cast<double>(__uint_as_float(g_sh.words[m * kExchWords])) - static_cast<double>(MT));
-        if (pd > 0.0) SD += pd * cold_exp2(static_cast<double>(__uint_as_float(g_sh.words[m * kExchWords + 1])) - static_cast<double>(MD));
+        ST += double_at(g_sh.words, m, 1) * static_cast<double>(fast_exp2(__uint_as_float(g_sh.words[m * kExchWords]) - MT));
+        SD += double_at(g_sh.words, m, 2) * static_cast<double>(fast_exp2(__uint_as_float(g_sh.words[m * kExchWords + 1]) - MD));
     }
     At = uniform_f64(static_cast<double>(MT) + cold_log2(ST));
     Ad = uniform_f64(static_cast<double>(MD) + cold_log2(SD));
@@ -711,70 +761,201 @@ __device__ __forceinline__ void team_stats(Team& t, const OnlineLse& lt, const O
 // One node task (or the resumed task of the node where the tree branches), by every member of the
 // team.  A function of its own, not inlined: what it keeps in registers (its part of the row pair)
 // then competes only with its own scalar steps for registers, not with the dispatcher or the sampler.
-// asked / own_task: the leader's notes for the task loop (has the team asked for its next task; the
-// task it is to run next without asking).
+//
+// Inside a workgroup the four waves split the work in another way as well: all four sweep their
+// share of the part, but everything scalar (statistics, weights, the child loop, the exchange with
+// the other members, what follows from the task) is the first wave's alone.  The other waves wait
+// at a barrier for the next sweep's constants: they issue no instruction meanwhile, which leaves
+// the compute unit to the sweeps of the other workgroups that live on it.
+//   first wave:   ... scalar step ... | write command | barrier B | sweep | partial | barrier A | read partials ...
+//   other waves:                                      | barrier B | sweep | partial | barrier A | (loop)
+// asked / own_task / own_flags: the leader's notes for the task loop (has the team asked for its
+// next task; the task it is to run next, already announced to the team, and its flags); only the
+// first wave's copies matter.
+
+constexpr int kCmdDone = 0;          // the task is over
+constexpr int kCmdMass = 1;          // sum (p - rho q)_+
+constexpr int kCmdMassSlope = 2;     // the same and sum_{p > rho q} rho q       (SpecTr's root search)
+constexpr int kCmdAcceptance = 3;    // the NSS / Naive acceptance-rate sum      (acceptance rates only)
+
+struct SweepCmd {
+    int kind;
+    float nAt, nAd, rho;             // constants of the residual sweeps
+    float sp, sq;                    // acceptance sweep: scale factors of p and q
+    int m, naive;                    // acceptance sweep: exponent, which formula
+};
+__shared__ SweepCmd g_cmd;
+
+// One sweep over the part on chip as the command says; the wave's partial sums go to g_sh.part.
+template <class E, int KIND, class PAIR>
+__device__ __forceinline__ void run_sweep(PAIR& pair, const SweepCmd& cmd, float k32, int wave, int lane) {
+    constexpr bool ACCEPT = KIND == kKindAcceptance;
+    constexpr bool SLOPE = KIND != MPV_METHOD_TRAVERSAL;      // SpecTr's search exists in the top-down kernels only
+    double s0 = 0.0, s1 = 0.0;
+    if (SLOPE && cmd.kind == kCmdMassSlope) {
+        ResidualMassSlopeRawF<E> f;
+        f.init();
+        f.k32 = k32; f.nAt = cmd.nAt; f.nAd = cmd.nAd; f.rho = cmd.rho;
+        pair.replay(f);
+        s0 = static_cast<double>(f.acc0) + static_cast<double>(f.acc1);
+        s1 = static_cast<double>(f.q0) + static_cast<double>(f.q1);
+    } else if (ACCEPT && cmd.kind == kCmdAcceptance) {
+        AcceptanceF<E> f;
+        f.init(k32, cmd.nAt, cmd.nAd, cmd.sp, cmd.sq, cmd.m, cmd.naive != 0);
+        pair.replay(f);
+        s0 = static_cast<double>(f.acc0) + static_cast<double>(f.acc1);
+    } else {
+        ResidualMassRawF<E> f;
+        f.init();
+        f.k32 = k32; f.nAt = cmd.nAt; f.nAd = cmd.nAd; f.rho = cmd.rho;
+        pair.replay(f);
+        s0 = static_cast<double>(f.acc0) + static_cast<double>(f.acc1);
+    }
+    s0 = wave_sum(s0);
+    if (SLOPE) s1 = wave_sum(s1);
+    if (lane == 0) { g_sh.part[wave][0] = s0; g_sh.part[wave][1] = s1; }
+}
+
+// First wave, after barrier A: the workgroup's sums of the last sweep, exchanged and added over the
+// team in member order.  Every lane of the first wave of every member gets the same bits.
+__device__ __forceinline__ void collect_sums(Team& t, double& s0, double& s1) {
+    const int lane = threadIdx.x;
+    t.seq++;
+    unsigned mine = 0u;
+    if (lane < 4) {
+        const int i = lane >> 1;
+        double b = g_sh.part[0][i];
+#pragma unroll
+        for (int w = 1; w < kTaskWaves; ++w) b += g_sh.part[w][i];
+        mine = half_of(b, lane & 1);
+    }
+    exchange_words(t, mine);
+    __builtin_amdgcn_wave_barrier();
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");       // the wave's own LDS writes, before its reads
+    t.dead = g_sh.dead;
+    double a = 0.0, b = 0.0;
+    for (int m = 0; m < t.size; ++m) { a += double_at(g_sh.words, m, 0); b += double_at(g_sh.words, m, 1); }
+    s0 = uniform_f64(a);
+    s1 = uniform_f64(b);
+}
+
 template <class E, int KIND>
-__device__ __attribute__((noinline)) void run_node_task(const Launch* launch, Team& team_io, int task_in, int flags_in,
-                                                        bool& asked_io, int& own_task_io) {
+__device__ __attribute__((noinline)) void run_node_task(Team& team_io, int task_in, int flags_in,
+                                                        bool& asked_io, int& own_task_io, int& own_flags_io) {
     using T = typename E::T;
     constexpr bool ACCEPT = KIND == kKindAcceptance;
     constexpr int METHOD = ACCEPT ? MPV_METHOD_SPECINFER : KIND;
-    // what arrives as an argument arrives in vector registers: back to scalar ones
-    const Launch* const L = uniform_ptr(launch);
-    const Args a = uniform_struct(L->a);
-    const Workspace ws = uniform_struct(L->ws);
-    const QueuePlan q = uniform_struct(L->q);
+    const Args& a = lds_launch().a;
+    const Workspace& ws = lds_launch().ws;
+    const QueuePlan& q = lds_launch().q;
     const TreeDesc& tree = g_tree;
+    // (what arrives as an argument arrives in vector registers: back to scalar ones)
     const int task = uniform_i32(task_in), flags = uniform_i32(flags_in);
+    const int wave = uniform_i32(static_cast<int>(threadIdx.x) / kWave), lane = threadIdx.x & (kWave - 1);
     uint4* const lds_t = g_rows;
     uint4* const lds_d = g_rows + kLdsVecs * kTaskBlock;
-    Team team = uniform_struct(team_io);               // in registers while the task runs
-    bool asked = asked_io;
-    int own_task = -1;
-    const bool leader = team.member == 0;
-    const bool lead = leader && threadIdx.x == 0;     // the one lane that talks to the rest of the launch
-    struct WriteBack {                                 // every way out hands the notes back
-        Team& t_out; Team& t; bool& a_out; bool& a; int& o_out; int& o;
-        __device__ ~WriteBack() { t_out = t; a_out = a; o_out = o; }
-    } write_back{team_io, team, asked_io, asked, own_task_io, own_task};
-    // a node task, or the resumed task of the node where the tree branches
-    // (tree, node: made scalar explicitly, so that the table lookups below have uniform addresses)
-    const bool resumed = task >= a.B * a.N + a.B;
-    const int b = __builtin_amdgcn_readfirstlane(resumed ? task - (a.B * a.N + a.B) : task / a.N);
-    const int n = __builtin_amdgcn_readfirstlane(resumed ? q.split_node : task % a.N);
-    const size_t bn = static_cast<size_t>(b) * a.N + n;
-    const T* zt = static_cast<const T*>(a.zt) + bn * a.V;
-    const T* zd = static_cast<const T*>(a.zd) + bn * a.V;
-    const int V = a.V;
-    const float k32 = a.k32;
 
-    const int k = tree.nchild[n];
-    if (lead) atomicAdd(&a.counters[resumed ? MPV_COUNTER_NODE_TASKS_RESUMED : MPV_COUNTER_NODE_TASKS_RUN], 1u);
-    const bool split_here = METHOD == MPV_METHOD_TRAVERSAL && a.lazy && !resumed && n == q.split_node;
-    const bool idle_seen = (flags & kFlagIdle) != 0;
+    // (tree, node: made scalar explicitly, so that the table lookups below have uniform addresses)
+    const int B = uniform_i32(a.B), N = uniform_i32(a.N), V = uniform_i32(a.V);
+    const bool resumed = task >= B * N + B;
+    const int b = uniform_i32(resumed ? task - (B * N + B) : task / N);
+    const int n = uniform_i32(resumed ? q.split_node : task % N);
+    const size_t bn = static_cast<size_t>(b) * N + n;
+    const T* zt = uniform_ptr(static_cast<const T*>(a.zt)) + bn * V;
+    const T* zd = uniform_ptr(static_cast<const T*>(a.zd)) + bn * V;
+    const float k32 = uniform_f32(a.k32);
+    const int k = uniform_i32(tree.nchild[n]);
 
     // ---- the part of the pair this member keeps: every load goes out now
     RetainedPart<E, kTaskBlock, kRegVecs, kLdsVecs> pair;
     int tid_l = threadIdx.x;
     asm volatile("" : "+v"(tid_l));     // per-task copy: nothing derived from it is kept across tasks
-    pair.setup(zt, zd, V, lds_t, lds_d, tid_l, team.member, team.size, q.part_vecs);
+    pair.setup(zt, zd, V, lds_t, lds_d, tid_l, uniform_i32(team_io.member), uniform_i32(team_io.size), uniform_i32(q.part_vecs));
     pair.issue_loads();
+
+    if (wave != 0) {
+        // ---- a sweeping wave: the statistics sweep, then whatever the first wave commands
+        {
+            PairStatsRawF<E> f;
+            f.t.init(); f.d.init(); f.k32 = k32;
+            pair.first_pass(f);
+            const float Mt_w = wave_max(f.t.mk), Md_w = wave_max(f.d.mk);
+            const double st_w = wave_sum((f.t.s > 0.f) ? static_cast<double>(f.t.s * fast_exp2(f.t.mk - Mt_w)) : 0.0);
+            const double sd_w = wave_sum((f.d.s > 0.f) ? static_cast<double>(f.d.s * fast_exp2(f.d.mk - Md_w)) : 0.0);
+            if (lane == 0) {
+                g_sh.partf[wave][0] = Mt_w; g_sh.partf[wave][1] = Md_w;
+                g_sh.part[wave][0] = st_w; g_sh.part[wave][1] = sd_w;
+            }
+        }
+        __syncthreads();                                  // A: the partials are there
+        for (;;) {
+            __syncthreads();                              // B: the command is there
+            const SweepCmd cmd = g_cmd;
+            if (uniform_i32(cmd.kind) == kCmdDone) break;
+            run_sweep<E, KIND>(pair, cmd, k32, wave, lane);
+            __syncthreads();                              // A
+        }
+        return;
+    }
+
+    // ================================================================ the first wave
+    Team team = uniform_struct(team_io);               // in registers while the task runs
+    bool asked = asked_io;
+    int own_task = -1, own_flags = 0;
+    struct WriteBack {                                 // every way out hands the notes back
+        Team& t_out; Team& t; bool& a_out; bool& a; int& o_out; int& o; int& f_out; int& f;
+        __device__ ~WriteBack() { t_out = t; a_out = a; o_out = o; f_out = f; }
+    } write_back{team_io, team, asked_io, asked, own_task_io, own_task, own_flags_io, own_flags};
+    const bool leader = team.member == 0;
+    const bool lead = leader && lane == 0;            // the one lane that talks to the rest of the launch
+    double At_ = 0.0, Ad_ = 0.0, wa = 1.0;            // log2-partitions of the two rows; the node's weight
+    // ends the task for the sweeping waves
+    auto release_waves = [&]() __attribute__((always_inline)) {
+        if (lane == 0) g_cmd.kind = kCmdDone;
+        __syncthreads();                                  // B
+    };
+    // one more sweep by all four waves; the team's sums come back
+    auto sweep = [&](int kind, const ResidualConsts& rc, float sp, float sq, int m, int naive, double& s0, double& s1) __attribute__((always_inline)) {
+        if (lane == 0) {
+            g_cmd.kind = kind; g_cmd.nAt = rc.nAt; g_cmd.nAd = rc.nAd; g_cmd.rho = rc.rho;
+            g_cmd.sp = sp; g_cmd.sq = sq; g_cmd.m = m; g_cmd.naive = naive;
+        }
+        __syncthreads();                                  // B
+        SweepCmd cmd;
+        cmd.kind = kind; cmd.nAt = uniform_f32(rc.nAt); cmd.nAd = uniform_f32(rc.nAd); cmd.rho = uniform_f32(rc.rho);
+        cmd.sp = sp; cmd.sq = sq; cmd.m = m; cmd.naive = naive;
+        run_sweep<E, KIND>(pair, cmd, k32, 0, lane);
+        __syncthreads();                                  // A
+        collect_sums(team, s0, s1);
+    };
+    // W(c) for one c
+    auto residual_mass = [&](double cc) __attribute__((always_inline)) -> double {
+        const ResidualConsts rc = cold_residual_consts(At_, Ad_, cc);
+        double s0, s1;
+        sweep(kCmdMass, rc, 0.f, 0.f, 0, 0, s0, s1);
+        return uniform_f64(uniform_f64(rc.scale) * s0);
+    };
+
+    if (lead) atomicAdd(&a.counters[resumed ? MPV_COUNTER_NODE_TASKS_RESUMED : MPV_COUNTER_NODE_TASKS_RUN], 1u);
+    // are teams idle?  Asked now, needed when this task hands on to the next (the leader's business)
+    int idle_now = 0;
+    if (lead) idle_now = ld_relaxed(&ws.qctl[4 + 2 * kMaxClasses]);
+    const bool split_here = METHOD == MPV_METHOD_TRAVERSAL && a.lazy && !resumed && n == q.split_node;
+    const bool idle_seen = (flags & kFlagIdle) != 0;
 
     // ---- the children's tokens and uniforms: fetched now, so that their latency hides behind
     //      the sweep (lane j looks after child j; every member fetches them: they are inputs)
     __shared__ int ch_tok[MPV_MAX_CHILDREN];
     __shared__ float ch_zt[MPV_MAX_CHILDREN], ch_zd[MPV_MAX_CHILDREN];
     __shared__ float ch_u[MPV_MAX_CHILDREN];
-    __shared__ double sh_a0;
-    __shared__ float sh_un;
     int pf_x = -1;
     float pf_u = 2.f;
-    if (threadIdx.x < k && a.tokens) {
-        const size_t bc = static_cast<size_t>(b) * a.N + tree.child_list[tree.child_off[n] + threadIdx.x];
+    if (lane < k && a.tokens) {
+        const size_t bc = static_cast<size_t>(b) * N + tree.child_list[tree.child_off[n] + lane];
         pf_x = a.tokens[bc];
         if (!a.estimate) pf_u = a.uniforms[bc];
     }
-    if (threadIdx.x == kWave && !a.estimate) pf_u = a.uniforms[bn];        // the node's own uniform
+    if (lane == MPV_MAX_CHILDREN && !a.estimate) pf_u = a.uniforms[bn];        // the node's own uniform
     T pf_t = 0, pf_d = 0;       // kept as stored until the sweep is over: touching them now would wait for every load above
     if (pf_x >= 0 && pf_x < V) {
         pf_t = zt[pf_x];
@@ -789,56 +970,100 @@ __device__ __attribute__((noinline)) void run_node_task(const Launch* launch, Te
         const int cn = tree.child_list[tree.child_off[n]];
         if (tree.nchild[cn] > 0) {
             child_ahead = true;
-            if (lead) append_task(tree, ws, tree.cls[cn], b * a.N + cn);
+            if (lead) append_task(tree, ws, tree.cls[cn], b * N + cn);
         }
     }
 
     // ---- softmax statistics of both rows: the one read of the pair from memory
-    double At, Ad, wa = 1.0;
+    float un = 2.f;                                   // the node's own uniform
     {
         PairStatsRawF<E> f;
         f.t.init(); f.d.init(); f.k32 = k32;
         pair.first_pass(f);
-        if (threadIdx.x < k) { ch_tok[threadIdx.x] = pf_x; ch_u[threadIdx.x] = pf_u; ch_zt[threadIdx.x] = E::load_one(&pf_t); ch_zd[threadIdx.x] = E::load_one(&pf_d); }
-        if (threadIdx.x == kWave) sh_un = pf_u;
-        if (threadIdx.x == 0) {
-            // Traversal: the starting weight comes from the parent's task, which published it
-            // before it queued this task (or publishes it shortly, if this task was queued ahead).
-            // The leader fetches it and passes it on with the statistics.
-            double a0 = 1.0;
-            if (leader && METHOD == MPV_METHOD_TRAVERSAL && n != 0) {
-                // value and "ready" flag are one 64-bit word (a weight is never NaN), read and
-                // written with relaxed device-scope atomics: no fence, no cache invalidation
-                unsigned long long bits = kNotReady;
-                for (int spin = 0; spin < kMaxSpins; ++spin) {
-                    bits = ld_relaxed(reinterpret_cast<const unsigned long long*>(&ws.a0[bn]));
-                    if (bits != kNotReady) break;
-                    if (wall_clock64() - team.t_start > kLaunchTimeoutTicks) break;
-                    __builtin_amdgcn_s_sleep(32);
-                }
-                if (bits != kNotReady) {
-                    a0 = __longlong_as_double(static_cast<long long>(bits));
-                } else {            // the parent's task never published it (must never happen): the subtree is written off
-                    a0 = 0.0;
-                    atomicAdd(&a.counters[MPV_COUNTER_DEPENDENCY_TIMEOUT], 1u);
-                }
+        if (lane < k) { ch_tok[lane] = pf_x; ch_u[lane] = pf_u; ch_zt[lane] = E::load_one(&pf_t); ch_zd[lane] = E::load_one(&pf_d); }
+        un = lane_f32(pf_u, MPV_MAX_CHILDREN);
+        // Traversal: the starting weight comes from the parent's task, which published it
+        // before it queued this task (or publishes it shortly, if this task was queued ahead).
+        // The leader fetches it and passes it on with the statistics.
+        double a0 = 1.0;
+        if (lead && METHOD == MPV_METHOD_TRAVERSAL && n != 0) {
+            // value and "ready" flag are one 64-bit word (a weight is never NaN), read and
+            // written with relaxed device-scope atomics: no fence, no cache invalidation
+            unsigned long long bits = kNotReady;
+            for (int spin = 0; spin < kMaxSpins; ++spin) {
+                bits = ld_relaxed(reinterpret_cast<const unsigned long long*>(&ws.a0[bn]));
+                if (bits != kNotReady) break;
+                if (wall_clock64() - team.t_start > kLaunchTimeoutTicks) break;
+                __builtin_amdgcn_s_sleep(32);
             }
-            sh_a0 = a0;
+            if (bits != kNotReady) {
+                a0 = __longlong_as_double(static_cast<long long>(bits));
+            } else {            // the parent's task never published it (must never happen): the subtree is written off
+                a0 = 0.0;
+                atomicAdd(&a.counters[MPV_COUNTER_DEPENDENCY_TIMEOUT], 1u);
+            }
         }
-        __syncthreads();
-        team_stats(team, f.t, f.d, sh_a0, At, Ad, wa, ws, a);
-        if (METHOD != MPV_METHOD_TRAVERSAL) wa = 1.0;
+        a0 = lane_f64(a0, 0);
+        // lanes to their wave's largest reference, waves to the workgroup's, members to the team's
+        const float Mt_w = wave_max(f.t.mk), Md_w = wave_max(f.d.mk);
+        const double st_w = wave_sum((f.t.s > 0.f) ? static_cast<double>(f.t.s * fast_exp2(f.t.mk - Mt_w)) : 0.0);
+        const double sd_w = wave_sum((f.d.s > 0.f) ? static_cast<double>(f.d.s * fast_exp2(f.d.mk - Md_w)) : 0.0);
+        if (lane == 0) {
+            g_sh.partf[0][0] = Mt_w; g_sh.partf[0][1] = Md_w;
+            g_sh.part[0][0] = st_w; g_sh.part[0][1] = sd_w;
+        }
+        __syncthreads();                                  // A: every wave's partials are there
+        team.seq++;
+        float Mt = g_sh.partf[0][0], Md = g_sh.partf[0][1];
+#pragma unroll
+        for (int w = 1; w < kTaskWaves; ++w) { Mt = fmaxf(Mt, g_sh.partf[w][0]); Md = fmaxf(Md, g_sh.partf[w][1]); }
+        double st = 0.0, sd = 0.0;
+#pragma unroll
+        for (int w = 0; w < kTaskWaves; ++w) {
+            st += g_sh.part[w][0] * static_cast<double>(fast_exp2(g_sh.partf[w][0] - Mt));
+            sd += g_sh.part[w][1] * static_cast<double>(fast_exp2(g_sh.partf[w][1] - Md));
+        }
+        unsigned mine = 0u;
+        switch (lane) {
+            case 0: mine = __float_as_uint(Mt); break;
+            case 1: mine = __float_as_uint(Md); break;
+            case 2: mine = half_of(st, 0); break;
+            case 3: mine = half_of(st, 1); break;
+            case 4: mine = half_of(sd, 0); break;
+            case 5: mine = half_of(sd, 1); break;
+            case 6: mine = half_of(a0, 0); break;
+            case 7: mine = half_of(a0, 1); break;
+            default: break;
+        }
+        exchange_words(team, mine);
+        __builtin_amdgcn_wave_barrier();
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        team.dead = g_sh.dead;
+        float MT = OnlineLse::kFloor, MD = OnlineLse::kFloor;
+        for (int m = 0; m < team.size; ++m) {
+            MT = fmaxf(MT, __uint_as_float(g_sh.words[m * kExchWords]));
+            MD = fmaxf(MD, __uint_as_float(g_sh.words[m * kExchWords + 1]));
+        }
+        double ST = 0.0, SD = 0.0;
+        for (int m = 0; m < team.size; ++m) {
+            ST += double_at(g_sh.words, m, 1) * static_cast<double>(fast_exp2(__uint_as_float(g_sh.words[m * kExchWords]) - MT));
+            SD += double_at(g_sh.words, m, 2) * static_cast<double>(fast_exp2(__uint_as_float(g_sh.words[m * kExchWords + 1]) - MD));
+        }
+        At_ = uniform_f64(static_cast<double>(MT) + cold_log2(ST));
+        Ad_ = uniform_f64(static_cast<double>(MD) + cold_log2(SD));
+        if (METHOD == MPV_METHOD_TRAVERSAL) wa = uniform_f64(double_at(g_sh.words, 0, 3));
     }
     RowStat rt, rd;
-    rt.A = At; rd.A = Ad; rt.m = 0.f; rd.m = 0.f;
+    rt.A = At_; rd.A = Ad_; rt.m = 0.f; rd.m = 0.f;
 
     // ---- per-child scalars and one residual-mass reduction per child
     if (METHOD == MPV_METHOD_TRAVERSAL && a.lazy && n != 0 && !(wa > 0.0)) {
         // queued ahead of its weight, which is 0: the parent has written off the whole subtree.
         // Nothing to do but to pass the news on to an only child queued ahead in turn.
+        release_waves();
         if (lead) {
             if (child_ahead) {
-                const size_t bc = static_cast<size_t>(b) * a.N + tree.child_list[tree.child_off[n]];
+                const size_t bc = static_cast<size_t>(b) * N + tree.child_list[tree.child_off[n]];
                 st_relaxed(reinterpret_cast<unsigned long long*>(&ws.a0[bc]), static_cast<unsigned long long>(__double_as_longlong(0.0)));
             }
             wait_memory();
@@ -888,17 +1113,11 @@ __device__ __attribute__((noinline)) void run_node_task(const Launch* launch, Te
                 x = uniform_f64(cand);
             }
             const ResidualConsts rc = cold_residual_consts(rt.A, rd.A, x);
-            ResidualMassSlopeRawF<E> f;
-            f.init();
-            f.k32 = k32; f.nAt = rc.nAt; f.nAd = rc.nAd; f.rho = uniform_f32(rc.rho);
-            pair.replay(f);
-            double sums[2] = {static_cast<double>(f.acc0) + static_cast<double>(f.acc1),
-                              static_cast<double>(f.q0) + static_cast<double>(f.q1)};
-            block_sum2<kTaskBlock>(sums[0], sums[1], g_sh.scratch);
-            team_sum(team, sums, g_sh.words, ws, a);
+            double sum_w, sum_q;
+            sweep(kCmdMassSlope, rc, 0.f, 0.f, 0, 0, sum_w, sum_q);
             const double scale = uniform_f64(rc.scale);
-            const double Wx = uniform_f64(scale * sums[0]);
-            const double dWx = -uniform_f64(scale * sums[1]) / x;       // the sweep added up rho q over {p > rho q}
+            const double Wx = uniform_f64(scale * sum_w);
+            const double dWx = -uniform_f64(scale * sum_q) / x;       // the sweep added up rho q over {p > rho q}
             const double Dx = fmin(fmax((Wx + x - 1.0) / x, 0.0), 1.0);
             const double dDx = (dWx + 1.0 - Dx) / x;
             const double kk = static_cast<double>(k);
@@ -917,17 +1136,6 @@ __device__ __attribute__((noinline)) void run_node_task(const Launch* launch, Te
             }
         }
     }
-    // W(c) for one c: a sweep over the part on chip, block sum, team sum
-    auto residual_mass = [&](double cc) __attribute__((always_inline)) -> double {
-        const ResidualConsts rc = cold_residual_consts(rt.A, rd.A, cc);
-        ResidualMassRawF<E> f;
-        f.init();
-        f.k32 = k32; f.nAt = rc.nAt; f.nAd = rc.nAd; f.rho = uniform_f32(rc.rho);
-        pair.replay(f);
-        double sums[1] = {block_sum<kTaskBlock>(static_cast<double>(f.acc0) + static_cast<double>(f.acc1), g_sh.scratch)};
-        team_sum(team, sums, g_sh.words, ws, a);
-        return uniform_f64(uniform_f64(rc.scale) * sums[0]);
-    };
     if (ACCEPT) {
         // Acceptance rate of this node (App. C): the chance that the solver's output is one of k draft
         // tokens drawn i.i.d. from q.  For SpecInfer and SpecTr the part of App. C's formulas that
@@ -949,15 +1157,15 @@ __device__ __attribute__((noinline)) void run_node_task(const Launch* launch, Te
             }
             alpha = 1.0 - Wc;
         } else {
-            AcceptanceF<E> f;
             const float At_hi = static_cast<float>(rt.A), Ad_hi = static_cast<float>(rd.A);
-            f.init(k32, -At_hi, -Ad_hi, static_cast<float>(cold_exp2(static_cast<double>(At_hi) - rt.A)),
-                   static_cast<float>(cold_exp2(static_cast<double>(Ad_hi) - rd.A)), a.walk == 1 ? k : k - 1, a.walk == 2);
-            pair.replay(f);
-            double sums[1] = {block_sum<kTaskBlock>(static_cast<double>(f.acc0) + static_cast<double>(f.acc1), g_sh.scratch)};
-            team_sum(team, sums, g_sh.words, ws, a);
-            alpha = uniform_f64(sums[0]);
+            ResidualConsts rc;
+            rc.nAt = -At_hi; rc.nAd = -Ad_hi; rc.rho = 0.f; rc.scale = 1.0;
+            double s0, s1;
+            sweep(kCmdAcceptance, rc, static_cast<float>(cold_exp2(static_cast<double>(At_hi) - rt.A)),
+                  static_cast<float>(cold_exp2(static_cast<double>(Ad_hi) - rd.A)), a.walk == 1 ? k : k - 1, a.walk == 2 ? 1 : 0, s0, s1);
+            alpha = s0;
         }
+        release_waves();
         if (lead) {
             a.alpha[bn] = static_cast<float>(fmin(fmax(alpha, 0.0), 1.0));
             atomicAdd(&ws.qctl[1], 1);
@@ -969,7 +1177,7 @@ __device__ __attribute__((noinline)) void run_node_task(const Launch* launch, Te
         // to get at the residual that follows its rejection
         const bool redone = resumed && j == 0;
         const int cn = tree.child_list[tree.child_off[n] + j];
-        const size_t bc = static_cast<size_t>(b) * a.N + cn;
+        const size_t bc = static_cast<size_t>(b) * N + cn;
         const int x = ch_tok[j];
         double px = 0.0, qx = 0.0;
         const bool tok_ok = (x >= 0 && x < V);
@@ -1027,7 +1235,7 @@ __device__ __attribute__((noinline)) void run_node_task(const Launch* launch, Te
         // already knows what it will run next (a child's task).
         if (leader && j == k - 1 && !asked && (own_child < 0 || own_given) &&
             !(METHOD == MPV_METHOD_SPECINFER && a.lazy && child_accepted && tree.nchild[cn] > 0)) {
-            if (threadIdx.x == 0) st_relaxed(&ws.mailbox[team.id], kMailboxSoon);
+            if (lane == 0) st_relaxed(&ws.mailbox[team.id], kMailboxSoon);
             asked = true;
         }
         if (lead && !redone) {
@@ -1041,7 +1249,7 @@ __device__ __attribute__((noinline)) void run_node_task(const Launch* launch, Te
                     // while this task goes on with the sweeps that follow.
                     if (run_child && (!first_to_run || own_given) && !child_ahead) {
                         wait_memory();                    // its starting weight has been written
-                        append_task(tree, ws, tree.cls[cn], b * a.N + cn);
+                        append_task(tree, ws, tree.cls[cn], b * N + cn);
                     }
                 }
             } else {
@@ -1116,29 +1324,32 @@ __device__ __attribute__((noinline)) void run_node_task(const Launch* launch, Te
                 else if (i > 0 && lead)
                     atomicAdd(&a.counters[MPV_COUNTER_BAD_TOKEN], 1u);
                 if (lead) {
-                    st_shared_f64(&ws.aux[static_cast<size_t>(b) * a.N + ci], r);
-                    if (i > 0) st_shared_f64(&ws.atest[static_cast<size_t>(b) * a.N + ci], 0.0);   // never tested
+                    st_shared_f64(&ws.aux[static_cast<size_t>(b) * N + ci], r);
+                    if (i > 0) st_shared_f64(&ws.atest[static_cast<size_t>(b) * N + ci], 0.0);   // never tested
                 }
                 settled_bits |= 1ull << tree.rank[ci];
             }
             break;
         }
     }
+    release_waves();
 
-    // ---- what follows from this task: the leader's business
+    // ---- what follows from this task: the leader's business (its first wave's)
     if (!leader) return;
+    own_flags = uniform_i32(idle_now) != 0 ? kFlagIdle : 0;
     if (paused) {
         // nothing is settled yet; the first child's task is run next by this team
-        own_task = b * a.N + tree.child_list[tree.child_off[n]];
-        if (threadIdx.x == 0) {
+        own_task = b * N + tree.child_list[tree.child_off[n]];
+        team_announce(team, own_task, own_flags);
+        if (lane == 0) {
             (void)atomicAdd(&ws.qctl[0], 1);
             wait_memory();                            // counted (and the child's weight written) before this task counts as finished
             atomicAdd(&ws.qctl[1], 1);
         }
         return;
     }
-    __shared__ int sh_push_sample, sh_settled, sh_resume;
-    if (threadIdx.x == 0) {
+    int push_sample_i = 0, settled_i = 0, resume_i = 0;
+    if (lane == 0) {
         st_shared_f64(&ws.At[bn], rt.A);
         st_shared_f64(&ws.Ad[bn], rd.A);
         st_shared_f64(&ws.cfin[bn], c);
@@ -1159,7 +1370,7 @@ __device__ __attribute__((noinline)) void run_node_task(const Launch* launch, Te
             if (METHOD == MPV_METHOD_TRAVERSAL && n != 0) {
                 const unsigned long long own = 1ull << tree.rank[n];
                 settled_bits |= own;
-                if (static_cast<double>(sh_un) < wa) accepted_bits |= own;
+                if (static_cast<double>(un) < wa) accepted_bits |= own;
             }
             wait_memory();                            // results written through before they are announced
             if (accepted_bits) {
@@ -1177,7 +1388,7 @@ __device__ __attribute__((noinline)) void run_node_task(const Launch* launch, Te
                 const int first = __ffsll(static_cast<long long>(open)) - 1;   // the root's bit is always set
                 settled = ((known >> first) & 1ull) != 0ull;
             } else {
-                const unsigned long long all = (a.N >= 64) ? ~0ull : ((1ull << a.N) - 1ull);
+                const unsigned long long all = (N >= 64) ? ~0ull : ((1ull << N) - 1ull);
                 settled = known == all;
             }
             push_sample = settled && decided_before == 0 && atomicCAS(&ws.decided[b], 0, 1) == 0;
@@ -1193,56 +1404,63 @@ __device__ __attribute__((noinline)) void run_node_task(const Launch* launch, Te
                 resume = (known & m) == m && (known_before & m) != m && (acc & m) == 0ull;
             }
         }
-        sh_push_sample = push_sample ? 1 : 0;
-        sh_settled = settled_tree ? 1 : 0;
-        sh_resume = resume ? 1 : 0;
+        push_sample_i = push_sample ? 1 : 0;
+        settled_i = settled_tree ? 1 : 0;
+        resume_i = resume ? 1 : 0;
     }
-    __syncthreads();
+    push_sample_i = uniform_i32(push_sample_i);
+    settled_i = uniform_i32(settled_i);
+    resume_i = uniform_i32(resume_i);
     // What follows from this task.  One task is run by this team itself, next (no queue,
     // no waiting): the sampling if this task settled the tree, else the first child that needs
     // its own task (Traversal) or the accepted child (SpecInfer).  The other children are queued.
-    if (sh_push_sample) {
-        own_task = a.B * a.N + b;
-    } else if (sh_resume) {
-        own_task = a.B * a.N + a.B + b;
+    if (push_sample_i) {
+        own_task = B * N + b;
+    } else if (resume_i) {
+        own_task = B * N + B + b;
     } else if (METHOD == MPV_METHOD_TRAVERSAL) {
-        if (own_child >= 0 && !own_given && !sh_settled) own_task = b * a.N + tree.child_list[tree.child_off[n] + own_child];
+        if (own_child >= 0 && !own_given && !settled_i) own_task = b * N + tree.child_list[tree.child_off[n] + own_child];
     } else if (a.lazy && next_node >= 0 && tree.nchild[next_node] > 0) {
-        own_task = b * a.N + next_node;
+        own_task = b * N + next_node;
     }
-    if (threadIdx.x == 0) {
+    // the others hear of it at once (they are waiting for the next task by now)
+    if (own_task >= 0) team_announce(team, own_task, own_flags);
+    if (lane == 0) {
         if (own_task >= 0) {
             (void)atomicAdd(&ws.qctl[0], 1);
             wait_memory();
         }
         // (cannot happen: a task that settles the tree or completes a subtree has no child left to run)
-        if (METHOD == MPV_METHOD_TRAVERSAL && own_child >= 0 && !own_given && !sh_settled && (sh_push_sample || sh_resume)) {
+        if (METHOD == MPV_METHOD_TRAVERSAL && own_child >= 0 && !own_given && !settled_i && (push_sample_i || resume_i)) {
             const int cn = tree.child_list[tree.child_off[n] + own_child];
-            append_task(tree, ws, tree.cls[cn], b * a.N + cn);
+            append_task(tree, ws, tree.cls[cn], b * N + cn);
         }
+        wait_memory();                                // every new task has been counted
+        atomicAdd(&ws.qctl[1], 1);
     }
-    __syncthreads();                                  // every new task has been counted
-    if (threadIdx.x == 0) atomicAdd(&ws.qctl[1], 1);
 }
 
 template <class E, int KIND>
-__global__ __launch_bounds__(kTaskBlock) __attribute__((amdgpu_waves_per_eu(4, 4)))
+__global__ __launch_bounds__(kTaskBlock) __attribute__((amdgpu_waves_per_eu(3, 3)))
 void node_task_kernel(const Launch* __restrict__ launch) {
     // KIND: MPV_METHOD_SPECINFER (all top-down rules) or MPV_METHOD_TRAVERSAL, or kKindAcceptance: the
     // top-down kernel reduced to what the acceptance rates need (an instantiation of its own, so that
     // its extra sweeps do not weigh on the register allocation of the verification kernels)
     constexpr bool ACCEPT = KIND == kKindAcceptance;
     constexpr int METHOD = ACCEPT ? MPV_METHOD_SPECINFER : KIND;
-    const QueuePlan& q = launch->q;
-    const Workspace& ws = launch->ws;
-    const Args& a = launch->a;
-
     __shared__ int sh_task, sh_flags;
-    // The tree tables are read from LDS, copied there from the workspace (init_kernel put them
-    // there): a table that is indexed with a value the compiler keeps in a vector register
-    // would otherwise be copied, whole, into every lane's private memory.
+    // The launch parameters and the tree tables are read from LDS, copied there from the
+    // workspace (init_kernel put them there): as kernel arguments, handed on by reference or
+    // indexed with a value the compiler keeps in a vector register, they were copied, whole,
+    // into every lane's private memory.
+    for (int w = threadIdx.x; w < static_cast<int>(sizeof(Launch) / sizeof(int)); w += kTaskBlock)
+        g_launch_words[w] = reinterpret_cast<const int*>(launch)[w];
     for (int w = threadIdx.x; w < static_cast<int>(sizeof(TreeDesc) / sizeof(int)); w += kTaskBlock)
-        reinterpret_cast<int*>(&g_tree)[w] = reinterpret_cast<const int*>(ws.tree)[w];
+        reinterpret_cast<int*>(&g_tree)[w] = reinterpret_cast<const int*>(launch->ws.tree)[w];
+    __syncthreads();
+    const QueuePlan& q = lds_launch().q;
+    const Workspace& ws = lds_launch().ws;
+    const Args& a = lds_launch().a;
     const TreeDesc& tree = g_tree;                // the task loop starts with a barrier
 
     // ---- this workgroup's place in its team
@@ -1271,75 +1489,69 @@ void node_task_kernel(const Launch* __restrict__ launch) {
     }
 
     const bool drop_settled = METHOD == MPV_METHOD_TRAVERSAL && a.lazy != 0;
+    const int wave = uniform_i32(static_cast<int>(threadIdx.x) / kWave);
+    // The task loop's own state lives in the first wave (the others only sweep):
     int previous_task = -4;                           // last task taken from the mailbox: none yet
     bool asked = true;                                // the team starts out waiting
-    int own_task = -1;                                // a task this team produced for itself
+    int own_task = -1;                                // a task this team produced for itself (already announced to the team)
+    int own_flags = 0;
     for (;;) {
     __syncthreads();                                  // the previous task is done with LDS
-    if (team.dead) break;
-    int task, flags = 0;
-    if (leader) {
-        bool from_queue = false;
-        if (own_task >= 0) {
-            task = own_task;
-            own_task = -1;
-        } else {
-            if (threadIdx.x < kWave) {
+    if (wave == 0) {
+        int task = kTaskExit, flags = 0;
+        if (team.dead) {
+            task = kTaskExit;
+        } else if (leader) {
+            for (;;) {
+                if (own_task >= 0) {
+                    task = own_task;
+                    flags = own_flags;
+                    own_task = -1;
+                    break;
+                }
                 if (!asked) {
                     if (threadIdx.x == 0) st_relaxed(&ws.mailbox[team.id], kMailboxWaiting);
                     wait_memory();
                 }
-                const int t = acquire_task(launch, team.id, previous_task, drop_settled, team.t_start);
-                if (threadIdx.x == 0) sh_task = t;
+                task = acquire_task(team.id, previous_task, drop_settled, team.t_start);
+                // are teams idle (as of the last round of dispatching)?
+                flags = uniform_i32(ld_relaxed(&ws.qctl[4 + 2 * kMaxClasses])) != 0 ? kFlagIdle : 0;
+                previous_task = task;
+                asked = false;
+                // tasks without any V-wide work are the leader's alone; everything else is announced
+                const bool solo = task != kTaskExit && task >= a.B * a.N && task < a.B * a.N + a.B && (ACCEPT || a.estimate);
+                if (solo) {
+                    if (!ACCEPT) estimate_wave<METHOD>(tree, ws, a, task - a.B * a.N);
+                    if (threadIdx.x == 0) {
+                        wait_memory();
+                        atomicAdd(&ws.qctl[1], 1);
+                    }
+                    continue;
+                }
+                team_announce(team, task, flags);
+                break;
             }
-            __syncthreads();
-            task = sh_task;
-            previous_task = task;
-            asked = false;
-            from_queue = true;
-        }
-        (void)from_queue;
-        // are teams idle (as of the last round of dispatching)?
-        if (threadIdx.x == 0) sh_flags = ld_relaxed(&ws.qctl[4 + 2 * kMaxClasses]) != 0 ? kFlagIdle : 0;
-        __syncthreads();
-        flags = sh_flags;
-        // tasks without any V-wide work are the leader's alone; everything else is announced
-        const bool solo = task != kTaskExit && task >= a.B * a.N && task < a.B * a.N + a.B && (ACCEPT || a.estimate);
-        if (!solo && threadIdx.x < kWave) team_announce(team, task, flags);
-        if (solo) {
-            if (!ACCEPT && threadIdx.x < kWave) estimate_wave<METHOD>(tree, ws, a, task - a.B * a.N);
-            if (threadIdx.x == 0) {
-                wait_memory();
-                atomicAdd(&ws.qctl[1], 1);
-            }
-            continue;
-        }
-        if (!(threadIdx.x < kWave)) team.tseq++;      // (the first wave counted it in team_announce)
-    } else {
-        if (threadIdx.x < kWave) {
-            int f = 0;
-            const int t = team_listen(team, f, ws);
-            if (threadIdx.x == 0) { sh_task = t; sh_flags = f; }
         } else {
-            team.tseq++;
+            task = team_listen(team, flags, ws);
         }
-        __syncthreads();
-        task = sh_task;
-        flags = sh_flags;
+        if (threadIdx.x == 0) { sh_task = task; sh_flags = flags; }
     }
+    __syncthreads();
+    const int task = uniform_i32(sh_task), flags = uniform_i32(sh_flags);
     if (task == kTaskExit) break;
-    task = __builtin_amdgcn_readfirstlane(task);
-    flags = __builtin_amdgcn_readfirstlane(flags);
-    const bool lead = leader && threadIdx.x == 0;     // the one lane that talks to the rest of the launch
     if (task >= a.B * a.N && task < a.B * a.N + a.B) {
         // the tree's outcome is settled: walk and bonus token
-        if (leader && !asked) {
+        if (wave == 0 && leader && !asked) {
             if (threadIdx.x == 0) st_relaxed(&ws.mailbox[team.id], kMailboxSoon);
             asked = true;
         }
-        const int next = sample_task<E, METHOD>(launch, team, task - a.B * a.N);
-        if (leader) {
-            if (next >= 0) own_task = next;           // a token-following walk goes on
+        const int next = sample_task<E, METHOD>(team, task - a.B * a.N);
+        if (wave == 0 && leader) {
+            if (next >= 0) {                          // a token-following walk goes on
+                own_task = next;
+                own_flags = flags;
+                team_announce(team, own_task, own_flags);
+            }
             if (threadIdx.x == 0) {
                 if (next >= 0) {
                     (void)atomicAdd(&ws.qctl[0], 1);
@@ -1350,7 +1562,7 @@ void node_task_kernel(const Launch* __restrict__ launch) {
         }
         continue;
     }
-    run_node_task<E, KIND>(launch, team, task, flags, asked, own_task);
+    run_node_task<E, KIND>(team, task, flags, asked, own_task, own_flags);
     }   // task loop
 }
 
@@ -1553,11 +1765,10 @@ struct ResidualTile {
 // member adds up the masses of its tiles, one exchange gives everybody every member's total, and
 // the member whose run contains u * R finds the token.
 template <class E, int METHOD>
-__device__ __attribute__((noinline)) int sample_task(const Launch* launch, Team& team_io, int b_in) {
+__device__ __attribute__((noinline)) int sample_task(Team& team_io, int b_in) {
     using T = typename E::T;
-    const Launch* const L = uniform_ptr(launch);
-    const Args a = uniform_struct(L->a);
-    const Workspace ws = uniform_struct(L->ws);
+    const Args& a = lds_launch().a;
+    const Workspace& ws = lds_launch().ws;
     const TreeDesc& tree = g_tree;
     const int b = uniform_i32(b_in);
     float* const tile_sum = reinterpret_cast<float*>(g_rows);
@@ -1603,7 +1814,9 @@ __device__ __attribute__((noinline)) int sample_task(const Launch* launch, Team&
         if (e_hi > e_lo) sweep_row<E, kTaskBlock, 2 * kTaskUnroll>(zt + e_lo, e_hi - e_lo, f);
         OnlineLse none; none.init();
         double unused_d, unused_a0;
-        team_stats(team, f.t, none, 0.0, At, unused_d, unused_a0, ws, a);
+        __shared__ double sh_no_weight;
+        if (threadIdx.x == 0) sh_no_weight = 0.0;
+        team_stats(team, f.t, none, &sh_no_weight, At, unused_d, unused_a0);
         if (lead) ws.At[bn] = At;
     } else {
         At = ld_shared_f64(&ws.At[bn]);
@@ -1684,7 +1897,7 @@ __device__ __attribute__((noinline)) int sample_task(const Launch* launch, Team&
         unsigned mine = 0u;
         if (threadIdx.x == 0) mine = half_of(local_total, 0);
         if (threadIdx.x == 1) mine = half_of(local_total, 1);
-        team_exchange(team, mine, g_sh.words, ws, a);
+        team_exchange(team, mine);
     }
     double total = 0.0, before = 0.0;
     for (int m = 0; m < team.size; ++m) {
@@ -1782,7 +1995,7 @@ __device__ __attribute__((noinline)) int sample_task(const Launch* launch, Team&
         {
             unsigned mine = 0u;
             if (threadIdx.x == 0 && mine_it) mine = static_cast<unsigned>(sh_tile);
-            team_exchange(team, mine, g_sh.words, ws, a);
+            team_exchange(team, mine);
         }
         tok = static_cast<int>(g_sh.words[owner * kExchWords]);
         if (wave == 0) {
@@ -2046,13 +2259,26 @@ static int compute_units() {
 // as many teams as there can be tasks at once, four workgroups per compute unit at most.
 struct Shape { int team_size, teams, part_vecs, same_xcd; };
 
+// Workgroups of a task kernel that one compute unit holds at a time, as the runtime computes it
+// from the kernel's registers and LDS (3 by design); a team never has more members than can be
+// resident together.
+template <class K>
+static int resident_per_cu(K kernel) {
+    int n = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, kernel, kTaskBlock, 0) != hipSuccess || n < 1) {
+        (void)hipGetLastError();
+        n = 1;
+    }
+    return n;
+}
+
 template <class E>
-static Shape launch_shape(const mpv_problem* p, int tasks) {
+static Shape launch_shape(const mpv_problem* p, int tasks, int per_cu) {
     Shape s;
     const int nvec = (p->V + E::VEC - 1) / E::VEC;
     int g = 1;
     while (g < kMaxTeam && static_cast<long long>(g) * kPartCapacity < nvec) g *= 2;
-    const int slots = 4 * compute_units() < kMaxGrid ? 4 * compute_units() : kMaxGrid;      // workgroups that can be resident
+    const int slots = per_cu * compute_units() < kMaxGrid ? per_cu * compute_units() : kMaxGrid;      // workgroups that can be resident
     int teams = slots / g;
     if (teams > kMaxTeams) teams = kMaxTeams;
     if (teams > tasks) teams = tasks;
@@ -2101,7 +2327,10 @@ static int launch_all(const mpv_problem* p, const Plan& plan, const Workspace& w
     }
     for (int c = 0; c <= q.nclass; ++c) tree.class_off[c] = q.off[c];
     const int tasks = q.off[q.nclass];
-    const Shape shape = launch_shape<E>(p, tasks);
+    static const int per_cu[3] = {resident_per_cu(node_task_kernel<E, MPV_METHOD_SPECINFER>),
+                                  resident_per_cu(node_task_kernel<E, MPV_METHOD_TRAVERSAL>),
+                                  resident_per_cu(node_task_kernel<E, kKindAcceptance>)};
+    const Shape shape = launch_shape<E>(p, tasks, per_cu[a.estimate == 2 ? 2 : (p->method == MPV_METHOD_TRAVERSAL ? 1 : 0)]);
     q.teams = shape.teams;
     q.team_size = shape.team_size;
     q.part_vecs = shape.part_vecs;
