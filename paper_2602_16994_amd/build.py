@@ -18,6 +18,9 @@ HIPCC_FLAGS = [
     "-fPIC",
     # no compiler-generated packed-fp32 instructions (v_pk_*_f32)
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # the task loops are long and cold: loop-invariant constants hoisted out of them would be
+    # held in registers across whole tasks and push the kept row pair into scratch memory
+    "-mllvm", "-disable-machine-licm",
     "-Wno-unused-command-line-argument",
 ]
 

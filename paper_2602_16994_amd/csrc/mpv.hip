@@ -346,16 +346,32 @@ __global__ void init_kernel(QueuePlan q, TreeDesc tree, Workspace ws, Args a) {
 // never queued).  Every wait is bounded.  Only the leader (member 0) of a team talks to the queue.
 
 __device__ __forceinline__ int ld_relaxed(const int32_t* p) {
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return __hip_atomic_load(as_global(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 __device__ __forceinline__ unsigned long long ld_relaxed(const unsigned long long* p) {
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return __hip_atomic_load(as_global(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 __device__ __forceinline__ void st_relaxed(int32_t* p, int v) {
-    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(as_global(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 __device__ __forceinline__ void st_relaxed(unsigned long long* p, unsigned long long v) {
-    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(as_global(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// The read-modify-write operations of the task kernels (relaxed, device scope, like HIP's own of
+// these names, which they hide inside this namespace) on pointers known to be global.
+__device__ __forceinline__ int atomicAdd(int* p, int v) {
+    return __hip_atomic_fetch_add(as_global(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ unsigned atomicAdd(unsigned* p, unsigned v) {
+    return __hip_atomic_fetch_add(as_global(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ unsigned long long atomicOr(unsigned long long* p, unsigned long long v) {
+    return __hip_atomic_fetch_or(as_global(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ int atomicCAS(int* p, int expected, int desired) {
+    __hip_atomic_compare_exchange_strong(as_global(p), &expected, desired, __ATOMIC_RELAXED, __ATOMIC_RELAXED,
+                                         __HIP_MEMORY_SCOPE_AGENT);
+    return expected;
 }
 // all loads, stores and atomics issued so far by this lane have been performed
 __device__ __forceinline__ void wait_memory() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
@@ -522,13 +538,13 @@ __device__ __attribute__((noinline)) int acquire_task(int team_in, int previous_
 // device-scope atomics.  Order between them is the writer's business: it waits for its stores
 // to be acknowledged (s_waitcnt vmcnt(0)) before the atomic that lets the reader start.
 __device__ __forceinline__ void st_shared_f64(double* p, double v) {
-    __hip_atomic_store(reinterpret_cast<unsigned long long*>(p),
+    __hip_atomic_store(as_global(reinterpret_cast<unsigned long long*>(p)),
                        static_cast<unsigned long long>(__double_as_longlong(v)), __ATOMIC_RELAXED,
                        __HIP_MEMORY_SCOPE_AGENT);
 }
 __device__ __forceinline__ double ld_shared_f64(const double* p) {
     return __longlong_as_double(static_cast<long long>(__hip_atomic_load(
-        reinterpret_cast<const unsigned long long*>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)));
+        as_global(reinterpret_cast<const unsigned long long*>(p)), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)));
 }
 
 // ------------------------------------------------------------------ teams
@@ -773,6 +789,7 @@ __device__ __forceinline__ void team_stats(Team& t, const OnlineLse& lt, const O
 // next task; the task it is to run next, already announced to the team, and its flags); only the
 // first wave's copies matter.
 
+constexpr int kCmdTask = 5;
 constexpr int kCmdDone = 0;          // the task is over
 constexpr int kCmdMass = 1;          // sum (p - rho q)_+
 constexpr int kCmdMassSlope = 2;     // the same and sum_{p > rho q} rho q       (SpecTr's root search)
@@ -850,70 +867,128 @@ __device__ __attribute__((noinline)) void run_node_task(Team& team_io, int task_
     const QueuePlan& q = lds_launch().q;
     const TreeDesc& tree = g_tree;
     // (what arrives as an argument arrives in vector registers: back to scalar ones)
-    const int task = uniform_i32(task_in), flags = uniform_i32(flags_in);
+    int task = uniform_i32(task_in), flags = uniform_i32(flags_in);
     const int wave = uniform_i32(static_cast<int>(threadIdx.x) / kWave), lane = threadIdx.x & (kWave - 1);
     uint4* const lds_t = g_rows;
     uint4* const lds_d = g_rows + kLdsVecs * kTaskBlock;
-
-    // (tree, node: made scalar explicitly, so that the table lookups below have uniform addresses)
     const int B = uniform_i32(a.B), N = uniform_i32(a.N), V = uniform_i32(a.V);
-    const bool resumed = task >= B * N + B;
-    const int b = uniform_i32(resumed ? task - (B * N + B) : task / N);
-    const int n = uniform_i32(resumed ? q.split_node : task % N);
-    const size_t bn = static_cast<size_t>(b) * N + n;
-    const T* zt = uniform_ptr(static_cast<const T*>(a.zt)) + bn * V;
-    const T* zd = uniform_ptr(static_cast<const T*>(a.zd)) + bn * V;
     const float k32 = uniform_f32(a.k32);
-    const int k = uniform_i32(tree.nchild[n]);
+    const int member = uniform_i32(team_io.member), team_size = uniform_i32(team_io.size);
 
-    // ---- the part of the pair this member keeps: every load goes out now
+    // what a task number stands for (tree, node: made scalar explicitly, so that the table lookups
+    // that follow have uniform addresses)
+    struct NodeView { int b, n, k; bool resumed; size_t bn; const T* zt; const T* zd; };
+    auto view_of = [&](int t) __attribute__((always_inline)) -> NodeView {
+        NodeView v;
+        v.resumed = t >= B * N + B;
+        v.b = uniform_i32(v.resumed ? t - (B * N + B) : t / N);
+        v.n = uniform_i32(v.resumed ? q.split_node : t % N);
+        v.bn = static_cast<size_t>(v.b) * N + v.n;
+        v.zt = uniform_ptr(static_cast<const T*>(a.zt)) + v.bn * V;
+        v.zd = uniform_ptr(static_cast<const T*>(a.zd)) + v.bn * V;
+        v.k = uniform_i32(tree.nchild[v.n]);
+        return v;
+    };
+
+    // ---- the part of the pair this member keeps on chip while a task runs
     RetainedPart<E, kTaskBlock, kRegVecs, kLdsVecs> pair;
-    int tid_l = threadIdx.x;
-    asm volatile("" : "+v"(tid_l));     // per-task copy: nothing derived from it is kept across tasks
-    pair.setup(zt, zd, V, lds_t, lds_d, tid_l, uniform_i32(team_io.member), uniform_i32(team_io.size), uniform_i32(q.part_vecs));
-    pair.issue_loads();
+    // the children's tokens, their two logits and the uniforms, for the first wave's scalar steps
+    __shared__ int ch_tok[MPV_MAX_CHILDREN];
+    __shared__ float ch_zt[MPV_MAX_CHILDREN], ch_zd[MPV_MAX_CHILDREN];
+    __shared__ float ch_u[MPV_MAX_CHILDREN + 1];      // last: the node's own uniform
 
     if (wave != 0) {
-        // ---- a sweeping wave: the statistics sweep, then whatever the first wave commands
-        {
-            PairStatsRawF<E> f;
-            f.t.init(); f.d.init(); f.k32 = k32;
-            pair.first_pass(f);
-            const float Mt_w = wave_max(f.t.mk), Md_w = wave_max(f.d.mk);
-            const double st_w = wave_sum((f.t.s > 0.f) ? static_cast<double>(f.t.s * fast_exp2(f.t.mk - Mt_w)) : 0.0);
-            const double sd_w = wave_sum((f.d.s > 0.f) ? static_cast<double>(f.d.s * fast_exp2(f.d.mk - Md_w)) : 0.0);
-            if (lane == 0) {
-                g_sh.partf[wave][0] = Mt_w; g_sh.partf[wave][1] = Md_w;
-                g_sh.part[wave][0] = st_w; g_sh.part[wave][1] = sd_w;
-            }
-        }
-        __syncthreads();                                  // A: the partials are there
+        // ---- a sweeping wave does what the first wave commands: it takes up a task (loads its
+        //      share of the pair and runs the statistics sweep) or sweeps once more
         for (;;) {
             __syncthreads();                              // B: the command is there
             const SweepCmd cmd = g_cmd;
-            if (uniform_i32(cmd.kind) == kCmdDone) break;
-            run_sweep<E, KIND>(pair, cmd, k32, wave, lane);
-            __syncthreads();                              // A
+            const int kind = uniform_i32(cmd.kind);
+            if (kind == kCmdDone) return;
+            if (kind == kCmdTask) {
+                const NodeView nv = view_of(uniform_i32(cmd.m));
+                int tid_l = threadIdx.x;
+                asm volatile("" : "+v"(tid_l));     // per-task copy: nothing derived from it is kept across tasks
+                pair.setup(nv.zt, nv.zd, V, lds_t, lds_d, tid_l, member, team_size, uniform_i32(q.part_vecs));
+                pair.issue_loads();
+                // The second wave also fetches what the scalar steps need of the children (lane j looks
+                // after child j): loads that depend on loads, kept off the first wave's path.  They
+                // return behind this wave's share of the pair, which the sweep waits for anyway.
+                int pf_x = -1;
+                float pf_u = 2.f;
+                T pf_t = 0, pf_d = 0;       // kept as stored until the sweep is over
+                if (wave == 1) {
+                    if (lane < nv.k && a.tokens) {
+                        const size_t bc = static_cast<size_t>(nv.b) * N + tree.child_list[tree.child_off[nv.n] + lane];
+                        pf_x = as_global(a.tokens)[bc];
+                        if (!a.estimate) pf_u = as_global(a.uniforms)[bc];
+                    }
+                    if (lane == MPV_MAX_CHILDREN && !a.estimate) pf_u = as_global(a.uniforms)[nv.bn];
+                    if (pf_x >= 0 && pf_x < V) {
+                        pf_t = as_global(nv.zt)[pf_x];
+                        pf_d = as_global(nv.zd)[pf_x];
+                    }
+                }
+                PairStatsRawF<E> f;
+                f.t.init(); f.d.init(); f.k32 = k32;
+                pair.first_pass(f);
+                if (wave == 1) {
+                    if (lane < nv.k) { ch_tok[lane] = pf_x; ch_u[lane] = pf_u; ch_zt[lane] = E::load_one(&pf_t); ch_zd[lane] = E::load_one(&pf_d); }
+                    if (lane == MPV_MAX_CHILDREN) ch_u[MPV_MAX_CHILDREN] = pf_u;
+                }
+                const float Mt_w = wave_max(f.t.mk), Md_w = wave_max(f.d.mk);
+                const double st_w = wave_sum((f.t.s > 0.f) ? static_cast<double>(f.t.s * fast_exp2(f.t.mk - Mt_w)) : 0.0);
+                const double sd_w = wave_sum((f.d.s > 0.f) ? static_cast<double>(f.d.s * fast_exp2(f.d.mk - Md_w)) : 0.0);
+                if (lane == 0) {
+                    g_sh.partf[wave][0] = Mt_w; g_sh.partf[wave][1] = Md_w;
+                    g_sh.part[wave][0] = st_w; g_sh.part[wave][1] = sd_w;
+                }
+            } else {
+                run_sweep<E, KIND>(pair, cmd, k32, wave, lane);
+            }
+            __syncthreads();                              // A: this wave's partial sums are there
         }
-        return;
     }
 
     // ================================================================ the first wave
-    Team team = uniform_struct(team_io);               // in registers while the task runs
+    Team team = uniform_struct(team_io);               // in registers while the tasks run
     bool asked = asked_io;
     int own_task = -1, own_flags = 0;
-    struct WriteBack {                                 // every way out hands the notes back
-        Team& t_out; Team& t; bool& a_out; bool& a; int& o_out; int& o; int& f_out; int& f;
-        __device__ ~WriteBack() { t_out = t; a_out = a; o_out = o; f_out = f; }
-    } write_back{team_io, team, asked_io, asked, own_task_io, own_task, own_flags_io, own_flags};
     const bool leader = team.member == 0;
     const bool lead = leader && lane == 0;            // the one lane that talks to the rest of the launch
-    double At_ = 0.0, Ad_ = 0.0, wa = 1.0;            // log2-partitions of the two rows; the node's weight
-    // ends the task for the sweeping waves
-    auto release_waves = [&]() __attribute__((always_inline)) {
-        if (lane == 0) g_cmd.kind = kCmdDone;
-        __syncthreads();                                  // B
+    // Takes a task up: the other waves are told, this wave's share of the pair is asked for.
+    auto start_task = [&](const NodeView& v, int t) __attribute__((always_inline)) {
+        if (lane == 0) { g_cmd.kind = kCmdTask; g_cmd.m = t; }
+        __syncthreads();                                  // B: the other waves take the task up
+        int tid_l = threadIdx.x;
+        asm volatile("" : "+v"(tid_l));     // per-task copy: nothing derived from it is kept across tasks
+        pair.setup(v.zt, v.zd, V, lds_t, lds_d, tid_l, member, team_size, uniform_i32(q.part_vecs));
+        pair.issue_loads();
     };
+    // A task taken up before it was certain (the task this team is most likely to run next,
+    // started while the leader still settles what follows from the last one), -1: none.
+    int started = -1;
+    // Outcomes settled by tasks that handed on to a child's task directly (see the end of the
+    // task): published by the first task that goes the long way.  And the weight such a child
+    // starts with (Traversal), known here without asking memory; negative: not known.
+    unsigned long long chain_settled = 0ull, chain_accepted = 0ull;
+    double a0_known = -1.0;
+    // One node task after the other, for as long as the team knows its next one itself (the task
+    // a node task hands to its own team: a child's, or the rest of the node where the tree
+    // branches): no way back through the task loop, no queue in between.
+    for (;;) {
+    {
+    const NodeView nv = view_of(task);
+    const bool resumed = nv.resumed;
+    const int b = nv.b, n = nv.n, k = nv.k;
+    const size_t bn = nv.bn;
+    const T* const zt = nv.zt;
+    const T* const zd = nv.zd;
+    (void)zt; (void)zd;
+    own_task = -1; own_flags = 0;
+    if (started != task) start_task(nv, task);            // (else: under way since the end of the task before)
+    started = -1;
+    double At_ = 0.0, Ad_ = 0.0, wa = 1.0;            // log2-partitions of the two rows; the node's weight
     // one more sweep by all four waves; the team's sums come back
     auto sweep = [&](int kind, const ResidualConsts& rc, float sp, float sq, int m, int naive, double& s0, double& s1) __attribute__((always_inline)) {
         if (lane == 0) {
@@ -943,24 +1018,6 @@ __device__ __attribute__((noinline)) void run_node_task(Team& team_io, int task_
     const bool split_here = METHOD == MPV_METHOD_TRAVERSAL && a.lazy && !resumed && n == q.split_node;
     const bool idle_seen = (flags & kFlagIdle) != 0;
 
-    // ---- the children's tokens and uniforms: fetched now, so that their latency hides behind
-    //      the sweep (lane j looks after child j; every member fetches them: they are inputs)
-    __shared__ int ch_tok[MPV_MAX_CHILDREN];
-    __shared__ float ch_zt[MPV_MAX_CHILDREN], ch_zd[MPV_MAX_CHILDREN];
-    __shared__ float ch_u[MPV_MAX_CHILDREN];
-    int pf_x = -1;
-    float pf_u = 2.f;
-    if (lane < k && a.tokens) {
-        const size_t bc = static_cast<size_t>(b) * N + tree.child_list[tree.child_off[n] + lane];
-        pf_x = a.tokens[bc];
-        if (!a.estimate) pf_u = a.uniforms[bc];
-    }
-    if (lane == MPV_MAX_CHILDREN && !a.estimate) pf_u = a.uniforms[bn];        // the node's own uniform
-    T pf_t = 0, pf_d = 0;       // kept as stored until the sweep is over: touching them now would wait for every load above
-    if (pf_x >= 0 && pf_x < V) {
-        pf_t = zt[pf_x];
-        pf_d = zd[pf_x];
-    }
     // Traversal, only what is needed, and idle teams about: an only child's task is queued
     // now, ahead of its starting weight.  It reads its rows while this task reads its own and
     // then finds the weight published (or waits a moment for it), so that a chain of nodes
@@ -977,24 +1034,24 @@ __device__ __attribute__((noinline)) void run_node_task(Team& team_io, int task_
     // ---- softmax statistics of both rows: the one read of the pair from memory
     float un = 2.f;                                   // the node's own uniform
     {
+        // Traversal: the starting weight comes from the parent's task, which published it
+        // before it queued this task (or publishes it shortly, if this task was queued ahead).
+        // The leader fetches it and passes it on with the statistics.  Value and "ready" flag
+        // are one 64-bit word (a weight is never NaN), read and written with relaxed
+        // device-scope atomics: no fence, no cache invalidation.  Asked for before the sweep:
+        // the answer is there when the sweep is over.
+        const bool wants_a0 = lead && METHOD == MPV_METHOD_TRAVERSAL && n != 0 && !(a0_known >= 0.0);
+        unsigned long long bits = kNotReady;
+        if (wants_a0) bits = ld_relaxed(reinterpret_cast<const unsigned long long*>(&ws.a0[bn]));
         PairStatsRawF<E> f;
         f.t.init(); f.d.init(); f.k32 = k32;
         pair.first_pass(f);
-        if (lane < k) { ch_tok[lane] = pf_x; ch_u[lane] = pf_u; ch_zt[lane] = E::load_one(&pf_t); ch_zd[lane] = E::load_one(&pf_d); }
-        un = lane_f32(pf_u, MPV_MAX_CHILDREN);
-        // Traversal: the starting weight comes from the parent's task, which published it
-        // before it queued this task (or publishes it shortly, if this task was queued ahead).
-        // The leader fetches it and passes it on with the statistics.
         double a0 = 1.0;
-        if (lead && METHOD == MPV_METHOD_TRAVERSAL && n != 0) {
-            // value and "ready" flag are one 64-bit word (a weight is never NaN), read and
-            // written with relaxed device-scope atomics: no fence, no cache invalidation
-            unsigned long long bits = kNotReady;
-            for (int spin = 0; spin < kMaxSpins; ++spin) {
-                bits = ld_relaxed(reinterpret_cast<const unsigned long long*>(&ws.a0[bn]));
-                if (bits != kNotReady) break;
+        if (wants_a0) {
+            for (int spin = 0; spin < kMaxSpins && bits == kNotReady; ++spin) {
                 if (wall_clock64() - team.t_start > kLaunchTimeoutTicks) break;
-                __builtin_amdgcn_s_sleep(32);
+                __builtin_amdgcn_s_sleep(8);
+                bits = ld_relaxed(reinterpret_cast<const unsigned long long*>(&ws.a0[bn]));
             }
             if (bits != kNotReady) {
                 a0 = __longlong_as_double(static_cast<long long>(bits));
@@ -1004,6 +1061,8 @@ __device__ __attribute__((noinline)) void run_node_task(Team& team_io, int task_
             }
         }
         a0 = lane_f64(a0, 0);
+        if (a0_known >= 0.0) a0 = a0_known;
+        a0_known = -1.0;
         // lanes to their wave's largest reference, waves to the workgroup's, members to the team's
         const float Mt_w = wave_max(f.t.mk), Md_w = wave_max(f.d.mk);
         const double st_w = wave_sum((f.t.s > 0.f) ? static_cast<double>(f.t.s * fast_exp2(f.t.mk - Mt_w)) : 0.0);
@@ -1013,6 +1072,7 @@ __device__ __attribute__((noinline)) void run_node_task(Team& team_io, int task_
             g_sh.part[0][0] = st_w; g_sh.part[0][1] = sd_w;
         }
         __syncthreads();                                  // A: every wave's partials are there
+        un = ch_u[MPV_MAX_CHILDREN];
         team.seq++;
         float Mt = g_sh.partf[0][0], Md = g_sh.partf[0][1];
 #pragma unroll
@@ -1049,18 +1109,18 @@ __device__ __attribute__((noinline)) void run_node_task(Team& team_io, int task_
             ST += double_at(g_sh.words, m, 1) * static_cast<double>(fast_exp2(__uint_as_float(g_sh.words[m * kExchWords]) - MT));
             SD += double_at(g_sh.words, m, 2) * static_cast<double>(fast_exp2(__uint_as_float(g_sh.words[m * kExchWords + 1]) - MD));
         }
-        At_ = uniform_f64(static_cast<double>(MT) + cold_log2(ST));
-        Ad_ = uniform_f64(static_cast<double>(MD) + cold_log2(SD));
+        const double lg = cold_log2(lane == 1 ? SD : ST);         // both logarithms in one go, a lane each
+        At_ = uniform_f64(static_cast<double>(MT) + lane_f64(lg, 0));
+        Ad_ = uniform_f64(static_cast<double>(MD) + lane_f64(lg, 1));
         if (METHOD == MPV_METHOD_TRAVERSAL) wa = uniform_f64(double_at(g_sh.words, 0, 3));
     }
     RowStat rt, rd;
     rt.A = At_; rd.A = Ad_; rt.m = 0.f; rd.m = 0.f;
 
     // ---- per-child scalars and one residual-mass reduction per child
-    if (METHOD == MPV_METHOD_TRAVERSAL && a.lazy && n != 0 && !(wa > 0.0)) {
+    if (METHOD == MPV_METHOD_TRAVERSAL && a.lazy && n != 0 && !(wa > 0.0) && chain_settled == 0ull) {
         // queued ahead of its weight, which is 0: the parent has written off the whole subtree.
         // Nothing to do but to pass the news on to an only child queued ahead in turn.
-        release_waves();
         if (lead) {
             if (child_ahead) {
                 const size_t bc = static_cast<size_t>(b) * N + tree.child_list[tree.child_off[n]];
@@ -1069,13 +1129,23 @@ __device__ __attribute__((noinline)) void run_node_task(Team& team_io, int task_
             wait_memory();
             atomicAdd(&ws.qctl[1], 1);
         }
-        return;
+        goto task_end;
     }
     double c = 0.0, W = 1.0;
     const double kd = static_cast<double>(k32);
+    // p(x) and q(x) of every child's token at once: lane j has the target's, lane 32 + j the draft's
+    static_assert(MPV_MAX_CHILDREN <= 32, "one lane per child and row");
+    double pq_all;
+    {
+        const int j = lane & 31;
+        const bool of_draft = lane >= 32;
+        const float z = j < k ? (of_draft ? ch_zd[j] : ch_zt[j]) : 0.f;
+        pq_all = cold_exp2(static_cast<double>(z) * kd - (of_draft ? Ad_ : At_));
+    }
     // test outcomes this task settles, one bit per node at its position in postorder
     unsigned long long settled_bits = 0ull, accepted_bits = 0ull;
     int next_node = -1;                               // SpecInfer, only what is needed: the accepted child
+    double own_w = 0.0;                               // ... and the weight it starts with
     int own_child = -1;                               // Traversal: index of the first child whose task is to be run
     bool paused = false;
     bool own_given = false;                           // that child's task was queued after all (some team is idle)
@@ -1165,12 +1235,11 @@ __device__ __attribute__((noinline)) void run_node_task(Team& team_io, int task_
                   static_cast<float>(cold_exp2(static_cast<double>(Ad_hi) - rd.A)), a.walk == 1 ? k : k - 1, a.walk == 2 ? 1 : 0, s0, s1);
             alpha = s0;
         }
-        release_waves();
         if (lead) {
-            a.alpha[bn] = static_cast<float>(fmin(fmax(alpha, 0.0), 1.0));
+            as_global(a.alpha)[bn] = static_cast<float>(fmin(fmax(alpha, 0.0), 1.0));
             atomicAdd(&ws.qctl[1], 1);
         }
-        return;
+        goto task_end;
     }
     for (int j = 0; j < k; ++j) {
         // a resumed task repeats the arithmetic of the first child (whose task has long run)
@@ -1182,8 +1251,8 @@ __device__ __attribute__((noinline)) void run_node_task(Team& team_io, int task_
         double px = 0.0, qx = 0.0;
         const bool tok_ok = (x >= 0 && x < V);
         if (tok_ok) {
-            px = cold_exp2(static_cast<double>(ch_zt[j]) * kd - rt.A);
-            qx = cold_exp2(static_cast<double>(ch_zd[j]) * kd - rd.A);
+            px = lane_f64(pq_all, j);
+            qx = lane_f64(pq_all, 32 + j);
         } else if (lead) {
             atomicAdd(&a.counters[MPV_COUNTER_BAD_TOKEN], 1u);
         }
@@ -1229,6 +1298,7 @@ __device__ __attribute__((noinline)) void run_node_task(Team& team_io, int task_
         if (first_to_run) {
             // kept for this team if it is the last thing this task finds out and nobody is idle
             own_child = j;
+            own_w = w_child;
             own_given = (idle_seen || j < k - 1 || child_ahead) && !(split_here && j == 0);
         }
         // One more sweep to go at most: time to ask for the next task, unless this team
@@ -1261,8 +1331,8 @@ __device__ __attribute__((noinline)) void run_node_task(Team& team_io, int task_
                 }
             }
             if (a.dbg_edge) {
-                a.dbg_edge[bc * 2] = static_cast<float>(px);
-                a.dbg_edge[bc * 2 + 1] = static_cast<float>(qx);
+                as_global(a.dbg_edge)[bc * 2] = static_cast<float>(px);
+                as_global(a.dbg_edge)[bc * 2 + 1] = static_cast<float>(qx);
             }
         }
 
@@ -1320,7 +1390,7 @@ __device__ __attribute__((noinline)) void run_node_task(Team& team_io, int task_
                 const int xi = ch_tok[i];
                 double r = 0.0;
                 if (xi >= 0 && xi < V)
-                    r = fmax(cold_exp2(static_cast<double>(ch_zt[i]) * kd - rt.A) - c * cold_exp2(static_cast<double>(ch_zd[i]) * kd - rd.A), 0.0) / W;
+                    r = fmax(lane_f64(pq_all, i) - c * lane_f64(pq_all, 32 + i), 0.0) / W;
                 else if (i > 0 && lead)
                     atomicAdd(&a.counters[MPV_COUNTER_BAD_TOKEN], 1u);
                 if (lead) {
@@ -1332,10 +1402,56 @@ __device__ __attribute__((noinline)) void run_node_task(Team& team_io, int task_
             break;
         }
     }
-    release_waves();
+
+    // ---- The sweeps are over and the part on chip is no longer needed.  What this team will
+    //      most likely run next (every member works it out by itself, from the same numbers) is
+    //      taken up at once: its rows travel while the leader settles what follows from this
+    //      task, and while the others wait to hear of it.
+    if (!team.dead) {
+        int likely = -1;
+        if (METHOD == MPV_METHOD_TRAVERSAL) {
+            if (paused) likely = b * N + tree.child_list[tree.child_off[n]];
+            else if (own_child >= 0 && !own_given) likely = b * N + tree.child_list[tree.child_off[n] + own_child];
+        } else if (a.lazy && next_node >= 0 && tree.nchild[next_node] > 0) {
+            likely = b * N + next_node;
+        }
+        if (likely >= 0) {
+            start_task(view_of(likely), likely);
+            started = likely;
+            // Where that task is a child's and nothing else follows from this one (a chain), the
+            // team simply goes on with it: every member knows the task and what it starts with,
+            // so nothing is announced, nothing waited for, and the outcomes settled here are
+            // noted for the first task that goes the long way to publish.  (If another branch
+            // settles the tree meanwhile, the chain runs on in vain until it ends.)
+            if (METHOD == MPV_METHOD_TRAVERSAL || a.walk == 0) {
+                if (!(METHOD == MPV_METHOD_TRAVERSAL && paused)) {
+                    if (lead) {
+                        st_shared_f64(&ws.At[bn], rt.A);
+                        st_shared_f64(&ws.Ad[bn], rd.A);
+                        st_shared_f64(&ws.cfin[bn], c);
+                        if (METHOD == MPV_METHOD_TRAVERSAL && n != 0) st_shared_f64(&ws.atest[bn], wa);
+                    }
+                    chain_settled |= settled_bits;
+                    chain_accepted |= accepted_bits;
+                    if (METHOD == MPV_METHOD_TRAVERSAL && n != 0) {
+                        const unsigned long long own = 1ull << tree.rank[n];
+                        chain_settled |= own;
+                        if (static_cast<double>(un) < wa) chain_accepted |= own;
+                    }
+                }
+                if (METHOD == MPV_METHOD_TRAVERSAL) a0_known = own_w;
+                task = likely;                            // (flags: as they are)
+                continue;
+            }
+        }
+    }
+    settled_bits |= chain_settled;
+    accepted_bits |= chain_accepted;
+    chain_settled = 0ull;
+    chain_accepted = 0ull;
 
     // ---- what follows from this task: the leader's business (its first wave's)
-    if (!leader) return;
+    if (!leader) goto task_end;
     own_flags = uniform_i32(idle_now) != 0 ? kFlagIdle : 0;
     if (paused) {
         // nothing is settled yet; the first child's task is run next by this team
@@ -1346,7 +1462,7 @@ __device__ __attribute__((noinline)) void run_node_task(Team& team_io, int task_
             wait_memory();                            // counted (and the child's weight written) before this task counts as finished
             atomicAdd(&ws.qctl[1], 1);
         }
-        return;
+        goto task_end;
     }
     int push_sample_i = 0, settled_i = 0, resume_i = 0;
     if (lane == 0) {
@@ -1415,7 +1531,13 @@ __device__ __attribute__((noinline)) void run_node_task(Team& team_io, int task_
     // no waiting): the sampling if this task settled the tree, else the first child that needs
     // its own task (Traversal) or the accepted child (SpecInfer).  The other children are queued.
     if (push_sample_i) {
-        own_task = B * N + b;
+        if (!ACCEPT && a.estimate) {
+            // the expected block efficiency instead of a walk: scalar work over the tree's
+            // per-node results, done here and now by this wave (there are no uniforms to walk with)
+            estimate_wave<METHOD>(tree, ws, a, b);
+        } else {
+            own_task = B * N + b;
+        }
     } else if (resume_i) {
         own_task = B * N + B + b;
     } else if (METHOD == MPV_METHOD_TRAVERSAL) {
@@ -1438,7 +1560,38 @@ __device__ __attribute__((noinline)) void run_node_task(Team& team_io, int task_
         wait_memory();                                // every new task has been counted
         atomicAdd(&ws.qctl[1], 1);
     }
+    }   // (the task's own scope)
+task_end:
+    // The task that follows: the leader knows (and has told the others, who hear of it here).
+    int next, next_flags = 0;
+    if (leader) {
+        next = own_task;
+        next_flags = own_flags;
+    } else {
+        next = team_listen(team, next_flags, ws);
+    }
+    const bool node_next = next >= 0 && !(next >= B * N && next < B * N + B) && !team.dead;
+    if (started >= 0 && (!node_next || next != started)) {
+        // taken up in vain (the tree was settled meanwhile, or the task went elsewhere): the other
+        // waves finish their sweep, this wave's loads land, and the slots are free again
+        __syncthreads();                                  // A
+        wait_memory();
+        started = -1;
+    }
+    if (!node_next) {
+        if (lane == 0) g_cmd.kind = kCmdDone;
+        __syncthreads();                                  // B: the other waves leave
+        team_io = team;
+        asked_io = asked;
+        own_task_io = next;                               // (already announced to, or heard by, the team)
+        own_flags_io = next_flags;
+        return;
+    }
+    task = next;
+    flags = next_flags;
+    }   // node tasks
 }
+
 
 template <class E, int KIND>
 __global__ __launch_bounds__(kTaskBlock) __attribute__((amdgpu_waves_per_eu(3, 3)))
@@ -1490,10 +1643,16 @@ void node_task_kernel(const Launch* __restrict__ launch) {
 
     const bool drop_settled = METHOD == MPV_METHOD_TRAVERSAL && a.lazy != 0;
     const int wave = uniform_i32(static_cast<int>(threadIdx.x) / kWave);
+    // The first wave's scalar steps are the critical path of every task and few in number: they
+    // go first when the compute unit's waves compete for issue slots.
+    if (wave == 0) __builtin_amdgcn_s_setprio(3);
     // The task loop's own state lives in the first wave (the others only sweep):
     int previous_task = -4;                           // last task taken from the mailbox: none yet
     bool asked = true;                                // the team starts out waiting
-    int own_task = -1;                                // a task this team produced for itself (already announced to the team)
+    // a task this team produced for itself, already announced to the team; a member: the task it
+    // has already heard of (a node task ends with listening for the next), kNothingHeard if none
+    constexpr int kNothingHeard = -4;
+    int own_task = leader ? -1 : kNothingHeard;
     int own_flags = 0;
     for (;;) {
     __syncthreads();                                  // the previous task is done with LDS
@@ -1531,6 +1690,10 @@ void node_task_kernel(const Launch* __restrict__ launch) {
                 team_announce(team, task, flags);
                 break;
             }
+        } else if (own_task != kNothingHeard) {
+            task = own_task;
+            flags = own_flags;
+            own_task = kNothingHeard;
         } else {
             task = team_listen(team, flags, ws);
         }
@@ -1540,6 +1703,18 @@ void node_task_kernel(const Launch* __restrict__ launch) {
     const int task = uniform_i32(sh_task), flags = uniform_i32(sh_flags);
     if (task == kTaskExit) break;
     if (task >= a.B * a.N && task < a.B * a.N + a.B) {
+        if (ACCEPT || a.estimate) {
+            // no walk in these modes (there are no uniforms): scalar work of the leader's first
+            // wave alone, whichever way the task came
+            if (wave == 0 && leader) {
+                if (!ACCEPT) estimate_wave<METHOD>(tree, ws, a, task - a.B * a.N);
+                if (threadIdx.x == 0) {
+                    wait_memory();
+                    atomicAdd(&ws.qctl[1], 1);
+                }
+            }
+            continue;
+        }
         // the tree's outcome is settled: walk and bonus token
         if (wave == 0 && leader && !asked) {
             if (threadIdx.x == 0) st_relaxed(&ws.mailbox[team.id], kMailboxSoon);
@@ -1581,13 +1756,13 @@ void node_task_kernel(const Launch* __restrict__ launch) {
 __device__ __forceinline__ void write_path(const TreeDesc& tree, const Args& a, int b, int stop) {
     const size_t base = static_cast<size_t>(b) * a.N;
     const int len = tree.depth[stop];
-    a.accept_len[b] = len;
+    as_global(a.accept_len)[b] = len;
     int32_t* pn = a.path_nodes + static_cast<size_t>(b) * a.max_depth;
     int32_t* pt = a.path_tokens + static_cast<size_t>(b) * a.max_depth;
     for (int i = len; i < a.max_depth; ++i) { pn[i] = -1; pt[i] = -1; }
     for (int n = stop, i = len - 1; n > 0; n = tree.parent[n], --i) {
         pn[i] = n;
-        pt[i] = a.tokens[base + n];
+        pt[i] = as_global(a.tokens)[base + n];
     }
 }
 
@@ -1598,12 +1773,12 @@ __device__ __forceinline__ int walk_wave(const TreeDesc& tree, const Workspace& 
     bool acc = false, near = false;
     if (lane > 0 && lane < a.N) {
         const double at = ld_shared_f64(&ws.atest[base + lane]);
-        const double uu = static_cast<double>(a.uniforms[base + lane]);
+        const double uu = static_cast<double>(as_global(a.uniforms)[base + lane]);
         acc = uu < at;
         near = fabs(at - uu) < 1e-6;
-        if (a.dbg_accept && record) a.dbg_accept[base + lane] = static_cast<float>(at);
+        if (a.dbg_accept && record) as_global(a.dbg_accept)[base + lane] = static_cast<float>(at);
     }
-    if (lane == 0 && a.dbg_accept && record) a.dbg_accept[base] = 1.f;
+    if (lane == 0 && a.dbg_accept && record) as_global(a.dbg_accept)[base] = 1.f;
     const unsigned long long accm = __ballot(acc);
     const unsigned long long nearm = __ballot(near);
     unsigned long long tested = 0ull;
@@ -1684,7 +1859,7 @@ __device__ __forceinline__ void estimate_wave(const TreeDesc& tree, const Worksp
         double step = 1.0;                            // from the parent to this node
         if (live && n > 0) {
             const int par = tree.parent[n], off = tree.child_off[par], k = tree.nchild[par];
-            const int x = a.tokens[base + n];
+            const int x = as_global(a.tokens)[base + n];
             double none_before = 1.0, none_at_all = 1.0;
             bool first_carrier = true;
             int j = 0;
@@ -1693,7 +1868,7 @@ __device__ __forceinline__ void estimate_wave(const TreeDesc& tree, const Worksp
                 if (sib == n) j = l;
                 if (sib < n) {                        // list order is node order
                     none_before *= 1.0 - sh_v[sib];
-                    if (a.tokens[base + sib] == x) first_carrier = false;
+                    if (as_global(a.tokens)[base + sib] == x) first_carrier = false;
                 }
                 none_at_all *= 1.0 - sh_v[sib];
             }
@@ -1714,9 +1889,9 @@ __device__ __forceinline__ void estimate_wave(const TreeDesc& tree, const Worksp
             for (int m = n; m > 0; m = tree.parent[m]) reach *= sh_v[m];
         }
     }
-    if (live && a.reach_prob) a.reach_prob[base + n] = static_cast<float>(reach);
+    if (live && a.reach_prob) as_global(a.reach_prob)[base + n] = static_cast<float>(reach);
     const double total = wave_sum(live ? reach : 0.0);
-    if (n == 0 && a.expected) a.expected[b] = static_cast<float>(total);
+    if (n == 0 && a.expected) as_global(a.expected)[b] = static_cast<float>(total);
 }
 
 // ------------------------------------------------------------------ bonus sample
@@ -1746,7 +1921,7 @@ struct ResidualTile {
 #pragma unroll
             for (int i = 0; i < PER_LANE; ++i) {
                 const int e = e0 + i;
-                r[i] = (e < V) ? term(E::load_one(zt + e), use_d ? E::load_one(zd + e) : 0.f) : 0.f;
+                r[i] = (e < V) ? term(E::load_one_global(zt + e), use_d ? E::load_one_global(zd + e) : 0.f) : 0.f;
             }
         }
     }
@@ -1904,7 +2079,7 @@ __device__ __attribute__((noinline)) int sample_task(Team& team_io, int b_in) {
         if (m == team.member) before = total;
         total += double_at(g_sh.words, m, 0);
     }
-    const float u_draw = a.walk ? a.draw_uniforms[bn] : a.uniforms[static_cast<size_t>(b) * a.N];
+    const float u_draw = a.walk ? as_global(a.draw_uniforms)[bn] : as_global(a.uniforms)[static_cast<size_t>(b) * a.N];
     const double target = static_cast<double>(u_draw) * total;
     // the member whose run contains the target: the first whose running total exceeds it and that
     // has mass; rounding only: the last one that has mass
@@ -1982,7 +2157,7 @@ __device__ __attribute__((noinline)) int sample_task(Team& team_io, int b_in) {
             if (found < 0) { found = last; lo = rem; hi = rem; }
             int tk = t * TILE + lane * PER_LANE + found;
             if (tk >= V) tk = V - 1;
-            a.bonus[b] = tk;
+            as_global(a.bonus)[b] = tk;
             sh_tile = tk;                             // (the tile number is no longer needed)
             const double gap = fmin(fabs(rem - lo), fabs(hi - rem));
             if (gap < 1e-6 * total) atomicAdd(&a.counters[MPV_COUNTER_NEAR_TIE_BONUS], 1u);
@@ -2001,7 +2176,7 @@ __device__ __attribute__((noinline)) int sample_task(Team& team_io, int b_in) {
         if (wave == 0) {
             const int k = tree.nchild[n];
             bool same = false;
-            if (lane < k) same = a.tokens[static_cast<size_t>(b) * a.N + tree.child_list[tree.child_off[n] + lane]] == tok;
+            if (lane < k) same = as_global(a.tokens)[static_cast<size_t>(b) * a.N + tree.child_list[tree.child_off[n] + lane]] == tok;
             const unsigned long long m = __ballot(same);
             if (m) {
                 const int to = tree.child_list[tree.child_off[n] + __ffsll(static_cast<long long>(m)) - 1];
@@ -2013,7 +2188,7 @@ __device__ __attribute__((noinline)) int sample_task(Team& team_io, int b_in) {
             } else if (leader) {
                 if (lane == 0) write_path(tree, a, b, n);
                 if (a.dbg_accept && lane < a.N)
-                    a.dbg_accept[static_cast<size_t>(b) * a.N + lane] =
+                    as_global(a.dbg_accept)[static_cast<size_t>(b) * a.N + lane] =
                         lane == 0 ? 1.f : static_cast<float>(ld_shared_f64(&ws.atest[static_cast<size_t>(b) * a.N + lane]));
             }
         }

@@ -19,18 +19,35 @@ namespace mpv {
 
 constexpr int kWave = 64;
 
+// Every pointer the kernels follow points into device memory.  Where the compiler cannot see
+// that (a pointer read from a table in LDS, or handed to a function that is not inlined) it
+// would use the generic "flat" instructions, whose completion is counted together with LDS
+// traffic: every wait for an LDS read would then also wait for every row load in flight.
+// as_global() states the address space.
+#define MPV_GLOBAL __attribute__((address_space(1)))
+template <class T>
+__device__ __forceinline__ MPV_GLOBAL T* as_global(T* p) { return (MPV_GLOBAL T*)p; }
+
+// 16 bytes from device memory
+__device__ __forceinline__ uint4 load_global_16B(const void* p) {
+    typedef unsigned v4u __attribute__((ext_vector_type(4)));
+    const v4u t = *as_global(reinterpret_cast<const v4u*>(p));
+    return make_uint4(t.x, t.y, t.z, t.w);
+}
+
 // ---------------------------------------------------------------- element types
 
 struct ElemF32 {
     using T = float;
     static constexpr int VEC = 4;                       // elements per 16-byte load
     __device__ static __forceinline__ float load_one(const T* p) { return *p; }
+    __device__ static __forceinline__ float load_one_global(const T* p) { return *as_global(p); }
     __device__ static __forceinline__ void unpack(const uint4& r, float (&o)[VEC]) {
         o[0] = __uint_as_float(r.x); o[1] = __uint_as_float(r.y);
         o[2] = __uint_as_float(r.z); o[3] = __uint_as_float(r.w);
     }
     __device__ static __forceinline__ void load_vec(const T* p, float (&o)[VEC]) {
-        unpack(*reinterpret_cast<const uint4*>(p), o);
+        unpack(load_global_16B(p), o);
     }
 };
 
@@ -40,6 +57,9 @@ struct ElemBF16 {
     __device__ static __forceinline__ float load_one(const T* p) {
         return __uint_as_float(static_cast<uint32_t>(*p) << 16);
     }
+    __device__ static __forceinline__ float load_one_global(const T* p) {
+        return __uint_as_float(static_cast<uint32_t>(*as_global(p)) << 16);
+    }
     __device__ static __forceinline__ void unpack(const uint4& r, float (&o)[VEC]) {
         o[0] = __uint_as_float(r.x << 16); o[1] = __uint_as_float(r.x & 0xffff0000u);
         o[2] = __uint_as_float(r.y << 16); o[3] = __uint_as_float(r.y & 0xffff0000u);
@@ -47,17 +67,17 @@ struct ElemBF16 {
         o[6] = __uint_as_float(r.w << 16); o[7] = __uint_as_float(r.w & 0xffff0000u);
     }
     __device__ static __forceinline__ void load_vec(const T* p, float (&o)[VEC]) {
-        unpack(*reinterpret_cast<const uint4*>(p), o);
+        unpack(load_global_16B(p), o);
     }
 };
 
 // 16 aligned bytes of a row, still packed
 template <class T>
-__device__ __forceinline__ uint4 load_raw(const T* p) { return *reinterpret_cast<const uint4*>(p); }
+__device__ __forceinline__ uint4 load_raw(const T* p) { return load_global_16B(p); }
 // vector number `vec` (16-byte units) after a wave-uniform base: 32-bit offset arithmetic
 template <class T>
 __device__ __forceinline__ uint4 load_raw_at(const T* base, int vec) {
-    return *reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(base) + (static_cast<unsigned>(vec) << 4));
+    return load_global_16B(reinterpret_cast<const char*>(base) + (static_cast<unsigned>(vec) << 4));
 }
 // the same, marked non-temporal: data that will not be read from memory again (it is kept on
 // chip) should not push re-read data out of the L2 cache
@@ -65,7 +85,7 @@ template <class T>
 __device__ __forceinline__ uint4 load_raw_at_nt(const T* base, int vec) {
     typedef unsigned v4u __attribute__((ext_vector_type(4)));
     const v4u t = __builtin_nontemporal_load(
-        reinterpret_cast<const v4u*>(reinterpret_cast<const char*>(base) + (static_cast<unsigned>(vec) << 4)));
+        as_global(reinterpret_cast<const v4u*>(reinterpret_cast<const char*>(base) + (static_cast<unsigned>(vec) << 4))));
     return make_uint4(t.x, t.y, t.z, t.w);
 }
 
@@ -213,8 +233,8 @@ __device__ __forceinline__ void sweep_pair(const typename E::T* __restrict__ zt,
     const int head = mis ? min(VEC - mis, V) : 0;
     const int nvec = (V - head) / VEC;
     const int tail0 = head + nvec * VEC;
-    if (tid < head) f.one(E::load_one(zt + tid), E::load_one(zd + tid));
-    if (tail0 + tid < V) f.one(E::load_one(zt + tail0 + tid), E::load_one(zd + tail0 + tid));
+    if (tid < head) f.one(E::load_one_global(zt + tid), E::load_one_global(zd + tid));
+    if (tail0 + tid < V) f.one(E::load_one_global(zt + tail0 + tid), E::load_one_global(zd + tail0 + tid));
     const T* bt = zt + head;
     const T* bd = zd + head;
     for (int i = tid; i < nvec; i += BLOCK * UNROLL) {
@@ -246,8 +266,8 @@ __device__ __forceinline__ void sweep_row(const typename E::T* __restrict__ z, i
     const int head = mis ? min(VEC - mis, V) : 0;
     const int nvec = (V - head) / VEC;
     const int tail0 = head + nvec * VEC;
-    if (tid < head) f.one(E::load_one(z + tid));
-    if (tail0 + tid < V) f.one(E::load_one(z + tail0 + tid));
+    if (tid < head) f.one(E::load_one_global(z + tid));
+    if (tail0 + tid < V) f.one(E::load_one_global(z + tail0 + tid));
     const T* bz = z + head;
     for (int i = tid; i < nvec; i += BLOCK * UNROLL) {
         uint4 ra[UNROLL];                         // kept packed until they are used
@@ -389,13 +409,26 @@ __device__ __forceinline__ ResidualConsts residual_consts(double At, double Ad, 
     ResidualConsts r;
     const float At_hi = static_cast<float>(At);
     const double At_lo = At - static_cast<double>(At_hi);
+    const double ln2 = 0.6931471805599453;
+    if (c < 0x1p40) {
+        // c of ordinary size multiplies q as a factor: no logarithm.  (For a huge c the product
+        // c q_v can be of ordinary size where q_v itself is below float range: then c goes into
+        // the exponent, below.)
+        const float Ad_hi = static_cast<float>(Ad);
+        const double Ad_lo = Ad - static_cast<double>(Ad_hi);
+        const double x = (At_lo - Ad_lo) * ln2, y = -At_lo * ln2;
+        r.nAt = -At_hi;
+        r.nAd = -Ad_hi;
+        r.rho = static_cast<float>(c * (1.0 + x + 0.5 * x * x));
+        r.scale = 1.0 + y + 0.5 * y * y;
+        return r;
+    }
     const double Adc = Ad - log2(c);                 // c > 0
     const float Ad_hi = static_cast<float>(Adc);
     const double Ad_lo = isfinite(Adc) ? Adc - static_cast<double>(Ad_hi) : 0.0;   // c = inf: every term vanishes
     r.nAt = -At_hi;
     r.nAd = -Ad_hi;
     // 2^x for |x| < 2^-17 (the float rounding remainders): two terms of the series are exact to 1e-16
-    const double ln2 = 0.6931471805599453;
     const double x = (At_lo - Ad_lo) * ln2, y = -At_lo * ln2;
     r.rho = static_cast<float>(1.0 + x + 0.5 * x * x);
     r.scale = 1.0 + y + 0.5 * y * y;
@@ -460,8 +493,8 @@ struct RetainedPart {
 
     template <class F>
     __device__ __forceinline__ void edges(F& f) const {
-        if (first_part && tid < head) f.one(E::load_one(zt + tid), E::load_one(zd + tid));
-        if (last_part && tail0 + tid < V) f.one(E::load_one(zt + tail0 + tid), E::load_one(zd + tail0 + tid));
+        if (first_part && tid < head) f.one(E::load_one_global(zt + tid), E::load_one_global(zd + tid));
+        if (last_part && tail0 + tid < V) f.one(E::load_one_global(zt + tail0 + tid), E::load_one_global(zd + tail0 + tid));
     }
 
     // slot s of this lane: its vector number in the row (clamped into the part: always a valid
