@@ -22,9 +22,24 @@ HBM_PEAK_GBS = 8000.0      # MI355X published peak
 METHOD_LABEL = {0: "SpecInfer", 1: "Traversal", 2: "NSS", 3: "Naive", 4: "SpecTr"}
 
 
+def kernel_source_digest():
+    """sha256 over the HIP sources the library is built from: a counter summary under
+    profiles/ says which sources it was measured on."""
+    import hashlib
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_2602_16994_amd", "csrc")
+    for name in sorted(os.listdir(csrc)):
+        with open(os.path.join(csrc, name), "rb") as f:
+            h.update(name.encode())
+            h.update(f.read())
+    return h.hexdigest()[:16]
+
+
 def parse_profile_traffic(path):
-    """HBM bytes per launch of the dominant kernel from the committed counter
-    summary (key = value lines), or None."""
+    """HBM bytes per launch of the dominant kernel from the committed counter summary
+    (key = value lines): (bytes or None, provenance).  A summary measured on other kernel
+    sources than the ones in the tree is stale: its figure is not reported."""
+    prov = {"file": os.path.relpath(path, ROOT), "status": "missing"}
     try:
         vals = {}
         with open(path) as f:
@@ -32,39 +47,91 @@ def parse_profile_traffic(path):
                 if "=" in line and not line.lstrip().startswith("#"):
                     k, v = line.split("=", 1)
                     vals[k.strip()] = v.strip()
-        return float(vals["hbm_bytes_per_launch"])
+        traffic = float(vals["hbm_bytes_per_launch"])
     except Exception:
-        return None
+        return None, prov
+    prov["measured_on_sources"] = vals.get("kernel_sources_sha256_16")
+    prov["sources_now"] = kernel_source_digest()
+    if prov["measured_on_sources"] != prov["sources_now"]:
+        prov["status"] = "stale: the kernel sources have changed since the counters were read"
+        return None, prov
+    prov["status"] = "current"
+    return traffic, prov
 
 
-def cpu_baseline(cfg, inputs, method, budget_s=20.0):
-    """The oracle, as it stands, in sample mode on trees of the same batch, in order,
-    until the time budget is used (single thread: numpy elementwise kernels do not
-    thread).  If the whole batch fits in the budget it is walked again from the start."""
-    from oracle import mpv_oracle as orc
-    parent = inputs["parent"]
-    done = 0
-    t_total = 0.0
-    b = 0
-    while t_total < budget_s:
-        tok = inputs["tokens"][b].cpu().numpy()
-        zt = inputs["target"][b].float().cpu().numpy()
-        zd = inputs["draft"][b].float().cpu().numpy()
-        u = inputs["uniforms"][b].cpu().numpy()
-        ud = inputs["draw_uniforms"][b].cpu().numpy()
-        t0 = time.perf_counter()
-        orc.verify_tree(method, parent, tok, zt, zd, cfg.T, u, ud)
-        t_total += time.perf_counter() - t0
-        done += 1
-        b = (b + 1) % cfg.B
+def cpu_baseline(cfg, inputs, method, budget_s=15.0):
+    """The oracle, as it stands, on every host core this box gives a GPU job: one worker
+    process per core (spawned; each imports numpy and the oracle only), each verifying one
+    tree of the batch in sample mode over and over for `budget_s` seconds."""
+    import multiprocessing as mp
+    import bench_cpu_worker
+    cores = max(1, min(16, os.cpu_count() or 1, cfg.B))       # a one-GPU box's CPU share is 16 cores
+    jobs = []
+    for b in range(cores):
+        jobs.append((method, list(inputs["parent"]),
+                     inputs["tokens"][b].cpu().numpy(),
+                     inputs["target"][b].float().cpu().numpy(),
+                     inputs["draft"][b].float().cpu().numpy(),
+                     cfg.T,
+                     inputs["uniforms"][b].cpu().numpy(),
+                     inputs["draw_uniforms"][b].cpu().numpy(),
+                     budget_s))
+    ctx = mp.get_context("spawn")
+    t0 = time.perf_counter()
+    with ctx.Pool(processes=cores) as pool:
+        results = pool.map(bench_cpu_worker.verify_repeatedly, jobs, chunksize=1)
+    wall = time.perf_counter() - t0
+    trees = sum(r[0] for r in results)
+    busy = max(r[1] for r in results)
+    print(f"[bench] cpu baseline: {cores} worker processes, {trees} trees in {busy:.1f} s "
+          f"({wall:.1f} s with start-up)", file=sys.stderr)
     return {
-        "value": done * cfg.N / t_total,
+        "value": trees * cfg.N / busy,
         "unit": "nodes/s",
-        "cores": 1,
+        "cores": cores,
         "kind": "oracle",
-        "sample": f"{done} trees of the same batch (in order, wrapping around after {cfg.B}), "
-                  f"sample mode, {t_total:.1f} s of oracle time",
+        "sample": f"{cores} worker processes (one per core), each verifying one tree of the same batch "
+                  f"(trees 0..{cores - 1}) repeatedly in sample mode for {budget_s:.0f} s: {trees} trees in {busy:.1f} s",
     }
+
+
+def other_configs(mpv, torch, workloads, skip, steps=10):
+    """The remaining benchmark configurations, each with the rules it is quoted with: time per
+    call, nodes per second, and the node-task kernel's algorithmic bytes over the whole call
+    time (a lower bound of the kernel's own figure: the call also holds the set-up kernel)."""
+    res = {}
+    for name, cfg in workloads.CONFIGS.items():
+        if name == skip:
+            continue
+        inp = workloads.make_inputs(cfg, "cuda:0")
+        pair_bytes = 2 * cfg.V * cfg.elem_bytes
+        entry = {"B": cfg.B, "N": cfg.N, "V": cfg.V, "logit_dtype": cfg.dtype, "methods": {}}
+        for method in cfg.methods:
+            def call(out=None):
+                return mpv.mpv_verify(inp["parent"], inp["tokens"], inp["target"], inp["draft"], cfg.T,
+                                      inp["uniforms"], method, debug=False, out=out,
+                                      draw_uniforms=inp["draw_uniforms"])
+            out = call()
+            for _ in range(3):
+                call(out)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(steps):
+                call(out)
+            torch.cuda.synchronize()
+            sec = (time.perf_counter() - t0) / steps
+            counters = out.counters.tolist()
+            if counters[4] != 0:
+                raise RuntimeError(f"{name}/{METHOD_LABEL[method]}: {counters[4]} dependency timeouts")
+            gbs = counters[5] * pair_bytes / sec / 1e9
+            entry["methods"][METHOD_LABEL[method]] = {
+                "ms_per_step": sec * 1e3, "nodes_per_s": cfg.B * cfg.N / sec, "node_tasks_run": counters[5],
+                "algorithmic_GBps": gbs, "frac_of_hbm_peak": gbs / HBM_PEAK_GBS,
+                "mean_accept_len": float(out.accept_len.float().mean().item())}
+        res[name] = entry
+        del inp
+        torch.cuda.empty_cache()
+    return res
 
 
 def side_measurements(mpv, torch, cfg, inputs, method, pair_bytes, steps=5):
@@ -218,11 +285,13 @@ def main():
             alg_bytes_per_launch = tasks_run * pair_bytes / launches
             avg_s = sum(nt) / len(nt) * 1e-3
             achieved = alg_bytes_per_launch / avg_s / 1e9
-            traffic = parse_profile_traffic(os.path.join(
+            traffic, traffic_provenance = parse_profile_traffic(os.path.join(
                 ROOT, "profiles", f"node_task_{cfg.name}_pmc.txt"))
             roofline = {"bound": "hbm", "kernel": "node_task_kernel", "achieved": achieved,
                         "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                         "traffic": traffic,
+                        # where the figure comes from (rocprofv3 counters, read in a run of their own)
+                        "traffic_provenance": traffic_provenance,
                         # the counted bytes (profiles/) over the launch time measured here
                         "traffic_GBps": None if traffic is None else traffic / avg_s / 1e9,
                         "traffic_frac": None if traffic is None else traffic / avg_s / 1e9 / HBM_PEAK_GBS,
@@ -231,6 +300,9 @@ def main():
                         "bytes_per_node_task": pair_bytes,
                         "avg_launch_ms": avg_s * 1e3, "launches_per_step": launches}
 
+    if counters[4] != 0:
+        # a wait inside the kernels ran into its time limit: the results of this run are invalid
+        raise RuntimeError(f"bench.py: {counters[4]} dependency timeouts reported by the library")
     nodes_per_s = cfg.B * cfg.N / (ms_per_step * 1e-3)
     result = {
         "metric": "draft-tree nodes verified/sec",
@@ -252,7 +324,6 @@ def main():
                    "method": {0: "specinfer", 1: "traversal", 2: "nss", 3: "naive", 4: "spectr"}[method],
                    "logit_dtype": cfg.dtype},
         "trees_per_s": cfg.B / (ms_per_step * 1e-3),
-        "dense_input_GBps_equivalent": cfg.B * (cfg.N + n_internal) * cfg.V * cfg.elem_bytes / (ms_per_step * 1e-3) / 1e9,
         "mean_accept_len": float(out.accept_len.float().mean().item()),
         "counters": counters,
         "kernels": kernels,
@@ -260,6 +331,7 @@ def main():
     }
     if not args.no_extra:
         result["also_measured"] = side_measurements(mpv, torch, cfg, inputs, method, pair_bytes)
+        result["also_measured"]["configs"] = other_configs(mpv, torch, workloads, cfg.name)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, inputs, method)
     print(json.dumps(result))

@@ -67,7 +67,7 @@
 extern "C" {
 #endif
 
-#define MPV_ABI_VERSION 6
+#define MPV_ABI_VERSION 7
 
 /* limits (larger requests return MPV_ERR_UNSUPPORTED) */
 #define MPV_MAX_NODES    64   /* nodes per tree, root included            */
@@ -259,13 +259,10 @@ int mpv_fill_uniforms(uint64_t seed, int64_t count, float* d_u, void* hip_stream
  * MPV_KERNEL_NODE_TASK, whose persistent workgroups run every node task (softmax
  * statistics, per-child test probabilities, residual masses) and every sampling task
  * (accept/reject walk, bonus token) of the batch (Sec. 2, step 3); MPV_KERNEL_DEBUG_STATS
- * follows when `stats` is requested.  MPV_KERNEL_WALK and MPV_KERNEL_SAMPLE are no longer
- * launches of their own; the ids stay reserved. */
+ * follows when `stats` is requested. */
 #define MPV_KERNEL_INIT        0
 #define MPV_KERNEL_NODE_TASK   1
-#define MPV_KERNEL_WALK        2
-#define MPV_KERNEL_SAMPLE      3
-#define MPV_KERNEL_DEBUG_STATS 4
+#define MPV_KERNEL_DEBUG_STATS 2
 int mpv_timing_enable(int32_t max_launches);
 int mpv_timing_read(float* ms_out, int32_t* kernel_out, int32_t capacity, int32_t* count);
 

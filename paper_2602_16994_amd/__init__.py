@@ -10,5 +10,8 @@ from .binding import (  # noqa: F401
     mpv_fill_uniforms, mpv_last_hip_error, mpv_row_stats, mpv_strerror,
     mpv_timing_enable, mpv_timing_read, mpv_verify, mpv_version, mpv_workspace_bytes,
     MPV_KERNEL_NAMES,
+    MPV_COUNTER_NEAR_TIE_ACCEPT, MPV_COUNTER_NEAR_TIE_BONUS, MPV_COUNTER_ZERO_MASS, MPV_COUNTER_BAD_TOKEN,
+    MPV_COUNTER_DEPENDENCY_TIMEOUT, MPV_COUNTER_NODE_TASKS_RUN, MPV_COUNTER_NODE_TASKS_CANCELLED,
+    MPV_COUNTER_NODE_TASKS_RESUMED,
 )
 from .trees import delayed_tree, root_tree, tree_depth  # noqa: F401

@@ -16,6 +16,15 @@ MPV_METHOD_TRAVERSAL = 1
 MPV_METHOD_NSS = 2
 MPV_METHOD_NAIVE = 3
 MPV_METHOD_SPECTR = 4
+# indices into the counters array of a call
+MPV_COUNTER_NEAR_TIE_ACCEPT = 0
+MPV_COUNTER_NEAR_TIE_BONUS = 1
+MPV_COUNTER_ZERO_MASS = 2
+MPV_COUNTER_BAD_TOKEN = 3
+MPV_COUNTER_DEPENDENCY_TIMEOUT = 4
+MPV_COUNTER_NODE_TASKS_RUN = 5
+MPV_COUNTER_NODE_TASKS_CANCELLED = 6
+MPV_COUNTER_NODE_TASKS_RESUMED = 7
 MPV_DTYPE_F32 = 0
 MPV_DTYPE_BF16 = 1
 
@@ -376,7 +385,7 @@ def mpv_fill_uniforms(seed, count, out=None, device="cuda", stream=None):
     return out
 
 
-MPV_KERNEL_NAMES = {0: "init", 1: "node_task", 2: "walk", 3: "sample", 4: "debug_stats"}
+MPV_KERNEL_NAMES = {0: "init", 1: "node_task", 2: "debug_stats"}
 
 
 def mpv_timing_enable(max_launches):

@@ -90,6 +90,7 @@ struct QueuePlan {
     // out to be rejected as a whole.
     int32_t split_node;
     unsigned long long split_mask;
+
 };
 
 constexpr int kMaxTeam = 16;                          // workgroups per team, at most
@@ -823,10 +824,9 @@ __device__ __forceinline__ void run_sweep(PAIR& pair, const SweepCmd& cmd, float
         s0 = static_cast<double>(f.acc0) + static_cast<double>(f.acc1);
     } else {
         ResidualMassRawF<E> f;
-        f.init();
-        f.k32 = k32; f.nAt = cmd.nAt; f.nAd = cmd.nAd; f.rho = cmd.rho;
+        f.init(k32, cmd.nAt, cmd.nAd, cmd.rho);
         pair.replay(f);
-        s0 = static_cast<double>(f.acc0) + static_cast<double>(f.acc1);
+        s0 = f.total();
     }
     s0 = wave_sum(s0);
     if (SLOPE) s1 = wave_sum(s1);

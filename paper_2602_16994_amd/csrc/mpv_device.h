@@ -331,6 +331,51 @@ struct OnlineLse {
     }
 };
 
+// The same sum for code that every lane of a wave runs together (the node task's sweep over the
+// part it keeps on chip): the reference is one per wave.  It starts as the wave's maximum of the
+// first vector it sees and is moved only when some lane meets a vector whose terms add up to
+// more than 2^kSlack (found by one comparison per vector instead of a running maximum per
+// element; the first vector, measured against the huge negative start value, always does).
+// Exponent arguments therefore stay below kSlack and exact to 2^-21.  The fields are those of
+// OnlineLse (mk the same in every lane of the wave), so lane states combine the same way.
+struct WaveLse : OnlineLse {
+    static constexpr float kSlack = 6.f;
+    template <int COUNT>
+    __device__ __forceinline__ float terms(const float (&z)[COUNT], float k32) const {
+        float t0 = 0.f, t1 = 0.f;
+#pragma unroll
+        for (int i = 0; i + 1 < COUNT; i += 2) {
+            t0 += fast_exp2(fmaf(z[i], k32, -mk));
+            t1 += fast_exp2(fmaf(z[i + 1], k32, -mk));
+        }
+        if (COUNT & 1) t0 += fast_exp2(fmaf(z[COUNT - 1], k32, -mk));
+        return t0 + t1;
+    }
+    // every lane of the wave must call this together
+    template <int COUNT>
+    __device__ __forceinline__ void add(const float (&z)[COUNT], float k32) {
+        float v = terms(z, k32);
+        if (__builtin_amdgcn_ballot_w64(!(v <= 0x1p6f)) != 0ull) {     // (also true for inf)
+            float lm = z[0];
+#pragma unroll
+            for (int i = 1; i < COUNT; ++i) lm = fmaxf(lm, z[i]);
+            const float nmk = wave_max(lm) * k32;
+            if (nmk > mk) {                      // the same in every lane; -inf (nothing but masked entries) moves nothing
+                s *= fast_exp2(mk - nmk);        // first time: 2^-huge = 0, s stays 0
+                mk = nmk;
+                v = terms(z, k32);
+            }
+        }
+        s += v;
+    }
+    template <int VEC>
+    __device__ __forceinline__ void vec(const float (&z)[VEC], float k32) { add(z, k32); }
+    __device__ __forceinline__ void one(float z, float k32) {
+        const float zz[1] = {z};
+        add(zz, k32);
+    }
+};
+
 // Result of the statistics of one row.
 struct RowStat {
     float m;      // max_v z_v  (-inf for a row of -inf)
@@ -491,10 +536,20 @@ struct RetainedPart {
         last_part = member == team_size - 1;
     }
 
+    // the elements before and after the aligned vectors: every lane calls the functor, with
+    // -inf logits (probability zero in every sweep) where it has no such element
     template <class F>
     __device__ __forceinline__ void edges(F& f) const {
-        if (first_part && tid < head) f.one(E::load_one_global(zt + tid), E::load_one_global(zd + tid));
-        if (last_part && tail0 + tid < V) f.one(E::load_one_global(zt + tail0 + tid), E::load_one_global(zd + tail0 + tid));
+        if (first_part && head > 0) {                       // (the same in every lane)
+            float a = -INFINITY, b = -INFINITY;
+            if (tid < head) { a = E::load_one_global(zt + tid); b = E::load_one_global(zd + tid); }
+            f.one(a, b);
+        }
+        if (last_part && tail0 < V) {
+            float a = -INFINITY, b = -INFINITY;
+            if (tail0 + tid < V) { a = E::load_one_global(zt + tail0 + tid); b = E::load_one_global(zd + tail0 + tid); }
+            f.one(a, b);
+        }
     }
 
     // slot s of this lane: its vector number in the row (clamped into the part: always a valid
@@ -533,8 +588,11 @@ struct RetainedPart {
                 d[u] = load_raw_at(bd, vec_of(s + u));
             }
 #pragma unroll
-            for (int u = 0; u < CH; ++u)
-                if (inside(s + u)) f.vec(a[u], d[u]);
+            for (int u = 0; u < CH; ++u) {
+                if (s + u >= nslots) break;               // (the same in every lane)
+                if (!inside(s + u)) { a[u] = NegInfVec<E>::v(); d[u] = NegInfVec<E>::v(); }
+                f.vec(a[u], d[u]);                        // every lane, together
+            }
         }
     }
 
@@ -590,7 +648,7 @@ struct RetainedPart {
 
 template <class E>
 struct PairStatsRawF {
-    OnlineLse t, d;
+    WaveLse t, d;               // (every lane of a wave calls one() and vec() together)
     float k32;
     __device__ __forceinline__ void one(float a, float b) { t.one(a, k32); d.one(b, k32); }
     __device__ __forceinline__ void vec(const uint4& ra, const uint4& rb) {
@@ -676,15 +734,33 @@ struct AcceptanceF {
     }
 };
 
+// The node task's form of it.  Both exponents are lowered by one, so that every term is below
+// 1 and "(x)_+" can be the clamp to [0, 1] that the multiply-add applies to its own result (one
+// instruction less per element); total() undoes the halving.
 template <class E>
-struct ResidualMassRawF : ResidualMassF<E> {
+struct ResidualMassRawF {
+    float k32, nAt, nAd, rho;
+    float acc0, acc1;
+    __device__ __forceinline__ void init(float k, float nat, float nad, float r) {
+        k32 = k; nAt = nat - 1.f; nAd = nad - 1.f; rho = r; acc0 = 0.f; acc1 = 0.f;
+    }
+    __device__ __forceinline__ float term(float a, float b) const {
+        const float et = fast_exp2(fmaf(a, k32, nAt));
+        const float ed = fast_exp2(fmaf(b, k32, nAd));
+        return __builtin_amdgcn_fmed3f(fmaf(-rho, ed, et), 0.f, 1.f);
+    }
+    __device__ __forceinline__ void one(float a, float b) { acc0 += term(a, b); }
     __device__ __forceinline__ void vec(const uint4& ra, const uint4& rb) {
         float a[E::VEC], b[E::VEC];
         E::unpack(ra, a);
         E::unpack(rb, b);
-        ResidualMassF<E>::vec(a, b);
+#pragma unroll
+        for (int i = 0; i < E::VEC; i += 2) {
+            acc0 += term(a[i], b[i]);
+            acc1 += term(a[i + 1], b[i + 1]);
+        }
     }
-    using ResidualMassF<E>::one;
+    __device__ __forceinline__ double total() const { return 2.0 * (static_cast<double>(acc0) + static_cast<double>(acc1)); }
 };
 
 }  // namespace mpv
