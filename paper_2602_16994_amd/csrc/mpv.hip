@@ -572,6 +572,21 @@ struct Team {
     int dead;                        // a partner never answered: results are invalid, every wait is skipped
 };
 
+// What a workgroup carries from task to task, kept in LDS: the functions that run the tasks are
+// not inlined, and state handed to them by reference would live in each lane's private memory.
+// Written by the first lane of the first wave only (between two barriers of the task loop);
+// whoever needs it takes a copy into registers.
+struct LoopState {
+    Team team;
+    int asked;            // the leader has asked for its next task (mailbox says waiting or soon)
+    int own_task;         // leader: a task the team produced for itself, already announced (-1: none);
+                          // member: the task it has already heard of (kNothingHeard: none)
+    int own_flags;
+    int previous_task;    // last task taken from the mailbox
+};
+__shared__ LoopState g_loop;
+constexpr int kNothingHeard = -4;
+
 // First wave only.  Lane w < kExchWords brings `mine`, its 32 bits of payload.  On return
 // g_sh.words[m * kExchWords + w] holds member m's word w (visible to the other waves after the
 // caller's next barrier) and g_sh.dead says whether a partner failed to answer.
@@ -710,7 +725,7 @@ constexpr int kFlagIdle = 1;          // teams were idle after the last round of
 // (defined below) walk and bonus token of tree b, or one draw of a token-following walk, by the
 // whole team; returns the task that follows from it (-1: none; the same in every lane of every member)
 template <class E, int METHOD>
-__device__ __attribute__((noinline)) int sample_task(Team& team_io, int b_in);
+__device__ __attribute__((noinline)) int sample_task(int b_in);
 
 // (defined below) expected block efficiency of tree b from the per-node results, by the first wave
 template <int METHOD>
@@ -857,8 +872,7 @@ __device__ __forceinline__ void collect_sums(Team& t, double& s0, double& s1) {
 }
 
 template <class E, int KIND>
-__device__ __attribute__((noinline)) void run_node_task(Team& team_io, int task_in, int flags_in,
-                                                        bool& asked_io, int& own_task_io, int& own_flags_io) {
+__device__ __attribute__((noinline)) void run_node_task(int task_in, int flags_in) {
     using T = typename E::T;
     constexpr bool ACCEPT = KIND == kKindAcceptance;
     constexpr int METHOD = ACCEPT ? MPV_METHOD_SPECINFER : KIND;
@@ -873,7 +887,7 @@ __device__ __attribute__((noinline)) void run_node_task(Team& team_io, int task_
     uint4* const lds_d = g_rows + kLdsVecs * kTaskBlock;
     const int B = uniform_i32(a.B), N = uniform_i32(a.N), V = uniform_i32(a.V);
     const float k32 = uniform_f32(a.k32);
-    const int member = uniform_i32(team_io.member), team_size = uniform_i32(team_io.size);
+    const int member = uniform_i32(g_loop.team.member), team_size = uniform_i32(g_loop.team.size);
 
     // what a task number stands for (tree, node: made scalar explicitly, so that the table lookups
     // that follow have uniform addresses)
@@ -951,8 +965,8 @@ __device__ __attribute__((noinline)) void run_node_task(Team& team_io, int task_
     }
 
     // ================================================================ the first wave
-    Team team = uniform_struct(team_io);               // in registers while the tasks run
-    bool asked = asked_io;
+    Team team = uniform_struct(g_loop.team);           // in registers while the tasks run
+    bool asked = uniform_i32(g_loop.asked) != 0;
     int own_task = -1, own_flags = 0;
     const bool leader = team.member == 0;
     const bool lead = leader && lane == 0;            // the one lane that talks to the rest of the launch
@@ -1581,10 +1595,12 @@ task_end:
     if (!node_next) {
         if (lane == 0) g_cmd.kind = kCmdDone;
         __syncthreads();                                  // B: the other waves leave
-        team_io = team;
-        asked_io = asked;
-        own_task_io = next;                               // (already announced to, or heard by, the team)
-        own_flags_io = next_flags;
+        if (lane == 0) {
+            g_loop.team = team;
+            g_loop.asked = asked ? 1 : 0;
+            g_loop.own_task = next;                       // (already announced to, or heard by, the team)
+            g_loop.own_flags = next_flags;
+        }
         return;
     }
     task = next;
@@ -1593,8 +1609,11 @@ task_end:
 }
 
 
+// (disable_tail_calls: a call marked as a possible tail call makes the compiler treat the callee
+// as one that must preserve registers for its caller, and the task functions, which use nearly
+// all of them, would save and restore dozens per call in private memory)
 template <class E, int KIND>
-__global__ __launch_bounds__(kTaskBlock) __attribute__((amdgpu_waves_per_eu(3, 3)))
+__global__ __launch_bounds__(kTaskBlock) __attribute__((amdgpu_waves_per_eu(3, 3))) __attribute__((disable_tail_calls))
 void node_task_kernel(const Launch* __restrict__ launch) {
     // KIND: MPV_METHOD_SPECINFER (all top-down rules) or MPV_METHOD_TRAVERSAL, or kKindAcceptance: the
     // top-down kernel reduced to what the acceptance rates need (an instantiation of its own, so that
@@ -1617,9 +1636,12 @@ void node_task_kernel(const Launch* __restrict__ launch) {
     const TreeDesc& tree = g_tree;                // the task loop starts with a barrier
 
     // ---- this workgroup's place in its team
-    Team team;
-    team.size = q.team_size;
+    const bool drop_settled = METHOD == MPV_METHOD_TRAVERSAL && a.lazy != 0;
+    const int wave = uniform_i32(static_cast<int>(threadIdx.x) / kWave);
+    bool leader;
     {
+        Team team;
+        team.size = q.team_size;
         const int i = static_cast<int>(blockIdx.x);
         if (q.same_xcd) {                         // workgroup i runs on chiplet i % 8: keep a team on one
             const int r = i / 8;
@@ -1629,34 +1651,33 @@ void node_task_kernel(const Launch* __restrict__ launch) {
             team.id = i / team.size;
             team.member = i % team.size;
         }
+        team.seq = 0u; team.tseq = 0u; team.dead = 0;
+        team.area = ws.exch + static_cast<size_t>(team.id) * 2 * team.size * kExchWords;
+        team.task_word = ws.team_task + static_cast<size_t>(team.id) * 2;
+        team.t_start = wall_clock64();
+        leader = team.member == 0;
+        if (threadIdx.x == 0) {
+            g_loop.team = team;
+            g_loop.asked = 1;                     // the team starts out waiting
+            g_loop.own_task = leader ? -1 : kNothingHeard;
+            g_loop.own_flags = 0;
+            g_loop.previous_task = -4;            // none yet
+            // the last member to arrive opens the team's mailbox: from then on the dispatcher may hand it tasks
+            const int n_arrived = atomicAdd(&ws.arrived[team.id], 1) + 1;
+            if (n_arrived == team.size) st_relaxed(&ws.mailbox[team.id], kMailboxWaiting);
+        }
     }
-    team.seq = 0u; team.tseq = 0u; team.dead = 0;
-    team.area = ws.exch + static_cast<size_t>(team.id) * 2 * team.size * kExchWords;
-    team.task_word = ws.team_task + static_cast<size_t>(team.id) * 2;
-    team.t_start = wall_clock64();
-    const bool leader = team.member == 0;
-    if (threadIdx.x == 0) {
-        // the last member to arrive opens the team's mailbox: from then on the dispatcher may hand it tasks
-        const int n_arrived = atomicAdd(&ws.arrived[team.id], 1) + 1;
-        if (n_arrived == team.size) st_relaxed(&ws.mailbox[team.id], kMailboxWaiting);
-    }
-
-    const bool drop_settled = METHOD == MPV_METHOD_TRAVERSAL && a.lazy != 0;
-    const int wave = uniform_i32(static_cast<int>(threadIdx.x) / kWave);
     // The first wave's scalar steps are the critical path of every task and few in number: they
     // go first when the compute unit's waves compete for issue slots.
     if (wave == 0) __builtin_amdgcn_s_setprio(3);
-    // The task loop's own state lives in the first wave (the others only sweep):
-    int previous_task = -4;                           // last task taken from the mailbox: none yet
-    bool asked = true;                                // the team starts out waiting
-    // a task this team produced for itself, already announced to the team; a member: the task it
-    // has already heard of (a node task ends with listening for the next), kNothingHeard if none
-    constexpr int kNothingHeard = -4;
-    int own_task = leader ? -1 : kNothingHeard;
-    int own_flags = 0;
     for (;;) {
-    __syncthreads();                                  // the previous task is done with LDS
+    __syncthreads();                                  // the previous task is done with LDS; g_loop is as it left it
     if (wave == 0) {
+        // the task loop's own state: taken from g_loop, put back before the barrier below
+        Team team = uniform_struct(g_loop.team);
+        bool asked = uniform_i32(g_loop.asked) != 0;
+        int own_task = uniform_i32(g_loop.own_task), own_flags = uniform_i32(g_loop.own_flags);
+        int previous_task = uniform_i32(g_loop.previous_task);
         int task = kTaskExit, flags = 0;
         if (team.dead) {
             task = kTaskExit;
@@ -1697,7 +1718,20 @@ void node_task_kernel(const Launch* __restrict__ launch) {
         } else {
             task = team_listen(team, flags, ws);
         }
-        if (threadIdx.x == 0) { sh_task = task; sh_flags = flags; }
+        const bool sampling = task != kTaskExit && task >= a.B * a.N && task < a.B * a.N + a.B && !(ACCEPT || a.estimate);
+        if (sampling && leader && !asked) {
+            // the walk and the bonus token come next: one sweep or two, then the team is free
+            if (threadIdx.x == 0) st_relaxed(&ws.mailbox[team.id], kMailboxSoon);
+            asked = true;
+        }
+        if (threadIdx.x == 0) {
+            g_loop.team = team;
+            g_loop.asked = asked ? 1 : 0;
+            g_loop.own_task = own_task;
+            g_loop.own_flags = own_flags;
+            g_loop.previous_task = previous_task;
+            sh_task = task; sh_flags = flags;
+        }
     }
     __syncthreads();
     const int task = uniform_i32(sh_task), flags = uniform_i32(sh_flags);
@@ -1716,16 +1750,16 @@ void node_task_kernel(const Launch* __restrict__ launch) {
             continue;
         }
         // the tree's outcome is settled: walk and bonus token
-        if (wave == 0 && leader && !asked) {
-            if (threadIdx.x == 0) st_relaxed(&ws.mailbox[team.id], kMailboxSoon);
-            asked = true;
-        }
-        const int next = sample_task<E, METHOD>(team, task - a.B * a.N);
+        const int next = sample_task<E, METHOD>(task - a.B * a.N);
         if (wave == 0 && leader) {
             if (next >= 0) {                          // a token-following walk goes on
-                own_task = next;
-                own_flags = flags;
-                team_announce(team, own_task, own_flags);
+                Team team = uniform_struct(g_loop.team);          // (as sample_task left it)
+                team_announce(team, next, flags);
+                if (threadIdx.x == 0) {
+                    g_loop.team = team;
+                    g_loop.own_task = next;
+                    g_loop.own_flags = flags;
+                }
             }
             if (threadIdx.x == 0) {
                 if (next >= 0) {
@@ -1737,7 +1771,7 @@ void node_task_kernel(const Launch* __restrict__ launch) {
         }
         continue;
     }
-    run_node_task<E, KIND>(team, task, flags, asked, own_task, own_flags);
+    run_node_task<E, KIND>(task, flags);
     }   // task loop
 }
 
@@ -1940,18 +1974,18 @@ struct ResidualTile {
 // member adds up the masses of its tiles, one exchange gives everybody every member's total, and
 // the member whose run contains u * R finds the token.
 template <class E, int METHOD>
-__device__ __attribute__((noinline)) int sample_task(Team& team_io, int b_in) {
+__device__ __attribute__((noinline)) int sample_task(int b_in) {
     using T = typename E::T;
     const Args& a = lds_launch().a;
     const Workspace& ws = lds_launch().ws;
     const TreeDesc& tree = g_tree;
     const int b = uniform_i32(b_in);
     float* const tile_sum = reinterpret_cast<float*>(g_rows);
-    Team team = uniform_struct(team_io);
-    struct WriteBack {
-        Team& t_out; Team& t;
-        __device__ ~WriteBack() { t_out = t; }
-    } write_back{team_io, team};
+    Team team = uniform_struct(g_loop.team);           // every lane its copy; they stay alike
+    struct WriteBack {                                 // (after the function's last barrier: nobody reads the old one any more)
+        Team& t;
+        __device__ ~WriteBack() { if (threadIdx.x == 0) g_loop.team = t; }
+    } write_back{team};
     constexpr int NW = kTaskWaves;
     constexpr int PER_LANE = ResidualTile<E>::PER_LANE;
     constexpr int TILE = ResidualTile<E>::TILE;
