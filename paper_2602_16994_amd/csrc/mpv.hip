@@ -178,7 +178,7 @@ constexpr int kTaskWaves = kTaskBlock / kWave;
 constexpr int kTaskUnroll = 4;
 // node tasks keep their part of a row pair on chip: per lane and row, kRegVecs 16-byte vectors in
 // registers and kLdsVecs in LDS
-constexpr int kRegVecs = 4;
+constexpr int kRegVecs = 6;
 constexpr int kLdsVecs = 6;
 constexpr int kPartCapacity = (kRegVecs + kLdsVecs) * kTaskBlock;     // vectors of a row one member keeps
 // upper bound on the polls of a dependency flag (about a second); see node_task_kernel
@@ -2485,9 +2485,14 @@ template <class E>
 static Shape launch_shape(const mpv_problem* p, int tasks, int per_cu) {
     Shape s;
     const int nvec = (p->V + E::VEC - 1) / E::VEC;
-    int g = 1;
-    while (g < kMaxTeam && static_cast<long long>(g) * kPartCapacity < nvec) g *= 2;
     const int slots = per_cu * compute_units() < kMaxGrid ? per_cu * compute_units() : kMaxGrid;      // workgroups that can be resident
+    // The fewest members whose kept parts (plus the one overflow slot a sweep hides) hold a row:
+    // the most teams, which is what counts when there are more trees than teams.  With fewer
+    // trees a task's own time counts: more members, parts of about 2048 vectors (measured: shorter
+    // parts no longer pay for the larger exchange), as long as every tree still has a team.
+    int g = 1;
+    while (g < kMaxTeam && static_cast<long long>(g) * (kPartCapacity + kTaskBlock / 2) < nvec) ++g;
+    while (g < kMaxTeam && slots / (g + 1) >= p->B && static_cast<long long>(g) * 2048 < nvec) ++g;
     int teams = slots / g;
     if (teams > kMaxTeams) teams = kMaxTeams;
     if (teams > tasks) teams = tasks;

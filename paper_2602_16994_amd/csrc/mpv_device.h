@@ -580,7 +580,7 @@ struct RetainedPart {
     template <class F>
     __device__ __forceinline__ void streamed(F& f) const {
         constexpr int CH = 2;
-        for (int s = R + L; s < nslots; s += CH) {
+        for (int s = R + L + 1; s < nslots; s += CH) {
             uint4 a[CH], d[CH];
 #pragma unroll
             for (int u = 0; u < CH; ++u) {
@@ -598,10 +598,27 @@ struct RetainedPart {
 
     // First sweep: consumes the loads of issue_loads() in the order they were issued, pads the
     // lanes past the end of the part with -inf (kept that way for the later sweeps).
+    // One slot beyond the kept ones (a part slightly too large) is asked for when a sweep starts
+    // and used when it ends: its memory latency hides behind the kept slots.  More than that is
+    // streamed two slots at a time (streamed()).
+    __device__ __forceinline__ bool has_overflow() const { return nslots > R + L; }      // (the same in every lane)
+    __device__ __forceinline__ void ask_overflow(uint4& a, uint4& d) const {
+        a = load_raw_at(bt, vec_of(R + L));
+        d = load_raw_at(bd, vec_of(R + L));
+    }
+    template <class F>
+    __device__ __forceinline__ void use_overflow(F& f, uint4 a, uint4 d) const {
+        if (!inside(R + L)) { a = NegInfVec<E>::v(); d = NegInfVec<E>::v(); }
+        f.vec(a, d);
+    }
+
     template <class F>
     __device__ __forceinline__ void first_pass(F& f) {
         edges(f);
         if (nv <= 0) return;
+        uint4 oa, od;
+        const bool overflow = has_overflow();
+        if (overflow) ask_overflow(oa, od);
 #pragma unroll
         for (int j = 0; j < R; ++j) {
             if (j < nslots) {
@@ -620,6 +637,7 @@ struct RetainedPart {
                 f.vec(a, d);
             }
         }
+        if (overflow) use_overflow(f, oa, od);
         streamed(f);
     }
 
@@ -630,6 +648,9 @@ struct RetainedPart {
     __device__ __forceinline__ void replay(F& f) {
         edges(f);
         if (nv <= 0) return;
+        uint4 oa, od;
+        const bool overflow = has_overflow();
+        if (overflow) ask_overflow(oa, od);
 #pragma unroll
         for (int j = 0; j < L; ++j) {
             if (R + j < nslots) f.vec(lt[j * BLOCK + tid], ld[j * BLOCK + tid]);
@@ -642,6 +663,7 @@ struct RetainedPart {
                 f.vec(rt[j], rd[j]);
             }
         }
+        if (overflow) use_overflow(f, oa, od);
         streamed(f);
     }
 };
