@@ -95,7 +95,7 @@ struct QueuePlan {
 
 constexpr int kMaxTeam = 16;                          // workgroups per team, at most
 constexpr int kExchWords = 8;                         // 64-bit words one member hands over per exchange
-constexpr int kMaxGrid = 768;                        // workgroups of a launch, at most (four per compute unit)
+constexpr int kMaxGrid = 768;                        // workgroups of a launch, at most (three per compute unit)
 
 // Per-(tree,node) scalars kept in the workspace, all double, each [B*N].
 struct Workspace {
@@ -2464,8 +2464,8 @@ static int compute_units() {
 }
 
 // How a launch is shaped: G workgroups per team so that a member's part of a row fits on chip
-// (a power of two, kMaxTeam at most: beyond that the rest of a part is re-read in every sweep),
-// as many teams as there can be tasks at once, four workgroups per compute unit at most.
+// (kMaxTeam at most: beyond that the rest of a part is re-read in every sweep), as many teams
+// as there can be tasks at once, three workgroups per compute unit at most.
 struct Shape { int team_size, teams, part_vecs, same_xcd; };
 
 // Workgroups of a task kernel that one compute unit holds at a time, as the runtime computes it
