@@ -199,6 +199,29 @@ def test_ragged_shapes(method, V, dtype, K, L1, L2, B, T):
     run_case(cfg, method)
 
 
+# How a row is split over a team's workgroups (the launch picks the team size from V, B and the
+# chip): the cases below sit on the edges of that choice.
+TEAM_SHAPES = [
+    # (V, dtype, K, L1, L2, B, T, trees compared)
+    (151937, "bf16", 2, 0, 2, 130, 1.0, 12),   # more trees than teams: the fewest members that hold a row (not a power
+                                              # of two), one slot per lane beyond the kept ones; odd V: misaligned rows,
+                                              # head elements with the first member, tail with the last
+    (450001, "bf16", 2, 0, 1, 2, 0.9, 2),      # beyond what 16 members keep on chip: the rest is read again in every sweep
+    (1 << 21, "bf16", 2, 0, 1, 1, 1.0, 1),     # the largest vocabulary the boundary admits
+    (300001, "f32", 2, 1, 1, 2, 1.0, 2),       # float rows, 16 members, ragged tail
+    (24577, "bf16", 3, 0, 2, 200, 1.0, 8),     # a row that just fits one workgroup, many trees
+]
+
+
+@pytest.mark.parametrize("method", [SI, TV, mpv.MPV_METHOD_SPECTR])
+@pytest.mark.parametrize("V,dtype,K,L1,L2,B,T,ntrees", TEAM_SHAPES)
+def test_team_shapes(method, V, dtype, K, L1, L2, B, T, ntrees):
+    cfg = workloads.Config(f"team_V{V}_{dtype}_B{B}", B=B, V=V, K=K, L1=L1, L2=L2, dtype=dtype,
+                           T=T, methods=[method], draft_sigma=2.0, target_sigma=1.0, seed=V % 9973 + B)
+    step = max(1, B // ntrees)
+    run_case(cfg, method, trees=list(range(0, B, step))[:ntrees])
+
+
 @pytest.mark.parametrize("method", ALL_METHODS)
 def test_root_only_tree(method):
     # N = 1: nothing to verify, the bonus token is a plain sample from p(.|root)
