@@ -1421,17 +1421,42 @@ __device__ __attribute__((noinline)) void run_node_task(int task_in, int flags_i
     //      most likely run next (every member works it out by itself, from the same numbers) is
     //      taken up at once: its rows travel while the leader settles what follows from this
     //      task, and while the others wait to hear of it.
+    int likely = -1;
     if (!team.dead) {
-        int likely = -1;
         if (METHOD == MPV_METHOD_TRAVERSAL) {
             if (paused) likely = b * N + tree.child_list[tree.child_off[n]];
             else if (own_child >= 0 && !own_given) likely = b * N + tree.child_list[tree.child_off[n] + own_child];
         } else if (a.lazy && next_node >= 0 && tree.nchild[next_node] > 0) {
             likely = b * N + next_node;
         }
+    }
+    // The team has asked for its next task ahead of time; if the answer is in the mailbox already
+    // (and nothing of this task's own can come first) the team is told now and takes the task
+    // up, while the leader settles what follows from this one: whatever that produces then goes
+    // to the queue instead of being run by this team.  (Not where the branching node may have to
+    // be resumed: that task has no place in the queue.  Nor with the token-following rules: a
+    // tree can need several draws, the queue has room for one.)
+    int taken = -1;
+    if (leader && likely < 0 && !paused && asked && !team.dead && a.walk == 0 &&
+        !(METHOD == MPV_METHOD_TRAVERSAL && a.lazy && q.split_node >= 0)) {
+        const int previous = uniform_i32(g_loop.previous_task);
+        int t = -1;
+        if (lane == 0) t = ld_relaxed(&ws.mailbox[team.id]);
+        t = uniform_i32(t);
+        if (t >= 0 && t != previous) {
+            taken = t;
+            asked = false;
+            if (lane == 0) g_loop.previous_task = t;
+            team_announce(team, t, uniform_i32(idle_now) != 0 ? kFlagIdle : 0);
+        }
+    }
+    {
+        const int start_now = likely >= 0 ? likely : ((taken >= 0 && !(taken >= B * N && taken < B * N + B)) ? taken : -1);
+        if (start_now >= 0) {
+            start_task(view_of(start_now), start_now);
+            started = start_now;
+        }
         if (likely >= 0) {
-            start_task(view_of(likely), likely);
-            started = likely;
             // Where that task is a child's and nothing else follows from this one (a chain), the
             // team simply goes on with it: every member knows the task and what it starts with,
             // so nothing is announced, nothing waited for, and the outcomes settled here are
@@ -1549,9 +1574,13 @@ __device__ __attribute__((noinline)) void run_node_task(int task_in, int flags_i
             // the expected block efficiency instead of a walk: scalar work over the tree's
             // per-node results, done here and now by this wave (there are no uniforms to walk with)
             estimate_wave<METHOD>(tree, ws, a, b);
+        } else if (taken >= 0) {
+            if (lane == 0) append_task(tree, ws, 0, B * N + b);      // (the results were waited for above)
         } else {
             own_task = B * N + b;
         }
+    } else if (taken >= 0) {
+        // (nothing else can follow from a task that has no child of its own to run)
     } else if (resume_i) {
         own_task = B * N + B + b;
     } else if (METHOD == MPV_METHOD_TRAVERSAL) {
@@ -1574,6 +1603,7 @@ __device__ __attribute__((noinline)) void run_node_task(int task_in, int flags_i
         wait_memory();                                // every new task has been counted
         atomicAdd(&ws.qctl[1], 1);
     }
+    if (taken >= 0) own_task = taken;                 // (announced above; counted when it was queued)
     }   // (the task's own scope)
 task_end:
     // The task that follows: the leader knows (and has told the others, who hear of it here).
