@@ -1229,6 +1229,11 @@ __device__ __attribute__((noinline)) void run_node_task(int task_in, int flags_i
         //   SpecTr     p_acc = 1 - (1 - beta(rho*))^k                          (the search above)
         //   NSS        sum_t p (1 - (1-q)^k)                                    (one sweep)
         //   Naive      sum_t min(p,q) + sum_t (p-q)_+ (1 - (1-q)^(k-1))         (one sweep)
+        // (nothing follows from such a task: the team asks for its next one right away)
+        if (leader && !asked) {
+            if (lane == 0) st_relaxed(&ws.mailbox[team.id], kMailboxSoon);
+            asked = true;
+        }
         double alpha;
         if (a.walk == 3) {
             const double D = fmin(fmax((sp_W + sp_rho - 1.0) / sp_rho, 0.0), 1.0);
@@ -1248,6 +1253,23 @@ __device__ __attribute__((noinline)) void run_node_task(int task_in, int flags_i
             sweep(kCmdAcceptance, rc, static_cast<float>(cold_exp2(static_cast<double>(At_hi) - rt.A)),
                   static_cast<float>(cold_exp2(static_cast<double>(Ad_hi) - rd.A)), a.walk == 1 ? k : k - 1, a.walk == 2 ? 1 : 0, s0, s1);
             alpha = s0;
+        }
+        // the answer may be there already: then the team goes straight on (see the end of the other tasks)
+        if (leader && asked && !team.dead) {
+            const int previous = uniform_i32(g_loop.previous_task);
+            int t = -1;
+            if (lane == 0) t = ld_relaxed(&ws.mailbox[team.id]);
+            t = uniform_i32(t);
+            if (t >= 0 && t != previous) {
+                asked = false;
+                if (lane == 0) g_loop.previous_task = t;
+                team_announce(team, t, 0);
+                if (!(t >= B * N && t < B * N + B)) {
+                    start_task(view_of(t), t);
+                    started = t;
+                }
+                own_task = t;                              // (announced; counted when it was queued)
+            }
         }
         if (lead) {
             as_global(a.alpha)[bn] = static_cast<float>(fmin(fmax(alpha, 0.0), 1.0));
