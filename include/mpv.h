@@ -170,7 +170,13 @@ int mpv_workspace_bytes(const mpv_problem* problem, size_t* out);
  * `workspace` is DEVICE memory, 256-byte aligned, of at least
  * mpv_workspace_bytes() bytes, owned by the caller; its contents on entry are
  * ignored and on exit unspecified.  Two calls that share a workspace or output
- * buffers must be ordered by the caller (same stream, or events). */
+ * buffers must be ordered by the caller (same stream, or events).
+ * The work is done by persistent workgroups grouped in teams; a team takes tasks
+ * only once all its workgroups are running, so a call makes progress with whatever
+ * share of the device it gets (another kernel, or another call on another stream,
+ * may hold compute units).  Every wait inside is bounded (2 s): a launch starved
+ * for longer than that gives up and reports it in counters[MPV_COUNTER_DEPENDENCY_TIMEOUT],
+ * in which case its outputs are invalid. */
 int mpv_verify(const mpv_problem* problem, const mpv_buffers* buffers,
                void* workspace, size_t workspace_bytes, void* hip_stream);
 
