@@ -6,7 +6,7 @@ package is only the ctypes binding and the tree-shape helpers around it.
 
 from .binding import (  # noqa: F401
     MPV_DTYPE_BF16, MPV_DTYPE_F32, MPV_METHOD_SPECINFER, MPV_METHOD_TRAVERSAL, MPV_METHOD_NSS, MPV_METHOD_NAIVE, MPV_METHOD_SPECTR,
-    MpvError, VerifyResult, BlockEfficiencyResult, lib_path, load_library, mpv_block_efficiency, mpv_nucleus_mask, mpv_acceptance_rates,
+    MpvError, MpvTimeout, VerifyResult, BlockEfficiencyResult, lib_path, load_library, mpv_block_efficiency, mpv_nucleus_mask, mpv_acceptance_rates,
     mpv_fill_uniforms, mpv_last_hip_error, mpv_row_stats, mpv_strerror,
     mpv_timing_enable, mpv_timing_read, mpv_verify, mpv_version, mpv_workspace_bytes,
     MPV_KERNEL_NAMES,

@@ -157,6 +157,18 @@ def _dtype_id(t):
     raise TypeError(f"logits must be float32 or bfloat16, got {t.dtype}")
 
 
+class MpvTimeout(RuntimeError):
+    """A wait inside the kernels ran into its time limit: the outputs of that call are invalid."""
+
+
+def _raise_on_timeout(counters, where):
+    """Reads the call's counters (this synchronises with the stream the call ran on) and raises
+    if the library reported a dependency timeout."""
+    n = int(counters[MPV_COUNTER_DEPENDENCY_TIMEOUT].item())
+    if n:
+        raise MpvTimeout(f"{where}: {n} waits inside the kernels timed out; the outputs are invalid")
+
+
 @dataclass
 class VerifyResult:
     accept_len: "object"
@@ -169,6 +181,10 @@ class VerifyResult:
     accept_prob: Optional["object"] = None
     final_residual: Optional["object"] = None
     workspace: Optional["object"] = None
+
+    def raise_on_timeout(self):
+        """Synchronises and raises MpvTimeout if the call gave up on a wait (counters[4] != 0)."""
+        _raise_on_timeout(self.counters, "mpv_verify")
 
 
 def mpv_verify(parent, tokens, target_logits, draft_logits, temperature, uniforms, method,
@@ -258,6 +274,10 @@ class BlockEfficiencyResult:
     reach_prob: "object"        # float32 [B,N]  P(node on the accepted path)
     counters: "object"
     workspace: Optional["object"] = None
+
+    def raise_on_timeout(self):
+        """Synchronises and raises MpvTimeout if the call gave up on a wait (counters[4] != 0)."""
+        _raise_on_timeout(self.counters, "mpv_block_efficiency")
 
 
 def mpv_block_efficiency(parent, tokens, target_logits, draft_logits, temperature, method,
