@@ -377,7 +377,8 @@ __device__ __forceinline__ int atomicCAS(int* p, int expected, int desired) {
 // all loads, stores and atomics issued so far by this lane have been performed
 __device__ __forceinline__ void wait_memory() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
-// Append one task to class c (one lane).  The caller's earlier stores have been waited for.
+// Append one task to class c (one lane).  What the task needs and this lane has stored before
+// is performed before the task can be handed out (the wait below covers it).
 __device__ __forceinline__ void append_task(const TreeDesc& tree, const Workspace& ws, int c, int entry) {
     (void)atomicAdd(&ws.qctl[0], 1);
     wait_memory();                                    // counted before it can be handed out (and finished)
@@ -1353,10 +1354,8 @@ __device__ __attribute__((noinline)) void run_node_task(int task_in, int flags_i
                     // The first child that needs a task is kept for this team (run next,
                     // no queue) unless some team is idle; every other one is queued now,
                     // while this task goes on with the sweeps that follow.
-                    if (run_child && (!first_to_run || own_given) && !child_ahead) {
-                        wait_memory();                    // its starting weight has been written
-                        append_task(tree, ws, tree.cls[cn], b * N + cn);
-                    }
+                    if (run_child && (!first_to_run || own_given) && !child_ahead)
+                        append_task(tree, ws, tree.cls[cn], b * N + cn);      // (waits for the weight's store with its own count)
                 }
             } else {
                 st_shared_f64(&ws.atest[bc], w_child);
