@@ -816,7 +816,10 @@ struct SweepCmd {
     int kind;
     float nAt, nAd, rho;             // constants of the residual sweeps
     float sp, sq;                    // acceptance sweep: scale factors of p and q
-    int m, naive;                    // acceptance sweep: exponent, which formula
+    int m, naive;                    // acceptance sweep: exponent, which formula (kCmdTask: m = the task)
+    int next;                        // a sweep: the task this team goes on with when the sweep was the
+                                     // current task's last (-1: not known); each wave asks for its share
+                                     // of that task's rows as soon as it is done with its share of the sweep
 };
 __shared__ SweepCmd g_cmd;
 
@@ -915,40 +918,54 @@ __device__ __attribute__((noinline)) void run_node_task(int task_in, int flags_i
     if (wave != 0) {
         // ---- a sweeping wave does what the first wave commands: it takes up a task (loads its
         //      share of the pair and runs the statistics sweep) or sweeps once more
+        // what the second wave fetches of the children (kept as stored until the sweep is over)
+        int pf_x = -1;
+        float pf_u = 2.f;
+        T pf_t = 0, pf_d = 0;
+        int asked_for = -1;                               // the task whose rows this wave has asked for already
+        // Asks for this wave's share of task t.  The second wave also fetches what the scalar steps
+        // need of the children (lane j looks after child j): the tokens first, so that they are there
+        // when the row loads have been issued, then the two logits at each token, which return behind
+        // this wave's share of the pair (the statistics sweep waits for that anyway).
+        auto take_up = [&](int t) __attribute__((always_inline)) {
+            const NodeView nv = view_of(t);
+            pf_x = -1; pf_u = 2.f; pf_t = 0; pf_d = 0;
+            if (wave == 1) {
+                if (lane < nv.k && a.tokens) {
+                    const size_t bc = static_cast<size_t>(nv.b) * N + tree.child_list[tree.child_off[nv.n] + lane];
+                    pf_x = as_global(a.tokens)[bc];
+                    if (!a.estimate) pf_u = as_global(a.uniforms)[bc];
+                }
+                if (lane == MPV_MAX_CHILDREN && !a.estimate) pf_u = as_global(a.uniforms)[nv.bn];
+            }
+            int tid_l = threadIdx.x;
+            asm volatile("" : "+v"(tid_l));     // per-task copy: nothing derived from it is kept across tasks
+            pair.setup(nv.zt, nv.zd, V, lds_t, lds_d, tid_l, member, team_size, uniform_i32(q.part_vecs));
+            pair.issue_loads();
+            if (wave == 1 && pf_x >= 0 && pf_x < V) {
+                pf_t = as_global(nv.zt)[pf_x];
+                pf_d = as_global(nv.zd)[pf_x];
+            }
+            asked_for = t;
+        };
         for (;;) {
             __syncthreads();                              // B: the command is there
             const SweepCmd cmd = g_cmd;
             const int kind = uniform_i32(cmd.kind);
-            if (kind == kCmdDone) return;
+            if (kind == kCmdDone) {
+                if (asked_for >= 0) wait_memory();        // (asked for in vain: nothing may land in LDS after this)
+                return;
+            }
             if (kind == kCmdTask) {
-                const NodeView nv = view_of(uniform_i32(cmd.m));
-                int tid_l = threadIdx.x;
-                asm volatile("" : "+v"(tid_l));     // per-task copy: nothing derived from it is kept across tasks
-                pair.setup(nv.zt, nv.zd, V, lds_t, lds_d, tid_l, member, team_size, uniform_i32(q.part_vecs));
-                pair.issue_loads();
-                // The second wave also fetches what the scalar steps need of the children (lane j looks
-                // after child j): loads that depend on loads, kept off the first wave's path.  They
-                // return behind this wave's share of the pair, which the sweep waits for anyway.
-                int pf_x = -1;
-                float pf_u = 2.f;
-                T pf_t = 0, pf_d = 0;       // kept as stored until the sweep is over
-                if (wave == 1) {
-                    if (lane < nv.k && a.tokens) {
-                        const size_t bc = static_cast<size_t>(nv.b) * N + tree.child_list[tree.child_off[nv.n] + lane];
-                        pf_x = as_global(a.tokens)[bc];
-                        if (!a.estimate) pf_u = as_global(a.uniforms)[bc];
-                    }
-                    if (lane == MPV_MAX_CHILDREN && !a.estimate) pf_u = as_global(a.uniforms)[nv.bn];
-                    if (pf_x >= 0 && pf_x < V) {
-                        pf_t = as_global(nv.zt)[pf_x];
-                        pf_d = as_global(nv.zd)[pf_x];
-                    }
-                }
+                const int t = uniform_i32(cmd.m);
+                if (asked_for != t) take_up(t);
+                asked_for = -1;
+                const int kk = uniform_i32(tree.nchild[view_of(t).n]);
                 PairStatsRawF<E> f;
                 f.t.init(); f.d.init(); f.k32 = k32;
                 pair.first_pass(f);
                 if (wave == 1) {
-                    if (lane < nv.k) { ch_tok[lane] = pf_x; ch_u[lane] = pf_u; ch_zt[lane] = E::load_one(&pf_t); ch_zd[lane] = E::load_one(&pf_d); }
+                    if (lane < kk) { ch_tok[lane] = pf_x; ch_u[lane] = pf_u; ch_zt[lane] = E::load_one(&pf_t); ch_zd[lane] = E::load_one(&pf_d); }
                     if (lane == MPV_MAX_CHILDREN) ch_u[MPV_MAX_CHILDREN] = pf_u;
                 }
                 const float Mt_w = wave_max(f.t.mk), Md_w = wave_max(f.d.mk);
@@ -960,6 +977,8 @@ __device__ __attribute__((noinline)) void run_node_task(int task_in, int flags_i
                 }
             } else {
                 run_sweep<E, KIND>(pair, cmd, k32, wave, lane);
+                const int nx = uniform_i32(cmd.next);
+                if (nx >= 0) take_up(nx);                 // this wave's slots are free again: the next task's rows
             }
             __syncthreads();                              // A: this wave's partial sums are there
         }
@@ -1004,16 +1023,17 @@ __device__ __attribute__((noinline)) void run_node_task(int task_in, int flags_i
     if (started != task) start_task(nv, task);            // (else: under way since the end of the task before)
     started = -1;
     double At_ = 0.0, Ad_ = 0.0, wa = 1.0;            // log2-partitions of the two rows; the node's weight
+    int next_hint = -1;                               // goes out with a sweep command (SweepCmd::next)
     // one more sweep by all four waves; the team's sums come back
     auto sweep = [&](int kind, const ResidualConsts& rc, float sp, float sq, int m, int naive, double& s0, double& s1) __attribute__((always_inline)) {
         if (lane == 0) {
             g_cmd.kind = kind; g_cmd.nAt = rc.nAt; g_cmd.nAd = rc.nAd; g_cmd.rho = rc.rho;
-            g_cmd.sp = sp; g_cmd.sq = sq; g_cmd.m = m; g_cmd.naive = naive;
+            g_cmd.sp = sp; g_cmd.sq = sq; g_cmd.m = m; g_cmd.naive = naive; g_cmd.next = next_hint;
         }
         __syncthreads();                                  // B
         SweepCmd cmd;
         cmd.kind = kind; cmd.nAt = uniform_f32(rc.nAt); cmd.nAd = uniform_f32(rc.nAd); cmd.rho = uniform_f32(rc.rho);
-        cmd.sp = sp; cmd.sq = sq; cmd.m = m; cmd.naive = naive;
+        cmd.sp = sp; cmd.sq = sq; cmd.m = m; cmd.naive = naive; cmd.next = -1;
         run_sweep<E, KIND>(pair, cmd, k32, 0, lane);
         __syncthreads();                                  // A
         collect_sums(team, s0, s1);
@@ -1405,7 +1425,11 @@ __device__ __attribute__((noinline)) void run_node_task(int task_in, int flags_i
         if (METHOD == MPV_METHOD_TRAVERSAL && !(wa > 0.0)) continue;   // (0*P - q)_+ = 0: nothing changes
         if (team.dead) break;
         const double c2 = uniform_f64(c + W / wa);
+        // the task's last sweep, and the team goes on with a child's task: the other waves may ask for its rows
+        if (METHOD == MPV_METHOD_TRAVERSAL && j == k - 1 && own_child >= 0 && !own_given)
+            next_hint = b * N + tree.child_list[tree.child_off[n] + own_child];
         const double W2 = residual_mass(c2);
+        next_hint = -1;
         if (W2 > 0.0) {
             if (METHOD == MPV_METHOD_TRAVERSAL) {
                 const double S = (wa / W) * W2;
