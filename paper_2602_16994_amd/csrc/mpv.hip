@@ -924,9 +924,10 @@ __device__ __attribute__((noinline)) void run_node_task(int task_in, int flags_i
         T pf_t = 0, pf_d = 0;
         int asked_for = -1;                               // the task whose rows this wave has asked for already
         // Asks for this wave's share of task t.  The second wave also fetches what the scalar steps
-        // need of the children (lane j looks after child j): the tokens first, so that they are there
-        // when the row loads have been issued, then the two logits at each token, which return behind
-        // this wave's share of the pair (the statistics sweep waits for that anyway).
+        // need of the children (lane j looks after child j): the tokens, then the two logits at each
+        // token, and only then its row loads.  (Loads that depend on loads: issued after the row
+        // loads they would wait for every one of them, the compiler cannot count past the
+        // conditional ones; before them they wait for the tokens alone.)
         auto take_up = [&](int t) __attribute__((always_inline)) {
             const NodeView nv = view_of(t);
             pf_x = -1; pf_u = 2.f; pf_t = 0; pf_d = 0;
@@ -937,15 +938,15 @@ __device__ __attribute__((noinline)) void run_node_task(int task_in, int flags_i
                     if (!a.estimate) pf_u = as_global(a.uniforms)[bc];
                 }
                 if (lane == MPV_MAX_CHILDREN && !a.estimate) pf_u = as_global(a.uniforms)[nv.bn];
+                if (pf_x >= 0 && pf_x < V) {
+                    pf_t = as_global(nv.zt)[pf_x];
+                    pf_d = as_global(nv.zd)[pf_x];
+                }
             }
             int tid_l = threadIdx.x;
             asm volatile("" : "+v"(tid_l));     // per-task copy: nothing derived from it is kept across tasks
             pair.setup(nv.zt, nv.zd, V, lds_t, lds_d, tid_l, member, team_size, uniform_i32(q.part_vecs));
             pair.issue_loads();
-            if (wave == 1 && pf_x >= 0 && pf_x < V) {
-                pf_t = as_global(nv.zt)[pf_x];
-                pf_d = as_global(nv.zd)[pf_x];
-            }
             asked_for = t;
         };
         for (;;) {
