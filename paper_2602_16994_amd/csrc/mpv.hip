@@ -806,6 +806,16 @@ __device__ __forceinline__ void team_stats(Team& t, const OnlineLse& lt, const O
 // next task; the task it is to run next, already announced to the team, and its flags); only the
 // first wave's copies matter.
 
+// The barrier between the waves of a workgroup inside a node task.  What the waves hand each other
+// there goes through LDS only (the command, partial sums, the children's scalars), so the barrier
+// waits for this wave's LDS operations and nothing else: __syncthreads() would also wait for every
+// global load in flight, i.e. for the rows of the next task that have just been asked for.
+__device__ __forceinline__ void task_barrier() {
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+}
+
 constexpr int kCmdTask = 5;
 constexpr int kCmdDone = 0;          // the task is over
 constexpr int kCmdMass = 1;          // sum (p - rho q)_+
@@ -950,7 +960,7 @@ __device__ __attribute__((noinline)) void run_node_task(int task_in, int flags_i
             asked_for = t;
         };
         for (;;) {
-            __syncthreads();                              // B: the command is there
+            task_barrier();                                // B: the command is there
             const SweepCmd cmd = g_cmd;
             const int kind = uniform_i32(cmd.kind);
             if (kind == kCmdDone) {
@@ -981,7 +991,7 @@ __device__ __attribute__((noinline)) void run_node_task(int task_in, int flags_i
                 const int nx = uniform_i32(cmd.next);
                 if (nx >= 0) take_up(nx);                 // this wave's slots are free again: the next task's rows
             }
-            __syncthreads();                              // A: this wave's partial sums are there
+            task_barrier();                                // A: this wave's partial sums are there
         }
     }
 
@@ -994,7 +1004,7 @@ __device__ __attribute__((noinline)) void run_node_task(int task_in, int flags_i
     // Takes a task up: the other waves are told, this wave's share of the pair is asked for.
     auto start_task = [&](const NodeView& v, int t) __attribute__((always_inline)) {
         if (lane == 0) { g_cmd.kind = kCmdTask; g_cmd.m = t; }
-        __syncthreads();                                  // B: the other waves take the task up
+        task_barrier();                                    // B: the other waves take the task up
         int tid_l = threadIdx.x;
         asm volatile("" : "+v"(tid_l));     // per-task copy: nothing derived from it is kept across tasks
         pair.setup(v.zt, v.zd, V, lds_t, lds_d, tid_l, member, team_size, uniform_i32(q.part_vecs));
@@ -1031,12 +1041,12 @@ __device__ __attribute__((noinline)) void run_node_task(int task_in, int flags_i
             g_cmd.kind = kind; g_cmd.nAt = rc.nAt; g_cmd.nAd = rc.nAd; g_cmd.rho = rc.rho;
             g_cmd.sp = sp; g_cmd.sq = sq; g_cmd.m = m; g_cmd.naive = naive; g_cmd.next = next_hint;
         }
-        __syncthreads();                                  // B
+        task_barrier();                                    // B
         SweepCmd cmd;
         cmd.kind = kind; cmd.nAt = uniform_f32(rc.nAt); cmd.nAd = uniform_f32(rc.nAd); cmd.rho = uniform_f32(rc.rho);
         cmd.sp = sp; cmd.sq = sq; cmd.m = m; cmd.naive = naive; cmd.next = -1;
         run_sweep<E, KIND>(pair, cmd, k32, 0, lane);
-        __syncthreads();                                  // A
+        task_barrier();                                    // A
         collect_sums(team, s0, s1);
     };
     // W(c) for one c
@@ -1107,7 +1117,7 @@ __device__ __attribute__((noinline)) void run_node_task(int task_in, int flags_i
             g_sh.partf[0][0] = Mt_w; g_sh.partf[0][1] = Md_w;
             g_sh.part[0][0] = st_w; g_sh.part[0][1] = sd_w;
         }
-        __syncthreads();                                  // A: every wave's partials are there
+        task_barrier();                                    // A: every wave's partials are there
         un = ch_u[MPV_MAX_CHILDREN];
         team.seq++;
         float Mt = g_sh.partf[0][0], Md = g_sh.partf[0][1];
@@ -1664,13 +1674,13 @@ task_end:
     if (started >= 0 && (!node_next || next != started)) {
         // taken up in vain (the tree was settled meanwhile, or the task went elsewhere): the other
         // waves finish their sweep, this wave's loads land, and the slots are free again
-        __syncthreads();                                  // A
+        task_barrier();                                    // A
         wait_memory();
         started = -1;
     }
     if (!node_next) {
         if (lane == 0) g_cmd.kind = kCmdDone;
-        __syncthreads();                                  // B: the other waves leave
+        task_barrier();                                    // B: the other waves leave
         if (lane == 0) {
             g_loop.team = team;
             g_loop.asked = asked ? 1 : 0;
