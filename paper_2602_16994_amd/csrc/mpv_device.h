@@ -556,6 +556,9 @@ struct RetainedPart {
     // address when the part is not empty) and whether it lies inside the part
     __device__ __forceinline__ int vec_of(int s) const { return v0 + min(s * BLOCK + tid, nv - 1); }
     __device__ __forceinline__ bool inside(int s) const { return s * BLOCK + tid < nv; }
+    // every lane of the workgroup owns a vector in slot s (the same in every lane: a branch, so
+    // that full slots do not pay for the padding of the last one)
+    __device__ __forceinline__ bool full_slot(int s) const { return (s + 1) * BLOCK <= nv; }
 
     // Put every load of the kept slots in flight (registers first: they are consumed first).
     // An empty part (nv = 0) loads nothing.
@@ -622,7 +625,9 @@ struct RetainedPart {
 #pragma unroll
         for (int j = 0; j < R; ++j) {
             if (j < nslots) {
-                if (!inside(j)) { rt[j] = NegInfVec<E>::v(); rd[j] = NegInfVec<E>::v(); }
+                if (!full_slot(j)) {
+                    if (!inside(j)) { rt[j] = NegInfVec<E>::v(); rd[j] = NegInfVec<E>::v(); }
+                }
                 f.vec(rt[j], rd[j]);
             }
         }
@@ -630,9 +635,11 @@ struct RetainedPart {
         for (int j = 0; j < L; ++j) {
             if (R + j < nslots) {
                 uint4 a = lt[j * BLOCK + tid], d = ld[j * BLOCK + tid];
-                if (!inside(R + j)) {
-                    a = NegInfVec<E>::v(); d = NegInfVec<E>::v();
-                    lt[j * BLOCK + tid] = a; ld[j * BLOCK + tid] = d;        // the lane's own entry
+                if (!full_slot(R + j)) {
+                    if (!inside(R + j)) {
+                        a = NegInfVec<E>::v(); d = NegInfVec<E>::v();
+                        lt[j * BLOCK + tid] = a; ld[j * BLOCK + tid] = d;        // the lane's own entry
+                    }
                 }
                 f.vec(a, d);
             }
