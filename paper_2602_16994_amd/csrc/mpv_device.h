@@ -342,13 +342,15 @@ struct WaveLse : OnlineLse {
     static constexpr float kSlack = 6.f;
     template <int COUNT>
     __device__ __forceinline__ float terms(const float (&z)[COUNT], float k32) const {
-        float t0 = 0.f, t1 = 0.f;
+        if (COUNT == 1) return fast_exp2(fmaf(z[0], k32, -mk));
+        float t0 = fast_exp2(fmaf(z[0], k32, -mk));            // (started with the first terms: no 0 + x)
+        float t1 = fast_exp2(fmaf(z[COUNT > 1 ? 1 : 0], k32, -mk));
 #pragma unroll
-        for (int i = 0; i + 1 < COUNT; i += 2) {
+        for (int i = 2; i + 1 < COUNT; i += 2) {
             t0 += fast_exp2(fmaf(z[i], k32, -mk));
             t1 += fast_exp2(fmaf(z[i + 1], k32, -mk));
         }
-        if (COUNT & 1) t0 += fast_exp2(fmaf(z[COUNT - 1], k32, -mk));
+        if (COUNT > 1 && (COUNT & 1)) t0 += fast_exp2(fmaf(z[COUNT - 1], k32, -mk));
         return t0 + t1;
     }
     // every lane of the wave must call this together
