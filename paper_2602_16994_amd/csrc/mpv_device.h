@@ -37,9 +37,21 @@ __device__ __forceinline__ uint4 load_global_16B(const void* p) {
 
 // ---------------------------------------------------------------- element types
 
+// What a node task keeps on chip is the row as stored, except for bf16 rows: those are kept as
+// IEEE half precision, to which the statistics sweep converts them while it has them unpacked
+// anyway.  Every bf16 logit of ordinary size is a half-precision number too (8 significant bits
+// against 11; exponents from 2^-14 to 2^15, below that down to 2^-24 with the bits that are left,
+// which moves an exponent argument by less than 2^-24), and the multiply-add that forms the
+// exponent argument reads a half-precision operand directly (v_fma_mix_f32): the later sweeps
+// save the two instructions per element pair that unpacking bf16 costs.
 struct ElemF32 {
     using T = float;
     static constexpr int VEC = 4;                       // elements per 16-byte load
+    static constexpr bool KEPT_AS_HALF = false;
+    __device__ static __forceinline__ void unpack_kept(const uint4& r, float (&o)[VEC]) { unpack(r, o); }
+    __device__ static __forceinline__ uint4 pack_kept(const float (&o)[VEC]) {
+        return make_uint4(__float_as_uint(o[0]), __float_as_uint(o[1]), __float_as_uint(o[2]), __float_as_uint(o[3]));
+    }
     __device__ static __forceinline__ float load_one(const T* p) { return *p; }
     __device__ static __forceinline__ float load_one_global(const T* p) { return *as_global(p); }
     __device__ static __forceinline__ void unpack(const uint4& r, float (&o)[VEC]) {
@@ -51,9 +63,25 @@ struct ElemF32 {
     }
 };
 
+typedef _Float16 mpv_half2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ unsigned pack_half2(float lo, float hi) {
+    // (round toward zero: the values are exact in half precision wherever that matters)
+    return __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pkrtz(lo, hi));
+}
+__device__ __forceinline__ float half_lo(unsigned w) { return static_cast<float>(__builtin_bit_cast(mpv_half2, w).x); }
+__device__ __forceinline__ float half_hi(unsigned w) { return static_cast<float>(__builtin_bit_cast(mpv_half2, w).y); }
+
 struct ElemBF16 {
     using T = uint16_t;
     static constexpr int VEC = 8;
+    static constexpr bool KEPT_AS_HALF = true;
+    __device__ static __forceinline__ void unpack_kept(const uint4& r, float (&o)[VEC]) {
+        o[0] = half_lo(r.x); o[1] = half_hi(r.x); o[2] = half_lo(r.y); o[3] = half_hi(r.y);
+        o[4] = half_lo(r.z); o[5] = half_hi(r.z); o[6] = half_lo(r.w); o[7] = half_hi(r.w);
+    }
+    __device__ static __forceinline__ uint4 pack_kept(const float (&o)[VEC]) {
+        return make_uint4(pack_half2(o[0], o[1]), pack_half2(o[2], o[3]), pack_half2(o[4], o[5]), pack_half2(o[6], o[7]));
+    }
     __device__ static __forceinline__ float load_one(const T* p) {
         return __uint_as_float(static_cast<uint32_t>(*p) << 16);
     }
@@ -630,20 +658,37 @@ struct RetainedPart {
                 if (!full_slot(j)) {
                     if (!inside(j)) { rt[j] = NegInfVec<E>::v(); rd[j] = NegInfVec<E>::v(); }
                 }
-                f.vec(rt[j], rd[j]);
+                if (E::KEPT_AS_HALF) {              // swept as stored, then kept in the form the later sweeps read
+                    float a[VEC], d[VEC];
+                    E::unpack(rt[j], a);
+                    E::unpack(rd[j], d);
+                    f.vecf(a, d);
+                    rt[j] = E::pack_kept(a);
+                    rd[j] = E::pack_kept(d);
+                } else {
+                    f.vec(rt[j], rd[j]);
+                }
             }
         }
 #pragma unroll
         for (int j = 0; j < L; ++j) {
             if (R + j < nslots) {
                 uint4 a = lt[j * BLOCK + tid], d = ld[j * BLOCK + tid];
+                bool padded = false;
                 if (!full_slot(R + j)) {
-                    if (!inside(R + j)) {
-                        a = NegInfVec<E>::v(); d = NegInfVec<E>::v();
-                        lt[j * BLOCK + tid] = a; ld[j * BLOCK + tid] = d;        // the lane's own entry
-                    }
+                    if (!inside(R + j)) { a = NegInfVec<E>::v(); d = NegInfVec<E>::v(); padded = true; }
                 }
-                f.vec(a, d);
+                if (E::KEPT_AS_HALF) {
+                    float fa[VEC], fd[VEC];
+                    E::unpack(a, fa);
+                    E::unpack(d, fd);
+                    f.vecf(fa, fd);
+                    lt[j * BLOCK + tid] = E::pack_kept(fa);                  // the lane's own entry
+                    ld[j * BLOCK + tid] = E::pack_kept(fd);
+                } else {
+                    if (padded) { lt[j * BLOCK + tid] = a; ld[j * BLOCK + tid] = d; }
+                    f.vec(a, d);
+                }
             }
         }
         if (overflow) use_overflow(f, oa, od);
@@ -662,14 +707,14 @@ struct RetainedPart {
         if (overflow) ask_overflow(oa, od);
 #pragma unroll
         for (int j = 0; j < L; ++j) {
-            if (R + j < nslots) f.vec(lt[j * BLOCK + tid], ld[j * BLOCK + tid]);
+            if (R + j < nslots) f.vec_kept(lt[j * BLOCK + tid], ld[j * BLOCK + tid]);
         }
 #pragma unroll
         for (int j = 0; j < R; ++j) {
             if (j < nslots) {
                 asm volatile("" : "+v"(rt[j].x), "+v"(rt[j].y), "+v"(rt[j].z), "+v"(rt[j].w));
                 asm volatile("" : "+v"(rd[j].x), "+v"(rd[j].y), "+v"(rd[j].z), "+v"(rd[j].w));
-                f.vec(rt[j], rd[j]);
+                f.vec_kept(rt[j], rd[j]);
             }
         }
         if (overflow) use_overflow(f, oa, od);
@@ -682,12 +727,15 @@ struct PairStatsRawF {
     WaveLse t, d;               // (every lane of a wave calls one() and vec() together)
     float k32;
     __device__ __forceinline__ void one(float a, float b) { t.one(a, k32); d.one(b, k32); }
+    __device__ __forceinline__ void vecf(const float (&a)[E::VEC], const float (&b)[E::VEC]) {
+        t.vec(a, k32);
+        d.vec(b, k32);
+    }
     __device__ __forceinline__ void vec(const uint4& ra, const uint4& rb) {
         float a[E::VEC], b[E::VEC];
         E::unpack(ra, a);
         E::unpack(rb, b);
-        t.vec(a, k32);
-        d.vec(b, k32);
+        vecf(a, b);
     }
 };
 
@@ -706,15 +754,24 @@ struct ResidualMassSlopeRawF {
         q += diff > 0.f ? ed : 0.f;
     }
     __device__ __forceinline__ void one(float a, float b) { term(a, b, acc0, q0); }
-    __device__ __forceinline__ void vec(const uint4& ra, const uint4& rb) {
-        float a[E::VEC], b[E::VEC];
-        E::unpack(ra, a);
-        E::unpack(rb, b);
+    __device__ __forceinline__ void vecf(const float (&a)[E::VEC], const float (&b)[E::VEC]) {
 #pragma unroll
         for (int i = 0; i < E::VEC; i += 2) {
             term(a[i], b[i], acc0, q0);
             term(a[i + 1], b[i + 1], acc1, q1);
         }
+    }
+    __device__ __forceinline__ void vec(const uint4& ra, const uint4& rb) {          // a vector as stored
+        float a[E::VEC], b[E::VEC];
+        E::unpack(ra, a);
+        E::unpack(rb, b);
+        vecf(a, b);
+    }
+    __device__ __forceinline__ void vec_kept(const uint4& ra, const uint4& rb) {     // a vector as kept on chip
+        float a[E::VEC], b[E::VEC];
+        E::unpack_kept(ra, a);
+        E::unpack_kept(rb, b);
+        vecf(a, b);
     }
 };
 
@@ -763,6 +820,12 @@ struct AcceptanceF {
         E::unpack(rb, b);
         vec(a, b);
     }
+    __device__ __forceinline__ void vec_kept(const uint4& ra, const uint4& rb) {     // a vector as kept on chip
+        float a[E::VEC], b[E::VEC];
+        E::unpack_kept(ra, a);
+        E::unpack_kept(rb, b);
+        vec(a, b);
+    }
 };
 
 // The node task's form of it.  Both exponents are lowered by one, so that every term is below
@@ -781,15 +844,24 @@ struct ResidualMassRawF {
         return __builtin_amdgcn_fmed3f(fmaf(-rho, ed, et), 0.f, 1.f);
     }
     __device__ __forceinline__ void one(float a, float b) { acc0 += term(a, b); }
-    __device__ __forceinline__ void vec(const uint4& ra, const uint4& rb) {
-        float a[E::VEC], b[E::VEC];
-        E::unpack(ra, a);
-        E::unpack(rb, b);
+    __device__ __forceinline__ void vecf(const float (&a)[E::VEC], const float (&b)[E::VEC]) {
 #pragma unroll
         for (int i = 0; i < E::VEC; i += 2) {
             acc0 += term(a[i], b[i]);
             acc1 += term(a[i + 1], b[i + 1]);
         }
+    }
+    __device__ __forceinline__ void vec(const uint4& ra, const uint4& rb) {          // a vector as stored
+        float a[E::VEC], b[E::VEC];
+        E::unpack(ra, a);
+        E::unpack(rb, b);
+        vecf(a, b);
+    }
+    __device__ __forceinline__ void vec_kept(const uint4& ra, const uint4& rb) {     // a vector as kept on chip
+        float a[E::VEC], b[E::VEC];
+        E::unpack_kept(ra, a);
+        E::unpack_kept(rb, b);
+        vecf(a, b);
     }
     __device__ __forceinline__ double total() const { return 2.0 * (static_cast<double>(acc0) + static_cast<double>(acc1)); }
 };
