@@ -82,7 +82,10 @@ extern "C" {
 #define MPV_METHOD_SPECTR    4
 
 #define MPV_DTYPE_F32  0      /* IEEE binary32 logits                      */
-#define MPV_DTYPE_BF16 1      /* bfloat16 logits (upper half of binary32)  */
+#define MPV_DTYPE_BF16 1      /* bfloat16 logits (upper half of binary32).  Finite values must lie
+                               * within +-65504; magnitudes below 2^-14 are used to within 2^-25
+                               * (an error of log2(e)/T * 2^-25 in the exponent of e^(z/T): nothing
+                               * for T >= 0.01).  -inf marks a token of probability zero.        */
 
 /* error codes: 0 = success, negative = failure (nothing was launched unless the
  * code is MPV_ERR_HIP, in which case some kernels may already be enqueued) */

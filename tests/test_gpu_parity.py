@@ -222,6 +222,16 @@ def test_team_shapes(method, V, dtype, K, L1, L2, B, T, ntrees):
     run_case(cfg, method, trees=list(range(0, B, step))[:ntrees])
 
 
+@pytest.mark.parametrize("method", [SI, TV])
+@pytest.mark.parametrize("scale", [2000.0, 2e-4])
+def test_logit_magnitudes(method, scale):
+    """bf16 rows are kept on chip in half precision: logits of thousands and of thousandths (with a
+    temperature to match) must come out as exactly as ordinary ones."""
+    cfg = workloads.Config(f"scale_{scale}", B=4, V=40000, K=3, L1=1, L2=2, dtype="bf16", T=0.5 * scale,
+                           methods=[method], draft_sigma=2.0 * scale, target_sigma=1.0 * scale, seed=77)
+    run_case(cfg, method)
+
+
 @pytest.mark.parametrize("method", ALL_METHODS)
 def test_root_only_tree(method):
     # N = 1: nothing to verify, the bonus token is a plain sample from p(.|root)
