@@ -320,7 +320,7 @@ def spectr_solver(P, Q, xs, decide):
 _SOLVERS = {NSS: nss_solver, NAIVE: naive_solver, SPECTR: spectr_solver}
 
 
-def token_walk(solver, children, tokens, p_of, q_of, decide, draw):
+def token_walk(solver, children, tokens, p_of, q_of, decide, draw, node_of=None):
     """Top-down walk (Sec. 3.2) for solvers whose output can be any token.
 
     At node n the solver either accepts a child or hands back the (unnormalised)
@@ -329,6 +329,10 @@ def token_walk(solver, children, tokens, p_of, q_of, decide, draw):
     there, otherwise it ends.  A leaf has no draft tokens: Y ~ p, and the walk
     ends.  Returns (stop_node, final_token, r_last): the node the walk ended in,
     the token drawn there and the vector it was drawn from.
+
+    node_of (Def. 3.1: a child list can name one node several times, each entry
+    with a number and a uniform of its own): node_of[c] is the node that entry c
+    stands for, where the walk goes on when c is accepted; None: c itself.
     """
     n = 0
     while True:
@@ -337,7 +341,7 @@ def token_walk(solver, children, tokens, p_of, q_of, decide, draw):
         i, r = solver(p_of(n), np.asarray(q_of(n), dtype=np.float64) if ch else None, xs,
                       lambda i, a: decide(ch[i], a))
         if i is not None:
-            n = ch[i]
+            n = ch[i] if node_of is None else int(node_of[ch[i]])
             continue
         y = draw(n, r)
         match = [c for c, x in zip(ch, xs) if x == y]
@@ -364,13 +368,14 @@ class _RowCache:
         return self.rows[n]
 
 
-def verify_tree(method, parent, tokens, target_logits, draft_logits, T, u, u_draw=None):
+def verify_tree(method, parent, tokens, target_logits, draft_logits, T, u, u_draw=None, node_of=None):
     """Sample mode for ONE tree.
 
     parent: [N] ints; tokens: [N] ints (tokens[0] ignored); target_logits,
     draft_logits: [N, V] arrays holding the exact stored logit values;
-    u: [N] uniforms in [0,1); u_draw: [N] more uniforms, needed by NSS and NAIVE
-    only (the draw at node n).  Returns a dict with
+    u: [N] uniforms in [0,1); u_draw: [N] more uniforms, needed by NSS, NAIVE and
+    SPECTR only (the draw at node n); node_of: see token_walk (those methods only).
+    Returns a dict with
       stop_node, accept_len, path_nodes, path_tokens, bonus_token,
       residual (float64 [V], normalised), decisions [(node, a, u, accepted)],
       min_margin (smallest |a - u| over decisions with a < 1, or inf),
@@ -394,7 +399,7 @@ def verify_tree(method, parent, tokens, target_logits, draft_logits, T, u, u_dra
             draws.append((int(n), int(t), float(g)))
             return t
 
-        stop, bonus, P = token_walk(_SOLVERS[method], children, tokens, p_of, q_of, decide, draw)
+        stop, bonus, P = token_walk(_SOLVERS[method], children, tokens, p_of, q_of, decide, draw, node_of)
         gap = min(g for (_, _, g) in draws)
     else:
         stop, P = _RULES[method](children, tokens, p_of, q_of, decide)
@@ -424,7 +429,7 @@ def verify_batch(method, parent, tokens, target_logits, draft_logits, T, u, u_dr
     ]
 
 
-def enumerate_outcomes(method, parent, tokens, p_of, q_of):
+def enumerate_outcomes(method, parent, tokens, p_of, q_of, node_of=None):
     """Probability mode: every reachable (stop_node, P) with its probability.
 
     Each test of a node with acceptance probability a is branched into
@@ -433,7 +438,7 @@ def enumerate_outcomes(method, parent, tokens, p_of, q_of):
     """
     children = children_lists(parent)
     if method in _SOLVERS:
-        return _enumerate_token_walk(_SOLVERS[method], children, tokens, p_of, q_of)
+        return _enumerate_token_walk(_SOLVERS[method], children, tokens, p_of, q_of, node_of)
     rule = _RULES[method]
     outcomes = []
     pending = [[]]                      # decision scripts still to run
@@ -459,7 +464,7 @@ def enumerate_outcomes(method, parent, tokens, p_of, q_of):
     return outcomes
 
 
-def _enumerate_token_walk(solver, children, tokens, p_of, q_of):
+def _enumerate_token_walk(solver, children, tokens, p_of, q_of, node_of=None):
     """Probability mode of token_walk: every test is branched as in
     enumerate_outcomes, every draw into one branch per token of positive mass.
     Returns (prob, stop_node, final_token) triples (the final token in place of
@@ -486,7 +491,7 @@ def _enumerate_token_walk(solver, children, tokens, p_of, q_of):
             made.append((y, float(r[y] / np.sum(r)), others))
             return y
 
-        stop, y, _ = token_walk(solver, children, tokens, p_of, q_of, decide, draw)
+        stop, y, _ = token_walk(solver, children, tokens, p_of, q_of, decide, draw, node_of)
         prob = 1.0
         for _, w, _ in made:
             prob *= w
