@@ -134,6 +134,59 @@ def other_configs(mpv, torch, workloads, skip, steps=10):
     return res
 
 
+def merged_trees(mpv, torch, workloads, names=("v128k_delayed", "v152k_root"), steps=3):
+    """mpv_verify_merged (draft trees whose nodes are distinct contexts, Def. 3.1) on batches whose
+    rows are functions of the context: time per call with the trees as drafted and with trees of
+    equal shape laid next to each other (one launch per run of equal shapes), next to the plain call
+    on the same batch, and what merging does to the accepted length."""
+    import numpy as np
+    res = {}
+    for name in names:
+        cfg = workloads.CONFIGS[name]
+        inp = workloads.make_context_inputs(cfg, "cuda:0")
+        merged_parent, context_node = mpv.mpv_merge_duplicates(cfg.parent, inp["tokens"].cpu().numpy())
+        order = sorted(range(cfg.B), key=lambda b: tuple(merged_parent[b]))
+        entry = {"B": cfg.B, "N": cfg.N, "V": cfg.V,
+                 "slots_that_repeat_a_context": int((context_node != np.arange(cfg.N)).sum()),
+                 "distinct_shapes": len({tuple(r) for r in merged_parent.tolist()}), "methods": {}}
+
+        def runs(rows):
+            return 1 + sum(1 for b in range(1, len(rows)) if not np.array_equal(rows[b], rows[b - 1]))
+
+        for method in cfg.methods:
+            def timed(batch, rows):
+                def call(out=None):
+                    return mpv.mpv_verify(batch["parent"], batch["tokens"], batch["target"], batch["draft"], cfg.T,
+                                          batch["uniforms"], method, debug=False, out=out,
+                                          draw_uniforms=batch["draw_uniforms"], merged_parent=rows)
+                out = call()
+                call(out)
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                for _ in range(steps):
+                    call(out)
+                torch.cuda.synchronize()
+                sec = (time.perf_counter() - t0) / steps
+                if out.counters.tolist()[4] != 0:
+                    raise RuntimeError(f"merged {name}/{METHOD_LABEL[method]}: dependency timeouts")
+                return sec, out
+            sec_plain, out_plain = timed(inp, None)
+            sec_drafted, out_merged = timed(inp, merged_parent)
+            moved = workloads.reorder_trees(inp, order)
+            sec_sorted, _ = timed(moved, merged_parent[order])
+            del moved
+            entry["methods"][METHOD_LABEL[method]] = {
+                "plain_call_ms": sec_plain * 1e3,
+                "merged_as_drafted": {"launches": runs(merged_parent), "ms_per_step": sec_drafted * 1e3},
+                "merged_sorted_by_shape": {"launches": runs(merged_parent[order]), "ms_per_step": sec_sorted * 1e3},
+                "mean_accept_len_plain": float(out_plain.accept_len.float().mean().item()),
+                "mean_accept_len_merged": float(out_merged.accept_len.float().mean().item())}
+        res[name] = entry
+        del inp
+        torch.cuda.empty_cache()
+    return res
+
+
 def side_measurements(mpv, torch, cfg, inputs, method, pair_bytes, steps=5):
     """Two reference points for the roofline, outside the timed region.
     every_node_task: the same call with the per-node test probabilities requested, which makes the
@@ -332,6 +385,7 @@ def main():
     if not args.no_extra:
         result["also_measured"] = side_measurements(mpv, torch, cfg, inputs, method, pair_bytes)
         result["also_measured"]["configs"] = other_configs(mpv, torch, workloads, cfg.name)
+        result["also_measured"]["merged_trees"] = merged_trees(mpv, torch, workloads)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, inputs, method)
     print(json.dumps(result))

@@ -67,7 +67,7 @@
 extern "C" {
 #endif
 
-#define MPV_ABI_VERSION 7
+#define MPV_ABI_VERSION 8
 
 /* limits (larger requests return MPV_ERR_UNSUPPORTED) */
 #define MPV_MAX_NODES    64   /* nodes per tree, root included            */
@@ -195,6 +195,42 @@ int mpv_verify(const mpv_problem* problem, const mpv_buffers* buffers,
  * the previous call's contents; the call itself clears what it needs. */
 #define MPV_STATIC_WORKSPACE_BYTES (4u << 20)
 int mpv_verify_static(const mpv_problem* problem, const mpv_buffers* buffers, void* hip_stream);
+
+/* Draft trees whose nodes are distinct contexts (Sec. 3, Def. 3.1 and its footnote; Sec. 5, Def. 5.2:
+ * paths can overlap after the branching node).  Drafting lays every tree out as `parent` says, each
+ * path owning its slots (one row pair, one token, one uniform per slot).  In the tree of Def. 3.1
+ * slots drafted for the same context are one node, and the child list of a node keeps one entry per
+ * drafted token, in slot order, so it can name the same child several times.
+ * mpv_merge_duplicates builds that tree for each of the B token assignments without moving data:
+ *   merged_parent[b,n] = the node of the context slot n was drafted after (-1 for n = 0);
+ *   context_node[b,n]  = the node of slot n's own context: the first slot (lowest index) drafted for
+ *                        it; n itself unless n is a later entry for the same token ("repeat").
+ * In merged_parent a repeat has no children (they hang under context_node[b,n] instead), and
+ * merged_parent[b,n] < n still holds.  Rows of one context are expected to be equal (the models are
+ * functions of the context); only the rows of context nodes matter.
+ * parent: HOST [N]; tokens: HOST int32 [B,N] (tokens[b,0] ignored); merged_parent: HOST int32 [B,N],
+ * written; context_node: HOST int32 [B,N], written, or NULL.  Host work only: no GPU is touched.
+ * Errors: MPV_ERR_NULL, _BAD_SHAPE (B < 0, N < 1), _UNSUPPORTED (N > MPV_MAX_NODES), _BAD_TREE. */
+int mpv_merge_duplicates(const int32_t* parent, const int32_t* tokens, int32_t B, int32_t N,
+                         int32_t* merged_parent, int32_t* context_node);
+
+/* mpv_verify for a batch in which every tree has a shape of its own: merged_parent is a HOST int32
+ * [B,N] array, row b the parent array of tree b (as mpv_merge_duplicates writes it; any valid parent
+ * arrays will do).  problem->parent is not read.  Everything else (buffers, layouts, workspace size:
+ * what mpv_workspace_bytes gives for a problem of the same B and N, outputs, counters summed over the
+ * batch, errors) is as for mpv_verify; path_nodes name context nodes.
+ * Why a repeat may be a leaf here: under the SpecInfer solver and under Traversal Verification it is
+ * tested only after the first entry for its token was rejected, which leaves that token no residual
+ * mass: it is tested with probability 0 and only its residual step remains (App. B, Alg. 4); NSS and
+ * Naive move to the first child that carries the drawn token, which is the context node.  SpecTr
+ * (App. B, Alg. 3) can accept a repeat on the repeat's own uniform and would have to go on below the
+ * context node: MPV_METHOD_SPECTR returns MPV_ERR_UNSUPPORTED.
+ * Cost: the kernels share one shape per launch, so the call makes one mpv_verify launch per run of
+ * consecutive trees with equal rows in merged_parent, one after the other on `hip_stream`; lay trees
+ * of equal shape next to each other (the shapes are known before the target pass writes its rows).
+ * Nothing is launched unless every run is a valid problem. */
+int mpv_verify_merged(const mpv_problem* problem, const int32_t* merged_parent, const mpv_buffers* buffers,
+                      void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* Expected block efficiency of every tree of the batch with the verification's own
  * randomness integrated out (Sec. 5, Eq. 1-3; branching probabilities of Def. 5.3 by

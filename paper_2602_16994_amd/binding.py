@@ -88,6 +88,12 @@ def load_library(path=None):
                                ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
     lib.mpv_verify_static.restype = ctypes.c_int
     lib.mpv_verify_static.argtypes = [ctypes.POINTER(_Problem), ctypes.POINTER(_Buffers), ctypes.c_void_p]
+    lib.mpv_merge_duplicates.restype = ctypes.c_int
+    lib.mpv_merge_duplicates.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32,
+                                         ctypes.c_void_p, ctypes.c_void_p]
+    lib.mpv_verify_merged.restype = ctypes.c_int
+    lib.mpv_verify_merged.argtypes = [ctypes.POINTER(_Problem), ctypes.c_void_p, ctypes.POINTER(_Buffers),
+                                      ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
     lib.mpv_block_efficiency.restype = ctypes.c_int
     lib.mpv_block_efficiency.argtypes = [ctypes.POINTER(_Problem), ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                          ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p,
@@ -187,9 +193,27 @@ class VerifyResult:
         _raise_on_timeout(self.counters, "mpv_verify")
 
 
+def mpv_merge_duplicates(parent, tokens):
+    """Host call (see include/mpv.h): parent list of N ints, tokens an int32 array [B,N] on the host
+    (numpy, or a CPU torch tensor).  Returns (merged_parent, context_node), numpy int32 [B,N]."""
+    import numpy as np
+    tok = np.ascontiguousarray(np.asarray(tokens), dtype=np.int32)
+    if tok.ndim != 2 or tok.shape[1] != len(parent):
+        raise ValueError("tokens must be [B,N] with N = len(parent)")
+    B, N = tok.shape
+    par = np.ascontiguousarray(np.asarray(parent, dtype=np.int32))
+    merged = np.empty((B, N), dtype=np.int32)
+    context = np.empty((B, N), dtype=np.int32)
+    rc = load_library().mpv_merge_duplicates(par.ctypes.data, tok.ctypes.data, B, N,
+                                             merged.ctypes.data, context.ctypes.data)
+    if rc != 0:
+        raise MpvError(rc, "mpv_merge_duplicates")
+    return merged, context
+
+
 def mpv_verify(parent, tokens, target_logits, draft_logits, temperature, uniforms, method,
                max_depth=None, debug=False, out=None, workspace=None, stream=None, draw_uniforms=None,
-               static_scratch=False):
+               static_scratch=False, merged_parent=None):
     """Enqueue one batched verification on the current (or given) torch stream.
 
     parent: list of N ints (host).  tokens int32 [B,N], target_logits / draft_logits
@@ -199,6 +223,8 @@ def mpv_verify(parent, tokens, target_logits, draft_logits, temperature, uniform
     draw_uniforms float32 [B,N] is needed by MPV_METHOD_NSS, MPV_METHOD_NAIVE and MPV_METHOD_SPECTR (the draw at
     each visited node); with those methods debug=True provides accept_prob and final_residual only.
     static_scratch=True calls mpv_verify_static: no workspace tensor, the library's own device array.
+    merged_parent (numpy int32 [B,N] on the host, one parent array per tree) calls mpv_verify_merged;
+    `parent` then only serves to size the outputs and the workspace.
     """
     import torch
     from .trees import tree_depth
@@ -258,6 +284,16 @@ def mpv_verify(parent, tokens, target_logits, draft_logits, temperature, uniform
                     ptr(out.bonus_token), ptr(out.counters),
                     ptr(out.stats), ptr(out.edge_probs), ptr(out.accept_prob), ptr(out.final_residual),
                     ptr(draw_uniforms))
+    if merged_parent is not None:
+        import numpy as np
+        rows = np.ascontiguousarray(np.asarray(merged_parent), dtype=np.int32)
+        if static_scratch or rows.shape != (B, N):
+            raise ValueError("merged_parent must be [B,N] and cannot be combined with static_scratch")
+        rc = lib.mpv_verify_merged(ctypes.byref(prob), rows.ctypes.data, ctypes.byref(bufs), ptr(workspace),
+                                   ctypes.c_size_t(workspace.numel()), _stream_ptr(stream))
+        if rc != 0:
+            raise MpvError(rc, "mpv_verify_merged")
+        return out
     if static_scratch:
         rc = lib.mpv_verify_static(ctypes.byref(prob), ctypes.byref(bufs), _stream_ptr(stream))
     else:

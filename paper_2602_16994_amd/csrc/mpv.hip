@@ -159,6 +159,8 @@ struct Args {
     // estimate = 2: acceptance rates instead (App. C): per internal node, from its two rows and its
     // number of children alone; no tokens are read, nothing follows the node tasks.  alpha [B,N].
     int32_t estimate = 0;
+    int32_t keep_counters = 0;   // the call continues an earlier one: init_kernel leaves the counters as they are
+    int32_t reserved = 0;
     float* reach_prob = nullptr;
     float* expected = nullptr;
     float* alpha = nullptr;
@@ -280,7 +282,7 @@ __global__ void init_kernel(QueuePlan q, TreeDesc tree, Workspace ws, Args a) {
         for (int w = me; w < kMaxTeams; w += stride) { ws.arrived[w] = 0; ws.mailbox[w] = kMailboxAbsent; }
     }
     if (n == 0) {
-        if (i < MPV_COUNTER_COUNT) a.counters[i] = 0u;
+        if (i < MPV_COUNTER_COUNT && !a.keep_counters) a.counters[i] = 0u;
         if (i == 0) { ws.qctl[0] = q.init_total; ws.qctl[1] = 0; ws.qctl[2] = 0; ws.qctl[3] = 0; ws.qctl[4 + 2 * kMaxClasses] = 0; }
         for (int c = 0; c < kMaxClasses; ++c)
             if (i == 0) {
@@ -2740,8 +2742,13 @@ int mpv_workspace_bytes(const mpv_problem* problem, size_t* out) {
     return MPV_OK;
 }
 
+// part_of_batch: the buffers are those of a larger batch moved on by a whole number of trees (the two
+// logit pointers by the same number of bytes, so the rows of a pair still share their offset modulo 16
+// bytes, which is what the kernels rely on; the caller has checked the batch's own pointers);
+// keep_counters: add to the counters instead of starting them at zero.
 static int verify_with_workspace(const mpv_problem* problem, const mpv_buffers* buf, void* workspace,
-                                 size_t workspace_bytes, void* hip_stream);
+                                 size_t workspace_bytes, void* hip_stream, bool part_of_batch = false,
+                                 bool keep_counters = false);
 
 int mpv_verify(const mpv_problem* problem, const mpv_buffers* buf, void* workspace,
                size_t workspace_bytes, void* hip_stream) {
@@ -2760,7 +2767,7 @@ int mpv_verify_static(const mpv_problem* problem, const mpv_buffers* buf, void* 
 }
 
 static int verify_with_workspace(const mpv_problem* problem, const mpv_buffers* buf, void* workspace,
-                                 size_t workspace_bytes, void* hip_stream) {
+                                 size_t workspace_bytes, void* hip_stream, bool part_of_batch, bool keep_counters) {
     mpv::Plan plan;
     const int rc = mpv::validate(problem, &plan);
     if (rc != MPV_OK) return rc;
@@ -2769,7 +2776,10 @@ static int verify_with_workspace(const mpv_problem* problem, const mpv_buffers* 
     if (!buf->target_logits || !buf->draft_logits || !buf->tokens || !buf->uniforms || !buf->accept_len ||
         !buf->path_nodes || !buf->path_tokens || !buf->bonus_token || !buf->counters)
         return MPV_ERR_NULL;
-    if ((reinterpret_cast<uintptr_t>(buf->target_logits) & 15u) || (reinterpret_cast<uintptr_t>(buf->draft_logits) & 15u))
+    if (!part_of_batch &&
+        ((reinterpret_cast<uintptr_t>(buf->target_logits) & 15u) || (reinterpret_cast<uintptr_t>(buf->draft_logits) & 15u)))
+        return MPV_ERR_ALIGNMENT;
+    if (((reinterpret_cast<uintptr_t>(buf->target_logits) ^ reinterpret_cast<uintptr_t>(buf->draft_logits)) & 15u) != 0)
         return MPV_ERR_ALIGNMENT;
     const size_t need = mpv::carve(problem, nullptr, nullptr);
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) || workspace_bytes < need) return MPV_ERR_WORKSPACE;
@@ -2790,9 +2800,107 @@ static int verify_with_workspace(const mpv_problem* problem, const mpv_buffers* 
     a.k32 = static_cast<float>(1.4426950408889634 / static_cast<double>(problem->temperature));
     a.lazy = (walk || (buf->edge_probs == nullptr && buf->accept_prob == nullptr && buf->stats == nullptr)) ? 1 : 0;
     a.estimate = 0; a.reach_prob = nullptr; a.expected = nullptr;
+    a.keep_counters = keep_counters ? 1 : 0;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     if (problem->logit_dtype == MPV_DTYPE_F32) return mpv::launch_all<mpv::ElemF32>(problem, plan, ws, a, s);
     return mpv::launch_all<mpv::ElemBF16>(problem, plan, ws, a, s);
+}
+
+int mpv_merge_duplicates(const int32_t* parent, const int32_t* tokens, int32_t B, int32_t N,
+                         int32_t* merged_parent, int32_t* context_node) {
+    if (!parent || !merged_parent || (B > 0 && !tokens)) return MPV_ERR_NULL;
+    if (B < 0 || N < 1) return MPV_ERR_BAD_SHAPE;
+    if (N > MPV_MAX_NODES) return MPV_ERR_UNSUPPORTED;
+    if (parent[0] != -1) return MPV_ERR_BAD_TREE;
+    for (int n = 1; n < N; ++n)
+        if (parent[n] < 0 || parent[n] >= n) return MPV_ERR_BAD_TREE;
+    for (int32_t b = 0; b < B; ++b) {
+        const int32_t* tok = tokens + static_cast<size_t>(b) * N;
+        int32_t* out = merged_parent + static_cast<size_t>(b) * N;
+        // stands_for[n]: the node of slot n's context; entries[c]: the slots already placed under the
+        // context node c that are nodes themselves (one per distinct token), in slot order
+        int32_t stands_for[MPV_MAX_NODES];
+        int8_t entries[MPV_MAX_NODES][MPV_MAX_NODES];
+        int8_t count[MPV_MAX_NODES];
+        memset(count, 0, sizeof(count));
+        stands_for[0] = 0;
+        out[0] = -1;
+        for (int n = 1; n < N; ++n) {
+            const int under = stands_for[parent[n]];
+            out[n] = under;
+            stands_for[n] = n;
+            for (int j = 0; j < count[under]; ++j) {
+                const int m = entries[under][j];
+                if (tok[m] == tok[n]) { stands_for[n] = m; break; }
+            }
+            if (stands_for[n] == n) entries[under][count[under]++] = static_cast<int8_t>(n);
+        }
+        if (context_node) memcpy(context_node + static_cast<size_t>(b) * N, stands_for, sizeof(int32_t) * N);
+    }
+    return MPV_OK;
+}
+
+int mpv_verify_merged(const mpv_problem* problem, const int32_t* merged_parent, const mpv_buffers* buf,
+                      void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (!problem || !buf) return MPV_ERR_NULL;
+    if (problem->B < 0 || problem->N < 1 || problem->V < 1) return MPV_ERR_BAD_SHAPE;
+    if (problem->method == MPV_METHOD_SPECTR) return MPV_ERR_UNSUPPORTED;
+    if (problem->B == 0) return MPV_OK;
+    if (!merged_parent) return MPV_ERR_NULL;
+    const int32_t B = problem->B, N = problem->N;
+    // first pass: every run of equal shapes is a valid problem, and the workspace holds the largest
+    // (its size depends on the number of trees and of nodes only, and grows with both)
+    mpv_problem run = *problem;
+    for (int32_t b0 = 0; b0 < B;) {
+        int32_t b1 = b0 + 1;
+        while (b1 < B && memcmp(merged_parent + static_cast<size_t>(b0) * N, merged_parent + static_cast<size_t>(b1) * N,
+                                sizeof(int32_t) * N) == 0)
+            ++b1;
+        run.B = b1 - b0;
+        run.parent = merged_parent + static_cast<size_t>(b0) * N;
+        mpv::Plan plan;
+        const int rc = mpv::validate(&run, &plan);
+        if (rc != MPV_OK) return rc;
+        b0 = b1;
+    }
+    run.B = B;
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) || workspace_bytes < mpv::carve(&run, nullptr, nullptr))
+        return MPV_ERR_WORKSPACE;
+    if ((reinterpret_cast<uintptr_t>(buf->target_logits) & 15u) || (reinterpret_cast<uintptr_t>(buf->draft_logits) & 15u))
+        return MPV_ERR_ALIGNMENT;
+    const size_t elem = problem->logit_dtype == MPV_DTYPE_F32 ? 4 : 2;
+    const size_t V = static_cast<size_t>(problem->V), D = static_cast<size_t>(problem->max_depth);
+    auto moved = [](const void* p, size_t bytes) -> const void* { return p ? static_cast<const char*>(p) + bytes : nullptr; };
+    auto moved_out = [](void* p, size_t bytes) -> void* { return p ? static_cast<char*>(p) + bytes : nullptr; };
+    bool first = true;
+    for (int32_t b0 = 0; b0 < B;) {
+        int32_t b1 = b0 + 1;
+        while (b1 < B && memcmp(merged_parent + static_cast<size_t>(b0) * N, merged_parent + static_cast<size_t>(b1) * N,
+                                sizeof(int32_t) * N) == 0)
+            ++b1;
+        run.B = b1 - b0;
+        run.parent = merged_parent + static_cast<size_t>(b0) * N;
+        const size_t t = static_cast<size_t>(b0), tn = t * N;
+        mpv_buffers part = *buf;
+        part.target_logits = moved(buf->target_logits, tn * V * elem);
+        part.draft_logits = moved(buf->draft_logits, tn * V * elem);
+        part.tokens = static_cast<const int32_t*>(moved(buf->tokens, tn * 4));
+        part.uniforms = static_cast<const float*>(moved(buf->uniforms, tn * 4));
+        part.draw_uniforms = static_cast<const float*>(moved(buf->draw_uniforms, tn * 4));
+        part.accept_len = static_cast<int32_t*>(moved_out(buf->accept_len, t * 4));
+        part.path_nodes = static_cast<int32_t*>(moved_out(buf->path_nodes, t * D * 4));
+        part.path_tokens = static_cast<int32_t*>(moved_out(buf->path_tokens, t * D * 4));
+        part.bonus_token = static_cast<int32_t*>(moved_out(buf->bonus_token, t * 4));
+        part.stats = static_cast<float*>(moved_out(buf->stats, tn * 4 * 4));
+        part.edge_probs = static_cast<float*>(moved_out(buf->edge_probs, tn * 2 * 4));
+        part.accept_prob = static_cast<float*>(moved_out(buf->accept_prob, tn * 4));
+        part.final_residual = static_cast<float*>(moved_out(buf->final_residual, t * V * 4));
+        const int rc = verify_with_workspace(&run, &part, workspace, workspace_bytes, hip_stream, true, !first);
+        if (rc != MPV_OK) return rc;
+        first = false;
+        b0 = b1;
+    }
+    return MPV_OK;
 }
 
 int mpv_block_efficiency(const mpv_problem* problem, const void* target_logits, const void* draft_logits,

@@ -28,7 +28,7 @@ def test_library_exports_every_declared_symbol(lib):
     text = re.sub(r"/\*.*?\*/", "", header_text(), flags=re.S)
     names = set(re.findall(r"\b(mpv_[a-z_]+)\s*\(", text))
     assert {"mpv_version", "mpv_strerror", "mpv_last_hip_error", "mpv_workspace_bytes",
-            "mpv_verify", "mpv_verify_static", "mpv_block_efficiency", "mpv_acceptance_rates", "mpv_nucleus_mask", "mpv_row_stats", "mpv_fill_uniforms", "mpv_timing_enable",
+            "mpv_verify", "mpv_verify_static", "mpv_merge_duplicates", "mpv_verify_merged", "mpv_block_efficiency", "mpv_acceptance_rates", "mpv_nucleus_mask", "mpv_row_stats", "mpv_fill_uniforms", "mpv_timing_enable",
             "mpv_timing_read"} <= names
     for name in names:
         assert getattr(lib, name) is not None, name
@@ -240,3 +240,83 @@ def test_static_scratch_entry_point_refuses_what_does_not_fit(lib):
     bufs = binding._Buffers(*([ctypes.c_void_p(256)] * 9), *([ctypes.c_void_p(0)] * 5))
     assert lib.mpv_verify_static(ctypes.byref(prob), ctypes.byref(bufs), ctypes.c_void_p(0)) == code("MPV_ERR_WORKSPACE")
     assert lib.mpv_verify_static(ctypes.byref(problem(T=0.0)), ctypes.byref(bufs), ctypes.c_void_p(0)) == code("MPV_ERR_BAD_TEMPERATURE")
+
+
+# ---------------------------------------------------------------- trees of distinct contexts (host logic)
+
+def test_merge_duplicates_agrees_with_the_oracle():
+    """mpv_merge_duplicates is host code: it is compared here, bit for bit, with the oracle's
+    construction of Def. 3.1 on layouts and tokens where shared prefixes are frequent."""
+    from oracle import merged_tree_oracle as merged
+    rng = np.random.default_rng(31)
+    layouts = [mpv.root_tree(2, 3), mpv.root_tree(8, 5), mpv.delayed_tree(4, 2, 3), mpv.delayed_tree(8, 3, 3),
+               [-1, 0, 0, 1, 1, 2, 5, 5, 0, 8, 9], [-1] + list(range(63))]
+    for _ in range(6):
+        n = int(rng.integers(2, 40))
+        layouts.append([-1] + [int(rng.integers(0, k)) for k in range(1, n)])
+    some_merge = 0
+    for parent in layouts:
+        for V in (1, 2, 3, 50):
+            tokens = rng.integers(0, V, size=(9, len(parent))).astype(np.int32)
+            got_p, got_c = mpv.mpv_merge_duplicates(parent, tokens)
+            want_p, want_c = merged.merge_batch(parent, tokens)
+            assert got_p.dtype == np.int32 and np.array_equal(got_p, want_p) and np.array_equal(got_c, want_c)
+            some_merge += int(np.any(got_c != np.arange(len(parent))))
+    assert some_merge > 20
+
+
+def test_merge_duplicates_validates(lib):
+    par = np.array([-1, 0, 1], dtype=np.int32)
+    tok = np.zeros((2, 3), dtype=np.int32)
+    out = np.zeros((2, 3), dtype=np.int32)
+    f = lib.mpv_merge_duplicates
+    assert f(par.ctypes.data, tok.ctypes.data, 2, 3, out.ctypes.data, None) == 0
+    assert out.tolist() == [[-1, 0, 1], [-1, 0, 1]]
+    assert f(None, tok.ctypes.data, 2, 3, out.ctypes.data, None) == code("MPV_ERR_NULL")
+    assert f(par.ctypes.data, None, 2, 3, out.ctypes.data, None) == code("MPV_ERR_NULL")
+    assert f(par.ctypes.data, tok.ctypes.data, 2, 3, None, None) == code("MPV_ERR_NULL")
+    assert f(par.ctypes.data, None, 0, 3, out.ctypes.data, None) == 0
+    assert f(par.ctypes.data, tok.ctypes.data, -1, 3, out.ctypes.data, None) == code("MPV_ERR_BAD_SHAPE")
+    assert f(par.ctypes.data, tok.ctypes.data, 2, 0, out.ctypes.data, None) == code("MPV_ERR_BAD_SHAPE")
+    assert f(par.ctypes.data, tok.ctypes.data, 2, header_constant("MPV_MAX_NODES") + 1, out.ctypes.data, None) \
+        == code("MPV_ERR_UNSUPPORTED")
+    bad = np.array([-1, 1, 0], dtype=np.int32)
+    assert f(bad.ctypes.data, tok.ctypes.data, 2, 3, out.ctypes.data, None) == code("MPV_ERR_BAD_TREE")
+    with pytest.raises(ValueError):
+        mpv.mpv_merge_duplicates([-1, 0], tok)
+
+
+def test_verify_merged_rejects_bad_arguments_before_any_launch(lib):
+    f = lib.mpv_verify_merged
+    bufs = binding._Buffers()
+    for name, _ in binding._Buffers._fields_[:9]:
+        setattr(bufs, name, 4096)
+    fake = ctypes.c_void_p(4096)
+    prob = problem(parent=None)                       # problem->parent is not read
+    rows = np.array([[-1, 0, 1], [-1, 0, 0]], dtype=np.int32)
+    ok = rows.ctypes.data
+    assert f(None, ok, ctypes.byref(bufs), fake, 1 << 20, None) == code("MPV_ERR_NULL")
+    assert f(ctypes.byref(prob), ok, None, fake, 1 << 20, None) == code("MPV_ERR_NULL")
+    assert f(ctypes.byref(prob), None, ctypes.byref(bufs), fake, 1 << 20, None) == code("MPV_ERR_NULL")
+    assert f(ctypes.byref(problem(parent=None, method=4)), ok, ctypes.byref(bufs), fake, 1 << 20, None) \
+        == code("MPV_ERR_UNSUPPORTED")
+    assert f(ctypes.byref(problem(parent=None, T=0.0)), ok, ctypes.byref(bufs), fake, 1 << 20, None) \
+        == code("MPV_ERR_BAD_TEMPERATURE")
+    # the second tree's array is invalid / deeper than max_depth / has too many children
+    bad = np.array([[-1, 0, 1], [-1, 1, 0]], dtype=np.int32)
+    assert f(ctypes.byref(prob), bad.ctypes.data, ctypes.byref(bufs), fake, 1 << 20, None) == code("MPV_ERR_BAD_TREE")
+    assert f(ctypes.byref(problem(parent=None, max_depth=1)), ok, ctypes.byref(bufs), fake, 1 << 20, None) \
+        == code("MPV_ERR_BAD_SHAPE")
+    n = header_constant("MPV_MAX_CHILDREN") + 2
+    star = np.array([[-1] + [0] * (n - 1)], dtype=np.int32)
+    assert f(ctypes.byref(problem(B=1, N=n, parent=None)), star.ctypes.data, ctypes.byref(bufs), fake, 1 << 20, None) \
+        == code("MPV_ERR_UNSUPPORTED")
+    # workspace, alignment, null members: as for mpv_verify
+    assert f(ctypes.byref(prob), ok, ctypes.byref(bufs), None, 1 << 20, None) == code("MPV_ERR_WORKSPACE")
+    assert f(ctypes.byref(prob), ok, ctypes.byref(bufs), fake, 16, None) == code("MPV_ERR_WORKSPACE")
+    bufs.draft_logits = 4096 + 2
+    assert f(ctypes.byref(prob), ok, ctypes.byref(bufs), fake, 1 << 20, None) == code("MPV_ERR_ALIGNMENT")
+    bufs.draft_logits = 4096
+    bufs.bonus_token = None
+    assert f(ctypes.byref(prob), ok, ctypes.byref(bufs), fake, 1 << 20, None) == code("MPV_ERR_NULL")
+    assert f(ctypes.byref(problem(B=0, parent=None)), None, ctypes.byref(binding._Buffers()), None, 0, None) == 0

@@ -149,6 +149,60 @@ def make_inputs(cfg, device="cuda", trees_per_chunk=8):
             "uniforms": uniforms, "draw_uniforms": draw_uniforms}
 
 
+def make_context_inputs(cfg, device="cuda"):
+    """make_inputs for models that are functions of the context (Sec. 3, Def. 3.1): slots of one
+    tree that were drafted for the same context (same tokens from the root down) hold the same
+    target row and the same draft row, and draft tokens are drawn from the row of the context.
+    Logit rows and uniforms are those of make_inputs(cfg); walking the slots in ascending order,
+    the token of slot n is drawn from the (already final) draft row of its parent slot, and if an
+    earlier slot of the tree has the same context, that slot's two rows are copied into slot n.
+    Adds "context_node" (numpy int32 [B,N]): the first slot drafted for slot n's context.
+    """
+    import numpy as np
+    inputs = make_inputs(cfg, device)
+    B, N = cfg.B, cfg.N
+    dev = torch.device(device)
+    target, draft = inputs["target"], inputs["draft"]
+    gen_tok = torch.Generator(device=dev)
+    gen_tok.manual_seed(cfg.seed + 1)
+    tokens = torch.zeros(B, N, dtype=torch.int32, device=dev)
+    first_slot = [dict() for _ in range(B)]           # per tree: (context's slot, token) -> first slot drafted for it
+    context_node = np.zeros((B, N), dtype=np.int32)
+    for n in range(1, N):
+        par = cfg.parent[n]
+        for b0 in range(0, B, 64):
+            b1 = min(B, b0 + 64)
+            q = torch.softmax(draft[b0:b1, par].float() / cfg.T, dim=-1)
+            tokens[b0:b1, n] = torch.multinomial(q, 1, generator=gen_tok).squeeze(1).to(torch.int32)
+        drawn = tokens[:, n].cpu().tolist()
+        again_b, again_m = [], []
+        for b in range(B):
+            m = first_slot[b].setdefault((int(context_node[b, par]), drawn[b]), n)
+            context_node[b, n] = m
+            if m != n:
+                again_b.append(b)
+                again_m.append(m)
+        if again_b:
+            ib = torch.tensor(again_b, device=dev)
+            im = torch.tensor(again_m, device=dev)
+            draft[ib, n] = draft[ib, im]
+            target[ib, n] = target[ib, im]
+    inputs["tokens"] = tokens
+    inputs["context_node"] = context_node
+    return inputs
+
+
+def reorder_trees(inputs, order):
+    """The same batch with its trees in another order (order: a permutation of range(B))."""
+    idx = torch.as_tensor(list(order), device=inputs["tokens"].device, dtype=torch.long)
+    out = dict(inputs)
+    for k in ("tokens", "target", "draft", "uniforms", "draw_uniforms"):
+        out[k] = inputs[k].index_select(0, idx).contiguous()
+    if "context_node" in inputs:
+        out["context_node"] = inputs["context_node"][list(order)]
+    return out
+
+
 def to_host(inputs):
     """numpy copies for the oracle (bfloat16 widened to float32, which is exact)."""
     host = {
