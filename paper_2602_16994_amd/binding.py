@@ -98,6 +98,10 @@ def load_library(path=None):
     lib.mpv_block_efficiency.argtypes = [ctypes.POINTER(_Problem), ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                          ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p,
                                          ctypes.c_void_p, ctypes.c_void_p]
+    lib.mpv_block_efficiency_merged.restype = ctypes.c_int
+    lib.mpv_block_efficiency_merged.argtypes = [ctypes.POINTER(_Problem), ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                                ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p,
+                                                ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
     lib.mpv_acceptance_rates.restype = ctypes.c_int
     lib.mpv_acceptance_rates.argtypes = [ctypes.POINTER(_Problem), ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                          ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
@@ -317,10 +321,11 @@ class BlockEfficiencyResult:
 
 
 def mpv_block_efficiency(parent, tokens, target_logits, draft_logits, temperature, method,
-                         out=None, stream=None):
+                         out=None, stream=None, merged_parent=None):
     """Expected block efficiency of every tree of the batch (see include/mpv.h): enqueued on the
     current (or given) torch stream; returns a BlockEfficiencyResult of CUDA tensors.  Arguments as
-    for mpv_verify, without uniforms.  `out` may be a previous result whose buffers are reused."""
+    for mpv_verify, without uniforms.  `out` may be a previous result whose buffers are reused.
+    merged_parent (numpy int32 [B,N] on the host) calls mpv_block_efficiency_merged."""
     import torch
     from .trees import tree_depth
     B, N, V = target_logits.shape
@@ -350,6 +355,17 @@ def mpv_block_efficiency(parent, tokens, target_logits, draft_logits, temperatur
     def ptr(t):
         return ctypes.c_void_p(t.data_ptr()) if t is not None else ctypes.c_void_p(0)
 
+    if merged_parent is not None:
+        import numpy as np
+        rows = np.ascontiguousarray(np.asarray(merged_parent), dtype=np.int32)
+        if rows.shape != (B, N):
+            raise ValueError("merged_parent must be [B,N]")
+        rc = lib.mpv_block_efficiency_merged(ctypes.byref(prob), rows.ctypes.data, ptr(target_logits), ptr(draft_logits),
+                                             ptr(tokens), ptr(out.workspace), ctypes.c_size_t(out.workspace.numel()),
+                                             ptr(out.reach_prob), ptr(out.expected), ptr(out.counters), _stream_ptr(stream))
+        if rc != 0:
+            raise MpvError(rc, "mpv_block_efficiency_merged")
+        return out
     rc = lib.mpv_block_efficiency(ctypes.byref(prob), ptr(target_logits), ptr(draft_logits), ptr(tokens),
                                   ptr(out.workspace), ctypes.c_size_t(out.workspace.numel()),
                                   ptr(out.reach_prob), ptr(out.expected), ptr(out.counters), _stream_ptr(stream))

@@ -2547,6 +2547,18 @@ static size_t carve(const mpv_problem* p, void* base, Workspace* ws) {
     return off < 256 ? 256 : off;
 }
 
+// Calls fn(b0, b1) for every run [b0, b1) of consecutive equal rows of rows[B][N], in order, until fn returns false.
+template <typename F>
+static void for_each_run(const int32_t* rows, int32_t B, int32_t N, F fn) {
+    for (int32_t b0 = 0; b0 < B;) {
+        int32_t b1 = b0 + 1;
+        while (b1 < B && memcmp(rows + static_cast<size_t>(b0) * N, rows + static_cast<size_t>(b1) * N, sizeof(int32_t) * N) == 0)
+            ++b1;
+        if (!fn(b0, b1)) return;
+        b0 = b1;
+    }
+}
+
 static int compute_units() {
     static int cus = 0;
     if (cus == 0) {
@@ -2851,18 +2863,15 @@ int mpv_verify_merged(const mpv_problem* problem, const int32_t* merged_parent, 
     // first pass: every run of equal shapes is a valid problem, and the workspace holds the largest
     // (its size depends on the number of trees and of nodes only, and grows with both)
     mpv_problem run = *problem;
-    for (int32_t b0 = 0; b0 < B;) {
-        int32_t b1 = b0 + 1;
-        while (b1 < B && memcmp(merged_parent + static_cast<size_t>(b0) * N, merged_parent + static_cast<size_t>(b1) * N,
-                                sizeof(int32_t) * N) == 0)
-            ++b1;
+    int rc = MPV_OK;
+    mpv::for_each_run(merged_parent, B, N, [&](int32_t b0, int32_t b1) {
         run.B = b1 - b0;
         run.parent = merged_parent + static_cast<size_t>(b0) * N;
         mpv::Plan plan;
-        const int rc = mpv::validate(&run, &plan);
-        if (rc != MPV_OK) return rc;
-        b0 = b1;
-    }
+        rc = mpv::validate(&run, &plan);
+        return rc == MPV_OK;
+    });
+    if (rc != MPV_OK) return rc;
     run.B = B;
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) || workspace_bytes < mpv::carve(&run, nullptr, nullptr))
         return MPV_ERR_WORKSPACE;
@@ -2873,11 +2882,7 @@ int mpv_verify_merged(const mpv_problem* problem, const int32_t* merged_parent, 
     auto moved = [](const void* p, size_t bytes) -> const void* { return p ? static_cast<const char*>(p) + bytes : nullptr; };
     auto moved_out = [](void* p, size_t bytes) -> void* { return p ? static_cast<char*>(p) + bytes : nullptr; };
     bool first = true;
-    for (int32_t b0 = 0; b0 < B;) {
-        int32_t b1 = b0 + 1;
-        while (b1 < B && memcmp(merged_parent + static_cast<size_t>(b0) * N, merged_parent + static_cast<size_t>(b1) * N,
-                                sizeof(int32_t) * N) == 0)
-            ++b1;
+    mpv::for_each_run(merged_parent, B, N, [&](int32_t b0, int32_t b1) {
         run.B = b1 - b0;
         run.parent = merged_parent + static_cast<size_t>(b0) * N;
         const size_t t = static_cast<size_t>(b0), tn = t * N;
@@ -2895,23 +2900,26 @@ int mpv_verify_merged(const mpv_problem* problem, const int32_t* merged_parent, 
         part.edge_probs = static_cast<float*>(moved_out(buf->edge_probs, tn * 2 * 4));
         part.accept_prob = static_cast<float*>(moved_out(buf->accept_prob, tn * 4));
         part.final_residual = static_cast<float*>(moved_out(buf->final_residual, t * V * 4));
-        const int rc = verify_with_workspace(&run, &part, workspace, workspace_bytes, hip_stream, true, !first);
-        if (rc != MPV_OK) return rc;
+        rc = verify_with_workspace(&run, &part, workspace, workspace_bytes, hip_stream, true, !first);
         first = false;
-        b0 = b1;
-    }
-    return MPV_OK;
+        return rc == MPV_OK;
+    });
+    return rc;
 }
 
-int mpv_block_efficiency(const mpv_problem* problem, const void* target_logits, const void* draft_logits,
-                         const int32_t* tokens, void* workspace, size_t workspace_bytes,
-                         float* reach_prob, float* expected, uint32_t* counters, void* hip_stream) {
+// part_of_batch, keep_counters: as for verify_with_workspace
+static int block_efficiency_with_workspace(const mpv_problem* problem, const void* target_logits, const void* draft_logits,
+                                           const int32_t* tokens, void* workspace, size_t workspace_bytes,
+                                           float* reach_prob, float* expected, uint32_t* counters, void* hip_stream,
+                                           bool part_of_batch, bool keep_counters) {
     mpv::Plan plan;
     const int rc = mpv::validate(problem, &plan);
     if (rc != MPV_OK) return rc;
     if (problem->B == 0) return MPV_OK;
     if (!target_logits || !draft_logits || !tokens || !expected || !counters) return MPV_ERR_NULL;
-    if ((reinterpret_cast<uintptr_t>(target_logits) & 15u) || (reinterpret_cast<uintptr_t>(draft_logits) & 15u))
+    if (!part_of_batch && ((reinterpret_cast<uintptr_t>(target_logits) & 15u) || (reinterpret_cast<uintptr_t>(draft_logits) & 15u)))
+        return MPV_ERR_ALIGNMENT;
+    if (((reinterpret_cast<uintptr_t>(target_logits) ^ reinterpret_cast<uintptr_t>(draft_logits)) & 15u) != 0)
         return MPV_ERR_ALIGNMENT;
     const size_t need = mpv::carve(problem, nullptr, nullptr);
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) || workspace_bytes < need) return MPV_ERR_WORKSPACE;
@@ -2927,9 +2935,58 @@ int mpv_block_efficiency(const mpv_problem* problem, const void* target_logits, 
     a.k32 = static_cast<float>(1.4426950408889634 / static_cast<double>(problem->temperature));
     a.lazy = 0;
     a.estimate = 1; a.reach_prob = reach_prob; a.expected = expected;
+    a.keep_counters = keep_counters ? 1 : 0;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     if (problem->logit_dtype == MPV_DTYPE_F32) return mpv::launch_all<mpv::ElemF32>(problem, plan, ws, a, s);
     return mpv::launch_all<mpv::ElemBF16>(problem, plan, ws, a, s);
+}
+
+int mpv_block_efficiency(const mpv_problem* problem, const void* target_logits, const void* draft_logits,
+                         const int32_t* tokens, void* workspace, size_t workspace_bytes,
+                         float* reach_prob, float* expected, uint32_t* counters, void* hip_stream) {
+    return block_efficiency_with_workspace(problem, target_logits, draft_logits, tokens, workspace, workspace_bytes,
+                                           reach_prob, expected, counters, hip_stream, false, false);
+}
+
+int mpv_block_efficiency_merged(const mpv_problem* problem, const int32_t* merged_parent, const void* target_logits,
+                                const void* draft_logits, const int32_t* tokens, void* workspace, size_t workspace_bytes,
+                                float* reach_prob, float* expected, uint32_t* counters, void* hip_stream) {
+    if (!problem) return MPV_ERR_NULL;
+    if (problem->B < 0 || problem->N < 1 || problem->V < 1) return MPV_ERR_BAD_SHAPE;
+    if (problem->method == MPV_METHOD_SPECTR) return MPV_ERR_UNSUPPORTED;
+    if (problem->B == 0) return MPV_OK;
+    if (!merged_parent) return MPV_ERR_NULL;
+    mpv_problem run = *problem;
+    int rc = MPV_OK;
+    mpv::for_each_run(merged_parent, problem->B, problem->N, [&](int32_t b0, int32_t b1) {
+        run.B = b1 - b0;
+        run.parent = merged_parent + static_cast<size_t>(b0) * problem->N;
+        mpv::Plan plan;
+        rc = mpv::validate(&run, &plan);
+        return rc == MPV_OK;
+    });
+    if (rc != MPV_OK) return rc;
+    run.B = problem->B;
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) || workspace_bytes < mpv::carve(&run, nullptr, nullptr))
+        return MPV_ERR_WORKSPACE;
+    if (!target_logits || !draft_logits || !tokens || !expected || !counters) return MPV_ERR_NULL;
+    if ((reinterpret_cast<uintptr_t>(target_logits) & 15u) || (reinterpret_cast<uintptr_t>(draft_logits) & 15u))
+        return MPV_ERR_ALIGNMENT;
+    const size_t elem = problem->logit_dtype == MPV_DTYPE_F32 ? 4 : 2;
+    const size_t N = static_cast<size_t>(problem->N), V = static_cast<size_t>(problem->V);
+    bool first = true;
+    mpv::for_each_run(merged_parent, problem->B, problem->N, [&](int32_t b0, int32_t b1) {
+        run.B = b1 - b0;
+        run.parent = merged_parent + static_cast<size_t>(b0) * N;
+        const size_t t = static_cast<size_t>(b0), tn = t * N;
+        rc = block_efficiency_with_workspace(&run, static_cast<const char*>(target_logits) + tn * V * elem,
+                                             static_cast<const char*>(draft_logits) + tn * V * elem, tokens + tn,
+                                             workspace, workspace_bytes, reach_prob ? reach_prob + tn : nullptr,
+                                             expected + t, counters, hip_stream, true, !first);
+        first = false;
+        return rc == MPV_OK;
+    });
+    return rc;
 }
 
 

@@ -189,3 +189,38 @@ def test_spectr_is_refused():
     with pytest.raises(mpv.MpvError) as e:
         run_merged(inputs, cfg, SPECTR, mp, debug=False)
     assert e.value.code == -8
+
+
+@pytest.mark.parametrize("method", [SI, TV, NSS, NAIVE])
+def test_block_efficiency_of_merged_trees(method):
+    """mpv_block_efficiency_merged against the block-efficiency oracle on each tree's merged array,
+    and against the unmerged estimate: under SpecInfer merging can only raise it (the child list of
+    a context is the unmerged one followed by further entries)."""
+    from tests.test_gpu_block_efficiency import compare
+    cfg = workloads.Config("be_merged", B=48, V=11, K=3, L1=1, L2=3, dtype="bf16", T=0.9, methods=[method],
+                           draft_sigma=1.2, target_sigma=0.7, seed=8311)
+    inputs = workloads.make_context_inputs(cfg, "cuda")
+    mp, cn = merged_arrays(cfg, inputs)
+    announce("block efficiency merged", NAMES[method], f"B={cfg.B} N={cfg.N} V={cfg.V} runs={len(runs_of(mp))}")
+    res = mpv.mpv_block_efficiency(cfg.parent, inputs["tokens"], inputs["target"], inputs["draft"], cfg.T, method,
+                                   merged_parent=mp)
+    torch.cuda.synchronize()
+    expected, reach, counters = res.expected.cpu().numpy(), res.reach_prob.cpu().numpy(), res.counters.cpu().numpy()
+    assert counters[4] == 0
+    host = workloads.to_host(inputs)
+    internal = 0
+    for b in range(cfg.B):
+        one = dict(host)
+        one["parent"] = [int(x) for x in mp[b]]
+        compare(method, one, cfg.T, expected, reach, trees=[b])
+        internal += len(set(one["parent"][1:]))
+        if method in (SI, TV):
+            assert np.all(reach[b][cn[b] != np.arange(cfg.N)] == 0.0)        # a repeat is never accepted
+    assert counters[5] == internal                                     # every internal node's task ran, summed over the runs
+    plain = mpv.mpv_block_efficiency(cfg.parent, inputs["tokens"], inputs["target"], inputs["draft"], cfg.T, method)
+    torch.cuda.synchronize()
+    if method == SI:
+        assert np.all(expected >= plain.expected.cpu().numpy() - 1e-5)
+        assert float(expected.mean()) > float(plain.expected.mean())
+    with pytest.raises(mpv.MpvError):
+        mpv.mpv_block_efficiency(cfg.parent, inputs["tokens"], inputs["target"], inputs["draft"], cfg.T, SPECTR, merged_parent=mp)
