@@ -223,14 +223,17 @@ int mpv_merge_duplicates(const int32_t* parent, const int32_t* tokens, int32_t B
  * tested only after the first entry for its token was rejected, which leaves that token no residual
  * mass: it is tested with probability 0 and only its residual step remains (App. B, Alg. 4); NSS and
  * Naive move to the first child that carries the drawn token, which is the context node.  SpecTr
- * (App. B, Alg. 3) can accept a repeat on the repeat's own uniform and would have to go on below the
- * context node: MPV_METHOD_SPECTR returns MPV_ERR_UNSUPPORTED.
+ * (App. B, Alg. 3) tests every entry with the entry's own uniform and can accept a repeat; the walk
+ * then goes on at the context node.  For that, MPV_METHOD_SPECTR needs context_node: DEVICE int32
+ * [B,N], what mpv_merge_duplicates wrote (copied to the device by the caller), borrowed like the
+ * buffers; an entry outside [0,N) is ignored (the walk stays at the accepted entry); with the other
+ * methods the argument is not read and may be NULL.
  * Cost: the kernels share one shape per launch, so the call makes one mpv_verify launch per run of
  * consecutive trees with equal rows in merged_parent, one after the other on `hip_stream`; lay trees
  * of equal shape next to each other (the shapes are known before the target pass writes its rows).
  * Nothing is launched unless every run is a valid problem. */
-int mpv_verify_merged(const mpv_problem* problem, const int32_t* merged_parent, const mpv_buffers* buffers,
-                      void* workspace, size_t workspace_bytes, void* hip_stream);
+int mpv_verify_merged(const mpv_problem* problem, const int32_t* merged_parent, const int32_t* context_node,
+                      const mpv_buffers* buffers, void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* Expected block efficiency of every tree of the batch with the verification's own
  * randomness integrated out (Sec. 5, Eq. 1-3; branching probabilities of Def. 5.3 by
@@ -255,8 +258,8 @@ int mpv_block_efficiency(const mpv_problem* problem, const void* target_logits, 
 
 /* mpv_block_efficiency for trees of distinct contexts: merged_parent is a HOST int32 [B,N] array, one
  * parent array per tree, as for mpv_verify_merged (problem->parent is not read; one launch per run of
- * consecutive equal rows; the counters are summed; MPV_METHOD_SPECTR returns MPV_ERR_UNSUPPORTED for
- * the reason given there).  A later entry for an already drafted token is a leaf of its tree's array
+ * consecutive equal rows; the counters are summed; MPV_METHOD_SPECTR returns MPV_ERR_UNSUPPORTED: its
+ * estimate would have to credit an accepted repeat to the context node).  A later entry for an already drafted token is a leaf of its tree's array
  * and gets the reach probability of that entry being accepted, which SpecInfer and Traversal make 0;
  * reach_prob of a context node covers every drafted path through it.  Everything else as for
  * mpv_block_efficiency. */

@@ -92,7 +92,7 @@ def load_library(path=None):
     lib.mpv_merge_duplicates.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32,
                                          ctypes.c_void_p, ctypes.c_void_p]
     lib.mpv_verify_merged.restype = ctypes.c_int
-    lib.mpv_verify_merged.argtypes = [ctypes.POINTER(_Problem), ctypes.c_void_p, ctypes.POINTER(_Buffers),
+    lib.mpv_verify_merged.argtypes = [ctypes.POINTER(_Problem), ctypes.c_void_p, ctypes.c_void_p, ctypes.POINTER(_Buffers),
                                       ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
     lib.mpv_block_efficiency.restype = ctypes.c_int
     lib.mpv_block_efficiency.argtypes = [ctypes.POINTER(_Problem), ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
@@ -217,7 +217,7 @@ def mpv_merge_duplicates(parent, tokens):
 
 def mpv_verify(parent, tokens, target_logits, draft_logits, temperature, uniforms, method,
                max_depth=None, debug=False, out=None, workspace=None, stream=None, draw_uniforms=None,
-               static_scratch=False, merged_parent=None):
+               static_scratch=False, merged_parent=None, context_node=None):
     """Enqueue one batched verification on the current (or given) torch stream.
 
     parent: list of N ints (host).  tokens int32 [B,N], target_logits / draft_logits
@@ -228,7 +228,8 @@ def mpv_verify(parent, tokens, target_logits, draft_logits, temperature, uniform
     each visited node); with those methods debug=True provides accept_prob and final_residual only.
     static_scratch=True calls mpv_verify_static: no workspace tensor, the library's own device array.
     merged_parent (numpy int32 [B,N] on the host, one parent array per tree) calls mpv_verify_merged;
-    `parent` then only serves to size the outputs and the workspace.
+    `parent` then only serves to size the outputs and the workspace.  MPV_METHOD_SPECTR also needs
+    context_node: an int32 CUDA tensor [B,N] (what mpv_merge_duplicates returned, copied to the device).
     """
     import torch
     from .trees import tree_depth
@@ -293,8 +294,11 @@ def mpv_verify(parent, tokens, target_logits, draft_logits, temperature, uniform
         rows = np.ascontiguousarray(np.asarray(merged_parent), dtype=np.int32)
         if static_scratch or rows.shape != (B, N):
             raise ValueError("merged_parent must be [B,N] and cannot be combined with static_scratch")
-        rc = lib.mpv_verify_merged(ctypes.byref(prob), rows.ctypes.data, ctypes.byref(bufs), ptr(workspace),
-                                   ctypes.c_size_t(workspace.numel()), _stream_ptr(stream))
+        if context_node is not None and (not context_node.is_cuda or not context_node.is_contiguous()
+                                         or context_node.dtype != torch.int32 or tuple(context_node.shape) != (B, N)):
+            raise ValueError("context_node must be a contiguous int32 CUDA tensor [B,N]")
+        rc = lib.mpv_verify_merged(ctypes.byref(prob), rows.ctypes.data, ptr(context_node), ctypes.byref(bufs),
+                                   ptr(workspace), ctypes.c_size_t(workspace.numel()), _stream_ptr(stream))
         if rc != 0:
             raise MpvError(rc, "mpv_verify_merged")
         return out

@@ -164,6 +164,9 @@ struct Args {
     float* reach_prob = nullptr;
     float* expected = nullptr;
     float* alpha = nullptr;
+    // Trees of distinct contexts, SpecTr: [B,N], the node an accepted child entry stands for (itself unless the
+    // entry repeats a token drafted earlier under the same node); null: every entry stands for itself.
+    const int32_t* context_node = nullptr;
 };
 
 // Everything node_task_kernel needs to know, in one block of the workspace: the kernel and the
@@ -1427,6 +1430,12 @@ __device__ __attribute__((noinline)) void run_node_task(int task_in, int flags_i
         // residual are not needed (the same in every lane: no lane is left behind)
         if (METHOD == MPV_METHOD_SPECINFER && a.lazy && child_accepted) {
             next_node = cn;
+            if (a.context_node) {
+                // the walk goes on at the node of the accepted entry's context (anything else than a node
+                // number is ignored)
+                const int stands_for = uniform_i32(as_global(a.context_node)[static_cast<size_t>(b) * N + cn]);
+                if (stands_for >= 0 && stands_for < N) next_node = stands_for;
+            }
             break;
         }
         // NSS: nothing else to find out here
@@ -2758,9 +2767,10 @@ int mpv_workspace_bytes(const mpv_problem* problem, size_t* out) {
 // logit pointers by the same number of bytes, so the rows of a pair still share their offset modulo 16
 // bytes, which is what the kernels rely on; the caller has checked the batch's own pointers);
 // keep_counters: add to the counters instead of starting them at zero.
+// context_node: see Args (device pointer, already moved on to the run's first tree).
 static int verify_with_workspace(const mpv_problem* problem, const mpv_buffers* buf, void* workspace,
                                  size_t workspace_bytes, void* hip_stream, bool part_of_batch = false,
-                                 bool keep_counters = false);
+                                 bool keep_counters = false, const int32_t* context_node = nullptr);
 
 int mpv_verify(const mpv_problem* problem, const mpv_buffers* buf, void* workspace,
                size_t workspace_bytes, void* hip_stream) {
@@ -2779,7 +2789,8 @@ int mpv_verify_static(const mpv_problem* problem, const mpv_buffers* buf, void* 
 }
 
 static int verify_with_workspace(const mpv_problem* problem, const mpv_buffers* buf, void* workspace,
-                                 size_t workspace_bytes, void* hip_stream, bool part_of_batch, bool keep_counters) {
+                                 size_t workspace_bytes, void* hip_stream, bool part_of_batch, bool keep_counters,
+                                 const int32_t* context_node) {
     mpv::Plan plan;
     const int rc = mpv::validate(problem, &plan);
     if (rc != MPV_OK) return rc;
@@ -2813,6 +2824,7 @@ static int verify_with_workspace(const mpv_problem* problem, const mpv_buffers* 
     a.lazy = (walk || (buf->edge_probs == nullptr && buf->accept_prob == nullptr && buf->stats == nullptr)) ? 1 : 0;
     a.estimate = 0; a.reach_prob = nullptr; a.expected = nullptr;
     a.keep_counters = keep_counters ? 1 : 0;
+    a.context_node = context_node;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     if (problem->logit_dtype == MPV_DTYPE_F32) return mpv::launch_all<mpv::ElemF32>(problem, plan, ws, a, s);
     return mpv::launch_all<mpv::ElemBF16>(problem, plan, ws, a, s);
@@ -2852,13 +2864,14 @@ int mpv_merge_duplicates(const int32_t* parent, const int32_t* tokens, int32_t B
     return MPV_OK;
 }
 
-int mpv_verify_merged(const mpv_problem* problem, const int32_t* merged_parent, const mpv_buffers* buf,
-                      void* workspace, size_t workspace_bytes, void* hip_stream) {
+int mpv_verify_merged(const mpv_problem* problem, const int32_t* merged_parent, const int32_t* context_node,
+                      const mpv_buffers* buf, void* workspace, size_t workspace_bytes, void* hip_stream) {
     if (!problem || !buf) return MPV_ERR_NULL;
     if (problem->B < 0 || problem->N < 1 || problem->V < 1) return MPV_ERR_BAD_SHAPE;
-    if (problem->method == MPV_METHOD_SPECTR) return MPV_ERR_UNSUPPORTED;
     if (problem->B == 0) return MPV_OK;
     if (!merged_parent) return MPV_ERR_NULL;
+    if (problem->method == MPV_METHOD_SPECTR && !context_node) return MPV_ERR_NULL;
+    if (problem->method != MPV_METHOD_SPECTR) context_node = nullptr;      // the other rules never accept a repeat
     const int32_t B = problem->B, N = problem->N;
     // first pass: every run of equal shapes is a valid problem, and the workspace holds the largest
     // (its size depends on the number of trees and of nodes only, and grows with both)
@@ -2900,7 +2913,8 @@ int mpv_verify_merged(const mpv_problem* problem, const int32_t* merged_parent, 
         part.edge_probs = static_cast<float*>(moved_out(buf->edge_probs, tn * 2 * 4));
         part.accept_prob = static_cast<float*>(moved_out(buf->accept_prob, tn * 4));
         part.final_residual = static_cast<float*>(moved_out(buf->final_residual, t * V * 4));
-        rc = verify_with_workspace(&run, &part, workspace, workspace_bytes, hip_stream, true, !first);
+        rc = verify_with_workspace(&run, &part, workspace, workspace_bytes, hip_stream, true, !first,
+                                   context_node ? context_node + tn : nullptr);
         first = false;
         return rc == MPV_OK;
     });

@@ -252,7 +252,8 @@ def compare_with_oracle(method, host, T, got, trees=None, check_debug=True):
         zt, zd, u = host["target"][b], host["draft"][b], host["uniforms"][b]
         token_walk = method in (orc.NSS, orc.NAIVE, orc.SPECTR)
         ref = orc.verify_tree(method, parent, tok, zt, zd, T, u,
-                              host["draw_uniforms"][b] if token_walk else None)
+                              host["draw_uniforms"][b] if token_walk else None,
+                              node_of=host.get("node_of"))     # trees of distinct contexts: see merged_tree_oracle
         report["trees"] += 1
         report["mean_accept_len"] += ref["accept_len"]
         g_len = int(got["accept_len"][b])

@@ -295,31 +295,32 @@ def test_verify_merged_rejects_bad_arguments_before_any_launch(lib):
     prob = problem(parent=None)                       # problem->parent is not read
     rows = np.array([[-1, 0, 1], [-1, 0, 0]], dtype=np.int32)
     ok = rows.ctypes.data
-    assert f(None, ok, ctypes.byref(bufs), fake, 1 << 20, None) == code("MPV_ERR_NULL")
-    assert f(ctypes.byref(prob), ok, None, fake, 1 << 20, None) == code("MPV_ERR_NULL")
-    assert f(ctypes.byref(prob), None, ctypes.byref(bufs), fake, 1 << 20, None) == code("MPV_ERR_NULL")
-    assert f(ctypes.byref(problem(parent=None, method=4)), ok, ctypes.byref(bufs), fake, 1 << 20, None) \
-        == code("MPV_ERR_UNSUPPORTED")
-    assert f(ctypes.byref(problem(parent=None, T=0.0)), ok, ctypes.byref(bufs), fake, 1 << 20, None) \
+    assert f(None, ok, None, ctypes.byref(bufs), fake, 1 << 20, None) == code("MPV_ERR_NULL")
+    assert f(ctypes.byref(prob), ok, None, None, fake, 1 << 20, None) == code("MPV_ERR_NULL")
+    assert f(ctypes.byref(prob), None, None, ctypes.byref(bufs), fake, 1 << 20, None) == code("MPV_ERR_NULL")
+    # SpecTr needs the context nodes on the device
+    assert f(ctypes.byref(problem(parent=None, method=4)), ok, None, ctypes.byref(bufs), fake, 1 << 20, None) \
+        == code("MPV_ERR_NULL")
+    assert f(ctypes.byref(problem(parent=None, T=0.0)), ok, None, ctypes.byref(bufs), fake, 1 << 20, None) \
         == code("MPV_ERR_BAD_TEMPERATURE")
     # the second tree's array is invalid / deeper than max_depth / has too many children
     bad = np.array([[-1, 0, 1], [-1, 1, 0]], dtype=np.int32)
-    assert f(ctypes.byref(prob), bad.ctypes.data, ctypes.byref(bufs), fake, 1 << 20, None) == code("MPV_ERR_BAD_TREE")
-    assert f(ctypes.byref(problem(parent=None, max_depth=1)), ok, ctypes.byref(bufs), fake, 1 << 20, None) \
+    assert f(ctypes.byref(prob), bad.ctypes.data, None, ctypes.byref(bufs), fake, 1 << 20, None) == code("MPV_ERR_BAD_TREE")
+    assert f(ctypes.byref(problem(parent=None, max_depth=1)), ok, None, ctypes.byref(bufs), fake, 1 << 20, None) \
         == code("MPV_ERR_BAD_SHAPE")
     n = header_constant("MPV_MAX_CHILDREN") + 2
     star = np.array([[-1] + [0] * (n - 1)], dtype=np.int32)
-    assert f(ctypes.byref(problem(B=1, N=n, parent=None)), star.ctypes.data, ctypes.byref(bufs), fake, 1 << 20, None) \
+    assert f(ctypes.byref(problem(B=1, N=n, parent=None)), star.ctypes.data, None, ctypes.byref(bufs), fake, 1 << 20, None) \
         == code("MPV_ERR_UNSUPPORTED")
     # workspace, alignment, null members: as for mpv_verify
-    assert f(ctypes.byref(prob), ok, ctypes.byref(bufs), None, 1 << 20, None) == code("MPV_ERR_WORKSPACE")
-    assert f(ctypes.byref(prob), ok, ctypes.byref(bufs), fake, 16, None) == code("MPV_ERR_WORKSPACE")
+    assert f(ctypes.byref(prob), ok, None, ctypes.byref(bufs), None, 1 << 20, None) == code("MPV_ERR_WORKSPACE")
+    assert f(ctypes.byref(prob), ok, None, ctypes.byref(bufs), fake, 16, None) == code("MPV_ERR_WORKSPACE")
     bufs.draft_logits = 4096 + 2
-    assert f(ctypes.byref(prob), ok, ctypes.byref(bufs), fake, 1 << 20, None) == code("MPV_ERR_ALIGNMENT")
+    assert f(ctypes.byref(prob), ok, None, ctypes.byref(bufs), fake, 1 << 20, None) == code("MPV_ERR_ALIGNMENT")
     bufs.draft_logits = 4096
     bufs.bonus_token = None
-    assert f(ctypes.byref(prob), ok, ctypes.byref(bufs), fake, 1 << 20, None) == code("MPV_ERR_NULL")
-    assert f(ctypes.byref(problem(B=0, parent=None)), None, ctypes.byref(binding._Buffers()), None, 0, None) == 0
+    assert f(ctypes.byref(prob), ok, None, ctypes.byref(bufs), fake, 1 << 20, None) == code("MPV_ERR_NULL")
+    assert f(ctypes.byref(problem(B=0, parent=None)), None, None, ctypes.byref(binding._Buffers()), None, 0, None) == 0
 
 
 def test_block_efficiency_merged_rejects_bad_arguments_before_any_launch(lib):

@@ -22,7 +22,7 @@ pytestmark = pytest.mark.gpu
 
 SI, TV = mpv.MPV_METHOD_SPECINFER, mpv.MPV_METHOD_TRAVERSAL
 NSS, NAIVE, SPECTR = mpv.MPV_METHOD_NSS, mpv.MPV_METHOD_NAIVE, mpv.MPV_METHOD_SPECTR
-NAMES = {SI: "specinfer", TV: "traversal", NSS: "nss", NAIVE: "naive"}
+NAMES = {SI: "specinfer", TV: "traversal", NSS: "nss", NAIVE: "naive", SPECTR: "spectr"}
 
 
 def announce(*a):
@@ -38,9 +38,13 @@ def merged_arrays(cfg, inputs):
     return got_p, got_c
 
 
-def run_merged(inputs, cfg, method, merged_parent, debug):
+def run_merged(inputs, cfg, method, merged_parent, debug, context_node=None):
+    on_device = None
+    if method == SPECTR:
+        on_device = torch.as_tensor(np.ascontiguousarray(context_node, dtype=np.int32), device="cuda")
     res = mpv.mpv_verify(cfg.parent, inputs["tokens"], inputs["target"], inputs["draft"], cfg.T, inputs["uniforms"],
-                         method, debug=debug, draw_uniforms=inputs["draw_uniforms"], merged_parent=merged_parent)
+                         method, debug=debug, draw_uniforms=inputs["draw_uniforms"], merged_parent=merged_parent,
+                         context_node=on_device)
     torch.cuda.synchronize()
     return result_to_host(res)
 
@@ -56,12 +60,14 @@ def runs_of(rows):
     return out
 
 
-def compare_trees(cfg, method, inputs, merged_parent, got, debug):
+def compare_trees(cfg, method, inputs, merged_parent, got, debug, context_node=None):
     host = workloads.to_host(inputs)
     report = {"trees": 0, "near_tie_paths": 0, "near_tie_bonus": 0, "mean_accept_len": 0.0, "max_prob_err": 0.0}
     for b in range(cfg.B):
         one = dict(host)
         one["parent"] = [int(x) for x in merged_parent[b]]
+        if method == SPECTR:
+            one["node_of"] = [int(x) for x in context_node[b]]
         rep = compare_with_oracle(method, one, cfg.T, got, trees=[b], check_debug=debug)
         for k in ("trees", "near_tie_paths", "near_tie_bonus"):
             report[k] += rep[k]
@@ -72,7 +78,7 @@ def compare_trees(cfg, method, inputs, merged_parent, got, debug):
             ref = merged.verify_tree_merged(method, cfg.parent, host["tokens"][b], host["target"][b], host["draft"][b],
                                             cfg.T, host["uniforms"][b], host["draw_uniforms"][b])
             plain = orc.verify_tree(method, one["parent"], host["tokens"][b], host["target"][b], host["draft"][b],
-                                    cfg.T, host["uniforms"][b], host["draw_uniforms"][b])
+                                    cfg.T, host["uniforms"][b], host["draw_uniforms"][b], node_of=one.get("node_of"))
             assert ref["path_nodes"] == plain["path_nodes"] and ref["bonus_token"] == plain["bonus_token"]
     report["mean_accept_len"] /= max(1, report["trees"])
     return report
@@ -87,7 +93,7 @@ CASES = [
 ]
 
 
-@pytest.mark.parametrize("method", [SI, TV, NSS, NAIVE])
+@pytest.mark.parametrize("method", [SI, TV, NSS, NAIVE, SPECTR])
 @pytest.mark.parametrize("name,B,V,K,L1,L2,dtype,T", CASES)
 def test_merged_trees_small_vocabularies(method, name, B, V, K, L1, L2, dtype, T):
     cfg = workloads.Config(name, B=B, V=V, K=K, L1=L1, L2=L2, dtype=dtype, T=T, methods=[method],
@@ -97,12 +103,12 @@ def test_merged_trees_small_vocabularies(method, name, B, V, K, L1, L2, dtype, T
     n_runs = len(runs_of(mp))
     announce(name, NAMES[method], f"B={B} N={cfg.N} V={V} {dtype} runs={n_runs} repeats={int((cn != np.arange(cfg.N)).sum())}")
     assert n_runs > 4
-    got = run_merged(inputs, cfg, method, mp, debug=True)
-    lean = run_merged(inputs, cfg, method, mp, debug=False)
+    got = run_merged(inputs, cfg, method, mp, debug=True, context_node=cn)
+    lean = run_merged(inputs, cfg, method, mp, debug=False, context_node=cn)
     for key in ("accept_len", "path_nodes", "path_tokens", "bonus_token"):
         assert np.array_equal(got[key], lean[key]), key
     assert got["counters"][4] == 0 and lean["counters"][4] == 0
-    rep = compare_trees(cfg, method, inputs, mp, got, debug=True)
+    rep = compare_trees(cfg, method, inputs, mp, got, debug=True, context_node=cn)
     print("[report]", rep, "counters", got["counters"].tolist(), flush=True)
     # no repeat is ever on an accepted path
     for b in range(B):
@@ -181,14 +187,34 @@ def test_large_vocabulary_sorted_and_unsorted():
             assert np.array_equal(again[key], got[key][order]), key
 
 
-def test_spectr_is_refused():
-    cfg = workloads.Config("refused", B=2, V=8, K=2, L1=0, L2=2, dtype="f32", T=1.0, methods=[SPECTR],
-                           draft_sigma=1.0, target_sigma=0.5, seed=1)
+def test_spectr_goes_on_below_an_accepted_repeat():
+    """SpecTr tests every entry with its own uniform, so a repeat can be the accepted entry; the walk
+    must then continue at the context node (whose rows and children are the repeat's context's).  A
+    target much flatter than the draft makes rho* large and every single test unlikely: first entries
+    fail often and later entries for the same token get their chance."""
+    cfg = workloads.Config("spectr_repeats", B=400, V=5, K=6, L1=0, L2=2, dtype="f32", T=1.0, methods=[SPECTR],
+                           draft_sigma=2.0, target_sigma=0.2, target_scale=0.3, seed=8421)
     inputs = workloads.make_context_inputs(cfg, "cuda")
-    mp, _ = mpv.mpv_merge_duplicates(cfg.parent, inputs["tokens"].cpu().numpy())
+    mp, cn = merged_arrays(cfg, inputs)
+    announce("spectr repeats", f"B={cfg.B} N={cfg.N} V={cfg.V} runs={len(runs_of(mp))}")
+    got = run_merged(inputs, cfg, SPECTR, mp, debug=True, context_node=cn)
+    assert got["counters"][4] == 0
+    rep = compare_trees(cfg, SPECTR, inputs, mp, got, debug=True, context_node=cn)
+    print("[report]", rep, flush=True)
+    # how often the oracle's accepted entry was a repeat (the case this test is about)
+    host = workloads.to_host(inputs)
+    through_repeat = 0
+    for b in range(cfg.B):
+        ref = merged.verify_tree_merged(SPECTR, cfg.parent, host["tokens"][b], host["target"][b], host["draft"][b],
+                                        cfg.T, host["uniforms"][b], host["draw_uniforms"][b])
+        through_repeat += sum(1 for node, _, _, ok in ref["decisions"] if ok and cn[b, node] != node)
+    print("[report] walks that went through an accepted repeat:", through_repeat, flush=True)
+    assert through_repeat >= 10
+    # without the context nodes the call is refused
     with pytest.raises(mpv.MpvError) as e:
-        run_merged(inputs, cfg, SPECTR, mp, debug=False)
-    assert e.value.code == -8
+        mpv.mpv_verify(cfg.parent, inputs["tokens"], inputs["target"], inputs["draft"], cfg.T, inputs["uniforms"],
+                       SPECTR, draw_uniforms=inputs["draw_uniforms"], merged_parent=mp)
+    assert e.value.code == -1
 
 
 @pytest.mark.parametrize("method", [SI, TV, NSS, NAIVE])
