@@ -26,8 +26,8 @@ where an accepted entry leads to the node of its context.  That last clause only
 SpecTr: under the SpecInfer solver and under Traversal Verification an entry is only tested
 again after the first entry for its token was rejected, which leaves no residual mass on that
 token, so a repeat is tested with probability 0 and only its residual step remains (App. B,
-Alg. 4; the Traversal reading of mpv_oracle); NSS and Naive move to "the first child that carries
-the drawn token", which is the node of the context (App. B, Alg. 1 and 2).  SpecTr (App. B,
+Alg. 4; the Traversal reading of mpv_oracle); NSS and Naive move to the first child in list order
+that carries the drawn token (mpv_oracle.token_walk), which is the node of the context.  SpecTr (App. B,
 Alg. 3) tests every entry against the same p / (rho* q) with the entry's own uniform, so a repeat
 can be the one that is accepted.
 

@@ -187,7 +187,7 @@ def specinfer_rule(children, tokens, p_of, q_of, decide):
                                 lambda i, a: decide(ch[i], a))
         if i is None:
             return n, P                         # Alg. 4: sample Y ~ p
-        n = ch[i]                               # progress to the child node
+        n = ch[i]                               # the walk goes on at the accepted child
 
 
 def traversal_rule(children, tokens, p_of, q_of, decide, observe=None, on_update=None):
