@@ -7,16 +7,17 @@
 // equal logits are kept or dropped together.
 //
 // One workgroup per row:
-//   1. softmax statistics of the row (maximum, log2 of the partition sum);
+//   1. the row's maximum m (the one read from memory that computes next to nothing);
 //   2. tau by bisection over the order-preserving integer keys of float values.  One probe per
 //      step: the mass of {z >= cut} together with the nearest row values on either side of the
 //      cut, to which the bracket then snaps, so a step never lands between two row values
-//      twice (at most 33 steps for float rows, 18 for bfloat16 rows).  A first sweep copies the
-//      tokens whose probability is within 2^-12 of the largest into LDS; if they reach top_p
-//      and fit, the probes run over that copy, else over the row itself (which stays in L2);
+//      twice (at most 33 steps for float rows, 18 for bfloat16 rows).  A first sweep adds up the
+//      whole row (masses are 2^((z - m) log2(e)/T): the largest is 1) and copies the tokens whose
+//      probability is within 2^-12 of the largest into LDS; if they reach top_p and fit, the
+//      probes run over that copy, else over the row itself (which stays in the caches);
 //   3. the row is written out, masked.
 // The masses are float sums in a fixed order (bitwise reproducible); "reaches top_p" is decided
-// against the sum of the whole row computed the same way.
+// against the sum of the whole row computed the same way, by the same sweep.
 
 #pragma once
 
@@ -61,31 +62,47 @@ struct NucleusProbeF {
     }
 };
 
-struct NucleusProbeResult { double mass; float below, above; int count; };
+struct NucleusProbeResult { double mass; float below, above; int count; double whole; };
 
-// One value per workgroup of each of the four numbers of a probe; the same values in every lane.
+// One value per workgroup of each of the numbers of a probe (`whole`: a second sum that goes along,
+// scratch has room for both); the same values in every lane.
 __device__ __forceinline__ NucleusProbeResult nucleus_reduce(double mass, float below, float above, int count,
-                                                             double* scratch, float* fscratch, int* iscratch) {
+                                                             double* scratch, float* fscratch, int* iscratch,
+                                                             double whole = 0.0) {
     constexpr int NW = kNucleusBlock / kWave;
     const int w = threadIdx.x / kWave, lane = threadIdx.x & (kWave - 1);
     const double m = wave_sum(mass);
+    const double wh = wave_sum(whole);
     const float lo = wave_max(below);
     const float hi = -wave_max(-above);
     const int c = wave_inclusive_scan_i32(count);            // lane 63 holds the wave's total
     __syncthreads();                                          // the previous probe's results have been read
-    if (lane == kWave - 1) { scratch[w] = m; fscratch[2 * w] = lo; fscratch[2 * w + 1] = hi; iscratch[w] = c; }
+    if (lane == kWave - 1) { scratch[w] = m; scratch[NW + w] = wh; fscratch[2 * w] = lo; fscratch[2 * w + 1] = hi; iscratch[w] = c; }
     __syncthreads();
     NucleusProbeResult r;
-    r.mass = scratch[0]; r.below = fscratch[0]; r.above = fscratch[1]; r.count = iscratch[0];
+    r.mass = scratch[0]; r.whole = scratch[NW]; r.below = fscratch[0]; r.above = fscratch[1]; r.count = iscratch[0];
 #pragma unroll
     for (int i = 1; i < NW; ++i) {
         r.mass += scratch[i];
+        r.whole += scratch[NW + i];
         r.below = fmaxf(r.below, fscratch[2 * i]);
         r.above = fminf(r.above, fscratch[2 * i + 1]);
         r.count += iscratch[i];
     }
     return r;
 }
+
+// the largest value of a row
+template <class E>
+struct RowMaxF {
+    float m0, m1;
+    __device__ __forceinline__ void init() { m0 = -INFINITY; m1 = -INFINITY; }
+    __device__ __forceinline__ void one(float z) { m0 = fmaxf(m0, z); }
+    __device__ __forceinline__ void vec(const float (&z)[E::VEC]) {
+#pragma unroll
+        for (int i = 0; i < E::VEC; i += 2) { m0 = fmaxf(m0, z[i]); m1 = fmaxf(m1, z[i + 1]); }
+    }
+};
 
 // Probe over the whole row in memory.
 template <class E>
@@ -114,14 +131,16 @@ struct NucleusCollectF {
     float* cand_e;
     int* cand_n;
     float acc0, acc1, below, above;
+    float all0, all1;       // the mass of the whole row
     int count;
     __device__ __forceinline__ void init(float k, float na, float c, float* cz, float* ce, int* cn) {
         k32 = k; nA = na; cut = c; cand_z = cz; cand_e = ce; cand_n = cn;
-        acc0 = 0.f; acc1 = 0.f; below = -INFINITY; above = INFINITY; count = 0;
+        acc0 = 0.f; acc1 = 0.f; all0 = 0.f; all1 = 0.f; below = -INFINITY; above = INFINITY; count = 0;
     }
-    __device__ __forceinline__ void item(float z, float& acc) {
+    __device__ __forceinline__ void item(float z, float& acc, float& all) {
         const float e = fast_exp2(fmaf(z, k32, nA));
         const bool in = z >= cut;
+        all += e;
         acc += in ? e : 0.f;
         below = in ? below : fmaxf(below, z);
         above = in ? fminf(above, z) : above;
@@ -137,10 +156,10 @@ struct NucleusCollectF {
             if (in && idx < kNucleusCap) { cand_z[idx] = z; cand_e[idx] = e; }
         }
     }
-    __device__ __forceinline__ void one(float z) { item(z, acc0); }
+    __device__ __forceinline__ void one(float z) { item(z, acc0, all0); }
     __device__ __forceinline__ void vec(const float (&z)[E::VEC]) {
 #pragma unroll
-        for (int i = 0; i < E::VEC; i += 2) { item(z[i], acc0); item(z[i + 1], acc1); }
+        for (int i = 0; i < E::VEC; i += 2) { item(z[i], acc0, all0); item(z[i + 1], acc1, all1); }
     }
 };
 
@@ -204,30 +223,32 @@ __global__ __launch_bounds__(kNucleusBlock) void nucleus_kernel(const typename E
     const T* z = in + r * V;
     T* o = out + r * V;
 
-    // 1. statistics
-    RowStatsF<E> sf;
-    sf.t.init(); sf.k32 = k32;
-    sweep_row<E, kNucleusBlock, kNucleusUnroll>(z, V, sf);
-    OnlineLse none; none.init();
-    RowStat rt, rd;
-    finish_stats2<kNucleusBlock>(sf.t, none, rt, rd, scratch);
-    const float nA = -static_cast<float>(rt.A);
-
-    // 2. tau.  The masses a probe adds up are 2^(z k32 + nA); over the whole row they add up to S.
-    const double S = exp2(rt.A + static_cast<double>(nA));
-    const double want = static_cast<double>(top_p) * S;
     float tau = -INFINITY;                                    // so far: everything is kept
     int kept = V;
+    // 1. the maximum (the same value in every lane)
+    float row_max = -INFINITY;
     if (!keep_all) {
+        RowMaxF<E> mf;
+        mf.init();
+        sweep_row<E, kNucleusBlock, kNucleusUnroll>(z, V, mf);
+        const NucleusProbeResult top = nucleus_reduce(0.0, fmaxf(mf.m0, mf.m1), INFINITY, 0, scratch, fscratch, iscratch);
+        row_max = top.below;
+    }
+    // 2. tau.  The masses a probe adds up are 2^(z k32 + nA) = 2^((z - m) k32); over the whole row
+    //    they add up to S.  (A row of -inf only has nothing to drop.)
+    if (!keep_all && row_max > -INFINITY) {
+        const float nA = -row_max * k32;
         if (threadIdx.x == 0) cand_n = 0;
         __syncthreads();
-        const float cut0 = rt.m - kNucleusSpan / k32;
+        const float cut0 = row_max - kNucleusSpan / k32;
         NucleusCollectF<E> cf;
         cf.init(k32, nA, cut0, cand_z, cand_e, &cand_n);
         sweep_row<E, kNucleusBlock, kNucleusUnroll>(z, V, cf);
         const NucleusProbeResult first = nucleus_reduce(static_cast<double>(cf.acc0) + static_cast<double>(cf.acc1),
-                                                        cf.below, cf.above, cf.count, scratch, fscratch, iscratch);
-        uint32_t lo_key, hi_key = float_key(rt.m) + 1u;       // cuts from hi_key on leave nothing above them
+                                                        cf.below, cf.above, cf.count, scratch, fscratch, iscratch,
+                                                        static_cast<double>(cf.all0) + static_cast<double>(cf.all1));
+        const double want = static_cast<double>(top_p) * first.whole;
+        uint32_t lo_key, hi_key = float_key(row_max) + 1u;    // cuts from hi_key on leave nothing above them
         bool in_lds = false;
         if (first.mass >= want) {                             // tau >= cut0
             tau = first.above;                                // the upper set of cut0, named by its smallest value
@@ -260,7 +281,7 @@ __global__ __launch_bounds__(kNucleusBlock) void nucleus_kernel(const typename E
                 tau = -INFINITY;
                 kept = V;
                 lo_key = float_key(-INFINITY);
-                hi_key = float_key(rt.m) + 1u;
+                hi_key = float_key(row_max) + 1u;
             }
         }
         for (int step = 0; step < 40 && hi_key - lo_key > 1u; ++step) {
@@ -286,7 +307,15 @@ __global__ __launch_bounds__(kNucleusBlock) void nucleus_kernel(const typename E
     if (tail0 + tid < V) o[tail0 + tid] = MaskedStore<E>::to_elem(MaskedStore<ElemF32>::one(E::load_one(z + tail0 + tid), tau));
     const uint4* zv = reinterpret_cast<const uint4*>(z + head);
     uint4* ov = reinterpret_cast<uint4*>(o + head);
-    for (int i = tid; i < nvec; i += kNucleusBlock) ov[i] = MaskedStore<E>::vec(zv[i], tau);
+    int i = tid;
+    for (; i + 3 * kNucleusBlock < nvec; i += 4 * kNucleusBlock) {       // four loads in flight per lane
+        const uint4 a0 = zv[i], a1 = zv[i + kNucleusBlock], a2 = zv[i + 2 * kNucleusBlock], a3 = zv[i + 3 * kNucleusBlock];
+        ov[i] = MaskedStore<E>::vec(a0, tau);
+        ov[i + kNucleusBlock] = MaskedStore<E>::vec(a1, tau);
+        ov[i + 2 * kNucleusBlock] = MaskedStore<E>::vec(a2, tau);
+        ov[i + 3 * kNucleusBlock] = MaskedStore<E>::vec(a3, tau);
+    }
+    for (; i < nvec; i += kNucleusBlock) ov[i] = MaskedStore<E>::vec(zv[i], tau);
     if (tid == 0) {
         if (threshold_out) threshold_out[r] = tau;
         if (kept_out) kept_out[r] = kept;
