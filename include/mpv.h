@@ -256,16 +256,17 @@ int mpv_block_efficiency(const mpv_problem* problem, const void* target_logits, 
                          const int32_t* tokens, void* workspace, size_t workspace_bytes,
                          float* reach_prob, float* expected, uint32_t* counters, void* hip_stream);
 
-/* mpv_block_efficiency for trees of distinct contexts: merged_parent is a HOST int32 [B,N] array, one
- * parent array per tree, as for mpv_verify_merged (problem->parent is not read; one launch per run of
- * consecutive equal rows; the counters are summed; MPV_METHOD_SPECTR returns MPV_ERR_UNSUPPORTED: its
- * estimate would have to credit an accepted repeat to the context node).  A later entry for an already drafted token is a leaf of its tree's array
- * and gets the reach probability of that entry being accepted, which SpecInfer and Traversal make 0;
- * reach_prob of a context node covers every drafted path through it.  Everything else as for
- * mpv_block_efficiency. */
-int mpv_block_efficiency_merged(const mpv_problem* problem, const int32_t* merged_parent, const void* target_logits,
-                                const void* draft_logits, const int32_t* tokens, void* workspace, size_t workspace_bytes,
-                                float* reach_prob, float* expected, uint32_t* counters, void* hip_stream);
+/* mpv_block_efficiency for trees of distinct contexts: merged_parent (HOST int32 [B,N], one parent
+ * array per tree) and context_node (DEVICE int32 [B,N], read for MPV_METHOD_SPECTR only) as for
+ * mpv_verify_merged; problem->parent is not read; one launch per run of consecutive equal rows; the
+ * counters are summed.  A later entry for an already drafted token is a leaf of its tree's array:
+ * SpecInfer and Traversal never accept it (reach probability 0); under SpecTr its acceptance is
+ * credited to the context node, whose reach probability covers every entry that stands for it, and
+ * the repeat itself gets 0.  Everything else as for mpv_block_efficiency. */
+int mpv_block_efficiency_merged(const mpv_problem* problem, const int32_t* merged_parent, const int32_t* context_node,
+                                const void* target_logits, const void* draft_logits, const int32_t* tokens, void* workspace,
+                                size_t workspace_bytes, float* reach_prob, float* expected, uint32_t* counters,
+                                void* hip_stream);
 
 /* Acceptance rates of the OTLP solver `problem->method` at every internal node of every tree
  * (Sec. 3.2; the listings of App. C): alpha[b,n] = the probability, over k draft tokens drawn

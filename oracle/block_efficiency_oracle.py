@@ -150,10 +150,12 @@ _BRANCHING = {SPECINFER: specinfer_branching_in_order, NSS: nss_branching, NAIVE
               SPECTR: spectr_branching}
 
 
-def reach_probabilities(method, parent, tokens, p_of, q_of):
+def reach_probabilities(method, parent, tokens, p_of, q_of, node_of=None):
     """P(node lies on the accepted path), for every node of one tree (root: 1).
 
-    p_of(n), q_of(n): node n's target / draft distribution (float64 vectors)."""
+    p_of(n), q_of(n): node n's target / draft distribution (float64 vectors).
+    node_of (top-down rules; Def. 3.1, see mpv_oracle.token_walk): the node an accepted child
+    entry stands for; None: itself."""
     children = base.children_lists(parent)
     n_nodes = len(parent)
     reach = np.zeros(n_nodes)
@@ -192,16 +194,23 @@ def reach_probabilities(method, parent, tokens, p_of, q_of):
                 # the draw; its residual has no mass on the rejected draft tokens anyway)
                 b += br.drawn[x]
                 seen.add(x)
-            reach[c] = reach[n] * b
+            if node_of is None:
+                reach[c] = reach[n] * b
+            else:
+                # an accepted entry is credited to the node it stands for; a drawn token already
+                # leads to the first sibling carrying it, which stands for itself
+                accepted = br.accept_at[j]
+                reach[int(node_of[c])] += reach[n] * accepted
+                reach[c] += reach[n] * (b - accepted)
     return reach
 
 
-def expected_block_efficiency(method, parent, tokens, target_logits, draft_logits, T):
+def expected_block_efficiency(method, parent, tokens, target_logits, draft_logits, T, node_of=None):
     """E[tau + 1 | tree] (Sec. 5, Eq. 1-3) and the reach probabilities, for one tree given
     its stored logits [N, V].  Returns (expected, reach[N])."""
     p_of = base._RowCache(target_logits, T)
     q_of = base._RowCache(draft_logits, T)
-    reach = reach_probabilities(method, parent, tokens, p_of, q_of)
+    reach = reach_probabilities(method, parent, tokens, p_of, q_of, node_of)
     return float(np.sum(reach)), reach
 
 

@@ -100,8 +100,8 @@ def load_library(path=None):
                                          ctypes.c_void_p, ctypes.c_void_p]
     lib.mpv_block_efficiency_merged.restype = ctypes.c_int
     lib.mpv_block_efficiency_merged.argtypes = [ctypes.POINTER(_Problem), ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
-                                                ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p,
-                                                ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+                                                ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t,
+                                                ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
     lib.mpv_acceptance_rates.restype = ctypes.c_int
     lib.mpv_acceptance_rates.argtypes = [ctypes.POINTER(_Problem), ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                          ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
@@ -325,11 +325,12 @@ class BlockEfficiencyResult:
 
 
 def mpv_block_efficiency(parent, tokens, target_logits, draft_logits, temperature, method,
-                         out=None, stream=None, merged_parent=None):
+                         out=None, stream=None, merged_parent=None, context_node=None):
     """Expected block efficiency of every tree of the batch (see include/mpv.h): enqueued on the
     current (or given) torch stream; returns a BlockEfficiencyResult of CUDA tensors.  Arguments as
     for mpv_verify, without uniforms.  `out` may be a previous result whose buffers are reused.
-    merged_parent (numpy int32 [B,N] on the host) calls mpv_block_efficiency_merged."""
+    merged_parent (numpy int32 [B,N] on the host) calls mpv_block_efficiency_merged; MPV_METHOD_SPECTR
+    then also needs context_node, an int32 CUDA tensor [B,N]."""
     import torch
     from .trees import tree_depth
     B, N, V = target_logits.shape
@@ -364,7 +365,10 @@ def mpv_block_efficiency(parent, tokens, target_logits, draft_logits, temperatur
         rows = np.ascontiguousarray(np.asarray(merged_parent), dtype=np.int32)
         if rows.shape != (B, N):
             raise ValueError("merged_parent must be [B,N]")
-        rc = lib.mpv_block_efficiency_merged(ctypes.byref(prob), rows.ctypes.data, ptr(target_logits), ptr(draft_logits),
+        if context_node is not None and (not context_node.is_cuda or not context_node.is_contiguous()
+                                         or context_node.dtype != torch.int32 or tuple(context_node.shape) != (B, N)):
+            raise ValueError("context_node must be a contiguous int32 CUDA tensor [B,N]")
+        rc = lib.mpv_block_efficiency_merged(ctypes.byref(prob), rows.ctypes.data, ptr(context_node), ptr(target_logits), ptr(draft_logits),
                                              ptr(tokens), ptr(out.workspace), ctypes.c_size_t(out.workspace.numel()),
                                              ptr(out.reach_prob), ptr(out.expected), ptr(out.counters), _stream_ptr(stream))
         if rc != 0:

@@ -2003,6 +2003,10 @@ __device__ __forceinline__ void estimate_wave(const TreeDesc& tree, const Worksp
             double none_before = 1.0, none_at_all = 1.0;
             bool first_carrier = true;
             int j = 0;
+            // trees of distinct contexts, SpecTr: an accepted entry leads to the node it stands for, so a
+            // node collects the acceptances of every entry that stands for it and a repeat collects nothing
+            const bool aliased = a.walk == 3 && a.context_node != nullptr;
+            double through_entries = 0.0;
             for (int l = 0; l < k; ++l) {
                 const int sib = tree.child_list[off + l];
                 if (sib == n) j = l;
@@ -2010,6 +2014,7 @@ __device__ __forceinline__ void estimate_wave(const TreeDesc& tree, const Worksp
                     none_before *= 1.0 - sh_v[sib];
                     if (as_global(a.tokens)[base + sib] == x) first_carrier = false;
                 }
+                if (aliased && as_global(a.context_node)[base + sib] == n) through_entries += sh_v[sib] * none_at_all;
                 none_at_all *= 1.0 - sh_v[sib];
             }
             if (a.walk == 0) step = sh_v[n] * none_before;
@@ -2017,6 +2022,8 @@ __device__ __forceinline__ void estimate_wave(const TreeDesc& tree, const Worksp
             else if (a.walk == 2) {
                 const double a1 = sh_v[tree.child_list[off]];
                 step = (j == 0 ? a1 : 0.0) + (first_carrier ? (1.0 - a1) * sh_w[n] : 0.0);
+            } else if (aliased) {
+                step = through_entries + (first_carrier ? sh_w[n] * none_at_all : 0.0);
             } else {
                 step = sh_v[n] * none_before + (first_carrier ? sh_w[n] * none_at_all : 0.0);
             }
@@ -2925,7 +2932,7 @@ int mpv_verify_merged(const mpv_problem* problem, const int32_t* merged_parent, 
 static int block_efficiency_with_workspace(const mpv_problem* problem, const void* target_logits, const void* draft_logits,
                                            const int32_t* tokens, void* workspace, size_t workspace_bytes,
                                            float* reach_prob, float* expected, uint32_t* counters, void* hip_stream,
-                                           bool part_of_batch, bool keep_counters) {
+                                           bool part_of_batch, bool keep_counters, const int32_t* context_node = nullptr) {
     mpv::Plan plan;
     const int rc = mpv::validate(problem, &plan);
     if (rc != MPV_OK) return rc;
@@ -2950,6 +2957,7 @@ static int block_efficiency_with_workspace(const mpv_problem* problem, const voi
     a.lazy = 0;
     a.estimate = 1; a.reach_prob = reach_prob; a.expected = expected;
     a.keep_counters = keep_counters ? 1 : 0;
+    a.context_node = context_node;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     if (problem->logit_dtype == MPV_DTYPE_F32) return mpv::launch_all<mpv::ElemF32>(problem, plan, ws, a, s);
     return mpv::launch_all<mpv::ElemBF16>(problem, plan, ws, a, s);
@@ -2962,14 +2970,16 @@ int mpv_block_efficiency(const mpv_problem* problem, const void* target_logits, 
                                            reach_prob, expected, counters, hip_stream, false, false);
 }
 
-int mpv_block_efficiency_merged(const mpv_problem* problem, const int32_t* merged_parent, const void* target_logits,
-                                const void* draft_logits, const int32_t* tokens, void* workspace, size_t workspace_bytes,
-                                float* reach_prob, float* expected, uint32_t* counters, void* hip_stream) {
+int mpv_block_efficiency_merged(const mpv_problem* problem, const int32_t* merged_parent, const int32_t* context_node,
+                                const void* target_logits, const void* draft_logits, const int32_t* tokens, void* workspace,
+                                size_t workspace_bytes, float* reach_prob, float* expected, uint32_t* counters,
+                                void* hip_stream) {
     if (!problem) return MPV_ERR_NULL;
     if (problem->B < 0 || problem->N < 1 || problem->V < 1) return MPV_ERR_BAD_SHAPE;
-    if (problem->method == MPV_METHOD_SPECTR) return MPV_ERR_UNSUPPORTED;
     if (problem->B == 0) return MPV_OK;
     if (!merged_parent) return MPV_ERR_NULL;
+    if (problem->method == MPV_METHOD_SPECTR && !context_node) return MPV_ERR_NULL;
+    if (problem->method != MPV_METHOD_SPECTR) context_node = nullptr;
     mpv_problem run = *problem;
     int rc = MPV_OK;
     mpv::for_each_run(merged_parent, problem->B, problem->N, [&](int32_t b0, int32_t b1) {
@@ -2996,7 +3006,8 @@ int mpv_block_efficiency_merged(const mpv_problem* problem, const int32_t* merge
         rc = block_efficiency_with_workspace(&run, static_cast<const char*>(target_logits) + tn * V * elem,
                                              static_cast<const char*>(draft_logits) + tn * V * elem, tokens + tn,
                                              workspace, workspace_bytes, reach_prob ? reach_prob + tn : nullptr,
-                                             expected + t, counters, hip_stream, true, !first);
+                                             expected + t, counters, hip_stream, true, !first,
+                                             context_node ? context_node + tn : nullptr);
         first = false;
         return rc == MPV_OK;
     });

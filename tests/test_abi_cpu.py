@@ -330,14 +330,15 @@ def test_block_efficiency_merged_rejects_bad_arguments_before_any_launch(lib):
     prob = problem(parent=None)
     rows = np.array([[-1, 0, 1], [-1, 0, 0]], dtype=np.int32)
     ok = rows.ctypes.data
-    assert f(None, ok, fake, fake, fake, fake, 1 << 20, fake, fake, fake, None) == code("MPV_ERR_NULL")
-    assert f(ctypes.byref(prob), None, fake, fake, fake, fake, 1 << 20, fake, fake, fake, None) == code("MPV_ERR_NULL")
-    assert f(ctypes.byref(problem(parent=None, method=4)), ok, fake, fake, fake, fake, 1 << 20, fake, fake, fake, None) \
-        == code("MPV_ERR_UNSUPPORTED")
+    assert f(None, ok, None, fake, fake, fake, fake, 1 << 20, fake, fake, fake, None) == code("MPV_ERR_NULL")
+    assert f(ctypes.byref(prob), None, None, fake, fake, fake, fake, 1 << 20, fake, fake, fake, None) == code("MPV_ERR_NULL")
+    # SpecTr needs the context nodes on the device
+    assert f(ctypes.byref(problem(parent=None, method=4)), ok, None, fake, fake, fake, fake, 1 << 20, fake, fake, fake, None) \
+        == code("MPV_ERR_NULL")
     bad = np.array([[-1, 0, 1], [-1, 0, 2]], dtype=np.int32)
-    assert f(ctypes.byref(prob), bad.ctypes.data, fake, fake, fake, fake, 1 << 20, fake, fake, fake, None) == code("MPV_ERR_BAD_TREE")
-    assert f(ctypes.byref(prob), ok, fake, fake, fake, fake, 16, fake, fake, fake, None) == code("MPV_ERR_WORKSPACE")
-    assert f(ctypes.byref(prob), ok, null, fake, fake, fake, 1 << 20, fake, fake, fake, None) == code("MPV_ERR_NULL")
-    assert f(ctypes.byref(prob), ok, fake, fake, fake, fake, 1 << 20, fake, null, fake, None) == code("MPV_ERR_NULL")
-    assert f(ctypes.byref(prob), ok, ctypes.c_void_p(4100), fake, fake, fake, 1 << 20, fake, fake, fake, None) == code("MPV_ERR_ALIGNMENT")
-    assert f(ctypes.byref(problem(B=0, parent=None)), None, null, null, null, null, 0, null, null, null, None) == 0
+    assert f(ctypes.byref(prob), bad.ctypes.data, None, fake, fake, fake, fake, 1 << 20, fake, fake, fake, None) == code("MPV_ERR_BAD_TREE")
+    assert f(ctypes.byref(prob), ok, None, fake, fake, fake, fake, 16, fake, fake, fake, None) == code("MPV_ERR_WORKSPACE")
+    assert f(ctypes.byref(prob), ok, None, null, fake, fake, fake, 1 << 20, fake, fake, fake, None) == code("MPV_ERR_NULL")
+    assert f(ctypes.byref(prob), ok, None, fake, fake, fake, fake, 1 << 20, fake, null, fake, None) == code("MPV_ERR_NULL")
+    assert f(ctypes.byref(prob), ok, None, ctypes.c_void_p(4100), fake, fake, fake, 1 << 20, fake, fake, fake, None) == code("MPV_ERR_ALIGNMENT")
+    assert f(ctypes.byref(problem(B=0, parent=None)), None, None, null, null, null, null, 0, null, null, null, None) == 0

@@ -39,7 +39,8 @@ def compare(method, host, T, expected, reach, trees=None):
     worst = 0.0
     for b in trees:
         want_e, want_r = beo.expected_block_efficiency(method, host["parent"], host["tokens"][b],
-                                                       host["target"][b], host["draft"][b], T)
+                                                       host["target"][b], host["draft"][b], T,
+                                                       node_of=host.get("node_of"))    # trees of distinct contexts
         tol = node_tolerances(method, host, b, T)
         err = np.abs(reach[b].astype(np.float64) - want_r)
         assert np.all(err <= tol), (f"tree {b}: reach probability off by {err.max():.3e} at node {int(err.argmax())} "

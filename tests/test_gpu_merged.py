@@ -217,7 +217,7 @@ def test_spectr_goes_on_below_an_accepted_repeat():
     assert e.value.code == -1
 
 
-@pytest.mark.parametrize("method", [SI, TV, NSS, NAIVE])
+@pytest.mark.parametrize("method", [SI, TV, NSS, NAIVE, SPECTR])
 def test_block_efficiency_of_merged_trees(method):
     """mpv_block_efficiency_merged against the block-efficiency oracle on each tree's merged array,
     and against the unmerged estimate: under SpecInfer merging can only raise it (the child list of
@@ -228,8 +228,9 @@ def test_block_efficiency_of_merged_trees(method):
     inputs = workloads.make_context_inputs(cfg, "cuda")
     mp, cn = merged_arrays(cfg, inputs)
     announce("block efficiency merged", NAMES[method], f"B={cfg.B} N={cfg.N} V={cfg.V} runs={len(runs_of(mp))}")
+    on_device = torch.as_tensor(cn, device="cuda") if method == SPECTR else None
     res = mpv.mpv_block_efficiency(cfg.parent, inputs["tokens"], inputs["target"], inputs["draft"], cfg.T, method,
-                                   merged_parent=mp)
+                                   merged_parent=mp, context_node=on_device)
     torch.cuda.synchronize()
     expected, reach, counters = res.expected.cpu().numpy(), res.reach_prob.cpu().numpy(), res.counters.cpu().numpy()
     assert counters[4] == 0
@@ -238,15 +239,18 @@ def test_block_efficiency_of_merged_trees(method):
     for b in range(cfg.B):
         one = dict(host)
         one["parent"] = [int(x) for x in mp[b]]
+        if method == SPECTR:
+            one["node_of"] = [int(x) for x in cn[b]]
         compare(method, one, cfg.T, expected, reach, trees=[b])
         internal += len(set(one["parent"][1:]))
-        if method in (SI, TV):
-            assert np.all(reach[b][cn[b] != np.arange(cfg.N)] == 0.0)        # a repeat is never accepted
+        if method in (SI, TV, SPECTR):
+            # a repeat is never accepted (SpecInfer, Traversal) or its acceptance is credited to the context's node (SpecTr)
+            assert np.all(reach[b][cn[b] != np.arange(cfg.N)] == 0.0)
     assert counters[5] == internal                                     # every internal node's task ran, summed over the runs
     plain = mpv.mpv_block_efficiency(cfg.parent, inputs["tokens"], inputs["target"], inputs["draft"], cfg.T, method)
     torch.cuda.synchronize()
     if method == SI:
         assert np.all(expected >= plain.expected.cpu().numpy() - 1e-5)
         assert float(expected.mean()) > float(plain.expected.mean())
-    with pytest.raises(mpv.MpvError):
+    with pytest.raises(mpv.MpvError):       # SpecTr without the context nodes
         mpv.mpv_block_efficiency(cfg.parent, inputs["tokens"], inputs["target"], inputs["draft"], cfg.T, SPECTR, merged_parent=mp)

@@ -208,3 +208,34 @@ def test_spectr_goes_on_below_an_accepted_repeat():
     assert not first[3] and second[3]
     assert res["path_nodes"][0] == 1                               # the node of the context, not slot 3
     assert res["accept_len"] >= 1 and set(res["path_nodes"]) <= {1, 2, 4}
+
+
+@pytest.mark.parametrize("method", METHODS + TOKEN_WALK_METHODS)
+def test_block_efficiency_of_a_merged_tree_is_its_expected_accepted_length(method):
+    """The block-efficiency oracle on the merged array (with the entries' nodes for the top-down rules)
+    against the verification oracle's own outcomes on the same tree: sum of reach probabilities =
+    E[accepted length] + 1, and node by node the probability of lying on the accepted path."""
+    from oracle import block_efficiency_oracle as beo
+    rng = np.random.default_rng(4242)
+    V, K, L = 3, 3, 2
+    model = ContextModel(rng, V, L, zero_frac=0.2)
+    parent = delayed_parent(K, 0, L)
+    checked = 0
+    for toks in itertools.product(range(V), repeat=len(parent) - 1):
+        tokens = (0,) + toks
+        mp, cn = merged.merge_duplicates(parent, tokens)
+        if mp == list(parent) and checked % 7:
+            continue
+        ctx = node_contexts(parent, tokens)
+        p_of, q_of = (lambda n: model.p[ctx[n]]), (lambda n: model.q[ctx[n]])
+        node_of = cn if method in TOKEN_WALK_METHODS + [orc.SPECINFER] else None
+        reach = beo.reach_probabilities(method, mp, tokens, p_of, q_of, node_of if method != orc.TRAVERSAL else None)
+        on_path = np.zeros(len(parent))
+        for pr, stop, _ in merged.enumerate_outcomes_merged(method, parent, tokens, p_of, q_of):
+            n = stop
+            while n >= 0:
+                on_path[n] += pr
+                n = mp[n]
+        assert np.allclose(reach, on_path, atol=1e-12), (method, tokens)
+        checked += 1
+    assert checked > 100
