@@ -67,7 +67,7 @@
 extern "C" {
 #endif
 
-#define MPV_ABI_VERSION 8
+#define MPV_ABI_VERSION 9
 
 /* limits (larger requests return MPV_ERR_UNSUPPORTED) */
 #define MPV_MAX_NODES    64   /* nodes per tree, root included            */
