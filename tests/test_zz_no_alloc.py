@@ -52,3 +52,37 @@ def test_static_scratch_matches_workspace_entry_point_twice(method):
         for debug in (False, True):
             ref, got = both(inputs, cfg.T, method, debug)
             same(ref, got)
+
+
+def test_static_scratch_call_can_be_captured_in_a_graph():
+    """The callers the entry point is for: a HIP graph that holds one call, replayed several times
+    with the program's own eager calls and synchronisations in between and with new inputs written
+    into the same tensors; every replay must give what the eager call gives on the same inputs."""
+    cfg = workloads.Config("static_graph", B=24, V=5003, K=3, L1=1, L2=2, dtype="bf16", T=1.0,
+                           methods=[TV], draft_sigma=2.0, target_sigma=1.0, seed=613)
+    print("[case] static scratch under graph capture", f"B={cfg.B} N={cfg.N} V={cfg.V}", flush=True)
+    inputs = workloads.make_inputs(cfg, "cuda")
+    args = (inputs["parent"], inputs["tokens"], inputs["target"], inputs["draft"], cfg.T, inputs["uniforms"], TV)
+    # outputs exist before the capture starts, and the library has looked up its array (first eager call)
+    out = mpv.mpv_verify(*args, static_scratch=True)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.graph(graph, stream=side):
+        mpv.mpv_verify(*args, static_scratch=True, out=out)
+    torch.cuda.synchronize()
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(99)
+    for replay in range(4):
+        if replay:
+            inputs["uniforms"].copy_(torch.rand(cfg.B, cfg.N, generator=gen, device="cuda"))
+        eager = mpv.mpv_verify(*args)                      # the program's own work between replays
+        torch.cuda.synchronize()
+        want = result_to_host(eager)
+        out.accept_len.fill_(-7)
+        out.bonus_token.fill_(-7)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        same(want, result_to_host(out))
