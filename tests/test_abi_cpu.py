@@ -342,3 +342,11 @@ def test_block_efficiency_merged_rejects_bad_arguments_before_any_launch(lib):
     assert f(ctypes.byref(prob), ok, None, fake, fake, fake, fake, 1 << 20, fake, null, fake, None) == code("MPV_ERR_NULL")
     assert f(ctypes.byref(prob), ok, None, ctypes.c_void_p(4100), fake, fake, fake, 1 << 20, fake, fake, fake, None) == code("MPV_ERR_ALIGNMENT")
     assert f(ctypes.byref(problem(B=0, parent=None)), None, None, null, null, null, null, 0, null, null, null, None) == 0
+
+
+def test_bench_runs_on_one_gpu_only():
+    """More than one GPU is refused with a message, before anything touches a GPU."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0 and "one GPU" in (r.stdout + r.stderr)
