@@ -280,6 +280,15 @@ int mpv_acceptance_rates(const mpv_problem* problem, const void* target_logits, 
                          void* workspace, size_t workspace_bytes, float* alpha, uint32_t* counters,
                          void* hip_stream);
 
+/* mpv_acceptance_rates for trees of distinct contexts: merged_parent (HOST int32 [B,N], one parent
+ * array per tree) as for mpv_verify_merged; problem->parent is not read; one launch per run of
+ * consecutive equal rows; the counters are summed.  k of a node is the length of its child list with
+ * every entry counted, later entries for an already drafted token included: they are draws from the
+ * node's draft distribution like the others (Def. 3.1).  Everything else as for mpv_acceptance_rates. */
+int mpv_acceptance_rates_merged(const mpv_problem* problem, const int32_t* merged_parent, const void* target_logits,
+                                const void* draft_logits, void* workspace, size_t workspace_bytes, float* alpha,
+                                uint32_t* counters, void* hip_stream);
+
 /* Nucleus (top-p) transform of `rows` contiguous logit rows of length V (Sec. 4.1: two of the
  * paper's eight sampling settings use nucleus sampling; the paper does not define it, the usual
  * definition is taken).  With p = softmax(z / T), row by row: the smallest set {v : z_v >= tau},

@@ -105,6 +105,10 @@ def load_library(path=None):
     lib.mpv_acceptance_rates.restype = ctypes.c_int
     lib.mpv_acceptance_rates.argtypes = [ctypes.POINTER(_Problem), ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                          ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+    lib.mpv_acceptance_rates_merged.restype = ctypes.c_int
+    lib.mpv_acceptance_rates_merged.argtypes = [ctypes.POINTER(_Problem), ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                                ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p,
+                                                ctypes.c_void_p]
     lib.mpv_nucleus_mask.restype = ctypes.c_int
     lib.mpv_nucleus_mask.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_int32,
                                      ctypes.c_float, ctypes.c_float, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
@@ -382,9 +386,10 @@ def mpv_block_efficiency(parent, tokens, target_logits, draft_logits, temperatur
     return out
 
 
-def mpv_acceptance_rates(parent, target_logits, draft_logits, temperature, method, stream=None):
+def mpv_acceptance_rates(parent, target_logits, draft_logits, temperature, method, stream=None, merged_parent=None):
     """Acceptance rate of the solver `method` at every internal node (see include/mpv.h): returns
-    (alpha float32 [B,N], counters) as CUDA tensors; leaves get 0."""
+    (alpha float32 [B,N], counters) as CUDA tensors; leaves get 0.  merged_parent (numpy int32 [B,N]
+    on the host, one parent array per tree) calls mpv_acceptance_rates_merged."""
     import torch
     from .trees import tree_depth
     B, N, V = target_logits.shape
@@ -404,6 +409,18 @@ def mpv_acceptance_rates(parent, target_logits, draft_logits, temperature, metho
     workspace = torch.empty(max(need.value, 256), dtype=torch.uint8, device=dev)
     alpha = torch.empty(B, N, dtype=torch.float32, device=dev)
     counters = torch.empty(8, dtype=torch.int32, device=dev)
+    if merged_parent is not None:
+        import numpy as np
+        rows = np.ascontiguousarray(np.asarray(merged_parent), dtype=np.int32)
+        if rows.shape != (B, N):
+            raise ValueError("merged_parent must be [B,N]")
+        rc = lib.mpv_acceptance_rates_merged(ctypes.byref(prob), rows.ctypes.data, ctypes.c_void_p(target_logits.data_ptr()),
+                                             ctypes.c_void_p(draft_logits.data_ptr()), ctypes.c_void_p(workspace.data_ptr()),
+                                             ctypes.c_size_t(workspace.numel()), ctypes.c_void_p(alpha.data_ptr()),
+                                             ctypes.c_void_p(counters.data_ptr()), _stream_ptr(stream))
+        if rc != 0:
+            raise MpvError(rc, "mpv_acceptance_rates_merged")
+        return alpha, counters
     rc = lib.mpv_acceptance_rates(ctypes.byref(prob), ctypes.c_void_p(target_logits.data_ptr()),
                                   ctypes.c_void_p(draft_logits.data_ptr()), ctypes.c_void_p(workspace.data_ptr()),
                                   ctypes.c_size_t(workspace.numel()), ctypes.c_void_p(alpha.data_ptr()),

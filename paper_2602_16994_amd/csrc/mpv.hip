@@ -3015,15 +3015,19 @@ int mpv_block_efficiency_merged(const mpv_problem* problem, const int32_t* merge
 }
 
 
-int mpv_acceptance_rates(const mpv_problem* problem, const void* target_logits, const void* draft_logits,
-                         void* workspace, size_t workspace_bytes, float* alpha, uint32_t* counters, void* hip_stream) {
+// part_of_batch, keep_counters: as for verify_with_workspace
+static int acceptance_rates_with_workspace(const mpv_problem* problem, const void* target_logits, const void* draft_logits,
+                                           void* workspace, size_t workspace_bytes, float* alpha, uint32_t* counters,
+                                           void* hip_stream, bool part_of_batch, bool keep_counters) {
     mpv::Plan plan;
     const int rc = mpv::validate(problem, &plan);
     if (rc != MPV_OK) return rc;
     if (problem->method == MPV_METHOD_TRAVERSAL) return MPV_ERR_UNSUPPORTED;     // not an OTLP solver: App. C has no rate for it
     if (problem->B == 0) return MPV_OK;
     if (!target_logits || !draft_logits || !alpha || !counters) return MPV_ERR_NULL;
-    if ((reinterpret_cast<uintptr_t>(target_logits) & 15u) || (reinterpret_cast<uintptr_t>(draft_logits) & 15u))
+    if (!part_of_batch && ((reinterpret_cast<uintptr_t>(target_logits) & 15u) || (reinterpret_cast<uintptr_t>(draft_logits) & 15u)))
+        return MPV_ERR_ALIGNMENT;
+    if (((reinterpret_cast<uintptr_t>(target_logits) ^ reinterpret_cast<uintptr_t>(draft_logits)) & 15u) != 0)
         return MPV_ERR_ALIGNMENT;
     const size_t need = mpv::carve(problem, nullptr, nullptr);
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) || workspace_bytes < need) return MPV_ERR_WORKSPACE;
@@ -3039,9 +3043,56 @@ int mpv_acceptance_rates(const mpv_problem* problem, const void* target_logits, 
     a.k32 = static_cast<float>(1.4426950408889634 / static_cast<double>(problem->temperature));
     a.lazy = 0;
     a.estimate = 2; a.alpha = alpha;
+    a.keep_counters = keep_counters ? 1 : 0;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     if (problem->logit_dtype == MPV_DTYPE_F32) return mpv::launch_all<mpv::ElemF32>(problem, plan, ws, a, s);
     return mpv::launch_all<mpv::ElemBF16>(problem, plan, ws, a, s);
+}
+
+int mpv_acceptance_rates(const mpv_problem* problem, const void* target_logits, const void* draft_logits,
+                         void* workspace, size_t workspace_bytes, float* alpha, uint32_t* counters, void* hip_stream) {
+    return acceptance_rates_with_workspace(problem, target_logits, draft_logits, workspace, workspace_bytes, alpha, counters,
+                                           hip_stream, false, false);
+}
+
+int mpv_acceptance_rates_merged(const mpv_problem* problem, const int32_t* merged_parent, const void* target_logits,
+                                const void* draft_logits, void* workspace, size_t workspace_bytes, float* alpha,
+                                uint32_t* counters, void* hip_stream) {
+    if (!problem) return MPV_ERR_NULL;
+    if (problem->B < 0 || problem->N < 1 || problem->V < 1) return MPV_ERR_BAD_SHAPE;
+    if (problem->method == MPV_METHOD_TRAVERSAL) return MPV_ERR_UNSUPPORTED;
+    if (problem->B == 0) return MPV_OK;
+    if (!merged_parent) return MPV_ERR_NULL;
+    mpv_problem run = *problem;
+    int rc = MPV_OK;
+    mpv::for_each_run(merged_parent, problem->B, problem->N, [&](int32_t b0, int32_t b1) {
+        run.B = b1 - b0;
+        run.parent = merged_parent + static_cast<size_t>(b0) * problem->N;
+        mpv::Plan plan;
+        rc = mpv::validate(&run, &plan);
+        return rc == MPV_OK;
+    });
+    if (rc != MPV_OK) return rc;
+    run.B = problem->B;
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) || workspace_bytes < mpv::carve(&run, nullptr, nullptr))
+        return MPV_ERR_WORKSPACE;
+    if (!target_logits || !draft_logits || !alpha || !counters) return MPV_ERR_NULL;
+    if ((reinterpret_cast<uintptr_t>(target_logits) & 15u) || (reinterpret_cast<uintptr_t>(draft_logits) & 15u))
+        return MPV_ERR_ALIGNMENT;
+    const size_t elem = problem->logit_dtype == MPV_DTYPE_F32 ? 4 : 2;
+    const size_t N = static_cast<size_t>(problem->N), V = static_cast<size_t>(problem->V);
+    bool first = true;
+    mpv::for_each_run(merged_parent, problem->B, problem->N, [&](int32_t b0, int32_t b1) {
+        run.B = b1 - b0;
+        run.parent = merged_parent + static_cast<size_t>(b0) * N;
+        const size_t tn = static_cast<size_t>(b0) * N;
+        rc = acceptance_rates_with_workspace(&run, static_cast<const char*>(target_logits) + tn * V * elem,
+                                             static_cast<const char*>(draft_logits) + tn * V * elem, workspace,
+                                             workspace_bytes, alpha + tn, counters, hip_stream, true, !first);
+        first = false;
+        return rc == MPV_OK;
+    });
+    return rc;
 }
 
 int mpv_timing_enable(int32_t max_launches) {

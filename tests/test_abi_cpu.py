@@ -28,7 +28,7 @@ def test_library_exports_every_declared_symbol(lib):
     text = re.sub(r"/\*.*?\*/", "", header_text(), flags=re.S)
     names = set(re.findall(r"\b(mpv_[a-z_]+)\s*\(", text))
     assert {"mpv_version", "mpv_strerror", "mpv_last_hip_error", "mpv_workspace_bytes",
-            "mpv_verify", "mpv_verify_static", "mpv_merge_duplicates", "mpv_verify_merged", "mpv_block_efficiency_merged", "mpv_block_efficiency", "mpv_acceptance_rates", "mpv_nucleus_mask", "mpv_row_stats", "mpv_fill_uniforms", "mpv_timing_enable",
+            "mpv_verify", "mpv_verify_static", "mpv_merge_duplicates", "mpv_verify_merged", "mpv_block_efficiency_merged", "mpv_acceptance_rates_merged", "mpv_block_efficiency", "mpv_acceptance_rates", "mpv_nucleus_mask", "mpv_row_stats", "mpv_fill_uniforms", "mpv_timing_enable",
             "mpv_timing_read"} <= names
     for name in names:
         assert getattr(lib, name) is not None, name
@@ -350,3 +350,22 @@ def test_bench_runs_on_one_gpu_only():
     import sys
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
     assert r.returncode != 0 and "one GPU" in (r.stdout + r.stderr)
+
+
+def test_acceptance_rates_merged_rejects_bad_arguments_before_any_launch(lib):
+    f = lib.mpv_acceptance_rates_merged
+    fake = ctypes.c_void_p(4096)
+    null = ctypes.c_void_p(0)
+    prob = problem(parent=None)
+    rows = np.array([[-1, 0, 1], [-1, 0, 0]], dtype=np.int32)
+    ok = rows.ctypes.data
+    assert f(None, ok, fake, fake, fake, 1 << 20, fake, fake, None) == code("MPV_ERR_NULL")
+    assert f(ctypes.byref(prob), None, fake, fake, fake, 1 << 20, fake, fake, None) == code("MPV_ERR_NULL")
+    assert f(ctypes.byref(problem(parent=None, method=1)), ok, fake, fake, fake, 1 << 20, fake, fake, None) == code("MPV_ERR_UNSUPPORTED")
+    bad = np.array([[-1, 0, 1], [-1, 0, 2]], dtype=np.int32)
+    assert f(ctypes.byref(prob), bad.ctypes.data, fake, fake, fake, 1 << 20, fake, fake, None) == code("MPV_ERR_BAD_TREE")
+    assert f(ctypes.byref(prob), ok, fake, fake, fake, 16, fake, fake, None) == code("MPV_ERR_WORKSPACE")
+    assert f(ctypes.byref(prob), ok, fake, null, fake, 1 << 20, fake, fake, None) == code("MPV_ERR_NULL")
+    assert f(ctypes.byref(prob), ok, fake, fake, fake, 1 << 20, null, fake, None) == code("MPV_ERR_NULL")
+    assert f(ctypes.byref(prob), ok, ctypes.c_void_p(4100), fake, fake, 1 << 20, fake, fake, None) == code("MPV_ERR_ALIGNMENT")
+    assert f(ctypes.byref(problem(B=0, parent=None)), None, null, null, null, 0, null, null, None) == 0

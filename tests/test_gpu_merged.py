@@ -254,3 +254,40 @@ def test_block_efficiency_of_merged_trees(method):
         assert float(expected.mean()) > float(plain.expected.mean())
     with pytest.raises(mpv.MpvError):       # SpecTr without the context nodes
         mpv.mpv_block_efficiency(cfg.parent, inputs["tokens"], inputs["target"], inputs["draft"], cfg.T, SPECTR, merged_parent=mp)
+
+
+@pytest.mark.parametrize("method", [SI, NSS, NAIVE, SPECTR])
+def test_acceptance_rates_of_merged_trees(method):
+    """mpv_acceptance_rates_merged against the acceptance-rate oracle on each tree's merged array:
+    the rate of a node depends on its two rows and on the length of its child list, in which a
+    later entry for an already drafted token counts like any other."""
+    from oracle import acceptance_oracle as acc
+    from tests.parity_util import PROB_ATOL, spectr_slack
+    cfg = workloads.Config("acc_merged", B=40, V=13, K=4, L1=1, L2=2, dtype="f32", T=1.1, methods=[method],
+                           draft_sigma=1.2, target_sigma=0.7, seed=8513)
+    inputs = workloads.make_context_inputs(cfg, "cuda")
+    mp, cn = merged_arrays(cfg, inputs)
+    announce("acceptance rates merged", NAMES[method], f"B={cfg.B} N={cfg.N} V={cfg.V} runs={len(runs_of(mp))}")
+    alpha, counters = mpv.mpv_acceptance_rates(cfg.parent, inputs["target"], inputs["draft"], cfg.T, method, merged_parent=mp)
+    torch.cuda.synchronize()
+    got, cnt = alpha.cpu().numpy(), counters.cpu().numpy()
+    host = workloads.to_host(inputs)
+    internal = 0
+    for b in range(cfg.B):
+        parent = [int(x) for x in mp[b]]
+        children = orc.children_lists(parent)
+        internal += sum(1 for ch in children if ch)
+        want = acc.acceptance_rates(method, parent, host["target"][b], host["draft"][b], cfg.T)
+        one = dict(host)
+        one["parent"] = parent
+        for n in range(cfg.N):
+            if not children[n]:
+                assert got[b, n] == 0.0
+                continue
+            tol = PROB_ATOL
+            if method == SPECTR and len(children[n]) > 1:
+                tol += len(children[n]) * spectr_slack(one, b, n, cfg.T, len(children[n]))
+            assert abs(float(got[b, n]) - want[n]) <= tol, (b, n, got[b, n], want[n])
+    assert cnt[4] == 0 and cnt[5] == internal
+    with pytest.raises(mpv.MpvError):
+        mpv.mpv_acceptance_rates(cfg.parent, inputs["target"], inputs["draft"], cfg.T, TV, merged_parent=mp)
