@@ -369,3 +369,20 @@ def test_acceptance_rates_merged_rejects_bad_arguments_before_any_launch(lib):
     assert f(ctypes.byref(prob), ok, fake, fake, fake, 1 << 20, null, fake, None) == code("MPV_ERR_NULL")
     assert f(ctypes.byref(prob), ok, ctypes.c_void_p(4100), fake, fake, 1 << 20, fake, fake, None) == code("MPV_ERR_ALIGNMENT")
     assert f(ctypes.byref(problem(B=0, parent=None)), None, null, null, null, 0, null, null, None) == 0
+
+
+def test_binding_prototypes_have_the_header_s_argument_counts(lib):
+    """Every function the binding declares takes as many arguments as include/mpv.h says."""
+    text = re.sub(r"/\*.*?\*/", "", header_text(), flags=re.S)
+    protos = dict(re.findall(r"\b(mpv_[a-z_]+)\s*\(([^;{]*?)\)\s*;", text, flags=re.S))
+    assert len(protos) >= 15
+    checked = 0
+    for name, params in protos.items():
+        fn = getattr(lib, name)
+        if fn.argtypes is None:
+            continue
+        params = params.strip()
+        want = 0 if params in ("", "void") else params.count(",") + 1
+        assert len(fn.argtypes) == want, f"{name}: binding declares {len(fn.argtypes)} arguments, header {want}"
+        checked += 1
+    assert checked >= 15
